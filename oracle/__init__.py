@@ -1,0 +1,160 @@
+"""fp64 CPU oracle for paged GQA + ALiBi attention -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper around ``optgqa_oracle.c`` (plain C, fp64, the paper's
+definitions written out; see the header of that file for the passages it
+follows).  Only the tests, the smoke check and the bench's CPU-baseline leg may
+import this package.  It never imports the HIP library or its binding.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "optgqa_oracle.c")
+_LIB = os.path.join(_HERE, "liboptgqa_oracle.so")
+
+DTYPES = {"f16": 0, "bf16": 1}
+
+
+def build(src: str = _SRC, out: str = _LIB, force: bool = True) -> str:
+    """Compile the oracle with gcc (OpenMP over independent (sequence, head) rows)."""
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+        tmp = out + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                               "-ffp-contract=off", "-o", tmp, src, "-lm"])
+        os.replace(tmp, out)
+    return out
+
+
+def load(path: Optional[str] = None) -> ctypes.CDLL:
+    if path is None:
+        path = build(force=False)
+    lib = ctypes.CDLL(path)
+    lib.oracle_num_threads.restype = ctypes.c_int
+    return lib
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def _get() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = load()
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dt) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def num_threads() -> int:
+    return int(_get().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _get().oracle_set_num_threads(ctypes.c_int(n))
+
+
+def reshape_and_cache(k, v, k_cache, v_cache, slot_mapping, lib=None) -> None:
+    """In place on k_cache / v_cache (uint16 [NB, Hkv, bs, D])."""
+    lib = lib or _get()
+    assert k_cache.dtype == np.uint16 and v_cache.dtype == np.uint16
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    k, v = _c(k, np.uint16), _c(v, np.uint16)
+    slots = _c(slot_mapping, np.int64)
+    T = slots.shape[0]
+    NB, Hkv, bs, D = k_cache.shape
+    stride = Hkv * D
+    lib.oracle_reshape_and_cache(_p(k), _p(v), _p(k_cache), _p(v_cache), _p(slots),
+                                 ctypes.c_int(T), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                 ctypes.c_int(bs), ctypes.c_int64(stride), ctypes.c_int64(stride))
+
+
+def _common(q, k_cache, block_tables, context_lens, slopes):
+    q = _c(q, np.uint16)
+    bt = _c(block_tables, np.int32)
+    cl = _c(context_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    NB, Hkv, bs, D = k_cache.shape
+    assert k_cache.dtype == np.uint16 and k_cache.flags.c_contiguous
+    return q, bt, cl, sl, Hkv, bs, D
+
+
+def paged_attention(q, k_cache, v_cache, block_tables, context_lens, slopes, scale, dtype,
+                    rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Decode attention in fp64.  Returns [B, Hq, D], or [n_rows, D] when ``rows`` lists
+    (sequence, head) pairs."""
+    lib = lib or _get()
+    q, bt, cl, sl, Hkv, bs, D = _common(q, k_cache, block_tables, context_lens, slopes)
+    B, Hq, _ = q.shape
+    MB = bt.shape[1]
+    assert v_cache.dtype == np.uint16 and v_cache.flags.c_contiguous
+    if rows is None:
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+        lib.oracle_paged_attention(_p(out), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(cl), _p(sl),
+                                   ctypes.c_float(scale), ctypes.c_int(B), ctypes.c_int(Hq),
+                                   ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
+                                   ctypes.c_int(MB), ctypes.c_int(DTYPES[dtype]))
+        return out
+    rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+    rs, rh = _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+    out = np.zeros((rows.shape[0], D), dtype=np.float64)
+    lib.oracle_paged_attention_rows(_p(out), _p(rs), _p(rh), ctypes.c_int(rows.shape[0]), _p(q),
+                                    _p(k_cache), _p(v_cache), _p(bt), _p(cl), _p(sl),
+                                    ctypes.c_float(scale), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+                                    ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(MB),
+                                    ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+def paged_attention_partitioned(q, k_cache, v_cache, block_tables, context_lens, slopes, scale,
+                                dtype, partition_size: int, lib=None) -> np.ndarray:
+    lib = lib or _get()
+    q, bt, cl, sl, Hkv, bs, D = _common(q, k_cache, block_tables, context_lens, slopes)
+    B, Hq, _ = q.shape
+    out = np.zeros((B, Hq, D), dtype=np.float64)
+    lib.oracle_paged_attention_partitioned(_p(out), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(cl),
+                                           _p(sl), ctypes.c_float(scale), ctypes.c_int(B),
+                                           ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                           ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
+                                           ctypes.c_int(partition_size),
+                                           ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+def paged_prefill(q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, slopes, scale, dtype,
+                  rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Causal + ALiBi attention of the new tokens over the paged cache, fp64.
+    Returns [T, Hq, D], or [n_rows, D] when ``rows`` lists (query token, head) pairs."""
+    lib = lib or _get()
+    q, bt, cl, sl, Hkv, bs, D = _common(q, k_cache, block_tables, context_lens, slopes)
+    cu = _c(cu_q_lens, np.int32)
+    T, Hq, _ = q.shape
+    B = cl.shape[0]
+    assert int(cu[-1]) == T
+    if rows is None:
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+        lib.oracle_paged_prefill(_p(out), _p(q), _p(k_cache), _p(v_cache), _p(bt), _p(cl), _p(cu),
+                                 _p(sl), ctypes.c_float(scale), ctypes.c_int(B), ctypes.c_int(Hq),
+                                 ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
+                                 ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+        return out
+    rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+    rt, rh = _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+    out = np.zeros((rows.shape[0], D), dtype=np.float64)
+    lib.oracle_paged_prefill_rows(_p(out), _p(rt), _p(rh), ctypes.c_int(rows.shape[0]), _p(q),
+                                  _p(k_cache), _p(v_cache), _p(bt), _p(cl), _p(cu), _p(sl),
+                                  ctypes.c_float(scale), ctypes.c_int(B), ctypes.c_int(Hq),
+                                  ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
+                                  ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+    return out
