@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged GQA + ALiBi decode hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic batch that is already resident in
+HBM: the KV-cache write of the step's new tokens (optgqa_reshape_and_cache) followed by decode
+attention over the paged cache (optgqa_paged_attention; split-context partitions + combine
+when the library or the workload asks for them).
+
+Prints ONE JSON line.  `value` is the KV-read rate: algorithmic KV bytes of the batch
+(2 * sum(context_lens) * Hkv * D * 2 bytes: every K and V element once per KV-head group)
+divided by the wall-clock time of a step.  `roofline` prices the attention call alone (HIP
+events on the launch stream) against the 8 TB/s HBM peak.  `cpu_baseline` times the fp64 CPU
+oracle on a bounded sample of the same batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--partition-size P]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
+# factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
+# measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--partition-size", type=int, default=None,
+                    help="override the workload's partition size (0 = library chooses, -1 = never split)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-seqs", type=int, default=0,
+                    help="sequences of the batch the CPU oracle is timed on (0 = pick for ~15 s)")
+    return ap.parse_args()
+
+
+def cpu_baseline(case, W, n_seqs: int):
+    """The oracle as it stands, on the first n_seqs sequences of the batch (all their heads)."""
+    import oracle as O
+    cfg = case.cfg
+    kc, vc = case.k_cache.copy(), case.v_cache.copy()
+    O.reshape_and_cache(case.k_new, case.v_new, kc, vc, case.slot_mapping)
+    lens = case.context_lens.astype(np.int64)
+    if n_seqs <= 0:
+        # ~1.5e8 fp64 multiply-adds per second per thread with this plain code (2-byte decode
+        # included); aim for about 15 s
+        budget = 1.5e8 * O.num_threads() * 15.0
+        per_seq = lens * cfg.num_heads * cfg.head_dim * 2
+        n_seqs = int(max(1, min(cfg.batch, np.searchsorted(np.cumsum(per_seq), budget) + 1)))
+    rows = [(b, h) for b in range(n_seqs) for h in range(cfg.num_heads)]
+    t0 = time.perf_counter()
+    if cfg.kind == "decode":
+        O.paged_attention(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
+                          case.dtype, rows=rows)
+    else:
+        rows = [(t, h) for t in range(int(case.cu_q_lens[n_seqs])) for h in range(cfg.num_heads)][::16]
+        O.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                        case.scale, case.dtype, rows=rows)
+    dt = time.perf_counter() - t0
+    kv_bytes = 2 * int(lens[:n_seqs].sum()) * cfg.num_kv_heads * cfg.head_dim * 2
+    return {
+        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
+        "sample": f"first {n_seqs} of {cfg.batch} sequences, all {cfg.num_heads} query heads "
+                  f"({kv_bytes / 1e6:.1f} MB of KV, {dt:.1f} s)",
+        "query_tokens_per_s": n_seqs / dt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(how the path would shard is described in DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2505_02351_amd as G
+    import workloads as W
+
+    G.load_library()                                   # no library, no benchmark
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    cfg = W.CONFIGS[args.workload]
+    case = W.make_case(cfg)
+    from paper_2505_02351_amd.testing import DevCase
+    dev = DevCase(case)
+    P = cfg.partition_size if args.partition_size is None else args.partition_size
+    decode = cfg.kind == "decode"
+    ws, chosen_P = dev.workspace(P) if decode else (None, 0)
+    max_ctx = case.max_context_len
+    scale = float(case.scale)
+    stream = torch.cuda.current_stream()
+
+    def attention():
+        if decode:
+            G.paged_attention(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                              dev.slopes, scale, max_ctx, P, ws, stream)
+        else:
+            G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                            dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
+
+    def step():
+        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
+        attention()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
+        starts[i].record(stream)
+        attention()
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    attn_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
+    kv_bytes = case.kv_bytes()
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = kv_bytes / (attn_ms.mean() * 1e-3) / 1e9
+    n_q = case.num_tokens
+
+    result = {
+        "metric": "paged GQA+ALiBi decode: KV-read HBM GB/s (% of peak) and query tokens/s",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": case.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "kind": cfg.kind, "batch": cfg.batch, "num_heads": cfg.num_heads,
+                   "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
+                   "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
+                   "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                     "kernel": "optgqa_paged_attention (partition kernel + combine)",
+                     "algorithmic_bytes_per_launch": kv_bytes,
+                     "launch_ms": {"mean": float(attn_ms.mean()), "median": float(np.median(attn_ms)),
+                                   "min": float(attn_ms.min()), "p90": float(np.percentile(attn_ms, 90))}},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(case, W, args.cpu_sample_seqs)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * optgqa -- paged grouped-query attention with ALiBi biases for AMD MI355X (gfx950).
+ *
+ * C ABI of the attention hot path of Opt-GQA (Alg. 1 "Opt-GQA Forward Pass" and Alg. 2
+ * "Opt-GQA Optimization on DCU" of the paper): the forward pass takes (Q, K, V, C_K, C_V, M)
+ * and returns the attention output; M.is_prompt selects the prompt branch or the
+ * "context attention with caches" branch.  Here the two branches are two entry points and
+ * the cache store is a third.
+ *
+ * General rules for every entry point
+ *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every
+ *     buffer.  The library never allocates, frees or synchronises; all work is enqueued on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *   - dtype selects the 2-byte element type of q, k, v, the caches and out.
+ *   - Return value: OPTGQA_OK or a negative optgqa_status.  Arguments are checked on the host
+ *     before anything is launched; on error nothing has been enqueued.
+ *   - Contents of device tables (block ids, slots, context lengths) are NOT checked by the
+ *     kernels; out-of-range values are undefined behaviour.  optgqa_validate_tables_host
+ *     checks host copies.
+ *
+ * Cache layout (both caches):  [num_blocks][num_kv_heads][block_size][head_dim], dense,
+ * head_dim innermost.  Token j of sequence b lives in physical block
+ * block_tables[b][j / block_size], row j % block_size.  (Section III-B: key-value vectors are
+ * kept in contiguous fixed-size blocks of a pre-allocated pool.)
+ *
+ * Supported shapes: head_dim in {64, 128}; block_size in {16, 32, 64};
+ * num_heads a multiple of num_kv_heads (any group size).
+ */
+#ifndef OPTGQA_H
+#define OPTGQA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { OPTGQA_F16 = 0, OPTGQA_BF16 = 1 } optgqa_dtype;
+
+typedef enum {
+    OPTGQA_OK = 0,
+    OPTGQA_ERR_NULL = -1,        /* a required pointer is NULL */
+    OPTGQA_ERR_SHAPE = -2,       /* inconsistent or non-positive sizes */
+    OPTGQA_ERR_UNSUPPORTED = -3, /* head_dim / block_size / dtype / alignment not supported */
+    OPTGQA_ERR_WORKSPACE = -4,   /* split-context needs a larger workspace */
+    OPTGQA_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch */
+    OPTGQA_ERR_TABLE = -6        /* optgqa_validate_tables_host found a bad entry */
+} optgqa_status;
+
+/* Library / ABI version, bumped when a signature changes. */
+int optgqa_abi_version(void);
+
+/* Static, human-readable text for a status code. */
+const char *optgqa_status_string(int status);
+
+/*
+ * KV-cache write (Alg. 1 "Reshape and store K, V into C_K, C_V"; eq. (2): the cache is the
+ * concatenation, along the token axis, of all blocks so far).
+ *
+ * For each token t with slot = slot_mapping[t] >= 0, the 2-byte patterns of k[t][g][:] and
+ * v[t][g][:] are copied to row slot % block_size of physical block slot / block_size, for every
+ * KV head g.  Negative slots are padding and are skipped.  Nothing else in the caches changes.
+ * Two tokens with the same slot in one call: undefined which one lands.
+ *
+ *   k, v            [num_tokens][num_kv_heads][head_dim]; token t starts at element
+ *                   t * k_token_stride (resp. v_token_stride); strides in elements,
+ *                   >= num_kv_heads * head_dim
+ *   k_cache,v_cache [num_blocks][num_kv_heads][block_size][head_dim], modified in place
+ *   slot_mapping    [num_tokens] int64
+ * num_tokens == 0 is allowed and does nothing.
+ */
+int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *v_cache,
+                             const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
+                             int head_dim, int block_size, int64_t k_token_stride,
+                             int64_t v_token_stride, optgqa_dtype dtype, void *stream);
+
+/*
+ * Decode attention over the paged cache (Alg. 2 "Compute context attention with caches";
+ * eq. (3)-(4); Section II query grouping, shared key-value and ALiBi; Section III-A pages
+ * and partitions).
+ *
+ * For sequence b and query head h, with g = h / (num_heads / num_kv_heads) and
+ * L = context_lens[b] (the token being decoded included, its K/V already in the cache):
+ *     s_j   = scale * <q[b][h], K_g[j]> + alibi_slopes[h] * (j - (L - 1)),   j = 0..L-1
+ *     out[b][h] = sum_j softmax(s)_j * V_g[j]
+ * accumulated in fp32 and rounded once (nearest-even) to dtype.  L == 0 gives a row of +0.
+ * Rows of a partial last block beyond L and unreferenced blocks are never read.
+ *
+ *   out, q          [num_seqs][num_heads][head_dim]
+ *   block_tables    [num_seqs][max_blocks_per_seq] int32; entries past ceil(L/block_size) unused
+ *   context_lens    [num_seqs] int32, 0 <= L <= max_blocks_per_seq * block_size
+ *   alibi_slopes    [num_heads] fp32, or NULL for no bias
+ *   max_context_len an upper bound on context_lens (used for sizing only)
+ *   partition_size  0: the library decides whether and how to split the context;
+ *                   >0: split the context into runs of this many tokens (multiple of
+ *                       block_size and of 16), one workgroup per run, then combine;
+ *                   <0: never split.
+ *   workspace       fp32 scratch for the split path, at least
+ *                   optgqa_paged_attention_workspace_bytes(...) bytes for the same arguments;
+ *                   may be NULL when that returns 0.  Contents are undefined afterwards.
+ *                   With partition_size == 0 and a NULL / too small workspace the library
+ *                   falls back to the unsplit kernel instead of failing.
+ */
+int optgqa_paged_attention(void *out, const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *block_tables, const int32_t *context_lens,
+                           const float *alibi_slopes, float scale, int num_seqs, int num_heads,
+                           int num_kv_heads, int head_dim, int block_size,
+                           int max_blocks_per_seq, int max_context_len, int partition_size,
+                           void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                           void *stream);
+
+/* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
+ * Also reports, when chosen_partition_size is not NULL, the partition size the library would
+ * use (0 = unsplit). */
+size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads,
+                                              int head_dim, int block_size, int max_context_len,
+                                              int partition_size, int *chosen_partition_size);
+
+/*
+ * Prefill over the paged cache (Alg. 1 prompt branch: scores, bias, softmax, weighted sum,
+ * with a causal mask and the ALiBi bias together).  Sequence b contributes
+ * n_b = cu_q_lens[b+1] - cu_q_lens[b] new query tokens whose K/V are already in the cache;
+ * query i sits at position pos = context_lens[b] - n_b + i, sees keys 0..pos, and gets the
+ * bias alibi_slopes[h] * (j - pos).  QK^T and PV run as bf16/fp16 MFMA contractions with
+ * fp32 accumulation; the softmax weights are rounded to dtype before the PV product.
+ *
+ *   out, q          [total_q_tokens][num_heads][head_dim], total_q_tokens = cu_q_lens[num_seqs]
+ *   cu_q_lens       [num_seqs + 1] int32, non-decreasing prefix sums of the n_b, cu_q_lens[0] = 0
+ *   context_lens    [num_seqs] int32, total length AFTER the new tokens were cached (>= n_b)
+ *   max_q_len       an upper bound on the n_b (sizes the launch; rows beyond n_b do not exist)
+ * Sequences with n_b == 0 produce nothing.
+ */
+int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const void *v_cache,
+                         const int32_t *block_tables, const int32_t *context_lens,
+                         const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
+                         int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                         int block_size, int max_blocks_per_seq, int max_q_len,
+                         optgqa_dtype dtype, void *stream);
+
+/*
+ * Diagnostic: un-page the cache (Section III-A: pages are only a re-arrangement of the
+ * sequence).  k_out / v_out are [num_seqs][max_context_len][num_kv_heads][head_dim]; token j of
+ * sequence b is copied bit for bit for j < context_lens[b]; other rows are left untouched.
+ */
+int optgqa_gather_kv(void *k_out, void *v_out, const void *k_cache, const void *v_cache,
+                     const int32_t *block_tables, const int32_t *context_lens, int num_seqs,
+                     int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                     int max_context_len, optgqa_dtype dtype, void *stream);
+
+/*
+ * Host-side check of host copies of the tables: every block id a sequence references is in
+ * [0, num_blocks), every context length fits its table row.  Returns OPTGQA_OK or
+ * OPTGQA_ERR_TABLE / OPTGQA_ERR_NULL / OPTGQA_ERR_SHAPE.  Touches no GPU.
+ */
+int optgqa_validate_tables_host(const int32_t *block_tables_host, const int32_t *context_lens_host,
+                                int num_seqs, int max_blocks_per_seq, int block_size,
+                                int num_blocks);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTGQA_H */

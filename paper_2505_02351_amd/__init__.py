@@ -1,0 +1,200 @@
+"""Python binding of liboptgqa.so: paged GQA + ALiBi attention for MI355X.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels behind the C ABI
+declared in include/optgqa.h.  PyTorch is used for device memory and streams; tensors are passed
+as raw device pointers.  There is no CPU or PyTorch fallback: if the shared library is missing
+or fails to load, importing the functions raises.
+
+Tensor conventions (see include/optgqa.h for the full contract):
+  q, out        [rows, Hq, D]            float16 or bfloat16
+  k, v          [T, Hkv, D]
+  k_cache, v_cache  [NB, Hkv, bs, D]
+  block_tables  [B, MB] int32,  context_lens [B] int32,  slot_mapping [T] int64
+  alibi_slopes  [Hq] float32 or None
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "liboptgqa.so")
+
+F16, BF16 = 0, 1
+OK = 0
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class OptGqaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """Load the C-ABI library and declare its signatures.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first (python -m paper_2505_02351_amd.build)")
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+    lib.optgqa_abi_version.restype = i32
+    lib.optgqa_abi_version.argtypes = []
+    lib.optgqa_status_string.restype = ctypes.c_char_p
+    lib.optgqa_status_string.argtypes = [i32]
+    lib.optgqa_reshape_and_cache.restype = i32
+    lib.optgqa_reshape_and_cache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, i32, vp]
+    lib.optgqa_paged_attention.restype = i32
+    lib.optgqa_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                           i32, vp, sz, i32, vp]
+    lib.optgqa_paged_attention_workspace_bytes.restype = sz
+    lib.optgqa_paged_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32,
+                                                           ctypes.POINTER(ctypes.c_int)]
+    lib.optgqa_paged_prefill.restype = i32
+    lib.optgqa_paged_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                         i32, vp]
+    lib.optgqa_gather_kv.restype = i32
+    lib.optgqa_gather_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
+    lib.optgqa_validate_tables_host.restype = i32
+    lib.optgqa_validate_tables_host.argtypes = [vp, vp, i32, i32, i32, i32]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().optgqa_status_string(int(status)).decode()
+
+
+def abi_version() -> int:
+    return int(load_library().optgqa_abi_version())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"optgqa: expected float16 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return ctypes.c_void_p(handle)
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise OptGqaError(status, where)
+
+
+def _dense(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_contiguous():
+        raise ValueError(f"optgqa: {name} must be contiguous")
+    return t
+
+
+def reshape_and_cache(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                      slot_mapping: torch.Tensor, stream=None) -> None:
+    """optgqa_reshape_and_cache: scatter the new tokens' K/V rows into the paged caches."""
+    lib = load_library()
+    NB, Hkv, bs, D = k_cache.shape
+    T = int(slot_mapping.shape[0])
+    _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(slot_mapping, "slot_mapping")
+    if T and (k.stride(-1) != 1 or k.stride(-2) != D or v.stride(-1) != 1 or v.stride(-2) != D):
+        raise ValueError("optgqa: k and v must be dense in their last two dims")
+    ks = int(k.stride(0)) if T else Hkv * D
+    vs = int(v.stride(0)) if T else Hkv * D
+    rc = lib.optgqa_reshape_and_cache(_ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache), _ptr(slot_mapping),
+                                      T, Hkv, D, bs, ks, vs, _dtype_code(k_cache), _stream(stream))
+    _check(rc, "optgqa_reshape_and_cache")
+
+
+def paged_attention_workspace_bytes(num_seqs: int, num_heads: int, num_kv_heads: int, head_dim: int,
+                                    block_size: int, max_context_len: int, partition_size: int = 0):
+    """optgqa_paged_attention_workspace_bytes -> (bytes, partition size the library would use)."""
+    lib = load_library()
+    chosen = ctypes.c_int(0)
+    n = lib.optgqa_paged_attention_workspace_bytes(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
+                                                   max_context_len, partition_size, ctypes.byref(chosen))
+    return int(n), int(chosen.value)
+
+
+def paged_attention(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                    block_tables: torch.Tensor, context_lens: torch.Tensor,
+                    alibi_slopes: Optional[torch.Tensor], scale: float, max_context_len: int,
+                    partition_size: int = 0, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """optgqa_paged_attention: decode attention of one query token per sequence."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_paged_attention(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                    _ptr(context_lens), _ptr(alibi_slopes), float(scale), B, Hq, Hkv, D, bs,
+                                    int(block_tables.shape[1]), int(max_context_len), int(partition_size),
+                                    _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_attention")
+
+
+def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                  block_tables: torch.Tensor, context_lens: torch.Tensor, cu_q_lens: torch.Tensor,
+                  alibi_slopes: Optional[torch.Tensor], scale: float, max_q_len: int, stream=None) -> None:
+    """optgqa_paged_prefill: causal + ALiBi attention of the new tokens over the paged cache."""
+    lib = load_library()
+    T, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (cu_q_lens, "cu_q_lens")):
+        _dense(t, n)
+    B = int(context_lens.shape[0])
+    rc = lib.optgqa_paged_prefill(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                  _ptr(context_lens), _ptr(cu_q_lens), _ptr(alibi_slopes), float(scale), B, Hq,
+                                  Hkv, D, bs, int(block_tables.shape[1]), int(max_q_len), _dtype_code(q),
+                                  _stream(stream))
+    _check(rc, "optgqa_paged_prefill")
+
+
+def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+              block_tables: torch.Tensor, context_lens: torch.Tensor, stream=None) -> None:
+    """optgqa_gather_kv: un-page the caches into [B, max_context_len, Hkv, D] (bit copy)."""
+    lib = load_library()
+    B, Lmax, Hkv, D = k_out.shape
+    NB, Hkv2, bs, D2 = k_cache.shape
+    if (Hkv, D) != (Hkv2, D2) or v_out.shape != k_out.shape:
+        raise ValueError("optgqa: shape mismatch in gather_kv")
+    for t, n in ((k_out, "k_out"), (v_out, "v_out"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    rc = lib.optgqa_gather_kv(_ptr(k_out), _ptr(v_out), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                              _ptr(context_lens), B, Hkv, D, bs, int(block_tables.shape[1]), Lmax,
+                              _dtype_code(k_cache), _stream(stream))
+    _check(rc, "optgqa_gather_kv")
+
+
+def validate_tables_host(block_tables, context_lens, block_size: int, num_blocks: int) -> int:
+    """optgqa_validate_tables_host on host numpy int32 arrays; returns the status code."""
+    import numpy as np
+    lib = load_library()
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    cl = np.ascontiguousarray(context_lens, dtype=np.int32)
+    return int(lib.optgqa_validate_tables_host(bt.ctypes.data_as(ctypes.c_void_p),
+                                               cl.ctypes.data_as(ctypes.c_void_p), int(cl.shape[0]),
+                                               int(bt.shape[1]), int(block_size), int(num_blocks)))

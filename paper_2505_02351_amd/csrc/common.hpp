@@ -1,0 +1,84 @@
+// Device-side helpers shared by the optgqa kernels: 2-byte float handling and wave64 lane exchange.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace optgqa {
+
+constexpr int kF16 = 0;
+constexpr int kBF16 = 1;
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Widen the low / high 2-byte element of a packed dword to fp32 (exact).
+template <int DT> __device__ __forceinline__ float widen_lo(uint32_t u);
+template <int DT> __device__ __forceinline__ float widen_hi(uint32_t u);
+template <> __device__ __forceinline__ float widen_lo<kBF16>(uint32_t u) { return __uint_as_float(u << 16); }
+template <> __device__ __forceinline__ float widen_hi<kBF16>(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+template <> __device__ __forceinline__ float widen_lo<kF16>(uint32_t u)
+{
+    return (float)__builtin_bit_cast(f16x2, u).x;
+}
+template <> __device__ __forceinline__ float widen_hi<kF16>(uint32_t u)
+{
+    return (float)__builtin_bit_cast(f16x2, u).y;
+}
+
+// acc + a.lo*b.lo + a.hi*b.hi with the products and the sum kept in fp32 (v_dot2c_f32_*).
+template <int DT> __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc);
+template <> __device__ __forceinline__ float dot2<kF16>(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b), acc, false);
+}
+template <> __device__ __forceinline__ float dot2<kBF16>(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+}
+
+// One rounding, nearest-even, fp32 -> 2-byte pattern.
+template <int DT> __device__ __forceinline__ uint16_t narrow(float x);
+template <> __device__ __forceinline__ uint16_t narrow<kF16>(float x)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)x);
+}
+template <> __device__ __forceinline__ uint16_t narrow<kBF16>(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);  // keep NaN a NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <int DT> __device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+{
+    return (uint32_t)narrow<DT>(lo) | ((uint32_t)narrow<DT>(hi) << 16);
+}
+
+// Data-parallel-primitive lane exchange inside a row of 16 lanes (full VALU rate, no LDS).
+template <int CTRL> __device__ __forceinline__ float dpp(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i inside each half row
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i inside each row
+constexpr int kDppRowRor4 = 0x124;    // row_ror:4
+constexpr int kDppRowRor8 = 0x128;
+constexpr int kDppRowRor12 = 0x12C;
+
+// Sum over the LPR (8 or 16) consecutive lanes that share a token row; every lane gets the sum.
+template <int LPR> __device__ __forceinline__ float row_group_sum(float x)
+{
+    x += dpp<kDppXor1>(x);
+    x += dpp<kDppXor2>(x);
+    x += dpp<kDppHalfMirror>(x);
+    if (LPR == 16) x += dpp<kDppMirror>(x);
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+}  // namespace optgqa

@@ -1,0 +1,241 @@
+// Paged decode attention: one query token per sequence against the block-indirected KV cache.
+//
+// Work unit: one workgroup (4 waves) per (context partition, KV head [x head chunk], sequence).
+// The GH query heads of the group that the workgroup serves all consume the SAME K and V
+// registers, so every KV element is fetched from HBM once per KV-head group (Section II,
+// "Shared Key-Value"), with 16-byte loads that cover a token row with D/8 consecutive lanes.
+//
+// Lane layout inside a wave: LPR = D/8 lanes share one token row (lane c holds dims 8c..8c+7),
+// TPS = 64/LPR token rows are processed per step.  Each row group keeps its own running
+// softmax state (m, l, acc); the states are merged once at the end (exactly, by the
+// max / rescale / add identity of Section III-A's carried partial results).
+#pragma once
+#include "common.hpp"
+
+namespace optgqa {
+
+struct DecodeParams {
+    void* out;                  // [B][Hq][D] dtype
+    float* ws_m;                // split path: [B][Hq][NP]   running max (base-2 domain)
+    float* ws_l;                //             [B][Hq][NP]   sum of weights
+    float* ws_o;                //             [B][Hq][NP][D] un-normalised weighted sum
+    const void* q;              // [B][Hq][D]
+    const void* k_cache;        // [NB][Hkv][bs][D]
+    const void* v_cache;
+    const int32_t* block_tables;
+    const int32_t* context_lens;
+    const float* slopes;        // [Hq] or nullptr
+    float scale2;               // scale * log2(e)
+    int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
+    int partition_size;         // tokens per workgroup; >= max context when unsplit
+    int num_partitions;         // 1 = unsplit: the kernel writes `out` itself
+    // Row mode.  nullptr: row = sequence (decode).  Otherwise row = new query token of a
+    // prefill batch: its sequence is found in cu_q_lens and it sees keys 0..its own position.
+    const int32_t* cu_q_lens;   // [num_seqs + 1] or nullptr
+    int num_seqs;
+    int row_offset;             // first row handled by this launch (grid.z/y counts from here)
+};
+
+// Sequence and number of visible keys of one output row; false if the row does not exist
+// (row-wise prefill launches num_seqs * max_q_len rows, an upper bound).
+__device__ __forceinline__ bool row_to_seq(const DecodeParams& p, int row, int& b, int& L)
+{
+    if (p.cu_q_lens == nullptr) {
+        b = row;
+        L = p.context_lens[b];
+        return true;
+    }
+    b = 0;
+    L = 0;
+    if (row >= p.cu_q_lens[p.num_seqs]) return false;
+    int lo = 0, hi = p.num_seqs - 1;                     // last b with cu_q_lens[b] <= row
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (p.cu_q_lens[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+    const int n_b = p.cu_q_lens[b + 1] - p.cu_q_lens[b];
+    L = p.context_lens[b] - n_b + (row - p.cu_q_lens[b]) + 1;   // keys 0..pos, pos = L - 1
+    return true;
+}
+
+constexpr int kDecodeWaves = 4;
+
+template <int DT, int D, int GH>
+__global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const DecodeParams p)
+{
+    constexpr int LPR = D / 8;            // lanes per token row
+    constexpr int TPS = 64 / LPR;         // token rows per wave step
+    constexpr int NW = kDecodeWaves;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane / LPR, c = lane % LPR;
+
+    const int part = blockIdx.x, row = p.row_offset + blockIdx.z;
+    const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
+    const int G = Hq / Hkv;
+    const int chunks = G / GH;
+    const int g = blockIdx.y / chunks;
+    const int h0 = g * G + (blockIdx.y - g * chunks) * GH;
+
+    int b, L;
+    if (!row_to_seq(p, row, b, L)) return;
+    const int t_begin = part * p.partition_size;
+    const int t_end = min(L, t_begin + p.partition_size);
+    const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
+    const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache);
+    const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
+
+    if (t_begin >= t_end) {
+        // An empty context still owes an output row (all +0); empty partitions owe nothing.
+        if (p.num_partitions == 1) {
+            uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
+            for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
+        }
+        return;
+    }
+
+    // q for the GH heads, this lane's 8 dims, still packed (consumed by 2-way dot products).
+    uint4 qv[GH];
+    float slope2[GH];
+#pragma unroll
+    for (int i = 0; i < GH; ++i) {
+        qv[i] = *reinterpret_cast<const uint4*>(qp + ((int64_t)row * Hq + h0 + i) * D + 8 * c);
+        slope2[i] = p.slopes ? p.slopes[h0 + i] * kLog2e : 0.f;
+    }
+
+    float m[GH], l[GH], acc[GH][8];
+#pragma unroll
+    for (int i = 0; i < GH; ++i) {
+        m[i] = -INFINITY;
+        l[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
+    }
+
+    const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
+    const int nsteps = (t_end - t_begin + TPS - 1) / TPS;
+    for (int s = wave; s < nsteps; s += NW) {
+        const int t0 = t_begin + s * TPS;                 // wave-uniform, never straddles a block
+        const int64_t blk = table[t0 / bs];
+        const int t = t0 + r;
+        const bool valid = t < t_end;
+        const int64_t off = ((blk * Hkv + g) * bs + (t0 % bs) + r) * D + 8 * c;
+        uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
+        if (valid) {
+            kr = *reinterpret_cast<const uint4*>(kc + off);
+            vr = *reinterpret_cast<const uint4*>(vc + off);
+        }
+        const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
+                             widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};
+        const float rel = (float)(t - (L - 1));           // exact: |rel| < 2^24
+#pragma unroll
+        for (int i = 0; i < GH; ++i) {
+            float d = dot2<DT>(qv[i].x, kr.x, 0.f);
+            d = dot2<DT>(qv[i].y, kr.y, d);
+            d = dot2<DT>(qv[i].z, kr.z, d);
+            d = dot2<DT>(qv[i].w, kr.w, d);
+            d = row_group_sum<LPR>(d);
+            const float s2 = valid ? fmaf(d, p.scale2, slope2[i] * rel) : -INFINITY;   // eq. (3), base 2
+            const float m_new = fmaxf(m[i], s2);
+            const bool none = m_new == -INFINITY;
+            const float alpha = none ? 1.f : fast_exp2(m[i] - m_new);
+            const float pj = none ? 0.f : fast_exp2(s2 - m_new);                        // eq. (4)
+            m[i] = m_new;
+            l[i] = fmaf(l[i], alpha, pj);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[i][e] = fmaf(acc[i][e], alpha, pj * vf[e]);
+        }
+    }
+
+    // ---- merge the TPS row groups of this wave (lanes with equal c, different r) ----------
+#pragma unroll
+    for (int i = 0; i < GH; ++i) {
+        float mw = m[i];
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+        const float f = (mw == -INFINITY) ? 0.f : fast_exp2(m[i] - mw);
+        float lw = l[i] * f;
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) lw += __shfl_xor(lw, off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float a = acc[i][e] * f;
+#pragma unroll
+            for (int off = LPR; off < 64; off <<= 1) a += __shfl_xor(a, off);
+            acc[i][e] = a;
+        }
+        m[i] = mw;
+        l[i] = lw;
+    }
+
+    // ---- merge the waves through LDS and write the result ---------------------------------
+    __shared__ float sm_m[NW][GH];
+    __shared__ float sm_l[NW][GH];
+    __shared__ float sm_o[NW][GH][D];
+    if (r == 0) {
+#pragma unroll
+        for (int i = 0; i < GH; ++i) {
+            if (c == 0) {
+                sm_m[wave][i] = m[i];
+                sm_l[wave][i] = l[i];
+            }
+            *reinterpret_cast<float4*>(&sm_o[wave][i][8 * c]) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+            *reinterpret_cast<float4*>(&sm_o[wave][i][8 * c + 4]) = make_float4(acc[i][4], acc[i][5], acc[i][6], acc[i][7]);
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < GH * D; idx += NW * 64) {
+        const int i = idx / D, d = idx - i * D;
+        float M = sm_m[0][i];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm_m[w][i]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = fast_exp2(sm_m[w][i] - M);    // a wave without tokens has m = -inf -> 0
+            num = fmaf(f, sm_o[w][i][d], num);
+            den = fmaf(f, sm_l[w][i], den);
+        }
+        const int h = h0 + i;
+        if (p.num_partitions == 1) {
+            static_cast<uint16_t*>(p.out)[((int64_t)row * Hq + h) * D + d] = narrow<DT>(num / den);
+        } else {
+            const int64_t slot = ((int64_t)row * Hq + h) * p.num_partitions + part;
+            if (d == 0) {
+                p.ws_m[slot] = M;
+                p.ws_l[slot] = den;
+            }
+            p.ws_o[slot * D + d] = num;
+        }
+    }
+}
+
+// Combine the per-partition (max, sum, weighted sum) triples of the split path:
+//   M = max_p m_p,  out = sum_p 2^(m_p-M) o_p / sum_p 2^(m_p-M) l_p.
+// grid = (Hq, rows), block = D threads.
+template <int DT, int D>
+__global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const DecodeParams p)
+{
+    const int h = blockIdx.x, row = p.row_offset + blockIdx.y, d = threadIdx.x;
+    int b, L;
+    if (!row_to_seq(p, row, b, L)) return;
+    uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * p.num_heads + h) * D;
+    if (L <= 0) {
+        o[d] = 0;
+        return;
+    }
+    const int np = (L + p.partition_size - 1) / p.partition_size;
+    const int64_t base = ((int64_t)row * p.num_heads + h) * p.num_partitions;
+    float M = -INFINITY;
+    for (int i = 0; i < np; ++i) M = fmaxf(M, p.ws_m[base + i]);
+    float num = 0.f, den = 0.f;
+    for (int i = 0; i < np; ++i) {
+        const float f = fast_exp2(p.ws_m[base + i] - M);
+        den = fmaf(f, p.ws_l[base + i], den);
+        num = fmaf(f, p.ws_o[(base + i) * D + d], num);
+    }
+    o[d] = narrow<DT>(num / den);
+}
+
+}  // namespace optgqa

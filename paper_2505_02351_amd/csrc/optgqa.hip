@@ -1,0 +1,356 @@
+// C ABI of the optgqa library: argument checks, launch-shape decisions, kernel dispatch.
+// Declarations and the meaning of every argument: include/optgqa.h.
+#include "optgqa.h"
+
+#include <hip/hip_runtime.h>
+
+#include "cache_kernels.hpp"
+#include "decode_kernels.hpp"
+#include "prefill_kernels.hpp"
+
+using namespace optgqa;
+
+namespace {
+
+constexpr int kAbiVersion = 1;
+constexpr int kNumCUs = 256;              // MI355X
+constexpr int kMinPartition = 256;        // tokens; smaller runs are dominated by the merge
+
+bool dtype_ok(int dt) { return dt == OPTGQA_F16 || dt == OPTGQA_BF16; }
+bool head_dim_ok(int d) { return d == 64 || d == 128; }
+bool block_size_ok(int bs) { return bs == 16 || bs == 32 || bs == 64; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? OPTGQA_OK : OPTGQA_ERR_LAUNCH;
+}
+
+// Largest of 8, 4, 2, 1 that divides the group size: the number of query heads one workgroup
+// serves from a single pass over its K/V tiles.
+int heads_per_workgroup(int group)
+{
+    for (int gh = 8; gh > 1; gh >>= 1)
+        if (group % gh == 0) return gh;
+    return 1;
+}
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Partition size the library picks when the caller leaves the choice to it (0 = do not split).
+// Aim: enough workgroups to occupy every CU several times over, runs no shorter than
+// kMinPartition tokens.
+int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int block_size, int max_context_len)
+{
+    if (max_context_len <= kMinPartition) return 0;
+    const int group = num_heads / num_kv_heads;
+    const long units = (long)num_seqs * num_kv_heads * (group / heads_per_workgroup(group));
+    const long want_wgs = 8L * kNumCUs;
+    if (units >= want_wgs) return 0;
+    long np = (want_wgs + units - 1) / units;                       // partitions per sequence
+    int step = block_size > 16 ? block_size : 16;
+    if (kMinPartition % step) step = kMinPartition;                  // keep P a multiple of both
+    int P = round_up((int)((max_context_len + np - 1) / np), step);
+    if (P < kMinPartition) P = kMinPartition;
+    if (P >= max_context_len) return 0;
+    return P;
+}
+
+struct SplitPlan {
+    int partition_size;   // 0 = unsplit
+    int num_partitions;
+    size_t bytes;
+};
+
+SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                     int max_context_len, int partition_size)
+{
+    SplitPlan s{0, 1, 0};
+    int P = partition_size;
+    if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, block_size, max_context_len);
+    if (P <= 0) return s;
+    s.partition_size = P;
+    s.num_partitions = (max_context_len + P - 1) / P;
+    if (s.num_partitions < 1) s.num_partitions = 1;
+    s.bytes = (size_t)num_seqs * num_heads * s.num_partitions * (head_dim + 2) * sizeof(float);
+    return s;
+}
+
+template <int DT, int D>
+int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
+{
+    const dim3 block(kDecodeWaves * 64);
+    switch (gh) {
+    case 8: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 8>), grid, block, 0, st, p); break;
+    case 4: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 4>), grid, block, 0, st, p); break;
+    case 2: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 2>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 1>), grid, block, 0, st, p); break;
+    }
+    return launch_status();
+}
+
+// Rows are sequences (decode) or new query tokens (row-wise prefill).  A launch covers at most
+// kMaxRowsPerLaunch rows because grid.y / grid.z are 16-bit.
+constexpr int kMaxRowsPerLaunch = 65535;
+
+template <int DT, int D>
+int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
+{
+    const int group = p.num_heads / p.num_kv_heads;
+    const int gh = heads_per_workgroup(group);
+    for (int first = 0; first < num_rows; first += kMaxRowsPerLaunch) {
+        const int rows = num_rows - first < kMaxRowsPerLaunch ? num_rows - first : kMaxRowsPerLaunch;
+        p.row_offset = first;
+        const dim3 grid(p.num_partitions, p.num_kv_heads * (group / gh), rows);
+        int rc = launch_decode_gh<DT, D>(p, gh, grid, st);
+        if (rc != OPTGQA_OK) return rc;
+        if (p.num_partitions == 1) continue;
+        hipLaunchKernelGGL((paged_decode_reduce_kernel<DT, D>), dim3(p.num_heads, rows), dim3(D), 0, st, p);
+        rc = launch_status();
+        if (rc != OPTGQA_OK) return rc;
+    }
+    return OPTGQA_OK;
+}
+
+template <typename... A>
+int launch_decode_any(int dtype, int head_dim, A... args)
+{
+    if (dtype == OPTGQA_F16)
+        return head_dim == 128 ? launch_decode<kF16, 128>(args...) : launch_decode<kF16, 64>(args...);
+    return head_dim == 128 ? launch_decode<kBF16, 128>(args...) : launch_decode<kBF16, 64>(args...);
+}
+
+// Row-wise prefill: every new query token is handled like a decode row whose context ends at
+// its own position (exact, but K/V are re-read per query token; used where the tiled MFMA
+// kernel does not apply).
+int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows_bound, int head_dim,
+                           int dtype, hipStream_t st)
+{
+    DecodeParams p;
+    p.out = pp.out;
+    p.ws_m = p.ws_l = p.ws_o = nullptr;
+    p.q = pp.q;
+    p.k_cache = pp.k_cache;
+    p.v_cache = pp.v_cache;
+    p.block_tables = pp.block_tables;
+    p.context_lens = pp.context_lens;
+    p.slopes = pp.slopes;
+    p.scale2 = pp.scale2;
+    p.num_heads = pp.num_heads;
+    p.num_kv_heads = pp.num_kv_heads;
+    p.block_size = pp.block_size;
+    p.max_blocks_per_seq = pp.max_blocks_per_seq;
+    p.partition_size = 1 << 30;
+    p.num_partitions = 1;
+    p.cu_q_lens = pp.cu_q_lens;
+    p.num_seqs = num_seqs;
+    p.row_offset = 0;
+    return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int optgqa_abi_version(void) { return kAbiVersion; }
+
+const char* optgqa_status_string(int status)
+{
+    switch (status) {
+    case OPTGQA_OK: return "ok";
+    case OPTGQA_ERR_NULL: return "a required pointer is NULL";
+    case OPTGQA_ERR_SHAPE: return "inconsistent or non-positive sizes";
+    case OPTGQA_ERR_UNSUPPORTED: return "unsupported head_dim, block_size, dtype or alignment";
+    case OPTGQA_ERR_WORKSPACE: return "workspace missing or too small for the split-context path";
+    case OPTGQA_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    case OPTGQA_ERR_TABLE: return "block table or context length out of range";
+    default: return "unknown status";
+    }
+}
+
+int optgqa_reshape_and_cache(const void* k, const void* v, void* k_cache, void* v_cache,
+                             const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
+                             int head_dim, int block_size, int64_t k_token_stride,
+                             int64_t v_token_stride, optgqa_dtype dtype, void* stream)
+{
+    if (num_tokens < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    const int64_t row = (int64_t)num_kv_heads * head_dim;
+    if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
+    if (num_tokens == 0) return OPTGQA_OK;
+    if (!k || !v || !k_cache || !v_cache || !slot_mapping) return OPTGQA_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v) |
+         reinterpret_cast<uintptr_t>(k_cache) | reinterpret_cast<uintptr_t>(v_cache)) & 1u)
+        return OPTGQA_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool wide = aligned16(k) && aligned16(v) && aligned16(k_cache) && aligned16(v_cache) &&
+                      k_token_stride % 8 == 0 && v_token_stride % 8 == 0;
+    const int elems = wide ? 8 : 1;
+    const int64_t threads = (int64_t)num_tokens * num_kv_heads * (head_dim / elems) * 2;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+    auto kk = static_cast<const uint16_t*>(k);
+    auto vv = static_cast<const uint16_t*>(v);
+    auto kc = static_cast<uint16_t*>(k_cache);
+    auto vc = static_cast<uint16_t*>(v_cache);
+    if (wide)
+        hipLaunchKernelGGL((reshape_and_cache_kernel<uint4>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
+                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
+                           v_token_stride);
+    else
+        hipLaunchKernelGGL((reshape_and_cache_kernel<uint16_t>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv,
+                           kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size,
+                           k_token_stride, v_token_stride);
+    return launch_status();
+}
+
+size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads,
+                                              int head_dim, int block_size, int max_context_len,
+                                              int partition_size, int* chosen_partition_size)
+{
+    if (chosen_partition_size) *chosen_partition_size = 0;
+    if (num_seqs <= 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_context_len <= 0 || num_heads % num_kv_heads)
+        return 0;
+    const SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
+                                   max_context_len, partition_size);
+    if (chosen_partition_size) *chosen_partition_size = s.partition_size;
+    return s.bytes;
+}
+
+int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* block_tables, const int32_t* context_lens,
+                           const float* alibi_slopes, float scale, int num_seqs, int num_heads,
+                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                           int max_context_len, int partition_size, void* workspace,
+                           size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_blocks_per_seq <= 0 || max_context_len < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
+    if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    if (partition_size > 0 && (partition_size % block_size || partition_size % 16)) return OPTGQA_ERR_SHAPE;
+    if (num_seqs == 0) return OPTGQA_OK;
+    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return OPTGQA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
+    if (num_heads > 65535) return OPTGQA_ERR_SHAPE;
+
+    SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
+                             max_context_len > 0 ? max_context_len : 1, partition_size);
+    if (s.partition_size > 0) {
+        const bool have = workspace && workspace_bytes >= s.bytes && aligned16(workspace);
+        if (!have) {
+            if (partition_size > 0) return OPTGQA_ERR_WORKSPACE;
+            s = SplitPlan{0, 1, 0};                      // library's own choice: fall back to unsplit
+        }
+    }
+
+    DecodeParams p;
+    p.out = out;
+    p.q = q;
+    p.k_cache = k_cache;
+    p.v_cache = v_cache;
+    p.block_tables = block_tables;
+    p.context_lens = context_lens;
+    p.slopes = alibi_slopes;
+    p.scale2 = scale * kLog2e;
+    p.num_heads = num_heads;
+    p.num_kv_heads = num_kv_heads;
+    p.block_size = block_size;
+    p.max_blocks_per_seq = max_blocks_per_seq;
+    if (s.partition_size > 0) {
+        const size_t n = (size_t)num_seqs * num_heads * s.num_partitions;
+        p.ws_m = static_cast<float*>(workspace);
+        p.ws_l = p.ws_m + n;
+        p.ws_o = p.ws_l + n;
+        p.partition_size = s.partition_size;
+        p.num_partitions = s.num_partitions;
+    } else {
+        p.ws_m = p.ws_l = p.ws_o = nullptr;
+        p.partition_size = 1 << 30;
+        p.num_partitions = 1;
+    }
+    p.cu_q_lens = nullptr;
+    p.num_seqs = num_seqs;
+    p.row_offset = 0;
+    return launch_decode_any((int)dtype, head_dim, p, num_seqs, static_cast<hipStream_t>(stream));
+}
+
+int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                         int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_blocks_per_seq <= 0 || max_q_len < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
+    if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens) return OPTGQA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs > 65535) return OPTGQA_ERR_SHAPE;
+    PrefillParams p;
+    p.out = out;
+    p.q = q;
+    p.k_cache = k_cache;
+    p.v_cache = v_cache;
+    p.block_tables = block_tables;
+    p.context_lens = context_lens;
+    p.cu_q_lens = cu_q_lens;
+    p.slopes = alibi_slopes;
+    p.scale2 = scale * kLog2e;
+    p.num_heads = num_heads;
+    p.num_kv_heads = num_kv_heads;
+    p.block_size = block_size;
+    p.max_blocks_per_seq = max_blocks_per_seq;
+    const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
+    if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+    return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, static_cast<hipStream_t>(stream));
+}
+
+int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* v_cache,
+                     const int32_t* block_tables, const int32_t* context_lens, int num_seqs,
+                     int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                     int max_context_len, optgqa_dtype dtype, void* stream)
+{
+    if (num_seqs < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 || max_blocks_per_seq <= 0 ||
+        max_context_len < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs == 0 || max_context_len == 0) return OPTGQA_OK;
+    if (!k_out || !v_out || !k_cache || !v_cache || !block_tables || !context_lens) return OPTGQA_ERR_NULL;
+    if (!aligned16(k_out) || !aligned16(v_out) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs > 65535) return OPTGQA_ERR_SHAPE;
+    const int64_t pieces = (int64_t)max_context_len * num_kv_heads * (head_dim / 8);
+    const dim3 grid((unsigned)((pieces + 255) / 256), num_seqs, 2);
+    hipLaunchKernelGGL(gather_kv_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out),
+                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
+                       block_tables, context_lens, num_kv_heads, head_dim, block_size, max_blocks_per_seq,
+                       max_context_len);
+    return launch_status();
+}
+
+int optgqa_validate_tables_host(const int32_t* block_tables_host, const int32_t* context_lens_host,
+                                int num_seqs, int max_blocks_per_seq, int block_size, int num_blocks)
+{
+    if (num_seqs < 0 || max_blocks_per_seq <= 0 || block_size <= 0 || num_blocks <= 0) return OPTGQA_ERR_SHAPE;
+    if (num_seqs == 0) return OPTGQA_OK;
+    if (!block_tables_host || !context_lens_host) return OPTGQA_ERR_NULL;
+    for (int b = 0; b < num_seqs; ++b) {
+        const int L = context_lens_host[b];
+        if (L < 0 || (int64_t)L > (int64_t)max_blocks_per_seq * block_size) return OPTGQA_ERR_TABLE;
+        const int nb = (L + block_size - 1) / block_size;
+        for (int i = 0; i < nb; ++i) {
+            const int id = block_tables_host[(int64_t)b * max_blocks_per_seq + i];
+            if (id < 0 || id >= num_blocks) return OPTGQA_ERR_TABLE;
+        }
+    }
+    return OPTGQA_OK;
+}
+
+}  // extern "C"

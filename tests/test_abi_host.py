@@ -1,0 +1,106 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before touching the GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "optgqa.h")
+
+
+@pytest.fixture(scope="module")
+def G():
+    import paper_2505_02351_amd as G
+    if not os.path.exists(G.LIB_PATH):
+        from paper_2505_02351_amd import build
+        build.build()
+    G.load_library()
+    return G
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(optgqa_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(G):
+    lib = G.load_library()
+    names = declared_symbols()
+    assert {"optgqa_reshape_and_cache", "optgqa_paged_attention", "optgqa_paged_prefill"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(G):
+    assert G.abi_version() >= 1
+    assert G.status_string(0) == "ok"
+    for code in range(-6, 0):
+        assert G.status_string(code) not in ("ok", "unknown status")
+    assert G.status_string(-99) == "unknown status"
+
+
+def test_argument_errors_before_any_launch(G):
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)       # non-null, aligned, never dereferenced: every call below fails first
+    # reshape_and_cache
+    f = lib.optgqa_reshape_and_cache
+    assert f(one, one, one, one, one, -1, 2, 64, 16, 128, 128, 0, None) == -2
+    assert f(one, one, one, one, one, 4, 2, 48, 16, 96, 96, 0, None) == -3          # head_dim
+    assert f(one, one, one, one, one, 4, 2, 64, 12, 128, 128, 0, None) == -3         # block_size
+    assert f(one, one, one, one, one, 4, 2, 64, 16, 100, 128, 0, None) == -2         # stride < row
+    assert f(one, one, one, one, one, 4, 2, 64, 16, 128, 128, 7, None) == -3         # dtype
+    assert f(None, one, one, one, one, 4, 2, 64, 16, 128, 128, 0, None) == -1
+    assert f(None, None, None, None, None, 0, 2, 64, 16, 128, 128, 0, None) == 0     # no tokens: no-op
+    # paged_attention
+    g = lib.optgqa_paged_attention
+    base = dict(scale=0.125, B=2, Hq=8, Hkv=2, D=64, bs=16, MB=8, Lmax=128, P=0)
+
+    def call(out=one, q=one, kc=one, vc=one, bt=one, cl=one, ws=None, wsb=0, dt=0, **kw):
+        a = dict(base, **kw)
+        return g(out, q, kc, vc, bt, cl, None, a["scale"], a["B"], a["Hq"], a["Hkv"], a["D"], a["bs"],
+                 a["MB"], a["Lmax"], a["P"], ws, wsb, dt, None)
+
+    assert call(Hq=7) == -2                      # Hq % Hkv
+    assert call(D=96) == -3
+    assert call(bs=8, Lmax=64) == -3
+    assert call(Lmax=129) == -2                  # exceeds the table row
+    assert call(P=24) == -2                      # not a multiple of block_size / 16
+    assert call(P=48, bs=32, MB=4) == -2
+    assert call(q=None) == -1
+    assert call(out=ctypes.c_void_p(8)) == -3    # misaligned
+    assert call(P=32) == -4                      # split forced, no workspace
+    assert call(B=0) == 0
+    assert call(dt=2) == -3
+    # prefill
+    h = lib.optgqa_paged_prefill
+    assert h(one, one, one, one, one, one, None, None, 0.1, 2, 8, 2, 64, 16, 8, 4, 0, None) == -1
+    assert h(one, one, one, one, one, one, one, None, 0.1, 2, 8, 3, 64, 16, 8, 4, 0, None) == -2
+    assert h(one, one, one, one, one, one, one, None, 0.1, 2, 8, 2, 64, 16, 8, 0, 0, None) == 0
+    # gather
+    k = lib.optgqa_gather_kv
+    assert k(one, one, one, one, one, None, 2, 2, 64, 16, 8, 128, 0, None) == -1
+    assert k(one, one, one, one, one, one, 2, 2, 32, 16, 8, 128, 0, None) == -3
+
+
+def test_workspace_query(G):
+    n, P = G.paged_attention_workspace_bytes(4, 64, 8, 128, 16, 32768, 512)
+    assert P == 512 and n == 4 * 64 * 64 * (128 + 2) * 4
+    n, P = G.paged_attention_workspace_bytes(1, 8, 2, 64, 16, 128, 0)
+    assert (n, P) == (0, 0)                      # short context: no split
+    n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, 0)
+    assert P > 0 and P % 32 == 0 and n > 0
+    n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, -1)
+    assert (n, P) == (0, 0)
+
+
+def test_validate_tables_host(G):
+    bt = np.array([[3, 1, -1], [0, 2, 4]], np.int32)
+    assert G.validate_tables_host(bt, np.array([20, 48], np.int32), 16, 5) == 0
+    assert G.validate_tables_host(bt, np.array([33, 48], np.int32), 16, 5) == -6    # reads the -1
+    assert G.validate_tables_host(bt, np.array([20, 48], np.int32), 16, 4) == -6    # id 4 >= 4
+    assert G.validate_tables_host(bt, np.array([20, 49], np.int32), 16, 5) == -6    # too long
+    assert G.validate_tables_host(bt, np.array([0, 0], np.int32), 16, 5) == 0

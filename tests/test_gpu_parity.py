@@ -1,0 +1,344 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 CPU oracle, element by element.
+
+Bar: caches and index work bit-exact; attention outputs within 2e-3 (fp16) / 1e-2 (bf16)
+max-abs of the oracle's fp64 result."""
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def U():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    import paper_2505_02351_amd as G
+    G.load_library()                       # fails loudly if the HIP library is not built
+    from paper_2505_02351_amd import testing
+    return testing
+
+
+def oracle_filled(O, case):
+    kc, vc = case.k_cache.copy(), case.v_cache.copy()
+    O.reshape_and_cache(case.k_new, case.v_new, kc, vc, case.slot_mapping)
+    return kc, vc
+
+
+def oracle_decode(O, case, kc, vc, rows=None, slopes="case"):
+    sl = case.slopes if isinstance(slopes, str) else slopes
+    return O.paged_attention(case.q, kc, vc, case.block_tables, case.context_lens, sl, case.scale,
+                             case.dtype, rows=rows)
+
+
+# ------------------------------------------------------------------ cache write (bit-exact)
+CW = [
+    dict(dtype=W.F16, batch=3, num_heads=8, num_kv_heads=2, head_dim=64, block_size=16, ctx_hi=90, q_len=1),
+    dict(dtype=W.BF16, batch=5, num_heads=8, num_kv_heads=4, head_dim=128, block_size=32, ctx_hi=300, q_len=1),
+    dict(dtype=W.BF16, batch=4, num_heads=4, num_kv_heads=1, head_dim=128, block_size=16, ctx_lo=40, ctx_hi=200,
+         q_len=37, kind="prefill"),
+    dict(dtype=W.F16, batch=2, num_heads=6, num_kv_heads=3, head_dim=64, block_size=64, ctx_lo=70, ctx_hi=500,
+         q_len=70, kind="prefill"),
+]
+
+
+@pytest.mark.parametrize("i", range(len(CW)))
+def test_cache_write_bit_exact(U, oracle, i):
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name=f"cw{i}", num_blocks=128, seed=300 + i, **CW[i])
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    torch.cuda.synchronize()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc)       # the ENTIRE buffers, NaN sentinels included
+    assert np.array_equal(U.to_host(dev.v_cache), vc)
+
+    # padding tokens (negative slots) and a strided source (token stride > Hkv*D)
+    dev2 = U.DevCase(case)
+    slots = case.slot_mapping.copy()
+    slots[1::3] = -1
+    T, Hkv, D = case.k_new.shape
+    wide_k = torch.zeros((T, Hkv * D + 24), dtype=dev2.k_new.dtype, device="cuda")
+    wide_v = torch.zeros((T, Hkv * D + 8), dtype=dev2.k_new.dtype, device="cuda")
+    wide_k[:, : Hkv * D] = dev2.k_new.reshape(T, -1)
+    wide_v[:, : Hkv * D] = dev2.v_new.reshape(T, -1)
+    k_view = wide_k[:, : Hkv * D].view(T, Hkv, D)
+    v_view = wide_v[:, : Hkv * D].view(T, Hkv, D)
+    G.reshape_and_cache(k_view, v_view, dev2.k_cache, dev2.v_cache, torch.from_numpy(slots).cuda())
+    torch.cuda.synchronize()
+    kc2, vc2 = case.k_cache.copy(), case.v_cache.copy()
+    oracle.reshape_and_cache(case.k_new, case.v_new, kc2, vc2, slots)
+    assert np.array_equal(U.to_host(dev2.k_cache), kc2)
+    assert np.array_equal(U.to_host(dev2.v_cache), vc2)
+
+    # odd element stride -> the 2-byte copy path
+    dev3 = U.DevCase(case)
+    odd_k = torch.zeros((T, Hkv * D + 3), dtype=dev3.k_new.dtype, device="cuda")
+    odd_k[:, : Hkv * D] = dev3.k_new.reshape(T, -1)
+    G.reshape_and_cache(odd_k[:, : Hkv * D].view(T, Hkv, D), dev3.v_new, dev3.k_cache, dev3.v_cache,
+                        dev3.slot_mapping)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.to_host(dev3.k_cache), kc)
+    assert np.array_equal(U.to_host(dev3.v_cache), vc)
+
+
+def test_gather_kv_bit_exact(U, oracle):
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="gather", dtype=W.BF16, batch=4, num_heads=8, num_kv_heads=2, head_dim=128,
+                         block_size=16, num_blocks=64, ctx_lo=1, ctx_hi=150, seed=310)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    Lmax = case.max_context_len
+    k_out = torch.zeros((cfg.batch, Lmax, 2, 128), dtype=torch.bfloat16, device="cuda")
+    v_out = torch.zeros_like(k_out)
+    G.gather_kv(k_out, v_out, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens)
+    torch.cuda.synchronize()
+    kc, vc = oracle_filled(oracle, case)
+    kh, vh = U.to_host(k_out), U.to_host(v_out)
+    for b in range(cfg.batch):
+        L = int(case.context_lens[b])
+        j = np.arange(L)
+        blk = case.block_tables[b, j // 16]
+        assert np.array_equal(kh[b, :L], kc[blk, :, j % 16, :])
+        assert np.array_equal(vh[b, :L], vc[blk, :, j % 16, :])
+        assert not kh[b, L:].any() and not vh[b, L:].any()
+
+
+# ------------------------------------------------------------------ decode, small sweep
+SWEEP = [
+    # dtype, Hq, Hkv, D, bs, batch, ctx_lo, ctx_hi
+    (W.F16, 8, 2, 64, 16, 3, 1, 200),
+    (W.BF16, 8, 2, 64, 16, 3, 1, 200),
+    (W.F16, 32, 8, 128, 16, 5, 1, 700),
+    (W.BF16, 32, 4, 128, 32, 4, 1, 900),
+    (W.F16, 16, 16, 128, 16, 2, 30, 333),       # MHA, G = 1
+    (W.BF16, 4, 2, 128, 64, 3, 1, 400),         # G = 2, block 64
+    (W.F16, 12, 4, 64, 32, 3, 1, 300),          # G = 3 -> one head per workgroup
+    (W.BF16, 12, 2, 128, 16, 2, 1, 300),        # G = 6 -> two heads per workgroup, three chunks
+    (W.F16, 32, 2, 64, 16, 2, 1, 500),          # G = 16 -> two chunks of eight
+    (W.BF16, 8, 1, 128, 16, 2, 1, 1500),        # multi-query
+]
+
+
+@pytest.mark.parametrize("i", range(len(SWEEP)))
+@pytest.mark.parametrize("partition", [-1, 0, 64, 256])
+def test_decode_sweep(U, oracle, i, partition):
+    dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
+    if partition > 0 and partition % bs:
+        pytest.skip("partition size must be a multiple of the block size")
+    cfg = W.small_config(name=f"sweep{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
+                         ctx_hi=hi, seed=400 + i)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    got = dev.decode(partition_size=partition)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    err = U.max_abs_err(got, ref, dtype)
+    assert err <= U.TOL[dtype], f"max abs err {err}"
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_decode_edge_lengths(U, oracle, dtype):
+    """Context lengths 0, 1, exactly one block, block +- 1, partition +- 1, in one batch."""
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1], np.int32)
+    cfg = W.small_config(name="edges", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2, head_dim=128,
+                         block_size=16, num_blocks=160, ctx_lo=1, ctx_hi=512, seed=420)
+    case = W.make_case(cfg, context_lens=lens)
+    # q rows exist only for non-empty sequences in the generator; give every sequence a row
+    q_full = np.zeros((len(lens), 8, 128), np.uint16)
+    q_full[lens > 0] = case.q
+    case.q = q_full
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    for partition in (-1, 0, 64, 256):
+        dev = U.DevCase(case)
+        dev.write_cache()
+        got = dev.decode(partition_size=partition)
+        assert not got[0].any(), "an empty context must give +0"
+        assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype]
+        # a one-token context returns V bit for bit (weight exactly 1)
+        for b in (1, 12):
+            pb = case.block_tables[b, 0]
+            for h in range(8):
+                assert np.array_equal(got[b, h], vc[pb, h // 4, 0, :])
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_decode_one_hot_selects_row_bit_exact(U, oracle, dtype):
+    """K = 0 and a slope of +-200: every weight but one underflows to exactly 0, so the output
+    must be the selected V row bit for bit -- pins block-table, partial-block and partition
+    indexing through the real kernels."""
+    Hq = 8
+    slopes = np.array([200.0, -200.0] * (Hq // 2), np.float32)
+    cfg = W.small_config(name="onehot", dtype=dtype, batch=6, num_heads=Hq, num_kv_heads=2, head_dim=128,
+                         block_size=16, num_blocks=300, ctx_lo=1, ctx_hi=700, seed=430)
+    case = W.make_case(cfg, slopes=slopes)
+    case.k_cache[:] = 0
+    case.k_new[:] = 0
+    kc, vc = oracle_filled(oracle, case)
+    for partition in (-1, 64, 256):
+        dev = U.DevCase(case)
+        dev.write_cache()
+        got = dev.decode(partition_size=partition)
+        for b in range(cfg.batch):
+            L = int(case.context_lens[b])
+            newest = vc[case.block_tables[b, (L - 1) // 16], :, (L - 1) % 16, :]
+            oldest = vc[case.block_tables[b, 0], :, 0, :]
+            for h in range(Hq):
+                want = newest if h % 2 == 0 else oldest
+                assert np.array_equal(got[b, h], want[h // 4]), (partition, b, h)
+
+
+def test_decode_block_permutation_bit_identical(U, oracle):
+    cfg = W.small_config(name="permgpu", dtype=W.F16, batch=4, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=16, num_blocks=256, ctx_lo=1, ctx_hi=800, seed=440)
+    outs = []
+    for ps in (None, 5, 6):
+        case = W.make_case(cfg, perm_seed=ps)
+        dev = U.DevCase(case)
+        dev.write_cache()
+        outs.append(dev.decode(partition_size=0))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_decode_no_slopes_and_steep_slopes(U, oracle):
+    cfg = W.small_config(name="slopes", dtype=W.F16, batch=3, num_heads=8, num_kv_heads=2, head_dim=64,
+                         block_size=16, num_blocks=200, ctx_lo=100, ctx_hi=900, seed=450)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    kc, vc = oracle_filled(oracle, case)
+    got = dev.decode(slopes=None)
+    ref = oracle_decode(oracle, case, kc, vc, slopes=None)
+    assert U.max_abs_err(got, ref, W.F16) <= U.TOL[W.F16]
+    import torch
+    steep = np.array([30.0, 7.0, 1.0, 0.0, 0.25, 3.0, 12.0, 0.01], np.float32)
+    for partition in (-1, 64):
+        got = dev.decode(slopes=torch.from_numpy(steep).cuda(), partition_size=partition)
+        ref = oracle_decode(oracle, case, kc, vc, slopes=steep)
+        assert U.max_abs_err(got, ref, W.F16) <= U.TOL[W.F16]
+
+
+def test_append_equals_bulk_fill(U, oracle):
+    """Token-by-token (cache write of one token, then decode) reaches the same cache bits and the
+    same output as one bulk fill followed by one decode (eq. (2))."""
+    import torch
+    import paper_2505_02351_amd as G
+    steps = 20
+    cfg = W.small_config(name="append", kind="prefill", dtype=W.BF16, batch=2, num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=32, ctx_lo=45, ctx_hi=60, q_len=steps, seed=460)
+    case = W.make_case(cfg)
+    bulk = U.DevCase(case)
+    bulk.write_cache()
+    inc = U.DevCase(case)
+    out = torch.empty((2, 8, 128), dtype=torch.bfloat16, device="cuda")
+    for s in range(steps):
+        idx = torch.tensor([int(case.cu_q_lens[b]) + s for b in range(2)], device="cuda")
+        G.reshape_and_cache(inc.k_new[idx], inc.v_new[idx], inc.k_cache, inc.v_cache, inc.slot_mapping[idx])
+        lens = torch.from_numpy(case.context_lens - steps + s + 1).cuda()
+        G.paged_attention(out, inc.q[idx].contiguous(), inc.k_cache, inc.v_cache, inc.block_tables, lens,
+                          inc.slopes, float(case.scale), int(lens.max()), -1, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.to_host(inc.k_cache), U.to_host(bulk.k_cache))
+    assert np.array_equal(U.to_host(inc.v_cache), U.to_host(bulk.v_cache))
+    last = torch.tensor([int(case.cu_q_lens[b]) + steps - 1 for b in range(2)], device="cuda")
+    out2 = torch.empty_like(out)
+    G.paged_attention(out2, bulk.q[last].contiguous(), bulk.k_cache, bulk.v_cache, bulk.block_tables,
+                      bulk.context_lens, bulk.slopes, float(case.scale), case.max_context_len, -1, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(U.to_host(out), U.to_host(out2))
+
+
+# ------------------------------------------------------------------ the workloads themselves
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_decode_workload_full(U, oracle, name):
+    case = W.make_case(W.CONFIGS[name])
+    dev = U.DevCase(case)
+    dev.write_cache()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    ref = oracle_decode(oracle, case, kc, vc)
+    for partition in (0, -1):
+        got = dev.decode(partition_size=partition)
+        err = U.max_abs_err(got, ref, case.dtype)
+        assert err <= U.TOL[case.dtype], (name, partition, err)
+
+
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_decode_workload_sampled(U, oracle, name):
+    """Full-size batch in the launch configuration the bench times; the oracle evaluates a sample
+    of (sequence, head) rows one by one, chosen to include the longest and shortest sequences."""
+    cfg = W.CONFIGS[name]
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    got = dev.decode(partition_size=cfg.partition_size)
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    kc, vc = oracle_filled(oracle, case)
+    rng = np.random.default_rng(99)
+    seqs = {int(np.argmax(case.context_lens)), int(np.argmin(case.context_lens)), 0, cfg.batch - 1}
+    rows = [(b, h) for b in sorted(seqs) for h in (0, cfg.num_heads // 2 + 1, cfg.num_heads - 1)]
+    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(20)]
+    ref = oracle_decode(oracle, case, kc, vc, rows=rows)
+    sub = np.stack([got[b, h] for b, h in rows])
+    err = U.max_abs_err(sub, ref, case.dtype)
+    assert err <= U.TOL[case.dtype], (name, err)
+    # the new tokens' cache rows were written bit-exactly
+    for b in range(cfg.batch):
+        s = int(case.slot_mapping[b])
+        assert np.array_equal(U.to_host(dev.k_cache[s // cfg.block_size, :, s % cfg.block_size]), case.k_new[b])
+
+
+# ------------------------------------------------------------------ prefill
+PF = [
+    (W.BF16, 8, 2, 128, 16, 3, 40, 300, 33),
+    (W.F16, 8, 2, 64, 16, 2, 20, 200, 20),
+    (W.BF16, 32, 8, 128, 16, 2, 300, 700, 130),
+    (W.F16, 4, 4, 128, 32, 2, 64, 400, 64),
+    (W.BF16, 6, 2, 128, 16, 2, 5, 100, 100),        # q_len > some contexts: whole prompt is new
+]
+
+
+@pytest.mark.parametrize("i", range(len(PF)))
+def test_prefill_sweep(U, oracle, i):
+    dtype, Hq, Hkv, D, bs, B, lo, hi, q_len = PF[i]
+    cfg = W.small_config(name=f"pf{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
+                         ctx_hi=hi, q_len=q_len, seed=500 + i)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    got = dev.prefill()
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, dtype)
+    err = U.max_abs_err(got, ref, dtype)
+    assert err <= U.TOL[dtype], err
+
+
+def test_prefill_workload_sampled(U, oracle):
+    cfg = W.CONFIGS["C5"]
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    got = dev.prefill()
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    rng = np.random.default_rng(98)
+    T = case.num_tokens
+    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (T // 2, 17)]
+    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, case.dtype, rows=rows)
+    sub = np.stack([got[t, h] for t, h in rows])
+    err = U.max_abs_err(sub, ref, case.dtype)
+    assert err <= U.TOL[case.dtype], err
