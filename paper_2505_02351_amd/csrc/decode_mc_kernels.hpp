@@ -1,0 +1,309 @@
+// Paged decode attention, group sizes that are multiples of 4: the fast path.
+//
+// Same work decomposition and the same K/V register layout as paged_decode_kernel (16-byte
+// loads, D/8 consecutive lanes per token row, one K/V fetch per KV-head group), but with the
+// arithmetic re-balanced for CDNA4:
+//   * q.k: 2-way dot instructions on the packed 2-byte data, then a TRANSPOSING reduction
+//     inside each quad of lanes, so that lane u of every quad ends up owning the finished
+//     scores of heads u and u+4 (no score is computed redundantly, softmax work is 4x less);
+//   * softmax: fp32, against a lazily updated reference maximum (the accumulators are only
+//     rescaled when a tile's maximum exceeds the reference by 2^kRescaleThreshold);
+//   * p.V: the matrix cores.  v_mfma_f32_4x4x1 performs 16 independent 4x4 outer products:
+//     block = quad of lanes, A = the quad's four weights (one head per lane), B = each lane's
+//     own widened V element.  All operands are fp32, so the weights are never rounded, and no
+//     tile row is padding: the instruction does exactly GH x 8 multiply-adds per lane that the
+//     vector ALU would otherwise issue one by one, and it runs beside the vector ALU.
+// K/V tiles are prefetched one wave tile (U steps) ahead into a second register set.
+#pragma once
+#include "decode_kernels.hpp"
+
+namespace optgqa {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kRescaleThreshold = 16.f;    // log2 units
+constexpr float kNoMax = -1.0e30f;           // "no key seen yet"; finite so that differences stay finite
+constexpr int kMcSteps = 2;                  // steps per wave tile
+
+template <int V> __device__ __forceinline__ float quad_bcast(float x)
+{
+    return dpp<V * 0x55>(x);                 // quad_perm [V,V,V,V]
+}
+
+// Sum over the quads of a token row group for values that differ between the lanes of a quad.
+template <int LPR> __device__ __forceinline__ float cross_quad_sum(float x);
+template <> __device__ __forceinline__ float cross_quad_sum<16>(float x)
+{
+    x += dpp<kDppRowRor8>(x);                // lane i ^ 8
+    x += dpp<kDppRowRor4>(x);                // now symmetric under ^8, so i-4 completes the four quads
+    return x;
+}
+template <> __device__ __forceinline__ float cross_quad_sum<8>(float x)
+{
+    // partner quad is lane i ^ 4: take i+4 in even quads, i-4 in odd quads
+    int v = __builtin_bit_cast(int, x);
+    int t = __builtin_amdgcn_update_dpp(0, v, 0x104, 0xf, 0x5, false);     // row_shl:4, quads 0 and 2
+    t = __builtin_amdgcn_update_dpp(t, v, 0x114, 0xf, 0xa, false);         // row_shr:4, quads 1 and 3
+    return x + __builtin_bit_cast(float, t);
+}
+
+template <int DT, int D, int GH>
+struct McTile {
+    uint4 k[kMcSteps];
+    uint4 v[kMcSteps];
+};
+
+template <int DT, int D, int GH>
+__global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(const DecodeParams p)
+{
+    static_assert(GH == 4 || GH == 8, "heads per workgroup must be 4 or 8");
+    constexpr int LPR = D / 8;               // lanes per token row
+    constexpr int TPS = 64 / LPR;            // token rows per step
+    constexpr int NW = kDecodeWaves;
+    constexpr int U = kMcSteps;
+    constexpr int TILE = U * TPS;            // tokens per wave tile
+    constexpr int HPL = GH / 4;              // heads owned per lane after the reduction
+    constexpr int NSTREAM = NW * TPS;        // independent softmax streams per workgroup
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane / LPR, c = lane % LPR, u = lane & 3;
+    const bool u0 = (lane & 1) != 0, u1 = (lane & 2) != 0;
+
+    const int part = blockIdx.x, row = p.row_offset + blockIdx.z;
+    const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
+    const int bs_shift = __builtin_ctz(bs);
+    const int G = Hq / Hkv;
+    const int chunks = G / GH;
+    const int g = blockIdx.y / chunks;
+    const int h0 = g * G + (blockIdx.y - g * chunks) * GH;
+
+    int b, L;
+    if (!row_to_seq(p, row, b, L)) return;
+    const int t_begin = part * p.partition_size;
+    const int t_end = min(L, t_begin + p.partition_size);
+    if (t_begin >= t_end) {
+        if (p.num_partitions == 1) {
+            uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
+            for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
+        }
+        return;
+    }
+    const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
+    const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache);
+    const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
+    const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
+
+    uint4 qv[GH];
+#pragma unroll
+    for (int i = 0; i < GH; ++i)
+        qv[i] = *reinterpret_cast<const uint4*>(qp + ((int64_t)row * Hq + h0 + i) * D + 8 * c);
+    float slope2[HPL], m_ref[HPL], l[HPL];
+    f32x4 acc[8][HPL];
+#pragma unroll
+    for (int i = 0; i < HPL; ++i) {
+        slope2[i] = p.slopes ? p.slopes[h0 + u + 4 * i] * kLog2e : 0.f;
+        m_ref[i] = kNoMax;
+        l[i] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float scale2 = p.scale2;
+    const int Lm1 = L - 1;
+    // Addresses: a wave-uniform 64-bit part (physical block, KV head, first row of the step)
+    // plus a small per-lane part (row inside the step, dim chunk).  Every load is in bounds and
+    // unconditional: steps or rows past the end of the range re-read the last valid row and are
+    // masked out of the scores instead.
+    const uint16_t* __restrict__ kc_g = kc + (int64_t)g * bs * D;
+    const uint16_t* __restrict__ vc_g = vc + (int64_t)g * bs * D;
+    const int64_t block_stride = (int64_t)Hkv * bs * D;
+    const int t_last = t_end - 1;
+    const int t_last0 = t_last & ~(TPS - 1);                         // first row of the last valid step
+
+    auto load_tile = [&](McTile<DT, D, GH>& T, int tile) {
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            const int t0 = min(t_begin + tile * TILE + s * TPS, t_last0);            // wave-uniform
+            const int blk = __builtin_amdgcn_readfirstlane(table[t0 >> bs_shift]);
+            const int64_t uni = blk * block_stride + (int64_t)(t0 & (bs - 1)) * D;
+            const int lane_off = (min(t0 + r, t_last) - t0) * D + 8 * c;
+            T.k[s] = *reinterpret_cast<const uint4*>(kc_g + uni + lane_off);
+            T.v[s] = *reinterpret_cast<const uint4*>(vc_g + uni + lane_off);
+        }
+    };
+
+    auto compute_tile = [&](const McTile<DT, D, GH>& T, int tile) {
+        float sc[U][HPL], tmax[HPL];
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) tmax[i] = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            const int t = t_begin + tile * TILE + s * TPS + r;
+            const bool valid = t < t_end;
+            const uint4 kr = T.k[s];
+            float part[GH];
+#pragma unroll
+            for (int i = 0; i < GH; ++i) {
+                float d = dot2<DT>(qv[i].x, kr.x, 0.f);
+                d = dot2<DT>(qv[i].y, kr.y, d);
+                d = dot2<DT>(qv[i].z, kr.z, d);
+                part[i] = dot2<DT>(qv[i].w, kr.w, d);
+            }
+            // transposing reduction inside the quad: lane u keeps heads with (h & 3) == u
+            float y[GH / 2];
+#pragma unroll
+            for (int j = 0; j < GH / 2; ++j) {
+                const float keep = u0 ? part[2 * j + 1] : part[2 * j];
+                const float send = u0 ? part[2 * j] : part[2 * j + 1];
+                y[j] = keep + dpp<kDppXor1>(send);                  // head 2j + u0, summed over the lane pair
+            }
+            const float rel = (float)(t - Lm1);                      // exact: |rel| < 2^24
+#pragma unroll
+            for (int i = 0; i < HPL; ++i) {
+                const float keep = u1 ? y[2 * i + 1] : y[2 * i];
+                const float send = u1 ? y[2 * i] : y[2 * i + 1];
+                float z = keep + dpp<kDppXor2>(send);                // head 4i + u, summed over the quad
+                z = cross_quad_sum<LPR>(z);                          // ... and over the whole token row
+                const float s2 = valid ? fmaf(z, scale2, slope2[i] * rel) : -INFINITY;   // eq. (3), base 2
+                sc[s][i] = s2;
+                tmax[i] = fmaxf(tmax[i], s2);
+            }
+        }
+        // lazy rescale: only when some head's tile maximum runs away from the reference
+        bool need = false;
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) need |= tmax[i] > m_ref[i] + kRescaleThreshold;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+            for (int i = 0; i < HPL; ++i) {
+                const bool nd = tmax[i] > m_ref[i] + kRescaleThreshold;
+                const float m_new = nd ? tmax[i] : m_ref[i];
+                const float alpha = fast_exp2(m_ref[i] - m_new);     // 1 when unchanged, 0 on first use
+                l[i] *= alpha;
+                m_ref[i] = m_new;
+                const float a0 = quad_bcast<0>(alpha), a1 = quad_bcast<1>(alpha);
+                const float a2 = quad_bcast<2>(alpha), a3 = quad_bcast<3>(alpha);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    acc[e][i][0] *= a0;
+                    acc[e][i][1] *= a1;
+                    acc[e][i][2] *= a2;
+                    acc[e][i][3] *= a3;
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < U; ++s) {
+            const uint4 vr = T.v[s];
+            const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
+                                 widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};
+            float pw[HPL];
+#pragma unroll
+            for (int i = 0; i < HPL; ++i) {
+                pw[i] = fast_exp2(sc[s][i] - m_ref[i]);              // eq. (4) numerator; 0 for absent keys
+                l[i] += pw[i];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int i = 0; i < HPL; ++i)
+                    acc[e][i] = __builtin_amdgcn_mfma_f32_4x4x1f32(pw[i], vf[e], acc[e][i], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: wave w owns tiles w, w+NW, ...; two register sets, one tile of lookahead
+    const int ntiles = (t_end - t_begin + TILE - 1) / TILE;
+    {
+        McTile<DT, D, GH> A, B;
+        int tile = wave;
+        if (tile < ntiles) load_tile(A, tile);
+        while (tile < ntiles) {
+            if (tile + NW < ntiles) load_tile(B, tile + NW);
+            compute_tile(A, tile);
+            tile += NW;
+            if (tile >= ntiles) break;
+            if (tile + NW < ntiles) load_tile(A, tile + NW);
+            compute_tile(B, tile);
+            tile += NW;
+        }
+    }
+
+    // ---- merge the NSTREAM softmax streams of the workgroup --------------------------------
+    __shared__ float sm_m[NSTREAM][GH];
+    __shared__ float sm_l[NSTREAM][GH];
+    __shared__ __attribute__((aligned(16))) float sm_o[NSTREAM / 2][GH][D];
+    const int stream = wave * TPS + r;
+    if (c < 4) {
+#pragma unroll
+        for (int i = 0; i < HPL; ++i) {
+            sm_m[stream][u + 4 * i] = m_ref[i];
+            sm_l[stream][u + 4 * i] = l[i];
+        }
+    }
+    __syncthreads();
+    // every lane: the workgroup maximum of each head and this stream's factor against it
+    float f[GH];
+#pragma unroll
+    for (int h = 0; h < GH; ++h) {
+        float M = sm_m[0][h];
+#pragma unroll
+        for (int s = 1; s < NSTREAM; ++s) M = fmaxf(M, sm_m[s][h]);
+        f[h] = fast_exp2(sm_m[stream][h] - M);              // a stream without keys: 2^(-1e30 - M) = 0
+    }
+    // output element(s) this thread finishes: one float4 of one head
+    constexpr int kVecs = GH * D / 4;
+    const int idx = threadIdx.x;
+    const int oh = idx / (D / 4), od = (idx - oh * (D / 4)) * 4;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        if (half) __syncthreads();                          // first half fully consumed
+        if ((stream >= NSTREAM / 2) == (half == 1)) {
+            const int sl = stream - half * (NSTREAM / 2);
+#pragma unroll
+            for (int h = 0; h < GH; ++h) {
+                const int i = h >> 2, v = h & 3;
+                *reinterpret_cast<float4*>(&sm_o[sl][h][8 * c]) =
+                    make_float4(acc[0][i][v] * f[h], acc[1][i][v] * f[h], acc[2][i][v] * f[h], acc[3][i][v] * f[h]);
+                *reinterpret_cast<float4*>(&sm_o[sl][h][8 * c + 4]) =
+                    make_float4(acc[4][i][v] * f[h], acc[5][i][v] * f[h], acc[6][i][v] * f[h], acc[7][i][v] * f[h]);
+            }
+        }
+        __syncthreads();
+        if (idx < kVecs) {
+#pragma unroll
+            for (int s = 0; s < NSTREAM / 2; ++s) {
+                const float4 x = *reinterpret_cast<const float4*>(&sm_o[s][oh][od]);
+                num.x += x.x;
+                num.y += x.y;
+                num.z += x.z;
+                num.w += x.w;
+            }
+        }
+    }
+    if (idx < kVecs) {
+        float M = sm_m[0][oh];
+#pragma unroll
+        for (int s = 1; s < NSTREAM; ++s) M = fmaxf(M, sm_m[s][oh]);
+        float den = 0.f;
+#pragma unroll
+        for (int s = 0; s < NSTREAM; ++s) den = fmaf(fast_exp2(sm_m[s][oh] - M), sm_l[s][oh], den);
+        const int h = h0 + oh;
+        if (p.num_partitions == 1) {
+            const float inv = 1.f / den;
+            uint2 packed;
+            packed.x = narrow2<DT>(num.x * inv, num.y * inv);
+            packed.y = narrow2<DT>(num.z * inv, num.w * inv);
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h) * D + od) = packed;
+        } else {
+            const int64_t slot = ((int64_t)row * Hq + h) * p.num_partitions + part;
+            if (od == 0) {
+                p.ws_m[slot] = M;
+                p.ws_l[slot] = den;
+            }
+            *reinterpret_cast<float4*>(p.ws_o + slot * D + od) = num;
+        }
+    }
+}
+
+}  // namespace optgqa

@@ -6,6 +6,7 @@
 
 #include "cache_kernels.hpp"
 #include "decode_kernels.hpp"
+#include "decode_mc_kernels.hpp"
 #include "prefill_kernels.hpp"
 
 using namespace optgqa;
@@ -81,8 +82,13 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
 {
     const dim3 block(kDecodeWaves * 64);
     switch (gh) {
+#ifdef OPTGQA_VALU_ONLY_DECODE
     case 8: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 8>), grid, block, 0, st, p); break;
     case 4: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 4>), grid, block, 0, st, p); break;
+#else
+    case 8: hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, 8>), grid, block, 0, st, p); break;
+    case 4: hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, 4>), grid, block, 0, st, p); break;
+#endif
     case 2: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 2>), grid, block, 0, st, p); break;
     default: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 1>), grid, block, 0, st, p); break;
     }
