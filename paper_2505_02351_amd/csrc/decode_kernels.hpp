@@ -61,6 +61,15 @@ __device__ __forceinline__ bool row_to_seq(const DecodeParams& p, int row, int& 
 
 constexpr int kDecodeWaves = 4;
 
+// Partition index of this workgroup.  Workgroups go to the 8 XCDs round-robin by flat id; with
+// grid.x = number of partitions and late partitions mostly empty (short sequences), the plain
+// mapping would give some XCDs all the work whenever grid.x shares a factor with 8.  Rotating
+// the partition index by the other two grid coordinates hands every XCD the same mix.
+__device__ __forceinline__ int skewed_partition(int num_partitions)
+{
+    return (blockIdx.x + blockIdx.y + blockIdx.z) % num_partitions;
+}
+
 template <int DT, int D, int GH>
 __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const DecodeParams p)
 {
@@ -71,7 +80,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane / LPR, c = lane % LPR;
 
-    const int part = blockIdx.x, row = p.row_offset + blockIdx.z;
+    const int row = p.row_offset + blockIdx.z;
+    const int part = skewed_partition(p.num_partitions);
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int G = Hq / Hkv;
     const int chunks = G / GH;

@@ -6,14 +6,21 @@
 //   * q.k: 2-way dot instructions on the packed 2-byte data, then a TRANSPOSING reduction
 //     inside each quad of lanes, so that lane u of every quad ends up owning the finished
 //     scores of heads u and u+4 (no score is computed redundantly, softmax work is 4x less);
-//   * softmax: fp32, against a lazily updated reference maximum (the accumulators are only
-//     rescaled when a tile's maximum exceeds the reference by 2^kRescaleThreshold);
+//   * softmax: fp32, against a lazily updated reference instead of the exact running maximum.
+//     ALiBi makes scores climb steadily along the context, so an exact running maximum would
+//     rescale the accumulators every tile.  The reference is only moved when a tile maximum
+//     exceeds it by 2^kRescaleThreshold, and is then placed 2^kRescaleHeadroom above that
+//     maximum: weights live in [2^-90, 2^30] relative to any later maximum that matters, well
+//     inside fp32 range, and softmax is invariant to the choice of reference;
 //   * p.V: the matrix cores.  v_mfma_f32_4x4x1 performs 16 independent 4x4 outer products:
 //     block = quad of lanes, A = the quad's four weights (one head per lane), B = each lane's
 //     own widened V element.  All operands are fp32, so the weights are never rounded, and no
 //     tile row is padding: the instruction does exactly GH x 8 multiply-adds per lane that the
 //     vector ALU would otherwise issue one by one, and it runs beside the vector ALU.
-// K/V tiles are prefetched one wave tile (U steps) ahead into a second register set.
+// K/V tiles travel HBM -> LDS with direct-to-LDS loads (no VGPRs held while in flight) into a
+// per-wave ring of kMcRingTiles tiles, kMcRingTiles-1 tiles ahead of the arithmetic; each lane
+// later reads back exactly the 16 bytes it fetched.  The ring is private to a wave, so the
+// only synchronisation is a vmcnt wait.
 #pragma once
 #include "decode_kernels.hpp"
 
@@ -21,9 +28,11 @@ namespace optgqa {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr float kRescaleThreshold = 16.f;    // log2 units
+constexpr float kRescaleThreshold = 30.f;    // log2 units: rescale when a tile maximum exceeds the reference by this
+constexpr float kRescaleHeadroom = 60.f;     // ... and then put the reference this far ABOVE the maximum
 constexpr float kNoMax = -1.0e30f;           // "no key seen yet"; finite so that differences stay finite
 constexpr int kMcSteps = 2;                  // steps per wave tile
+constexpr int kMcRingTiles = 3;              // ring slots per wave (tiles in flight + the one in use)
 
 template <int V> __device__ __forceinline__ float quad_bcast(float x)
 {
@@ -47,16 +56,45 @@ template <> __device__ __forceinline__ float cross_quad_sum<8>(float x)
     return x + __builtin_bit_cast(float, t);
 }
 
-template <int DT, int D, int GH>
-struct McTile {
-    uint4 k[kMcSteps];
-    uint4 v[kMcSteps];
-};
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Wait until at most NEWER direct-to-LDS loads issued after the wanted tile are still in
+// flight, then read the tile's four 16-byte pieces (K step 0, K step 1, V step 0, V step 1)
+// back from this lane's place in the ring.  The wait and the reads are one asm block because
+// the compiler cannot be told which outstanding load a given LDS read depends on (it would
+// wait for all of them, the newest prefetch included).
+template <int NEWER>
+__device__ __forceinline__ void ring_read2(uint32_t lds_addr, u32x4& k0, u32x4& k1, u32x4& v0, u32x4& v1)
+{
+    asm volatile(
+        "s_waitcnt vmcnt(%5)\n\t"
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:1024\n\t"
+        "ds_read_b128 %2, %4 offset:2048\n\t"
+        "ds_read_b128 %3, %4 offset:3072\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k0), "=&v"(k1), "=&v"(v0), "=&v"(v1)
+        : "v"(lds_addr), "n"(NEWER)
+        : "memory");
+}
+
+// Read one block-table entry through the scalar (constant) cache.  Written as asm because the
+// compiler stops selecting scalar loads once direct-to-LDS loads (which it must treat as
+// stores it cannot see through) are in flight, and a vector load here would force a wait for
+// every outstanding prefetch.  Read-only; the table is never written while the kernel runs.
+__device__ __forceinline__ int scalar_load_i32(const int32_t* uniform_ptr)
+{
+    int v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(uniform_ptr) : "memory");
+    return v;
+}
 
 template <int DT, int D, int GH>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(const DecodeParams p)
 {
     static_assert(GH == 4 || GH == 8, "heads per workgroup must be 4 or 8");
+    static_assert(kMcSteps == 2, "ring_read2 reads two steps per tile");
+    static_assert(kMcSteps * (64 / (D / 8)) <= 16, "a wave tile must not straddle a 16-token block");
     constexpr int LPR = D / 8;               // lanes per token row
     constexpr int TPS = 64 / LPR;            // token rows per step
     constexpr int NW = kDecodeWaves;
@@ -64,13 +102,23 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
     constexpr int TILE = U * TPS;            // tokens per wave tile
     constexpr int HPL = GH / 4;              // heads owned per lane after the reduction
     constexpr int NSTREAM = NW * TPS;        // independent softmax streams per workgroup
+    constexpr int NT = kMcRingTiles;
+    constexpr int PT = NT - 1;               // tiles of lookahead
+    constexpr int kTileBytes = U * 2 * 1024; // K and V, 1 KiB per step each
+    constexpr int kRingBytes = NW * NT * kTileBytes;
+    constexpr int kMergeBytes = (NSTREAM / 2) * GH * D * 4;
+    constexpr int kSmemBytes = kRingBytes > kMergeBytes ? kRingBytes : kMergeBytes;
+
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];   // ring, later the merge buffer
+    __shared__ float sm_m[NSTREAM][GH];
+    __shared__ float sm_l[NSTREAM][GH];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane / LPR, c = lane % LPR, u = lane & 3;
-    const bool u0 = (lane & 1) != 0, u1 = (lane & 2) != 0;
 
-    const int part = blockIdx.x, row = p.row_offset + blockIdx.z;
+    const int row = p.row_offset + blockIdx.z;
+    const int part = skewed_partition(p.num_partitions);
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
     const int G = Hq / Hkv;
@@ -94,10 +142,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
     const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
     const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
 
+    // q, this lane's 8 dims, still packed, in a lane-dependent head order: slot 4i+k holds head
+    // 4i + (u ^ k).  With that order the transposing reduction needs no selects: slot 0 is the
+    // head this lane ends up owning, slots 1..3 are the partial sums it hands to lanes u^1, u^2.
     uint4 qv[GH];
 #pragma unroll
     for (int i = 0; i < GH; ++i)
-        qv[i] = *reinterpret_cast<const uint4*>(qp + ((int64_t)row * Hq + h0 + i) * D + 8 * c);
+        qv[i] = *reinterpret_cast<const uint4*>(qp + ((int64_t)row * Hq + h0 + (i & ~3) + (u ^ (i & 3))) * D + 8 * c);
     float slope2[HPL], m_ref[HPL], l[HPL];
     f32x4 acc[8][HPL];
 #pragma unroll
@@ -120,19 +171,30 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
     const int t_last = t_end - 1;
     const int t_last0 = t_last & ~(TPS - 1);                         // first row of the last valid step
 
-    auto load_tile = [&](McTile<DT, D, GH>& T, int tile) {
+    // Each wave owns a contiguous quarter of the tiles (so that the ALiBi bias climbs slowly
+    // along a wave's stream); its j-th tile lives in ring slot j % NT.
+    const int ntiles = (t_end - t_begin + TILE - 1) / TILE;
+    const int tpw = (ntiles + NW - 1) / NW;
+    const int tile_first = wave * tpw;
+    const int ntw = max(0, min(tpw, ntiles - tile_first));
+    unsigned char* const ring = smem + wave * (NT * kTileBytes);
+
+    auto issue_tile = [&](int j) {
+        const int tile = tile_first + j;
+        unsigned char* const slot = ring + (j % NT) * kTileBytes;
+        const int tile_t0 = t_begin + tile * TILE;                                    // < t_end
+        const int blk = scalar_load_i32(table + (tile_t0 >> bs_shift));               // one block per tile
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const int t0 = min(t_begin + tile * TILE + s * TPS, t_last0);            // wave-uniform
-            const int blk = __builtin_amdgcn_readfirstlane(table[t0 >> bs_shift]);
+            const int t0 = min(tile_t0 + s * TPS, t_last0);                           // wave-uniform
             const int64_t uni = blk * block_stride + (int64_t)(t0 & (bs - 1)) * D;
             const int lane_off = (min(t0 + r, t_last) - t0) * D + 8 * c;
-            T.k[s] = *reinterpret_cast<const uint4*>(kc_g + uni + lane_off);
-            T.v[s] = *reinterpret_cast<const uint4*>(vc_g + uni + lane_off);
+            __builtin_amdgcn_global_load_lds(kc_g + uni + lane_off, slot + s * 1024, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vc_g + uni + lane_off, slot + (U + s) * 1024, 16, 0, 0);
         }
     };
 
-    auto compute_tile = [&](const McTile<DT, D, GH>& T, int tile) {
+    auto compute_tile = [&](const u32x4 (&kt)[U], const u32x4 (&vt)[U], int tile) {
         float sc[U][HPL], tmax[HPL];
 #pragma unroll
         for (int i = 0; i < HPL; ++i) tmax[i] = -INFINITY;
@@ -140,44 +202,38 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
         for (int s = 0; s < U; ++s) {
             const int t = t_begin + tile * TILE + s * TPS + r;
             const bool valid = t < t_end;
-            const uint4 kr = T.k[s];
+            const u32x4 kr = kt[s];
             float part[GH];
 #pragma unroll
             for (int i = 0; i < GH; ++i) {
-                float d = dot2<DT>(qv[i].x, kr.x, 0.f);
-                d = dot2<DT>(qv[i].y, kr.y, d);
-                d = dot2<DT>(qv[i].z, kr.z, d);
-                part[i] = dot2<DT>(qv[i].w, kr.w, d);
+                float d = dot2<DT>(qv[i].x, kr[0], 0.f);
+                d = dot2<DT>(qv[i].y, kr[1], d);
+                d = dot2<DT>(qv[i].z, kr[2], d);
+                part[i] = dot2<DT>(qv[i].w, kr[3], d);
             }
-            // transposing reduction inside the quad: lane u keeps heads with (h & 3) == u
-            float y[GH / 2];
-#pragma unroll
-            for (int j = 0; j < GH / 2; ++j) {
-                const float keep = u0 ? part[2 * j + 1] : part[2 * j];
-                const float send = u0 ? part[2 * j] : part[2 * j + 1];
-                y[j] = keep + dpp<kDppXor1>(send);                  // head 2j + u0, summed over the lane pair
-            }
+            // transposing reduction inside the quad (see the order of qv): afterwards lane u holds
+            // the finished dot products of heads 4i + u
             const float rel = (float)(t - Lm1);                      // exact: |rel| < 2^24
 #pragma unroll
             for (int i = 0; i < HPL; ++i) {
-                const float keep = u1 ? y[2 * i + 1] : y[2 * i];
-                const float send = u1 ? y[2 * i] : y[2 * i + 1];
-                float z = keep + dpp<kDppXor2>(send);                // head 4i + u, summed over the quad
+                const float yk = part[4 * i + 0] + dpp<kDppXor1>(part[4 * i + 1]);
+                const float ys = part[4 * i + 2] + dpp<kDppXor1>(part[4 * i + 3]);
+                float z = yk + dpp<kDppXor2>(ys);                    // head 4i + u, summed over the quad
                 z = cross_quad_sum<LPR>(z);                          // ... and over the whole token row
                 const float s2 = valid ? fmaf(z, scale2, slope2[i] * rel) : -INFINITY;   // eq. (3), base 2
                 sc[s][i] = s2;
                 tmax[i] = fmaxf(tmax[i], s2);
             }
         }
-        // lazy rescale: only when some head's tile maximum runs away from the reference
+        // lazy rescale: when some head's tile maximum runs away from its reference, move every
+        // reference of the wave to kRescaleHeadroom above the current maxima
         bool need = false;
 #pragma unroll
         for (int i = 0; i < HPL; ++i) need |= tmax[i] > m_ref[i] + kRescaleThreshold;
         if (__builtin_amdgcn_ballot_w64(need) != 0) {
 #pragma unroll
             for (int i = 0; i < HPL; ++i) {
-                const bool nd = tmax[i] > m_ref[i] + kRescaleThreshold;
-                const float m_new = nd ? tmax[i] : m_ref[i];
+                const float m_new = fmaxf(m_ref[i], tmax[i] + kRescaleHeadroom);
                 const float alpha = fast_exp2(m_ref[i] - m_new);     // 1 when unchanged, 0 on first use
                 l[i] *= alpha;
                 m_ref[i] = m_new;
@@ -194,9 +250,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
         }
 #pragma unroll
         for (int s = 0; s < U; ++s) {
-            const uint4 vr = T.v[s];
-            const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
-                                 widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};
+            const u32x4 vr = vt[s];
+            const float vf[8] = {widen_lo<DT>(vr[0]), widen_hi<DT>(vr[0]), widen_lo<DT>(vr[1]), widen_hi<DT>(vr[1]),
+                                 widen_lo<DT>(vr[2]), widen_hi<DT>(vr[2]), widen_lo<DT>(vr[3]), widen_hi<DT>(vr[3])};
             float pw[HPL];
 #pragma unroll
             for (int i = 0; i < HPL; ++i) {
@@ -211,27 +267,26 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
         }
     };
 
-    // ---- main loop: wave w owns tiles w, w+NW, ...; two register sets, one tile of lookahead
-    const int ntiles = (t_end - t_begin + TILE - 1) / TILE;
-    {
-        McTile<DT, D, GH> A, B;
-        int tile = wave;
-        if (tile < ntiles) load_tile(A, tile);
-        while (tile < ntiles) {
-            if (tile + NW < ntiles) load_tile(B, tile + NW);
-            compute_tile(A, tile);
-            tile += NW;
-            if (tile >= ntiles) break;
-            if (tile + NW < ntiles) load_tile(A, tile + NW);
-            compute_tile(B, tile);
-            tile += NW;
+    // ---- main loop -------------------------------------------------------------------------
+    const uint32_t ring_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring + lane * 16;
+    for (int j = 0; j < PT && j < ntw; ++j) issue_tile(j);
+    for (int j = 0; j < ntw; ++j) {
+        if (j + PT < ntw) issue_tile(j + PT);
+        const int newer = min(ntw - 1 - j, PT);              // tiles issued after tile j (uniform)
+        const uint32_t addr = ring_lane + (j % NT) * kTileBytes;
+        u32x4 kt[U], vt[U];
+        static_assert(PT <= 3, "extend the switch");
+        switch (newer) {
+        case 0: ring_read2<0>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 1: ring_read2<2 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 2: ring_read2<4 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        default: ring_read2<6 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
         }
+        compute_tile(kt, vt, tile_first + j);
     }
 
     // ---- merge the NSTREAM softmax streams of the workgroup --------------------------------
-    __shared__ float sm_m[NSTREAM][GH];
-    __shared__ float sm_l[NSTREAM][GH];
-    __shared__ __attribute__((aligned(16))) float sm_o[NSTREAM / 2][GH][D];
+    float (*sm_o)[GH][D] = reinterpret_cast<float (*)[GH][D]>(smem);
     const int stream = wave * TPS + r;
     if (c < 4) {
 #pragma unroll
@@ -240,7 +295,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
             sm_l[stream][u + 4 * i] = l[i];
         }
     }
-    __syncthreads();
+    __syncthreads();                                        // also: every wave is done with its ring
     // every lane: the workgroup maximum of each head and this stream's factor against it
     float f[GH];
 #pragma unroll
