@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--partition-size", type=int, default=None,
                     help="override the workload's partition size (0 = library chooses, -1 = never split)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lib", default=None, help="load this build of liboptgqa.so instead of the in-tree one")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = pick for ~15 s)")
     return ap.parse_args()
@@ -90,7 +91,7 @@ def main():
     import paper_2505_02351_amd as G
     import workloads as W
 
-    G.load_library()                                   # no library, no benchmark
+    G.load_library(args.lib) if args.lib else G.load_library()      # no library, no benchmark
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)

@@ -25,11 +25,13 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(keep_asm: bool = False, verbose: bool = False) -> str:
+def build(keep_asm: bool = False, verbose: bool = False, defines=(), out: str = LIB) -> str:
+    """Compile csrc/optgqa.hip.  `defines` (e.g. ["OPTGQA_RING_TILES=4"]) and `out` exist for
+    tuning experiments; the product library is the default call."""
     os.makedirs(BUILD_DIR, exist_ok=True)
     tmp = os.path.join(BUILD_DIR, f"liboptgqa.{os.getpid()}.so")
-    cmd = ["hipcc", *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG, "csrc"),
-           SRC, "-o", tmp]
+    cmd = ["hipcc", *HIPCC_FLAGS, *["-D" + d for d in defines], "-I" + os.path.join(ROOT, "include"),
+           "-I" + os.path.join(PKG, "csrc"), SRC, "-o", tmp]
     if keep_asm:
         cmd.append("-save-temps=obj")
     res = subprocess.run(cmd, capture_output=True, text=True, cwd=BUILD_DIR)
@@ -39,8 +41,8 @@ def build(keep_asm: bool = False, verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

@@ -34,6 +34,7 @@ struct DecodeParams {
     const int32_t* cu_q_lens;   // [num_seqs + 1] or nullptr
     int num_seqs;
     int row_offset;             // first row handled by this launch (grid.z/y counts from here)
+    int heads_per_wg;           // query heads one workgroup serves (divides the group size)
 };
 
 // Sequence and number of visible keys of one output row; false if the row does not exist

@@ -32,7 +32,10 @@ constexpr float kRescaleThreshold = 30.f;    // log2 units: rescale when a tile 
 constexpr float kRescaleHeadroom = 60.f;     // ... and then put the reference this far ABOVE the maximum
 constexpr float kNoMax = -1.0e30f;           // "no key seen yet"; finite so that differences stay finite
 constexpr int kMcSteps = 2;                  // steps per wave tile
-constexpr int kMcRingTiles = 3;              // ring slots per wave (tiles in flight + the one in use)
+#ifndef OPTGQA_RING_TILES
+#define OPTGQA_RING_TILES 3
+#endif
+constexpr int kMcRingTiles = OPTGQA_RING_TILES;  // ring slots per wave (tiles in flight + the one in use)
 
 template <int V> __device__ __forceinline__ float quad_bcast(float x)
 {
@@ -89,6 +92,17 @@ __device__ __forceinline__ int scalar_load_i32(const int32_t* uniform_ptr)
     return v;
 }
 
+// Dynamic LDS of the kernel: [ring of all waves | merge buffer] followed by the per-stream
+// (max, sum) pairs.
+template <int D, int GH>
+struct McSmem {
+    static constexpr int kStreams = kDecodeWaves * (64 / (D / 8));
+    static constexpr int kRingBytes = kDecodeWaves * kMcRingTiles * kMcSteps * 2 * 1024;
+    static constexpr int kMergeBytes = (kStreams / 2) * GH * D * 4;
+    static constexpr int kBulkBytes = kRingBytes > kMergeBytes ? kRingBytes : kMergeBytes;
+    static constexpr int kBytes = kBulkBytes + 2 * kStreams * GH * 4;
+};
+
 template <int DT, int D, int GH>
 __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(const DecodeParams p)
 {
@@ -105,13 +119,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
     constexpr int NT = kMcRingTiles;
     constexpr int PT = NT - 1;               // tiles of lookahead
     constexpr int kTileBytes = U * 2 * 1024; // K and V, 1 KiB per step each
-    constexpr int kRingBytes = NW * NT * kTileBytes;
-    constexpr int kMergeBytes = (NSTREAM / 2) * GH * D * 4;
-    constexpr int kSmemBytes = kRingBytes > kMergeBytes ? kRingBytes : kMergeBytes;
+    using Smem = McSmem<D, GH>;
 
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];   // ring, later the merge buffer
-    __shared__ float sm_m[NSTREAM][GH];
-    __shared__ float sm_l[NSTREAM][GH];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];      // ring, later the merge buffer
+    float (*sm_m)[GH] = reinterpret_cast<float (*)[GH]>(smem + Smem::kBulkBytes);
+    float (*sm_l)[GH] = sm_m + NSTREAM;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -275,12 +287,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
         const int newer = min(ntw - 1 - j, PT);              // tiles issued after tile j (uniform)
         const uint32_t addr = ring_lane + (j % NT) * kTileBytes;
         u32x4 kt[U], vt[U];
-        static_assert(PT <= 3, "extend the switch");
+        static_assert(PT <= 7, "extend the switch");
         switch (newer) {
         case 0: ring_read2<0>(addr, kt[0], kt[1], vt[0], vt[1]); break;
         case 1: ring_read2<2 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
         case 2: ring_read2<4 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
-        default: ring_read2<6 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 3: ring_read2<6 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 4: ring_read2<8 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 5: ring_read2<10 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        case 6: ring_read2<12 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
+        default: ring_read2<14 * U>(addr, kt[0], kt[1], vt[0], vt[1]); break;
         }
         compute_tile(kt, vt, tile_first + j);
     }

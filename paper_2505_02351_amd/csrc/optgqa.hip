@@ -7,6 +7,7 @@
 #include "cache_kernels.hpp"
 #include "decode_kernels.hpp"
 #include "decode_mc_kernels.hpp"
+#include "decode_mma_kernels.hpp"
 #include "prefill_kernels.hpp"
 
 using namespace optgqa;
@@ -27,10 +28,16 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? OPTGQA_OK : OPTGQA_ERR_LAUNCH;
 }
 
-// Largest of 8, 4, 2, 1 that divides the group size: the number of query heads one workgroup
-// serves from a single pass over its K/V tiles.
-int heads_per_workgroup(int group)
+// Number of query heads one workgroup serves from a single pass over its K/V tiles; always a
+// divisor of the group size.  head_dim 128 uses the matrix-core kernel, whose score tile has
+// 16 rows: the largest divisor <= 16.  head_dim 64: the largest of 8, 4, 2, 1.
+int heads_per_workgroup(int group, int head_dim)
 {
+    if (head_dim == 128) {
+        for (int gh = group < kMmaMaxHeads ? group : kMmaMaxHeads; gh > 1; --gh)
+            if (group % gh == 0) return gh;
+        return 1;
+    }
     for (int gh = 8; gh > 1; gh >>= 1)
         if (group % gh == 0) return gh;
     return 1;
@@ -41,11 +48,12 @@ int round_up(int x, int m) { return (x + m - 1) / m * m; }
 // Partition size the library picks when the caller leaves the choice to it (0 = do not split).
 // Aim: enough workgroups to occupy every CU several times over, runs no shorter than
 // kMinPartition tokens.
-int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int block_size, int max_context_len)
+int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                   int max_context_len)
 {
     if (max_context_len <= kMinPartition) return 0;
     const int group = num_heads / num_kv_heads;
-    const long units = (long)num_seqs * num_kv_heads * (group / heads_per_workgroup(group));
+    const long units = (long)num_seqs * num_kv_heads * (group / heads_per_workgroup(group, head_dim));
     const long want_wgs = 8L * kNumCUs;
     if (units >= want_wgs) return 0;
     long np = (want_wgs + units - 1) / units;                       // partitions per sequence
@@ -68,7 +76,7 @@ SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim
 {
     SplitPlan s{0, 1, 0};
     int P = partition_size;
-    if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, block_size, max_context_len);
+    if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
     if (P <= 0) return s;
     s.partition_size = P;
     s.num_partitions = (max_context_len + P - 1) / P;
@@ -77,18 +85,34 @@ SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim
     return s;
 }
 
+// The fast decode kernel takes its LDS as dynamic shared memory (the ring may exceed the 64 KiB
+// a kernel gets by default); the size limit is raised once per kernel instantiation.
+template <int DT, int D, int GH>
+int launch_decode_mc(const DecodeParams& p, dim3 grid, dim3 block, hipStream_t st)
+{
+    constexpr int kBytes = McSmem<D, GH>::kBytes;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&paged_decode_mc_kernel<DT, D, GH>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+    if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
+    hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, GH>), grid, block, kBytes, st, p);
+    return launch_status();
+}
+
 template <int DT, int D>
 int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
 {
     const dim3 block(kDecodeWaves * 64);
+    if (D == 128) {
+        hipLaunchKernelGGL((paged_decode_mma_kernel<DT>), grid, block, 0, st, p);
+        return launch_status();
+    }
+#ifndef OPTGQA_VALU_ONLY_DECODE
+    if (gh == 8) return launch_decode_mc<DT, D, 8>(p, grid, block, st);
+    if (gh == 4) return launch_decode_mc<DT, D, 4>(p, grid, block, st);
+#endif
     switch (gh) {
-#ifdef OPTGQA_VALU_ONLY_DECODE
     case 8: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 8>), grid, block, 0, st, p); break;
     case 4: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 4>), grid, block, 0, st, p); break;
-#else
-    case 8: hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, 8>), grid, block, 0, st, p); break;
-    case 4: hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, 4>), grid, block, 0, st, p); break;
-#endif
     case 2: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 2>), grid, block, 0, st, p); break;
     default: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 1>), grid, block, 0, st, p); break;
     }
@@ -103,7 +127,8 @@ template <int DT, int D>
 int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
 {
     const int group = p.num_heads / p.num_kv_heads;
-    const int gh = heads_per_workgroup(group);
+    const int gh = heads_per_workgroup(group, D);
+    p.heads_per_wg = gh;
     for (int first = 0; first < num_rows; first += kMaxRowsPerLaunch) {
         const int rows = num_rows - first < kMaxRowsPerLaunch ? num_rows - first : kMaxRowsPerLaunch;
         p.row_offset = first;
