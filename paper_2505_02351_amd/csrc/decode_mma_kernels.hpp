@@ -18,10 +18,10 @@
 //           transposed through 1 KiB of LDS.
 //
 // The ALU is left with the softmax (4 scores per lane per 16 tokens), the widening of V and
-// addresses.  K/V tiles travel HBM -> LDS with direct-to-LDS loads into a per-wave ring (no
-// VGPRs held while in flight, no cross-wave synchronisation: a vmcnt wait is enough), each
-// lane later reading back exactly the 16 bytes it fetched.  One K/V fetch serves all heads of
-// the group (Section II, "Shared Key-Value").
+// addresses, which leaves registers to spare: K/V tiles are fetched straight into VGPRs,
+// kMmaBufs - 1 tiles (8 KiB each per wave) ahead of the arithmetic, in a rotating set of
+// register buffers (the loop is unrolled by kMmaBufs so that the rotation costs no moves).
+// One K/V fetch serves all heads of the group (Section II, "Shared Key-Value").
 //
 // Softmax uses a lazily moved reference instead of the exact running maximum: with ALiBi the
 // scores climb steadily along the context and an exact running maximum would rescale the
@@ -34,13 +34,20 @@
 
 namespace optgqa {
 
-#ifndef OPTGQA_MMA_RING_TILES
-#define OPTGQA_MMA_RING_TILES 2
+#ifndef OPTGQA_MMA_BUFS
+#define OPTGQA_MMA_BUFS 2
 #endif
-constexpr int kMmaRingTiles = OPTGQA_MMA_RING_TILES;   // ring slots per wave (in flight + in use)
+#ifndef OPTGQA_MMA_WAVES_PER_SIMD
+#define OPTGQA_MMA_WAVES_PER_SIMD 2
+#endif
+constexpr int kMmaBufs = OPTGQA_MMA_BUFS;              // register tile buffers per wave (in flight + in use)
 constexpr int kMmaTile = 16;                           // tokens per wave tile
-constexpr int kMmaTileBytes = 2 * kMmaTile * 128 * 2;  // K and V of one tile at head_dim 128
 constexpr int kMmaMaxHeads = 16;                       // MFMA M dimension
+
+struct MmaTile {
+    uint4 k[4];     // K: token j16, dims 32i + 8hg .. +7   (B operand of score MFMA i)
+    uint4 v[4];     // V: token 4s + hg, dims 8*j16 .. +7    (B operand of the output MFMAs of step s)
+};
 
 template <int DT> __device__ __forceinline__ f32x4 mfma_qk(uint4 a, uint4 b, f32x4 c);
 template <> __device__ __forceinline__ f32x4 mfma_qk<kF16>(uint4 a, uint4 b, f32x4 c)
@@ -54,29 +61,6 @@ template <> __device__ __forceinline__ f32x4 mfma_qk<kBF16>(uint4 a, uint4 b, f3
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// Wait until at most NEWER direct-to-LDS loads issued after the wanted tile are in flight, then
-// read the tile back: four K pieces (one per 32-dim slab) and four V pieces (one per step).
-// One asm block, because the compiler cannot be told which outstanding load a given LDS read
-// depends on and would otherwise wait for all of them, the newest prefetch included.
-template <int NEWER>
-__device__ __forceinline__ void ring_read_tile(uint32_t lds_addr, u32x4 (&k)[4], u32x4 (&v)[4])
-{
-    asm volatile(
-        "s_waitcnt vmcnt(%9)\n\t"
-        "ds_read_b128 %0, %8\n\t"
-        "ds_read_b128 %1, %8 offset:1024\n\t"
-        "ds_read_b128 %2, %8 offset:2048\n\t"
-        "ds_read_b128 %3, %8 offset:3072\n\t"
-        "ds_read_b128 %4, %8 offset:4096\n\t"
-        "ds_read_b128 %5, %8 offset:5120\n\t"
-        "ds_read_b128 %6, %8 offset:6144\n\t"
-        "ds_read_b128 %7, %8 offset:7168\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(k[0]), "=&v"(k[1]), "=&v"(k[2]), "=&v"(k[3]), "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
-        : "v"(lds_addr), "n"(NEWER)
-        : "memory");
-}
-
 template <int CTRL> __device__ __forceinline__ float dpp_max(float x) { return fmaxf(x, dpp<CTRL>(x)); }
 __device__ __forceinline__ float row16_max(float x)
 {
@@ -87,18 +71,15 @@ __device__ __forceinline__ float row16_max(float x)
 }
 
 template <int DT>
-__global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mma_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void paged_decode_mma_kernel(const DecodeParams p)
 {
     constexpr int D = 128;
     constexpr int NW = kDecodeWaves;
     constexpr int TILE = kMmaTile;
-    constexpr int NT = kMmaRingTiles;
-    constexpr int PT = NT - 1;                      // tiles of lookahead
-    constexpr int kLoadsPerTile = 8;
-    static_assert(PT >= 1 && PT <= 3, "extend the wait switch");
-    static_assert(NW * 16 * D * 4 <= NW * NT * kMmaTileBytes, "merge buffer must fit in the ring");
+    constexpr int NB = kMmaBufs;
+    constexpr int PT = NB - 1;                      // tiles of lookahead
 
-    __shared__ __attribute__((aligned(16))) unsigned char ring[NW * NT * kMmaTileBytes];
+    __shared__ __attribute__((aligned(16))) float merge[NW][kMmaMaxHeads][D];      // epilogue only
     __shared__ __attribute__((aligned(16))) float p_lds[NW][TILE][kMmaMaxHeads];   // tile weights [token][head]
     __shared__ float sm_m[NW][kMmaMaxHeads];
     __shared__ float sm_l[NW][kMmaMaxHeads];
@@ -134,29 +115,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mma_kernel(
     const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
     const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
 
-    // A operand of the score MFMAs: lane (head j16, k-slab hg) holds dims 32i + 8hg .. +7 of its head.
-    uint4 qa[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        qa[i] = make_uint4(0, 0, 0, 0);
-        if (j16 < GH) qa[i] = *reinterpret_cast<const uint4*>(qp + ((int64_t)row * Hq + h0 + j16) * D + 32 * i + 8 * hg);
-    }
-    // Softmax state and output accumulators of heads 4hg + v (v = 0..3); scores of those heads for
-    // token j16 arrive in this lane, and the output MFMA leaves the same heads here for dims 8*j16 + e.
-    float slope2[4], m_ref[4], l[4];
-    f32x4 acc[8];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int h = 4 * hg + v;
-        slope2[v] = (p.slopes && h < GH) ? p.slopes[h0 + h] * kLog2e : 0.f;
-        m_ref[v] = kNoMax;
-        l[v] = 0.f;
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // weights of padding heads are never written; the A operand reads them, so they must be finite
-    for (int i = lane; i < TILE * kMmaMaxHeads; i += 64) (&p_lds[wave][0][0])[i] = 0.f;
-
     const float scale2 = p.scale2;
     const int Lm1 = L - 1;
     const uint16_t* __restrict__ kc_g = kc + (int64_t)g * bs * D;
@@ -164,66 +122,81 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mma_kernel(
     const int64_t block_stride = (int64_t)Hkv * bs * D;
     const int t_last = t_end - 1;
 
-    // Each wave owns a contiguous quarter of the partition's tiles; its j-th tile uses ring slot j % NT.
+    // Each wave owns a contiguous quarter of the partition's tiles.
     const int ntiles = (t_end - t_begin + TILE - 1) / TILE;
     const int tpw = (ntiles + NW - 1) / NW;
     const int tile_first = wave * tpw;
     const int ntw = max(0, min(tpw, ntiles - tile_first));
-    unsigned char* const my_ring = ring + wave * (NT * kMmaTileBytes);
 
     // All 16 tokens of a tile lie in one physical block (tiles are 16-aligned, blocks >= 16 tokens).
     // Loads are unconditional and in bounds: rows past the end of the range re-read the last valid
     // row and are masked out of the scores.
-    auto issue_tile = [&](int j) {
+    auto load_tile = [&](MmaTile& T, int j) {
         const int tile_t0 = t_begin + (tile_first + j) * TILE;                       // < t_end
-        unsigned char* const slot = my_ring + (j % NT) * kMmaTileBytes;
-        const int blk = scalar_load_i32(table + (tile_t0 >> bs_shift));
+        const int blk = __builtin_amdgcn_readfirstlane(table[tile_t0 >> bs_shift]);
         const int64_t uni = blk * block_stride + (int64_t)(tile_t0 & (bs - 1)) * D;
-        const uint16_t* kb = kc_g + uni;
-        const uint16_t* vb = vc_g + uni;
-        if (tile_t0 + TILE <= t_end) {                                               // full tile (uniform)
-            const uint16_t* ka = kb + j16 * D + 8 * hg;
-            const uint16_t* va = vb + hg * D + 8 * j16;
+        const int tk = min(tile_t0 + j16, t_last) - tile_t0;
+        const uint16_t* ka = kc_g + uni + tk * D + 8 * hg;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                __builtin_amdgcn_global_load_lds(ka + 32 * i, slot + i * 1024, 16, 0, 0);
+        for (int i = 0; i < 4; ++i) T.k[i] = *reinterpret_cast<const uint4*>(ka + 32 * i);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-                __builtin_amdgcn_global_load_lds(va + 4 * s * D, slot + 4096 + s * 1024, 16, 0, 0);
-        } else {
-            const int tk = min(tile_t0 + j16, t_last) - tile_t0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                __builtin_amdgcn_global_load_lds(kb + tk * D + 32 * i + 8 * hg, slot + i * 1024, 16, 0, 0);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-                __builtin_amdgcn_global_load_lds(vb + tv * D + 8 * j16, slot + 4096 + s * 1024, 16, 0, 0);
-            }
+        for (int s = 0; s < 4; ++s) {
+            const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
+            T.v[s] = *reinterpret_cast<const uint4*>(vc_g + uni + tv * D + 8 * j16);
         }
     };
 
-    const uint32_t ring_lane = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)my_ring + lane * 16;
+    // Start the first tiles' loads before anything else touches memory, so that the query rows
+    // and slopes arrive in their shadow.
+    MmaTile buf[NB];
+    const int j_last = max(ntw - 1, 0);
+    if (ntw > 0) {
+#pragma unroll
+        for (int i = 0; i < PT; ++i) load_tile(buf[i], min(i, j_last));
+    }
+
+    // A operand of the score MFMAs: lane (head j16, k-slab hg) holds dims 32i + 8hg .. +7 of its head.
+    // (Loaded unconditionally from a clamped head and zeroed afterwards: no branches around loads.)
+    uint4 qa[4];
+    {
+        const uint16_t* qrow = qp + ((int64_t)row * Hq + h0 + min(j16, GH - 1)) * D + 8 * hg;
+        const uint32_t keep = j16 < GH ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 x = *reinterpret_cast<const uint4*>(qrow + 32 * i);
+            qa[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
+        }
+    }
+    // Softmax state and output accumulators of heads 4hg + v (v = 0..3); scores of those heads for
+    // token j16 arrive in this lane, and the output MFMA leaves the same heads here for dims 8*j16 + e.
+    float slope2[4], m_ref[4], l[4];
+    f32x4 acc[8];
+    {
+        float sl[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.slopes) {                                          // uniform; one batch of loads
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sl[v] = p.slopes[h0 + min(4 * hg + v, GH - 1)];
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            slope2[v] = 4 * hg + v < GH ? sl[v] * kLog2e : 0.f;
+            m_ref[v] = kNoMax;
+            l[v] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // the A operand of the output MFMA reads all 16 head columns: start them finite
+    reinterpret_cast<float4*>(&p_lds[wave][0][0])[lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+
     float* const pw_write = &p_lds[wave][j16][4 * hg];      // this lane's 4 weights of token j16
     const float* const pw_read = &p_lds[wave][hg][j16];     // + 4s*16: weight of head j16 for token 4s + hg
 
-    for (int j = 0; j < PT && j < ntw; ++j) issue_tile(j);
-    for (int j = 0; j < ntw; ++j) {
-        if (j + PT < ntw) issue_tile(j + PT);
-        const int newer = min(ntw - 1 - j, PT);             // tiles issued after tile j (uniform)
-        const uint32_t addr = ring_lane + (j % NT) * kMmaTileBytes;
-        u32x4 kt[4], vt[4];
-        switch (newer) {
-        case 0: ring_read_tile<0>(addr, kt, vt); break;
-        case 1: ring_read_tile<kLoadsPerTile>(addr, kt, vt); break;
-        case 2: ring_read_tile<2 * kLoadsPerTile>(addr, kt, vt); break;
-        default: ring_read_tile<3 * kLoadsPerTile>(addr, kt, vt); break;
-        }
-
+    auto compute_tile = [&](const MmaTile& T, int j) {
         // scores of heads 4hg..4hg+3 for token j16 of the tile: eq. (3) in base 2
         f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) S = mfma_qk<DT>(qa[i], __builtin_bit_cast(uint4, kt[i]), S);
+        for (int i = 0; i < 4; ++i) S = mfma_qk<DT>(qa[i], T.k[i], S);
         const int t = t_begin + (tile_first + j) * TILE + j16;
         const bool valid = t < t_end;
         const float rel = (float)(t - Lm1);                  // exact: |rel| < 2^24
@@ -261,11 +234,28 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mma_kernel(
         for (int s = 0; s < 4; ++s) a[s] = pw_read[4 * s * kMmaMaxHeads];   // ... read back as [head][token]
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const u32x4 vr = vt[s];
-            const float vf[8] = {widen_lo<DT>(vr[0]), widen_hi<DT>(vr[0]), widen_lo<DT>(vr[1]), widen_hi<DT>(vr[1]),
-                                 widen_lo<DT>(vr[2]), widen_hi<DT>(vr[2]), widen_lo<DT>(vr[3]), widen_hi<DT>(vr[3])};
+            const uint4 vr = T.v[s];
+            const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
+                                 widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], vf[e], acc[e], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: NB rotating register buffers, unrolled by NB ----------------------------
+    // Every iteration issues exactly one tile of loads, so the number of loads in flight at each
+    // use is a compile-time constant.  Past the end of the wave's range the prefetch re-reads the
+    // wave's last tile (a cache hit, never consumed) instead of branching around the loads.
+    if (ntw > 0) {
+        const int trips = (ntw + NB - 1) / NB;
+        for (int it = 0; it < trips; ++it) {
+            const int j0 = it * NB;
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int j = j0 + i;
+                load_tile(buf[(i + PT) % NB], min(j + PT, j_last));
+                if (j <= j_last) compute_tile(buf[i], j);
+            }
         }
     }
 
@@ -279,8 +269,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mma_kernel(
             sm_l[wave][4 * hg + v] = l[v];
         }
     }
-    __syncthreads();                                         // also: every wave is done with its ring
-    float (*merge)[kMmaMaxHeads][D] = reinterpret_cast<float (*)[kMmaMaxHeads][D]>(ring);
+    __syncthreads();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int h = 4 * hg + v;
