@@ -223,30 +223,60 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
 }
 
 // Combine the per-partition (max, sum, weighted sum) triples of the split path:
-//   M = max_p m_p,  out = sum_p 2^(m_p-M) o_p / sum_p 2^(m_p-M) l_p.
-// grid = (Hq, rows), block = D threads.
+//   M = max_p m_p,  out = sum_p 2^(m_p-M) o_p / sum_p 2^(m_p-M) l_p
+// (Section III-A: the per-partition results are carried forward and merged).
+// One thread per 4 output dims; kReduceHeads heads per workgroup; grid = (ceil(Hq / kReduceHeads), rows).
+// Partitions are taken in batches of 8 whose loads are all issued before the first use: the
+// kernel is a few microseconds of pure memory latency, so the loads must overlap.
+constexpr int kReduceThreads = 256;
+
 template <int DT, int D>
-__global__ __launch_bounds__(D) void paged_decode_reduce_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kReduceThreads) void paged_decode_reduce_kernel(const DecodeParams p)
 {
-    const int h = blockIdx.x, row = p.row_offset + blockIdx.y, d = threadIdx.x;
+    constexpr int kVecPerHead = D / 4;
+    constexpr int kHeads = kReduceThreads / kVecPerHead;
+    const int h = blockIdx.x * kHeads + threadIdx.x / kVecPerHead;
+    const int od = (threadIdx.x % kVecPerHead) * 4;
+    const int row = p.row_offset + blockIdx.y;
+    if (h >= p.num_heads) return;
     int b, L;
     if (!row_to_seq(p, row, b, L)) return;
-    uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * p.num_heads + h) * D;
+    uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * p.num_heads + h) * D + od;
     if (L <= 0) {
-        o[d] = 0;
+        *reinterpret_cast<uint2*>(o) = make_uint2(0u, 0u);
         return;
     }
     const int np = (L + p.partition_size - 1) / p.partition_size;
     const int64_t base = ((int64_t)row * p.num_heads + h) * p.num_partitions;
     float M = -INFINITY;
     for (int i = 0; i < np; ++i) M = fmaxf(M, p.ws_m[base + i]);
-    float num = 0.f, den = 0.f;
-    for (int i = 0; i < np; ++i) {
-        const float f = fast_exp2(p.ws_m[base + i] - M);
-        den = fmaf(f, p.ws_l[base + i], den);
-        num = fmaf(f, p.ws_o[(base + i) * D + d], num);
+    float den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = 0; i0 < np; i0 += 8) {
+        float mm[8], ll[8];
+        float4 x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = min(i0 + k, np - 1);
+            mm[k] = p.ws_m[base + i];
+            ll[k] = p.ws_l[base + i];
+            x[k] = *reinterpret_cast<const float4*>(p.ws_o + (base + i) * D + od);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float f = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
+            den = fmaf(f, ll[k], den);
+            num.x = fmaf(f, x[k].x, num.x);
+            num.y = fmaf(f, x[k].y, num.y);
+            num.z = fmaf(f, x[k].z, num.z);
+            num.w = fmaf(f, x[k].w, num.w);
+        }
     }
-    o[d] = narrow<DT>(num / den);
+    const float inv = 1.f / den;
+    uint2 packed;
+    packed.x = narrow2<DT>(num.x * inv, num.y * inv);
+    packed.y = narrow2<DT>(num.z * inv, num.w * inv);
+    *reinterpret_cast<uint2*>(o) = packed;
 }
 
 }  // namespace optgqa

@@ -136,7 +136,9 @@ int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
         int rc = launch_decode_gh<DT, D>(p, gh, grid, st);
         if (rc != OPTGQA_OK) return rc;
         if (p.num_partitions == 1) continue;
-        hipLaunchKernelGGL((paged_decode_reduce_kernel<DT, D>), dim3(p.num_heads, rows), dim3(D), 0, st, p);
+        constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
+        hipLaunchKernelGGL((paged_decode_reduce_kernel<DT, D>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, rows),
+                           dim3(kReduceThreads), 0, st, p);
         rc = launch_status();
         if (rc != OPTGQA_OK) return rc;
     }
