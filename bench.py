@@ -31,7 +31,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
 # measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/paged_decode_C3.md: (311412.3 KiB FETCH_SIZE x 2.000 + 5994.2 KiB WRITE_SIZE x 1.000) x 1024
+    "C3": 643910451,
+}
 
 
 def parse():
