@@ -181,6 +181,34 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
+// Tiled matrix-core prefill (head_dim 128); other shapes go row by row.
+int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st)
+{
+    if (head_dim != 128) {
+        const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
+        if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+        return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, st);
+    }
+    const int group = p.num_heads / p.num_kv_heads;
+    const int gh = heads_per_workgroup(group, 128);
+    int shift = 0;
+    while ((1 << shift) < gh) ++shift;
+    const int tokens_per_wg = kPfRows >> shift;
+    p.num_seqs = num_seqs;
+    p.heads_per_wg = gh;
+    p.heads_pow2_shift = shift;
+    p.q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
+    p.units = num_seqs * p.num_kv_heads * (group / gh);
+    const int64_t blocks = (int64_t)((p.units + 7) / 8) * 8 * p.q_tiles;
+    if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+    const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
+    if (dtype == OPTGQA_F16)
+        hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16>), grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16>), grid, block, 0, st, p);
+    return launch_status();
+}
+
 }  // namespace
 
 extern "C" {
@@ -340,9 +368,7 @@ int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const vo
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
     p.max_blocks_per_seq = max_blocks_per_seq;
-    const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
-    if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
-    return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, static_cast<hipStream_t>(stream));
+    return launch_prefill(p, num_seqs, max_q_len, head_dim, dtype, static_cast<hipStream_t>(stream));
 }
 
 int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* v_cache,

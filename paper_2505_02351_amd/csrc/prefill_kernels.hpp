@@ -1,6 +1,31 @@
-// Prefill over the paged cache: several new query tokens per sequence, causal mask + ALiBi.
+// Prefill over the paged cache: several new query tokens per sequence, causal mask + ALiBi
+// (Alg. 1, prompt branch: scores, bias, softmax, weighted sum), as tiled matrix-core contractions.
+//
+// Workgroup (4 waves) = kPfRows (query token, head) rows of one (sequence, KV head [x chunk of the
+// group]) against the whole visible context, in 32-key tiles staged through LDS and shared by the
+// four waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
+// tile (Section II, "Shared Key-Value").
+//
+// Both contractions are computed transposed so that no operand has to be transposed in registers:
+//   S^T[key][row] = K Q^T      v_mfma_f32_16x16x32: A = K rows from LDS (natural layout: a lane
+//                              needs 8 consecutive dims of one key), B = query rows held in VGPRs.
+//                              A lane then holds, for ONE query row, keys 4hg+v of both 16-key
+//                              halves of the tile: 8 weights that pack straight into ...
+//   O^T[dim][row] += V^T P^T   ... the B operand of the second v_mfma_f32_16x16x32, whose
+//                              contraction index runs over the tile's keys in exactly that
+//                              (permuted) order.  A = V^T from LDS; V is transposed once per tile
+//                              when it is written to LDS (4 keys x 8 dims per loader thread,
+//                              interleaved with byte permutes, stored key-permuted), not per wave.
+// Scores, sums and the output accumulate in fp32.  For the second contraction the softmax
+// weights must become 2-byte values:
+//   fp16: one rounding (11 significant bits); the lazily moved reference of the exponentials (see
+//         decode_mma_kernels.hpp) is kept tight enough (threshold 2^14, headroom 2^2) that weights
+//         stay inside fp16's range;
+//   bf16: 8 significant bits are not enough for the 1e-2 output budget once the output itself is
+//         rounded to bf16 (measured: 1.003e-2), so each weight is split into a bf16 head and a
+//         bf16 tail and the contraction runs twice; bf16's range allows the wide lazy reference.
 #pragma once
-#include "common.hpp"
+#include "decode_mma_kernels.hpp"
 
 namespace optgqa {
 
@@ -15,6 +40,265 @@ struct PrefillParams {
     const float* slopes;        // [Hq] or nullptr
     float scale2;               // scale * log2(e)
     int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
+    int num_seqs;
+    int heads_per_wg;           // GH: query heads per workgroup (divides the group size, <= 16)
+    int heads_pow2_shift;       // log2 of GH rounded up to a power of two (row = token * 2^shift + head)
+    int q_tiles;                // ceil(max_q_len / tokens per workgroup)
+    int units;                  // num_seqs * num_kv_heads * (group / GH)
 };
+
+constexpr int kPfWaves = 4;
+constexpr int kPfRowBlocks = 2;                          // 16-row blocks per wave
+constexpr int kPfRows = kPfWaves * kPfRowBlocks * 16;    // (token, head) rows per workgroup
+constexpr int kPfKeys = 32;                              // keys per tile
+constexpr int kPfKRow = 128 + 8;                         // LDS K row, elements (padding spreads banks)
+constexpr int kPfVRow = kPfKeys + 8;                     // LDS V^T row, elements
+
+template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow2<DT>(lo, hi); }
+
+template <int DT> struct PfSoftmax;
+template <> struct PfSoftmax<kF16> {
+    static constexpr float kThreshold = 14.f, kHeadroom = 2.f;
+    static constexpr bool kSplitWeights = false;
+};
+template <> struct PfSoftmax<kBF16> {
+    static constexpr float kThreshold = kRescaleThreshold, kHeadroom = kRescaleHeadroom;
+    static constexpr bool kSplitWeights = true;
+};
+
+template <int DT>
+__global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(const PrefillParams p)
+{
+    constexpr int D = 128;
+    constexpr int RB = kPfRowBlocks;
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kPfKeys][kPfKRow];
+    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][D][kPfVRow];
+
+    // ---- which rows -----------------------------------------------------------------------
+    // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
+    // head) unit are given the same residue so that its K/V stay in one XCD's L2.
+    const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
+    const int qt = w % p.q_tiles;
+    const int unit = (w / p.q_tiles) * 8 + xcd;
+    if (unit >= p.units) return;
+    const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
+    const int bs_shift = __builtin_ctz(bs);
+    const int GH = p.heads_per_wg, gshift = p.heads_pow2_shift;
+    const int G = Hq / Hkv, chunks = G / GH;
+    const int units_per_seq = Hkv * chunks;
+    const int b = unit / units_per_seq;
+    const int gu = unit - b * units_per_seq;
+    const int g = gu / chunks;
+    const int h0 = g * G + (gu - g * chunks) * GH;
+    const int tokens_per_wg = kPfRows >> gshift;
+
+    const int cu0 = p.cu_q_lens[b];
+    const int n_b = p.cu_q_lens[b + 1] - cu0;
+    const int tq0 = qt * tokens_per_wg;
+    if (tq0 >= n_b) return;
+    const int L = p.context_lens[b];
+    const int pos0 = L - n_b;                                   // position of the sequence's first new token
+    const int kmax = pos0 + min(tq0 + tokens_per_wg, n_b);      // keys 0 .. kmax-1 are visible to some row
+    const int ntiles = (kmax + kPfKeys - 1) / kPfKeys;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n16 = lane & 15, hg = lane >> 4;
+
+    const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
+    const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache) + (int64_t)g * bs * D;
+    const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache) + (int64_t)g * bs * D;
+    const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
+    const int64_t block_stride = (int64_t)Hkv * bs * D;
+
+    // This lane's query row in each of the wave's row blocks: B operand of the score MFMAs
+    // (row n16, dims 32i + 8hg .. +7), its position, slope and validity.
+    uint4 qb[RB][4];
+    float posf[RB], slope2[RB], m_ref[RB], lsum[RB];
+    int pos[RB];
+    bool row_ok[RB];
+    int64_t out_off[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = 16 * (wave * RB + rb) + n16;
+        const int ti = tq0 + (row >> gshift), head = row & ((1 << gshift) - 1);
+        row_ok[rb] = ti < n_b && head < GH;
+        const int tc = min(ti, n_b - 1), hc = min(head, GH - 1);
+        const int64_t qrow = ((int64_t)(cu0 + tc) * Hq + h0 + hc) * D;
+        out_off[rb] = qrow;
+        pos[rb] = pos0 + tc;
+        posf[rb] = (float)pos[rb];
+        slope2[rb] = p.slopes ? p.slopes[h0 + hc] * kLog2e : 0.f;
+        m_ref[rb] = kNoMax;
+        lsum[rb] = 0.f;
+        const uint32_t keep = row_ok[rb] ? 0xffffffffu : 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint4 x = *reinterpret_cast<const uint4*>(qp + qrow + 32 * i + 8 * hg);
+            qb[rb][i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
+        }
+    }
+    f32x4 acc[RB][8];                                            // O^T: dims 16dt + 4hg + v of row n16
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) acc[rb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- tile staging: threads 0..127 fetch K (key tid/4, 64 bytes), 128..255 fetch and
+    // transpose V (4 keys x 8 dims each) -------------------------------------------------------
+    const bool k_loader = tid < 128;
+    const int ld = k_loader ? tid : tid - 128;
+    const int lk_key = ld >> 2, lk_piece = ld & 3;               // K: key 0..31, dims 32*piece ..
+    const int lv_group = ld >> 4, lv_chunk = ld & 15;            // V: keys 4*group .. +3, dims 8*chunk ..
+    // key-permuted position of V's key group inside the LDS row (see the header comment)
+    const int lv_pos = lv_group < 4 ? 8 * lv_group : 8 * (lv_group - 4) + 4;
+    uint4 stage[4];
+
+    auto fetch_tile = [&](int kt) {
+        const int key0 = kt * kPfKeys;
+        if (k_loader) {
+            const int key = min(key0 + lk_key, kmax - 1);
+            const int64_t blk = table[key >> bs_shift];
+            const uint16_t* src = kc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 32 * lk_piece;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) stage[j] = *reinterpret_cast<const uint4*>(src + 8 * j);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int key = min(key0 + 4 * lv_group + j, kmax - 1);
+                const int64_t blk = table[key >> bs_shift];
+                stage[j] = *reinterpret_cast<const uint4*>(vc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 8 * lv_chunk);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        if (k_loader) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint4*>(&k_lds[buf][lk_key][32 * lk_piece + 8 * j]) = stage[j];
+        } else {
+            // stage[j] = key j, 8 dims as 4 dwords (dim pairs).  For dim pair w: interleave the four keys.
+            const uint32_t r[4][4] = {{stage[0].x, stage[0].y, stage[0].z, stage[0].w},
+                                      {stage[1].x, stage[1].y, stage[1].z, stage[1].w},
+                                      {stage[2].x, stage[2].y, stage[2].z, stage[2].w},
+                                      {stage[3].x, stage[3].y, stage[3].z, stage[3].w}};
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                // even dim: low halves of keys (0,1) and (2,3); odd dim: high halves
+                const uint32_t e01 = __builtin_amdgcn_perm(r[1][w2], r[0][w2], 0x05040100u);
+                const uint32_t e23 = __builtin_amdgcn_perm(r[3][w2], r[2][w2], 0x05040100u);
+                const uint32_t o01 = __builtin_amdgcn_perm(r[1][w2], r[0][w2], 0x07060302u);
+                const uint32_t o23 = __builtin_amdgcn_perm(r[3][w2], r[2][w2], 0x07060302u);
+                *reinterpret_cast<uint2*>(&vt_lds[buf][8 * lv_chunk + 2 * w2][lv_pos]) = make_uint2(e01, e23);
+                *reinterpret_cast<uint2*>(&vt_lds[buf][8 * lv_chunk + 2 * w2 + 1][lv_pos]) = make_uint2(o01, o23);
+            }
+        }
+    };
+
+    fetch_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    const float scale2 = p.scale2;
+    for (int kt = 0; kt < ntiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < ntiles) fetch_tile(kt + 1);
+
+        // ---- S^T = K Q^T : st[rb][half][v] = score of key 32kt + 16half + 4hg + v against row n16
+        f32x4 st[RB][2];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) st[rb][0] = st[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint4 ka = *reinterpret_cast<const uint4*>(&k_lds[buf][16 * half + n16][32 * i + 8 * hg]);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) st[rb][half] = mfma_qk<DT>(ka, qb[rb][i], st[rb][half]);
+            }
+
+        // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
+        const int keyb = kt * kPfKeys + 4 * hg;
+        uint32_t pk[RB][4], pk_lo[RB][4];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            float s2[8];
+            bool need = false;
+#pragma unroll
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int key = keyb + 16 * half + v;
+                    const float x = fmaf(st[rb][half][v], scale2, slope2[rb] * ((float)key - posf[rb]));
+                    s2[4 * half + v] = key <= pos[rb] ? x : -INFINITY;
+                    need |= s2[4 * half + v] > m_ref[rb] + PfSoftmax<DT>::kThreshold;
+                }
+            if (__builtin_amdgcn_ballot_w64(need) != 0) {
+                float mx = s2[0];
+#pragma unroll
+                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s2[e]);
+                mx = fmaxf(mx, __shfl_xor(mx, 16));              // the row's keys live in 4 lanes (hg)
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_ref[rb], mx + PfSoftmax<DT>::kHeadroom);
+                const float alpha = fast_exp2(m_ref[rb] - m_new);
+                m_ref[rb] = m_new;
+                lsum[rb] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[rb][dt][v] *= alpha;
+            }
+            float pw[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pw[e] = fast_exp2(s2[e] - m_ref[rb]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pk[rb][e] = pack2<DT>(pw[2 * e], pw[2 * e + 1]);
+                pk_lo[rb][e] = 0u;
+                if (PfSoftmax<DT>::kSplitWeights) {
+                    pk_lo[rb][e] = pack2<DT>(pw[2 * e] - widen_lo<DT>(pk[rb][e]), pw[2 * e + 1] - widen_hi<DT>(pk[rb][e]));
+                    lsum[rb] += pw[2 * e] + pw[2 * e + 1];
+                } else {
+                    // single rounding: normalise by the weights as rounded, so that the output stays
+                    // an exact convex combination of V rows
+                    lsum[rb] += widen_lo<DT>(pk[rb][e]) + widen_hi<DT>(pk[rb][e]);
+                }
+            }
+        }
+
+        // ---- O^T += V^T P^T ---------------------------------------------------------------------
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const uint4 va = *reinterpret_cast<const uint4*>(&vt_lds[buf][16 * dt + n16][8 * hg]);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                acc[rb][dt] = mfma_qk<DT>(va, make_uint4(pk[rb][0], pk[rb][1], pk[rb][2], pk[rb][3]), acc[rb][dt]);
+                if (PfSoftmax<DT>::kSplitWeights)
+                    acc[rb][dt] = mfma_qk<DT>(va, make_uint4(pk_lo[rb][0], pk_lo[rb][1], pk_lo[rb][2], pk_lo[rb][3]), acc[rb][dt]);
+            }
+        }
+
+        if (kt + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and write: this lane holds dims 16dt + 4hg + v of its row --------------------
+    uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        float lt = lsum[rb];
+        lt += __shfl_xor(lt, 16);
+        lt += __shfl_xor(lt, 32);
+        if (!row_ok[rb]) continue;
+        const float inv = 1.f / lt;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            uint2 packed;
+            packed.x = narrow2<DT>(acc[rb][dt][0] * inv, acc[rb][dt][1] * inv);
+            packed.y = narrow2<DT>(acc[rb][dt][2] * inv, acc[rb][dt][3] * inv);
+            *reinterpret_cast<uint2*>(op + out_off[rb] + 16 * dt + 4 * hg) = packed;
+        }
+    }
+}
 
 }  // namespace optgqa

@@ -303,7 +303,12 @@ PF = [
     (W.F16, 8, 2, 64, 16, 2, 20, 200, 20),
     (W.BF16, 32, 8, 128, 16, 2, 300, 700, 130),
     (W.F16, 4, 4, 128, 32, 2, 64, 400, 64),
-    (W.BF16, 6, 2, 128, 16, 2, 5, 100, 100),        # q_len > some contexts: whole prompt is new
+    (W.BF16, 6, 2, 128, 16, 2, 5, 100, 100),        # q_len > some contexts: whole prompt is new; G = 3
+    (W.F16, 16, 2, 128, 32, 2, 100, 500, 77),       # G = 8, block 32, ragged tiles
+    (W.BF16, 4, 4, 128, 16, 3, 1, 260, 260),        # MHA (G = 1), prompts from scratch incl. length 1
+    (W.F16, 32, 2, 128, 16, 1, 300, 300, 40),       # G = 16
+    (W.BF16, 40, 2, 128, 64, 1, 200, 200, 33),      # G = 20 -> two chunks of 10 heads (padded to 16)
+    (W.BF16, 8, 2, 128, 16, 2, 700, 1500, 1),       # one new token per sequence through the prefill path
 ]
 
 
