@@ -51,9 +51,18 @@ template <> __device__ __forceinline__ uint16_t narrow<kBF16>(float x)
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
-template <int DT> __device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+// Two values at once: gfx950 has single-instruction packed conversions (v_cvt_pk_bf16_f32,
+// v_cvt_pk_f16_f32), both round-to-nearest-even and NaN-preserving.
+template <int DT> __device__ __forceinline__ uint32_t narrow2(float lo, float hi);
+template <> __device__ __forceinline__ uint32_t narrow2<kF16>(float lo, float hi)
 {
-    return (uint32_t)narrow<DT>(lo) | ((uint32_t)narrow<DT>(hi) << 16);
+    const f16x2 r = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, r);
+}
+template <> __device__ __forceinline__ uint32_t narrow2<kBF16>(float lo, float hi)
+{
+    const bf16x2 r = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // Data-parallel-primitive lane exchange inside a row of 16 lanes (full VALU rate, no LDS).

@@ -25,6 +25,8 @@
 //         rounded to bf16 (measured: 1.003e-2), so each weight is split into a bf16 head and a
 //         bf16 tail and the contraction runs twice; bf16's range allows the wide lazy reference.
 #pragma once
+#include <type_traits>
+
 #include "decode_mma_kernels.hpp"
 
 namespace optgqa {
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
         pos[rb] = pos0 + tc;
         posf[rb] = (float)pos[rb];
         slope2[rb] = p.slopes ? p.slopes[h0 + hc] * kLog2e : 0.f;
-        m_ref[rb] = kNoMax;
+        m_ref[rb] = 0.f;                                         // the first tile always sets it
         lsum[rb] = 0.f;
         const uint32_t keep = row_ok[rb] ? 0xffffffffu : 0u;
 #pragma unroll
@@ -152,26 +154,37 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
     const int lv_group = ld >> 4, lv_chunk = ld & 15;            // V: keys 4*group .. +3, dims 8*chunk ..
     // key-permuted position of V's key group inside the LDS row (see the header comment)
     const int lv_pos = lv_group < 4 ? 8 * lv_group : 8 * (lv_group - 4) + 4;
-    uint4 stage[4];
+    // Two register stages (tile t lives in stage t & 1) keep two tiles in flight behind the one
+    // being computed; the block id of the next tile to fetch is read one fetch earlier, so a fetch
+    // never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
+    // no branches around loads, which keeps the compiler's load counting exact.
+    uint4 stage_a[4], stage_b[4];
+    const int last_tile = ntiles - 1;
+    auto load_blk = [&](int t) {
+        const int key = min(min(t, last_tile) * kPfKeys + (k_loader ? lk_key : 4 * lv_group), kmax - 1);
+        return table[key >> bs_shift];
+    };
+    int blk_next = load_blk(0);
 
-    auto fetch_tile = [&](int kt) {
-        const int key0 = kt * kPfKeys;
+    auto fetch_tile = [&](uint4 (&stage)[4], int t) __attribute__((always_inline)) {
+        const int key0 = min(t, last_tile) * kPfKeys;
+        const int64_t blk = blk_next;
         if (k_loader) {
             const int key = min(key0 + lk_key, kmax - 1);
-            const int64_t blk = table[key >> bs_shift];
             const uint16_t* src = kc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 32 * lk_piece;
 #pragma unroll
             for (int j = 0; j < 4; ++j) stage[j] = *reinterpret_cast<const uint4*>(src + 8 * j);
         } else {
+            // the four keys of the group share a block (groups are 4-aligned, clamping keeps the block)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int key = min(key0 + 4 * lv_group + j, kmax - 1);
-                const int64_t blk = table[key >> bs_shift];
                 stage[j] = *reinterpret_cast<const uint4*>(vc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 8 * lv_chunk);
             }
         }
+        blk_next = load_blk(t + 1);
     };
-    auto store_tile = [&](int buf) {
+    auto store_tile = [&](const uint4 (&stage)[4], int buf) __attribute__((always_inline)) {
         if (k_loader) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -195,15 +208,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
         }
     };
 
-    fetch_tile(0);
-    store_tile(0);
-    __syncthreads();
-
     const float scale2 = p.scale2;
-    for (int kt = 0; kt < ntiles; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < ntiles) fetch_tile(kt + 1);
-
+    auto compute_tile = [&](int kt, int buf, auto masked) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked)::value;
         // ---- S^T = K Q^T : st[rb][half][v] = score of key 32kt + 16half + 4hg + v against row n16
         f32x4 st[RB][2];
 #pragma unroll
@@ -218,31 +225,35 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
             }
 
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
-        const int keyb = kt * kPfKeys + 4 * hg;
+        // x = score - reference, formed directly: st*scale2 + slope2*key + (-slope2*pos - m_ref)
+        float keyf[8];
+        {
+            const float k0 = (float)(kt * kPfKeys + 4 * hg);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) keyf[e] = k0 + (float)(16 * (e >> 2) + (e & 3));
+        }
         uint32_t pk[RB][4], pk_lo[RB][4];
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            float s2[8];
-            bool need = false;
+            const float cm = -fmaf(slope2[rb], posf[rb], m_ref[rb]);
+            float x[8];
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int key = keyb + 16 * half + v;
-                    const float x = fmaf(st[rb][half][v], scale2, slope2[rb] * ((float)key - posf[rb]));
-                    s2[4 * half + v] = key <= pos[rb] ? x : -INFINITY;
-                    need |= s2[4 * half + v] > m_ref[rb] + PfSoftmax<DT>::kThreshold;
-                }
-            if (__builtin_amdgcn_ballot_w64(need) != 0) {
-                float mx = s2[0];
-#pragma unroll
-                for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s2[e]);
+            for (int e = 0; e < 8; ++e) {
+                x[e] = fmaf(st[rb][e >> 2][e & 3], scale2, fmaf(slope2[rb], keyf[e], cm));
+                if (MASKED) x[e] = keyf[e] <= posf[rb] ? x[e] : -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+            if (__builtin_amdgcn_ballot_w64(kt == 0 || mx > PfSoftmax<DT>::kThreshold) != 0) {
                 mx = fmaxf(mx, __shfl_xor(mx, 16));              // the row's keys live in 4 lanes (hg)
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_ref[rb], mx + PfSoftmax<DT>::kHeadroom);
-                const float alpha = fast_exp2(m_ref[rb] - m_new);
-                m_ref[rb] = m_new;
+                // move the reference up to kHeadroom above this tile's maximum; it never moves down
+                // (rows with no visible key in the tile, or with lower scores, keep theirs)
+                const float delta = fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
+                const float alpha = fast_exp2(-delta);
+                m_ref[rb] += delta;
                 lsum[rb] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] -= delta;
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
@@ -250,7 +261,7 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
             }
             float pw[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pw[e] = fast_exp2(s2[e] - m_ref[rb]);
+            for (int e = 0; e < 8; ++e) pw[e] = fast_exp2(x[e]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 pk[rb][e] = pack2<DT>(pw[2 * e], pw[2 * e + 1]);
@@ -278,7 +289,38 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
             }
         }
 
-        if (kt + 1 < ntiles) store_tile(buf ^ 1);
+    };
+
+    const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
+
+    fetch_tile(stage_a, 0);
+    store_tile(stage_a, 0);
+    fetch_tile(stage_b, 1);
+    fetch_tile(stage_a, 2);
+    __syncthreads();
+    // Tiles below the diagonal of every row first (no mask), then the few that touch it.
+    const int n_unmasked = min(ntiles, max(0, (pos_min + 1) / kPfKeys));
+    int kt = 0;
+    for (; kt < n_unmasked; ++kt) {
+        compute_tile(kt, kt & 1, std::false_type{});
+        if (kt & 1) {
+            if (kt + 1 < ntiles) store_tile(stage_a, 0);
+            fetch_tile(stage_a, kt + 3);
+        } else {
+            if (kt + 1 < ntiles) store_tile(stage_b, 1);
+            fetch_tile(stage_b, kt + 3);
+        }
+        __syncthreads();
+    }
+    for (; kt < ntiles; ++kt) {
+        compute_tile(kt, kt & 1, std::true_type{});
+        if (kt & 1) {
+            if (kt + 1 < ntiles) store_tile(stage_a, 0);
+            fetch_tile(stage_a, kt + 3);
+        } else {
+            if (kt + 1 < ntiles) store_tile(stage_b, 1);
+            fetch_tile(stage_b, kt + 3);
+        }
         __syncthreads();
     }
 
