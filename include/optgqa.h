@@ -38,6 +38,9 @@ extern "C" {
 
 typedef enum { OPTGQA_F16 = 0, OPTGQA_BF16 = 1 } optgqa_dtype;
 
+/* partition_size value that asks optgqa_paged_attention for the equal-work split. */
+#define OPTGQA_SPLIT_BALANCED (-2)
+
 typedef enum {
     OPTGQA_OK = 0,
     OPTGQA_ERR_NULL = -1,        /* a required pointer is NULL */
@@ -95,7 +98,12 @@ int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *
  *   partition_size  0: the library decides whether and how to split the context;
  *                   >0: split the context into runs of this many tokens (multiple of
  *                       block_size and of 16), one workgroup per run, then combine;
- *                   <0: never split.
+ *                   OPTGQA_SPLIT_BALANCED: split by equal work - every wave of the launch gets
+ *                       the same number of 16-token tiles, whatever the mix of context
+ *                       lengths, and the pieces are combined afterwards (head_dim 128 only,
+ *                       else OPTGQA_ERR_UNSUPPORTED); this is also what 0 picks for
+ *                       head_dim 128 whenever it splits;
+ *                   any other negative value: never split.
  *   workspace       fp32 scratch for the split path, at least
  *                   optgqa_paged_attention_workspace_bytes(...) bytes for the same arguments;
  *                   may be NULL when that returns 0.  Contents are undefined afterwards.
@@ -112,7 +120,7 @@ int optgqa_paged_attention(void *out, const void *q, const void *k_cache, const 
 
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
  * Also reports, when chosen_partition_size is not NULL, the partition size the library would
- * use (0 = unsplit). */
+ * use (0 = unsplit, OPTGQA_SPLIT_BALANCED = the equal-work split). */
 size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads,
                                               int head_dim, int block_size, int max_context_len,
                                               int partition_size, int *chosen_partition_size);

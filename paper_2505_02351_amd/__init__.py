@@ -24,6 +24,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "liboptgqa.so")
 
 F16, BF16 = 0, 1
+SPLIT_BALANCED = -2          # partition_size: equal-work split (OPTGQA_SPLIT_BALANCED)
 OK = 0
 
 _lib: Optional[ctypes.CDLL] = None

@@ -35,6 +35,14 @@ struct DecodeParams {
     int num_seqs;
     int row_offset;             // first row handled by this launch (grid.z/y counts from here)
     int heads_per_wg;           // query heads one workgroup serves (divides the group size)
+    // Equal-work split (head_dim 128): one unit per wave, see decode_flat_kernels.hpp.
+    // There ws_m / ws_l are [slot][heads_per_wg] and ws_o is [slot][heads_per_wg][D].
+    int num_units;              // waves of the launch
+    int segs_per_seq;           // KV heads x head chunks
+    int32_t* plan;              // [num_seqs + 1]: tile prefix P_b per non-empty sequence, then tiles per unit
+#ifdef OPTGQA_FLAT_TIMING
+    unsigned long long* timing; // development builds only: 4 clock samples per unit
+#endif
 };
 
 // Sequence and number of visible keys of one output row; false if the row does not exist

@@ -8,6 +8,7 @@
 #include "decode_kernels.hpp"
 #include "decode_mc_kernels.hpp"
 #include "decode_mma_kernels.hpp"
+#include "decode_flat_kernels.hpp"
 #include "prefill_kernels.hpp"
 
 using namespace optgqa;
@@ -65,18 +66,67 @@ int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int head_dim, 
     return P;
 }
 
+// Rows are sequences (decode) or new query tokens (row-wise prefill).  A launch covers at most
+// kMaxRowsPerLaunch rows because grid.y / grid.z are 16-bit.
+constexpr int kMaxRowsPerLaunch = 65535;
+
 struct SplitPlan {
-    int partition_size;   // 0 = unsplit
+    int partition_size;   // 0 = unsplit, OPTGQA_SPLIT_BALANCED = equal-work split
     int num_partitions;
     size_t bytes;
+    // equal-work split only
+    int workgroups;
+    int segs_per_seq;
+    size_t plan_floats, ml_floats;
 };
+
+// Equal-work split: one wave per hardware wave slot at most, and no wave with less than
+// kFlatMinTiles tiles of 16 tokens when the lengths are at their bound.
+constexpr int kFlatMaxWorkgroups = kNumCUs * OPTGQA_FLAT_WGS_PER_CU;
+#ifndef OPTGQA_FLAT_MIN_TILES
+#define OPTGQA_FLAT_MIN_TILES 8
+#endif
+constexpr int kFlatMinTiles = OPTGQA_FLAT_MIN_TILES;
+
+size_t round_up4(size_t x) { return (x + 3) / 4 * 4; }
+
+bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len)
+{
+    const int group = num_heads / num_kv_heads;
+    const int gh = heads_per_workgroup(group, 128);
+    const int64_t Y = (int64_t)num_kv_heads * (group / gh);
+    const int64_t segs = Y * num_seqs;
+    if (num_seqs > kMaxRowsPerLaunch) return false;          // the combine kernel's grid.y
+    // Flat tile indices are 32-bit.  2^30 tiles would be 8 TiB of cache, so the margin of 2 also
+    // covers lengths above the stated bound.
+    const int64_t tiles = segs * ((max_context_len + kMmaTile - 1) / kMmaTile);
+    if (tiles >= (1LL << 30)) return false;
+    int64_t wgs = (tiles + (int64_t)kDecodeWaves * kFlatMinTiles - 1) / ((int64_t)kDecodeWaves * kFlatMinTiles);
+    if (wgs > kFlatMaxWorkgroups) wgs = kFlatMaxWorkgroups;
+    if (wgs < 1) wgs = 1;
+    s.partition_size = OPTGQA_SPLIT_BALANCED;
+    s.num_partitions = 1;
+    s.workgroups = (int)wgs;
+    s.segs_per_seq = (int)Y;
+    const size_t slots = (size_t)wgs * kDecodeWaves + (size_t)segs;
+    s.plan_floats = round_up4((size_t)num_seqs + 1);
+    s.ml_floats = round_up4(slots * gh);
+    s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * gh * 128) * sizeof(float);
+    return true;
+}
 
 SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                      int max_context_len, int partition_size)
 {
-    SplitPlan s{0, 1, 0};
+    SplitPlan s{0, 1, 0, 0, 0, 0, 0};
     int P = partition_size;
     if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
+    // The library's own choice for head_dim 128 is the equal-work split whenever splitting pays.
+    if (head_dim == 128 && (partition_size == OPTGQA_SPLIT_BALANCED || (partition_size == 0 && P > 0))) {
+        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len))
+            return s;
+        if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
+    }
     if (P <= 0) return s;
     s.partition_size = P;
     s.num_partitions = (max_context_len + P - 1) / P;
@@ -119,9 +169,6 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
     return launch_status();
 }
 
-// Rows are sequences (decode) or new query tokens (row-wise prefill).  A launch covers at most
-// kMaxRowsPerLaunch rows because grid.y / grid.z are 16-bit.
-constexpr int kMaxRowsPerLaunch = 65535;
 
 template <int DT, int D>
 int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
@@ -153,6 +200,40 @@ int launch_decode_any(int dtype, int head_dim, A... args)
     return head_dim == 128 ? launch_decode<kBF16, 128>(args...) : launch_decode<kBF16, 64>(args...);
 }
 
+// Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
+// the device keeps resident at once, because a unit that has to wait for a free slot would start
+// when every other unit is nearly done.
+template <int DT>
+int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
+{
+    static const int resident = [] {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT>, kDecodeWaves * 64, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        return per_cu * cus;
+    }();
+    if (resident <= 0) return OPTGQA_ERR_LAUNCH;
+    if (workgroups > resident) workgroups = resident;
+    const int group = p.num_heads / p.num_kv_heads;
+    p.heads_per_wg = heads_per_workgroup(group, 128);
+    p.num_units = workgroups * kDecodeWaves;
+    hipLaunchKernelGGL((paged_decode_flat_kernel<DT>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+    int rc = launch_status();
+    if (rc != OPTGQA_OK) return rc;
+    constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
+    hipLaunchKernelGGL((paged_decode_flat_reduce_kernel<DT>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+                       dim3(kReduceThreads), 0, st, p);
+    return launch_status();
+}
+
+int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st)
+{
+    return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16>(p, workgroups, st)
+                               : launch_decode_flat_dt<kBF16>(p, workgroups, st);
+}
+
 // Row-wise prefill: every new query token is handled like a decode row whose context ends at
 // its own position (exact, but K/V are re-read per query token; used where the tiled MFMA
 // kernel does not apply).
@@ -178,6 +259,8 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     p.cu_q_lens = pp.cu_q_lens;
     p.num_seqs = num_seqs;
     p.row_offset = 0;
+    p.plan = nullptr;
+    p.num_units = p.segs_per_seq = 0;
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
@@ -300,11 +383,13 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
 
     SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
                              max_context_len > 0 ? max_context_len : 1, partition_size);
-    if (s.partition_size > 0) {
+    if (partition_size == OPTGQA_SPLIT_BALANCED && s.partition_size != OPTGQA_SPLIT_BALANCED)
+        return OPTGQA_ERR_UNSUPPORTED;                   // head_dim 64, or sizes beyond 32-bit tile indices
+    if (s.partition_size != 0) {
         const bool have = workspace && workspace_bytes >= s.bytes && aligned16(workspace);
         if (!have) {
-            if (partition_size > 0) return OPTGQA_ERR_WORKSPACE;
-            s = SplitPlan{0, 1, 0};                      // library's own choice: fall back to unsplit
+            if (partition_size != 0) return OPTGQA_ERR_WORKSPACE;
+            s = SplitPlan{0, 1, 0, 0, 0, 0, 0};          // library's own choice: fall back to unsplit
         }
     }
 
@@ -321,6 +406,25 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
     p.max_blocks_per_seq = max_blocks_per_seq;
+    p.cu_q_lens = nullptr;
+    p.num_seqs = num_seqs;
+    p.row_offset = 0;
+    if (s.partition_size == OPTGQA_SPLIT_BALANCED) {
+        p.plan = static_cast<int32_t*>(workspace);
+        p.ws_m = static_cast<float*>(workspace) + s.plan_floats;
+        p.ws_l = p.ws_m + s.ml_floats;
+        p.ws_o = p.ws_l + s.ml_floats;
+        p.partition_size = 1 << 30;
+        p.num_partitions = 1;
+        p.segs_per_seq = s.segs_per_seq;
+#ifdef OPTGQA_FLAT_TIMING
+        p.timing = workspace_bytes >= s.bytes + (size_t)s.workgroups * kDecodeWaves * 32
+                       ? reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + s.bytes) : nullptr;
+#endif
+        return launch_decode_flat((int)dtype, p, s.workgroups, static_cast<hipStream_t>(stream));
+    }
+    p.plan = nullptr;
+    p.num_units = p.segs_per_seq = 0;
     if (s.partition_size > 0) {
         const size_t n = (size_t)num_seqs * num_heads * s.num_partitions;
         p.ws_m = static_cast<float*>(workspace);
@@ -333,9 +437,6 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
         p.partition_size = 1 << 30;
         p.num_partitions = 1;
     }
-    p.cu_q_lens = nullptr;
-    p.num_seqs = num_seqs;
-    p.row_offset = 0;
     return launch_decode_any((int)dtype, head_dim, p, num_seqs, static_cast<hipStream_t>(stream));
 }
 

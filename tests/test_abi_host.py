@@ -73,6 +73,8 @@ def test_argument_errors_before_any_launch(G):
     assert call(q=None) == -1
     assert call(out=ctypes.c_void_p(8)) == -3    # misaligned
     assert call(P=32) == -4                      # split forced, no workspace
+    assert call(P=-2) == -3                      # equal-work split: head_dim 128 only
+    assert call(P=-2, D=128) == -4               # ... and it needs its workspace
     assert call(B=0) == 0
     assert call(dt=2) == -3
     # prefill
@@ -91,7 +93,18 @@ def test_workspace_query(G):
     assert P == 512 and n == 4 * 64 * 64 * (128 + 2) * 4
     n, P = G.paged_attention_workspace_bytes(1, 8, 2, 64, 16, 128, 0)
     assert (n, P) == (0, 0)                      # short context: no split
+    # head_dim 128 and worth splitting: the equal-work split, one slot per wave plus one per
+    # (sequence, KV head), each slot 8 heads x (128 + 2) floats, after 64 + 1 plan entries padded to 4
     n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, 0)
+    slots = 256 * 3 * 4 + 64 * 4
+    assert P == G.SPLIT_BALANCED and n == (68 + slots * 8 * (128 + 2)) * 4
+    assert G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, G.SPLIT_BALANCED) == (n, P)
+    # small problems get fewer waves: 2 x 2 segments x 13 tiles -> 52 tiles -> 2 workgroups
+    n, P = G.paged_attention_workspace_bytes(2, 8, 2, 128, 16, 200, G.SPLIT_BALANCED)
+    assert P == G.SPLIT_BALANCED and n == (4 + (2 * 4 + 4) * 4 * (128 + 2)) * 4
+    # head_dim 64 has no equal-work split; its own choice stays a fixed partition size
+    assert G.paged_attention_workspace_bytes(64, 32, 4, 64, 32, 8192, G.SPLIT_BALANCED) == (0, 0)
+    n, P = G.paged_attention_workspace_bytes(64, 32, 4, 64, 32, 8192, 0)
     assert P > 0 and P % 32 == 0 and n > 0
     n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, -1)
     assert (n, P) == (0, 0)

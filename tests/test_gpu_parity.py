@@ -111,6 +111,8 @@ def test_gather_kv_bit_exact(U, oracle):
 
 
 # ------------------------------------------------------------------ decode, small sweep
+BALANCED = -2      # OPTGQA_SPLIT_BALANCED
+
 SWEEP = [
     # dtype, Hq, Hkv, D, bs, batch, ctx_lo, ctx_hi
     (W.F16, 8, 2, 64, 16, 3, 1, 200),
@@ -127,11 +129,13 @@ SWEEP = [
 
 
 @pytest.mark.parametrize("i", range(len(SWEEP)))
-@pytest.mark.parametrize("partition", [-1, 0, 64, 256])
+@pytest.mark.parametrize("partition", [-1, 0, 64, 256, BALANCED])
 def test_decode_sweep(U, oracle, i, partition):
     dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
     if partition > 0 and partition % bs:
         pytest.skip("partition size must be a multiple of the block size")
+    if partition == BALANCED and D != 128:
+        pytest.skip("the equal-work split exists for head_dim 128 only")
     cfg = W.small_config(name=f"sweep{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
                          head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
                          ctx_hi=hi, seed=400 + i)
@@ -158,7 +162,7 @@ def test_decode_edge_lengths(U, oracle, dtype):
     case.q = q_full
     kc, vc = oracle_filled(oracle, case)
     ref = oracle_decode(oracle, case, kc, vc)
-    for partition in (-1, 0, 64, 256):
+    for partition in (-1, 0, 64, 256, BALANCED):
         dev = U.DevCase(case)
         dev.write_cache()
         got = dev.decode(partition_size=partition)
@@ -184,7 +188,7 @@ def test_decode_one_hot_selects_row_bit_exact(U, oracle, dtype):
     case.k_cache[:] = 0
     case.k_new[:] = 0
     kc, vc = oracle_filled(oracle, case)
-    for partition in (-1, 64, 256):
+    for partition in (-1, 64, 256, BALANCED):
         dev = U.DevCase(case)
         dev.write_cache()
         got = dev.decode(partition_size=partition)
@@ -257,6 +261,55 @@ def test_append_equals_bulk_fill(U, oracle):
     assert np.array_equal(U.to_host(out), U.to_host(out2))
 
 
+@pytest.mark.parametrize("B,hi,zeros", [(300, 90, 40), (4200, 40, 900)])
+def test_decode_balanced_many_sequences(U, oracle, B, hi, zeros):
+    """Equal-work split with more sequences than lanes (every lane scans a run of sequences, then
+    the run is searched), short and empty contexts mixed in, so that many units cross several
+    sequence boundaries and some sequences are skipped altogether."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(1, hi + 1, size=B).astype(np.int32)
+    lens[rng.choice(B, size=zeros, replace=False)] = 0
+    lens[-1] = 0                      # the walk must also end on an empty sequence
+    lens[B // 2] = hi * 8             # one long context among the short ones
+    cfg = W.small_config(name="many", dtype=W.BF16, batch=B, num_heads=8, num_kv_heads=2, head_dim=128,
+                         block_size=16, num_blocks=int(np.sum((lens + 15) // 16)) + 5, ctx_lo=1,
+                         ctx_hi=hi * 8, seed=B)
+    case = W.make_case(cfg, context_lens=lens)
+    q_full = np.zeros((B, 8, 128), np.uint16)
+    q_full[lens > 0] = case.q
+    case.q = q_full
+    dev = U.DevCase(case)
+    dev.write_cache()
+    got = dev.decode(partition_size=BALANCED)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    assert not got[lens == 0].any(), "an empty context must give +0"
+    assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+
+
+def test_decode_balanced_matches_fixed_partitions(U):
+    """The two ways of splitting the context agree to fp32 combine rounding (both well inside the
+    output rounding), on a ragged batch whose units start and end inside segments."""
+    cfg = W.small_config(name="bal", dtype=W.F16, batch=9, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=32, num_blocks=9 * 40 + 3, ctx_lo=1, ctx_hi=1200, seed=77)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    a = W.from_bits(dev.decode(partition_size=BALANCED), W.F16)
+    b = W.from_bits(dev.decode(partition_size=256), W.F16)
+    assert np.max(np.abs(a - b)) <= 2.0 ** -9
+
+
+def test_decode_balanced_rejects_head_dim_64(U):
+    import torch
+    cfg = W.small_config(name="bal64", dtype=W.F16, batch=2, num_heads=8, num_kv_heads=2, head_dim=64,
+                         block_size=16, num_blocks=40, ctx_lo=10, ctx_hi=200, seed=5)
+    dev = U.DevCase(W.make_case(cfg))
+    dev.write_cache()
+    with pytest.raises(RuntimeError):
+        dev.decode(partition_size=BALANCED, workspace=torch.empty(1 << 20, dtype=torch.float32, device="cuda"))
+
+
 # ------------------------------------------------------------------ the workloads themselves
 @pytest.mark.parametrize("name", ["C1", "C2"])
 def test_decode_workload_full(U, oracle, name):
@@ -272,15 +325,16 @@ def test_decode_workload_full(U, oracle, name):
         assert err <= U.TOL[case.dtype], (name, partition, err)
 
 
-@pytest.mark.parametrize("name", ["C3", "C4"])
-def test_decode_workload_sampled(U, oracle, name):
-    """Full-size batch in the launch configuration the bench times; the oracle evaluates a sample
-    of (sequence, head) rows one by one, chosen to include the longest and shortest sequences."""
+@pytest.mark.parametrize("name,partition", [("C3", None), ("C4", None), ("C4", BALANCED), ("C3", 1024)])
+def test_decode_workload_sampled(U, oracle, name, partition):
+    """Full-size batch in the launch configuration the bench times (and in the other split mode);
+    the oracle evaluates a sample of (sequence, head) rows one by one, chosen to include the
+    longest and shortest sequences."""
     cfg = W.CONFIGS[name]
     case = W.make_case(cfg)
     dev = U.DevCase(case)
     dev.write_cache()
-    got = dev.decode(partition_size=cfg.partition_size)
+    got = dev.decode(partition_size=cfg.partition_size if partition is None else partition)
     assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
     kc, vc = oracle_filled(oracle, case)
     rng = np.random.default_rng(99)
