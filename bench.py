@@ -2,15 +2,21 @@
 """Benchmark of the paged GQA + ALiBi decode hot path on one MI355X.
 
 One "step" = one pass of the whole path over one synthetic batch that is already resident in
-HBM: the KV-cache write of the step's new tokens (optgqa_reshape_and_cache) followed by decode
-attention over the paged cache (optgqa_paged_attention; split-context partitions + combine
-when the library or the workload asks for them).
+HBM: the KV-cache write of the step's new tokens and decode attention over the paged cache
+(block-table lookup, group scores, ALiBi, softmax, weighted sum, split-context partition +
+combine).  Decode workloads whose partition size is left to the library run the step as ONE
+call, optgqa_decode_step; with --partition-size (or a workload that fixes it) the step is
+optgqa_reshape_and_cache followed by optgqa_paged_attention.  Prefill workloads (C5) run
+optgqa_reshape_and_cache + optgqa_paged_prefill.
 
 Prints ONE JSON line.  `value` is the KV-read rate: algorithmic KV bytes of the batch
 (2 * sum(context_lens) * Hkv * D * 2 bytes: every K and V element once per KV-head group)
-divided by the wall-clock time of a step.  `roofline` prices the attention call alone (HIP
-events on the launch stream) against the 8 TB/s HBM peak.  `cpu_baseline` times the fp64 CPU
-oracle on a bounded sample of the same batch.
+divided by the wall-clock time of a step, over K steps timed without any event in the stream.
+`roofline` prices the dominant kernel alone - the one that streams the KV cache - from HIP
+events that the library records around that kernel's launch (optgqa_set_kernel_events) in a
+second pass of K steps: HBM-bound for decode (8 TB/s peak), MFMA-bound for the tiled prefill
+(2.5 PFLOP/s dense bf16/fp16).  `cpu_baseline` times the fp64 CPU oracle on a bounded sample
+of the same batch.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--partition-size P]
 """
@@ -28,6 +34,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
 # HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
 # measured for the workload.
@@ -134,7 +141,14 @@ def main():
     scale = float(case.scale)
     stream = torch.cuda.current_stream()
 
-    def attention():
+    one_call = decode and P == 0
+
+    def step():
+        if one_call:
+            G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                          dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
+            return
+        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
         if decode:
             G.paged_attention(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
                               dev.slopes, scale, max_ctx, P, ws, stream)
@@ -142,32 +156,60 @@ def main():
             G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
                             dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
 
-    def step():
-        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
-        attention()
-
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    # ---- pass 1: K steps, wall clock, nothing but the step's own launches in the stream -------
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
-        starts[i].record(stream)
-        attention()
-        stops[i].record(stream)
+        step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # ---- pass 2: the same K steps with an event pair around the dominant kernel of each --------
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    for e in starts + stops:
+        e.record(stream)                      # makes torch create the HIP event behind it
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        G.set_kernel_events(starts[i], stops[i])
+        step()
+    G.set_kernel_events(None, None)
+    torch.cuda.synchronize()
+    kernel_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
+
     ms_per_step = wall * 1e3 / args.steps
-    attn_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
     kv_bytes = case.kv_bytes()
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
-    achieved = kv_bytes / (attn_ms.mean() * 1e-3) / 1e9
     n_q = case.num_tokens
+    launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
+                 "min": float(kernel_ms.min()), "p90": float(np.percentile(kernel_ms, 90))}
+    if decode:
+        achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
+        if chosen_P == G.SPLIT_BALANCED:
+            kname = "paged_decode_flat_kernel (equal-work split%s)" % (", cache write fused" if one_call else "")
+        else:
+            kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None else None,
+                    "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
+    else:
+        # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
+        # (query, key, head) each
+        flops = 0
+        for b in range(cfg.batch):
+            n_b = int(case.q_lens[b])
+            first = int(case.context_lens[b]) - n_b
+            flops += 4 * cfg.num_heads * cfg.head_dim * (n_b * first + n_b * (n_b + 1) // 2)
+        achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
+                    "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
+                    "launch_ms": launch_ms}
 
     result = {
         "metric": "paged GQA+ALiBi decode: KV-read HBM GB/s (% of peak) and query tokens/s",
@@ -177,15 +219,11 @@ def main():
         "config": {"workload": cfg.name, "kind": cfg.kind, "batch": cfg.batch, "num_heads": cfg.num_heads,
                    "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
                    "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
-                   "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks},
+                   "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
+                   "calls_per_step": 1 if one_call else 2},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                     "kernel": "optgqa_paged_attention (partition kernel + combine kernel)",
-                     "algorithmic_bytes_per_launch": kv_bytes,
-                     "launch_ms": {"mean": float(attn_ms.mean()), "median": float(np.median(attn_ms)),
-                                   "min": float(attn_ms.min()), "p90": float(np.percentile(attn_ms, 90))}},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(case, W, args.cpu_sample_seqs)

@@ -118,6 +118,45 @@ int optgqa_paged_attention(void *out, const void *q, const void *k_cache, const 
                            void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
                            void *stream);
 
+/*
+ * Measurement aid, not part of the method: with two hipEvent_t handles set, every later
+ * optgqa_paged_attention / optgqa_decode_step / optgqa_paged_prefill call made by the SAME
+ * host thread records `start_event` just before and `stop_event` just after it launches the
+ * kernel that streams the KV cache (the partition / equal-work / tiled prefill kernel), on
+ * the call's stream - the small combine and cache-write kernels stay outside the pair.  The
+ * caller owns the events and reads hipEventElapsedTime after synchronising.  (NULL, NULL)
+ * switches the recording off; one NULL and one handle is OPTGQA_ERR_NULL.
+ */
+int optgqa_set_kernel_events(void *start_event, void *stop_event);
+
+/*
+ * One decode step as a single call (Alg. 2: store K_new, V_new into the caches, then compute
+ * the context attention with the caches).  Sequence b appends exactly one token: its K/V rows
+ * k_new[b], v_new[b] go to logical position context_lens[b] - 1 (context_lens already counts
+ * the new token; the physical slot is block_tables[b][pos / block_size] * block_size +
+ * pos % block_size), and out[b] is the attention of q[b] over positions 0 .. context_lens[b] - 1.
+ * Same result, bit for bit in the caches and to rounding in `out`, as
+ * optgqa_reshape_and_cache with that slot mapping followed by optgqa_paged_attention with
+ * partition_size 0; sequences with context_lens[b] == 0 write nothing and give a row of +0.
+ * Where the equal-work split applies (head_dim 128, workspace given) the cache write happens
+ * inside the attention kernel - one launch less per step; otherwise the library issues the
+ * two launches itself.
+ *
+ *   k_new, v_new    [num_seqs][num_kv_heads][head_dim]; sequence b starts at element
+ *                   b * k_token_stride (resp. v_token_stride), strides >= num_kv_heads * head_dim
+ *   k_cache,v_cache modified in place (one row per sequence and KV head)
+ *   workspace       as for optgqa_paged_attention with partition_size 0 (sized by
+ *                   optgqa_paged_attention_workspace_bytes); NULL / too small: unsplit kernels
+ * Other arguments and errors as optgqa_paged_attention.
+ */
+int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *v_new,
+                       void *k_cache, void *v_cache, const int32_t *block_tables,
+                       const int32_t *context_lens, const float *alibi_slopes, float scale,
+                       int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                       int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
+                       int64_t v_token_stride, void *workspace, size_t workspace_bytes,
+                       optgqa_dtype dtype, void *stream);
+
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
  * Also reports, when chosen_partition_size is not NULL, the partition size the library would
  * use (0 = unsplit, OPTGQA_SPLIT_BALANCED = the equal-work split). */

@@ -54,6 +54,11 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_attention.restype = i32
     lib.optgqa_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                            i32, vp, sz, i32, vp]
+    lib.optgqa_set_kernel_events.restype = i32
+    lib.optgqa_set_kernel_events.argtypes = [vp, vp]
+    lib.optgqa_decode_step.restype = i32
+    lib.optgqa_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                       i64, i64, vp, sz, i32, vp]
     lib.optgqa_paged_attention_workspace_bytes.restype = sz
     lib.optgqa_paged_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32,
                                                            ctypes.POINTER(ctypes.c_int)]
@@ -151,6 +156,45 @@ def paged_attention(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v
                                     int(block_tables.shape[1]), int(max_context_len), int(partition_size),
                                     _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_paged_attention")
+
+
+def set_kernel_events(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
+    """optgqa_set_kernel_events: record the two events around the KV-streaming kernel of later calls
+    (None, None switches it off).  The events must have been recorded once already, so that
+    torch has created the underlying HIP events."""
+    lib = load_library()
+    if start is None and stop is None:
+        _check(lib.optgqa_set_kernel_events(None, None), "optgqa_set_kernel_events")
+        return
+    a, b = int(start.cuda_event), int(stop.cuda_event)
+    if not a or not b:
+        raise ValueError("optgqa: record the events once before handing them over")
+    _check(lib.optgqa_set_kernel_events(ctypes.c_void_p(a), ctypes.c_void_p(b)), "optgqa_set_kernel_events")
+
+
+def decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                context_lens: torch.Tensor, alibi_slopes: Optional[torch.Tensor], scale: float,
+                max_context_len: int, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """optgqa_decode_step: the step's cache write and its decode attention in one call."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    if B and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if B else Hkv * D
+    vs = int(v_new.stride(0)) if B else Hkv * D
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_decode_step(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale), B, Hq,
+                                Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len), ks, vs,
+                                _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_decode_step")
 
 
 def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

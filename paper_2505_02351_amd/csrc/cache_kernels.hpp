@@ -8,11 +8,15 @@ namespace optgqa {
 // token's K row or V row; pieces of a row are handled by consecutive lanes, so reads and
 // writes are contiguous runs of head_dim * 2 bytes.
 //   grid.x covers num_tokens * pieces_per_token * 2 threads (K pieces then V pieces).
+//   slot_mapping == nullptr (decode step): token t is the newest token of sequence t and goes to
+//   position context_lens[t] - 1, whose slot is read from the block table; empty sequences skip.
 template <typename VecT>
 __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, uint16_t* __restrict__ k_cache,
     uint16_t* __restrict__ v_cache, const int64_t* __restrict__ slot_mapping, int num_tokens,
-    int num_kv_heads, int head_dim, int block_size, int64_t k_token_stride, int64_t v_token_stride)
+    int num_kv_heads, int head_dim, int block_size, int64_t k_token_stride, int64_t v_token_stride,
+    const int32_t* __restrict__ block_tables = nullptr, const int32_t* __restrict__ context_lens = nullptr,
+    int max_blocks_per_seq = 0)
 {
     constexpr int kElems = sizeof(VecT) / 2;
     const int pieces_per_head = head_dim / kElems;
@@ -24,7 +28,14 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
     const int64_t rem = idx - (int64_t)which * num_tokens * pieces_per_token;
     const int t = (int)(rem / pieces_per_token);
     const int piece = (int)(rem - (int64_t)t * pieces_per_token);
-    const int64_t slot = slot_mapping[t];
+    int64_t slot;
+    if (slot_mapping) {
+        slot = slot_mapping[t];
+    } else {
+        const int pos = context_lens[t] - 1;
+        if (pos < 0) return;
+        slot = (int64_t)block_tables[(int64_t)t * max_blocks_per_seq + pos / block_size] * block_size + pos % block_size;
+    }
     if (slot < 0) return;                                   // padding token
     const int g = piece / pieces_per_head;
     const int d0 = (piece - g * pieces_per_head) * kElems;

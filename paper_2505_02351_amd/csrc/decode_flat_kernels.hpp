@@ -46,7 +46,13 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
     return x;
 }
 
-template <int DT>
+//
+// FUSED: the kernel also performs the step's cache write (Alg. 2 stores the new K/V, then attends
+// over the cache).  The new token of sequence b is its last one; whichever wave handles the tile
+// that contains it takes that row from k_new / v_new instead of the cache (a per-lane pointer
+// select), and the wave that finishes a KV head's segment copies the row into the cache.  No
+// wave reads that cache row during the launch, so there is nothing to order.
+template <int DT, bool FUSED>
 __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
     constexpr int D = 128;
@@ -136,20 +142,27 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
 
     // One 16-token tile of a segment into operand order.  All 16 tokens lie in one physical block;
     // rows past t_last (the piece's last token) re-read that row and are masked out of the scores.
-    auto load_tile = [&](MmaTile& Tl, const int32_t* tab, int64_t head_off, int t_last, int tile_t0)
-                         __attribute__((always_inline)) {
+    const uint16_t* __restrict__ k_new = static_cast<const uint16_t*>(p.k_new);
+    const uint16_t* __restrict__ v_new = static_cast<const uint16_t*>(p.v_new);
+    // (new_pos, new_off_k, new_off_v: position of the segment's new token and where its K / V
+    // rows start in k_new / v_new; only read when FUSED)
+    auto load_tile = [&](MmaTile& Tl, const int32_t* tab, int64_t head_off, int t_last, int tile_t0,
+                         int new_pos, int64_t new_off_k, int64_t new_off_v) __attribute__((always_inline)) {
         // through the scalar cache: a vector load here would make the wave wait for every tile
         // load still in flight before it could read the block number
         const int blk = scalar_load_i32(tab + (tile_t0 >> bs_shift));
         const int64_t uni = blk * block_stride + head_off + (int64_t)(tile_t0 & (bs - 1)) * D;
         const int tk = min(tile_t0 + j16, t_last) - tile_t0;
         const uint16_t* ka = kc + uni + tk * D + 8 * hg;
+        if (FUSED && tile_t0 + tk == new_pos) ka = k_new + new_off_k + 8 * hg;
 #pragma unroll
         for (int i = 0; i < 4; ++i) Tl.k[i] = *reinterpret_cast<const uint4*>(ka + 32 * i);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-            Tl.v[s] = *reinterpret_cast<const uint4*>(vc + uni + tv * D + 8 * j16);
+            const uint16_t* va = vc + uni + tv * D + 8 * j16;
+            if (FUSED && tile_t0 + tv == new_pos) va = v_new + new_off_v + 8 * j16;
+            Tl.v[s] = *reinterpret_cast<const uint4*>(va);
         }
     };
     // A operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
@@ -191,10 +204,23 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         const int g = y / chunks;
         const int32_t* table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
+        const int64_t new_off_k = FUSED ? b * p.k_new_stride + (int64_t)g * D : 0;
+        const int64_t new_off_v = FUSED ? b * p.v_new_stride + (int64_t)g * D : 0;
 
         if (!chained) {
             load_q(qa, slope2, b, y);
-            load_tile(buf[0], table, head_off, t_last, t_begin);
+            load_tile(buf[0], table, head_off, t_last, t_begin, Lm1, new_off_k, new_off_v);
+        }
+        if (FUSED && tau_end == n && y == g * chunks) {
+            // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
+            const int blk = scalar_load_i32(table + (Lm1 >> bs_shift));
+            const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
+            if (lane < 32) {
+                const int piece = 8 * (lane & 15);
+                const uint16_t* src = lane < 16 ? k_new + new_off_k + piece : v_new + new_off_v + piece;
+                uint16_t* dstp = (lane < 16 ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + dst + piece;
+                *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
+            }
         }
         if (lane == 0) {
             // the combine kernel needs P_b of every non-empty sequence and the unit length
@@ -225,6 +251,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         const int64_t nhead_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
         const int nt_last = has_next ? min(nL, min(nn, f1 - (f + ntw)) * TILE) - 1 : t_last;
         const int nt0 = has_next ? 0 : t_begin + j_last * TILE;
+        const int64_t nnew_off_k = FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
+        const int64_t nnew_off_v = FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
         load_q(qn, slope2n, nb, ny);
 
         float m_ref[4], l[4];
@@ -294,14 +322,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         const int trips = (ntw + 1) >> 1;
         for (int it = 0; it < trips; ++it) {
             const int j = 2 * it;
-            load_tile(buf[1], table, head_off, t_last, t_begin + min(j + 1, j_last) * TILE);
+            load_tile(buf[1], table, head_off, t_last, t_begin + min(j + 1, j_last) * TILE, Lm1, new_off_k, new_off_v);
             compute_tile(buf[0], j);
 #ifdef OPTGQA_FLAT_TIMING
             if (tm1 == 0) tm1 = wall_clock64();
 #endif
             const bool more = j + 2 <= j_last;
             load_tile(buf[0], more ? table : ntable, more ? head_off : nhead_off, more ? t_last : nt_last,
-                      more ? t_begin + (j + 2) * TILE : nt0);
+                      more ? t_begin + (j + 2) * TILE : nt0, more ? Lm1 : nL - 1, more ? new_off_k : nnew_off_k,
+                      more ? new_off_v : nnew_off_v);
             if (j + 1 <= j_last) compute_tile(buf[1], j + 1);
         }
 

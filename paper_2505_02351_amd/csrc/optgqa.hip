@@ -29,6 +29,23 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? OPTGQA_OK : OPTGQA_ERR_LAUNCH;
 }
 
+// Profiling aid (optgqa_set_kernel_events): events recorded around the launch of the kernel that
+// streams the KV cache, per calling thread.
+thread_local hipEvent_t g_event_start = nullptr;
+thread_local hipEvent_t g_event_stop = nullptr;
+
+struct KernelEvents {
+    hipStream_t st;
+    explicit KernelEvents(hipStream_t s) : st(s)
+    {
+        if (g_event_start) (void)hipEventRecord(g_event_start, st);
+    }
+    ~KernelEvents()
+    {
+        if (g_event_stop) (void)hipEventRecord(g_event_stop, st);
+    }
+};
+
 // Number of query heads one workgroup serves from a single pass over its K/V tiles; always a
 // divisor of the group size.  head_dim 128 uses the matrix-core kernel, whose score tile has
 // 16 rows: the largest divisor <= 16.  head_dim 64: the largest of 8, 4, 2, 1.
@@ -180,7 +197,11 @@ int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
         const int rows = num_rows - first < kMaxRowsPerLaunch ? num_rows - first : kMaxRowsPerLaunch;
         p.row_offset = first;
         const dim3 grid(p.num_partitions, p.num_kv_heads * (group / gh), rows);
-        int rc = launch_decode_gh<DT, D>(p, gh, grid, st);
+        int rc;
+        {
+            KernelEvents ev(st);
+            rc = launch_decode_gh<DT, D>(p, gh, grid, st);
+        }
         if (rc != OPTGQA_OK) return rc;
         if (p.num_partitions == 1) continue;
         constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
@@ -203,12 +224,12 @@ int launch_decode_any(int dtype, int head_dim, A... args)
 // Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
 // the device keeps resident at once, because a unit that has to wait for a free slot would start
 // when every other unit is nearly done.
-template <int DT>
+template <int DT, bool FUSED>
 int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 {
     static const int resident = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT>, kDecodeWaves * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED>, kDecodeWaves * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -219,7 +240,10 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     const int group = p.num_heads / p.num_kv_heads;
     p.heads_per_wg = heads_per_workgroup(group, 128);
     p.num_units = workgroups * kDecodeWaves;
-    hipLaunchKernelGGL((paged_decode_flat_kernel<DT>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+    {
+        KernelEvents ev(st);
+        hipLaunchKernelGGL((paged_decode_flat_kernel<DT, FUSED>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+    }
     int rc = launch_status();
     if (rc != OPTGQA_OK) return rc;
     constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
@@ -230,8 +254,11 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 
 int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st)
 {
-    return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16>(p, workgroups, st)
-                               : launch_decode_flat_dt<kBF16>(p, workgroups, st);
+    if (p.k_new)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, true>(p, workgroups, st);
+    return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false>(p, workgroups, st)
+                               : launch_decode_flat_dt<kBF16, false>(p, workgroups, st);
 }
 
 // Row-wise prefill: every new query token is handled like a decode row whose context ends at
@@ -261,6 +288,9 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     p.row_offset = 0;
     p.plan = nullptr;
     p.num_units = p.segs_per_seq = 0;
+    p.k_new = p.v_new = nullptr;
+    p.k_cache_w = p.v_cache_w = nullptr;
+    p.k_new_stride = p.v_new_stride = 0;
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
@@ -285,6 +315,7 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const int64_t blocks = (int64_t)((p.units + 7) / 8) * 8 * p.q_tiles;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
+    KernelEvents ev(st);
     if (dtype == OPTGQA_F16)
         hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16>), grid, block, 0, st, p);
     else
@@ -297,6 +328,14 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
 extern "C" {
 
 int optgqa_abi_version(void) { return kAbiVersion; }
+
+int optgqa_set_kernel_events(void* start_event, void* stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return OPTGQA_ERR_NULL;
+    g_event_start = static_cast<hipEvent_t>(start_event);
+    g_event_stop = static_cast<hipEvent_t>(stop_event);
+    return OPTGQA_OK;
+}
 
 const char* optgqa_status_string(int status)
 {
@@ -362,12 +401,50 @@ size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int n
     return s.bytes;
 }
 
-int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
-                           const int32_t* block_tables, const int32_t* context_lens,
-                           const float* alibi_slopes, float scale, int num_seqs, int num_heads,
-                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                           int max_context_len, int partition_size, void* workspace,
-                           size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+}  // extern "C"
+
+namespace {
+
+// New-token inputs of a fused decode step (all null / zero for plain attention).
+struct StepInputs {
+    const void* k_new;
+    const void* v_new;
+    int64_t k_stride, v_stride;
+    void* k_cache_w;
+    void* v_cache_w;
+};
+
+int write_new_tokens(const StepInputs& n, const int64_t* slot_mapping, const int32_t* block_tables,
+                     const int32_t* context_lens, int num_tokens, int num_kv_heads, int head_dim, int block_size,
+                     int max_blocks_per_seq, hipStream_t st)
+{
+    const bool wide = aligned16(n.k_new) && aligned16(n.v_new) && aligned16(n.k_cache_w) && aligned16(n.v_cache_w) &&
+                      n.k_stride % 8 == 0 && n.v_stride % 8 == 0;
+    const int elems = wide ? 8 : 1;
+    const int64_t threads = (int64_t)num_tokens * num_kv_heads * (head_dim / elems) * 2;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+    auto kk = static_cast<const uint16_t*>(n.k_new);
+    auto vv = static_cast<const uint16_t*>(n.v_new);
+    auto kc = static_cast<uint16_t*>(n.k_cache_w);
+    auto vc = static_cast<uint16_t*>(n.v_cache_w);
+    if (wide)
+        hipLaunchKernelGGL((reshape_and_cache_kernel<uint4>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
+                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, n.k_stride,
+                           n.v_stride, block_tables, context_lens, max_blocks_per_seq);
+    else
+        hipLaunchKernelGGL((reshape_and_cache_kernel<uint16_t>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv,
+                           kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, n.k_stride,
+                           n.v_stride, block_tables, context_lens, max_blocks_per_seq);
+    return launch_status();
+}
+
+// Decode attention, optionally preceded by (or fused with) the step's cache write.
+int attention_impl(void* out, const void* q, const void* k_cache, const void* v_cache,
+                   const int32_t* block_tables, const int32_t* context_lens, const float* alibi_slopes,
+                   float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                   int max_blocks_per_seq, int max_context_len, int partition_size, void* workspace,
+                   size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step)
 {
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_context_len < 0)
@@ -376,9 +453,16 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
     if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
     if (partition_size > 0 && (partition_size % block_size || partition_size % 16)) return OPTGQA_ERR_SHAPE;
+    if (step) {
+        const int64_t row = (int64_t)num_kv_heads * head_dim;
+        if (step->k_stride < row || step->v_stride < row) return OPTGQA_ERR_SHAPE;
+    }
     if (num_seqs == 0) return OPTGQA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens) return OPTGQA_ERR_NULL;
+    if (step && (!step->k_new || !step->v_new)) return OPTGQA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
+    if (step && ((reinterpret_cast<uintptr_t>(step->k_new) | reinterpret_cast<uintptr_t>(step->v_new)) & 1u))
+        return OPTGQA_ERR_UNSUPPORTED;
     if (num_heads > 65535) return OPTGQA_ERR_SHAPE;
 
     SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
@@ -409,6 +493,23 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
     p.cu_q_lens = nullptr;
     p.num_seqs = num_seqs;
     p.row_offset = 0;
+    p.k_new = p.v_new = nullptr;
+    p.k_cache_w = p.v_cache_w = nullptr;
+    p.k_new_stride = p.v_new_stride = 0;
+
+    // The cache write rides inside the equal-work kernel when that kernel runs and the new rows
+    // can be moved as 16-byte pieces; otherwise it is a launch of its own ahead of the attention.
+    bool fused = false;
+    if (step) {
+        fused = s.partition_size == OPTGQA_SPLIT_BALANCED && aligned16(step->k_new) && aligned16(step->v_new) &&
+                step->k_stride % 8 == 0 && step->v_stride % 8 == 0;
+        if (!fused) {
+            const int rc = write_new_tokens(*step, nullptr, block_tables, context_lens, num_seqs, num_kv_heads,
+                                            head_dim, block_size, max_blocks_per_seq, st);
+            if (rc != OPTGQA_OK) return rc;
+        }
+    }
+
     if (s.partition_size == OPTGQA_SPLIT_BALANCED) {
         p.plan = static_cast<int32_t*>(workspace);
         p.ws_m = static_cast<float*>(workspace) + s.plan_floats;
@@ -417,11 +518,19 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
         p.partition_size = 1 << 30;
         p.num_partitions = 1;
         p.segs_per_seq = s.segs_per_seq;
+        if (fused) {
+            p.k_new = step->k_new;
+            p.v_new = step->v_new;
+            p.k_new_stride = step->k_stride;
+            p.v_new_stride = step->v_stride;
+            p.k_cache_w = step->k_cache_w;
+            p.v_cache_w = step->v_cache_w;
+        }
 #ifdef OPTGQA_FLAT_TIMING
         p.timing = workspace_bytes >= s.bytes + (size_t)s.workgroups * kDecodeWaves * 32
                        ? reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + s.bytes) : nullptr;
 #endif
-        return launch_decode_flat((int)dtype, p, s.workgroups, static_cast<hipStream_t>(stream));
+        return launch_decode_flat(dtype, p, s.workgroups, st);
     }
     p.plan = nullptr;
     p.num_units = p.segs_per_seq = 0;
@@ -437,7 +546,37 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
         p.partition_size = 1 << 30;
         p.num_partitions = 1;
     }
-    return launch_decode_any((int)dtype, head_dim, p, num_seqs, static_cast<hipStream_t>(stream));
+    return launch_decode_any(dtype, head_dim, p, num_seqs, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* block_tables, const int32_t* context_lens,
+                           const float* alibi_slopes, float scale, int num_seqs, int num_heads,
+                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                           int max_context_len, int partition_size, void* workspace,
+                           size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          partition_size, workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream),
+                          nullptr);
+}
+
+int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                       void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                       const float* alibi_slopes, float scale, int num_seqs, int num_heads,
+                       int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                       int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
+                       void* workspace, size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len, 0,
+                          workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream), &step);
 }
 
 int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const void* v_cache,

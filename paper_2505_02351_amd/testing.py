@@ -60,6 +60,15 @@ class DevCase:
         torch.cuda.synchronize()
         return to_host(self.out)
 
+    def step(self, workspace="auto"):
+        """Cache write + decode attention through the single-call entry point."""
+        ws = self.workspace(0)[0] if isinstance(workspace, str) else workspace
+        self.out.fill_(float("nan"))
+        G.decode_step(self.out, self.q, self.k_new, self.v_new, self.k_cache, self.v_cache, self.block_tables,
+                      self.context_lens, self.slopes, float(self.case.scale), self.case.max_context_len, ws)
+        torch.cuda.synchronize()
+        return to_host(self.out)
+
     def prefill(self):
         self.out.fill_(float("nan"))
         G.paged_prefill(self.out, self.q, self.k_cache, self.v_cache, self.block_tables, self.context_lens,

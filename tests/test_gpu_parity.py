@@ -310,6 +310,78 @@ def test_decode_balanced_rejects_head_dim_64(U):
         dev.decode(partition_size=BALANCED, workspace=torch.empty(1 << 20, dtype=torch.float32, device="cuda"))
 
 
+# ------------------------------------------------------------------ decode step in one call
+@pytest.mark.parametrize("i", range(len(SWEEP)))
+def test_decode_step_sweep(U, oracle, i):
+    """optgqa_decode_step = cache write + attention: caches bit-exact, output within tolerance.
+    head_dim 128 shapes with a long enough context take the fused kernel, the others the
+    library's two-launch path."""
+    dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
+    cfg = W.small_config(name=f"step{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
+                         ctx_hi=hi, seed=700 + i)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    got = dev.step()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    ref = oracle_decode(oracle, case, kc, vc)
+    assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype]
+    # without a workspace the library must still do both halves (unsplit kernels)
+    dev2 = U.DevCase(case)
+    got2 = dev2.step(workspace=None)
+    assert np.array_equal(U.to_host(dev2.k_cache), kc) and np.array_equal(U.to_host(dev2.v_cache), vc)
+    assert U.max_abs_err(got2, ref, dtype) <= U.TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_decode_step_edge_lengths(U, oracle, dtype):
+    """The new token is the only one (L = 1), first / last row of a block, last token of a full
+    tile, and absent (L = 0: nothing written, +0 out) - all in one fused launch."""
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1, 0, 300], np.int32)
+    cfg = W.small_config(name="step_edges", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=200, ctx_lo=1, ctx_hi=512, seed=421)
+    case = W.make_case(cfg, context_lens=lens)
+    full = lambda a, shape: (lambda z: (z.__setitem__(lens > 0, a), z)[1])(np.zeros(shape, np.uint16))
+    q_full = full(case.q, (len(lens), 8, 128))
+    k_full = full(case.k_new, (len(lens), 2, 128))
+    v_full = full(case.v_new, (len(lens), 2, 128))
+    kc, vc = oracle_filled(oracle, case)
+    case.q = q_full
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    dev.k_new, dev.v_new = U.to_dev(k_full, dtype), U.to_dev(v_full, dtype)
+    got = dev.step()
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert not got[lens == 0].any()
+    assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype]
+    for b in (1, 12):                       # one-token context: the new V row, bit for bit
+        for h in range(8):
+            assert np.array_equal(got[b, h], v_full[b, h // 4])
+
+
+def test_decode_step_strided_new_rows(U, oracle):
+    """k_new / v_new as slices of a wider buffer: a stride that keeps 16-byte pieces (fused) and an
+    odd one (separate narrow cache write); both must land the same bits."""
+    import torch
+    cfg = W.small_config(name="step_stride", dtype=W.BF16, batch=6, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=32, num_blocks=6 * 20 + 3, ctx_lo=200, ctx_hi=600, seed=43)
+    case = W.make_case(cfg)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    for pad in (64, 3):
+        dev = U.DevCase(case)
+        wide_k = torch.zeros(6, 4 * 128 + pad, dtype=torch.bfloat16, device="cuda")
+        wide_v = torch.zeros(6, 4 * 128 + pad, dtype=torch.bfloat16, device="cuda")
+        wide_k[:, :512] = dev.k_new.reshape(6, 512)
+        wide_v[:, :512] = dev.v_new.reshape(6, 512)
+        dev.k_new = wide_k[:, :512].unflatten(1, (4, 128))
+        dev.v_new = wide_v[:, :512].unflatten(1, (4, 128))
+        got = dev.step()
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), pad
+        assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+
+
 # ------------------------------------------------------------------ the workloads themselves
 @pytest.mark.parametrize("name", ["C1", "C2"])
 def test_decode_workload_full(U, oracle, name):
@@ -325,7 +397,7 @@ def test_decode_workload_full(U, oracle, name):
         assert err <= U.TOL[case.dtype], (name, partition, err)
 
 
-@pytest.mark.parametrize("name,partition", [("C3", None), ("C4", None), ("C4", BALANCED), ("C3", 1024)])
+@pytest.mark.parametrize("name,partition", [("C3", None), ("C4", None), ("C4", BALANCED), ("C3", 1024), ("C3", "step")])
 def test_decode_workload_sampled(U, oracle, name, partition):
     """Full-size batch in the launch configuration the bench times (and in the other split mode);
     the oracle evaluates a sample of (sequence, head) rows one by one, chosen to include the
@@ -334,7 +406,11 @@ def test_decode_workload_sampled(U, oracle, name, partition):
     case = W.make_case(cfg)
     dev = U.DevCase(case)
     dev.write_cache()
-    got = dev.decode(partition_size=cfg.partition_size if partition is None else partition)
+    if partition == "step":
+        dev = U.DevCase(case)           # caches still without the new tokens
+        got = dev.step()
+    else:
+        got = dev.decode(partition_size=cfg.partition_size if partition is None else partition)
     assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
     kc, vc = oracle_filled(oracle, case)
     rng = np.random.default_rng(99)
