@@ -39,8 +39,8 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
 # factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
 # measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/paged_decode_C3.md: (311412.3 KiB FETCH_SIZE x 2.000 + 5994.2 KiB WRITE_SIZE x 1.000) x 1024
-    "C3": 643910451,
+    # profiles/paged_decode_C3.md: (310526.8 KiB FETCH_SIZE x 2.000 + 5372.0 KiB WRITE_SIZE x 1.000) x 1024
+    "C3": 641459814,
 }
 
 
