@@ -268,6 +268,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         reinterpret_cast<float4*>(&p_lds[wave][0][0])[lane] = make_float4(0.f, 0.f, 0.f, 0.f);
 
         auto compute_tile = [&](const MmaTile& Tl, int j) __attribute__((always_inline)) {
+#if defined(OPTGQA_FLAT_ABLATE) && OPTGQA_FLAT_ABLATE == 1
+            // development only: consume the loads without arithmetic
+            uint32_t x = 0;
+            for (int i = 0; i < 4; ++i) x ^= Tl.k[i].x ^ Tl.k[i].y ^ Tl.k[i].z ^ Tl.k[i].w ^ Tl.v[i].x ^ Tl.v[i].y ^ Tl.v[i].z ^ Tl.v[i].w;
+            acc[0][0] += __uint_as_float(x & 0x3fffffffu);
+            l[0] += (float)j;
+            return;
+#endif
             f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < 4; ++i) S = mfma_qk<DT>(qa[i], Tl.k[i], S);

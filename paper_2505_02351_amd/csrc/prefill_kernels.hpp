@@ -13,9 +13,12 @@
 //                              halves of the tile: 8 weights that pack straight into ...
 //   O^T[dim][row] += V^T P^T   ... the B operand of the second v_mfma_f32_16x16x32, whose
 //                              contraction index runs over the tile's keys in exactly that
-//                              (permuted) order.  A = V^T from LDS; V is transposed once per tile
-//                              when it is written to LDS (4 keys x 8 dims per loader thread,
-//                              interleaved with byte permutes, stored key-permuted), not per wave.
+//                              (permuted) order.  A = V^T: V lies in LDS in its natural [key][dim]
+//                              layout and is read with the LDS transpose load (ds_read_b64_tr_b16:
+//                              inside each group of 16 lanes, lane i receives element i % 4 of the
+//                              8-byte chunks addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4),
+//                              so that lane (dim i, slab q) ends up with keys 4q .. 4q+3 of dim i
+//                              from one instruction and keys 16 + 4q .. from a second one.
 // Scores, sums and the output accumulate in fp32.  For the second contraction the softmax
 // weights must become 2-byte values:
 //   fp16: one rounding (11 significant bits); the lazily moved reference of the exponentials (see
@@ -54,7 +57,8 @@ constexpr int kPfRowBlocks = 2;                          // 16-row blocks per wa
 constexpr int kPfRows = kPfWaves * kPfRowBlocks * 16;    // (token, head) rows per workgroup
 constexpr int kPfKeys = 32;                              // keys per tile
 constexpr int kPfKRow = 128 + 8;                         // LDS K row, elements (padding spreads banks)
-constexpr int kPfVRow = kPfKeys + 8;                     // LDS V^T row, elements
+constexpr int kPfVRow = 128 + 16;                        // LDS V row, elements: 288 bytes, so that the 8 rows a
+                                                         // transpose load touches per pass cover all 64 banks
 
 template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow2<DT>(lo, hi); }
 
@@ -73,8 +77,9 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
 {
     constexpr int D = 128;
     constexpr int RB = kPfRowBlocks;
-    __shared__ __attribute__((aligned(16))) uint16_t k_lds[2][kPfKeys][kPfKRow];
-    __shared__ __attribute__((aligned(16))) uint16_t vt_lds[2][D][kPfVRow];
+    // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
+    constexpr int kKTile = kPfKeys * kPfKRow, kBuf = kKTile + kPfKeys * kPfVRow;
+    __shared__ __attribute__((aligned(16))) uint16_t tile_lds[2 * kBuf];
 
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
@@ -146,66 +151,42 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) acc[rb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- tile staging: threads 0..127 fetch K (key tid/4, 64 bytes), 128..255 fetch and
-    // transpose V (4 keys x 8 dims each) -------------------------------------------------------
+    // ---- tile staging: threads 0..127 fetch K, 128..255 fetch V; either way a thread moves the
+    // same 16-byte column piece of 4 consecutive keys (16 lanes cover one 256-byte row) ------------
     const bool k_loader = tid < 128;
     const int ld = k_loader ? tid : tid - 128;
-    const int lk_key = ld >> 2, lk_piece = ld & 3;               // K: key 0..31, dims 32*piece ..
-    const int lv_group = ld >> 4, lv_chunk = ld & 15;            // V: keys 4*group .. +3, dims 8*chunk ..
-    // key-permuted position of V's key group inside the LDS row (see the header comment)
-    const int lv_pos = lv_group < 4 ? 8 * lv_group : 8 * (lv_group - 4) + 4;
-    // Two register stages (tile t lives in stage t & 1) keep two tiles in flight behind the one
-    // being computed; the block id of the next tile to fetch is read one fetch earlier, so a fetch
-    // never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
+    const int l_group = ld >> 4, l_chunk = ld & 15;              // keys 4*group .. +3, dims 8*chunk ..
+    const uint16_t* __restrict__ l_src = k_loader ? kc : vc;
+    const int l_pitch = k_loader ? kPfKRow : kPfVRow;
+    const int l_dst = (k_loader ? 0 : kKTile) + 4 * l_group * l_pitch + 8 * l_chunk;
+    // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
+    // tile t + 2 is on its way to registers; the block id of the next tile to fetch is read one
+    // fetch earlier, so a fetch never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
     // no branches around loads, which keeps the compiler's load counting exact.
-    uint4 stage_a[4], stage_b[4];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: plain loads and stores
+    u32x4 stage[4];
     const int last_tile = ntiles - 1;
-    auto load_blk = [&](int t) {
-        const int key = min(min(t, last_tile) * kPfKeys + (k_loader ? lk_key : 4 * lv_group), kmax - 1);
+    auto load_blk = [&](int t) __attribute__((always_inline)) {
+        // the four keys of a group share a block (groups are 4-aligned, clamping keeps the block)
+        const int key = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
         return table[key >> bs_shift];
     };
     int blk_next = load_blk(0);
 
-    auto fetch_tile = [&](uint4 (&stage)[4], int t) __attribute__((always_inline)) {
-        const int key0 = min(t, last_tile) * kPfKeys;
-        const int64_t blk = blk_next;
-        if (k_loader) {
-            const int key = min(key0 + lk_key, kmax - 1);
-            const uint16_t* src = kc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 32 * lk_piece;
+    auto fetch_tile = [&](u32x4 (&stage)[4], int t) __attribute__((always_inline)) {
+        const int key0 = min(t, last_tile) * kPfKeys + 4 * l_group;
+        const uint16_t* src = l_src + blk_next * block_stride + 8 * l_chunk;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) stage[j] = *reinterpret_cast<const uint4*>(src + 8 * j);
-        } else {
-            // the four keys of the group share a block (groups are 4-aligned, clamping keeps the block)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = min(key0 + 4 * lv_group + j, kmax - 1);
-                stage[j] = *reinterpret_cast<const uint4*>(vc + blk * block_stride + (int64_t)(key & (bs - 1)) * D + 8 * lv_chunk);
-            }
+        for (int j = 0; j < 4; ++j) {
+            const int key = min(key0 + j, kmax - 1);
+            stage[j] = *reinterpret_cast<const u32x4*>(src + (int64_t)(key & (bs - 1)) * D);
         }
         blk_next = load_blk(t + 1);
     };
-    auto store_tile = [&](const uint4 (&stage)[4], int buf) __attribute__((always_inline)) {
-        if (k_loader) {
+    auto store_tile = [&](const u32x4 (&stage)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<uint4*>(&k_lds[buf][lk_key][32 * lk_piece + 8 * j]) = stage[j];
-        } else {
-            // stage[j] = key j, 8 dims as 4 dwords (dim pairs).  For dim pair w: interleave the four keys.
-            const uint32_t r[4][4] = {{stage[0].x, stage[0].y, stage[0].z, stage[0].w},
-                                      {stage[1].x, stage[1].y, stage[1].z, stage[1].w},
-                                      {stage[2].x, stage[2].y, stage[2].z, stage[2].w},
-                                      {stage[3].x, stage[3].y, stage[3].z, stage[3].w}};
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) {
-                // even dim: low halves of keys (0,1) and (2,3); odd dim: high halves
-                const uint32_t e01 = __builtin_amdgcn_perm(r[1][w2], r[0][w2], 0x05040100u);
-                const uint32_t e23 = __builtin_amdgcn_perm(r[3][w2], r[2][w2], 0x05040100u);
-                const uint32_t o01 = __builtin_amdgcn_perm(r[1][w2], r[0][w2], 0x07060302u);
-                const uint32_t o23 = __builtin_amdgcn_perm(r[3][w2], r[2][w2], 0x07060302u);
-                *reinterpret_cast<uint2*>(&vt_lds[buf][8 * lv_chunk + 2 * w2][lv_pos]) = make_uint2(e01, e23);
-                *reinterpret_cast<uint2*>(&vt_lds[buf][8 * lv_chunk + 2 * w2 + 1][lv_pos]) = make_uint2(o01, o23);
-            }
-        }
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<u32x4*>(&tile_lds[buf * kBuf + l_dst + j * l_pitch]) = stage[j];
     };
 
     const float scale2 = p.scale2;
@@ -219,7 +200,8 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
         for (int half = 0; half < 2; ++half)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const uint4 ka = *reinterpret_cast<const uint4*>(&k_lds[buf][16 * half + n16][32 * i + 8 * hg]);
+                const uint4 ka = *reinterpret_cast<const uint4*>(
+                    &tile_lds[buf * kBuf + (16 * half + n16) * kPfKRow + 32 * i + 8 * hg]);
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb) st[rb][half] = mfma_qk<DT>(ka, qb[rb][i], st[rb][half]);
             }
@@ -278,9 +260,15 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
         }
 
         // ---- O^T += V^T P^T ---------------------------------------------------------------------
+        typedef short i16x4 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
+        const uint16_t* vrow = &tile_lds[buf * kBuf + kKTile + (4 * hg + (n16 >> 2)) * kPfVRow + 4 * (n16 & 3)];
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            const uint4 va = *reinterpret_cast<const uint4*>(&vt_lds[buf][16 * dt + n16][8 * hg]);
+            const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * dt));
+            const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * kPfVRow + 16 * dt));
+            const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+            const uint4 va = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
                 acc[rb][dt] = mfma_qk<DT>(va, make_uint4(pk[rb][0], pk[rb][1], pk[rb][2], pk[rb][3]), acc[rb][dt]);
@@ -293,34 +281,23 @@ __global__ __launch_bounds__(kPfWaves * 64, 2) void paged_prefill_mma_kernel(con
 
     const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
 
-    fetch_tile(stage_a, 0);
-    store_tile(stage_a, 0);
-    fetch_tile(stage_b, 1);
-    fetch_tile(stage_a, 2);
+    fetch_tile(stage, 0);
+    store_tile(stage, 0);
+    fetch_tile(stage, 1);
     __syncthreads();
     // Tiles below the diagonal of every row first (no mask), then the few that touch it.
     const int n_unmasked = min(ntiles, max(0, (pos_min + 1) / kPfKeys));
     int kt = 0;
     for (; kt < n_unmasked; ++kt) {
         compute_tile(kt, kt & 1, std::false_type{});
-        if (kt & 1) {
-            if (kt + 1 < ntiles) store_tile(stage_a, 0);
-            fetch_tile(stage_a, kt + 3);
-        } else {
-            if (kt + 1 < ntiles) store_tile(stage_b, 1);
-            fetch_tile(stage_b, kt + 3);
-        }
+        if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
+        fetch_tile(stage, kt + 2);
         __syncthreads();
     }
     for (; kt < ntiles; ++kt) {
         compute_tile(kt, kt & 1, std::true_type{});
-        if (kt & 1) {
-            if (kt + 1 < ntiles) store_tile(stage_a, 0);
-            fetch_tile(stage_a, kt + 3);
-        } else {
-            if (kt + 1 < ntiles) store_tile(stage_b, 1);
-            fetch_tile(stage_b, kt + 3);
-        }
+        if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
+        fetch_tile(stage, kt + 2);
         __syncthreads();
     }
 
