@@ -16,7 +16,9 @@ divided by the wall-clock time of a step, over K steps timed without any event i
 events that the library records around that kernel's launch (optgqa_set_kernel_events) in a
 second pass of K steps: HBM-bound for decode (8 TB/s peak), MFMA-bound for the tiled prefill
 (2.5 PFLOP/s dense bf16/fp16).  `cpu_baseline` times the fp64 CPU oracle on a bounded sample
-of the same batch.
+of the same batch.  With the default workload (C3, drawn context lengths) a `target_check`
+object adds the same measurement for C3-all8k - the batch with every context at 8192 tokens,
+which is how the target ("batch 64 / 8k context") is worded.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--partition-size P]
 """
@@ -57,6 +59,8 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB five times "
                          "(known traffic, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--no-target-check", action="store_true",
+                    help="skip the extra C3-all8k measurement (every context 8192: the 'batch 64 / 8k' case)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
     return ap.parse_args()
@@ -130,101 +134,116 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    cfg = W.CONFIGS[args.workload]
-    case = W.make_case(cfg)
-    from paper_2505_02351_amd.testing import DevCase
-    dev = DevCase(case)
-    P = cfg.partition_size if args.partition_size is None else args.partition_size
-    decode = cfg.kind == "decode"
-    ws, chosen_P = dev.workspace(P) if decode else (None, 0)
-    max_ctx = case.max_context_len
-    scale = float(case.scale)
-    stream = torch.cuda.current_stream()
+    def measure(workload: str, steps: int, warmup: int):
+        """Runs one workload; returns (result dict, case)."""
+        cfg = W.CONFIGS[workload]
+        case = W.make_case(cfg)
+        from paper_2505_02351_amd.testing import DevCase
+        dev = DevCase(case)
+        P = cfg.partition_size if args.partition_size is None else args.partition_size
+        decode = cfg.kind == "decode"
+        ws, chosen_P = dev.workspace(P) if decode else (None, 0)
+        max_ctx = case.max_context_len
+        scale = float(case.scale)
+        stream = torch.cuda.current_stream()
 
-    one_call = decode and P == 0
+        one_call = decode and P == 0
 
-    def step():
-        if one_call:
-            G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
-                          dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
-            return
-        G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
+        def step():
+            if one_call:
+                G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                              dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
+                return
+            G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
+            if decode:
+                G.paged_attention(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                                  dev.slopes, scale, max_ctx, P, ws, stream)
+            else:
+                G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                                dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+
+        # ---- pass 1: K steps, wall clock, nothing but the step's own launches in the stream -------
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+
+        # ---- pass 2: the same K steps with an event pair around the dominant kernel of each --------
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        for e in starts + stops:
+            e.record(stream)                      # makes torch create the HIP event behind it
+        torch.cuda.synchronize()
+        for i in range(steps):
+            G.set_kernel_events(starts[i], stops[i])
+            step()
+        G.set_kernel_events(None, None)
+        torch.cuda.synchronize()
+        kernel_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
+
+        ms_per_step = wall * 1e3 / steps
+        kv_bytes = case.kv_bytes()
+        value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+        n_q = case.num_tokens
+        launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
+                     "min": float(kernel_ms.min()), "p90": float(np.percentile(kernel_ms, 90))}
         if decode:
-            G.paged_attention(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
-                              dev.slopes, scale, max_ctx, P, ws, stream)
+            achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
+            if chosen_P == G.SPLIT_BALANCED:
+                kname = "paged_decode_flat_kernel (equal-work split%s)" % (", cache write fused" if one_call else "")
+            else:
+                kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
+            roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": achieved / HBM_PEAK_GBS,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None else None,
+                        "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
         else:
-            G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
-                            dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
+            # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
+            # (query, key, head) each
+            flops = 0
+            for b in range(cfg.batch):
+                n_b = int(case.q_lens[b])
+                first = int(case.context_lens[b]) - n_b
+                flops += 4 * cfg.num_heads * cfg.head_dim * (n_b * first + n_b * (n_b + 1) // 2)
+            achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
+                        "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
+                        "launch_ms": launch_ms}
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+        result = {
+            "metric": "paged GQA+ALiBi decode: KV-read HBM GB/s (% of peak) and query tokens/s",
+            "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": case.dtype, "data": "synthetic",
+            "config": {"workload": cfg.name, "kind": cfg.kind, "batch": cfg.batch, "num_heads": cfg.num_heads,
+                       "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
+                       "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
+                       "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
+                       "calls_per_step": 1 if one_call else 2},
+            "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+            "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
+            "roofline": roofline,
+        }
+        return result, case
 
-    # ---- pass 1: K steps, wall clock, nothing but the step's own launches in the stream -------
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    # ---- pass 2: the same K steps with an event pair around the dominant kernel of each --------
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    for e in starts + stops:
-        e.record(stream)                      # makes torch create the HIP event behind it
-    torch.cuda.synchronize()
-    for i in range(args.steps):
-        G.set_kernel_events(starts[i], stops[i])
-        step()
-    G.set_kernel_events(None, None)
-    torch.cuda.synchronize()
-    kernel_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
-
-    ms_per_step = wall * 1e3 / args.steps
-    kv_bytes = case.kv_bytes()
-    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
-    n_q = case.num_tokens
-    launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
-                 "min": float(kernel_ms.min()), "p90": float(np.percentile(kernel_ms, 90))}
-    if decode:
-        achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
-        if chosen_P == G.SPLIT_BALANCED:
-            kname = "paged_decode_flat_kernel (equal-work split%s)" % (", cache write fused" if one_call else "")
-        else:
-            kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
-        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None else None,
-                    "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
-    else:
-        # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
-        # (query, key, head) each
-        flops = 0
-        for b in range(cfg.batch):
-            n_b = int(case.q_lens[b])
-            first = int(case.context_lens[b]) - n_b
-            flops += 4 * cfg.num_heads * cfg.head_dim * (n_b * first + n_b * (n_b + 1) // 2)
-        achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
-                    "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
-                    "launch_ms": launch_ms}
-
-    result = {
-        "metric": "paged GQA+ALiBi decode: KV-read HBM GB/s (% of peak) and query tokens/s",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": case.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "kind": cfg.kind, "batch": cfg.batch, "num_heads": cfg.num_heads,
-                   "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
-                   "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
-                   "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
-                   "calls_per_step": 1 if one_call else 2},
-        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
-        "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
-        "roofline": roofline,
-    }
+    result, case = measure(args.workload, args.steps, args.warmup)
+    if args.workload == "C3" and args.partition_size is None and not args.no_target_check:
+        # the target is worded "batch 64 / 8k context": the same batch with every context at 8192
+        extra, _ = measure("C3-all8k", max(args.steps // 2, 1), max(args.warmup // 2, 1))
+        result["target_check"] = {
+            "workload": "C3-all8k", "what": "same batch with every context length 8192",
+            "value": extra["value"], "unit": "GB/s", "pct_of_hbm_peak": extra["pct_of_hbm_peak"],
+            "ms_per_step": extra["ms_per_step"], "steps": extra["steps"],
+            "roofline_frac": extra["roofline"]["frac"], "kernel_ms": extra["roofline"]["launch_ms"]["mean"],
+            "kv_bytes": extra["config"]["kv_bytes"],
+        }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(case, W, args.cpu_sample_seqs)
     print(json.dumps(result))
