@@ -16,17 +16,19 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "optgqa_oracle.c")
+_SRC_E4M3 = os.path.join(_HERE, "optgqa_oracle_e4m3.c")        # 8-bit KV-cache variant
 _LIB = os.path.join(_HERE, "liboptgqa_oracle.so")
 
 DTYPES = {"f16": 0, "bf16": 1}
 
 
-def build(src: str = _SRC, out: str = _LIB, force: bool = True) -> str:
+def build(src: str = _SRC, out: str = _LIB, force: bool = True, src_e4m3: str = _SRC_E4M3) -> str:
     """Compile the oracle with gcc (OpenMP over independent (sequence, head) rows)."""
-    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+    newest = max(os.path.getmtime(src), os.path.getmtime(src_e4m3))
+    if force or not os.path.exists(out) or os.path.getmtime(out) < newest:
         tmp = out + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
-                               "-ffp-contract=off", "-o", tmp, src, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, src, src_e4m3, "-lm"])
         os.replace(tmp, out)
     return out
 
@@ -157,4 +159,67 @@ def paged_prefill(q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, sl
                                   ctypes.c_float(scale), ctypes.c_int(B), ctypes.c_int(Hq),
                                   ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
                                   ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# 8-bit (E4M3) KV-cache variant: optgqa_oracle_e4m3.c
+# ---------------------------------------------------------------------------------------------
+def e4m3_values(lib=None) -> np.ndarray:
+    """Value of each of the 256 codes (fp64; the two NaN codes give NaN)."""
+    lib = lib or _get()
+    out = np.zeros(256, dtype=np.float64)
+    lib.oracle_e4m3_values(_p(out))
+    return out
+
+
+def e4m3_nearest(x, lib=None) -> np.ndarray:
+    """Nearest code (ties to even, saturating at +-448, NaN -> 0x7f) of each float32."""
+    lib = lib or _get()
+    x = _c(x, np.float32).ravel()
+    out = np.zeros(x.shape[0], dtype=np.uint8)
+    lib.oracle_e4m3_nearest(_p(x), ctypes.c_int(x.shape[0]), _p(out))
+    return out
+
+
+def reshape_and_cache_e4m3(k, v, k_cache, v_cache, slot_mapping, k_scale, v_scale, dtype, lib=None) -> None:
+    """Quantising cache write, in place on k_cache / v_cache (uint8 [NB, Hkv, bs, D])."""
+    lib = lib or _get()
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    k, v = _c(k, np.uint16), _c(v, np.uint16)
+    slots = _c(slot_mapping, np.int64)
+    NB, Hkv, bs, D = k_cache.shape
+    stride = Hkv * D
+    lib.oracle_reshape_and_cache_e4m3(_p(k), _p(v), _p(k_cache), _p(v_cache), _p(slots),
+                                      ctypes.c_int(slots.shape[0]), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                      ctypes.c_int(bs), ctypes.c_int64(stride), ctypes.c_int64(stride),
+                                      ctypes.c_float(k_scale), ctypes.c_float(v_scale),
+                                      ctypes.c_int(DTYPES[dtype]))
+
+
+def paged_attention_e4m3(q, k_cache, v_cache, block_tables, context_lens, slopes, scale, k_scale, v_scale,
+                         dtype, rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Decode attention over an E4M3 cache in fp64: [B, Hq, D], or [n_rows, D] for listed
+    (sequence, head) pairs."""
+    lib = lib or _get()
+    q = _c(q, np.uint16)
+    bt, cl = _c(block_tables, np.int32), _c(context_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    NB, Hkv, bs, D = k_cache.shape
+    B, Hq, _ = q.shape
+    if rows is None:
+        n, rs, rh = B * Hq, None, None
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rs, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_attention_e4m3(_p(out), _p(rs), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                    _p(bt), _p(cl), _p(sl), ctypes.c_float(scale), ctypes.c_float(k_scale),
+                                    ctypes.c_float(v_scale), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+                                    ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
+                                    ctypes.c_int(DTYPES[dtype]))
     return out
