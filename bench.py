@@ -37,6 +37,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
+KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-448 covers +-5.6 sigma
 # HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
 # measured for the workload.
@@ -59,11 +60,41 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run a plain device copy of MIB MiB five times "
                          "(known traffic, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--kv-cache", choices=["native", "e4m3"], default="native",
+                    help="e4m3: the same decode workload over 8-bit (E4M3) KV caches with per-tensor scales - "
+                         "quantising cache write + optgqa_paged_attention_fp8; KV bytes are then 1 per element")
     ap.add_argument("--no-target-check", action="store_true",
                     help="skip the extra C3-all8k measurement (every context 8192: the 'batch 64 / 8k' case)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
     return ap.parse_args()
+
+
+def cpu_baseline_e4m3(case, W, n_seqs: int, min_seconds: float = 10.0):
+    """The oracle's 8-bit clause on the first n_seqs sequences (0 = all): its own quantising cache
+    write of the whole batch once (not timed), then dequantise-then-attend, repeated ~min_seconds."""
+    import oracle as O
+    cfg = case.cfg
+    k_all, v_all, slots = W.all_token_rows(case)
+    shape = (cfg.num_blocks, cfg.num_kv_heads, cfg.block_size, cfg.head_dim)
+    kc8, vc8 = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
+    O.reshape_and_cache_e4m3(k_all, v_all, kc8, vc8, slots, KV_SCALE, KV_SCALE, case.dtype)
+    n_seqs = n_seqs if n_seqs > 0 else cfg.batch
+    rows = [(b, h) for b in range(n_seqs) for h in range(cfg.num_heads)]
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                               KV_SCALE, KV_SCALE, case.dtype, rows=rows)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or reps >= 1000:
+            break
+    per = dt / reps
+    kv_bytes = 2 * int(case.context_lens[:n_seqs].astype(np.int64).sum()) * cfg.num_kv_heads * cfg.head_dim
+    return {"value": kv_bytes / per / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"first {n_seqs} of {cfg.batch} sequences, all {cfg.num_heads} query heads, E4M3 caches "
+                      f"({kv_bytes / 1e6:.1f} MB of KV per pass, {reps} passes in {dt:.1f} s)",
+            "query_tokens_per_s": n_seqs / per}
 
 
 def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0):
@@ -147,9 +178,29 @@ def main():
         scale = float(case.scale)
         stream = torch.cuda.current_stream()
 
-        one_call = decode and P == 0
+        e4m3 = args.kv_cache == "e4m3"
+        if e4m3:
+            assert decode, "--kv-cache e4m3 applies to decode workloads"
+            # 8-bit caches of the same logical content, quantised on the GPU from the 2-byte rows of
+            # every token but the step's new ones (those are written by the timed step)
+            k_old, v_old, slots_old = W.all_token_rows(case, include_new=False)
+            shape = (cfg.num_blocks, cfg.num_kv_heads, cfg.block_size, cfg.head_dim)
+            k8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
+            v8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
+            from paper_2505_02351_amd.testing import to_dev
+            G.reshape_and_cache_fp8(to_dev(k_old, case.dtype), to_dev(v_old, case.dtype), k8, v8,
+                                    torch.from_numpy(slots_old).cuda(), KV_SCALE, KV_SCALE)
+            torch.cuda.synchronize()
+            del k_old, v_old
+            ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
+        one_call = decode and P == 0 and not e4m3
 
         def step():
+            if e4m3:
+                G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
+                G.paged_attention_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.slopes,
+                                      scale, KV_SCALE, KV_SCALE, max_ctx, ws, stream)
+                return
             if one_call:
                 G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
                               dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
@@ -188,7 +239,7 @@ def main():
         kernel_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
 
         ms_per_step = wall * 1e3 / steps
-        kv_bytes = case.kv_bytes()
+        kv_bytes = case.kv_bytes() // (2 if e4m3 else 1)
         value = kv_bytes / (ms_per_step * 1e-3) / 1e9
         n_q = case.num_tokens
         launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
@@ -196,12 +247,13 @@ def main():
         if decode:
             achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
             if chosen_P == G.SPLIT_BALANCED:
-                kname = "paged_decode_flat_kernel (equal-work split%s)" % (", cache write fused" if one_call else "")
+                kname = "paged_decode_flat_kernel (equal-work split%s)" % (
+                    ", E4M3 caches" if e4m3 else ", cache write fused" if one_call else "")
             else:
                 kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
             roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None else None,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None and not e4m3 else None,
                         "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
         else:
             # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
@@ -226,7 +278,8 @@ def main():
                        "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
                        "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
                        "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
-                       "calls_per_step": 1 if one_call else 2},
+                       "calls_per_step": 1 if one_call else 2,
+                       "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype},
             "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
@@ -234,7 +287,7 @@ def main():
         return result, case
 
     result, case = measure(args.workload, args.steps, args.warmup)
-    if args.workload == "C3" and args.partition_size is None and not args.no_target_check:
+    if args.workload == "C3" and args.partition_size is None and not args.no_target_check and args.kv_cache == "native":
         # the target is worded "batch 64 / 8k context": the same batch with every context at 8192
         extra, _ = measure("C3-all8k", max(args.steps // 2, 1), max(args.warmup // 2, 1))
         result["target_check"] = {
@@ -245,7 +298,8 @@ def main():
             "kv_bytes": extra["config"]["kv_bytes"],
         }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case, W, args.cpu_sample_seqs)
+        result["cpu_baseline"] = (cpu_baseline_e4m3 if args.kv_cache == "e4m3" else cpu_baseline)(
+            case, W, args.cpu_sample_seqs)
     print(json.dumps(result))
 
 

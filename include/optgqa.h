@@ -157,6 +157,42 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
                        int64_t v_token_stride, void *workspace, size_t workspace_bytes,
                        optgqa_dtype dtype, void *stream);
 
+/*
+ * 8-bit KV cache (the paper's title and Section I pair quantisation with grouped-query attention
+ * as the levers on KV-cache traffic; it fixes no format - this is the variant built here).
+ * The caches hold 1-byte E4M3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
+ * infinities, largest finite value 448, codes 0x7f / 0xff are NaN) in the same
+ * [num_blocks][num_kv_heads][block_size][head_dim] layout, with ONE scale per tensor.
+ *
+ * optgqa_reshape_and_cache_fp8: as optgqa_reshape_and_cache, with a quantiser in front:
+ *     code = nearest_e4m3( fp32(x) * fp32(1 / scale) )
+ * - one fp32 division on the host, one fp32 multiplication per element, round to nearest with
+ * ties to the even code, magnitudes above 448 (infinities included) saturate to +-448, NaN
+ * becomes 0x7f.  k and v are 2-byte elements of `dtype`; they must be 16-byte aligned with
+ * token strides that are multiples of 8 elements, the caches 8-byte aligned
+ * (else OPTGQA_ERR_UNSUPPORTED).  k_scale, v_scale: finite and > 0 (else OPTGQA_ERR_SHAPE).
+ *
+ * optgqa_paged_attention_fp8: as optgqa_paged_attention over such caches (dequantise, then attend):
+ *     s_j = scale * k_scale * <q[b][h], value(kcode_j)> + alibi_slopes[h] * (j - (L - 1))
+ *     out[b][h] = v_scale * sum_j softmax(s)_j * value(vcode_j)
+ * q and out are 2-byte elements of `dtype`.  head_dim 128 only; always the equal-work split, so
+ * the workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED, ...) is
+ * required (OPTGQA_ERR_WORKSPACE without it).
+ */
+int optgqa_reshape_and_cache_fp8(const void *k, const void *v, void *k_cache, void *v_cache,
+                                 const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
+                                 int head_dim, int block_size, int64_t k_token_stride,
+                                 int64_t v_token_stride, float k_scale, float v_scale,
+                                 optgqa_dtype dtype, void *stream);
+
+int optgqa_paged_attention_fp8(void *out, const void *q, const void *k_cache, const void *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               const float *alibi_slopes, float scale, float k_scale, float v_scale,
+                               int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                               int block_size, int max_blocks_per_seq, int max_context_len,
+                               void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                               void *stream);
+
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
  * Also reports, when chosen_partition_size is not NULL, the partition size the library would
  * use (0 = unsplit, OPTGQA_SPLIT_BALANCED = the equal-work split). */

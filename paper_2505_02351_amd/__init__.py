@@ -59,6 +59,11 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_decode_step.restype = i32
     lib.optgqa_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                        i64, i64, vp, sz, i32, vp]
+    lib.optgqa_reshape_and_cache_fp8.restype = i32
+    lib.optgqa_reshape_and_cache_fp8.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, f32, f32, i32, vp]
+    lib.optgqa_paged_attention_fp8.restype = i32
+    lib.optgqa_paged_attention_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
+                                               i32, i32, vp, sz, i32, vp]
     lib.optgqa_paged_attention_workspace_bytes.restype = sz
     lib.optgqa_paged_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32,
                                                            ctypes.POINTER(ctypes.c_int)]
@@ -195,6 +200,50 @@ def decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: 
                                 Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len), ks, vs,
                                 _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_decode_step")
+
+
+def reshape_and_cache_fp8(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                          slot_mapping: torch.Tensor, k_scale: float, v_scale: float, stream=None) -> None:
+    """optgqa_reshape_and_cache_fp8: quantise the new tokens' K/V rows to E4M3 codes in the paged
+    caches (uint8 tensors [NB, Hkv, bs, D])."""
+    lib = load_library()
+    NB, Hkv, bs, D = k_cache.shape
+    T = int(slot_mapping.shape[0])
+    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
+    _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(slot_mapping, "slot_mapping")
+    if T and (k.stride(-1) != 1 or k.stride(-2) != D or v.stride(-1) != 1 or v.stride(-2) != D):
+        raise ValueError("optgqa: k and v must be dense in their last two dims")
+    ks = int(k.stride(0)) if T else Hkv * D
+    vs = int(v.stride(0)) if T else Hkv * D
+    rc = lib.optgqa_reshape_and_cache_fp8(_ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache), _ptr(slot_mapping),
+                                          T, Hkv, D, bs, ks, vs, float(k_scale), float(v_scale),
+                                          _dtype_code(k), _stream(stream))
+    _check(rc, "optgqa_reshape_and_cache_fp8")
+
+
+def paged_attention_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                        block_tables: torch.Tensor, context_lens: torch.Tensor,
+                        alibi_slopes: Optional[torch.Tensor], scale: float, k_scale: float, v_scale: float,
+                        max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_paged_attention_fp8: decode attention over E4M3 caches (uint8 tensors)."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_paged_attention_fp8(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                        _ptr(context_lens), _ptr(alibi_slopes), float(scale), float(k_scale),
+                                        float(v_scale), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
+                                        int(max_context_len), _ptr(workspace), ws_bytes, _dtype_code(q),
+                                        _stream(stream))
+    _check(rc, "optgqa_paged_attention_fp8")
 
 
 def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

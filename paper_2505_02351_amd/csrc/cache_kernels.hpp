@@ -49,6 +49,54 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
         *reinterpret_cast<VecT*>(v_cache + dst) = *reinterpret_cast<const VecT*>(v + t * v_token_stride + src_off);
 }
 
+// Cache store with a quantiser in front, for caches that hold 1-byte E4M3 codes (largest finite
+// value 448, no infinities) and one scale per tensor:
+//     code = nearest_e4m3( fp32(x) * inv_scale ),  inv_scale = fp32(1 / scale) computed on the host.
+// One fp32 multiplication, then the hardware's round-to-nearest-even conversion; the hardware
+// turns magnitudes beyond the format's range into NaN, so the product is clamped to +-448 first
+// (saturation), and a NaN input is given the code 0x7f explicitly.
+// One thread moves 8 elements of one token's K or V row: 16 bytes in, 8 bytes out.
+template <int DT>
+__global__ __launch_bounds__(256) void reshape_and_cache_e4m3_kernel(
+    const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, unsigned char* __restrict__ k_cache,
+    unsigned char* __restrict__ v_cache, const int64_t* __restrict__ slot_mapping, int num_tokens,
+    int num_kv_heads, int head_dim, int block_size, int64_t k_token_stride, int64_t v_token_stride,
+    float k_inv_scale, float v_inv_scale)
+{
+    const int pieces_per_head = head_dim / 8;
+    const int pieces_per_token = num_kv_heads * pieces_per_head;
+    const int64_t total = (int64_t)num_tokens * pieces_per_token * 2;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int which = (int)(idx / ((int64_t)num_tokens * pieces_per_token));   // 0 = K, 1 = V
+    const int64_t rem = idx - (int64_t)which * num_tokens * pieces_per_token;
+    const int t = (int)(rem / pieces_per_token);
+    const int piece = (int)(rem - (int64_t)t * pieces_per_token);
+    const int64_t slot = slot_mapping[t];
+    if (slot < 0) return;                                   // padding token
+    const int g = piece / pieces_per_head;
+    const int d0 = (piece - g * pieces_per_head) * 8;
+    const int64_t block = slot / block_size;
+    const int64_t row = slot - block * block_size;
+    const int64_t dst = ((block * num_kv_heads + g) * block_size + row) * head_dim + d0;
+    const uint16_t* src = which == 0 ? k + t * k_token_stride : v + t * v_token_stride;
+    const float inv = which == 0 ? k_inv_scale : v_inv_scale;
+    const uint4 x = *reinterpret_cast<const uint4*>(src + (int64_t)g * head_dim + d0);
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = widen_lo<DT>(w[i]) * inv, b = widen_hi<DT>(w[i]) * inv;
+        const float ac = fminf(fmaxf(a, -448.f), 448.f), bc = fminf(fmaxf(b, -448.f), 448.f);
+        uint32_t two = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ac, bc, 0, false) & 0xffffu;
+        if (a != a) two = (two & 0xff00u) | 0x7fu;
+        if (b != b) two = (two & 0x00ffu) | 0x7f00u;
+        packed[i >> 1] |= two << (16 * (i & 1));
+    }
+    unsigned char* out = (which == 0 ? k_cache : v_cache) + dst;
+    *reinterpret_cast<uint2*>(out) = make_uint2(packed[0], packed[1]);
+}
+
 // Un-paging: copy token j of sequence b, all KV heads, to dense [B][max_context_len][Hkv][D].
 // One thread per 16-byte piece; grid = (ceil(max_context_len * pieces_per_token / 256), B, 2).
 __global__ __launch_bounds__(256) void gather_kv_kernel(

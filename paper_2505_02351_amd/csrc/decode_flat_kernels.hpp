@@ -23,6 +23,8 @@
 // the context lengths itself (two memory round trips for any batch size), and the wave that
 // processes the first tile of a sequence records P_b for the combine kernel.
 #pragma once
+#include <type_traits>
+
 #include "decode_mma_kernels.hpp"
 
 namespace optgqa {
@@ -52,9 +54,34 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 // that contains it takes that row from k_new / v_new instead of the cache (a per-lane pointer
 // select), and the wave that finishes a KV head's segment copies the row into the cache.  No
 // wave reads that cache row during the launch, so there is nothing to order.
-template <int DT, bool FUSED>
+//
+// KV8: the caches hold 1-byte E4M3 codes (largest finite value 448, no infinities) instead of
+// 2-byte elements, with one scale per tensor: k_scale is folded into the score scale on the host,
+// v_scale into the combine kernel's normalisation.  A token row is then 128 bytes; a lane's
+// 16-byte K piece holds 16 consecutive dims and feeds two score MFMAs after widening to DT
+// (exact: every E4M3 value is an fp16 and a bf16 number), a lane's 8-byte V piece widens to the
+// same 8 fp32 values per lane as before.  Not combined with FUSED.
+struct MmaTile8 {
+    uint4 k[2];     // K: token j16, dims 64j + 16hg .. +15
+    uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
+};
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// eight E4M3 codes (two dwords) -> eight DT values (one MFMA operand)
+template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint32_t hi)
+{
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+    return make_uint4(narrow2<DT>(a[0], a[1]), narrow2<DT>(b[0], b[1]), narrow2<DT>(c[0], c[1]), narrow2<DT>(d[0], d[1]));
+}
+
+template <int DT, bool FUSED, bool KV8 = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
+    static_assert(!(FUSED && KV8), "the fused cache write exists for 2-byte caches only");
+    typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
+    constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     constexpr int D = 128;
     constexpr int TILE = kMmaTile;
     constexpr int NB = kMmaBufs;
@@ -133,8 +160,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     }
 
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
-    const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache);
-    const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
+    const unsigned char* __restrict__ kc = static_cast<const unsigned char*>(p.k_cache);
+    const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache);
     const float scale2 = p.scale2;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
     float* const pw_write = &p_lds[wave][j16][4 * hg];
@@ -146,23 +173,34 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     const uint16_t* __restrict__ v_new = static_cast<const uint16_t*>(p.v_new);
     // (new_pos, new_off_k, new_off_v: position of the segment's new token and where its K / V
     // rows start in k_new / v_new; only read when FUSED)
-    auto load_tile = [&](MmaTile& Tl, const int32_t* tab, int64_t head_off, int t_last, int tile_t0,
+    auto load_tile = [&](Tile& Tl, const int32_t* tab, int64_t head_off, int t_last, int tile_t0,
                          int new_pos, int64_t new_off_k, int64_t new_off_v) __attribute__((always_inline)) {
         // through the scalar cache: a vector load here would make the wave wait for every tile
         // load still in flight before it could read the block number
         const int blk = scalar_load_i32(tab + (tile_t0 >> bs_shift));
         const int64_t uni = blk * block_stride + head_off + (int64_t)(tile_t0 & (bs - 1)) * D;
         const int tk = min(tile_t0 + j16, t_last) - tile_t0;
-        const uint16_t* ka = kc + uni + tk * D + 8 * hg;
-        if (FUSED && tile_t0 + tk == new_pos) ka = k_new + new_off_k + 8 * hg;
+        if constexpr (KV8) {
+            const unsigned char* ka = kc + uni + tk * D + 16 * hg;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) Tl.k[i] = *reinterpret_cast<const uint4*>(ka + 32 * i);
+            for (int j = 0; j < 2; ++j) Tl.k[j] = *reinterpret_cast<const uint4*>(ka + 64 * j);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-            const uint16_t* va = vc + uni + tv * D + 8 * j16;
-            if (FUSED && tile_t0 + tv == new_pos) va = v_new + new_off_v + 8 * j16;
-            Tl.v[s] = *reinterpret_cast<const uint4*>(va);
+            for (int s = 0; s < 4; ++s) {
+                const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
+                Tl.v[s] = *reinterpret_cast<const uint2*>(vc + uni + tv * D + 8 * j16);
+            }
+        } else {
+            const unsigned char* ka = kc + (uni + tk * D + 8 * hg) * ES;
+            if (FUSED && tile_t0 + tk == new_pos) ka = reinterpret_cast<const unsigned char*>(k_new + new_off_k + 8 * hg);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) Tl.k[i] = *reinterpret_cast<const uint4*>(ka + 64 * i);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
+                const unsigned char* va = vc + (uni + tv * D + 8 * j16) * ES;
+                if (FUSED && tile_t0 + tv == new_pos) va = reinterpret_cast<const unsigned char*>(v_new + new_off_v + 8 * j16);
+                Tl.v[s] = *reinterpret_cast<const uint4*>(va);
+            }
         }
     };
     // A operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
@@ -170,11 +208,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     auto load_q = [&](uint4 (&qd)[4], float (&sd)[4], int bb, int yy) __attribute__((always_inline)) {
         const int gg = yy / chunks;
         const int hh0 = gg * G + (yy - gg * chunks) * GH;
-        const uint16_t* qrow = qp + ((int64_t)bb * Hq + hh0 + min(j16, GH - 1)) * D + 8 * hg;
+        // (2-byte caches: MFMA i contracts dims 32i + 8hg .. +7; E4M3 caches: dims
+        // 64(i/2) + 16hg + 8(i%2) .. +7, the order in which a lane's 16-byte K pieces arrive)
+        const uint16_t* qrow = qp + ((int64_t)bb * Hq + hh0 + min(j16, GH - 1)) * D + (KV8 ? 16 : 8) * hg;
         const uint32_t keep = j16 < GH ? 0xffffffffu : 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint4 x = *reinterpret_cast<const uint4*>(qrow + 32 * i);
+            const uint4 x = *reinterpret_cast<const uint4*>(qrow + (KV8 ? 64 * (i >> 1) + 8 * (i & 1) : 32 * i));
             qd[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
         float sl[4] = {0.f, 0.f, 0.f, 0.f};
@@ -187,7 +227,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     };
 
     static_assert(NB == 2, "the hand-over of the next piece's first tile assumes two register buffers");
-    MmaTile buf[NB];
+    Tile buf[NB];
     uint4 qa[4], qn[4];
     float slope2[4], slope2n[4];
     bool chained = false;         // buf[0], qa, slope2 were filled by the previous piece
@@ -267,18 +307,26 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         // the A operand of the output MFMA reads all 16 head columns: start them finite
         reinterpret_cast<float4*>(&p_lds[wave][0][0])[lane] = make_float4(0.f, 0.f, 0.f, 0.f);
 
-        auto compute_tile = [&](const MmaTile& Tl, int j) __attribute__((always_inline)) {
+        auto compute_tile = [&](const Tile& Tl, int j) __attribute__((always_inline)) {
 #if defined(OPTGQA_FLAT_ABLATE) && OPTGQA_FLAT_ABLATE == 1
             // development only: consume the loads without arithmetic
             uint32_t x = 0;
-            for (int i = 0; i < 4; ++i) x ^= Tl.k[i].x ^ Tl.k[i].y ^ Tl.k[i].z ^ Tl.k[i].w ^ Tl.v[i].x ^ Tl.v[i].y ^ Tl.v[i].z ^ Tl.v[i].w;
+            for (int i = 0; i < (KV8 ? 2 : 4); ++i) x ^= Tl.k[i].x ^ Tl.k[i].y ^ Tl.k[i].z ^ Tl.k[i].w;
+            for (int i = 0; i < 4; ++i) x ^= Tl.v[i].x ^ Tl.v[i].y;
             acc[0][0] += __uint_as_float(x & 0x3fffffffu);
             l[0] += (float)j;
             return;
 #endif
             f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) S = mfma_qk<DT>(qa[i], Tl.k[i], S);
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (KV8) {
+                    const uint4 kk = Tl.k[i >> 1];
+                    S = mfma_qk<DT>(qa[i], (i & 1) ? widen8_e4m3<DT>(kk.z, kk.w) : widen8_e4m3<DT>(kk.x, kk.y), S);
+                } else {
+                    S = mfma_qk<DT>(qa[i], Tl.k[i], S);
+                }
+            }
             const int t = t_begin + j * TILE + j16;
             const bool valid = t < t_end;
             const float rel = (float)(t - Lm1);
@@ -315,9 +363,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
             for (int s = 0; s < 4; ++s) a[s] = pw_read[4 * s * kMmaMaxHeads];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const uint4 vr = Tl.v[s];
-                const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
-                                     widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};
+                float vf[8];
+                if constexpr (KV8) {
+                    const f32x2 v01 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].x, false), v23 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].x, true);
+                    const f32x2 v45 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].y, false), v67 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].y, true);
+                    vf[0] = v01[0], vf[1] = v01[1], vf[2] = v23[0], vf[3] = v23[1];
+                    vf[4] = v45[0], vf[5] = v45[1], vf[6] = v67[0], vf[7] = v67[1];
+                } else {
+                    const uint4 vr = Tl.v[s];
+                    vf[0] = widen_lo<DT>(vr.x), vf[1] = widen_hi<DT>(vr.x), vf[2] = widen_lo<DT>(vr.y), vf[3] = widen_hi<DT>(vr.y);
+                    vf[4] = widen_lo<DT>(vr.z), vf[5] = widen_hi<DT>(vr.z), vf[6] = widen_lo<DT>(vr.w), vf[7] = widen_hi<DT>(vr.w);
+                }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], vf[e], acc[e], 0, 0, 0);
             }
@@ -446,7 +502,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
             num.w = fmaf(fct, x[k].w, num.w);
         }
     }
-    const float inv = 1.f / den;
+    const float inv = p.out_scale / den;                 // out_scale: 1, or v_scale of an E4M3 cache
     uint2 packed;
     packed.x = narrow2<DT>(num.x * inv, num.y * inv);
     packed.y = narrow2<DT>(num.z * inv, num.w * inv);

@@ -97,9 +97,16 @@ struct SplitPlan {
     size_t plan_floats, ml_floats;
 };
 
-// Equal-work split: one wave per hardware wave slot at most, and no wave with less than
-// kFlatMinTiles tiles of 16 tokens when the lengths are at their bound.
-constexpr int kFlatMaxWorkgroups = kNumCUs * OPTGQA_FLAT_WGS_PER_CU;
+// Equal-work split: one workgroup per CU for 2-byte caches (one wave per SIMD streams best),
+// OPTGQA_FLAT_WGS_PER_CU_KV8 per CU for 8-bit caches (half the bytes per tile: the second wave
+// per SIMD hides the arithmetic); no wave with less than kFlatMinTiles tiles of 16 tokens when
+// the lengths are at their bound.  The workspace is sized for the larger of the two.
+#ifndef OPTGQA_FLAT_WGS_PER_CU_KV8
+#define OPTGQA_FLAT_WGS_PER_CU_KV8 2
+#endif
+constexpr int kFlatWorkgroups = kNumCUs * OPTGQA_FLAT_WGS_PER_CU;
+constexpr int kFlatWorkgroupsKv8 = kNumCUs * OPTGQA_FLAT_WGS_PER_CU_KV8;
+constexpr int kFlatMaxWorkgroups = kFlatWorkgroups > kFlatWorkgroupsKv8 ? kFlatWorkgroups : kFlatWorkgroupsKv8;
 #ifndef OPTGQA_FLAT_MIN_TILES
 #define OPTGQA_FLAT_MIN_TILES 8
 #endif
@@ -224,12 +231,12 @@ int launch_decode_any(int dtype, int head_dim, A... args)
 // Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
 // the device keeps resident at once, because a unit that has to wait for a free slot would start
 // when every other unit is nearly done.
-template <int DT, bool FUSED>
+template <int DT, bool FUSED, bool KV8 = false>
 int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 {
     static const int resident = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED>, kDecodeWaves * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8>, kDecodeWaves * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -242,7 +249,7 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     p.num_units = workgroups * kDecodeWaves;
     {
         KernelEvents ev(st);
-        hipLaunchKernelGGL((paged_decode_flat_kernel<DT, FUSED>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+        hipLaunchKernelGGL((paged_decode_flat_kernel<DT, FUSED, KV8>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
     }
     int rc = launch_status();
     if (rc != OPTGQA_OK) return rc;
@@ -252,8 +259,11 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     return launch_status();
 }
 
-int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st)
+int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
 {
+    if (kv8)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, false, true>(p, workgroups, st);
     if (p.k_new)
         return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true>(p, workgroups, st)
                                    : launch_decode_flat_dt<kBF16, true>(p, workgroups, st);
@@ -291,6 +301,7 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     p.k_new = p.v_new = nullptr;
     p.k_cache_w = p.v_cache_w = nullptr;
     p.k_new_stride = p.v_new_stride = 0;
+    p.out_scale = 1.f;
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
@@ -444,8 +455,15 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
                    const int32_t* block_tables, const int32_t* context_lens, const float* alibi_slopes,
                    float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                    int max_blocks_per_seq, int max_context_len, int partition_size, void* workspace,
-                   size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step)
+                   size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step,
+                   const float* kv_scales = nullptr)      // {k_scale, v_scale}: the caches hold E4M3 codes
 {
+    if (kv_scales) {
+        if (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f)
+            return OPTGQA_ERR_SHAPE;
+        if (head_dim != 128 || step) return OPTGQA_ERR_UNSUPPORTED;
+        partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that reads E4M3 caches
+    }
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_context_len < 0)
         return OPTGQA_ERR_SHAPE;
@@ -496,6 +514,11 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.k_new = p.v_new = nullptr;
     p.k_cache_w = p.v_cache_w = nullptr;
     p.k_new_stride = p.v_new_stride = 0;
+    p.out_scale = 1.f;
+    if (kv_scales) {
+        p.scale2 *= kv_scales[0];
+        p.out_scale = kv_scales[1];
+    }
 
     // The cache write rides inside the equal-work kernel when that kernel runs and the new rows
     // can be moved as 16-byte pieces; otherwise it is a launch of its own ahead of the attention.
@@ -530,7 +553,8 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
         p.timing = workspace_bytes >= s.bytes + (size_t)s.workgroups * kDecodeWaves * 32
                        ? reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + s.bytes) : nullptr;
 #endif
-        return launch_decode_flat(dtype, p, s.workgroups, st);
+        const int cap = kv_scales ? kFlatWorkgroupsKv8 : kFlatWorkgroups;
+        return launch_decode_flat(dtype, p, s.workgroups < cap ? s.workgroups : cap, st, kv_scales != nullptr);
     }
     p.plan = nullptr;
     p.num_units = p.segs_per_seq = 0;
@@ -564,6 +588,57 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           partition_size, workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream),
                           nullptr);
+}
+
+int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, void* v_cache,
+                                 const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
+                                 int head_dim, int block_size, int64_t k_token_stride,
+                                 int64_t v_token_stride, float k_scale, float v_scale,
+                                 optgqa_dtype dtype, void* stream)
+{
+    if (num_tokens < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    const int64_t row = (int64_t)num_kv_heads * head_dim;
+    if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
+    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3e38f || v_scale > 3e38f) return OPTGQA_ERR_SHAPE;
+    if (num_tokens == 0) return OPTGQA_OK;
+    if (!k || !v || !k_cache || !v_cache || !slot_mapping) return OPTGQA_ERR_NULL;
+    // 16-byte pieces in, 8-byte pieces out
+    if (!aligned16(k) || !aligned16(v) || k_token_stride % 8 || v_token_stride % 8 ||
+        ((reinterpret_cast<uintptr_t>(k_cache) | reinterpret_cast<uintptr_t>(v_cache)) & 7u))
+        return OPTGQA_ERR_UNSUPPORTED;
+    const int64_t threads = (int64_t)num_tokens * num_kv_heads * (head_dim / 8) * 2;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
+    const float k_inv = 1.0f / k_scale, v_inv = 1.0f / v_scale;       // one fp32 division each
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    auto kk = static_cast<const uint16_t*>(k);
+    auto vv = static_cast<const uint16_t*>(v);
+    auto kc = static_cast<unsigned char*>(k_cache);
+    auto vc = static_cast<unsigned char*>(v_cache);
+    if (dtype == OPTGQA_F16)
+        hipLaunchKernelGGL((reshape_and_cache_e4m3_kernel<kF16>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
+                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
+                           v_token_stride, k_inv, v_inv);
+    else
+        hipLaunchKernelGGL((reshape_and_cache_e4m3_kernel<kBF16>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
+                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
+                           v_token_stride, k_inv, v_inv);
+    return launch_status();
+}
+
+int optgqa_paged_attention_fp8(void* out, const void* q, const void* k_cache, const void* v_cache,
+                               const int32_t* block_tables, const int32_t* context_lens,
+                               const float* alibi_slopes, float scale, float k_scale, float v_scale,
+                               int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                               int block_size, int max_blocks_per_seq, int max_context_len,
+                               void* workspace, size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    const float kv_scales[2] = {k_scale, v_scale};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), nullptr, kv_scales);
 }
 
 int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,

@@ -88,22 +88,9 @@ def _small_case(dtype, seed=31):
 
 
 def _all_tokens(case):
-    """The 2-byte K/V rows of every token of the batch (gathered from the generator's cache image
-    and its new-token arrays by plain indexing) with the slot of each."""
-    cfg = case.cfg
-    kc, vc = case.k_cache.copy(), case.v_cache.copy()
-    bs = cfg.block_size
-    for t, s in enumerate(case.slot_mapping):
-        kc[s // bs, :, s % bs, :] = case.k_new[t]
-        vc[s // bs, :, s % bs, :] = case.v_new[t]
-    ks, vs, slots = [], [], []
-    for b in range(cfg.batch):
-        for j in range(int(case.context_lens[b])):
-            blk = int(case.block_tables[b, j // bs])
-            ks.append(kc[blk, :, j % bs, :])
-            vs.append(vc[blk, :, j % bs, :])
-            slots.append(blk * bs + j % bs)
-    return np.stack(ks), np.stack(vs), np.array(slots, np.int64)
+    """The 2-byte K/V rows of every token of the batch with the slot of each (the generator's own
+    indexing helper)."""
+    return W.all_token_rows(case)
 
 
 def quantised_cache(case, k_scale, v_scale, lib=None):

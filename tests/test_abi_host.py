@@ -97,7 +97,7 @@ def test_workspace_query(G):
     # of 256 CUs) plus one per (sequence, KV head), each slot 8 heads x (128 + 2) floats, after
     # 64 + 1 plan entries padded to 4
     n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, 0)
-    slots = 256 * 4 + 64 * 4
+    slots = 256 * 2 * 4 + 64 * 4                 # sized for two workgroups per CU (the 8-bit cache path)
     assert P == G.SPLIT_BALANCED and n == (68 + slots * 8 * (128 + 2)) * 4
     assert G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, G.SPLIT_BALANCED) == (n, P)
     # small problems get fewer waves: 2 x 2 segments x 13 tiles -> 52 tiles -> 2 workgroups

@@ -382,6 +382,148 @@ def test_decode_step_strided_new_rows(U, oracle):
         assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
 
 
+# ------------------------------------------------------------------ 8-bit (E4M3) KV cache
+def fp8_caches(U, case, k_scale, v_scale):
+    """Quantise the whole batch into 8-bit caches on both sides (oracle: numpy image; GPU: uint8
+    tensors through optgqa_reshape_and_cache_fp8) from the same 2-byte rows and slots."""
+    import torch
+    import pins_e4m3
+    import paper_2505_02351_amd as G
+    kc8, vc8, (k_all, v_all, slots) = pins_e4m3.quantised_cache(case, k_scale, v_scale)
+    dk = torch.full(kc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    dv = torch.full(vc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    G.reshape_and_cache_fp8(U.to_dev(k_all, case.dtype), U.to_dev(v_all, case.dtype), dk, dv,
+                            torch.from_numpy(slots).cuda(), k_scale, v_scale)
+    torch.cuda.synchronize()
+    return kc8, vc8, dk, dv
+
+
+def fp8_decode(U, case, dk, dv, k_scale, v_scale, q=None):
+    import torch
+    import paper_2505_02351_amd as G
+    c = case.cfg
+    qd = U.to_dev(case.q if q is None else q, case.dtype)
+    out = torch.full_like(qd, float("nan"))
+    n, _ = G.paged_attention_workspace_bytes(qd.shape[0], c.num_heads, c.num_kv_heads, c.head_dim, c.block_size,
+                                             max(case.max_context_len, 1), G.SPLIT_BALANCED)
+    ws = torch.empty(n // 4, dtype=torch.float32, device="cuda")
+    G.paged_attention_fp8(out, qd, dk, dv, torch.from_numpy(case.block_tables).cuda(),
+                          torch.from_numpy(case.context_lens).cuda(), torch.from_numpy(case.slopes).cuda(),
+                          float(case.scale), k_scale, v_scale, case.max_context_len, ws)
+    torch.cuda.synchronize()
+    return U.to_host(out)
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_fp8_cache_write_every_input_pattern(U, oracle, dtype):
+    """All 65 536 two-byte patterns (NaNs and infinities included) through the quantising cache
+    write, at scales that exercise the subnormal codes, the normal range and saturation: the
+    codes must equal the oracle's bit for bit."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(64, 8, 128)     # [T][Hkv][D]
+    slots = np.random.default_rng(1).permutation(96)[:64].astype(np.int64)            # 6 blocks of 16
+    slots[5] = -1                                                                       # one padding token
+    for k_scale, v_scale in ((1.0, 0.013), (37.5, 2.0 ** -12), (3e-3, 1e4)):
+        kc8 = np.full((6, 8, 16, 128), 0x7F, np.uint8)
+        vc8 = np.full((6, 8, 16, 128), 0x7F, np.uint8)
+        O.reshape_and_cache_e4m3(bits, bits, kc8, vc8, slots, k_scale, v_scale, dtype)
+        dk = torch.full(kc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+        dv = torch.full(vc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+        G.reshape_and_cache_fp8(U.to_dev(bits, dtype), U.to_dev(bits, dtype), dk, dv, torch.from_numpy(slots).cuda(),
+                                k_scale, v_scale)
+        torch.cuda.synchronize()
+        assert np.array_equal(dk.cpu().numpy(), kc8), (dtype, k_scale)
+        assert np.array_equal(dv.cpu().numpy(), vc8), (dtype, v_scale)
+
+
+FP8_SWEEP = [i for i, s in enumerate(SWEEP) if s[3] == 128]
+
+
+@pytest.mark.parametrize("i", FP8_SWEEP)
+def test_fp8_decode_sweep(U, oracle, i):
+    import oracle as O
+    dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
+    cfg = W.small_config(name=f"fp8_{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
+                         ctx_hi=hi, seed=900 + i)
+    case = W.make_case(cfg)
+    k_scale, v_scale = 0.0125, 0.02                     # N(0,1) data: the format's range covers +-5.6 / +-9 sigma
+    kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
+    ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                 k_scale, v_scale, dtype)
+    err = U.max_abs_err(got, ref, dtype)
+    assert err <= U.TOL[dtype], f"max abs err {err}"
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_fp8_decode_edge_lengths(U, oracle, dtype):
+    import oracle as O
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1, 0], np.int32)
+    cfg = W.small_config(name="fp8_edges", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=180, ctx_lo=1, ctx_hi=512, seed=422)
+    case = W.make_case(cfg, context_lens=lens)
+    q_full = np.zeros((len(lens), 8, 128), np.uint16)
+    q_full[lens > 0] = case.q
+    # the generator's new-token rows exist for non-empty sequences only; rebuild the case's views
+    case.q = q_full
+    k_scale, v_scale = 0.02, 0.5
+    kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
+    ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                 k_scale, v_scale, dtype)
+    assert not got[lens == 0].any()
+    assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype]
+    # one-token contexts: weight exactly 1, so the output is v_scale * value(code), rounded once
+    vals = O.e4m3_values()
+    for b in (1, 12):
+        blk = case.block_tables[b, 0]
+        for h in range(8):
+            want = W.to_bits((v_scale * vals[vc8[blk, h // 4, 0, :]]).astype(np.float32), dtype)
+            assert np.array_equal(got[b, h], want)
+
+
+def test_fp8_decode_workload_sampled(U, oracle):
+    """The bench's batch (C3 shapes) with 8-bit caches; the oracle evaluates sampled rows."""
+    import oracle as O
+    cfg = W.CONFIGS["C3"]
+    case = W.make_case(cfg)
+    k_scale, v_scale = 0.0125, 0.0125
+    kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
+    rng = np.random.default_rng(98)
+    seqs = {int(np.argmax(case.context_lens)), int(np.argmin(case.context_lens)), 0, cfg.batch - 1}
+    rows = [(b, h) for b in sorted(seqs) for h in (0, cfg.num_heads // 2 + 1, cfg.num_heads - 1)]
+    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(20)]
+    ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                 k_scale, v_scale, case.dtype, rows=rows)
+    sub = np.stack([got[b, h] for b, h in rows])
+    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+
+
+def test_fp8_rejects_what_it_cannot_do(U):
+    import torch
+    import paper_2505_02351_amd as G
+    q = torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda")
+    c8 = torch.zeros(4, 2, 16, 64, dtype=torch.uint8, device="cuda")
+    bt = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
+    cl = torch.ones(2, dtype=torch.int32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 64
+        G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 1.0, 1.0, 32, ws)
+    q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
+    c8 = torch.zeros(4, 2, 16, 128, dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError):                    # no workspace
+        G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 1.0, 1.0, 32, None)
+    with pytest.raises(RuntimeError):                    # scale must be positive
+        G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 0.0, 1.0, 32, ws)
+
+
 # ------------------------------------------------------------------ the workloads themselves
 @pytest.mark.parametrize("name", ["C1", "C2"])
 def test_decode_workload_full(U, oracle, name):

@@ -137,6 +137,30 @@ class Case:
         return int(2 * int(self.context_lens.astype(np.int64).sum()) * c.num_kv_heads * c.head_dim * 2)
 
 
+def all_token_rows(case: "Case", include_new: bool = True):
+    """The 2-byte K and V rows of every token of the batch, sequence after sequence in logical
+    order, and each token's slot (physical_block * block_size + row): ``(k [N, Hkv, D],
+    v [N, Hkv, D], slots [N] int64)``.  Plain indexing of the cache image (the new tokens' rows are
+    put back first unless ``include_new`` is False, in which case those tokens are left out).
+    Used to build caches of another element type from the same logical content."""
+    cfg, bs = case.cfg, case.cfg.block_size
+    kc, vc = case.k_cache, case.v_cache
+    if include_new:
+        kc, vc = kc.copy(), vc.copy()
+        s = case.slot_mapping
+        kc[s // bs, :, s % bs, :] = case.k_new
+        vc[s // bs, :, s % bs, :] = case.v_new
+    ks, vs, slots = [], [], []
+    for b in range(cfg.batch):
+        n = int(case.context_lens[b]) - (0 if include_new else int(case.q_lens[b]))
+        j = np.arange(max(n, 0))
+        blk = case.block_tables[b, j // bs].astype(np.int64)
+        ks.append(kc[blk, :, j % bs, :])
+        vs.append(vc[blk, :, j % bs, :])
+        slots.append(blk * bs + j % bs)
+    return np.concatenate(ks), np.concatenate(vs), np.concatenate(slots).astype(np.int64)
+
+
 def make_case(cfg: Config, seed: Optional[int] = None, perm_seed: Optional[int] = None,
               context_lens: Optional[np.ndarray] = None, slopes: Optional[np.ndarray] = None,
               identity_blocks: bool = False) -> Case:
