@@ -63,6 +63,8 @@ def parse():
     ap.add_argument("--kv-cache", choices=["native", "e4m3"], default="native",
                     help="e4m3: the same decode workload over 8-bit (E4M3) KV caches with per-tensor scales - "
                          "quantising cache write + optgqa_paged_attention_fp8; KV bytes are then 1 per element")
+    ap.add_argument("--no-stream-probe", action="store_true",
+                    help="skip the no-arithmetic streaming measurement over the same caches")
     ap.add_argument("--no-target-check", action="store_true",
                     help="skip the extra C3-all8k measurement (every context 8192: the 'batch 64 / 8k' case)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
@@ -269,6 +271,32 @@ def main():
                         "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
                         "launch_ms": launch_ms}
 
+        stream_probe = None
+        if decode and not e4m3 and not args.no_stream_probe and cfg.head_dim == 128:
+            # The decode kernels' load pattern with no arithmetic, over the same caches: every wave of a
+            # one-workgroup-per-CU launch streams an equal share of randomly chosen 16-token pieces
+            # (4 KiB of K and 4 KiB of V each), as many bytes as the batch's KV.
+            pool_bytes = dev.k_cache.numel() * 2
+            wgs = 256
+            tiles = max(int(kv_bytes // 8192 // (wgs * 4)), 1)
+            rng = np.random.default_rng(123)
+            pairs = rng.permutation(pool_bytes // 8192)[:(wgs * 4 * tiles + 1) // 2]
+            lst = np.stack([2 * pairs, 2 * pairs + 1], axis=1).reshape(-1)[:wgs * 4 * tiles].astype(np.int32)
+            sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+            lst_dev = G.stream_probe(dev.k_cache, dev.v_cache, lst, wgs, tiles, sink, None, stream)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(30)]
+            for a, b in ev:
+                a.record(stream)
+                G.stream_probe(dev.k_cache, dev.v_cache, lst, wgs, tiles, sink, lst_dev, stream)
+                b.record(stream)
+            torch.cuda.synchronize()
+            ms = np.array([a.elapsed_time(b) for a, b in ev][5:])
+            nbytes = wgs * 4 * tiles * 8192
+            stream_probe = {"bytes": nbytes, "kernel_ms": float(ms.mean()), "GB/s": nbytes / (ms.mean() * 1e-3) / 1e9,
+                            "frac_of_peak": nbytes / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "what": "optgqa_stream_probe: same K/V load pattern, random 16-token pieces of the "
+                                    "same caches, one wave per SIMD, no arithmetic; event-timed per launch"}
+
         result = {
             "metric": "paged GQA+ALiBi decode: KV-read HBM GB/s (% of peak) and query tokens/s",
             "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -284,6 +312,9 @@ def main():
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
         }
+        if stream_probe:
+            result["stream_probe"] = stream_probe
+            result["roofline"]["frac_of_stream_probe"] = roofline["achieved"] / stream_probe["GB/s"]
         return result, case
 
     result, case = measure(args.workload, args.steps, args.warmup)

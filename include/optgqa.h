@@ -232,6 +232,25 @@ int optgqa_gather_kv(void *k_out, void *v_out, const void *k_cache, const void *
                      int max_context_len, optgqa_dtype dtype, void *stream);
 
 /*
+ * Measurement aid, not part of the method: the decode kernels' memory access pattern with no
+ * arithmetic behind it, for pricing them against what the memory system actually delivers.
+ * num_workgroups x 4 waves each stream tiles_per_wave "tiles"; tile t of wave w is the 4 KiB
+ * piece number tile_list[w * tiles_per_wave + t] of k_pool AND of v_pool (4 KiB = 16 token rows
+ * of 256 bytes), read with the K-operand load pattern and the V load pattern of the decode
+ * kernels, one tile ahead of a consumer that only XORs the registers together.  Nothing is
+ * written (`sink`, 16 bytes, exists so that the loads cannot be optimised away).
+ *
+ *   k_pool, v_pool  device buffers of pool_bytes each (16-byte aligned)
+ *   tile_list       device copy of the list; tile_list_host the SAME list in host memory: every
+ *                   entry is checked against pool_bytes / 4096 on the host before the launch
+ *                   (OPTGQA_ERR_TABLE if out of range)
+ * Bytes read per launch: num_workgroups * 4 * tiles_per_wave * 8192.
+ */
+int optgqa_stream_probe(const void *k_pool, const void *v_pool, size_t pool_bytes,
+                        const int32_t *tile_list, const int32_t *tile_list_host,
+                        int num_workgroups, int tiles_per_wave, void *sink, void *stream);
+
+/*
  * Host-side check of host copies of the tables: every block id a sequence references is in
  * [0, num_blocks), every context length fits its table row.  Returns OPTGQA_OK or
  * OPTGQA_ERR_TABLE / OPTGQA_ERR_NULL / OPTGQA_ERR_SHAPE.  Touches no GPU.

@@ -70,6 +70,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_prefill.restype = i32
     lib.optgqa_paged_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                          i32, vp]
+    lib.optgqa_stream_probe.restype = i32
+    lib.optgqa_stream_probe.argtypes = [vp, vp, sz, vp, vp, i32, i32, vp, vp]
     lib.optgqa_gather_kv.restype = i32
     lib.optgqa_gather_kv.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]
     lib.optgqa_validate_tables_host.restype = i32
@@ -281,6 +283,29 @@ def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v
                               _ptr(context_lens), B, Hkv, D, bs, int(block_tables.shape[1]), Lmax,
                               _dtype_code(k_cache), _stream(stream))
     _check(rc, "optgqa_gather_kv")
+
+
+def stream_probe(k_pool: torch.Tensor, v_pool: torch.Tensor, tile_list_host, num_workgroups: int,
+                 tiles_per_wave: int, sink: torch.Tensor, tile_list_dev: Optional[torch.Tensor] = None,
+                 stream=None) -> torch.Tensor:
+    """optgqa_stream_probe: stream 4 KiB pieces of two device buffers with the decode kernels' load
+    pattern and no arithmetic.  ``tile_list_host`` is a numpy int32 array
+    [num_workgroups * 4 * tiles_per_wave]; returns the device copy of it (pass it back in as
+    ``tile_list_dev`` for repeated launches)."""
+    import numpy as np
+    lib = load_library()
+    host = np.ascontiguousarray(tile_list_host, dtype=np.int32)
+    if host.size != num_workgroups * 4 * tiles_per_wave:
+        raise ValueError("optgqa: tile list size does not match the launch")
+    dev = tile_list_dev if tile_list_dev is not None else torch.from_numpy(host).to(k_pool.device)
+    nbytes = k_pool.numel() * k_pool.element_size()
+    if v_pool.numel() * v_pool.element_size() != nbytes:
+        raise ValueError("optgqa: the two pools must have the same size")
+    rc = lib.optgqa_stream_probe(_ptr(k_pool), _ptr(v_pool), nbytes, _ptr(dev),
+                                 host.ctypes.data_as(ctypes.c_void_p), int(num_workgroups), int(tiles_per_wave),
+                                 _ptr(sink), _stream(stream))
+    _check(rc, "optgqa_stream_probe")
+    return dev
 
 
 def validate_tables_host(block_tables, context_lens, block_size: int, num_blocks: int) -> int:

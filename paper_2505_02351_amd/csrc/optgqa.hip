@@ -10,6 +10,7 @@
 #include "decode_mma_kernels.hpp"
 #include "decode_flat_kernels.hpp"
 #include "prefill_kernels.hpp"
+#include "probe_kernels.hpp"
 
 using namespace optgqa;
 
@@ -684,6 +685,24 @@ int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const vo
     p.block_size = block_size;
     p.max_blocks_per_seq = max_blocks_per_seq;
     return launch_prefill(p, num_seqs, max_q_len, head_dim, dtype, static_cast<hipStream_t>(stream));
+}
+
+int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_bytes,
+                        const int32_t* tile_list, const int32_t* tile_list_host, int num_workgroups,
+                        int tiles_per_wave, void* sink, void* stream)
+{
+    if (num_workgroups <= 0 || tiles_per_wave <= 0 || pool_bytes < 4096) return OPTGQA_ERR_SHAPE;
+    if (!k_pool || !v_pool || !tile_list || !tile_list_host || !sink) return OPTGQA_ERR_NULL;
+    if (!aligned16(k_pool) || !aligned16(v_pool) || !aligned16(sink)) return OPTGQA_ERR_UNSUPPORTED;
+    // every listed piece must lie inside the pools: checked here, on the host copy of the list
+    const int64_t pieces = (int64_t)(pool_bytes / 4096);
+    const int64_t n = (int64_t)num_workgroups * 4 * tiles_per_wave;
+    for (int64_t i = 0; i < n; ++i)
+        if (tile_list_host[i] < 0 || tile_list_host[i] >= pieces) return OPTGQA_ERR_TABLE;
+    hipLaunchKernelGGL(stream_probe_kernel, dim3(num_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const unsigned char*>(k_pool), static_cast<const unsigned char*>(v_pool),
+                       tile_list, tiles_per_wave, static_cast<uint4*>(sink));
+    return launch_status();
 }
 
 int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* v_cache,

@@ -88,6 +88,42 @@ def test_argument_errors_before_any_launch(G):
     assert k(one, one, one, one, one, one, 2, 2, 32, 16, 8, 128, 0, None) == -3
 
 
+def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
+    import ctypes
+    import numpy as np
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)
+    # decode step: strides shorter than a token row, missing new rows
+    d = lib.optgqa_decode_step
+    args = lambda k_new=one, ks=128, D=64: (one, one, k_new, one, one, one, one, one, None, 0.1, 2, 8, 2, D, 16, 8, 128,
+                                           ks, 128, None, 0, 0, None)
+    assert d(*args(ks=64)) == -2
+    assert d(*args(k_new=None)) == -1
+    assert d(*args(D=96)) == -3
+    # 8-bit caches: scales must be positive and finite, head_dim 128 only, workspace required
+    a = lib.optgqa_paged_attention_fp8
+    f = lambda ks=1.0, vs=1.0, D=128, ws=None, wsb=0: a(one, one, one, one, one, one, None, 0.1, ks, vs, 2, 8, 2, D, 16,
+                                                        8, 128, ws, wsb, 0, None)
+    assert f(ks=0.0) == -2 and f(vs=-1.0) == -2 and f(ks=float("inf")) == -2 and f(ks=float("nan")) == -2
+    assert f(D=64) == -3
+    assert f() == -4
+    r = lib.optgqa_reshape_and_cache_fp8
+    g = lambda k=one, ks=1.0, stride=256, T=3: r(k, one, one, one, one, T, 2, 128, 16, stride, 256, ks, 1.0, 1, None)
+    assert g(ks=0.0) == -2 and g(stride=100) == -2 and g(stride=260) == -3 and g(k=ctypes.c_void_p(8)) == -3
+    assert g(T=0) == 0
+    # streaming probe: the host copy of the tile list is checked against the pool size
+    p = lib.optgqa_stream_probe
+    lst = np.array([0, 1, 2, 3, 4, 5, 6, 7], np.int32)
+    h = lst.ctypes.data_as(ctypes.c_void_p)
+    lst[5] = 8                                                              # one piece past the pool
+    assert p(one, one, 8 * 4096, one, h, 1, 2, one, None) == -6
+    assert p(one, one, 8 * 4096, one, None, 1, 2, one, None) == -1
+    assert p(one, one, 100, one, h, 1, 2, one, None) == -2
+    # kernel-event hook: both or neither
+    assert lib.optgqa_set_kernel_events(one, None) == -1
+    assert lib.optgqa_set_kernel_events(None, None) == 0
+
+
 def test_workspace_query(G):
     n, P = G.paged_attention_workspace_bytes(4, 64, 8, 128, 16, 32768, 512)
     assert P == 512 and n == 4 * 64 * 64 * (128 + 2) * 4

@@ -524,6 +524,20 @@ def test_fp8_rejects_what_it_cannot_do(U):
         G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 0.0, 1.0, 32, ws)
 
 
+def test_stream_probe_runs_and_checks_its_list(U):
+    import torch
+    import paper_2505_02351_amd as G
+    pool = torch.zeros(64 * 4096, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    lst = np.random.default_rng(0).integers(0, 64, size=2 * 4 * 5).astype(np.int32)
+    G.stream_probe(pool, pool, lst, 2, 5, sink)
+    torch.cuda.synchronize()
+    assert not sink.any()
+    lst[7] = 64
+    with pytest.raises(RuntimeError):
+        G.stream_probe(pool, pool, lst, 2, 5, sink)
+
+
 # ------------------------------------------------------------------ the workloads themselves
 @pytest.mark.parametrize("name", ["C1", "C2"])
 def test_decode_workload_full(U, oracle, name):
