@@ -13,15 +13,29 @@
 //   flat order F(b, y, tau) = Y * P_b + y * n_b + tau,  P_b = sum_{b' < b} n_b',  T = Y * P_B
 //   unit u     (one wave) owns flat tiles [u*c, min((u+1)*c, T)),  c = ceil(T / U)
 //
-// A unit's range is a short list of pieces, each inside one segment; per piece the wave runs the
-// same register-prefetched matrix-core loop as the fixed-partition kernel and leaves one partial
-// result (reference, weight sum, un-normalised output) for the combine kernel.  The pairs
+// A unit's range is a short list of pieces, each inside one segment; per piece the wave runs a
+// register-prefetched matrix-core loop (K/V tiles fetched one tile ahead straight into VGPRs, as
+// in the fixed-partition kernel) and leaves one partial result (reference, weight sum,
+// un-normalised output) for the combine kernel.  The pairs
 // (unit, segment) that occur form a staircase, so slot = u + s (s = b*Y + y) numbers them
 // without collisions and without any bookkeeping: at most U + B*Y slots.
 //
 // Nothing is planned on the host (the context lengths live in device memory): every wave scans
 // the context lengths itself (two memory round trips for any batch size), and the wave that
 // processes the first tile of a sequence records P_b for the combine kernel.
+//
+// Arithmetic.  Unlike the fixed-partition kernel (fp32 output MFMAs, 32 per tile), both
+// contractions here are 16-bit MFMAs, computed transposed so that no operand is transposed in
+// registers (the scheme of the tiled prefill kernel): S^T = K Q^T leaves a lane with the scores of
+// four tokens of ONE head, which after the softmax are exactly its slice of the B operand of
+// O^T += V^T P^T; V^T is read with the transposing LDS load from a per-wave LDS copy of the V rows
+// of two tiles.  The output contraction thus runs once per 32 tokens with 8 (fp16) or 16 (bf16)
+// MFMAs of 16 cycles, where the fp32 version spent 64 MFMAs of 32 cycles - measured, that alone
+// was 6 us of a 122 us launch (the matrix pipes' activity slows the stream even though the
+// kernel is memory-bound).  Weights are rounded to the input type for this: fp16 keeps its
+// softmax reference within 2^14 of the running maximum, bf16 splits every weight into head +
+// tail (see prefill_kernels.hpp for the error budget); either way the normaliser is the sum of
+// the weights AS ROUNDED, so the output stays an exact convex combination of V rows.
 #pragma once
 #include <type_traits>
 
@@ -35,6 +49,21 @@ namespace optgqa {
 #ifndef OPTGQA_FLAT_WAVES_PER_SIMD
 #define OPTGQA_FLAT_WAVES_PER_SIMD 2
 #endif
+
+constexpr int kFlatVRow = 128 + 16;      // LDS V row, elements: 288 bytes (see prefill_kernels.hpp, same reason)
+
+// How far the softmax reference may lag behind the running maximum before the accumulators are
+// rescaled, and how far above the maximum it is then put.  16-bit weights: fp16 must keep them
+// inside its range; bf16 has the range but not the precision, so its weights are split in two.
+template <int DT> struct FlatSoftmax;
+template <> struct FlatSoftmax<kF16> {
+    static constexpr float kThreshold = 14.f, kHeadroom = 2.f;
+    static constexpr bool kSplitWeights = false;
+};
+template <> struct FlatSoftmax<kBF16> {
+    static constexpr float kThreshold = kRescaleThreshold, kHeadroom = kRescaleHeadroom;
+    static constexpr bool kSplitWeights = true;
+};
 
 __device__ __forceinline__ int flat_tiles(int L) { return (max(L, 0) + kMmaTile - 1) / kMmaTile; }
 
@@ -59,8 +88,8 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 // 2-byte elements, with one scale per tensor: k_scale is folded into the score scale on the host,
 // v_scale into the combine kernel's normalisation.  A token row is then 128 bytes; a lane's
 // 16-byte K piece holds 16 consecutive dims and feeds two score MFMAs after widening to DT
-// (exact: every E4M3 value is an fp16 and a bf16 number), a lane's 8-byte V piece widens to the
-// same 8 fp32 values per lane as before.  Not combined with FUSED.
+// (exact: every E4M3 value is an fp16 and a bf16 number), a lane's 8-byte V piece widens to 8 DT
+// values on its way into the LDS copy.  Not combined with FUSED.
 struct MmaTile8 {
     uint4 k[2];     // K: token j16, dims 64j + 16hg .. +15
     uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
@@ -77,7 +106,7 @@ template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint
 }
 
 template <int DT, bool FUSED, bool KV8 = false>
-__global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
     static_assert(!(FUSED && KV8), "the fused cache write exists for 2-byte caches only");
     typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
@@ -87,7 +116,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     constexpr int NB = kMmaBufs;
     constexpr int PT = NB - 1;
 
-    __shared__ __attribute__((aligned(16))) float p_lds[kDecodeWaves][TILE][kMmaMaxHeads];
+    // per wave: the V rows of two consecutive tiles (32 tokens) in their natural [token][dim] layout
+    __shared__ __attribute__((aligned(16))) uint16_t v_lds[kDecodeWaves][2 * TILE][kFlatVRow];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -164,8 +194,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
     const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache);
     const float scale2 = p.scale2;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
-    float* const pw_write = &p_lds[wave][j16][4 * hg];
-    const float* const pw_read = &p_lds[wave][hg][j16];
 
     // One 16-token tile of a segment into operand order.  All 16 tokens lie in one physical block;
     // rows past t_last (the piece's last token) re-read that row and are masked out of the scores.
@@ -203,9 +231,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
             }
         }
     };
-    // A operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
-    // 32i + 8hg .. +7 of its head, rows >= GH zero - and the slopes (base 2) of heads 4hg + v.
-    auto load_q = [&](uint4 (&qd)[4], float (&sd)[4], int bb, int yy) __attribute__((always_inline)) {
+    // B operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
+    // 32i + 8hg .. +7 of its head, rows >= GH zero - and that head's slope (base 2).
+    auto load_q = [&](uint4 (&qd)[4], float& sd, int bb, int yy) __attribute__((always_inline)) {
         const int gg = yy / chunks;
         const int hh0 = gg * G + (yy - gg * chunks) * GH;
         // (2-byte caches: MFMA i contracts dims 32i + 8hg .. +7; E4M3 caches: dims
@@ -217,19 +245,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
             const uint4 x = *reinterpret_cast<const uint4*>(qrow + (KV8 ? 64 * (i >> 1) + 8 * (i & 1) : 32 * i));
             qd[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
-        float sl[4] = {0.f, 0.f, 0.f, 0.f};
-        if (p.slopes) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sl[v] = p.slopes[hh0 + min(4 * hg + v, GH - 1)];
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sd[v] = 4 * hg + v < GH ? sl[v] * kLog2e : 0.f;
+        // this lane's scores belong to head j16: one slope
+        float sl = 0.f;
+        if (p.slopes) sl = p.slopes[hh0 + min(j16, GH - 1)];
+        sd = j16 < GH ? sl * kLog2e : 0.f;
     };
 
     static_assert(NB == 2, "the hand-over of the next piece's first tile assumes two register buffers");
     Tile buf[NB];
-    uint4 qa[4], qn[4];
-    float slope2[4], slope2n[4];
+    uint4 qa[4];
+    float slope2;                 // ALiBi slope (base 2) of head j16
     bool chained = false;         // buf[0], qa, slope2 were filled by the previous piece
     int f = f0;
     for (;;) {
@@ -293,101 +318,119 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         const int nt0 = has_next ? 0 : t_begin + j_last * TILE;
         const int64_t nnew_off_k = FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int64_t nnew_off_v = FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
-        load_q(qn, slope2n, nb, ny);
 
-        float m_ref[4], l[4];
-        f32x4 acc[8];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            m_ref[v] = kNoMax;
-            l[v] = 0.f;
-        }
+        // ---- both contractions on 16-bit MFMAs, transposed so that nothing is transposed in registers:
+        //   S^T[token][head] = K Q^T : A = the K tile as fetched (lane (token j16, slab hg)), B = the query
+        //       rows; a lane ends up with the scores of tokens 4hg + v (v = 0..3) for ONE head, j16.
+        //   O^T[dim][head] += V^T P^T over 32 tokens (two tiles): B = this lane's own 8 weights (4 of the
+        //       even tile, 4 of the odd one) rounded to DT; A = V^T, read out of the wave's LDS copy of
+        //       the V rows with the transposing LDS load (see prefill_kernels.hpp for its lane layout).
+        // The output MFMAs therefore run once per two tiles, 8 (fp16) or 16 (bf16, weights split in
+        // a head and a tail) of them, instead of 32 fp32 MFMAs per tile.
+        float m_ref = kNoMax;                 // reference of head j16 (equal in the 4 lanes that share it)
+        float pend[4] = {0.f, 0.f, 0.f, 0.f}; // weights of the even tile, waiting for the odd one
+        f32x4 lsum = f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 acc[8];                         // O^T: dims 16db + 4hg + v of head j16
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // the A operand of the output MFMA reads all 16 head columns: start them finite
-        reinterpret_cast<float4*>(&p_lds[wave][0][0])[lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+        uint16_t* const v_rows = &v_lds[wave][0][0];
+        typedef short i16x4 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
 
-        auto compute_tile = [&](const Tile& Tl, int j) __attribute__((always_inline)) {
-#if defined(OPTGQA_FLAT_ABLATE) && OPTGQA_FLAT_ABLATE == 1
-            // development only: consume the loads without arithmetic
-            uint32_t x = 0;
-            for (int i = 0; i < (KV8 ? 2 : 4); ++i) x ^= Tl.k[i].x ^ Tl.k[i].y ^ Tl.k[i].z ^ Tl.k[i].w;
-            for (int i = 0; i < 4; ++i) x ^= Tl.v[i].x ^ Tl.v[i].y;
-            acc[0][0] += __uint_as_float(x & 0x3fffffffu);
-            l[0] += (float)j;
-            return;
-#endif
+        auto weighted_sum = [&](const float (&w_even)[4], const float (&w_odd)[4]) __attribute__((always_inline)) {
+            uint32_t hi[4], lo[4];
+            hi[0] = narrow2<DT>(w_even[0], w_even[1]);
+            hi[1] = narrow2<DT>(w_even[2], w_even[3]);
+            hi[2] = narrow2<DT>(w_odd[0], w_odd[1]);
+            hi[3] = narrow2<DT>(w_odd[2], w_odd[3]);
+            const uint4 ph = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            uint4 pl = make_uint4(0u, 0u, 0u, 0u);
+            if (FlatSoftmax<DT>::kSplitWeights) {
+                lo[0] = narrow2<DT>(w_even[0] - widen_lo<DT>(hi[0]), w_even[1] - widen_hi<DT>(hi[0]));
+                lo[1] = narrow2<DT>(w_even[2] - widen_lo<DT>(hi[1]), w_even[3] - widen_hi<DT>(hi[1]));
+                lo[2] = narrow2<DT>(w_odd[0] - widen_lo<DT>(hi[2]), w_odd[1] - widen_hi<DT>(hi[2]));
+                lo[3] = narrow2<DT>(w_odd[2] - widen_lo<DT>(hi[3]), w_odd[3] - widen_hi<DT>(hi[3]));
+                pl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+            }
+            // sum of the weights as rounded (the output stays an exact convex combination of V rows)
+            const uint32_t one2 = DT == kF16 ? 0x3c003c00u : 0x3f803f80u;
+            const uint4 ones = make_uint4(one2, one2, one2, one2);
+            lsum = mfma_qk<DT>(ones, ph, lsum);
+            if (FlatSoftmax<DT>::kSplitWeights) lsum = mfma_qk<DT>(ones, pl, lsum);
+            const uint16_t* vrow = v_rows + (4 * hg + (j16 >> 2)) * kFlatVRow + 4 * (j16 & 3);
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                const i16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * db));
+                const i16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * kFlatVRow + 16 * db));
+                const uint2 a0 = __builtin_bit_cast(uint2, r0), a1 = __builtin_bit_cast(uint2, r1);
+                const uint4 va = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                acc[db] = mfma_qk<DT>(va, ph, acc[db]);
+                if (FlatSoftmax<DT>::kSplitWeights) acc[db] = mfma_qk<DT>(va, pl, acc[db]);
+            }
+        };
+
+        auto compute_tile = [&](const Tile& Tl, int j, auto odd_tile) __attribute__((always_inline)) {
+            constexpr bool ODD = decltype(odd_tile)::value;
+            // the tile's V rows go to LDS as they are (rows 16*ODD + 4s + hg, this lane's 8 dims)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                uint4 vr;
+                if constexpr (KV8) vr = widen8_e4m3<DT>(Tl.v[s].x, Tl.v[s].y);
+                else vr = Tl.v[s];
+                *reinterpret_cast<uint4*>(v_rows + (16 * ODD + 4 * s + hg) * kFlatVRow + 8 * j16) = vr;
+            }
             f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if constexpr (KV8) {
                     const uint4 kk = Tl.k[i >> 1];
-                    S = mfma_qk<DT>(qa[i], (i & 1) ? widen8_e4m3<DT>(kk.z, kk.w) : widen8_e4m3<DT>(kk.x, kk.y), S);
+                    S = mfma_qk<DT>((i & 1) ? widen8_e4m3<DT>(kk.z, kk.w) : widen8_e4m3<DT>(kk.x, kk.y), qa[i], S);
                 } else {
-                    S = mfma_qk<DT>(qa[i], Tl.k[i], S);
+                    S = mfma_qk<DT>(Tl.k[i], qa[i], S);
                 }
             }
-            const int t = t_begin + j * TILE + j16;
-            const bool valid = t < t_end;
-            const float rel = (float)(t - Lm1);
-            float s2[4];
+            const int t0 = t_begin + j * TILE + 4 * hg;
+            float x[4];
             bool need = false;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                s2[v] = valid ? fmaf(S[v], scale2, slope2[v] * rel) : -INFINITY;     // eq. (3), base 2
-                need |= s2[v] > m_ref[v] + kRescaleThreshold;
+                const int t = t0 + v;
+                x[v] = t < t_end ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;     // eq. (3), base 2
+                need |= x[v] > m_ref + FlatSoftmax<DT>::kThreshold;
             }
             if (__builtin_amdgcn_ballot_w64(need) != 0) {
+                float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));              // a head's tokens live in 4 lanes (hg)
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m_ref, mx + FlatSoftmax<DT>::kHeadroom);
+                const float alpha = fast_exp2(m_ref - m_new);    // 1 when unchanged, 0 on first use
+                m_ref = m_new;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    const float m_new = fmaxf(m_ref[v], row16_max(s2[v]) + kRescaleHeadroom);
-                    const float alpha = fast_exp2(m_ref[v] - m_new);
-                    m_ref[v] = m_new;
-                    l[v] *= alpha;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[e][v] *= alpha;
+                    lsum[v] *= alpha;
+                    pend[v] *= alpha;
                 }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[e][v] *= alpha;
             }
-            float4 pw;
-            pw.x = fast_exp2(s2[0] - m_ref[0]);                                       // eq. (4) numerators
-            pw.y = fast_exp2(s2[1] - m_ref[1]);
-            pw.z = fast_exp2(s2[2] - m_ref[2]);
-            pw.w = fast_exp2(s2[3] - m_ref[3]);
-            l[0] += pw.x;
-            l[1] += pw.y;
-            l[2] += pw.z;
-            l[3] += pw.w;
-            *reinterpret_cast<float4*>(pw_write) = pw;
-            float a[4];
+            float w[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) a[s] = pw_read[4 * s * kMmaMaxHeads];
+            for (int v = 0; v < 4; ++v) w[v] = fast_exp2(x[v] - m_ref);                               // eq. (4) numerators
+            if constexpr (ODD) {
+                weighted_sum(pend, w);
+            } else {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                float vf[8];
-                if constexpr (KV8) {
-                    const f32x2 v01 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].x, false), v23 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].x, true);
-                    const f32x2 v45 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].y, false), v67 = __builtin_amdgcn_cvt_pk_f32_fp8(Tl.v[s].y, true);
-                    vf[0] = v01[0], vf[1] = v01[1], vf[2] = v23[0], vf[3] = v23[1];
-                    vf[4] = v45[0], vf[5] = v45[1], vf[6] = v67[0], vf[7] = v67[1];
-                } else {
-                    const uint4 vr = Tl.v[s];
-                    vf[0] = widen_lo<DT>(vr.x), vf[1] = widen_hi<DT>(vr.x), vf[2] = widen_lo<DT>(vr.y), vf[3] = widen_hi<DT>(vr.y);
-                    vf[4] = widen_lo<DT>(vr.z), vf[5] = widen_hi<DT>(vr.z), vf[6] = widen_lo<DT>(vr.w), vf[7] = widen_hi<DT>(vr.w);
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[s], vf[e], acc[e], 0, 0, 0);
+                for (int v = 0; v < 4; ++v) pend[v] = w[v];
             }
         };
 
-        // Two tiles per trip; every half issues exactly one tile of loads (no branches around
-        // loads, so the number in flight at each use is a compile-time constant).  The first half
-        // prefetches into buf[1], the second into buf[0]; past the end of the piece the second half
-        // fetches the next piece's first tile, which is therefore always found in buf[0].
         const int trips = (ntw + 1) >> 1;
         for (int it = 0; it < trips; ++it) {
             const int j = 2 * it;
             load_tile(buf[1], table, head_off, t_last, t_begin + min(j + 1, j_last) * TILE, Lm1, new_off_k, new_off_v);
-            compute_tile(buf[0], j);
+            compute_tile(buf[0], j, std::false_type{});
 #ifdef OPTGQA_FLAT_TIMING
             if (tm1 == 0) tm1 = wall_clock64();
 #endif
@@ -395,30 +438,36 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
             load_tile(buf[0], more ? table : ntable, more ? head_off : nhead_off, more ? t_last : nt_last,
                       more ? t_begin + (j + 2) * TILE : nt0, more ? Lm1 : nL - 1, more ? new_off_k : nnew_off_k,
                       more ? new_off_v : nnew_off_v);
-            if (j + 1 <= j_last) compute_tile(buf[1], j + 1);
+            if (j + 1 <= j_last) {
+                compute_tile(buf[1], j + 1, std::true_type{});
+            } else {
+                // odd number of tiles: the last even tile has no partner; give it rows of zeros
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+                    *reinterpret_cast<uint4*>(v_rows + (16 + 4 * s + hg) * kFlatVRow + 8 * j16) = make_uint4(0u, 0u, 0u, 0u);
+                const float none[4] = {0.f, 0.f, 0.f, 0.f};
+                weighted_sum(pend, none);
+            }
         }
 
 #ifdef OPTGQA_FLAT_TIMING
         tm2 = wall_clock64();
 #endif
-        // ---- leave the piece's partial result in slot u + s ----------------------------------
-#pragma unroll
-        for (int v = 0; v < 4; ++v) l[v] = row_group_sum<16>(l[v]);
+        // ---- leave the piece's partial result in slot u + s: this lane holds dims 16db + 4hg + v of
+        // head j16 ----------------------------------------------------------------------------------
         const int64_t slot = (int64_t)u + (int64_t)b * Y + y;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int hh = 4 * hg + v;
-            if (hh < GH) {
-                const int64_t e0 = slot * GH + hh;
-                if (j16 == 0) {
-                    p.ws_m[e0] = m_ref[v];
-                    p.ws_l[e0] = l[v];
-                }
-                float* o = p.ws_o + e0 * D + 8 * j16;
-                *reinterpret_cast<float4*>(o) = make_float4(acc[0][v], acc[1][v], acc[2][v], acc[3][v]);
-                *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4][v], acc[5][v], acc[6][v], acc[7][v]);
+        if (j16 < GH) {
+            const int64_t e0 = slot * GH + j16;
+            if (hg == 0) {
+                p.ws_m[e0] = m_ref;
+                p.ws_l[e0] = lsum[0];
             }
+            float* o = p.ws_o + e0 * D + 4 * hg;
+#pragma unroll
+            for (int db = 0; db < 8; ++db)
+                *reinterpret_cast<float4*>(o + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
         }
+
 
         // ---- next piece ------------------------------------------------------------------------
 #ifdef OPTGQA_FLAT_TIMING
@@ -433,10 +482,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_FLAT_WAVES_PER_SIMD) void
         f += ntw;
         if (y + 1 == Y) P_b += n;                            // sequences skipped on the way have no tiles
         b = nb, y = ny, L = nL, n = nn, tau = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) qa[i] = qn[i];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) slope2[v] = slope2n[v];
+        load_q(qa, slope2, b, y);
         chained = true;
     }
 }
