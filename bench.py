@@ -42,8 +42,8 @@ KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-44
 # factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
 # measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/paged_decode_C3.md: (310526.8 KiB FETCH_SIZE x 2.000 + 5372.0 KiB WRITE_SIZE x 1.000) x 1024
-    "C3": 641459814,
+    # profiles/paged_decode_C3.md: (310421.1 KiB FETCH_SIZE x 2.000 + 5373.0 KiB WRITE_SIZE x 1.000) x 1024
+    "C3": 641244365,
 }
 
 
