@@ -524,6 +524,40 @@ def test_fp8_rejects_what_it_cannot_do(U):
         G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 0.0, 1.0, 32, ws)
 
 
+def test_decode_step_replays_from_a_hip_graph(U, oracle):
+    """The one-call step allocates nothing, synchronises nothing and records no memset, so it can be
+    captured: every replay (with eager steps and synchronisations in between) must reproduce the
+    eager output bit for bit and leave the caches as the oracle's cache write does."""
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="graph", dtype=W.BF16, batch=7, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=32, num_blocks=7 * 30 + 3, ctx_lo=100, ctx_hi=900, seed=17)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    ws, _ = dev.workspace(0)
+    def step():
+        G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                      dev.context_lens, dev.slopes, float(case.scale), case.max_context_len, ws)
+    step()                                   # also does the library's one-off occupancy query
+    torch.cuda.synchronize()
+    eager = dev.out.clone()
+    kc, vc = oracle_filled(oracle, case)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        dev.out.fill_(float("nan"))
+        dev.k_cache.copy_(U.to_dev(case.k_cache, case.dtype))      # back to the image before the step
+        dev.v_cache.copy_(U.to_dev(case.v_cache, case.dtype))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dev.out, eager), rep
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), rep
+        step()                               # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(dev.out, eager), rep
+
+
 def test_stream_probe_runs_and_checks_its_list(U):
     import torch
     import paper_2505_02351_amd as G
