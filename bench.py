@@ -39,10 +39,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
 KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-448 covers +-5.6 sigma
 # HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# factor a plain copy kernel of known size reads on the same counters (profiles/).  None until
+# factor a plain copy kernel of known size reads on the same counters.  None until
 # measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/paged_decode_C3.md: (310421.1 KiB FETCH_SIZE x 2.000 + 5373.0 KiB WRITE_SIZE x 1.000) x 1024
+    # from the committed rocprofv3 counter summary of this workload: (310421.1 KiB FETCH_SIZE x 2.000 + 5373.0 KiB WRITE_SIZE x 1.000) x 1024
     "C3": 641244365,
 }
 
@@ -148,7 +148,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(how the path would shard is described in DESIGN.md)", file=sys.stderr)
+              "(units of work are independent per sequence and KV head; nothing is sharded here)", file=sys.stderr)
         sys.exit(2)
     import torch
     if args.copy_calibration:

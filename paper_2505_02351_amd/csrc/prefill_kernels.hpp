@@ -87,13 +87,6 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
     // head) unit are given the same residue so that its K/V stay in one XCD's L2.
-#ifdef OPTGQA_PF_STAGGER
-    // development: offset the two waves that share a SIMD by part of a tile time
-    if (__builtin_amdgcn_s_getreg(0x1804) & 1) {
-#pragma unroll 1
-        for (int i = 0; i < OPTGQA_PF_STAGGER; ++i) __builtin_amdgcn_s_sleep(8);
-    }
-#endif
     const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
     const int qt = w % p.q_tiles;
     const int unit = (w / p.q_tiles) * 8 + xcd;
