@@ -65,7 +65,14 @@ template <> struct FlatSoftmax<kBF16> {
     static constexpr bool kSplitWeights = true;
 };
 
-__device__ __forceinline__ int flat_tiles(int L) { return (max(L, 0) + kMmaTile - 1) / kMmaTile; }
+// Tiles of one segment of a sequence of length L.  Plain: 16-token tiles of the cache.  FUSED
+// (the step's cache write happens inside the kernel): the tokens already in the cache, L - 1 of
+// them, in 16-token tiles, plus one tile that holds only the new token.
+template <bool FUSED> __device__ __forceinline__ int flat_tiles(int L)
+{
+    if (L <= 0) return 0;
+    return FUSED ? (L - 1 + kMmaTile - 1) / kMmaTile + 1 : (L + kMmaTile - 1) / kMmaTile;
+}
 
 __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 {
@@ -79,10 +86,11 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 
 //
 // FUSED: the kernel also performs the step's cache write (Alg. 2 stores the new K/V, then attends
-// over the cache).  The new token of sequence b is its last one; whichever wave handles the tile
-// that contains it takes that row from k_new / v_new instead of the cache (a per-lane pointer
-// select), and the wave that finishes a KV head's segment copies the row into the cache.  No
-// wave reads that cache row during the launch, so there is nothing to order.
+// over the cache).  The new token of sequence b is its last one; it is given a tile of its own at
+// the end of every segment (so the tiles of the cache cover positions 0 .. L - 2 only), which the
+// wave that gets it reads from k_new / v_new - a wave-uniform choice of base address, nothing per
+// lane - and the wave that finishes a KV head's segment copies the row into the cache.  No wave
+// reads that cache row during the launch, so there is nothing to order.
 //
 // KV8: the caches hold 1-byte E4M3 codes (largest finite value 448, no infinities) instead of
 // 2-byte elements, with one scale per tensor: k_scale is folded into the score scale on the host,
@@ -113,8 +121,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     constexpr int D = 128;
     constexpr int TILE = kMmaTile;
-    constexpr int NB = kMmaBufs;
-    constexpr int PT = NB - 1;
+    static_assert(kMmaBufs == 2, "two register tile buffers: one in use, one in flight");
 
     // per wave: the V rows of two consecutive tiles (32 tokens) in their natural [token][dim] layout
     __shared__ __attribute__((aligned(16))) uint16_t v_lds[kDecodeWaves][2 * TILE][kFlatVRow];
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     for (int i = 0; i < k; ++i) {
         const int idx = lane * k + i;
         my_len = idx < B ? ctx[idx] : 0;
-        mine += flat_tiles(my_len);
+        mine += flat_tiles<FUSED>(my_len);
     }
     const int incl = wave_inclusive_scan(mine, lane);
     const int P_total = __builtin_amdgcn_readlane(incl, 63);
@@ -167,7 +174,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         L = 0;
         for (int base = 0; base < k; base += 64) {
             const int idx = cl * k + base + lane;
-            const int nl = flat_tiles(base + lane < k && idx < B ? ctx[idx] : 0);
+            const int nl = flat_tiles<FUSED>(base + lane < k && idx < B ? ctx[idx] : 0);
             const int inc2 = wave_inclusive_scan(nl, lane);
             const int tot = __builtin_amdgcn_readlane(inc2, 63);
             if (Y * (P_b + tot) > f0) {
@@ -192,43 +199,62 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
     const unsigned char* __restrict__ kc = static_cast<const unsigned char*>(p.k_cache);
     const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache);
+    const unsigned char* __restrict__ k_new = static_cast<const unsigned char*>(p.k_new);
+    const unsigned char* __restrict__ v_new = static_cast<const unsigned char*>(p.v_new);
     const float scale2 = p.scale2;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
 
-    // One 16-token tile of a segment into operand order.  All 16 tokens lie in one physical block;
-    // rows past t_last (the piece's last token) re-read that row and are masked out of the scores.
-    const uint16_t* __restrict__ k_new = static_cast<const uint16_t*>(p.k_new);
-    const uint16_t* __restrict__ v_new = static_cast<const uint16_t*>(p.v_new);
-    // (new_pos, new_off_k, new_off_v: position of the segment's new token and where its K / V
-    // rows start in k_new / v_new; only read when FUSED)
-    auto load_tile = [&](Tile& Tl, const int32_t* tab, int64_t head_off, int t_last, int tile_t0,
-                         int new_pos, int64_t new_off_k, int64_t new_off_v) __attribute__((always_inline)) {
-        // through the scalar cache: a vector load here would make the wave wait for every tile
-        // load still in flight before it could read the block number
-        const int blk = scalar_load_i32(tab + (tile_t0 >> bs_shift));
-        const int64_t uni = blk * block_stride + head_off + (int64_t)(tile_t0 & (bs - 1)) * D;
-        const int tk = min(tile_t0 + j16, t_last) - tile_t0;
+    // Where a tile comes from, in wave-uniform terms: the byte address of its first K / V row, the
+    // last row that exists (later rows re-read it and are masked out of the scores), and the tokens
+    // it stands for.  A regular tile is 16 consecutive tokens of one physical block.  FUSED: the
+    // last tile of a segment is the new token alone, read from k_new / v_new (row 0, nothing else).
+    struct TileSrc {
+        const unsigned char* k;
+        const unsigned char* v;
+        int last_row;           // >= 0
+        int tok0, tok_end;      // row r is token tok0 + r, valid if < tok_end
+    };
+    // (segment: block table row, element offset of the KV head inside a block, length, tiles;
+    //  reg_end: end of the regular tokens the piece covers; new_k / new_v: element offsets of the
+    //  sequence's new rows in k_new / v_new, FUSED only)
+    auto tile_src = [&](const int32_t* tab, int64_t head_off, int Lseg, int nseg, int reg_end,
+                        int64_t new_k, int64_t new_v, int ti) __attribute__((always_inline)) {
+        TileSrc s;
+        if (FUSED && ti == nseg - 1) {
+            s.k = k_new + new_k * 2;
+            s.v = v_new + new_v * 2;
+            s.last_row = 0;
+            s.tok0 = Lseg - 1;
+            s.tok_end = Lseg;
+        } else {
+            const int t0 = ti * TILE;
+            // through the scalar cache: a vector load here would make the wave wait for every tile
+            // load still in flight before it could read the block number
+            const int blk = scalar_load_i32(tab + (t0 >> bs_shift));
+            const int64_t uni = blk * block_stride + head_off + (int64_t)(t0 & (bs - 1)) * D;
+            s.k = kc + uni * ES;
+            s.v = vc + uni * ES;
+            s.last_row = max(reg_end - 1 - t0, 0);
+            s.tok0 = t0;
+            s.tok_end = reg_end;
+        }
+        return s;
+    };
+    // The tile's bytes into operand order: no branches, rows clamped.
+    auto load_tile = [&](Tile& Tl, const TileSrc& s) __attribute__((always_inline)) {
+        const unsigned char* ka = s.k + min(j16, s.last_row) * (D * ES) + 16 * hg;
         if constexpr (KV8) {
-            const unsigned char* ka = kc + uni + tk * D + 16 * hg;
 #pragma unroll
             for (int j = 0; j < 2; ++j) Tl.k[j] = *reinterpret_cast<const uint4*>(ka + 64 * j);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-                Tl.v[s] = *reinterpret_cast<const uint2*>(vc + uni + tv * D + 8 * j16);
-            }
+            for (int r = 0; r < 4; ++r)
+                Tl.v[r] = *reinterpret_cast<const uint2*>(s.v + min(4 * r + hg, s.last_row) * D + 8 * j16);
         } else {
-            const unsigned char* ka = kc + (uni + tk * D + 8 * hg) * ES;
-            if (FUSED && tile_t0 + tk == new_pos) ka = reinterpret_cast<const unsigned char*>(k_new + new_off_k + 8 * hg);
 #pragma unroll
             for (int i = 0; i < 4; ++i) Tl.k[i] = *reinterpret_cast<const uint4*>(ka + 64 * i);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-                const unsigned char* va = vc + (uni + tv * D + 8 * j16) * ES;
-                if (FUSED && tile_t0 + tv == new_pos) va = reinterpret_cast<const unsigned char*>(v_new + new_off_v + 8 * j16);
-                Tl.v[s] = *reinterpret_cast<const uint4*>(va);
-            }
+            for (int r = 0; r < 4; ++r)
+                Tl.v[r] = *reinterpret_cast<const uint4*>(s.v + min(4 * r + hg, s.last_row) * (D * 2) + 16 * j16);
         }
     };
     // B operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
@@ -245,36 +271,35 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             const uint4 x = *reinterpret_cast<const uint4*>(qrow + (KV8 ? 64 * (i >> 1) + 8 * (i & 1) : 32 * i));
             qd[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
-        // this lane's scores belong to head j16: one slope
         float sl = 0.f;
         if (p.slopes) sl = p.slopes[hh0 + min(j16, GH - 1)];
         sd = j16 < GH ? sl * kLog2e : 0.f;
     };
 
-    static_assert(NB == 2, "the hand-over of the next piece's first tile assumes two register buffers");
-    Tile buf[NB];
+    Tile buf[2];
+    TileSrc d0, d1;               // what buf[0] / buf[1] hold (or are receiving)
     uint4 qa[4];
     float slope2;                 // ALiBi slope (base 2) of head j16
-    bool chained = false;         // buf[0], qa, slope2 were filled by the previous piece
+    bool chained = false;         // buf[0] / d0 were filled by the previous piece
     int f = f0;
     for (;;) {
         // ---- one piece: tiles [tau, tau_end) of segment (b, y) -------------------------------
         const int tau_end = min(n, tau + (f1 - f));
         const int ntw = tau_end - tau;                      // >= 1
         const int j_last = ntw - 1;
-        const int t_begin = tau * TILE;
-        const int t_end = min(L, tau_end * TILE);
-        const int t_last = t_end - 1;
         const int Lm1 = L - 1;
+        // regular (cached) tokens the piece covers end here; FUSED: the segment's last tile is the new token
+        const int reg_end = FUSED ? min(Lm1, (tau_end == n ? tau_end - 1 : tau_end) * TILE) : min(L, tau_end * TILE);
         const int g = y / chunks;
         const int32_t* table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
-        const int64_t new_off_k = FUSED ? b * p.k_new_stride + (int64_t)g * D : 0;
-        const int64_t new_off_v = FUSED ? b * p.v_new_stride + (int64_t)g * D : 0;
+        const int64_t new_k = FUSED ? b * p.k_new_stride + (int64_t)g * D : 0;
+        const int64_t new_v = FUSED ? b * p.v_new_stride + (int64_t)g * D : 0;
 
+        load_q(qa, slope2, b, y);
         if (!chained) {
-            load_q(qa, slope2, b, y);
-            load_tile(buf[0], table, head_off, t_last, t_begin, Lm1, new_off_k, new_off_v);
+            d0 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau);
+            load_tile(buf[0], d0);
         }
         if (FUSED && tau_end == n && y == g * chunks) {
             // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
@@ -282,7 +307,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
             if (lane < 32) {
                 const int piece = 8 * (lane & 15);
-                const uint16_t* src = lane < 16 ? k_new + new_off_k + piece : v_new + new_off_v + piece;
+                const unsigned char* src = lane < 16 ? k_new + (new_k + piece) * 2 : v_new + (new_v + piece) * 2;
                 uint16_t* dstp = (lane < 16 ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + dst + piece;
                 *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
             }
@@ -293,9 +318,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             if (f == 0) p.plan[B] = c;
         }
 
-        // ---- the piece after this one (same unit), so that its first tile and its query rows are
-        // on their way before this piece ends.  Without one, the spare prefetch slot re-reads this
-        // piece's last tile (a cache hit, never consumed).
+        // ---- the piece after this one (same unit), so that its first tile is on its way before this
+        // piece ends.  Without one, the spare prefetch slot re-reads this piece's last tile (a cache
+        // hit, never consumed).
         bool has_next = f + ntw < f1;                        // then this piece ends its segment
         int nb = b, ny = y, nL = L, nn = n;
         if (has_next) {
@@ -304,7 +329,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 do {                                         // skip sequences without tokens
                     ++nb;
                     nL = scalar_load_i32(ctx + nb);
-                    nn = flat_tiles(nL);
+                    nn = flat_tiles<FUSED>(nL);
                 } while (nn == 0 && nb + 1 < B);
                 if (nn == 0) {                               // cannot happen for consistent lengths
                     has_next = false;
@@ -312,12 +337,18 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 }
             }
         }
-        const int32_t* ntable = has_next ? p.block_tables + (int64_t)nb * p.max_blocks_per_seq : table;
-        const int64_t nhead_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
-        const int nt_last = has_next ? min(nL, min(nn, f1 - (f + ntw)) * TILE) - 1 : t_last;
-        const int nt0 = has_next ? 0 : t_begin + j_last * TILE;
-        const int64_t nnew_off_k = FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
-        const int64_t nnew_off_v = FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
+        // arguments of tile_src for "the tile after this piece": the next piece's first one, or
+        // (nothing follows) this piece's last one again
+        const int n_tau_end = min(nn, f1 - (f + ntw));
+        const int32_t* x_table = has_next ? p.block_tables + (int64_t)nb * p.max_blocks_per_seq : table;
+        const int64_t x_head_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
+        const int x_L = has_next ? nL : L, x_n = has_next ? nn : n;
+        const int x_reg_end = !has_next ? reg_end
+                              : FUSED ? min(nL - 1, (n_tau_end == nn ? n_tau_end - 1 : n_tau_end) * TILE)
+                                      : min(nL, n_tau_end * TILE);
+        const int64_t x_new_k = !has_next ? new_k : FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
+        const int64_t x_new_v = !has_next ? new_v : FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
+        const int x_ti = has_next ? 0 : tau + j_last;
 
         // ---- both contractions on 16-bit MFMAs, transposed so that nothing is transposed in registers:
         //   S^T[token][head] = K Q^T : A = the K tile as fetched (lane (token j16, slab hg)), B = the query
@@ -369,15 +400,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             }
         };
 
-        auto compute_tile = [&](const Tile& Tl, int j, auto odd_tile) __attribute__((always_inline)) {
+        auto compute_tile = [&](const Tile& Tl, const TileSrc& src, auto odd_tile) __attribute__((always_inline)) {
             constexpr bool ODD = decltype(odd_tile)::value;
-            // the tile's V rows go to LDS as they are (rows 16*ODD + 4s + hg, this lane's 8 dims)
+            // the tile's V rows go to LDS as they are (rows 16*ODD + 4r + hg, this lane's 8 dims)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int r = 0; r < 4; ++r) {
                 uint4 vr;
-                if constexpr (KV8) vr = widen8_e4m3<DT>(Tl.v[s].x, Tl.v[s].y);
-                else vr = Tl.v[s];
-                *reinterpret_cast<uint4*>(v_rows + (16 * ODD + 4 * s + hg) * kFlatVRow + 8 * j16) = vr;
+                if constexpr (KV8) vr = widen8_e4m3<DT>(Tl.v[r].x, Tl.v[r].y);
+                else vr = Tl.v[r];
+                *reinterpret_cast<uint4*>(v_rows + (16 * ODD + 4 * r + hg) * kFlatVRow + 8 * j16) = vr;
             }
             f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -389,13 +420,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                     S = mfma_qk<DT>(Tl.k[i], qa[i], S);
                 }
             }
-            const int t0 = t_begin + j * TILE + 4 * hg;
+            const int t0 = src.tok0 + 4 * hg;
             float x[4];
             bool need = false;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int t = t0 + v;
-                x[v] = t < t_end ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;     // eq. (3), base 2
+                x[v] = t < src.tok_end ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;   // eq. (3), base 2
                 need |= x[v] > m_ref + FlatSoftmax<DT>::kThreshold;
             }
             if (__builtin_amdgcn_ballot_w64(need) != 0) {
@@ -426,25 +457,31 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             }
         };
 
+        // Two tiles per trip; every half issues exactly one tile of loads (no branches around
+        // loads, so the number in flight at each use is a compile-time constant).  The first half
+        // prefetches into buf[1], the second into buf[0]; past the end of the piece the second half
+        // fetches the next piece's first tile, which is therefore always found in buf[0].
         const int trips = (ntw + 1) >> 1;
         for (int it = 0; it < trips; ++it) {
             const int j = 2 * it;
-            load_tile(buf[1], table, head_off, t_last, t_begin + min(j + 1, j_last) * TILE, Lm1, new_off_k, new_off_v);
-            compute_tile(buf[0], j, std::false_type{});
+            d1 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau + min(j + 1, j_last));
+            load_tile(buf[1], d1);
+            compute_tile(buf[0], d0, std::false_type{});
 #ifdef OPTGQA_FLAT_TIMING
             if (tm1 == 0) tm1 = wall_clock64();
 #endif
             const bool more = j + 2 <= j_last;
-            load_tile(buf[0], more ? table : ntable, more ? head_off : nhead_off, more ? t_last : nt_last,
-                      more ? t_begin + (j + 2) * TILE : nt0, more ? Lm1 : nL - 1, more ? new_off_k : nnew_off_k,
-                      more ? new_off_v : nnew_off_v);
+            d0 = tile_src(more ? table : x_table, more ? head_off : x_head_off, more ? L : x_L, more ? n : x_n,
+                          more ? reg_end : x_reg_end, more ? new_k : x_new_k, more ? new_v : x_new_v,
+                          more ? tau + j + 2 : x_ti);
+            load_tile(buf[0], d0);
             if (j + 1 <= j_last) {
-                compute_tile(buf[1], j + 1, std::true_type{});
+                compute_tile(buf[1], d1, std::true_type{});
             } else {
                 // odd number of tiles: the last even tile has no partner; give it rows of zeros
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
-                    *reinterpret_cast<uint4*>(v_rows + (16 + 4 * s + hg) * kFlatVRow + 8 * j16) = make_uint4(0u, 0u, 0u, 0u);
+                for (int r = 0; r < 4; ++r)
+                    *reinterpret_cast<uint4*>(v_rows + (16 + 4 * r + hg) * kFlatVRow + 8 * j16) = make_uint4(0u, 0u, 0u, 0u);
                 const float none[4] = {0.f, 0.f, 0.f, 0.f};
                 weighted_sum(pend, none);
             }
@@ -468,7 +505,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 *reinterpret_cast<float4*>(o + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
         }
 
-
         // ---- next piece ------------------------------------------------------------------------
 #ifdef OPTGQA_FLAT_TIMING
         if (!has_next && p.timing && lane == 0) {
@@ -482,7 +518,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         f += ntw;
         if (y + 1 == Y) P_b += n;                            // sequences skipped on the way have no tiles
         b = nb, y = ny, L = nL, n = nn, tau = 0;
-        load_q(qa, slope2, b, y);
         chained = true;
     }
 }
@@ -516,7 +551,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int hh = within - chunk * GH;
     const int Y = p.segs_per_seq;
     const int y = g * chunks + chunk;
-    const int n = flat_tiles(L);
+    const int n = p.k_new ? flat_tiles<true>(L) : flat_tiles<false>(L);      // the numbering the main kernel used
     // (the clamps only matter if the lengths changed under the kernels: they keep every read
     // inside the workspace)
     const int c = max(p.plan[p.num_seqs], 1);
