@@ -271,6 +271,22 @@ def main():
                         "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
                         "launch_ms": launch_ms}
 
+        # the cache write on its own (it is part of every step above; inside the kernel for one-call steps)
+        cw = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+        for a, b in cw:
+            a.record(stream)
+            if e4m3:
+                G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
+            else:
+                G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
+            b.record(stream)
+        torch.cuda.synchronize()
+        cw_ms = np.array([a.elapsed_time(b) for a, b in cw][5:])
+        moved = 2 * case.num_tokens * cfg.num_kv_heads * cfg.head_dim * (3 if e4m3 else 4)   # read + written
+        cache_write = {"entry_point": "optgqa_reshape_and_cache" + ("_fp8" if e4m3 else ""), "tokens": case.num_tokens,
+                       "bytes_moved": moved, "call_ms": float(cw_ms.mean()),
+                       "what": "separate launch, event-timed per call (launch latency included)"}
+
         stream_probe = None
         if decode and not e4m3 and not args.no_stream_probe and cfg.head_dim == 128:
             # The decode kernels' load pattern with no arithmetic, over the same caches: every wave of a
@@ -312,6 +328,7 @@ def main():
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
         }
+        result["cache_write"] = cache_write
         if stream_probe:
             result["stream_probe"] = stream_probe
             result["roofline"]["frac_of_stream_probe"] = roofline["achieved"] / stream_probe["GB/s"]
