@@ -223,3 +223,31 @@ def paged_attention_e4m3(q, k_cache, v_cache, block_tables, context_lens, slopes
                                     ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
                                     ctypes.c_int(DTYPES[dtype]))
     return out
+
+
+def paged_prefill_e4m3(q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, slopes, scale, k_scale,
+                       v_scale, dtype, rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Causal + ALiBi attention of the new tokens over an E4M3 cache, fp64: [T, Hq, D], or [n_rows, D]
+    for listed (query token, head) pairs."""
+    lib = lib or _get()
+    q = _c(q, np.uint16)
+    bt, cl, cu = _c(block_tables, np.int32), _c(context_lens, np.int32), _c(cu_q_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    NB, Hkv, bs, D = k_cache.shape
+    T, Hq, _ = q.shape
+    assert int(cu[-1]) == T
+    if rows is None:
+        n, rt, rh = T * Hq, None, None
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rt, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_prefill_e4m3(_p(out), _p(rt), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                  _p(bt), _p(cl), _p(cu), _p(sl), ctypes.c_float(scale), ctypes.c_float(k_scale),
+                                  ctypes.c_float(v_scale), ctypes.c_int(cl.shape[0]), ctypes.c_int(Hq),
+                                  ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
+                                  ctypes.c_int(DTYPES[dtype]))
+    return out

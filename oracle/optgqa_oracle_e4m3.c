@@ -184,3 +184,33 @@ void oracle_paged_attention_e4m3(double *out, const int32_t *row_seq, const int3
                         num_kv_heads, head_dim, block_size, dtype);
     }
 }
+
+/* Prefill over an E4M3 cache (Alg. 1 prompt branch on dequantised values): query token t of
+ * sequence b sits at position pos = context_lens[b] - q_len_b + (t - cu_q_lens[b]), sees keys
+ * 0..pos and gets the bias slope * (j - pos).  For a list of (query token, head) pairs
+ * (row_token == NULL: all pairs in order, n_rows = total tokens * num_heads); out is [n_rows, D]. */
+void oracle_paged_prefill_e4m3(double *out, const int32_t *row_token, const int32_t *row_head,
+                               int n_rows, const uint16_t *q,
+                               const uint8_t *k_cache, const uint8_t *v_cache,
+                               const int32_t *block_tables, const int32_t *context_lens,
+                               const int32_t *cu_q_lens, const float *alibi_slopes,
+                               float scale, float k_scale, float v_scale, int num_seqs,
+                               int num_heads, int num_kv_heads, int head_dim, int block_size,
+                               int max_blocks_per_seq, int dtype)
+{
+    int group = num_heads / num_kv_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < n_rows; ++r) {
+        int t = row_token ? row_token[r] : r / num_heads;
+        int h = row_token ? row_head[r] : r % num_heads;
+        int b = 0;
+        while (b + 1 < num_seqs && cu_q_lens[b + 1] <= t) ++b;
+        int new_tokens = cu_q_lens[b + 1] - cu_q_lens[b];
+        int pos = context_lens[b] - new_tokens + (t - cu_q_lens[b]);
+        double slope = alibi_slopes ? (double)alibi_slopes[h] : 0.0;
+        attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)t * num_heads + h) * head_dim,
+                        k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,
+                        h / group, slope, (double)scale, (double)k_scale, (double)v_scale,
+                        num_kv_heads, head_dim, block_size, dtype);
+    }
+}

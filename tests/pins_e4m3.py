@@ -181,7 +181,41 @@ def check_scales_enter_where_the_definition_says(lib=None):
             assert np.array_equal(one[b, h], 0.5 * vals[vc8[blk, h // 4, 0, :]])
 
 
+def check_prefill_reduces_to_two_byte_oracle_and_to_decodes(lib=None):
+    """Prefill over the 8-bit cache: equals the 2-byte prefill oracle (pinned separately) on the
+    dequantised cache, and every row equals a decode call whose context ends at that row."""
+    vals = _library_values()
+    cfg = W.small_config(name="e4m3pf", kind="prefill", dtype=W.BF16, batch=3, num_heads=8, num_kv_heads=2,
+                         head_dim=16, block_size=4, num_blocks=64, ctx_lo=9, ctx_hi=37, q_len=7, seed=37)
+    case = W.make_case(cfg)
+    k_scale, v_scale = np.float32(0.25), np.float32(3.0)
+    kc8, vc8, _ = quantised_cache(case, k_scale, v_scale, lib)
+    got = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, k_scale, v_scale, W.BF16, lib=lib)
+    deq = lambda c8: W.to_bits(np.nan_to_num(vals[c8], nan=0.0).astype(np.float32), W.BF16)
+    ref = O.paged_prefill(case.q, deq(kc8), deq(vc8), case.block_tables, case.context_lens, case.cu_q_lens,
+                          case.slopes, np.float32(case.scale * k_scale), W.BF16)
+    np.testing.assert_allclose(got, ref * float(v_scale), rtol=1e-12, atol=1e-12)
+    # row t of sequence b == decode of that query with the context cut after its own position
+    for b in range(cfg.batch):
+        n_b = int(case.q_lens[b])
+        for i in (0, n_b // 2, n_b - 1):
+            t = int(case.cu_q_lens[b]) + i
+            lens = case.context_lens.copy()
+            lens[b] = int(case.context_lens[b]) - n_b + i + 1
+            qd = np.zeros((cfg.batch, 8, 16), np.uint16)
+            qd[b] = case.q[t]
+            dec = O.paged_attention_e4m3(qd, kc8, vc8, case.block_tables, lens, case.slopes, case.scale,
+                                         k_scale, v_scale, W.BF16, lib=lib)
+            np.testing.assert_allclose(got[t], dec[b], rtol=1e-13, atol=1e-13)
+    rows = [(5, 3), (0, 0), (int(case.cu_q_lens[-1]) - 1, 7)]
+    sub = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, k_scale, v_scale, W.BF16, rows=rows, lib=lib)
+    np.testing.assert_allclose(sub, np.stack([got[t, h] for t, h in rows]), rtol=0, atol=0)
+
+
 ALL_CHECKS = [
+    check_prefill_reduces_to_two_byte_oracle_and_to_decodes,
     check_values_match_library_type,
     check_nearest_on_representable_values_and_midpoints,
     check_nearest_matches_library_in_range,

@@ -37,6 +37,9 @@ MUTANTS = {
     "v_scale_dropped": ("for (int d = 0; d < head_dim; ++d) out_row[d] *= v_scale;", ""),
     "bias_scaled_by_k_scale": ("s[j] = scale * k_scale * dot + slope * (double)(j - pos_q);",
                                "s[j] = k_scale * (scale * dot + slope * (double)(j - pos_q));"),
+    "prefill_not_causal": ("block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,\n                        h / group",
+                           "block_tables + (int64_t)b * max_blocks_per_seq, context_lens[b], pos,\n                        h / group"),
+    "prefill_ignores_prefix": ("int pos = context_lens[b] - new_tokens + (t - cu_q_lens[b]);", "int pos = (t - cu_q_lens[b]);"),
     "v_read_from_k": ("out_row[d] += w * e4m3_value(v_cache[at + d]);", "out_row[d] += w * e4m3_value(k_cache[at + d]);"),
 }
 
