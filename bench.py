@@ -82,6 +82,24 @@ def cpu_baseline_e4m3(case, W, n_seqs: int, min_seconds: float = 10.0):
     kc8, vc8 = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
     O.reshape_and_cache_e4m3(k_all, v_all, kc8, vc8, slots, KV_SCALE, KV_SCALE, case.dtype)
     n_seqs = n_seqs if n_seqs > 0 else cfg.batch
+    if cfg.kind != "decode":
+        # as for the 2-byte caches: every 16th (token, head) pair of the first sequence
+        T0 = int(case.cu_q_lens[1])
+        rows = [(t, h) for t in range(T0) for h in range(cfg.num_heads)][::16]
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                 case.slopes, case.scale, KV_SCALE, KV_SCALE, case.dtype, rows=rows)
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= min_seconds or reps >= 1000:
+                break
+        per = dt / reps
+        kv_bytes = 2 * int(case.context_lens[0]) * cfg.num_kv_heads * cfg.head_dim // 16
+        return {"value": kv_bytes / per / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
+                "sample": f"every 16th (query token, head) row of sequence 0 ({len(rows)} rows), E4M3 caches "
+                          f"({kv_bytes / 1e6:.1f} MB of KV per pass, {reps} passes in {dt:.1f} s)",
+                "query_tokens_per_s": T0 / 16.0 / per}
     rows = [(b, h) for b in range(n_seqs) for h in range(cfg.num_heads)]
     reps, t0 = 0, time.perf_counter()
     while True:
@@ -182,7 +200,6 @@ def main():
 
         e4m3 = args.kv_cache == "e4m3"
         if e4m3:
-            assert decode, "--kv-cache e4m3 applies to decode workloads"
             # 8-bit caches of the same logical content, quantised on the GPU from the 2-byte rows of
             # every token but the step's new ones (those are written by the timed step)
             k_old, v_old, slots_old = W.all_token_rows(case, include_new=False)
@@ -190,18 +207,24 @@ def main():
             k8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
             v8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
             from paper_2505_02351_amd.testing import to_dev
-            G.reshape_and_cache_fp8(to_dev(k_old, case.dtype), to_dev(v_old, case.dtype), k8, v8,
-                                    torch.from_numpy(slots_old).cuda(), KV_SCALE, KV_SCALE)
+            if len(slots_old):
+                G.reshape_and_cache_fp8(to_dev(k_old, case.dtype), to_dev(v_old, case.dtype), k8, v8,
+                                        torch.from_numpy(slots_old).cuda(), KV_SCALE, KV_SCALE)
             torch.cuda.synchronize()
             del k_old, v_old
-            ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
+            if decode:
+                ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
         one_call = decode and P == 0 and not e4m3
 
         def step():
             if e4m3:
                 G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
-                G.paged_attention_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.slopes,
-                                      scale, KV_SCALE, KV_SCALE, max_ctx, ws, stream)
+                if decode:
+                    G.paged_attention_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.slopes,
+                                          scale, KV_SCALE, KV_SCALE, max_ctx, ws, stream)
+                else:
+                    G.paged_prefill_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens,
+                                        dev.cu_q_lens, dev.slopes, scale, KV_SCALE, KV_SCALE, case.max_q_len, stream)
                 return
             if one_call:
                 G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
@@ -268,7 +291,8 @@ def main():
             achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
-                        "kernel": "paged_prefill_mma_kernel", "algorithmic_flops_per_launch": flops,
+                        "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else ""),
+                        "algorithmic_flops_per_launch": flops,
                         "launch_ms": launch_ms}
 
         # the cache write on its own (it is part of every step above; inside the kernel for one-call steps)

@@ -178,6 +178,10 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
  * q and out are 2-byte elements of `dtype`.  head_dim 128 only; always the equal-work split, so
  * the workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED, ...) is
  * required (OPTGQA_ERR_WORKSPACE without it).
+ *
+ * optgqa_paged_prefill_fp8: as optgqa_paged_prefill over such caches, same formulas with the
+ * causal bound (query i of sequence b sees keys 0 .. pos_i).  head_dim 128 only
+ * (OPTGQA_ERR_UNSUPPORTED otherwise); no workspace.
  */
 int optgqa_reshape_and_cache_fp8(const void *k, const void *v, void *k_cache, void *v_cache,
                                  const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
@@ -192,6 +196,14 @@ int optgqa_paged_attention_fp8(void *out, const void *q, const void *k_cache, co
                                int block_size, int max_blocks_per_seq, int max_context_len,
                                void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
                                void *stream);
+
+int optgqa_paged_prefill_fp8(void *out, const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *block_tables, const int32_t *context_lens,
+                             const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
+                             float k_scale, float v_scale, int num_seqs, int num_heads,
+                             int num_kv_heads, int head_dim, int block_size,
+                             int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype,
+                             void *stream);
 
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
  * Also reports, when chosen_partition_size is not NULL, the partition size the library would

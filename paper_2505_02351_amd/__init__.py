@@ -64,6 +64,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_attention_fp8.restype = i32
     lib.optgqa_paged_attention_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
                                                i32, i32, vp, sz, i32, vp]
+    lib.optgqa_paged_prefill_fp8.restype = i32
+    lib.optgqa_paged_prefill_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
+                                             i32, i32, i32, vp]
     lib.optgqa_paged_attention_workspace_bytes.restype = sz
     lib.optgqa_paged_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32,
                                                            ctypes.POINTER(ctypes.c_int)]
@@ -246,6 +249,28 @@ def paged_attention_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tenso
                                         int(max_context_len), _ptr(workspace), ws_bytes, _dtype_code(q),
                                         _stream(stream))
     _check(rc, "optgqa_paged_attention_fp8")
+
+
+def paged_prefill_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                      block_tables: torch.Tensor, context_lens: torch.Tensor, cu_q_lens: torch.Tensor,
+                      alibi_slopes: Optional[torch.Tensor], scale: float, k_scale: float, v_scale: float,
+                      max_q_len: int, stream=None) -> None:
+    """optgqa_paged_prefill_fp8: causal + ALiBi attention of the new tokens over E4M3 caches."""
+    lib = load_library()
+    T, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (cu_q_lens, "cu_q_lens")):
+        _dense(t, n)
+    rc = lib.optgqa_paged_prefill_fp8(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                      _ptr(context_lens), _ptr(cu_q_lens), _ptr(alibi_slopes), float(scale),
+                                      float(k_scale), float(v_scale), int(context_lens.shape[0]), Hq, Hkv, D, bs,
+                                      int(block_tables.shape[1]), int(max_q_len), _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_prefill_fp8")
 
 
 def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -90,4 +90,15 @@ template <int LPR> __device__ __forceinline__ float row_group_sum(float x)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// eight E4M3 codes (two dwords) -> eight DT values (one MFMA operand)
+template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint32_t hi)
+{
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+    return make_uint4(narrow2<DT>(a[0], a[1]), narrow2<DT>(b[0], b[1]), narrow2<DT>(c[0], c[1]), narrow2<DT>(d[0], d[1]));
+}
+
+
 }  // namespace optgqa

@@ -103,16 +103,6 @@ struct MmaTile8 {
     uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
 };
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-// eight E4M3 codes (two dwords) -> eight DT values (one MFMA operand)
-template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint32_t hi)
-{
-    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
-    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
-    return make_uint4(narrow2<DT>(a[0], a[1]), narrow2<DT>(b[0], b[1]), narrow2<DT>(c[0], c[1]), narrow2<DT>(d[0], d[1]));
-}
-
 template <int DT, bool FUSED, bool KV8 = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {

@@ -307,9 +307,11 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
 }
 
 // Tiled matrix-core prefill (head_dim 128); other shapes go row by row.
-int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st)
+int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
+                   bool kv8 = false)
 {
     if (head_dim != 128) {
+        if (kv8) return OPTGQA_ERR_UNSUPPORTED;
         const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
         if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
         return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, st);
@@ -328,10 +330,16 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
     KernelEvents ev(st);
-    if (dtype == OPTGQA_F16)
+    if (kv8) {
+        if (dtype == OPTGQA_F16)
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, true>), grid, block, 0, st, p);
+        else
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, true>), grid, block, 0, st, p);
+    } else if (dtype == OPTGQA_F16) {
         hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16>), grid, block, 0, st, p);
-    else
+    } else {
         hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16>), grid, block, 0, st, p);
+    }
     return launch_status();
 }
 
@@ -655,17 +663,21 @@ int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* 
                           workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream), &step);
 }
 
-int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const void* v_cache,
-                         const int32_t* block_tables, const int32_t* context_lens,
-                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
-                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
-                         int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream)
+static int prefill_impl(void* out, const void* q, const void* k_cache, const void* v_cache,
+                        const int32_t* block_tables, const int32_t* context_lens,
+                        const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                        int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                        int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream,
+                        const float* kv_scales)
 {
+    if (kv_scales && (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f))
+        return OPTGQA_ERR_SHAPE;
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_q_len < 0)
         return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    if (kv_scales && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
     if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens) return OPTGQA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
@@ -679,12 +691,37 @@ int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const vo
     p.context_lens = context_lens;
     p.cu_q_lens = cu_q_lens;
     p.slopes = alibi_slopes;
-    p.scale2 = scale * kLog2e;
+    p.scale2 = scale * kLog2e * (kv_scales ? kv_scales[0] : 1.f);
+    p.out_scale = kv_scales ? kv_scales[1] : 1.f;
     p.num_heads = num_heads;
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
     p.max_blocks_per_seq = max_blocks_per_seq;
-    return launch_prefill(p, num_seqs, max_q_len, head_dim, dtype, static_cast<hipStream_t>(stream));
+    return launch_prefill(p, num_seqs, max_q_len, head_dim, dtype, static_cast<hipStream_t>(stream), kv_scales != nullptr);
+}
+
+int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* block_tables, const int32_t* context_lens,
+                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                         int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream)
+{
+    return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
+                        num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
+                        dtype, stream, nullptr);
+}
+
+int optgqa_paged_prefill_fp8(void* out, const void* q, const void* k_cache, const void* v_cache,
+                             const int32_t* block_tables, const int32_t* context_lens,
+                             const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                             float k_scale, float v_scale, int num_seqs, int num_heads,
+                             int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                             int max_q_len, optgqa_dtype dtype, void* stream)
+{
+    const float kv_scales[2] = {k_scale, v_scale};
+    return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
+                        num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
+                        dtype, stream, kv_scales);
 }
 
 int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_bytes,

@@ -43,7 +43,8 @@ struct PrefillParams {
     const int32_t* context_lens;
     const int32_t* cu_q_lens;   // [B + 1]
     const float* slopes;        // [Hq] or nullptr
-    float scale2;               // scale * log2(e)
+    float scale2;               // scale * log2(e) (times k_scale for E4M3 caches)
+    float out_scale;            // multiplies the output (v_scale of an E4M3 cache, else 1)
     int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
     int num_seqs;
     int heads_per_wg;           // GH: query heads per workgroup (divides the group size, <= 16)
@@ -75,10 +76,14 @@ template <> struct PfSoftmax<kBF16> {
 #ifndef OPTGQA_PF_WAVES_PER_SIMD
 #define OPTGQA_PF_WAVES_PER_SIMD 2
 #endif
-template <int DT>
+// KV8: the caches hold 1-byte E4M3 codes with per-tensor scales (k_scale folded into scale2,
+// v_scale into out_scale on the host); the loader threads widen them to DT - exactly - on the
+// way into LDS, everything after that is unchanged.
+template <int DT, bool KV8 = false>
 __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
     constexpr int D = 128;
+    constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     constexpr int RB = kPfRowBlocks;
     // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
     constexpr int kKTile = kPfKeys * kPfKRow, kBuf = kKTile + kPfKeys * kPfVRow;
@@ -116,8 +121,8 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int n16 = lane & 15, hg = lane >> 4;
 
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
-    const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache) + (int64_t)g * bs * D;
-    const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache) + (int64_t)g * bs * D;
+    const unsigned char* __restrict__ kc = static_cast<const unsigned char*>(p.k_cache) + (int64_t)g * bs * D * ES;
+    const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache) + (int64_t)g * bs * D * ES;
     const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
 
@@ -159,15 +164,17 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const bool k_loader = tid < 128;
     const int ld = k_loader ? tid : tid - 128;
     const int l_group = ld >> 4, l_chunk = ld & 15;              // keys 4*group .. +3, dims 8*chunk ..
-    const uint16_t* __restrict__ l_src = k_loader ? kc : vc;
+    const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
     const int l_dst = (k_loader ? 0 : kKTile) + 4 * l_group * l_pitch + 8 * l_chunk;
     // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
     // tile t + 2 is on its way to registers; the block id of the next tile to fetch is read one
     // fetch earlier, so a fetch never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
     // no branches around loads, which keeps the compiler's load counting exact.
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a native vector: plain loads and stores
-    u32x4 stage[4];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: plain loads and stores
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef typename std::conditional<KV8, u32x2, u32x4>::type StageT;   // 8 elements of one key
+    StageT stage[4];
     const int last_tile = ntiles - 1;
     auto load_blk = [&](int t) __attribute__((always_inline)) {
         // the four keys of a group share a block (groups are 4-aligned, clamping keeps the block)
@@ -176,20 +183,28 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     };
     int blk_next = load_blk(0);
 
-    auto fetch_tile = [&](u32x4 (&stage)[4], int t) __attribute__((always_inline)) {
+    auto fetch_tile = [&](StageT (&stage)[4], int t) __attribute__((always_inline)) {
         const int key0 = min(t, last_tile) * kPfKeys + 4 * l_group;
-        const uint16_t* src = l_src + blk_next * block_stride + 8 * l_chunk;
+        const unsigned char* src = l_src + (blk_next * block_stride + 8 * l_chunk) * ES;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int key = min(key0 + j, kmax - 1);
-            stage[j] = *reinterpret_cast<const u32x4*>(src + (int64_t)(key & (bs - 1)) * D);
+            stage[j] = *reinterpret_cast<const StageT*>(src + (int64_t)(key & (bs - 1)) * (D * ES));
         }
         blk_next = load_blk(t + 1);
     };
-    auto store_tile = [&](const u32x4 (&stage)[4], int buf) __attribute__((always_inline)) {
+    auto store_tile = [&](const StageT (&stage)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            *reinterpret_cast<u32x4*>(&tile_lds[buf * kBuf + l_dst + j * l_pitch]) = stage[j];
+        for (int j = 0; j < 4; ++j) {
+            u32x4 w;
+            if constexpr (KV8) {
+                const uint4 x = widen8_e4m3<DT>(stage[j][0], stage[j][1]);
+                w = u32x4{x.x, x.y, x.z, x.w};
+            } else {
+                w = stage[j];
+            }
+            *reinterpret_cast<u32x4*>(&tile_lds[buf * kBuf + l_dst + j * l_pitch]) = w;
+        }
     };
 
     const float scale2 = p.scale2;
@@ -312,7 +327,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         lt += __shfl_xor(lt, 16);
         lt += __shfl_xor(lt, 32);
         if (!row_ok[rb]) continue;
-        const float inv = 1.f / lt;
+        const float inv = p.out_scale / lt;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
             uint2 packed;

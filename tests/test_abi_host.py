@@ -111,6 +111,10 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     g = lambda k=one, ks=1.0, stride=256, T=3: r(k, one, one, one, one, T, 2, 128, 16, stride, 256, ks, 1.0, 1, None)
     assert g(ks=0.0) == -2 and g(stride=100) == -2 and g(stride=260) == -3 and g(k=ctypes.c_void_p(8)) == -3
     assert g(T=0) == 0
+    pf = lib.optgqa_paged_prefill_fp8
+    e = lambda ks=1.0, D=128, B=2, cu=one: pf(one, one, one, one, one, one, cu, None, 0.1, ks, 1.0, B, 8, 2, D, 16, 8,
+                                             32, 0, None)
+    assert e(ks=0.0) == -2 and e(D=64) == -3 and e(cu=None) == -1 and e(B=0) == 0
     # streaming probe: the host copy of the tile list is checked against the pool size
     p = lib.optgqa_stream_probe
     lst = np.array([0, 1, 2, 3, 4, 5, 6, 7], np.int32)

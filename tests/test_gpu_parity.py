@@ -506,6 +506,64 @@ def test_fp8_decode_workload_sampled(U, oracle):
     assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
 
 
+@pytest.mark.parametrize("i", [0, 2, 3, 4, 6, 8, 9])
+def test_fp8_prefill(U, oracle, i):
+    """Tiled prefill over 8-bit caches against the oracle's clause (the caches are filled by the
+    quantising cache write on both sides, codes compared bit for bit first)."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    dtype, Hq, Hkv, D, bs, B, lo, hi, qlen = PF[i]
+    if D != 128:
+        pytest.skip("8-bit caches: head_dim 128 only")
+    cfg = W.small_config(name=f"fp8pf{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
+                         ctx_hi=hi, q_len=qlen, seed=950 + i)
+    case = W.make_case(cfg)
+    k_scale, v_scale = 0.0125, 0.02
+    kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    qd = U.to_dev(case.q, dtype)
+    out = torch.full_like(qd, float("nan"))
+    G.paged_prefill_fp8(out, qd, dk, dv, torch.from_numpy(case.block_tables).cuda(),
+                        torch.from_numpy(case.context_lens).cuda(), torch.from_numpy(case.cu_q_lens).cuda(),
+                        torch.from_numpy(case.slopes).cuda(), float(case.scale), k_scale, v_scale, case.max_q_len)
+    torch.cuda.synchronize()
+    ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, k_scale, v_scale, dtype)
+    err = U.max_abs_err(U.to_host(out), ref, dtype)
+    assert err <= U.TOL[dtype], f"max abs err {err}"
+
+
+def test_fp8_prefill_workload_sampled(U, oracle):
+    """The prefill workload (4 x 2048 new tokens, 32/8 heads) over 8-bit caches: sampled rows."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    cfg = W.CONFIGS["C5"]
+    case = W.make_case(cfg)
+    k_scale, v_scale = 0.0125, 0.0125
+    kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    qd = U.to_dev(case.q, case.dtype)
+    out = torch.full_like(qd, float("nan"))
+    G.paged_prefill_fp8(out, qd, dk, dv, torch.from_numpy(case.block_tables).cuda(),
+                        torch.from_numpy(case.context_lens).cuda(), torch.from_numpy(case.cu_q_lens).cuda(),
+                        torch.from_numpy(case.slopes).cuda(), float(case.scale), k_scale, v_scale, case.max_q_len)
+    torch.cuda.synchronize()
+    got = U.to_host(out)
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    rng = np.random.default_rng(99)
+    T = case.num_tokens
+    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (T // 2, 17)]
+    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
+    ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, k_scale, v_scale, case.dtype, rows=rows)
+    sub = np.stack([got[t, h] for t, h in rows])
+    err = U.max_abs_err(sub, ref, case.dtype)
+    assert err <= U.TOL[case.dtype], err
+
+
 def test_fp8_rejects_what_it_cannot_do(U):
     import torch
     import paper_2505_02351_amd as G
@@ -516,6 +574,9 @@ def test_fp8_rejects_what_it_cannot_do(U):
     ws = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
     with pytest.raises(RuntimeError):                    # head_dim 64
         G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 1.0, 1.0, 32, ws)
+    cu = torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 64, prefill
+        G.paged_prefill_fp8(torch.empty_like(q), q, c8, c8, bt, cl, cu, None, 0.1, 1.0, 1.0, 1)
     q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
     c8 = torch.zeros(4, 2, 16, 128, dtype=torch.uint8, device="cuda")
     with pytest.raises(RuntimeError):                    # no workspace
