@@ -17,18 +17,20 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "optgqa_oracle.c")
 _SRC_E4M3 = os.path.join(_HERE, "optgqa_oracle_e4m3.c")        # 8-bit KV-cache variant
+_SRC_WINDOW = os.path.join(_HERE, "optgqa_oracle_window.c")    # causal + sliding-window masks
 _LIB = os.path.join(_HERE, "liboptgqa_oracle.so")
 
 DTYPES = {"f16": 0, "bf16": 1}
 
 
-def build(src: str = _SRC, out: str = _LIB, force: bool = True, src_e4m3: str = _SRC_E4M3) -> str:
+def build(src: str = _SRC, out: str = _LIB, force: bool = True, src_e4m3: str = _SRC_E4M3,
+          src_window: str = _SRC_WINDOW) -> str:
     """Compile the oracle with gcc (OpenMP over independent (sequence, head) rows)."""
-    newest = max(os.path.getmtime(src), os.path.getmtime(src_e4m3))
+    newest = max(os.path.getmtime(src), os.path.getmtime(src_e4m3), os.path.getmtime(src_window))
     if force or not os.path.exists(out) or os.path.getmtime(out) < newest:
         tmp = out + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
-                               "-ffp-contract=off", "-o", tmp, src, src_e4m3, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, src, src_e4m3, src_window, "-lm"])
         os.replace(tmp, out)
     return out
 
@@ -250,4 +252,53 @@ def paged_prefill_e4m3(q, k_cache, v_cache, block_tables, context_lens, cu_q_len
                                   ctypes.c_float(v_scale), ctypes.c_int(cl.shape[0]), ctypes.c_int(Hq),
                                   ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
                                   ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# causal + sliding-window masks: optgqa_oracle_window.c
+# ---------------------------------------------------------------------------------------------
+def paged_attention_window(q, k_cache, v_cache, block_tables, context_lens, slopes, scale, window, dtype,
+                           rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Decode attention over the last ``window`` tokens (<= 0: all), fp64: [B, Hq, D], or
+    [n_rows, D] for listed (sequence, head) pairs."""
+    lib = lib or _get()
+    q, bt, cl, sl, Hkv, bs, D = _common(q, k_cache, block_tables, context_lens, slopes)
+    assert v_cache.dtype == np.uint16 and v_cache.flags.c_contiguous
+    B, Hq, _ = q.shape
+    if rows is None:
+        n, rs, rh = B * Hq, None, None
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rs, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_attention_window(_p(out), _p(rs), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                      _p(bt), _p(cl), _p(sl), ctypes.c_float(scale), ctypes.c_int(int(window)),
+                                      ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
+                                      ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+def paged_prefill_window(q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, slopes, scale, window, dtype,
+                         rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Causal attention of the new tokens, each over its last ``window`` keys (<= 0: all), fp64:
+    [T, Hq, D], or [n_rows, D] for listed (query token, head) pairs."""
+    lib = lib or _get()
+    q, bt, cl, sl, Hkv, bs, D = _common(q, k_cache, block_tables, context_lens, slopes)
+    assert v_cache.dtype == np.uint16 and v_cache.flags.c_contiguous
+    cu = _c(cu_q_lens, np.int32)
+    T, Hq, _ = q.shape
+    assert int(cu[-1]) == T
+    if rows is None:
+        n, rt, rh = T * Hq, None, None
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rt, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_prefill_window(_p(out), _p(rt), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                    _p(bt), _p(cl), _p(cu), _p(sl), ctypes.c_float(scale), ctypes.c_int(int(window)),
+                                    ctypes.c_int(cl.shape[0]), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                    ctypes.c_int(bs), ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
     return out
