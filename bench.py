@@ -67,6 +67,9 @@ def parse():
                     help="skip the no-arithmetic streaming measurement over the same caches")
     ap.add_argument("--no-target-check", action="store_true",
                     help="skip the extra C3-all8k measurement (every context 8192: the 'batch 64 / 8k' case)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="> 0: the same workload with a sliding window of this many tokens (local mask of "
+                         "Alg. 1), 2-byte caches; KV bytes and flops count the visible keys only")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
     return ap.parse_args()
@@ -117,9 +120,10 @@ def cpu_baseline_e4m3(case, W, n_seqs: int, min_seconds: float = 10.0):
             "query_tokens_per_s": n_seqs / per}
 
 
-def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0):
+def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0, window: int = 0):
     """The oracle as it stands on the first n_seqs sequences of the batch (all their heads; 0 = the
-    whole batch), repeated until about min_seconds of CPU work has been timed."""
+    whole batch), repeated until about min_seconds of CPU work has been timed.  window > 0: the
+    oracle's local-mask clause (which scores every key and masks afterwards, as the definition says)."""
     import oracle as O
     cfg = case.cfg
     kc, vc = case.k_cache.copy(), case.v_cache.copy()
@@ -132,9 +136,14 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0):
         what = f"first {n_seqs} of {cfg.batch} sequences, all {cfg.num_heads} query heads"
 
         def run():
-            O.paged_attention(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
-                              case.dtype, rows=rows)
-        kv_bytes = 2 * int(lens[:n_seqs].sum()) * cfg.num_kv_heads * cfg.head_dim * 2
+            if window > 0:
+                O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes,
+                                         case.scale, window, case.dtype, rows=rows)
+            else:
+                O.paged_attention(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                  case.dtype, rows=rows)
+        seen = np.minimum(lens[:n_seqs], window) if window > 0 else lens[:n_seqs]
+        kv_bytes = 2 * int(seen.sum()) * cfg.num_kv_heads * cfg.head_dim * 2
         n_q = n_seqs
     else:
         # every 16th (token, head) pair of the first sequence: the oracle re-reads K/V per row
@@ -143,8 +152,12 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0):
         what = f"every 16th (query token, head) row of sequence 0 ({len(rows)} rows)"
 
         def run():
-            O.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
-                            case.scale, case.dtype, rows=rows)
+            if window > 0:
+                O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                       case.slopes, case.scale, window, case.dtype, rows=rows)
+            else:
+                O.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                                case.scale, case.dtype, rows=rows)
         kv_bytes = 2 * int(lens[0]) * cfg.num_kv_heads * cfg.head_dim * 2 // 16
         n_q = T0 / 16.0
     reps, t0 = 0, time.perf_counter()
@@ -157,7 +170,8 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0):
     per = dt / reps
     return {
         "value": kv_bytes / per / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
-        "sample": f"{what} ({kv_bytes / 1e6:.1f} MB of KV per pass, {reps} passes in {dt:.1f} s)",
+        "sample": f"{what}{f', window {window}' if window > 0 else ''} ({kv_bytes / 1e6:.1f} MB of KV per pass, "
+                  f"{reps} passes in {dt:.1f} s)",
         "query_tokens_per_s": n_q / per,
     }
 
@@ -199,6 +213,10 @@ def main():
         stream = torch.cuda.current_stream()
 
         e4m3 = args.kv_cache == "e4m3"
+        window = max(args.window, 0)
+        assert not (e4m3 and window), "--window runs over 2-byte caches"
+        if window and decode:
+            ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
         if e4m3:
             # 8-bit caches of the same logical content, quantised on the GPU from the 2-byte rows of
             # every token but the step's new ones (those are written by the timed step)
@@ -214,7 +232,7 @@ def main():
             del k_old, v_old
             if decode:
                 ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
-        one_call = decode and P == 0 and not e4m3
+        one_call = decode and (P == 0 or window) and not e4m3
 
         def step():
             if e4m3:
@@ -226,6 +244,10 @@ def main():
                     G.paged_prefill_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens,
                                         dev.cu_q_lens, dev.slopes, scale, KV_SCALE, KV_SCALE, case.max_q_len, stream)
                 return
+            if one_call and window:
+                G.decode_step_window(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache,
+                                     dev.block_tables, dev.context_lens, dev.slopes, scale, window, max_ctx, ws, stream)
+                return
             if one_call:
                 G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
                               dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
@@ -234,6 +256,9 @@ def main():
             if decode:
                 G.paged_attention(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
                                   dev.slopes, scale, max_ctx, P, ws, stream)
+            elif window:
+                G.paged_prefill_window(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                                       dev.cu_q_lens, dev.slopes, scale, window, case.max_q_len, stream)
             else:
                 G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
                                 dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
@@ -265,6 +290,9 @@ def main():
 
         ms_per_step = wall * 1e3 / steps
         kv_bytes = case.kv_bytes() // (2 if e4m3 else 1)
+        if window and decode:                      # a query reads min(L, window) tokens of each KV head
+            seen = np.minimum(case.context_lens.astype(np.int64), window)
+            kv_bytes = int(2 * int(seen.sum()) * cfg.num_kv_heads * cfg.head_dim * 2)
         value = kv_bytes / (ms_per_step * 1e-3) / 1e9
         n_q = case.num_tokens
         launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
@@ -272,13 +300,15 @@ def main():
         if decode:
             achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
             if chosen_P == G.SPLIT_BALANCED:
-                kname = "paged_decode_flat_kernel (equal-work split%s)" % (
-                    ", E4M3 caches" if e4m3 else ", cache write fused" if one_call else "")
+                kname = "paged_decode_flat_kernel (equal-work split%s%s)" % (
+                    ", E4M3 caches" if e4m3 else ", cache write fused" if one_call else "",
+                    f", window {window}" if window else "")
             else:
                 kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
             roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.partition_size is None and not e4m3 else None,
+                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)
+                        if args.partition_size is None and not e4m3 and not window else None,
                         "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
         else:
             # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
@@ -287,11 +317,16 @@ def main():
             for b in range(cfg.batch):
                 n_b = int(case.q_lens[b])
                 first = int(case.context_lens[b]) - n_b
-                flops += 4 * cfg.num_heads * cfg.head_dim * (n_b * first + n_b * (n_b + 1) // 2)
+                if window:
+                    visible = np.minimum(np.arange(first, first + n_b, dtype=np.int64) + 1, window).sum()
+                else:
+                    visible = n_b * first + n_b * (n_b + 1) // 2
+                flops += 4 * cfg.num_heads * cfg.head_dim * int(visible)
             achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
-                        "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else ""),
+                        "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else "")
+                                  + (f" (window {window})" if window else ""),
                         "algorithmic_flops_per_launch": flops,
                         "launch_ms": launch_ms}
 
@@ -312,7 +347,7 @@ def main():
                        "what": "separate launch, event-timed per call (launch latency included)"}
 
         stream_probe = None
-        if decode and not e4m3 and not args.no_stream_probe and cfg.head_dim == 128:
+        if decode and not e4m3 and not window and not args.no_stream_probe and cfg.head_dim == 128:
             # The decode kernels' load pattern with no arithmetic, over the same caches: every wave of a
             # one-workgroup-per-CU launch streams an equal share of randomly chosen 16-token pieces
             # (4 KiB of K and 4 KiB of V each), as many bytes as the batch's KV.
@@ -347,7 +382,8 @@ def main():
                        "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
                        "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
                        "calls_per_step": 1 if one_call else 2,
-                       "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype},
+                       "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype,
+                       **({"window": window} if window else {})},
             "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
@@ -359,7 +395,8 @@ def main():
         return result, case
 
     result, case = measure(args.workload, args.steps, args.warmup)
-    if args.workload == "C3" and args.partition_size is None and not args.no_target_check and args.kv_cache == "native":
+    if (args.workload == "C3" and args.partition_size is None and not args.no_target_check
+            and args.kv_cache == "native" and args.window <= 0):
         # the target is worded "batch 64 / 8k context": the same batch with every context at 8192
         extra, _ = measure("C3-all8k", max(args.steps // 2, 1), max(args.warmup // 2, 1))
         result["target_check"] = {
@@ -370,8 +407,10 @@ def main():
             "kv_bytes": extra["config"]["kv_bytes"],
         }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = (cpu_baseline_e4m3 if args.kv_cache == "e4m3" else cpu_baseline)(
-            case, W, args.cpu_sample_seqs)
+        if args.kv_cache == "e4m3":
+            result["cpu_baseline"] = cpu_baseline_e4m3(case, W, args.cpu_sample_seqs)
+        else:
+            result["cpu_baseline"] = cpu_baseline(case, W, args.cpu_sample_seqs, window=max(args.window, 0))
     print(json.dumps(result))
 
 

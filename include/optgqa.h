@@ -234,6 +234,48 @@ int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const vo
                          optgqa_dtype dtype, void *stream);
 
 /*
+ * Local attention (Alg. 1: when no ALiBi slopes are given the bias is built from "causal and
+ * local" masks; eq. (4) adds the mask inside the softmax).  The paper fixes no window size and
+ * no boundary convention; here `window` = W > 0 means that the query at position pos sees
+ * exactly the keys pos - W < j <= pos (all of them while pos + 1 <= W).  The mask composes
+ * with the ALiBi term, which stays relative to the query's position: pass alibi_slopes or NULL.
+ * Blocks that lie wholly before the window are never read.
+ *
+ *   optgqa_paged_attention_window   optgqa_paged_attention restricted to the last W tokens
+ *   optgqa_decode_step_window       optgqa_decode_step (cache write + attention) likewise
+ *   optgqa_paged_prefill_window     optgqa_paged_prefill, every new token with its own window
+ *
+ * head_dim 128 only (OPTGQA_ERR_UNSUPPORTED otherwise); window <= 0 is OPTGQA_ERR_SHAPE (call
+ * the plain entry points for full attention).  The two decode calls always use the equal-work
+ * split: a workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED)
+ * bytes is required (OPTGQA_ERR_WORKSPACE without it).  Other arguments, layouts, ownership
+ * and errors as for the calls they extend.
+ */
+int optgqa_paged_attention_window(void *out, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *block_tables,
+                                  const int32_t *context_lens, const float *alibi_slopes,
+                                  float scale, int window, int num_seqs, int num_heads,
+                                  int num_kv_heads, int head_dim, int block_size,
+                                  int max_blocks_per_seq, int max_context_len, void *workspace,
+                                  size_t workspace_bytes, optgqa_dtype dtype, void *stream);
+
+int optgqa_decode_step_window(void *out, const void *q, const void *k_new, const void *v_new,
+                              void *k_cache, void *v_cache, const int32_t *block_tables,
+                              const int32_t *context_lens, const float *alibi_slopes, float scale,
+                              int window, int num_seqs, int num_heads, int num_kv_heads,
+                              int head_dim, int block_size, int max_blocks_per_seq,
+                              int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
+                              void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                              void *stream);
+
+int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *block_tables, const int32_t *context_lens,
+                                const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
+                                int window, int num_seqs, int num_heads, int num_kv_heads,
+                                int head_dim, int block_size, int max_blocks_per_seq,
+                                int max_q_len, optgqa_dtype dtype, void *stream);
+
+/*
  * Diagnostic: un-page the cache (Section III-A: pages are only a re-arrangement of the
  * sequence).  k_out / v_out are [num_seqs][max_context_len][num_kv_heads][head_dim]; token j of
  * sequence b is copied bit for bit for j < context_lens[b]; other rows are left untouched.

@@ -73,6 +73,15 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_prefill.restype = i32
     lib.optgqa_paged_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                          i32, vp]
+    lib.optgqa_paged_attention_window.restype = i32
+    lib.optgqa_paged_attention_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                                  i32, vp, sz, i32, vp]
+    lib.optgqa_decode_step_window.restype = i32
+    lib.optgqa_decode_step_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32,
+                                              i32, i32, i64, i64, vp, sz, i32, vp]
+    lib.optgqa_paged_prefill_window.restype = i32
+    lib.optgqa_paged_prefill_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32,
+                                                i32, i32, i32, vp]
     lib.optgqa_stream_probe.restype = i32
     lib.optgqa_stream_probe.argtypes = [vp, vp, sz, vp, vp, i32, i32, vp, vp]
     lib.optgqa_gather_kv.restype = i32
@@ -291,6 +300,74 @@ def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_c
                                   Hkv, D, bs, int(block_tables.shape[1]), int(max_q_len), _dtype_code(q),
                                   _stream(stream))
     _check(rc, "optgqa_paged_prefill")
+
+
+def paged_attention_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                           block_tables: torch.Tensor, context_lens: torch.Tensor,
+                           alibi_slopes: Optional[torch.Tensor], scale: float, window: int, max_context_len: int,
+                           workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_paged_attention_window: decode attention over the last ``window`` tokens."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_paged_attention_window(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                           _ptr(context_lens), _ptr(alibi_slopes), float(scale), int(window), B, Hq,
+                                           Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len),
+                                           _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_attention_window")
+
+
+def decode_step_window(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                       k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                       context_lens: torch.Tensor, alibi_slopes: Optional[torch.Tensor], scale: float, window: int,
+                       max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_decode_step_window: the step's cache write and its windowed decode attention."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    if B and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if B else Hkv * D
+    vs = int(v_new.stride(0)) if B else Hkv * D
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_decode_step_window(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale),
+                                       int(window), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
+                                       int(max_context_len), ks, vs, _ptr(workspace), ws_bytes, _dtype_code(q),
+                                       _stream(stream))
+    _check(rc, "optgqa_decode_step_window")
+
+
+def paged_prefill_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                         block_tables: torch.Tensor, context_lens: torch.Tensor, cu_q_lens: torch.Tensor,
+                         alibi_slopes: Optional[torch.Tensor], scale: float, window: int, max_q_len: int,
+                         stream=None) -> None:
+    """optgqa_paged_prefill_window: causal attention of the new tokens, each over its last ``window`` keys."""
+    lib = load_library()
+    T, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (cu_q_lens, "cu_q_lens")):
+        _dense(t, n)
+    B = int(context_lens.shape[0])
+    rc = lib.optgqa_paged_prefill_window(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                         _ptr(context_lens), _ptr(cu_q_lens), _ptr(alibi_slopes), float(scale),
+                                         int(window), B, Hq, Hkv, D, bs, int(block_tables.shape[1]), int(max_q_len),
+                                         _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_prefill_window")
 
 
 def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -65,13 +65,21 @@ template <> struct FlatSoftmax<kBF16> {
     static constexpr bool kSplitWeights = true;
 };
 
-// Tiles of one segment of a sequence of length L.  Plain: 16-token tiles of the cache.  FUSED
-// (the step's cache write happens inside the kernel): the tokens already in the cache, L - 1 of
-// them, in 16-token tiles, plus one tile that holds only the new token.
-template <bool FUSED> __device__ __forceinline__ int flat_tiles(int L)
+// First token a decode query of a sequence of length L sees: with a sliding window of W > 0
+// tokens (Alg. 1, local mask) the last W ones, positions L - W .. L - 1; W <= 0: all of them.
+__device__ __forceinline__ int flat_first_token(int L, int W) { return W > 0 ? max(L - W, 0) : 0; }
+
+// Tiles of one segment of a sequence of length L.  Plain: the 16-token tiles of the cache that
+// hold a visible token (tile indices first_token / 16 .. (L - 1) / 16).  FUSED (the step's cache
+// write happens inside the kernel): the same over the tokens already in the cache, L - 1 of
+// them, plus one tile that holds only the new token.
+template <bool FUSED> __device__ __forceinline__ int flat_tiles(int L, int W)
 {
     if (L <= 0) return 0;
-    return FUSED ? (L - 1 + kMmaTile - 1) / kMmaTile + 1 : (L + kMmaTile - 1) / kMmaTile;
+    const int lo = flat_first_token(L, W);
+    const int reg = FUSED ? L - 1 : L;                          // tokens read from the cache
+    const int regular = reg > lo ? (reg + kMmaTile - 1) / kMmaTile - lo / kMmaTile : 0;
+    return regular + (FUSED ? 1 : 0);
 }
 
 __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
@@ -133,6 +141,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     const int chunks = G / GH;
     const int u = blockIdx.x * kDecodeWaves + wave;
     const int32_t* __restrict__ ctx = p.context_lens;
+    const int W = p.window;
 
     // ---- where does this unit start?  level 1: lane i sums the tiles of sequences [i*k, (i+1)*k)
     const int k = (B + 63) >> 6;
@@ -140,7 +149,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     for (int i = 0; i < k; ++i) {
         const int idx = lane * k + i;
         my_len = idx < B ? ctx[idx] : 0;
-        mine += flat_tiles<FUSED>(my_len);
+        mine += flat_tiles<FUSED>(my_len, W);
     }
     const int incl = wave_inclusive_scan(mine, lane);
     const int P_total = __builtin_amdgcn_readlane(incl, 63);
@@ -164,7 +173,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         L = 0;
         for (int base = 0; base < k; base += 64) {
             const int idx = cl * k + base + lane;
-            const int nl = flat_tiles<FUSED>(base + lane < k && idx < B ? ctx[idx] : 0);
+            const int nl = flat_tiles<FUSED>(base + lane < k && idx < B ? ctx[idx] : 0, W);
             const int inc2 = wave_inclusive_scan(nl, lane);
             const int tot = __builtin_amdgcn_readlane(inc2, 63);
             if (Y * (P_b + tot) > f0) {
@@ -202,11 +211,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const unsigned char* k;
         const unsigned char* v;
         int last_row;           // >= 0
-        int tok0, tok_end;      // row r is token tok0 + r, valid if < tok_end
+        int tok0;               // row r is token tok0 + r ...
+        int rel0, span;         // ... and visible if 0 <= rel0 + r < span (window start .. end of the piece)
     };
     // (segment: block table row, element offset of the KV head inside a block, length, tiles;
     //  reg_end: end of the regular tokens the piece covers; new_k / new_v: element offsets of the
-    //  sequence's new rows in k_new / v_new, FUSED only)
+    //  sequence's new rows in k_new / v_new, FUSED only; ti counts from the segment's first tile,
+    //  the one that holds the first visible token)
     auto tile_src = [&](const int32_t* tab, int64_t head_off, int Lseg, int nseg, int reg_end,
                         int64_t new_k, int64_t new_v, int ti) __attribute__((always_inline)) {
         TileSrc s;
@@ -215,9 +226,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             s.v = v_new + new_v * 2;
             s.last_row = 0;
             s.tok0 = Lseg - 1;
-            s.tok_end = Lseg;
+            s.rel0 = 0;
+            s.span = 1;
         } else {
-            const int t0 = ti * TILE;
+            const int lo = flat_first_token(Lseg, W);
+            const int t0 = (ti + lo / TILE) * TILE;
             // through the scalar cache: a vector load here would make the wave wait for every tile
             // load still in flight before it could read the block number
             const int blk = scalar_load_i32(tab + (t0 >> bs_shift));
@@ -226,7 +239,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
             s.v = vc + uni * ES;
             s.last_row = max(reg_end - 1 - t0, 0);
             s.tok0 = t0;
-            s.tok_end = reg_end;
+            s.rel0 = t0 - lo;
+            s.span = reg_end - lo;
         }
         return s;
     };
@@ -279,7 +293,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const int j_last = ntw - 1;
         const int Lm1 = L - 1;
         // regular (cached) tokens the piece covers end here; FUSED: the segment's last tile is the new token
-        const int reg_end = FUSED ? min(Lm1, (tau_end == n ? tau_end - 1 : tau_end) * TILE) : min(L, tau_end * TILE);
+        const int first = flat_first_token(L, W) / TILE;     // the segment's tiles start at this tile of the cache
+        const int reg_end = FUSED ? min(Lm1, ((tau_end == n ? tau_end - 1 : tau_end) + first) * TILE)
+                                  : min(L, (tau_end + first) * TILE);
         const int g = y / chunks;
         const int32_t* table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
@@ -319,7 +335,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 do {                                         // skip sequences without tokens
                     ++nb;
                     nL = scalar_load_i32(ctx + nb);
-                    nn = flat_tiles<FUSED>(nL);
+                    nn = flat_tiles<FUSED>(nL, W);
                 } while (nn == 0 && nb + 1 < B);
                 if (nn == 0) {                               // cannot happen for consistent lengths
                     has_next = false;
@@ -333,9 +349,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const int32_t* x_table = has_next ? p.block_tables + (int64_t)nb * p.max_blocks_per_seq : table;
         const int64_t x_head_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
         const int x_L = has_next ? nL : L, x_n = has_next ? nn : n;
+        const int n_first = flat_first_token(nL, W) / TILE;
         const int x_reg_end = !has_next ? reg_end
-                              : FUSED ? min(nL - 1, (n_tau_end == nn ? n_tau_end - 1 : n_tau_end) * TILE)
-                                      : min(nL, n_tau_end * TILE);
+                              : FUSED ? min(nL - 1, ((n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE)
+                                      : min(nL, (n_tau_end + n_first) * TILE);
         const int64_t x_new_k = !has_next ? new_k : FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int64_t x_new_v = !has_next ? new_v : FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int x_ti = has_next ? 0 : tau + j_last;
@@ -411,12 +428,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 }
             }
             const int t0 = src.tok0 + 4 * hg;
+            const int r0 = src.rel0 + 4 * hg;
             float x[4];
             bool need = false;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int t = t0 + v;
-                x[v] = t < src.tok_end ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;   // eq. (3), base 2
+                // one unsigned compare covers both ends: rows before the window and rows past the piece
+                const bool visible = (unsigned)(r0 + v) < (unsigned)src.span;
+                x[v] = visible ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;   // eq. (3), base 2
                 need |= x[v] > m_ref + FlatSoftmax<DT>::kThreshold;
             }
             if (__builtin_amdgcn_ballot_w64(need) != 0) {
@@ -541,7 +561,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int hh = within - chunk * GH;
     const int Y = p.segs_per_seq;
     const int y = g * chunks + chunk;
-    const int n = p.k_new ? flat_tiles<true>(L) : flat_tiles<false>(L);      // the numbering the main kernel used
+    const int n = p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);      // the numbering the main kernel used
     // (the clamps only matter if the lengths changed under the kernels: they keep every read
     // inside the workspace)
     const int c = max(p.plan[p.num_seqs], 1);

@@ -115,7 +115,7 @@ constexpr int kFlatMinTiles = OPTGQA_FLAT_MIN_TILES;
 
 size_t round_up4(size_t x) { return (x + 3) / 4 * 4; }
 
-bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len)
+bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int window = 0)
 {
     const int group = num_heads / num_kv_heads;
     const int gh = heads_per_workgroup(group, 128);
@@ -124,8 +124,10 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     if (num_seqs > kMaxRowsPerLaunch) return false;          // the combine kernel's grid.y
     // Flat tile indices are 32-bit.  2^30 tiles would be 8 TiB of cache, so the margin of 2 also
     // covers lengths above the stated bound.
-    const int64_t tiles = segs * ((max_context_len + kMmaTile - 1) / kMmaTile);
-    if (tiles >= (1LL << 30)) return false;
+    if (segs * ((max_context_len + kMmaTile - 1) / kMmaTile) >= (1LL << 30)) return false;
+    // tiles that will be read: with a sliding window at most window + 15 tokens per segment
+    const int seen = window > 0 && window + kMmaTile - 1 < max_context_len ? window + kMmaTile - 1 : max_context_len;
+    const int64_t tiles = segs * ((seen + kMmaTile - 1) / kMmaTile);
     int64_t wgs = (tiles + (int64_t)kDecodeWaves * kFlatMinTiles - 1) / ((int64_t)kDecodeWaves * kFlatMinTiles);
     if (wgs > kFlatMaxWorkgroups) wgs = kFlatMaxWorkgroups;
     if (wgs < 1) wgs = 1;
@@ -141,14 +143,14 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
 }
 
 SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
-                     int max_context_len, int partition_size)
+                     int max_context_len, int partition_size, int window = 0)
 {
     SplitPlan s{0, 1, 0, 0, 0, 0, 0};
     int P = partition_size;
     if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
     // The library's own choice for head_dim 128 is the equal-work split whenever splitting pays.
     if (head_dim == 128 && (partition_size == OPTGQA_SPLIT_BALANCED || (partition_size == 0 && P > 0))) {
-        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len))
+        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len, window))
             return s;
         if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
     }
@@ -303,6 +305,7 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     p.k_cache_w = p.v_cache_w = nullptr;
     p.k_new_stride = p.v_new_stride = 0;
     p.out_scale = 1.f;
+    p.window = 0;
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
@@ -330,7 +333,13 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
     KernelEvents ev(st);
-    if (kv8) {
+    if (p.window > 0) {
+        if (kv8) return OPTGQA_ERR_UNSUPPORTED;
+        if (dtype == OPTGQA_F16)
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, false, true>), grid, block, 0, st, p);
+        else
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, false, true>), grid, block, 0, st, p);
+    } else if (kv8) {
         if (dtype == OPTGQA_F16)
             hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, true>), grid, block, 0, st, p);
         else
@@ -465,8 +474,13 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
                    float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                    int max_blocks_per_seq, int max_context_len, int partition_size, void* workspace,
                    size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step,
-                   const float* kv_scales = nullptr)      // {k_scale, v_scale}: the caches hold E4M3 codes
+                   const float* kv_scales = nullptr,      // {k_scale, v_scale}: the caches hold E4M3 codes
+                   int window = 0)                        // > 0: sliding window (Alg. 1, local mask)
 {
+    if (window > 0) {
+        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
+        partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that knows about windows
+    }
     if (kv_scales) {
         if (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f)
             return OPTGQA_ERR_SHAPE;
@@ -493,7 +507,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (num_heads > 65535) return OPTGQA_ERR_SHAPE;
 
     SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
-                             max_context_len > 0 ? max_context_len : 1, partition_size);
+                             max_context_len > 0 ? max_context_len : 1, partition_size, window);
     if (partition_size == OPTGQA_SPLIT_BALANCED && s.partition_size != OPTGQA_SPLIT_BALANCED)
         return OPTGQA_ERR_UNSUPPORTED;                   // head_dim 64, or sizes beyond 32-bit tile indices
     if (s.partition_size != 0) {
@@ -524,6 +538,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.k_cache_w = p.v_cache_w = nullptr;
     p.k_new_stride = p.v_new_stride = 0;
     p.out_scale = 1.f;
+    p.window = window > 0 ? window : 0;
     if (kv_scales) {
         p.scale2 *= kv_scales[0];
         p.out_scale = kv_scales[1];
@@ -663,12 +678,42 @@ int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* 
                           workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream), &step);
 }
 
+int optgqa_paged_attention_window(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                  const int32_t* block_tables, const int32_t* context_lens,
+                                  const float* alibi_slopes, float scale, int window, int num_seqs,
+                                  int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                  int max_blocks_per_seq, int max_context_len, void* workspace,
+                                  size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    if (window <= 0) return OPTGQA_ERR_SHAPE;
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), nullptr, nullptr, window);
+}
+
+int optgqa_decode_step_window(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                              void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                              const float* alibi_slopes, float scale, int window, int num_seqs,
+                              int num_heads, int num_kv_heads, int head_dim, int block_size,
+                              int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
+                              int64_t v_token_stride, void* workspace, size_t workspace_bytes,
+                              optgqa_dtype dtype, void* stream)
+{
+    if (window <= 0) return OPTGQA_ERR_SHAPE;
+    const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), &step, nullptr, window);
+}
+
 static int prefill_impl(void* out, const void* q, const void* k_cache, const void* v_cache,
                         const int32_t* block_tables, const int32_t* context_lens,
                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                         int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream,
-                        const float* kv_scales)
+                        const float* kv_scales, int window = 0)
 {
     if (kv_scales && (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f))
         return OPTGQA_ERR_SHAPE;
@@ -677,7 +722,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
         return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
-    if (kv_scales && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
+    if ((kv_scales || window > 0) && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;   // tiled kernel only
     if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens) return OPTGQA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;
@@ -693,6 +738,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     p.slopes = alibi_slopes;
     p.scale2 = scale * kLog2e * (kv_scales ? kv_scales[0] : 1.f);
     p.out_scale = kv_scales ? kv_scales[1] : 1.f;
+    p.window = window > 0 ? window : 0;
     p.num_heads = num_heads;
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
@@ -722,6 +768,19 @@ int optgqa_paged_prefill_fp8(void* out, const void* q, const void* k_cache, cons
     return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
                         num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
                         dtype, stream, kv_scales);
+}
+
+int optgqa_paged_prefill_window(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                const int32_t* block_tables, const int32_t* context_lens,
+                                const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                                int window, int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                                int block_size, int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype,
+                                void* stream)
+{
+    if (window <= 0) return OPTGQA_ERR_SHAPE;
+    return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
+                        num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
+                        dtype, stream, nullptr, window);
 }
 
 int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_bytes,

@@ -51,6 +51,7 @@ struct PrefillParams {
     int heads_pow2_shift;       // log2 of GH rounded up to a power of two (row = token * 2^shift + head)
     int q_tiles;                // ceil(max_q_len / tokens per workgroup)
     int units;                  // num_seqs * num_kv_heads * (group / GH)
+    int window;                 // > 0: the query at position pos sees keys pos - window < j <= pos only
 };
 
 constexpr int kPfWaves = 4;
@@ -79,7 +80,7 @@ template <> struct PfSoftmax<kBF16> {
 // KV8: the caches hold 1-byte E4M3 codes with per-tensor scales (k_scale folded into scale2,
 // v_scale into out_scale on the host); the loader threads widen them to DT - exactly - on the
 // way into LDS, everything after that is unchanged.
-template <int DT, bool KV8 = false>
+template <int DT, bool KV8 = false, bool WIN = false>
 __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
     constexpr int D = 128;
@@ -115,6 +116,13 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int pos0 = L - n_b;                                   // position of the sequence's first new token
     const int kmax = pos0 + min(tq0 + tokens_per_wg, n_b);      // keys 0 .. kmax-1 are visible to some row
     const int ntiles = (kmax + kPfKeys - 1) / kPfKeys;
+    // Sliding window (Alg. 1, local mask): the workgroup's first row sits at pos0 + tq0 and sees no
+    // key before kmin, later rows see even fewer of the early keys, so the tiles before kmin's are
+    // never read.
+    // (WIN is a compile-time switch so that the plain causal kernel carries none of this)
+    const int W = WIN ? p.window : 0;
+    const int kmin = W > 0 ? max(pos0 + tq0 - W + 1, 0) : 0;
+    const int kt0 = kmin / kPfKeys;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -129,9 +137,9 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     // This lane's query row in each of the wave's row blocks: B operand of the score MFMAs
     // (row n16, dims 32i + 8hg .. +7), its position, slope and validity.
     uint4 qb[RB][4];
-    float posf[RB], slope2[RB], m_ref[RB], lsum[RB];
+    float posf[RB], lof[RB], slope2[RB], m_ref[RB], lsum[RB];
     int pos[RB];
-    bool row_ok[RB];
+    bool row_ok[RB], started[RB];
     int64_t out_off[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -143,8 +151,10 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         out_off[rb] = qrow;
         pos[rb] = pos0 + tc;
         posf[rb] = (float)pos[rb];
+        lof[rb] = W > 0 ? (float)(pos[rb] - W) : -1.f;           // keys above this one are inside the window
         slope2[rb] = p.slopes ? p.slopes[h0 + hc] * kLog2e : 0.f;
-        m_ref[rb] = 0.f;                                         // the first tile always sets it
+        m_ref[rb] = 0.f;                                         // set by the first tile in which the row sees a key
+        started[rb] = false;
         lsum[rb] = 0.f;
         const uint32_t keep = row_ok[rb] ? 0xffffffffu : 0u;
 #pragma unroll
@@ -175,13 +185,13 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     typedef typename std::conditional<KV8, u32x2, u32x4>::type StageT;   // 8 elements of one key
     StageT stage[4];
-    const int last_tile = ntiles - 1;
+    const int last_tile = ntiles - 1;                             // >= kt0
     auto load_blk = [&](int t) __attribute__((always_inline)) {
         // the four keys of a group share a block (groups are 4-aligned, clamping keeps the block)
         const int key = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
         return table[key >> bs_shift];
     };
-    int blk_next = load_blk(0);
+    int blk_next = load_blk(kt0);
 
     auto fetch_tile = [&](StageT (&stage)[4], int t) __attribute__((always_inline)) {
         const int key0 = min(t, last_tile) * kPfKeys + 4 * l_group;
@@ -240,16 +250,26 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 x[e] = fmaf(st[rb][e >> 2][e & 3], scale2, fmaf(slope2[rb], keyf[e], cm));
-                if (MASKED) x[e] = keyf[e] <= posf[rb] ? x[e] : -INFINITY;
+                if (MASKED) {
+                    const bool visible = WIN ? (keyf[e] <= posf[rb] && keyf[e] > lof[rb]) : keyf[e] <= posf[rb];
+                    x[e] = visible ? x[e] : -INFINITY;
+                }
             }
             float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            if (__builtin_amdgcn_ballot_w64(kt == 0 || mx > PfSoftmax<DT>::kThreshold) != 0) {
+            // Has the row seen a key yet?  Plain causal rows all see key 0 in tile 0, so there the
+            // answer is wave-uniform; with a window a row's first visible key may lie in a later tile.
+            const bool first = WIN ? !started[rb] : kt == 0;
+            if (__builtin_amdgcn_ballot_w64(first || mx > PfSoftmax<DT>::kThreshold) != 0) {
                 mx = fmaxf(mx, __shfl_xor(mx, 16));              // the row's keys live in 4 lanes (hg)
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // move the reference up to kHeadroom above this tile's maximum; it never moves down
-                // (rows with no visible key in the tile, or with lower scores, keep theirs)
-                const float delta = fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
-                const float alpha = fast_exp2(-delta);
+                // The first keys a row sees put its reference kHeadroom above their maximum, wherever
+                // that is (nothing has been accumulated yet); afterwards the reference only moves up
+                // (rows with no visible key in the tile, or with lower scores, keep theirs).
+                const bool sees = mx > -INFINITY;
+                const float delta = first ? (sees ? mx + PfSoftmax<DT>::kHeadroom : 0.f)
+                                          : fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
+                const float alpha = first ? 1.f : fast_exp2(-delta);
+                if (WIN) started[rb] = started[rb] || sees;
                 m_ref[rb] += delta;
                 lsum[rb] *= alpha;
 #pragma unroll
@@ -299,25 +319,29 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
 
-    fetch_tile(stage, 0);
-    store_tile(stage, 0);
-    fetch_tile(stage, 1);
+    fetch_tile(stage, kt0);
+    store_tile(stage, kt0 & 1);
+    fetch_tile(stage, kt0 + 1);
     __syncthreads();
-    // Tiles below the diagonal of every row first (no mask), then the few that touch it.
+    // Tiles wholly inside every row's visible range need no mask: those that end at or below the
+    // first row's position (causal side) and start at or above the last row's window start.
     const int n_unmasked = min(ntiles, max(0, (pos_min + 1) / kPfKeys));
-    int kt = 0;
-    for (; kt < n_unmasked; ++kt) {
-        compute_tile(kt, kt & 1, std::false_type{});
-        if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
-        fetch_tile(stage, kt + 2);
-        __syncthreads();
-    }
-    for (; kt < ntiles; ++kt) {
-        compute_tile(kt, kt & 1, std::true_type{});
-        if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
-        fetch_tile(stage, kt + 2);
-        __syncthreads();
-    }
+    const int n_window_cut = W > 0 ? (max(kmax - W, 0) + kPfKeys - 1) / kPfKeys : 0;
+    // (three plain loops rather than one with a branch in it: the compiler schedules the loads of a
+    // loop whose body is one straight line far better)
+    auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
+        for (int kt = from; kt < to; ++kt) {
+            compute_tile(kt, kt & 1, masked);
+            if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
+            fetch_tile(stage, kt + 2);
+            __syncthreads();
+        }
+    };
+    const int cut_end = max(kt0, min(n_window_cut, n_unmasked));   // tiles cut by some row's window start
+    const int plain_end = max(cut_end, n_unmasked);                // tiles no mask touches
+    if (WIN) run_tiles(kt0, cut_end, std::true_type{});
+    run_tiles(cut_end, plain_end, std::false_type{});
+    run_tiles(plain_end, ntiles, std::true_type{});
 
     // ---- normalise and write: this lane holds dims 16dt + 4hg + v of its row --------------------
     uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);

@@ -69,6 +69,30 @@ class DevCase:
         torch.cuda.synchronize()
         return to_host(self.out)
 
+    def decode_window(self, window, slopes="case", fused=False):
+        """Windowed decode: over filled caches, or (fused) with the step's cache write in the call."""
+        sl = self.slopes if isinstance(slopes, str) else slopes
+        ws = self.workspace(G.SPLIT_BALANCED)[0]
+        self.out.fill_(float("nan"))
+        if fused:
+            G.decode_step_window(self.out, self.q, self.k_new, self.v_new, self.k_cache, self.v_cache,
+                                 self.block_tables, self.context_lens, sl, float(self.case.scale), window,
+                                 self.case.max_context_len, ws)
+        else:
+            G.paged_attention_window(self.out, self.q, self.k_cache, self.v_cache, self.block_tables,
+                                     self.context_lens, sl, float(self.case.scale), window,
+                                     self.case.max_context_len, ws)
+        torch.cuda.synchronize()
+        return to_host(self.out)
+
+    def prefill_window(self, window, slopes="case"):
+        sl = self.slopes if isinstance(slopes, str) else slopes
+        self.out.fill_(float("nan"))
+        G.paged_prefill_window(self.out, self.q, self.k_cache, self.v_cache, self.block_tables, self.context_lens,
+                               self.cu_q_lens, sl, float(self.case.scale), window, self.case.max_q_len)
+        torch.cuda.synchronize()
+        return to_host(self.out)
+
     def prefill(self):
         self.out.fill_(float("nan"))
         G.paged_prefill(self.out, self.q, self.k_cache, self.v_cache, self.block_tables, self.context_lens,

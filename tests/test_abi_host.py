@@ -115,6 +115,17 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     e = lambda ks=1.0, D=128, B=2, cu=one: pf(one, one, one, one, one, one, cu, None, 0.1, ks, 1.0, B, 8, 2, D, 16, 8,
                                              32, 0, None)
     assert e(ks=0.0) == -2 and e(D=64) == -3 and e(cu=None) == -1 and e(B=0) == 0
+    # sliding window: positive windows only, head_dim 128 only, decode needs the workspace
+    wa = lib.optgqa_paged_attention_window
+    f = lambda W=8, D=128: wa(one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, None, 0, 0, None)
+    assert f(W=0) == -2 and f(W=-5) == -2 and f(D=64) == -3 and f() == -4
+    wsx = lib.optgqa_decode_step_window
+    f = lambda W=8, D=128, ks=256: wsx(one, one, one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, ks,
+                                       256, None, 0, 0, None)
+    assert f(W=0) == -2 and f(D=64) == -3 and f(ks=100) == -2 and f() == -4
+    wp = lib.optgqa_paged_prefill_window
+    f = lambda W=8, D=128, B=2, cu=one: wp(one, one, one, one, one, one, cu, None, 0.1, W, B, 8, 2, D, 16, 8, 32, 0, None)
+    assert f(W=0) == -2 and f(D=64) == -3 and f(cu=None) == -1 and f(B=0) == 0
     # streaming probe: the host copy of the tile list is checked against the pool size
     p = lib.optgqa_stream_probe
     lst = np.array([0, 1, 2, 3, 4, 5, 6, 7], np.int32)

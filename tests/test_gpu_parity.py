@@ -585,6 +585,177 @@ def test_fp8_rejects_what_it_cannot_do(U):
         G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 0.0, 1.0, 32, ws)
 
 
+# ------------------------------------------------------------------ sliding window (local mask)
+WINDOWS = [1, 2, 15, 16, 17, 33, 100, 257, 10 ** 6]
+
+
+@pytest.mark.parametrize("i", [2, 3, 4, 5, 7, 9])
+def test_decode_window_sweep(U, oracle, i):
+    """Windowed decode against the oracle's local-mask clause, every window of WINDOWS on the
+    head_dim 128 sweep shapes, both over filled caches and with the cache write in the same call
+    (caches bit-exact); without slopes on one pass (Alg. 1 builds the local mask when there are none)."""
+    import oracle as O
+    dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
+    cfg = W.small_config(name=f"win{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
+                         ctx_hi=hi, seed=1400 + i)
+    case = W.make_case(cfg)
+    kc, vc = oracle_filled(oracle, case)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    for window in WINDOWS:
+        ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                       window, dtype)
+        err = U.max_abs_err(dev.decode_window(window), ref, dtype)
+        assert err <= U.TOL[dtype], f"window {window}: {err}"
+        fresh = U.DevCase(case)
+        err = U.max_abs_err(fresh.decode_window(window, fused=True), ref, dtype)
+        assert err <= U.TOL[dtype], f"window {window}, fused step: {err}"
+        assert np.array_equal(U.to_host(fresh.k_cache), kc) and np.array_equal(U.to_host(fresh.v_cache), vc)
+    ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, None, case.scale, 40, dtype)
+    assert U.max_abs_err(dev.decode_window(40, slopes=None), ref, dtype) <= U.TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_decode_window_edge_lengths(U, oracle, dtype):
+    """Windows that start on / next to tile and block boundaries, contexts shorter than the window,
+    empty sequences, and a batch of more than 64 sequences (two-level scan) in one launch."""
+    import oracle as O
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 48, 49, 63, 64, 65, 255, 256, 257, 512, 1, 0, 300] * 4, np.int32)
+    cfg = W.small_config(name="win_edges", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=len(lens) * 33, ctx_lo=1, ctx_hi=512, seed=1421)
+    case = W.make_case(cfg, context_lens=lens)
+    full = lambda a, shape: (lambda z: (z.__setitem__(lens > 0, a), z)[1])(np.zeros(shape, np.uint16))
+    q_full = full(case.q, (len(lens), 8, 128))
+    k_full = full(case.k_new, (len(lens), 2, 128))
+    v_full = full(case.v_new, (len(lens), 2, 128))
+    kc, vc = oracle_filled(oracle, case)
+    case.q = q_full
+    for window in (1, 16, 17, 32, 48, 250):
+        ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                       window, dtype)
+        dev = U.DevCase(case)
+        dev.k_new, dev.v_new = U.to_dev(k_full, dtype), U.to_dev(v_full, dtype)
+        got = dev.decode_window(window, fused=True)
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+        assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype], window
+        assert not got[lens == 0].any()
+        got = dev.decode_window(window)                      # caches now filled: the plain windowed call
+        assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype], window
+
+
+def test_decode_window_workload_sampled(U, oracle):
+    """The decode workload (batch 64, contexts 6k..8k) with a 1024-token window: sampled rows."""
+    import oracle as O
+    cfg = W.CONFIGS["C3"]
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    got = dev.decode_window(1024, fused=True)
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    rng = np.random.default_rng(7)
+    rows = [(0, 0), (cfg.batch - 1, cfg.num_heads - 1)]
+    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(60)]
+    ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                   1024, case.dtype, rows=rows)
+    sub = np.stack([got[b, h] for b, h in rows])
+    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+
+
+@pytest.mark.parametrize("i", [0, 2, 3, 4, 5, 6, 7, 8, 9])
+def test_prefill_window_sweep(U, oracle, i):
+    import oracle as O
+    dtype, Hq, Hkv, D, bs, B, lo, hi, q_len = PF[i]
+    cfg = W.small_config(name=f"pfwin{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
+                         ctx_hi=hi, q_len=q_len, seed=1500 + i)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    kc, vc = oracle_filled(oracle, case)
+    for window in (1, 7, 31, 32, 33, 64, 150, 10 ** 6):
+        ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                     case.slopes, case.scale, window, dtype)
+        err = U.max_abs_err(dev.prefill_window(window), ref, dtype)
+        assert err <= U.TOL[dtype], f"window {window}: {err}"
+    ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, None,
+                                 case.scale, 20, dtype)
+    assert U.max_abs_err(dev.prefill_window(20, slopes=None), ref, dtype) <= U.TOL[dtype]
+
+
+def test_prefill_window_workload_sampled(U, oracle):
+    """The prefill workload with a 512-key window: sampled rows."""
+    import oracle as O
+    cfg = W.CONFIGS["C5"]
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    kc, vc = oracle_filled(oracle, case)
+    got = dev.prefill_window(512)
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    rng = np.random.default_rng(97)
+    T = case.num_tokens
+    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (513, 7), (T // 2, 17)]
+    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
+    ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                 case.slopes, case.scale, 512, case.dtype, rows=rows)
+    sub = np.stack([got[t, h] for t, h in rows])
+    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_prefill_with_scores_far_below_zero(U, oracle, dtype):
+    """Every score of every row strongly negative (queries opposed to all keys): the softmax
+    reference has to follow the first visible keys down, or the 16-bit weights underflow."""
+    cfg = W.small_config(name="pfneg", kind="prefill", dtype=dtype, batch=2, num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=64, ctx_lo=100, ctx_hi=300, q_len=70, seed=1600)
+    case = W.make_case(cfg)
+    kc, vc = oracle_filled(oracle, case)
+    # keys share a strong common component c; queries point along -c
+    rng = np.random.default_rng(5)
+    c = rng.standard_normal(128).astype(np.float32)
+    kf = W.from_bits(kc, dtype).astype(np.float32)
+    kf = np.nan_to_num(kf) * 0.3 + c
+    kc = W.to_bits(kf, dtype)
+    q = W.to_bits((W.from_bits(case.q, dtype).astype(np.float32) * 0.3 - 3.0 * c).astype(np.float32), dtype)
+    import torch
+    dev = U.DevCase(case)
+    dev.k_cache = U.to_dev(kc, dtype)
+    dev.v_cache = U.to_dev(vc, dtype)
+    dev.q = U.to_dev(q, dtype)
+    ref = oracle.paged_prefill(q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                               case.scale, dtype)
+    assert U.max_abs_err(dev.prefill(), ref, dtype) <= U.TOL[dtype]
+    import oracle as O
+    ref = O.paged_prefill_window(q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                                 case.scale, 50, dtype)
+    assert U.max_abs_err(dev.prefill_window(50), ref, dtype) <= U.TOL[dtype]
+
+
+def test_window_rejects_what_it_cannot_do(U):
+    import torch
+    import paper_2505_02351_amd as G
+    bt = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
+    cl = torch.ones(2, dtype=torch.int32, device="cuda")
+    cu = torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+    q = torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda")
+    c = torch.zeros(4, 2, 16, 64, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 64
+        G.paged_attention_window(torch.empty_like(q), q, c, c, bt, cl, None, 0.1, 8, 32, ws)
+    with pytest.raises(RuntimeError):
+        G.paged_prefill_window(torch.empty_like(q), q, c, c, bt, cl, cu, None, 0.1, 8, 1)
+    q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
+    c = torch.zeros(4, 2, 16, 128, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # no workspace
+        G.paged_attention_window(torch.empty_like(q), q, c, c, bt, cl, None, 0.1, 8, 32, None)
+    with pytest.raises(RuntimeError):                    # window must be positive
+        G.paged_attention_window(torch.empty_like(q), q, c, c, bt, cl, None, 0.1, 0, 32, ws)
+    with pytest.raises(RuntimeError):
+        G.paged_prefill_window(torch.empty_like(q), q, c, c, bt, cl, cu, None, 0.1, 0, 1)
+
+
 def test_decode_step_replays_from_a_hip_graph(U, oracle):
     """The one-call step allocates nothing, synchronises nothing and records no memset, so it can be
     captured: every replay (with eager steps and synchronisations in between) must reproduce the
