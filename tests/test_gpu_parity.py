@@ -536,7 +536,7 @@ def test_fp8_prefill(U, oracle, i):
 
 
 def test_fp8_prefill_workload_sampled(U, oracle):
-    """The prefill workload (4 x 2048 new tokens, 32/8 heads) over 8-bit caches: sampled rows."""
+    """The prefill workload (8 sequences, 512 new tokens after 2048 cached ones) over 8-bit caches: sampled rows."""
     import torch
     import oracle as O
     import paper_2505_02351_amd as G
