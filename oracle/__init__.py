@@ -18,19 +18,21 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "optgqa_oracle.c")
 _SRC_E4M3 = os.path.join(_HERE, "optgqa_oracle_e4m3.c")        # 8-bit KV-cache variant
 _SRC_WINDOW = os.path.join(_HERE, "optgqa_oracle_window.c")    # causal + sliding-window masks
+_SRC_PROMPT = os.path.join(_HERE, "optgqa_oracle_prompt.c")    # whole prompt over its own K/V
 _LIB = os.path.join(_HERE, "liboptgqa_oracle.so")
 
 DTYPES = {"f16": 0, "bf16": 1}
 
 
 def build(src: str = _SRC, out: str = _LIB, force: bool = True, src_e4m3: str = _SRC_E4M3,
-          src_window: str = _SRC_WINDOW) -> str:
+          src_window: str = _SRC_WINDOW, src_prompt: str = _SRC_PROMPT) -> str:
     """Compile the oracle with gcc (OpenMP over independent (sequence, head) rows)."""
-    newest = max(os.path.getmtime(src), os.path.getmtime(src_e4m3), os.path.getmtime(src_window))
+    newest = max(os.path.getmtime(src), os.path.getmtime(src_e4m3), os.path.getmtime(src_window),
+                 os.path.getmtime(src_prompt))
     if force or not os.path.exists(out) or os.path.getmtime(out) < newest:
         tmp = out + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
-                               "-ffp-contract=off", "-o", tmp, src, src_e4m3, src_window, "-lm"])
+                               "-ffp-contract=off", "-o", tmp, src, src_e4m3, src_window, src_prompt, "-lm"])
         os.replace(tmp, out)
     return out
 
@@ -301,4 +303,32 @@ def paged_prefill_window(q, k_cache, v_cache, block_tables, context_lens, cu_q_l
                                     _p(bt), _p(cl), _p(cu), _p(sl), ctypes.c_float(scale), ctypes.c_int(int(window)),
                                     ctypes.c_int(cl.shape[0]), ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D),
                                     ctypes.c_int(bs), ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+# ---------------------------------------------------------------------------------------------
+# whole prompt over its own K / V (caches empty): optgqa_oracle_prompt.c
+# ---------------------------------------------------------------------------------------------
+def prompt_attention(q, k, v, cu_seq_lens, slopes, scale, dtype, rows: Optional[Sequence] = None,
+                     lib=None) -> np.ndarray:
+    """Causal (+ ALiBi) attention of every prompt token over the earlier tokens of its own sequence,
+    from dense q [T, Hq, D], k / v [T, Hkv, D], fp64: [T, Hq, D], or [n_rows, D] for listed
+    (token, head) pairs."""
+    lib = lib or _get()
+    q, k, v = _c(q, np.uint16), _c(k, np.uint16), _c(v, np.uint16)
+    cu = _c(cu_seq_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (T, Hkv, D) and v.shape == (T, Hkv, D) and int(cu[-1]) == T
+    if rows is None:
+        n, rt, rh = T * Hq, None, None
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rt, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_prompt_attention(_p(out), _p(rt), _p(rh), ctypes.c_int(n), _p(q), _p(k), _p(v), _p(cu), _p(sl),
+                                ctypes.c_float(scale), ctypes.c_int(cu.shape[0] - 1), ctypes.c_int(Hq),
+                                ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(DTYPES[dtype]))
     return out
