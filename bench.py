@@ -152,7 +152,10 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0, window: int = 
         what = f"every 16th (query token, head) row of sequence 0 ({len(rows)} rows)"
 
         def run():
-            if window > 0:
+            if cfg.name.endswith("-prompt"):
+                O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale,
+                                   case.dtype, rows=rows)
+            elif window > 0:
                 O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
                                        case.slopes, case.scale, window, case.dtype, rows=rows)
             else:
@@ -234,7 +237,14 @@ def main():
                 ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
         one_call = decode and (P == 0 or window) and not e4m3
 
+        prompt = cfg.name.endswith("-prompt")       # whole prompts, caches empty: one call stores K/V and attends
+        assert not (prompt and (e4m3 or window)), "the whole-prompt workload runs over 2-byte inputs, full causal mask"
+
         def step():
+            if prompt:
+                G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                                 dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
+                return
             if e4m3:
                 G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
                 if decode:
@@ -326,6 +336,7 @@ def main():
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
                         "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else "")
+                                  + (" (K/V from the contiguous inputs, cache write fused)" if prompt else "")
                                   + (f" (window {window})" if window else ""),
                         "algorithmic_flops_per_launch": flops,
                         "launch_ms": launch_ms}
@@ -381,7 +392,7 @@ def main():
                        "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
                        "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
                        "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
-                       "calls_per_step": 1 if one_call else 2,
+                       "calls_per_step": 1 if one_call or prompt else 2,
                        "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype,
                        **({"window": window} if window else {})},
             "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,

@@ -276,6 +276,33 @@ int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, c
                                 int max_q_len, optgqa_dtype dtype, void *stream);
 
 /*
+ * Whole-prompt attention with empty caches (Alg. 1, prompt branch: "Reshape and store K, V into
+ * C_K, C_V", then causal / ALiBi attention computed on the inputs themselves).  Sequence b owns
+ * tokens cu_seq_lens[b] .. cu_seq_lens[b+1] - 1 of q, k, v; token i of a sequence attends to
+ * tokens 0 .. i of the same sequence with bias slope_h * (j - i).  K / V are read from the
+ * contiguous inputs, never from the cache.  With k_cache and v_cache given, the same launch
+ * also stores token i's K / V rows at slot block_tables[b][i / block_size] * block_size +
+ * i % block_size - bit for bit what optgqa_reshape_and_cache does with that slot mapping -
+ * so that later decode steps find them; with both NULL nothing is stored and block_tables,
+ * block_size, max_blocks_per_seq are ignored.
+ *
+ *   out, q          [T][num_heads][head_dim], dense
+ *   k, v            [T][num_kv_heads][head_dim]; token t starts at element t * k_token_stride
+ *                   (resp. v_token_stride): strides >= num_kv_heads * head_dim and multiples of 8
+ *   cu_seq_lens     [num_seqs + 1] int32, cu_seq_lens[0] = 0, T = cu_seq_lens[num_seqs]
+ *   max_seq_len     an upper bound on the sequences' lengths (<= max_blocks_per_seq * block_size
+ *                   when the caches are given)
+ * head_dim 128 only (OPTGQA_ERR_UNSUPPORTED otherwise).  All pointers device memory, 16-byte
+ * aligned; errors as for optgqa_paged_prefill.
+ */
+int optgqa_prompt_prefill(void *out, const void *q, const void *k, const void *v, void *k_cache,
+                          void *v_cache, const int32_t *block_tables, const int32_t *cu_seq_lens,
+                          const float *alibi_slopes, float scale, int num_seqs, int num_heads,
+                          int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                          int max_seq_len, int64_t k_token_stride, int64_t v_token_stride,
+                          optgqa_dtype dtype, void *stream);
+
+/*
  * Diagnostic: un-page the cache (Section III-A: pages are only a re-arrangement of the
  * sequence).  k_out / v_out are [num_seqs][max_context_len][num_kv_heads][head_dim]; token j of
  * sequence b is copied bit for bit for j < context_lens[b]; other rows are left untouched.

@@ -82,6 +82,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_prefill_window.restype = i32
     lib.optgqa_paged_prefill_window.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32,
                                                 i32, i32, i32, vp]
+    lib.optgqa_prompt_prefill.restype = i32
+    lib.optgqa_prompt_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                          i64, i64, i32, vp]
     lib.optgqa_stream_probe.restype = i32
     lib.optgqa_stream_probe.argtypes = [vp, vp, sz, vp, vp, i32, i32, vp, vp]
     lib.optgqa_gather_kv.restype = i32
@@ -368,6 +371,36 @@ def paged_prefill_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tens
                                          int(window), B, Hq, Hkv, D, bs, int(block_tables.shape[1]), int(max_q_len),
                                          _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_paged_prefill_window")
+
+
+def prompt_prefill(out: torch.Tensor, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                   k_cache: Optional[torch.Tensor], v_cache: Optional[torch.Tensor],
+                   block_tables: Optional[torch.Tensor], cu_seq_lens: torch.Tensor,
+                   alibi_slopes: Optional[torch.Tensor], scale: float, max_seq_len: int, stream=None) -> None:
+    """optgqa_prompt_prefill: causal (+ ALiBi) attention of whole prompts over their own K / V, storing
+    K / V into the paged caches in the same launch when the caches are given."""
+    lib = load_library()
+    T, Hq, D = q.shape
+    Hkv = k.shape[1]
+    if out.shape != q.shape or k.shape != (T, Hkv, D) or v.shape != (T, Hkv, D):
+        raise ValueError("optgqa: shape mismatch between q, out, k and v")
+    _dense(out, "out"), _dense(q, "q"), _dense(cu_seq_lens, "cu_seq_lens")
+    if T and (k.stride(-1) != 1 or k.stride(-2) != D or v.stride(-1) != 1 or v.stride(-2) != D):
+        raise ValueError("optgqa: k and v must be dense in their last two dims")
+    ks = int(k.stride(0)) if T else Hkv * D
+    vs = int(v.stride(0)) if T else Hkv * D
+    bs, mb = 0, 0
+    if k_cache is not None:
+        NB, Hkv2, bs, Dk = k_cache.shape
+        if Dk != D or Hkv2 != Hkv or block_tables is None:
+            raise ValueError("optgqa: cache shape / block tables do not match k and v")
+        _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(block_tables, "block_tables")
+        mb = int(block_tables.shape[1])
+    rc = lib.optgqa_prompt_prefill(_ptr(out), _ptr(q), _ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache),
+                                   _ptr(block_tables), _ptr(cu_seq_lens), _ptr(alibi_slopes), float(scale),
+                                   int(cu_seq_lens.shape[0]) - 1, Hq, Hkv, D, int(bs), mb, int(max_seq_len), ks, vs,
+                                   _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_prompt_prefill")
 
 
 def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

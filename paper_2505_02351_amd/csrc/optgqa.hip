@@ -311,10 +311,10 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
 
 // Tiled matrix-core prefill (head_dim 128); other shapes go row by row.
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
-                   bool kv8 = false)
+                   bool kv8 = false, bool contig = false)
 {
     if (head_dim != 128) {
-        if (kv8) return OPTGQA_ERR_UNSUPPORTED;
+        if (kv8 || contig) return OPTGQA_ERR_UNSUPPORTED;
         const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
         if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
         return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, st);
@@ -333,7 +333,13 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
     KernelEvents ev(st);
-    if (p.window > 0) {
+    if (contig) {
+        if (kv8 || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
+        if (dtype == OPTGQA_F16)
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, false, false, true>), grid, block, 0, st, p);
+        else
+            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, false, false, true>), grid, block, 0, st, p);
+    } else if (p.window > 0) {
         if (kv8) return OPTGQA_ERR_UNSUPPORTED;
         if (dtype == OPTGQA_F16)
             hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, false, true>), grid, block, 0, st, p);
@@ -739,6 +745,9 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     p.scale2 = scale * kLog2e * (kv_scales ? kv_scales[0] : 1.f);
     p.out_scale = kv_scales ? kv_scales[1] : 1.f;
     p.window = window > 0 ? window : 0;
+    p.k_in = p.v_in = nullptr;
+    p.k_in_stride = p.v_in_stride = 0;
+    p.k_cache_w = p.v_cache_w = nullptr;
     p.num_heads = num_heads;
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
@@ -781,6 +790,57 @@ int optgqa_paged_prefill_window(void* out, const void* q, const void* k_cache, c
     return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
                         num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
                         dtype, stream, nullptr, window);
+}
+
+int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v, void* k_cache, void* v_cache,
+                          const int32_t* block_tables, const int32_t* cu_seq_lens, const float* alibi_slopes,
+                          float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                          int block_size, int max_blocks_per_seq, int max_seq_len, int64_t k_token_stride,
+                          int64_t v_token_stride, optgqa_dtype dtype, void* stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || max_seq_len < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
+    const int64_t row = (int64_t)num_kv_heads * head_dim;
+    if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
+    if ((k_cache == nullptr) != (v_cache == nullptr)) return OPTGQA_ERR_NULL;
+    const bool store = k_cache != nullptr;
+    if (store) {
+        if (block_size <= 0 || max_blocks_per_seq <= 0) return OPTGQA_ERR_SHAPE;
+        if ((int64_t)max_seq_len > (int64_t)max_blocks_per_seq * block_size) return OPTGQA_ERR_SHAPE;
+        if (!block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    }
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim)) return OPTGQA_ERR_UNSUPPORTED;
+    if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;                 // tiled kernel only
+    if (k_token_stride % 8 || v_token_stride % 8) return OPTGQA_ERR_UNSUPPORTED;   // rows move as 16-byte pieces
+    if (num_seqs == 0 || max_seq_len == 0) return OPTGQA_OK;
+    if (!out || !q || !k || !v || !cu_seq_lens || (store && !block_tables)) return OPTGQA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k) || !aligned16(v) ||
+        (store && (!aligned16(k_cache) || !aligned16(v_cache))))
+        return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs > 65535) return OPTGQA_ERR_SHAPE;
+    PrefillParams p;
+    p.out = out;
+    p.q = q;
+    p.k_cache = p.v_cache = nullptr;
+    p.block_tables = block_tables;
+    p.context_lens = nullptr;
+    p.cu_q_lens = cu_seq_lens;
+    p.slopes = alibi_slopes;
+    p.scale2 = scale * kLog2e;
+    p.out_scale = 1.f;
+    p.window = 0;
+    p.k_in = k;
+    p.v_in = v;
+    p.k_in_stride = k_token_stride;
+    p.v_in_stride = v_token_stride;
+    p.k_cache_w = k_cache;
+    p.v_cache_w = v_cache;
+    p.num_heads = num_heads;
+    p.num_kv_heads = num_kv_heads;
+    p.block_size = store ? block_size : 16;
+    p.max_blocks_per_seq = store ? max_blocks_per_seq : 0;
+    return launch_prefill(p, num_seqs, max_seq_len, head_dim, dtype, static_cast<hipStream_t>(stream), false, true);
 }
 
 int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_bytes,

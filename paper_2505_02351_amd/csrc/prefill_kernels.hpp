@@ -52,6 +52,12 @@ struct PrefillParams {
     int q_tiles;                // ceil(max_q_len / tokens per workgroup)
     int units;                  // num_seqs * num_kv_heads * (group / GH)
     int window;                 // > 0: the query at position pos sees keys pos - window < j <= pos only
+    // whole-prompt variant (CONTIG): K/V come from the step's contiguous inputs, not from the cache
+    const void* k_in;           // [T][Hkv][D] with token strides (elements)
+    const void* v_in;
+    int64_t k_in_stride, v_in_stride;
+    void* k_cache_w;            // caches to store the prompt's K/V into (both or neither), else nullptr
+    void* v_cache_w;
 };
 
 constexpr int kPfWaves = 4;
@@ -80,9 +86,17 @@ template <> struct PfSoftmax<kBF16> {
 // KV8: the caches hold 1-byte E4M3 codes with per-tensor scales (k_scale folded into scale2,
 // v_scale into out_scale on the host); the loader threads widen them to DT - exactly - on the
 // way into LDS, everything after that is unchanged.
-template <int DT, bool KV8 = false, bool WIN = false>
+//
+// CONTIG: the whole prompt is new and nothing of it is in the cache yet (Alg. 1, prompt branch with
+// empty caches): the context of sequence b is its own cu_q_lens[b+1] - cu_q_lens[b] tokens, and
+// K / V tiles are fetched from the contiguous inputs k_in / v_in (token strides) instead of
+// through the block table.  With k_cache_w / v_cache_w set, the workgroups of a KV head's first
+// head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1 "reshape
+// and store K, V"), so the step needs no separate cache-write launch.
+template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false>
 __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
+    static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     constexpr int D = 128;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     constexpr int RB = kPfRowBlocks;
@@ -112,7 +126,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int n_b = p.cu_q_lens[b + 1] - cu0;
     const int tq0 = qt * tokens_per_wg;
     if (tq0 >= n_b) return;
-    const int L = p.context_lens[b];
+    const int L = CONTIG ? n_b : p.context_lens[b];
     const int pos0 = L - n_b;                                   // position of the sequence's first new token
     const int kmax = pos0 + min(tq0 + tokens_per_wg, n_b);      // keys 0 .. kmax-1 are visible to some row
     const int ntiles = (kmax + kPfKeys - 1) / kPfKeys;
@@ -129,10 +143,28 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int n16 = lane & 15, hg = lane >> 4;
 
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
-    const unsigned char* __restrict__ kc = static_cast<const unsigned char*>(p.k_cache) + (int64_t)g * bs * D * ES;
-    const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache) + (int64_t)g * bs * D * ES;
+    // paged: the KV head's offset inside a block; CONTIG: the sequence's token 0, KV head g
+    const unsigned char* __restrict__ kc = CONTIG
+        ? static_cast<const unsigned char*>(p.k_in) + (cu0 * p.k_in_stride + (int64_t)g * D) * 2
+        : static_cast<const unsigned char*>(p.k_cache) + (int64_t)g * bs * D * ES;
+    const unsigned char* __restrict__ vc = CONTIG
+        ? static_cast<const unsigned char*>(p.v_in) + (cu0 * p.v_in_stride + (int64_t)g * D) * 2
+        : static_cast<const unsigned char*>(p.v_cache) + (int64_t)g * bs * D * ES;
     const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
+
+    if (CONTIG && p.k_cache_w && gu == g * chunks) {
+        // store this workgroup's own tokens' K / V rows of head g (16-byte pieces: 16 per row and tensor)
+        const int ntok = min(tokens_per_wg, n_b - tq0);
+        for (int idx = threadIdx.x; idx < ntok * 32; idx += kPfWaves * 64) {
+            const int tok = tq0 + (idx >> 5), is_v = (idx >> 4) & 1, piece = idx & 15;
+            const int blk = table[tok >> bs_shift];
+            const int64_t dst = blk * block_stride + (int64_t)g * bs * D + (int64_t)(tok & (bs - 1)) * D + 8 * piece;
+            const unsigned char* src = (is_v ? vc + (int64_t)tok * p.v_in_stride * 2 : kc + (int64_t)tok * p.k_in_stride * 2) + 16 * piece;
+            uint16_t* dstp = (is_v ? static_cast<uint16_t*>(p.v_cache_w) : static_cast<uint16_t*>(p.k_cache_w)) + dst;
+            *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
+        }
+    }
 
     // This lane's query row in each of the wave's row blocks: B operand of the score MFMAs
     // (row n16, dims 32i + 8hg .. +7), its position, slope and validity.
@@ -175,6 +207,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int ld = k_loader ? tid : tid - 128;
     const int l_group = ld >> 4, l_chunk = ld & 15;              // keys 4*group .. +3, dims 8*chunk ..
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
+    const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
     const int l_dst = (k_loader ? 0 : kKTile) + 4 * l_group * l_pitch + 8 * l_chunk;
     // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
@@ -188,6 +221,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int last_tile = ntiles - 1;                             // >= kt0
     auto load_blk = [&](int t) __attribute__((always_inline)) {
         // the four keys of a group share a block (groups are 4-aligned, clamping keeps the block)
+        if (CONTIG) return 0;
         const int key = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
         return table[key >> bs_shift];
     };
@@ -199,7 +233,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int key = min(key0 + j, kmax - 1);
-            stage[j] = *reinterpret_cast<const StageT*>(src + (int64_t)(key & (bs - 1)) * (D * ES));
+            stage[j] = *reinterpret_cast<const StageT*>(src + (int64_t)(CONTIG ? key : key & (bs - 1)) * l_row);
         }
         blk_next = load_blk(t + 1);
     };

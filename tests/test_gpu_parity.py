@@ -756,6 +756,123 @@ def test_window_rejects_what_it_cannot_do(U):
         G.paged_prefill_window(torch.empty_like(q), q, c, c, bt, cl, cu, None, 0.1, 0, 1)
 
 
+# ------------------------------------------------------------------ whole prompt, caches empty
+PROMPT = [
+    # dtype, Hq, Hkv, bs, batch, len_lo, len_hi
+    (W.BF16, 8, 2, 16, 3, 1, 300),
+    (W.F16, 32, 8, 16, 2, 100, 700),
+    (W.F16, 4, 4, 32, 3, 1, 400),          # MHA: 128 tokens per workgroup
+    (W.BF16, 6, 2, 16, 2, 5, 100),         # G = 3
+    (W.F16, 32, 2, 64, 2, 30, 260),        # G = 16: 8 tokens per workgroup
+    (W.BF16, 40, 2, 16, 1, 200, 200),      # G = 20 -> two head chunks; only the first stores the rows
+]
+
+
+@pytest.mark.parametrize("i", range(len(PROMPT)))
+def test_prompt_prefill_sweep(U, oracle, i):
+    """optgqa_prompt_prefill against the oracle's whole-prompt clause; the caches it fills must equal
+    the cache-write oracle's bit for bit (untouched rows keep their fill pattern); K / V given as
+    strided views of one fused [T, (Hq + 2 Hkv) D] tensor on one pass."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    dtype, Hq, Hkv, bs, B, lo, hi = PROMPT[i]
+    D = 128
+    cfg = W.small_config(name=f"prompt{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
+                         ctx_hi=hi, q_len=hi, seed=1700 + i)
+    case = W.make_case(cfg)
+    assert np.array_equal(case.q_lens, case.context_lens)
+    ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, dtype)
+    kc, vc = oracle_filled(oracle, case)
+    dev = U.DevCase(case)
+    # dense inputs, caches stored
+    dev.out.fill_(float("nan"))
+    G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables, dev.cu_q_lens,
+                     dev.slopes, float(case.scale), case.max_q_len)
+    torch.cuda.synchronize()
+    assert U.max_abs_err(U.to_host(dev.out), ref, dtype) <= U.TOL[dtype]
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    # fused QKV tensor: k and v are strided views; no caches
+    T = case.num_tokens
+    fused = torch.zeros(T, (Hq + 2 * Hkv) * D, dtype=dev.q.dtype, device="cuda")
+    fused[:, Hq * D:(Hq + Hkv) * D] = dev.k_new.reshape(T, Hkv * D)
+    fused[:, (Hq + Hkv) * D:] = dev.v_new.reshape(T, Hkv * D)
+    k_view = fused[:, Hq * D:(Hq + Hkv) * D].unflatten(1, (Hkv, D))
+    v_view = fused[:, (Hq + Hkv) * D:].unflatten(1, (Hkv, D))
+    dev.out.fill_(float("nan"))
+    G.prompt_prefill(dev.out, dev.q, k_view, v_view, None, None, None, dev.cu_q_lens, None, float(case.scale),
+                     case.max_q_len)
+    torch.cuda.synchronize()
+    ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, None, case.scale, dtype)
+    assert U.max_abs_err(U.to_host(dev.out), ref, dtype) <= U.TOL[dtype]
+
+
+def test_prompt_prefill_then_decode(U, oracle):
+    """A prompt processed by optgqa_prompt_prefill, then one decode step over the caches it filled:
+    the step's output equals the oracle's decode over the oracle's caches."""
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="prompt_then_decode", dtype=W.BF16, batch=4, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=16, num_blocks=4 * 40 + 3, ctx_lo=50, ctx_hi=600, seed=1750)
+    case = W.make_case(cfg)                                        # decode case: last token is the step's
+    k_all, v_all, slots = W.all_token_rows(case, include_new=False)
+    lens = case.context_lens.astype(np.int64) - 1
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    dev = U.DevCase(case)
+    dev.k_cache.fill_(float("nan")), dev.v_cache.fill_(float("nan"))
+    T = int(cu[-1])
+    qp = torch.zeros(T, 16, 128, dtype=dev.q.dtype, device="cuda")
+    G.prompt_prefill(torch.empty_like(qp), qp, U.to_dev(k_all, W.BF16), U.to_dev(v_all, W.BF16), dev.k_cache,
+                     dev.v_cache, dev.block_tables, torch.from_numpy(cu).cuda(), dev.slopes, float(case.scale),
+                     int(lens.max()))
+    got = dev.step()
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+
+
+def test_prompt_prefill_workload_sampled(U, oracle):
+    """Eight prompts of 2560 tokens at the prefill workload's head shapes: sampled rows, caches bit-exact."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    case = W.make_case(W.CONFIGS["C5-prompt"])
+    cfg = case.cfg
+    dev = U.DevCase(case)
+    dev.out.fill_(float("nan"))
+    G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables, dev.cu_q_lens,
+                     dev.slopes, float(case.scale), case.max_q_len)
+    torch.cuda.synchronize()
+    got = U.to_host(dev.out)
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
+    rng = np.random.default_rng(96)
+    T = case.num_tokens
+    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (2559, 5), (2560, 6), (T // 2, 17)]
+    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
+    ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, case.dtype,
+                             rows=rows)
+    sub = np.stack([got[t, h] for t, h in rows])
+    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+
+
+def test_prompt_prefill_rejects_what_it_cannot_do(U):
+    import torch
+    import paper_2505_02351_amd as G
+    cu = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    q = torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda")
+    kv = torch.zeros(2, 2, 64, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 64
+        G.prompt_prefill(torch.empty_like(q), q, kv, kv, None, None, None, cu, None, 0.1, 2)
+    q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
+    wide = torch.zeros(2, 2 * 128 + 4, dtype=torch.float16, device="cuda")
+    kv = wide[:, :256].unflatten(1, (2, 128))            # token stride 260: not a multiple of 8
+    with pytest.raises(RuntimeError):
+        G.prompt_prefill(torch.empty_like(q), q, kv, kv, None, None, None, cu, None, 0.1, 2)
+
+
 def test_decode_step_replays_from_a_hip_graph(U, oracle):
     """The one-call step allocates nothing, synchronises nothing and records no memset, so it can be
     captured: every replay (with eager steps and synchronisations in between) must reproduce the

@@ -96,6 +96,8 @@ CONFIGS: Dict[str, Config] = {
     "C4": Config("C4", "decode", F16, 4, 64, 8, 128, 16, 16384, 32768, 32768,
                  partition_size=512, seed=3),
     "C5": Config("C5", "prefill", BF16, 8, 32, 8, 128, 16, 2560, 2560, 2560, q_len=512, seed=4),
+    # the same sequences as whole prompts with empty caches (every token new)
+    "C5-prompt": Config("C5-prompt", "prefill", BF16, 8, 32, 8, 128, 16, 2560, 2560, 2560, q_len=2560, seed=5),
 }
 
 
