@@ -309,6 +309,23 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
+#ifdef OPTGQA_PF_TIMING
+unsigned long long* g_pf_timing = nullptr;      // development builds only
+#endif
+
+// The tiled prefill kernel takes its LDS as dynamic shared memory (more than the 64 KiB a kernel
+// gets by default); the limit is raised once per instantiation.
+template <int DT, bool KV8, bool WIN, bool CONTIG>
+int launch_prefill_mma(const PrefillParams& p, dim3 grid, dim3 block, hipStream_t st)
+{
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+    if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
+    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG>), grid, block, kPfLdsBytes, st, p);
+    return launch_status();
+}
+
 // Tiled matrix-core prefill (head_dim 128); other shapes go row by row.
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
                    bool kv8 = false, bool contig = false)
@@ -332,33 +349,33 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const int64_t blocks = (int64_t)((p.units + 7) / 8) * 8 * p.q_tiles;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
+#ifdef OPTGQA_PF_TIMING
+    p.timing = g_pf_timing;
+#endif
     KernelEvents ev(st);
+    const bool f16 = dtype == OPTGQA_F16;
     if (contig) {
         if (kv8 || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
-        if (dtype == OPTGQA_F16)
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, false, false, true>), grid, block, 0, st, p);
-        else
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, false, false, true>), grid, block, 0, st, p);
-    } else if (p.window > 0) {
-        if (kv8) return OPTGQA_ERR_UNSUPPORTED;
-        if (dtype == OPTGQA_F16)
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, false, true>), grid, block, 0, st, p);
-        else
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, false, true>), grid, block, 0, st, p);
-    } else if (kv8) {
-        if (dtype == OPTGQA_F16)
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16, true>), grid, block, 0, st, p);
-        else
-            hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16, true>), grid, block, 0, st, p);
-    } else if (dtype == OPTGQA_F16) {
-        hipLaunchKernelGGL((paged_prefill_mma_kernel<kF16>), grid, block, 0, st, p);
-    } else {
-        hipLaunchKernelGGL((paged_prefill_mma_kernel<kBF16>), grid, block, 0, st, p);
+        return f16 ? launch_prefill_mma<kF16, false, false, true>(p, grid, block, st)
+                   : launch_prefill_mma<kBF16, false, false, true>(p, grid, block, st);
     }
-    return launch_status();
+    if (p.window > 0) {
+        if (kv8) return OPTGQA_ERR_UNSUPPORTED;
+        return f16 ? launch_prefill_mma<kF16, false, true, false>(p, grid, block, st)
+                   : launch_prefill_mma<kBF16, false, true, false>(p, grid, block, st);
+    }
+    if (kv8)
+        return f16 ? launch_prefill_mma<kF16, true, false, false>(p, grid, block, st)
+                   : launch_prefill_mma<kBF16, true, false, false>(p, grid, block, st);
+    return f16 ? launch_prefill_mma<kF16, false, false, false>(p, grid, block, st)
+               : launch_prefill_mma<kBF16, false, false, false>(p, grid, block, st);
 }
 
 }  // namespace
+
+#ifdef OPTGQA_PF_TIMING
+extern "C" int optgqa_set_pf_timing(void* buf) { g_pf_timing = static_cast<unsigned long long*>(buf); return 0; }
+#endif
 
 extern "C" {
 

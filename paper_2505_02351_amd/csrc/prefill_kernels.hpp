@@ -6,19 +6,28 @@
 // four waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
 // tile (Section II, "Shared Key-Value").
 //
-// Both contractions are computed transposed so that no operand has to be transposed in registers:
-//   S^T[key][row] = K Q^T      v_mfma_f32_16x16x32: A = K rows from LDS (natural layout: a lane
-//                              needs 8 consecutive dims of one key), B = query rows held in VGPRs.
-//                              A lane then holds, for ONE query row, keys 4hg+v of both 16-key
-//                              halves of the tile: 8 weights that pack straight into ...
-//   O^T[dim][row] += V^T P^T   ... the B operand of the second v_mfma_f32_16x16x32, whose
+// A wave owns 32 rows.  Both contractions are computed transposed, with v_mfma_f32_32x32x16, so that
+// no operand has to be transposed in registers:
+//   S^T[key][row] = K Q^T      A = K rows from LDS (natural layout: lane (key L % 32, slab L / 32)
+//                              needs 8 consecutive dims of its key), B = the lane's query row held in
+//                              VGPRs.  The accumulator starts from the tile-invariant part of the
+//                              ALiBi term, so one FMA per score finishes eq. (3).  A lane then holds,
+//                              for ONE query row, 16 of the tile's 32 scores (keys 8i + 4 * slab + j in
+//                              element 4i + j), which after the softmax pack straight into ...
+//   O^T[dim][row] += V^T P^T   ... the B operands of the two output MFMAs of a 32-dim block, whose
 //                              contraction index runs over the tile's keys in exactly that
 //                              (permuted) order.  A = V^T: V lies in LDS in its natural [key][dim]
 //                              layout and is read with the LDS transpose load (ds_read_b64_tr_b16:
 //                              inside each group of 16 lanes, lane i receives element i % 4 of the
 //                              8-byte chunks addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4),
-//                              so that lane (dim i, slab q) ends up with keys 4q .. 4q+3 of dim i
-//                              from one instruction and keys 16 + 4q .. from a second one.
+//                              so that a lane ends up with four consecutive keys of its dim from
+//                              one instruction.
+// (32x32x16 rather than 16x16x32 MFMAs: same flops per cycle, half as many matrix and LDS
+// instructions per tile, and a row's scores live in 2 lanes instead of 4.  Measured on this chip, a
+// SIMD does not overlap 16x16x32 MFMAs of one wave with vector instructions of another at all, and
+// 32x32x16 ones only partly, and a wave issues at most one instruction every ~4.4 cycles: the
+// loop's cost is close to MFMA cycles plus 4.4 cycles per other instruction, so instruction
+// count per tile is what this kernel is tuned for.)
 // Scores, sums and the output accumulate in fp32.  For the second contraction the softmax
 // weights must become 2-byte values:
 //   fp16: one rounding (11 significant bits); the lazily moved reference of the exponentials (see
@@ -58,17 +67,42 @@ struct PrefillParams {
     int64_t k_in_stride, v_in_stride;
     void* k_cache_w;            // caches to store the prompt's K/V into (both or neither), else nullptr
     void* v_cache_w;
+#ifdef OPTGQA_PF_TIMING
+    unsigned long long* timing; // development builds: per-wave cycle sums of the loop's phases
+#endif
 };
 
 constexpr int kPfWaves = 4;
 constexpr int kPfRowBlocks = 2;                          // 16-row blocks per wave
 constexpr int kPfRows = kPfWaves * kPfRowBlocks * 16;    // (token, head) rows per workgroup
 constexpr int kPfKeys = 32;                              // keys per tile
+#ifndef OPTGQA_PF_GROUP
+#define OPTGQA_PF_GROUP 1
+#endif
+constexpr int kPfGroup = OPTGQA_PF_GROUP;                // 32-key tiles per LDS buffer (and per barrier)
 constexpr int kPfKRow = 128 + 8;                         // LDS K row, elements (padding spreads banks)
 constexpr int kPfVRow = 128 + 16;                        // LDS V row, elements: 288 bytes, so that the 8 rows a
                                                          // transpose load touches per pass cover all 64 banks
 
+constexpr int kPfLdsBytes = 2 * kPfGroup * kPfKeys * (kPfKRow + kPfVRow) * 2;   // two buffers of K and V tiles
+
 template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow2<DT>(lo, hi); }
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+// v_mfma_f32_32x32x16: A lane (row L % 32, k-slab L / 32) holds k = 8 * slab .. + 7, B likewise
+// for its column; C / D lane (column L % 32, half L / 32) holds rows 8i + 4 * half + j in
+// element 4i + j (i, j = 0..3).
+template <int DT> __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c);
+template <> __device__ __forceinline__ f32x16 mfma32<kF16>(uint4 a, uint4 b, f32x16 c)
+{
+    typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16 mfma32<kBF16>(uint4 a, uint4 b, f32x16 c)
+{
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
 
 template <int DT> struct PfSoftmax;
 template <> struct PfSoftmax<kF16> {
@@ -99,10 +133,10 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     constexpr int D = 128;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
-    constexpr int RB = kPfRowBlocks;
     // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
-    constexpr int kKTile = kPfKeys * kPfKRow, kBuf = kKTile + kPfKeys * kPfVRow;
-    __shared__ __attribute__((aligned(16))) uint16_t tile_lds[2 * kBuf];
+    // (kPfGroup tiles of 32 keys each: the waves meet at a barrier once per group)
+    constexpr int kKTile = kPfGroup * kPfKeys * kPfKRow, kBuf = kKTile + kPfGroup * kPfKeys * kPfVRow;
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile_lds[];          // kPfLdsBytes
 
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
@@ -140,7 +174,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n16 = lane & 15, hg = lane >> 4;
+    const int n32 = lane & 31, h2 = lane >> 5;
 
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
     // paged: the KV head's offset inside a block; CONTIG: the sequence's token 0, KV head g
@@ -166,40 +200,46 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         }
     }
 
-    // This lane's query row in each of the wave's row blocks: B operand of the score MFMAs
-    // (row n16, dims 32i + 8hg .. +7), its position, slope and validity.
-    uint4 qb[RB][4];
-    float posf[RB], lof[RB], slope2[RB], m_ref[RB], lsum[RB];
-    int pos[RB];
-    bool row_ok[RB], started[RB];
-    int64_t out_off[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = 16 * (wave * RB + rb) + n16;
+    // This lane's query row (row n32 of the wave's 32): B operand of the score MFMAs (dims
+    // 16m + 8h2 .. +7, m = 0..7), its position, slope and validity.
+    uint4 qb[8];
+    float posf, lof, slope2, m_ref, lsum;
+    bool row_ok, started;
+    int64_t out_off;
+    {
+        const int row = 32 * wave + n32;
         const int ti = tq0 + (row >> gshift), head = row & ((1 << gshift) - 1);
-        row_ok[rb] = ti < n_b && head < GH;
+        row_ok = ti < n_b && head < GH;
         const int tc = min(ti, n_b - 1), hc = min(head, GH - 1);
         const int64_t qrow = ((int64_t)(cu0 + tc) * Hq + h0 + hc) * D;
-        out_off[rb] = qrow;
-        pos[rb] = pos0 + tc;
-        posf[rb] = (float)pos[rb];
-        lof[rb] = W > 0 ? (float)(pos[rb] - W) : -1.f;           // keys above this one are inside the window
-        slope2[rb] = p.slopes ? p.slopes[h0 + hc] * kLog2e : 0.f;
-        m_ref[rb] = 0.f;                                         // set by the first tile in which the row sees a key
-        started[rb] = false;
-        lsum[rb] = 0.f;
-        const uint32_t keep = row_ok[rb] ? 0xffffffffu : 0u;
+        out_off = qrow;
+        const int pos = pos0 + tc;
+        posf = (float)pos;
+        lof = W > 0 ? (float)(pos - W) : -1.f;                   // keys above this one are inside the window
+        slope2 = p.slopes ? p.slopes[h0 + hc] * kLog2e : 0.f;
+        m_ref = 0.f;                                             // set by the first tile in which the row sees a key
+        started = false;
+        lsum = 0.f;
+        const uint32_t keep = row_ok ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint4 x = *reinterpret_cast<const uint4*>(qp + qrow + 32 * i + 8 * hg);
-            qb[rb][i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
+        for (int m = 0; m < 8; ++m) {
+            const uint4 x = *reinterpret_cast<const uint4*>(qp + qrow + 16 * m + 8 * h2);
+            qb[m] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
     }
-    f32x4 acc[RB][8];                                            // O^T: dims 16dt + 4hg + v of row n16
+    // slope * (offset of the lane's e-th key from its first key in a tile) / score scale: the part of
+    // the ALiBi term that does not change from tile to tile, as the score MFMAs' starting value
+    f32x16 key_bias;
+    {
+        const float per_key = slope2 / p.scale2;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+        for (int e = 0; e < 16; ++e) key_bias[e] = per_key * (float)(8 * (e >> 2) + (e & 3));
+    }
+    f32x16 acc[4];                                               // O^T: dims 32db + 8i + 4h2 + j of row n32 in element 4i + j
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) acc[rb][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[db][e] = 0.f;
 
     // ---- tile staging: threads 0..127 fetch K, 128..255 fetch V; either way a thread moves the
     // same 16-byte column piece of 4 consecutive keys (16 lanes cover one 256-byte row) ------------
@@ -209,7 +249,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
-    const int l_dst = (k_loader ? 0 : kKTile) + 4 * l_group * l_pitch + 8 * l_chunk;
+    const int l_dst = 4 * l_group * l_pitch + 8 * l_chunk;
     // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
     // tile t + 2 is on its way to registers; the block id of the next tile to fetch is read one
     // fetch earlier, so a fetch never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
@@ -237,6 +277,14 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         }
         blk_next = load_blk(t + 1);
     };
+    // A tile's place in LDS: tile number j (counted from the first tile read) sits in buffer
+    // (j / kPfGroup) % 2 at position j % kPfGroup.
+    auto tile_base = [&](int j) __attribute__((always_inline)) {
+        return ((j / kPfGroup) & 1) * kBuf + (j % kPfGroup) * kPfKeys * kPfKRow;
+    };
+    auto tile_base_v = [&](int j) __attribute__((always_inline)) {
+        return ((j / kPfGroup) & 1) * kBuf + kKTile + (j % kPfGroup) * kPfKeys * kPfVRow;
+    };
     auto store_tile = [&](const StageT (&stage)[4], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -247,115 +295,131 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
             } else {
                 w = stage[j];
             }
-            *reinterpret_cast<u32x4*>(&tile_lds[buf * kBuf + l_dst + j * l_pitch]) = w;
+            *reinterpret_cast<u32x4*>(&tile_lds[(k_loader ? tile_base(buf) : tile_base_v(buf)) + l_dst + j * l_pitch]) = w;
         }
     };
 
     const float scale2 = p.scale2;
+#ifdef OPTGQA_PF_TIMING
+    unsigned long long tm_sum[6] = {0, 0, 0, 0, 0, 0}, tm_last = clock64();
+    auto stamp = [&](int i) __attribute__((always_inline)) {
+        const unsigned long long t = clock64();
+        tm_sum[i] += t - tm_last;
+        tm_last = t;
+    };
+#define PF_STAMP(i) stamp(i)
+#define PF_TOUCH(x) asm volatile("v_mov_b32 %0, %0" : "+v"(x))
+#else
+#define PF_STAMP(i)
+#define PF_TOUCH(x)
+#endif
     auto compute_tile = [&](int kt, int buf, auto masked) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked)::value;
-        // ---- S^T = K Q^T : st[rb][half][v] = score of key 32kt + 16half + 4hg + v against row n16
-        f32x4 st[RB][2];
+        // ---- S^T = K Q^T : element 4i + j = score of key 32kt + 8i + 4h2 + j against row n32
+        // (the accumulator starts from the tile-invariant part of the ALiBi term, already divided by the
+        // score scale, so that one FMA per score finishes eq. (3))
+        f32x16 st = key_bias;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) st[rb][0] = st[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int half = 0; half < 2; ++half)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint4 ka = *reinterpret_cast<const uint4*>(
-                    &tile_lds[buf * kBuf + (16 * half + n16) * kPfKRow + 32 * i + 8 * hg]);
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb) st[rb][half] = mfma_qk<DT>(ka, qb[rb][i], st[rb][half]);
-            }
+        for (int m = 0; m < 8; ++m) {
+            const uint4 ka = *reinterpret_cast<const uint4*>(&tile_lds[tile_base(buf) + n32 * kPfKRow + 16 * m + 8 * h2]);
+            st = mfma32<DT>(ka, qb[m], st);
+        }
 
+        PF_TOUCH(st[0]); PF_TOUCH(st[15]);
+        PF_STAMP(0);                                             // scores ready
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
         // x = score - reference, formed directly: st*scale2 + slope2*key + (-slope2*pos - m_ref)
-        float keyf[8];
-        {
-            const float k0 = (float)(kt * kPfKeys + 4 * hg);
+        const float k0 = (float)(kt * kPfKeys + 4 * h2);
+        const float cm = -fmaf(slope2, posf, m_ref);
+        const float b0 = fmaf(slope2, k0, cm);                   // bias - reference of this lane's first key
+        float x[16];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) keyf[e] = k0 + (float)(16 * (e >> 2) + (e & 3));
+        for (int e = 0; e < 16; ++e) {
+            x[e] = fmaf(st[e], scale2, b0);
+            if (MASKED) {
+                const float keyf = k0 + (float)(8 * (e >> 2) + (e & 3));
+                const bool visible = WIN ? (keyf <= posf && keyf > lof) : keyf <= posf;
+                x[e] = visible ? x[e] : -INFINITY;
+            }
         }
-        uint32_t pk[RB][4], pk_lo[RB][4];
+        float mx = x[0];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-            const float cm = -fmaf(slope2[rb], posf[rb], m_ref[rb]);
-            float x[8];
+        for (int e = 1; e < 16; ++e) mx = fmaxf(mx, x[e]);
+        // Has the row seen a key yet?  Plain causal rows all see key 0 in tile 0, so there the
+        // answer is wave-uniform; with a window a row's first visible key may lie in a later tile.
+        const bool first = WIN ? !started : kt == 0;
+        if (__builtin_amdgcn_ballot_w64(first || mx > PfSoftmax<DT>::kThreshold) != 0) {
+            mx = fmaxf(mx, __shfl_xor(mx, 32));                  // the row's keys live in 2 lanes (h2)
+            // The first keys a row sees put its reference kHeadroom above their maximum, wherever
+            // that is (nothing has been accumulated yet); afterwards the reference only moves up
+            // (rows with no visible key in the tile, or with lower scores, keep theirs).
+            const bool sees = mx > -INFINITY;
+            const float delta = first ? (sees ? mx + PfSoftmax<DT>::kHeadroom : 0.f)
+                                      : fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
+            const float alpha = first ? 1.f : fast_exp2(-delta);
+            if (WIN) started = started || sees;
+            m_ref += delta;
+            lsum *= alpha;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                x[e] = fmaf(st[rb][e >> 2][e & 3], scale2, fmaf(slope2[rb], keyf[e], cm));
-                if (MASKED) {
-                    const bool visible = WIN ? (keyf[e] <= posf[rb] && keyf[e] > lof[rb]) : keyf[e] <= posf[rb];
-                    x[e] = visible ? x[e] : -INFINITY;
-                }
-            }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            // Has the row seen a key yet?  Plain causal rows all see key 0 in tile 0, so there the
-            // answer is wave-uniform; with a window a row's first visible key may lie in a later tile.
-            const bool first = WIN ? !started[rb] : kt == 0;
-            if (__builtin_amdgcn_ballot_w64(first || mx > PfSoftmax<DT>::kThreshold) != 0) {
-                mx = fmaxf(mx, __shfl_xor(mx, 16));              // the row's keys live in 4 lanes (hg)
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // The first keys a row sees put its reference kHeadroom above their maximum, wherever
-                // that is (nothing has been accumulated yet); afterwards the reference only moves up
-                // (rows with no visible key in the tile, or with lower scores, keep theirs).
-                const bool sees = mx > -INFINITY;
-                const float delta = first ? (sees ? mx + PfSoftmax<DT>::kHeadroom : 0.f)
-                                          : fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
-                const float alpha = first ? 1.f : fast_exp2(-delta);
-                if (WIN) started[rb] = started[rb] || sees;
-                m_ref[rb] += delta;
-                lsum[rb] *= alpha;
+            for (int e = 0; e < 16; ++e) x[e] -= delta;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) x[e] -= delta;
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt)
+                for (int e = 0; e < 16; ++e) acc[db][e] *= alpha;
+        }
+        // weights as 2-byte pairs: pk[m] = B operand of the output MFMA over keys 16m .. 16m + 15
+        // (its contraction slot (h2, e) is key 16m + 8(e / 4) + 4h2 + e % 4, elements 8m + e of x)
+        uint32_t pk[2][4], pk_lo[2][4];
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[rb][dt][v] *= alpha;
-            }
-            float pw[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pw[e] = fast_exp2(x[e]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                pk[rb][e] = pack2<DT>(pw[2 * e], pw[2 * e + 1]);
-                pk_lo[rb][e] = 0u;
-                if (PfSoftmax<DT>::kSplitWeights) {
-                    pk_lo[rb][e] = pack2<DT>(pw[2 * e] - widen_lo<DT>(pk[rb][e]), pw[2 * e + 1] - widen_hi<DT>(pk[rb][e]));
-                    lsum[rb] += pw[2 * e] + pw[2 * e + 1];
-                } else {
-                    // single rounding: normalise by the weights as rounded, so that the output stays
-                    // an exact convex combination of V rows
-                    lsum[rb] += widen_lo<DT>(pk[rb][e]) + widen_hi<DT>(pk[rb][e]);
-                }
+        for (int e = 0; e < 8; ++e) {
+            const float w0 = fast_exp2(x[2 * e]), w1 = fast_exp2(x[2 * e + 1]);
+            const uint32_t hi = pack2<DT>(w0, w1);
+            pk[e >> 2][e & 3] = hi;
+            pk_lo[e >> 2][e & 3] = 0u;
+            if (PfSoftmax<DT>::kSplitWeights) {
+                pk_lo[e >> 2][e & 3] = pack2<DT>(w0 - widen_lo<DT>(hi), w1 - widen_hi<DT>(hi));
+                lsum += w0 + w1;
+            } else {
+                // single rounding: normalise by the weights as rounded, so that the output stays
+                // an exact convex combination of V rows
+                lsum += widen_lo<DT>(hi) + widen_hi<DT>(hi);
             }
         }
 
+        PF_TOUCH(pk[1][3]);
+        PF_STAMP(1);                                             // weights packed
         // ---- O^T += V^T P^T ---------------------------------------------------------------------
+        // A = V^T for dims 32db .. +31: this lane is dim 32db + n32 and needs keys 16m + 4h2 + (0..3)
+        // and 16m + 8 + 4h2 + (0..3).  One transposing load hands each group of 16 lanes 4 keys x
+        // 16 dims: lane s of a group addresses key (s / 4) of the four, dims 4 (s % 4) .. + 3.
         typedef short i16x4 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
-        const uint16_t* vrow = &tile_lds[buf * kBuf + kKTile + (4 * hg + (n16 >> 2)) * kPfVRow + 4 * (n16 & 3)];
+        const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
+        const uint16_t* vrow = &tile_lds[tile_base_v(buf) + (4 * h2 + (s16 >> 2)) * kPfVRow + 16 * dhalf + 4 * (s16 & 3)];
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * dt));
-            const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * kPfVRow + 16 * dt));
-            const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-            const uint4 va = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                acc[rb][dt] = mfma_qk<DT>(va, make_uint4(pk[rb][0], pk[rb][1], pk[rb][2], pk[rb][3]), acc[rb][dt]);
+            for (int m = 0; m < 2; ++m) {
+                const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * m * kPfVRow + 32 * db));
+                const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + (16 * m + 8) * kPfVRow + 32 * db));
+                const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                const uint4 va = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
+                acc[db] = mfma32<DT>(va, make_uint4(pk[m][0], pk[m][1], pk[m][2], pk[m][3]), acc[db]);
                 if (PfSoftmax<DT>::kSplitWeights)
-                    acc[rb][dt] = mfma_qk<DT>(va, make_uint4(pk_lo[rb][0], pk_lo[rb][1], pk_lo[rb][2], pk_lo[rb][3]), acc[rb][dt]);
+                    acc[db] = mfma32<DT>(va, make_uint4(pk_lo[m][0], pk_lo[m][1], pk_lo[m][2], pk_lo[m][3]), acc[db]);
             }
-        }
-
     };
 
     const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
 
-    fetch_tile(stage, kt0);
-    store_tile(stage, kt0 & 1);
-    fetch_tile(stage, kt0 + 1);
+    // Prologue: the first kPfGroup tiles go to buffer 0, the one after them is left in flight.
+    const int nt = ntiles - kt0;                                 // tiles this workgroup reads, numbered j = 0 ..
+#pragma unroll
+    for (int j = 0; j < kPfGroup; ++j) {
+        fetch_tile(stage, kt0 + j);
+        store_tile(stage, j);
+    }
+    fetch_tile(stage, kt0 + kPfGroup);
     __syncthreads();
     // Tiles wholly inside every row's visible range need no mask: those that end at or below the
     // first row's position (causal side) and start at or above the last row's window start.
@@ -363,12 +427,19 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int n_window_cut = W > 0 ? (max(kmax - W, 0) + kPfKeys - 1) / kPfKeys : 0;
     // (three plain loops rather than one with a branch in it: the compiler schedules the loads of a
     // loop whose body is one straight line far better)
+    // While tile j is computed, tile j + kPfGroup (fetched one step earlier) is put into the other
+    // buffer and tile j + kPfGroup + 1 is fetched; the waves meet after the last tile of a group.
     auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
         for (int kt = from; kt < to; ++kt) {
-            compute_tile(kt, kt & 1, masked);
-            if (kt + 1 < ntiles) store_tile(stage, (kt + 1) & 1);
-            fetch_tile(stage, kt + 2);
-            __syncthreads();
+            const int j = kt - kt0;
+            compute_tile(kt, j, masked);
+            PF_STAMP(2);                                         // output MFMAs issued
+            if (j + kPfGroup < nt) store_tile(stage, j + kPfGroup);
+            PF_STAMP(3);                                         // a later tile stored (waits for its loads)
+            fetch_tile(stage, kt + kPfGroup + 1);
+            PF_STAMP(4);
+            if (j % kPfGroup == kPfGroup - 1) __syncthreads();
+            PF_STAMP(5);                                         // barrier passed
         }
     };
     const int cut_end = max(kt0, min(n_window_cut, n_unmasked));   // tiles cut by some row's window start
@@ -377,22 +448,29 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     run_tiles(cut_end, plain_end, std::false_type{});
     run_tiles(plain_end, ntiles, std::true_type{});
 
-    // ---- normalise and write: this lane holds dims 16dt + 4hg + v of its row --------------------
+#ifdef OPTGQA_PF_TIMING
+    if (p.timing && lane == 0) {
+        unsigned long long* t = p.timing + 8 * ((size_t)blockIdx.x * kPfWaves + wave);
+        for (int i = 0; i < 6; ++i) t[i] = tm_sum[i];
+        t[6] = (unsigned long long)(ntiles - kt0);
+        t[7] = clock64();
+    }
+#endif
+    // ---- normalise and write: this lane holds dims 32db + 8i + 4h2 + (0..3) of its row -----------
     uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        float lt = lsum[rb];
-        lt += __shfl_xor(lt, 16);
-        lt += __shfl_xor(lt, 32);
-        if (!row_ok[rb]) continue;
+    float lt = lsum;
+    lt += __shfl_xor(lt, 32);
+    if (row_ok) {
         const float inv = p.out_scale / lt;
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            uint2 packed;
-            packed.x = narrow2<DT>(acc[rb][dt][0] * inv, acc[rb][dt][1] * inv);
-            packed.y = narrow2<DT>(acc[rb][dt][2] * inv, acc[rb][dt][3] * inv);
-            *reinterpret_cast<uint2*>(op + out_off[rb] + 16 * dt + 4 * hg) = packed;
-        }
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint2 packed;
+                packed.x = narrow2<DT>(acc[db][4 * i] * inv, acc[db][4 * i + 1] * inv);
+                packed.y = narrow2<DT>(acc[db][4 * i + 2] * inv, acc[db][4 * i + 3] * inv);
+                *reinterpret_cast<uint2*>(op + out_off + 32 * db + 8 * i + 4 * h2) = packed;
+            }
     }
 }
 
