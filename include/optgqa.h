@@ -245,11 +245,12 @@ int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const vo
  *   optgqa_decode_step_window       optgqa_decode_step (cache write + attention) likewise
  *   optgqa_paged_prefill_window     optgqa_paged_prefill, every new token with its own window
  *
- * head_dim 128 only (OPTGQA_ERR_UNSUPPORTED otherwise); window <= 0 is OPTGQA_ERR_SHAPE (call
- * the plain entry points for full attention).  The two decode calls always use the equal-work
- * split: a workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED)
- * bytes is required (OPTGQA_ERR_WORKSPACE without it).  Other arguments, layouts, ownership
- * and errors as for the calls they extend.
+ * window <= 0 is OPTGQA_ERR_SHAPE (call the plain entry points for full attention).  For
+ * head_dim 128 the two decode calls always use the equal-work split: a workspace of
+ * optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED) bytes is required
+ * (OPTGQA_ERR_WORKSPACE without it).  head_dim 64 runs unsplit through the general kernels (a
+ * window bounds the work per query) and needs no workspace.  Other arguments, layouts,
+ * ownership and errors as for the calls they extend.
  */
 int optgqa_paged_attention_window(void *out, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *block_tables,

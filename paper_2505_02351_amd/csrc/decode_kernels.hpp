@@ -108,8 +108,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
 
     int b, L;
     if (!row_to_seq(p, row, b, L)) return;
-    const int t_begin = part * p.partition_size;
-    const int t_end = min(L, t_begin + p.partition_size);
+    // Sliding window (Alg. 1, local mask; unsplit launches only): the query at position L - 1 sees
+    // tokens lo .. L - 1; the steps start at the row group that holds token lo.
+    const int lo = (p.window > 0 && p.num_partitions == 1) ? max(L - p.window, 0) : 0;
+    const int t_begin = max(part * p.partition_size, lo / TPS * TPS);
+    const int t_end = min(L, part * p.partition_size + p.partition_size);
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
     const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache);
     const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
         const int t0 = t_begin + s * TPS;                 // wave-uniform, never straddles a block
         const int64_t blk = table[t0 / bs];
         const int t = t0 + r;
-        const bool valid = t < t_end;
+        const bool valid = t < t_end && t >= lo;
         const int64_t off = ((blk * Hkv + g) * bs + (t0 % bs) + r) * D + 8 * c;
         uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
         if (valid) {

@@ -184,8 +184,10 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
         return launch_status();
     }
 #ifndef OPTGQA_VALU_ONLY_DECODE
-    if (gh == 8) return launch_decode_mc<DT, D, 8>(p, grid, block, st);
-    if (gh == 4) return launch_decode_mc<DT, D, 4>(p, grid, block, st);
+    if (p.window <= 0) {                                 // (the general kernel is the one that knows about windows)
+        if (gh == 8) return launch_decode_mc<DT, D, 8>(p, grid, block, st);
+        if (gh == 4) return launch_decode_mc<DT, D, 4>(p, grid, block, st);
+    }
 #endif
     switch (gh) {
     case 8: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 8>), grid, block, 0, st, p); break;
@@ -305,7 +307,7 @@ int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows
     p.k_cache_w = p.v_cache_w = nullptr;
     p.k_new_stride = p.v_new_stride = 0;
     p.out_scale = 1.f;
-    p.window = 0;
+    p.window = pp.window;
     return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
 }
 
@@ -500,10 +502,8 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
                    const float* kv_scales = nullptr,      // {k_scale, v_scale}: the caches hold E4M3 codes
                    int window = 0)                        // > 0: sliding window (Alg. 1, local mask)
 {
-    if (window > 0) {
-        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
-        partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that knows about windows
-    }
+    if (window > 0)                                      // head_dim 128: the equal-work kernel; 64: the general
+        partition_size = head_dim == 128 ? OPTGQA_SPLIT_BALANCED : -1;   // kernel, unsplit (a window bounds the work)
     if (kv_scales) {
         if (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f)
             return OPTGQA_ERR_SHAPE;
@@ -745,7 +745,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
         return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
-    if ((kv_scales || window > 0) && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;   // tiled kernel only
+    if (kv_scales && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;   // tiled kernel only
     if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens) return OPTGQA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;

@@ -118,14 +118,14 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     # sliding window: positive windows only, head_dim 128 only, decode needs the workspace
     wa = lib.optgqa_paged_attention_window
     f = lambda W=8, D=128: wa(one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, None, 0, 0, None)
-    assert f(W=0) == -2 and f(W=-5) == -2 and f(D=64) == -3 and f() == -4
+    assert f(W=0) == -2 and f(W=-5) == -2 and f(D=96) == -3 and f() == -4
     wsx = lib.optgqa_decode_step_window
     f = lambda W=8, D=128, ks=256: wsx(one, one, one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, ks,
                                        256, None, 0, 0, None)
-    assert f(W=0) == -2 and f(D=64) == -3 and f(ks=100) == -2 and f() == -4
+    assert f(W=0) == -2 and f(D=96) == -3 and f(ks=100) == -2 and f() == -4
     wp = lib.optgqa_paged_prefill_window
     f = lambda W=8, D=128, B=2, cu=one: wp(one, one, one, one, one, one, cu, None, 0.1, W, B, 8, 2, D, 16, 8, 32, 0, None)
-    assert f(W=0) == -2 and f(D=64) == -3 and f(cu=None) == -1 and f(B=0) == 0
+    assert f(W=0) == -2 and f(D=96) == -3 and f(cu=None) == -1 and f(B=0) == 0
     # whole-prompt prefill: strides, both caches or neither, head_dim 128 only
     pp = lib.optgqa_prompt_prefill
     f = lambda kc=None, vc=None, D=128, ks=256, cu=one, B=2, bt=None, L=32: pp(
