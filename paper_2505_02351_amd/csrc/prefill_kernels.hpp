@@ -267,14 +267,20 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     };
     int blk_next = load_blk(kt0);
 
+    // (address arithmetic kept short on purpose - this loop pays for every instruction: one 64-bit
+    // multiply-add for the block, one shift-add for the first row, then per key a clamp and a shift-add;
+    // rows past the sequence's last key re-read that key, which lies in the same block)
+    const unsigned char* const l_lane = l_src + 8 * l_chunk * ES;                 // this lane's column piece
+    const uint32_t l_blk_bytes = (uint32_t)(block_stride * ES);                   // < 2^32: one block of all KV heads
     auto fetch_tile = [&](StageT (&stage)[4], int t) __attribute__((always_inline)) {
-        const int key0 = min(t, last_tile) * kPfKeys + 4 * l_group;
-        const unsigned char* src = l_src + (blk_next * block_stride + 8 * l_chunk) * ES;
+        const int key0 = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
+        const int rmax = kmax - 1 - key0;                         // >= 0; < 3 only at the sequence's end
+        const unsigned char* base;
+        if (CONTIG) base = l_lane + (uint64_t)(uint32_t)key0 * (uint32_t)l_row;
+        else base = l_lane + (uint64_t)(uint32_t)blk_next * l_blk_bytes + (uint32_t)((key0 & (bs - 1)) * (D * ES));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = min(key0 + j, kmax - 1);
-            stage[j] = *reinterpret_cast<const StageT*>(src + (int64_t)(CONTIG ? key : key & (bs - 1)) * l_row);
-        }
+        for (int j = 0; j < 4; ++j)
+            stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
         blk_next = load_blk(t + 1);
     };
     // A tile's place in LDS: tile number j (counted from the first tile read) sits in buffer
