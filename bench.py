@@ -70,6 +70,7 @@ def parse():
     ap.add_argument("--window", type=int, default=0,
                     help="> 0: the same workload with a sliding window of this many tokens (local mask of "
                          "Alg. 1), 2-byte caches; KV bytes and flops count the visible keys only")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache pass (evict, then time each step)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
     return ap.parse_args()
@@ -171,7 +172,20 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0, window: int = 
         if dt >= min_seconds or reps >= 1000:
             break
     per = dt / reps
+    single = None
+    if cfg.name in ("C1", "C2"):
+        # the small configs once more on one thread (a few passes)
+        nthreads = O.num_threads()
+        O.set_num_threads(1)
+        t1 = time.perf_counter()
+        n1 = 0
+        while n1 < 3 and time.perf_counter() - t1 < 10.0:
+            run()
+            n1 += 1
+        single = {"value": kv_bytes / ((time.perf_counter() - t1) / n1) / 1e9, "unit": "GB/s", "cores": 1, "passes": n1}
+        O.set_num_threads(nthreads)
     return {
+        **({"single_thread": single} if single else {}),
         "value": kv_bytes / per / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
         "sample": f"{what}{f', window {window}' if window > 0 else ''} ({kv_bytes / 1e6:.1f} MB of KV per pass, "
                   f"{reps} passes in {dt:.1f} s)",
@@ -298,6 +312,29 @@ def main():
         torch.cuda.synchronize()
         kernel_ms = np.array([s.elapsed_time(e) for s, e in zip(starts, stops)])
 
+        # ---- pass 3: cold steps - the last-level cache (256 MiB) is evicted before every step by
+        # READING a 1 GiB scratch buffer (a written one leaves dirty lines whose write-back then runs
+        # under the timed step: measured +60 us on the decode workload), and each whole step is timed
+        # by its own event pair --
+        cold = None
+        if not args.no_cold:
+            n_cold = min(steps, 50)
+            scratch = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+            c0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_cold)]
+            c1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_cold)]
+            for i in range(n_cold):
+                scratch.sum()
+                c0[i].record(stream)
+                step()
+                c1[i].record(stream)
+            torch.cuda.synchronize()
+            del scratch
+            cold_ms = np.array([a.elapsed_time(b) for a, b in zip(c0, c1)])
+            cold = {"steps": n_cold, "median_ms": float(np.median(cold_ms)), "min_ms": float(cold_ms.min()),
+                    "p90_ms": float(np.percentile(cold_ms, 90)),
+                    "what": "whole step, event pair per step (includes ~3 us of event overhead), 1 GiB "
+                            "read between steps to evict the last-level cache"}
+
         ms_per_step = wall * 1e3 / steps
         kv_bytes = case.kv_bytes() // (2 if e4m3 else 1)
         if window and decode:                      # a query reads min(L, window) tokens of each KV head
@@ -399,6 +436,8 @@ def main():
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
         }
+        if cold:
+            result["cold_step"] = cold
         result["cache_write"] = cache_write
         if stream_probe:
             result["stream_probe"] = stream_probe
