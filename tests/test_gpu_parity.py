@@ -868,6 +868,139 @@ def test_prompt_prefill_rejects_what_it_cannot_do(U):
         G.prompt_prefill(torch.empty_like(q), q, kv, kv, None, None, None, cu, None, 0.1, 2)
 
 
+# ------------------------------------------------------------------ seeded random mixes
+def check_scaled(U, got, ref, dtype, tag):
+    """The stated tolerances budget one output rounding at magnitudes below 4 (half an ulp there:
+    7.8e-3 bf16, 9.8e-4 fp16).  Random mixes also produce the odd output of magnitude 4 .. 8 (a row
+    that sees one or two keys with a large V element), whose own rounding is twice that: the bound
+    doubles with every binade beyond [2, 4), and only there."""
+    g = W.from_bits(got, dtype)
+    assert np.all(np.isfinite(g)), f"{tag}: non-finite values in the GPU output"
+    binade = np.floor(np.log2(np.maximum(np.abs(ref), 2.0)))        # 1 for |ref| < 4, 2 for [4, 8), ...
+    err = np.abs(g - ref) / np.exp2(binade - 1.0)
+    i = np.unravel_index(np.argmax(err), err.shape)
+    assert err[i] <= U.TOL[dtype], f"{tag}: |{g[i]} - {ref[i]}| = {abs(g[i] - ref[i])} at {i}"
+
+
+def test_random_mix_of_decode_calls(U, oracle):
+    """Forty seeded random decode batches (head counts, group sizes, block sizes, ragged lengths incl.
+    empty sequences) through a randomly chosen entry point each: plain attention with a random split,
+    the one-call step, a sliding window (plain / fused), the 8-bit caches.  Every output against
+    the oracle clause that defines it; caches bit-exact where the call writes them."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    rng = np.random.default_rng(20251)
+    for it in range(40):
+        D = int(rng.choice([64, 128, 128, 128]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        Gq = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        bs = int(rng.choice([16, 32, 64]))
+        B = int(rng.integers(1, 12))
+        hi = int(rng.choice([40, 200, 700, 1500]))
+        dtype = W.F16 if rng.integers(2) else W.BF16
+        cfg = W.small_config(name=f"mix{it}", dtype=dtype, batch=B, num_heads=Hkv * Gq, num_kv_heads=Hkv, head_dim=D,
+                             block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 9, ctx_lo=1, ctx_hi=hi,
+                             seed=3000 + it)
+        lens = rng.integers(1, hi + 1, size=B).astype(np.int32)
+        case = W.make_case(cfg, context_lens=lens)
+        kc, vc = oracle_filled(oracle, case)
+        mode = ["plain", "step", "window", "window_step", "fp8"][int(rng.integers(5))]
+        if mode == "fp8" and D != 128:
+            mode = "plain"
+        tag = f"case {it}: {mode} D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} {dtype}"
+        dev = U.DevCase(case)
+        if mode == "plain":
+            dev.write_cache()
+            P = int(rng.choice([-1, 0, 64, 256, BALANCED]))
+            if P > 0 and P % bs:
+                P = 0
+            if P == BALANCED and D != 128:
+                P = 0
+            got = dev.decode(partition_size=P)
+            ref = oracle_decode(oracle, case, kc, vc)
+        elif mode == "step":
+            got = dev.step()
+            assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), tag
+            ref = oracle_decode(oracle, case, kc, vc)
+        elif mode in ("window", "window_step"):
+            window = int(rng.choice([1, 3, 16, 31, 100, 500]))
+            if mode == "window":
+                dev.write_cache()
+            got = dev.decode_window(window, fused=(mode == "window_step"))
+            assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), tag
+            ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes,
+                                           case.scale, window, dtype)
+        else:
+            k_scale, v_scale = float(rng.choice([0.01, 0.05, 1.0])), float(rng.choice([0.02, 0.5]))
+            kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+            assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8), tag
+            got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
+            ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes,
+                                         case.scale, k_scale, v_scale, dtype)
+        check_scaled(U, got, ref, dtype, tag)
+
+
+def test_random_mix_of_prefill_calls(U, oracle):
+    """Twenty-four seeded random prefill batches (chunk lengths from 1 token to the whole prompt)
+    through the paged kernel, its windowed and 8-bit variants and the whole-prompt call."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    rng = np.random.default_rng(20252)
+    for it in range(24):
+        D = int(rng.choice([64, 128, 128, 128]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        Gq = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        bs = int(rng.choice([16, 32, 64]))
+        B = int(rng.integers(1, 5))
+        hi = int(rng.choice([60, 300, 900]))
+        q_len = int(rng.choice([1, 7, 33, 130, hi]))
+        dtype = W.F16 if rng.integers(2) else W.BF16
+        cfg = W.small_config(name=f"pmix{it}", kind="prefill", dtype=dtype, batch=B, num_heads=Hkv * Gq,
+                             num_kv_heads=Hkv, head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5,
+                             ctx_lo=1, ctx_hi=hi, q_len=q_len, seed=3100 + it)
+        case = W.make_case(cfg)
+        kc, vc = oracle_filled(oracle, case)
+        mode = ["plain", "window", "fp8", "prompt"][int(rng.integers(4))]
+        if D != 128 and mode in ("fp8", "prompt"):
+            mode = "plain"
+        if mode == "prompt" and not np.array_equal(case.q_lens, case.context_lens):
+            mode = "window"
+        tag = f"case {it}: {mode} D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} q_len={q_len} {dtype}"
+        dev = U.DevCase(case)
+        if mode == "plain":
+            dev.write_cache()
+            got = dev.prefill()
+            ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                       case.slopes, case.scale, dtype)
+        elif mode == "window":
+            window = int(rng.choice([1, 5, 32, 77, 400]))
+            dev.write_cache()
+            got = dev.prefill_window(window)
+            ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                         case.slopes, case.scale, window, dtype)
+        elif mode == "fp8":
+            k_scale, v_scale = float(rng.choice([0.0125, 0.1])), float(rng.choice([0.02, 1.0]))
+            kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
+            out = torch.full_like(dev.q, float("nan"))
+            G.paged_prefill_fp8(out, dev.q, dk, dv, dev.block_tables, dev.context_lens, dev.cu_q_lens, dev.slopes,
+                                float(case.scale), k_scale, v_scale, case.max_q_len)
+            torch.cuda.synchronize()
+            got = U.to_host(out)
+            ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                       case.slopes, case.scale, k_scale, v_scale, dtype)
+        else:
+            dev.out.fill_(float("nan"))
+            G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                             dev.cu_q_lens, dev.slopes, float(case.scale), case.max_q_len)
+            torch.cuda.synchronize()
+            got = U.to_host(dev.out)
+            assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), tag
+            ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, dtype)
+        check_scaled(U, got, ref, dtype, tag)
+
+
 def test_decode_step_replays_from_a_hip_graph(U, oracle):
     """The one-call step allocates nothing, synchronises nothing and records no memset, so it can be
     captured: every replay (with eager steps and synchronisations in between) must reproduce the
