@@ -177,3 +177,16 @@ def test_validate_tables_host(G):
     assert G.validate_tables_host(bt, np.array([20, 48], np.int32), 16, 4) == -6    # id 4 >= 4
     assert G.validate_tables_host(bt, np.array([20, 49], np.int32), 16, 5) == -6    # too long
     assert G.validate_tables_host(bt, np.array([0, 0], np.int32), 16, 5) == 0
+
+
+def test_missing_library_fails_loudly():
+    """No CPU or PyTorch fallback: without the built library the binding raises at load time."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r); import paper_2505_02351_amd as G\n"
+            "try:\n    G.load_library('/nonexistent/liboptgqa.so')\n"
+            "except ImportError as e:\n    print('raised:', e); sys.exit(7)\n"
+            "sys.exit(0)\n" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 7 and "is missing" in r.stdout, (r.returncode, r.stdout, r.stderr[-300:])
