@@ -293,8 +293,7 @@ int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, c
  *   cu_seq_lens     [num_seqs + 1] int32, cu_seq_lens[0] = 0, T = cu_seq_lens[num_seqs]
  *   max_seq_len     an upper bound on the sequences' lengths (<= max_blocks_per_seq * block_size
  *                   when the caches are given)
- * head_dim 128 only (OPTGQA_ERR_UNSUPPORTED otherwise).  All pointers device memory, 16-byte
- * aligned; errors as for optgqa_paged_prefill.
+ * All pointers device memory, 16-byte aligned; errors as for optgqa_paged_prefill.
  */
 int optgqa_prompt_prefill(void *out, const void *q, const void *k, const void *v, void *k_cache,
                           void *v_cache, const int32_t *block_tables, const int32_t *cu_seq_lens,

@@ -29,9 +29,6 @@ struct DecodeParams {
     int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
     int partition_size;         // tokens per workgroup; >= max context when unsplit
     int num_partitions;         // 1 = unsplit: the kernel writes `out` itself
-    // Row mode.  nullptr: row = sequence (decode).  Otherwise row = new query token of a
-    // prefill batch: its sequence is found in cu_q_lens and it sees keys 0..its own position.
-    const int32_t* cu_q_lens;   // [num_seqs + 1] or nullptr
     int num_seqs;
     int row_offset;             // first row handled by this launch (grid.z/y counts from here)
     int heads_per_wg;           // query heads one workgroup serves (divides the group size)
@@ -54,26 +51,11 @@ struct DecodeParams {
 #endif
 };
 
-// Sequence and number of visible keys of one output row; false if the row does not exist
-// (row-wise prefill launches num_seqs * max_q_len rows, an upper bound).
+// Sequence and number of visible keys of one output row (decode: row = sequence).
 __device__ __forceinline__ bool row_to_seq(const DecodeParams& p, int row, int& b, int& L)
 {
-    if (p.cu_q_lens == nullptr) {
-        b = row;
-        L = p.context_lens[b];
-        return true;
-    }
-    b = 0;
-    L = 0;
-    if (row >= p.cu_q_lens[p.num_seqs]) return false;
-    int lo = 0, hi = p.num_seqs - 1;                     // last b with cu_q_lens[b] <= row
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (p.cu_q_lens[mid] <= row) lo = mid; else hi = mid - 1;
-    }
-    b = lo;
-    const int n_b = p.cu_q_lens[b + 1] - p.cu_q_lens[b];
-    L = p.context_lens[b] - n_b + (row - p.cu_q_lens[b]) + 1;   // keys 0..pos, pos = L - 1
+    b = row;
+    L = p.context_lens[b];
     return true;
 }
 

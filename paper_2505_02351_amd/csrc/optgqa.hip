@@ -84,8 +84,8 @@ int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int head_dim, 
     return P;
 }
 
-// Rows are sequences (decode) or new query tokens (row-wise prefill).  A launch covers at most
-// kMaxRowsPerLaunch rows because grid.y / grid.z are 16-bit.
+// Rows are sequences.  A launch covers at most kMaxRowsPerLaunch rows because grid.y / grid.z
+// are 16-bit.
 constexpr int kMaxRowsPerLaunch = 65535;
 
 struct SplitPlan {
@@ -276,68 +276,38 @@ int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStre
                                : launch_decode_flat_dt<kBF16, false>(p, workgroups, st);
 }
 
-// Row-wise prefill: every new query token is handled like a decode row whose context ends at
-// its own position (exact, but K/V are re-read per query token; used where the tiled MFMA
-// kernel does not apply).
-int launch_prefill_rowwise(const PrefillParams& pp, int num_seqs, int total_rows_bound, int head_dim,
-                           int dtype, hipStream_t st)
-{
-    DecodeParams p;
-    p.out = pp.out;
-    p.ws_m = p.ws_l = p.ws_o = nullptr;
-    p.q = pp.q;
-    p.k_cache = pp.k_cache;
-    p.v_cache = pp.v_cache;
-    p.block_tables = pp.block_tables;
-    p.context_lens = pp.context_lens;
-    p.slopes = pp.slopes;
-    p.scale2 = pp.scale2;
-    p.num_heads = pp.num_heads;
-    p.num_kv_heads = pp.num_kv_heads;
-    p.block_size = pp.block_size;
-    p.max_blocks_per_seq = pp.max_blocks_per_seq;
-    p.partition_size = 1 << 30;
-    p.num_partitions = 1;
-    p.cu_q_lens = pp.cu_q_lens;
-    p.num_seqs = num_seqs;
-    p.row_offset = 0;
-    p.plan = nullptr;
-    p.num_units = p.segs_per_seq = 0;
-    p.k_new = p.v_new = nullptr;
-    p.k_cache_w = p.v_cache_w = nullptr;
-    p.k_new_stride = p.v_new_stride = 0;
-    p.out_scale = 1.f;
-    p.window = pp.window;
-    return launch_decode_any(dtype, head_dim, p, total_rows_bound, st);
-}
-
 #ifdef OPTGQA_PF_TIMING
 unsigned long long* g_pf_timing = nullptr;      // development builds only
 #endif
 
 // The tiled prefill kernel takes its LDS as dynamic shared memory (more than the 64 KiB a kernel
 // gets by default); the limit is raised once per instantiation.
-template <int DT, bool KV8, bool WIN, bool CONTIG>
-int launch_prefill_mma(const PrefillParams& p, dim3 grid, dim3 block, hipStream_t st)
+template <int DT, bool KV8, bool WIN, bool CONTIG, int D>
+int launch_prefill_mma_d(const PrefillParams& p, dim3 grid, dim3 block, hipStream_t st)
 {
+    constexpr int kBytes = PfTile<D>::kLdsBytes;
     static const hipError_t attr = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes);
+        reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
     if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
-    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG>), grid, block, kPfLdsBytes, st, p);
+    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D>), grid, block, kBytes, st, p);
     return launch_status();
 }
 
-// Tiled matrix-core prefill (head_dim 128); other shapes go row by row.
+template <int DT, bool KV8, bool WIN, bool CONTIG>
+int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, dim3 block, hipStream_t st)
+{
+    if constexpr (!KV8) {
+        if (head_dim == 64) return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 64>(p, grid, block, st);
+    }
+    return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, block, st);
+}
+
+// Tiled matrix-core prefill (head_dim 128 or 64; 8-bit caches: 128 only).
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
                    bool kv8 = false, bool contig = false)
 {
-    if (head_dim != 128) {
-        if (kv8 || contig) return OPTGQA_ERR_UNSUPPORTED;
-        const int64_t rows_bound = (int64_t)num_seqs * max_q_len;
-        if (rows_bound > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
-        return launch_prefill_rowwise(p, num_seqs, (int)rows_bound, head_dim, dtype, st);
-    }
+    if (head_dim != 128 && (kv8 || head_dim != 64)) return OPTGQA_ERR_UNSUPPORTED;
     const int group = p.num_heads / p.num_kv_heads;
     const int gh = heads_per_workgroup(group, 128);
     int shift = 0;
@@ -358,19 +328,19 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const bool f16 = dtype == OPTGQA_F16;
     if (contig) {
         if (kv8 || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
-        return f16 ? launch_prefill_mma<kF16, false, false, true>(p, grid, block, st)
-                   : launch_prefill_mma<kBF16, false, false, true>(p, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, false, false, true>(p, head_dim, grid, block, st)
+                   : launch_prefill_mma<kBF16, false, false, true>(p, head_dim, grid, block, st);
     }
     if (p.window > 0) {
         if (kv8) return OPTGQA_ERR_UNSUPPORTED;
-        return f16 ? launch_prefill_mma<kF16, false, true, false>(p, grid, block, st)
-                   : launch_prefill_mma<kBF16, false, true, false>(p, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, false, true, false>(p, head_dim, grid, block, st)
+                   : launch_prefill_mma<kBF16, false, true, false>(p, head_dim, grid, block, st);
     }
     if (kv8)
-        return f16 ? launch_prefill_mma<kF16, true, false, false>(p, grid, block, st)
-                   : launch_prefill_mma<kBF16, true, false, false>(p, grid, block, st);
-    return f16 ? launch_prefill_mma<kF16, false, false, false>(p, grid, block, st)
-               : launch_prefill_mma<kBF16, false, false, false>(p, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, true, false, false>(p, head_dim, grid, block, st)
+                   : launch_prefill_mma<kBF16, true, false, false>(p, head_dim, grid, block, st);
+    return f16 ? launch_prefill_mma<kF16, false, false, false>(p, head_dim, grid, block, st)
+               : launch_prefill_mma<kBF16, false, false, false>(p, head_dim, grid, block, st);
 }
 
 }  // namespace
@@ -554,7 +524,6 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.num_kv_heads = num_kv_heads;
     p.block_size = block_size;
     p.max_blocks_per_seq = max_blocks_per_seq;
-    p.cu_q_lens = nullptr;
     p.num_seqs = num_seqs;
     p.row_offset = 0;
     p.k_new = p.v_new = nullptr;
@@ -828,7 +797,6 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
         if (!block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
     }
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim)) return OPTGQA_ERR_UNSUPPORTED;
-    if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;                 // tiled kernel only
     if (k_token_stride % 8 || v_token_stride % 8) return OPTGQA_ERR_UNSUPPORTED;   // rows move as 16-byte pieces
     if (num_seqs == 0 || max_seq_len == 0) return OPTGQA_OK;
     if (!out || !q || !k || !v || !cu_seq_lens || (store && !block_tables)) return OPTGQA_ERR_NULL;

@@ -80,11 +80,12 @@ constexpr int kPfKeys = 32;                              // keys per tile
 #define OPTGQA_PF_GROUP 1
 #endif
 constexpr int kPfGroup = OPTGQA_PF_GROUP;                // 32-key tiles per LDS buffer (and per barrier)
-constexpr int kPfKRow = 128 + 8;                         // LDS K row, elements (padding spreads banks)
-constexpr int kPfVRow = 128 + 16;                        // LDS V row, elements: 288 bytes, so that the 8 rows a
-                                                         // transpose load touches per pass cover all 64 banks
-
-constexpr int kPfLdsBytes = 2 * kPfGroup * kPfKeys * (kPfKRow + kPfVRow) * 2;   // two buffers of K and V tiles
+// LDS rows, elements: K rows padded by 8 (16-byte reads of 16 keys then cover all 64 banks), V rows
+// by 16 (so do the rows a transposing load touches) - head_dim 128: 272 / 288 bytes, 64: 144 / 160
+template <int D> struct PfTile {
+    static constexpr int kKRow = D + 8, kVRow = D + 16;
+    static constexpr int kLdsBytes = 2 * kPfGroup * kPfKeys * (kKRow + kVRow) * 2;   // two buffers of K and V tiles
+};
 
 template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow2<DT>(lo, hi); }
 
@@ -127,16 +128,22 @@ template <> struct PfSoftmax<kBF16> {
 // through the block table.  With k_cache_w / v_cache_w set, the workgroups of a KV head's first
 // head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1 "reshape
 // and store K, V"), so the step needs no separate cache-write launch.
-template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false>
+template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128>
 __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
-    constexpr int D = 128;
+    static_assert(D == 128 || D == 64, "head_dim 64 or 128");
+    static_assert(!(KV8 && D != 128), "8-bit caches: head_dim 128");
+    constexpr int kPfKRow = PfTile<D>::kKRow, kPfVRow = PfTile<D>::kVRow;
+    constexpr int kQ = D / 16;                          // score MFMAs per tile (16 dims each)
+    constexpr int kDB = D / 32;                         // 32-dim blocks of the output
+    constexpr int kCPR = D / 8;                         // 16-byte (8-element) column pieces per row
+    constexpr int kKPT = 4 * D / 128;                   // consecutive keys a loader thread moves per tile
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
-    // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
+    // two tile buffers, each K tiles [32][kPfKRow] followed by V tiles [32][kPfVRow]
     // (kPfGroup tiles of 32 keys each: the waves meet at a barrier once per group)
     constexpr int kKTile = kPfGroup * kPfKeys * kPfKRow, kBuf = kKTile + kPfGroup * kPfKeys * kPfVRow;
-    extern __shared__ __attribute__((aligned(16))) uint16_t tile_lds[];          // kPfLdsBytes
+    extern __shared__ __attribute__((aligned(16))) uint16_t tile_lds[];          // PfTile<D>::kLdsBytes
 
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
@@ -188,10 +195,10 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     const int64_t block_stride = (int64_t)Hkv * bs * D;
 
     if (CONTIG && p.k_cache_w && gu == g * chunks) {
-        // store this workgroup's own tokens' K / V rows of head g (16-byte pieces: 16 per row and tensor)
+        // store this workgroup's own tokens' K / V rows of head g (16-byte pieces: kCPR per row and tensor)
         const int ntok = min(tokens_per_wg, n_b - tq0);
-        for (int idx = threadIdx.x; idx < ntok * 32; idx += kPfWaves * 64) {
-            const int tok = tq0 + (idx >> 5), is_v = (idx >> 4) & 1, piece = idx & 15;
+        for (int idx = threadIdx.x; idx < ntok * 2 * kCPR; idx += kPfWaves * 64) {
+            const int tok = tq0 + idx / (2 * kCPR), is_v = (idx / kCPR) & 1, piece = idx % kCPR;
             const int blk = table[tok >> bs_shift];
             const int64_t dst = blk * block_stride + (int64_t)g * bs * D + (int64_t)(tok & (bs - 1)) * D + 8 * piece;
             const unsigned char* src = (is_v ? vc + (int64_t)tok * p.v_in_stride * 2 : kc + (int64_t)tok * p.k_in_stride * 2) + 16 * piece;
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     // This lane's query row (row n32 of the wave's 32): B operand of the score MFMAs (dims
     // 16m + 8h2 .. +7, m = 0..7), its position, slope and validity.
-    uint4 qb[8];
+    uint4 qb[kQ];
     float posf, lof, slope2, m_ref, lsum;
     bool row_ok, started;
     int64_t out_off;
@@ -222,7 +229,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         lsum = 0.f;
         const uint32_t keep = row_ok ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
+        for (int m = 0; m < kQ; ++m) {
             const uint4 x = *reinterpret_cast<const uint4*>(qp + qrow + 16 * m + 8 * h2);
             qb[m] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
@@ -235,21 +242,21 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #pragma unroll
         for (int e = 0; e < 16; ++e) key_bias[e] = per_key * (float)(8 * (e >> 2) + (e & 3));
     }
-    f32x16 acc[4];                                               // O^T: dims 32db + 8i + 4h2 + j of row n32 in element 4i + j
+    f32x16 acc[kDB];                                             // O^T: dims 32db + 8i + 4h2 + j of row n32 in element 4i + j
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < kDB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[db][e] = 0.f;
 
     // ---- tile staging: threads 0..127 fetch K, 128..255 fetch V; either way a thread moves the
-    // same 16-byte column piece of 4 consecutive keys (16 lanes cover one 256-byte row) ------------
+    // same 16-byte column piece of kKPT consecutive keys (kCPR lanes cover one row) ----------------
     const bool k_loader = tid < 128;
     const int ld = k_loader ? tid : tid - 128;
-    const int l_group = ld >> 4, l_chunk = ld & 15;              // keys 4*group .. +3, dims 8*chunk ..
+    const int l_group = ld / kCPR, l_chunk = ld % kCPR;          // keys kKPT*group .. , dims 8*chunk ..
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
-    const int l_dst = 4 * l_group * l_pitch + 8 * l_chunk;
+    const int l_dst = kKPT * l_group * l_pitch + 8 * l_chunk;
     // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
     // tile t + 2 is on its way to registers; the block id of the next tile to fetch is read one
     // fetch earlier, so a fetch never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
@@ -257,12 +264,12 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: plain loads and stores
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     typedef typename std::conditional<KV8, u32x2, u32x4>::type StageT;   // 8 elements of one key
-    StageT stage[4];
+    StageT stage[kKPT];
     const int last_tile = ntiles - 1;                             // >= kt0
     auto load_blk = [&](int t) __attribute__((always_inline)) {
-        // the four keys of a group share a block (groups are 4-aligned, clamping keeps the block)
+        // the keys of a group share a block (groups are aligned, clamping keeps the block)
         if (CONTIG) return 0;
-        const int key = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
+        const int key = min(min(t, last_tile) * kPfKeys + kKPT * l_group, kmax - 1);
         return table[key >> bs_shift];
     };
     int blk_next = load_blk(kt0);
@@ -272,14 +279,14 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     // rows past the sequence's last key re-read that key, which lies in the same block)
     const unsigned char* const l_lane = l_src + 8 * l_chunk * ES;                 // this lane's column piece
     const uint32_t l_blk_bytes = (uint32_t)(block_stride * ES);                   // < 2^32: one block of all KV heads
-    auto fetch_tile = [&](StageT (&stage)[4], int t) __attribute__((always_inline)) {
-        const int key0 = min(min(t, last_tile) * kPfKeys + 4 * l_group, kmax - 1);
-        const int rmax = kmax - 1 - key0;                         // >= 0; < 3 only at the sequence's end
+    auto fetch_tile = [&](StageT (&stage)[kKPT], int t) __attribute__((always_inline)) {
+        const int key0 = min(min(t, last_tile) * kPfKeys + kKPT * l_group, kmax - 1);
+        const int rmax = kmax - 1 - key0;                         // >= 0; < kKPT - 1 only at the sequence's end
         const unsigned char* base;
         if (CONTIG) base = l_lane + (uint64_t)(uint32_t)key0 * (uint32_t)l_row;
         else base = l_lane + (uint64_t)(uint32_t)blk_next * l_blk_bytes + (uint32_t)((key0 & (bs - 1)) * (D * ES));
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kKPT; ++j)
             stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
         blk_next = load_blk(t + 1);
     };
@@ -291,9 +298,9 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     auto tile_base_v = [&](int j) __attribute__((always_inline)) {
         return ((j / kPfGroup) & 1) * kBuf + kKTile + (j % kPfGroup) * kPfKeys * kPfVRow;
     };
-    auto store_tile = [&](const StageT (&stage)[4], int buf) __attribute__((always_inline)) {
+    auto store_tile = [&](const StageT (&stage)[kKPT], int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kKPT; ++j) {
             u32x4 w;
             if constexpr (KV8) {
                 const uint4 x = widen8_e4m3<DT>(stage[j][0], stage[j][1]);
@@ -326,7 +333,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         // score scale, so that one FMA per score finishes eq. (3))
         f32x16 st = key_bias;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
+        for (int m = 0; m < kQ; ++m) {
             const uint4 ka = *reinterpret_cast<const uint4*>(&tile_lds[tile_base(buf) + n32 * kPfKRow + 16 * m + 8 * h2]);
             st = mfma32<DT>(ka, qb[m], st);
         }
@@ -369,7 +376,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #pragma unroll
             for (int e = 0; e < 16; ++e) x[e] -= delta;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < kDB; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[db][e] *= alpha;
         }
@@ -403,7 +410,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
         const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
         const uint16_t* vrow = &tile_lds[tile_base_v(buf) + (4 * h2 + (s16 >> 2)) * kPfVRow + 16 * dhalf + 4 * (s16 & 3)];
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < kDB; ++db)
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * m * kPfVRow + 32 * db));
@@ -469,7 +476,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     if (row_ok) {
         const float inv = p.out_scale / lt;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < kDB; ++db)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 uint2 packed;

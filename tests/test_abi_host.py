@@ -130,7 +130,7 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     pp = lib.optgqa_prompt_prefill
     f = lambda kc=None, vc=None, D=128, ks=256, cu=one, B=2, bt=None, L=32: pp(
         one, one, one, one, kc, vc, bt, cu, None, 0.1, B, 8, 2, D, 16, 8, L, ks, 256, 0, None)
-    assert f(ks=100) == -2 and f(ks=260) == -3 and f(D=64) == -3 and f(cu=None) == -1 and f(B=0) == 0
+    assert f(ks=100) == -2 and f(ks=260) == -3 and f(D=96) == -3 and f(cu=None) == -1 and f(B=0) == 0
     assert f(kc=one) == -1                                   # one cache without the other
     assert f(kc=one, vc=one) == -1                           # caches without block tables
     assert f(kc=one, vc=one, bt=one, L=8 * 16 + 1) == -2     # prompts longer than the tables can address
