@@ -249,7 +249,7 @@ def main():
             del k_old, v_old
             if decode:
                 ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
-        one_call = decode and (P == 0 or window) and not e4m3
+        one_call = decode and (P == 0 or window or e4m3)
 
         prompt = cfg.name.endswith("-prompt")       # whole prompts, caches empty: one call stores K/V and attends
         assert not (prompt and (e4m3 or window)), "the whole-prompt workload runs over 2-byte inputs, full causal mask"
@@ -259,14 +259,14 @@ def main():
                 G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
                                  dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
                 return
+            if e4m3 and decode:
+                G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, k8, v8, dev.block_tables, dev.context_lens,
+                                  dev.slopes, scale, KV_SCALE, KV_SCALE, max_ctx, ws, stream)
+                return
             if e4m3:
                 G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
-                if decode:
-                    G.paged_attention_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.slopes,
-                                          scale, KV_SCALE, KV_SCALE, max_ctx, ws, stream)
-                else:
-                    G.paged_prefill_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens,
-                                        dev.cu_q_lens, dev.slopes, scale, KV_SCALE, KV_SCALE, case.max_q_len, stream)
+                G.paged_prefill_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.cu_q_lens,
+                                    dev.slopes, scale, KV_SCALE, KV_SCALE, case.max_q_len, stream)
                 return
             if one_call and window:
                 G.decode_step_window(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache,
@@ -348,7 +348,7 @@ def main():
             achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
             if chosen_P == G.SPLIT_BALANCED:
                 kname = "paged_decode_flat_kernel (equal-work split%s%s)" % (
-                    ", E4M3 caches" if e4m3 else ", cache write fused" if one_call else "",
+                    ", E4M3 caches, new token merged by the combine kernel" if e4m3 else ", cache write fused" if one_call else "",
                     f", window {window}" if window else "")
             else:
                 kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"

@@ -179,6 +179,14 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
  * the workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED, ...) is
  * required (OPTGQA_ERR_WORKSPACE without it).
  *
+ * optgqa_decode_step_fp8: optgqa_decode_step over such caches - the new token's K / V rows
+ * (2-byte, k_new / v_new) are quantised as optgqa_reshape_and_cache_fp8 quantises them and
+ * stored at position context_lens[b] - 1, and the attention runs over the codes, the new
+ * token's included: same cache bytes and same output (to rounding) as the two calls.  Two
+ * launches instead of three: the attention kernel streams the tokens already cached, the
+ * combine kernel adds the new token's term and stores its codes.  k_new, v_new 16-byte
+ * aligned, strides multiples of 8 (OPTGQA_ERR_UNSUPPORTED otherwise); workspace required.
+ *
  * optgqa_paged_prefill_fp8: as optgqa_paged_prefill over such caches, same formulas with the
  * causal bound (query i of sequence b sees keys 0 .. pos_i).  head_dim 128 only
  * (OPTGQA_ERR_UNSUPPORTED otherwise); no workspace.
@@ -196,6 +204,14 @@ int optgqa_paged_attention_fp8(void *out, const void *q, const void *k_cache, co
                                int block_size, int max_blocks_per_seq, int max_context_len,
                                void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
                                void *stream);
+
+int optgqa_decode_step_fp8(void *out, const void *q, const void *k_new, const void *v_new,
+                           void *k_cache, void *v_cache, const int32_t *block_tables,
+                           const int32_t *context_lens, const float *alibi_slopes, float scale,
+                           float k_scale, float v_scale, int num_seqs, int num_heads,
+                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                           int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
+                           void *workspace, size_t workspace_bytes, optgqa_dtype dtype, void *stream);
 
 int optgqa_paged_prefill_fp8(void *out, const void *q, const void *k_cache, const void *v_cache,
                              const int32_t *block_tables, const int32_t *context_lens,

@@ -64,6 +64,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_attention_fp8.restype = i32
     lib.optgqa_paged_attention_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
                                                i32, i32, vp, sz, i32, vp]
+    lib.optgqa_decode_step_fp8.restype = i32
+    lib.optgqa_decode_step_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
+                                           i32, i32, i64, i64, vp, sz, i32, vp]
     lib.optgqa_paged_prefill_fp8.restype = i32
     lib.optgqa_paged_prefill_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
                                              i32, i32, i32, vp]
@@ -261,6 +264,35 @@ def paged_attention_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tenso
                                         int(max_context_len), _ptr(workspace), ws_bytes, _dtype_code(q),
                                         _stream(stream))
     _check(rc, "optgqa_paged_attention_fp8")
+
+
+def decode_step_fp8(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                    k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                    context_lens: torch.Tensor, alibi_slopes: Optional[torch.Tensor], scale: float, k_scale: float,
+                    v_scale: float, max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_decode_step_fp8: quantising cache write of the step's new tokens and decode attention over
+    the E4M3 caches in one call."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows and the caches")
+    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
+        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    if B and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if B else Hkv * D
+    vs = int(v_new.stride(0)) if B else Hkv * D
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib.optgqa_decode_step_fp8(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                    _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale),
+                                    float(k_scale), float(v_scale), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
+                                    int(max_context_len), ks, vs, _ptr(workspace), ws_bytes, _dtype_code(q),
+                                    _stream(stream))
+    _check(rc, "optgqa_decode_step_fp8")
 
 
 def paged_prefill_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -52,9 +52,7 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
 // Cache store with a quantiser in front, for caches that hold 1-byte E4M3 codes (largest finite
 // value 448, no infinities) and one scale per tensor:
 //     code = nearest_e4m3( fp32(x) * inv_scale ),  inv_scale = fp32(1 / scale) computed on the host.
-// One fp32 multiplication, then the hardware's round-to-nearest-even conversion; the hardware
-// turns magnitudes beyond the format's range into NaN, so the product is clamped to +-448 first
-// (saturation), and a NaN input is given the code 0x7f explicitly.
+// One fp32 multiplication, then e4m3_codes2 (round to nearest even, saturating, NaN -> 0x7f).
 // One thread moves 8 elements of one token's K or V row: 16 bytes in, 8 bytes out.
 template <int DT>
 __global__ __launch_bounds__(256) void reshape_and_cache_e4m3_kernel(
@@ -86,11 +84,7 @@ __global__ __launch_bounds__(256) void reshape_and_cache_e4m3_kernel(
     uint32_t packed[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const float a = widen_lo<DT>(w[i]) * inv, b = widen_hi<DT>(w[i]) * inv;
-        const float ac = fminf(fmaxf(a, -448.f), 448.f), bc = fminf(fmaxf(b, -448.f), 448.f);
-        uint32_t two = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ac, bc, 0, false) & 0xffffu;
-        if (a != a) two = (two & 0xff00u) | 0x7fu;
-        if (b != b) two = (two & 0x00ffu) | 0x7f00u;
+        const uint32_t two = e4m3_codes2(widen_lo<DT>(w[i]) * inv, widen_hi<DT>(w[i]) * inv);
         packed[i >> 1] |= two << (16 * (i & 1));
     }
     unsigned char* out = (which == 0 ? k_cache : v_cache) + dst;

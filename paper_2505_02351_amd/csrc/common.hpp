@@ -100,5 +100,16 @@ template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint
     return make_uint4(narrow2<DT>(a[0], a[1]), narrow2<DT>(b[0], b[1]), narrow2<DT>(c[0], c[1]), narrow2<DT>(d[0], d[1]));
 }
 
+// two fp32 values -> two E4M3 codes (bits 0..15): round to nearest even; the hardware conversion
+// turns magnitudes beyond the format's range into NaN, so the values are clamped to +-448 first
+// (saturation), and a NaN input is given the code 0x7f explicitly
+__device__ __forceinline__ uint32_t e4m3_codes2(float a, float b)
+{
+    const float ac = fminf(fmaxf(a, -448.f), 448.f), bc = fminf(fmaxf(b, -448.f), 448.f);
+    uint32_t two = (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(ac, bc, 0, false) & 0xffffu;
+    if (a != a) two = (two & 0xff00u) | 0x7fu;
+    if (b != b) two = (two & 0x00ffu) | 0x7f00u;
+    return two;
+}
 
 }  // namespace optgqa

@@ -71,15 +71,16 @@ __device__ __forceinline__ int flat_first_token(int L, int W) { return W > 0 ? m
 
 // Tiles of one segment of a sequence of length L.  Plain: the 16-token tiles of the cache that
 // hold a visible token (tile indices first_token / 16 .. (L - 1) / 16).  FUSED (the step's cache
-// write happens inside the kernel): the same over the tokens already in the cache, L - 1 of
-// them, plus one tile that holds only the new token.
-template <bool FUSED> __device__ __forceinline__ int flat_tiles(int L, int W)
+// write happens inside the call): the same over the tokens already in the cache, L - 1 of
+// them, plus - 2-byte caches - one tile that holds only the new token (8-bit caches: the new
+// token's term is added by the combine kernel, no tile).
+template <bool FUSED, bool KV8 = false> __device__ __forceinline__ int flat_tiles(int L, int W)
 {
     if (L <= 0) return 0;
     const int lo = flat_first_token(L, W);
     const int reg = FUSED ? L - 1 : L;                          // tokens read from the cache
     const int regular = reg > lo ? (reg + kMmaTile - 1) / kMmaTile - lo / kMmaTile : 0;
-    return regular + (FUSED ? 1 : 0);
+    return regular + (FUSED && !KV8 ? 1 : 0);
 }
 
 __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
@@ -114,7 +115,7 @@ struct MmaTile8 {
 template <int DT, bool FUSED, bool KV8 = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
-    static_assert(!(FUSED && KV8), "the fused cache write exists for 2-byte caches only");
+    constexpr bool NEW_TILE = FUSED && !KV8;            // the new token is a tile of its own, read from k_new / v_new
     typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     constexpr int D = 128;
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     for (int i = 0; i < k; ++i) {
         const int idx = lane * k + i;
         my_len = idx < B ? ctx[idx] : 0;
-        mine += flat_tiles<FUSED>(my_len, W);
+        mine += flat_tiles<FUSED, KV8>(my_len, W);
     }
     const int incl = wave_inclusive_scan(mine, lane);
     const int P_total = __builtin_amdgcn_readlane(incl, 63);
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         L = 0;
         for (int base = 0; base < k; base += 64) {
             const int idx = cl * k + base + lane;
-            const int nl = flat_tiles<FUSED>(base + lane < k && idx < B ? ctx[idx] : 0, W);
+            const int nl = flat_tiles<FUSED, KV8>(base + lane < k && idx < B ? ctx[idx] : 0, W);
             const int inc2 = wave_inclusive_scan(nl, lane);
             const int tot = __builtin_amdgcn_readlane(inc2, 63);
             if (Y * (P_b + tot) > f0) {
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
     auto tile_src = [&](const int32_t* tab, int64_t head_off, int Lseg, int nseg, int reg_end,
                         int64_t new_k, int64_t new_v, int ti) __attribute__((always_inline)) {
         TileSrc s;
-        if (FUSED && ti == nseg - 1) {
+        if (NEW_TILE && ti == nseg - 1) {
             s.k = k_new + new_k * 2;
             s.v = v_new + new_v * 2;
             s.last_row = 0;
@@ -294,20 +295,19 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const int Lm1 = L - 1;
         // regular (cached) tokens the piece covers end here; FUSED: the segment's last tile is the new token
         const int first = flat_first_token(L, W) / TILE;     // the segment's tiles start at this tile of the cache
-        const int reg_end = FUSED ? min(Lm1, ((tau_end == n ? tau_end - 1 : tau_end) + first) * TILE)
-                                  : min(L, (tau_end + first) * TILE);
+        const int reg_end = min(FUSED ? Lm1 : L, ((NEW_TILE && tau_end == n ? tau_end - 1 : tau_end) + first) * TILE);
         const int g = y / chunks;
         const int32_t* table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
-        const int64_t new_k = FUSED ? b * p.k_new_stride + (int64_t)g * D : 0;
-        const int64_t new_v = FUSED ? b * p.v_new_stride + (int64_t)g * D : 0;
+        const int64_t new_k = NEW_TILE ? b * p.k_new_stride + (int64_t)g * D : 0;
+        const int64_t new_v = NEW_TILE ? b * p.v_new_stride + (int64_t)g * D : 0;
 
         load_q(qa, slope2, b, y);
         if (!chained) {
             d0 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau);
             load_tile(buf[0], d0);
         }
-        if (FUSED && tau_end == n && y == g * chunks) {
+        if (NEW_TILE && tau_end == n && y == g * chunks) {
             // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
             const int blk = scalar_load_i32(table + (Lm1 >> bs_shift));
             const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 do {                                         // skip sequences without tokens
                     ++nb;
                     nL = scalar_load_i32(ctx + nb);
-                    nn = flat_tiles<FUSED>(nL, W);
+                    nn = flat_tiles<FUSED, KV8>(nL, W);
                 } while (nn == 0 && nb + 1 < B);
                 if (nn == 0) {                               // cannot happen for consistent lengths
                     has_next = false;
@@ -351,10 +351,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const int x_L = has_next ? nL : L, x_n = has_next ? nn : n;
         const int n_first = flat_first_token(nL, W) / TILE;
         const int x_reg_end = !has_next ? reg_end
-                              : FUSED ? min(nL - 1, ((n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE)
-                                      : min(nL, (n_tau_end + n_first) * TILE);
-        const int64_t x_new_k = !has_next ? new_k : FUSED ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
-        const int64_t x_new_v = !has_next ? new_v : FUSED ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
+                              : min(FUSED ? nL - 1 : nL, ((NEW_TILE && n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE);
+        const int64_t x_new_k = !has_next ? new_k : NEW_TILE ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
+        const int64_t x_new_v = !has_next ? new_v : NEW_TILE ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int x_ti = has_next ? 0 : tau + j_last;
 
         // ---- both contractions on 16-bit MFMAs, transposed so that nothing is transposed in registers:
@@ -536,7 +535,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
 // u + s for the units u that touched its segment (a contiguous range found from P_b, n_b and c).
 // Same arithmetic as the fixed-partition combine:
 //   M = max_u m_u,  out = sum_u 2^(m_u-M) o_u / sum_u 2^(m_u-M) l_u.
-template <int DT>
+//
+// NEWTOK (decode step over E4M3 caches): the step's new token was not among the streamed tiles.
+// Its term is added here from k_new / v_new - quantised exactly as the cache write quantises,
+// so that it is the cache's own codes that are attended to - and the thread that holds dims
+// od .. od + 3 of a KV head's first query head stores the four K and four V codes into the caches
+// (Alg. 2 "store K, V": nothing in the step has read that cache row).
+template <int DT, bool NEWTOK = false>
 __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kernel(const DecodeParams p)
 {
     constexpr int D = 128;
@@ -556,18 +561,30 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int G = p.num_heads / p.num_kv_heads;
     const int chunks = G / GH;
     const int g = h / G;
+    // NEWTOK: the new token's rows, the query and the block of the new row are fetched first, so that
+    // they arrive while the partial results are being read
+    uint2 kw = make_uint2(0u, 0u), vw = kw, qw = kw;
+    int new_blk = 0;
+    if constexpr (NEWTOK) {
+        kw = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.k_new) + (int64_t)b * p.k_new_stride + (int64_t)g * D + od);
+        vw = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.v_new) + (int64_t)b * p.v_new_stride + (int64_t)g * D + od);
+        qw = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(p.q) + ((int64_t)b * p.num_heads + h) * D + od);
+        new_blk = p.block_tables[(int64_t)b * p.max_blocks_per_seq + (L - 1) / p.block_size];
+    }
     const int within = h - g * G;
     const int chunk = within / GH;
     const int hh = within - chunk * GH;
     const int Y = p.segs_per_seq;
     const int y = g * chunks + chunk;
-    const int n = p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);      // the numbering the main kernel used
+    // the numbering the main kernel used
+    const int n = NEWTOK ? flat_tiles<true, true>(L, p.window)
+                         : p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);
     // (the clamps only matter if the lengths changed under the kernels: they keep every read
-    // inside the workspace)
-    const int c = max(p.plan[p.num_seqs], 1);
-    const int F0 = Y * p.plan[b] + y * n;
+    // inside the workspace; n == 0 - NEWTOK only: nothing was streamed, nobody wrote the plan)
+    const int c = n > 0 ? max(p.plan[p.num_seqs], 1) : 1;
+    const int F0 = n > 0 ? Y * p.plan[b] + y * n : 0;
     const int u0 = min(max(F0 / c, 0), p.num_units - 1);
-    const int np = min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0);
+    const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
     const int64_t base = ((int64_t)u0 + (int64_t)b * Y + y) * GH + hh;       // slot stride between units: GH
     float M = -INFINITY;
     for (int i = 0; i < np; ++i) M = fmaxf(M, p.ws_m[base + (int64_t)i * GH]);
@@ -591,6 +608,35 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
             num.y = fmaf(fct, x[k].y, num.y);
             num.z = fmaf(fct, x[k].z, num.z);
             num.w = fmaf(fct, x[k].w, num.w);
+        }
+    }
+    if constexpr (NEWTOK) {
+        // the new token, at the query's own position (ALiBi term 0): codes, their values, its score
+        const uint32_t kcodes = e4m3_codes2(widen_lo<DT>(kw.x) * p.k_inv_scale, widen_hi<DT>(kw.x) * p.k_inv_scale) |
+                                e4m3_codes2(widen_lo<DT>(kw.y) * p.k_inv_scale, widen_hi<DT>(kw.y) * p.k_inv_scale) << 16;
+        const uint32_t vcodes = e4m3_codes2(widen_lo<DT>(vw.x) * p.v_inv_scale, widen_hi<DT>(vw.x) * p.v_inv_scale) |
+                                e4m3_codes2(widen_lo<DT>(vw.y) * p.v_inv_scale, widen_hi<DT>(vw.y) * p.v_inv_scale) << 16;
+        const f32x2 k01 = __builtin_amdgcn_cvt_pk_f32_fp8(kcodes, false), k23 = __builtin_amdgcn_cvt_pk_f32_fp8(kcodes, true);
+        const f32x2 v01 = __builtin_amdgcn_cvt_pk_f32_fp8(vcodes, false), v23 = __builtin_amdgcn_cvt_pk_f32_fp8(vcodes, true);
+        float dot = widen_lo<DT>(qw.x) * k01[0];
+        dot = fmaf(widen_hi<DT>(qw.x), k01[1], dot);
+        dot = fmaf(widen_lo<DT>(qw.y), k23[0], dot);
+        dot = fmaf(widen_hi<DT>(qw.y), k23[1], dot);
+#pragma unroll
+        for (int off = 1; off < kVecPerHead; off <<= 1) dot += __shfl_xor(dot, off);      // a head's 32 threads are half a wave
+        const float s_new = dot * p.scale2;                                               // eq. (3), base 2, k_scale folded in
+        const float M2 = fmaxf(M, s_new);
+        const float f_old = np > 0 ? fast_exp2(M - M2) : 0.f, f_new = fast_exp2(s_new - M2);
+        den = fmaf(den, f_old, f_new);
+        num.x = fmaf(num.x, f_old, f_new * v01[0]);
+        num.y = fmaf(num.y, f_old, f_new * v01[1]);
+        num.z = fmaf(num.z, f_old, f_new * v23[0]);
+        num.w = fmaf(num.w, f_old, f_new * v23[1]);
+        if (h == g * G) {
+            const int pos = L - 1;
+            const int64_t dst = (((int64_t)new_blk * p.num_kv_heads + g) * p.block_size + pos % p.block_size) * D + od;
+            *reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(p.k_cache_w) + dst) = kcodes;
+            *reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(p.v_cache_w) + dst) = vcodes;
         }
     }
     const float inv = p.out_scale / den;                 // out_scale: 1, or v_scale of an E4M3 cache

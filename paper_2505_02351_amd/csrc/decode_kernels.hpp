@@ -38,6 +38,10 @@ struct DecodeParams {
     int segs_per_seq;           // KV heads x head chunks
     int32_t* plan;              // [num_seqs + 1]: tile prefix P_b per non-empty sequence, then tiles per unit
     float out_scale;            // multiplies the combined output (v_scale of an E4M3 cache, else 1)
+    // E4M3 decode step: the new token is not among the streamed tiles; the combine kernel adds its term
+    // (quantised with these reciprocal scales, as the cache write does) and stores its codes
+    int new_token_in_combine;
+    float k_inv_scale, v_inv_scale;
     int window;                 // > 0: a query sees only the last `window` tokens up to its own (equal-work kernel only)
     // Fused decode step (cache write inside the attention kernel): the new token of sequence b
     // sits at position context_lens[b] - 1; its rows come from k_new / v_new instead of the cache.

@@ -259,13 +259,16 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     int rc = launch_status();
     if (rc != OPTGQA_OK) return rc;
     constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
-    hipLaunchKernelGGL((paged_decode_flat_reduce_kernel<DT>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+    hipLaunchKernelGGL((paged_decode_flat_reduce_kernel<DT, FUSED && KV8>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
                        dim3(kReduceThreads), 0, st, p);
     return launch_status();
 }
 
 int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
 {
+    if (kv8 && p.k_new)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, true, true>(p, workgroups, st);
     if (kv8)
         return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, true>(p, workgroups, st)
                                    : launch_decode_flat_dt<kBF16, false, true>(p, workgroups, st);
@@ -477,7 +480,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (kv_scales) {
         if (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f)
             return OPTGQA_ERR_SHAPE;
-        if (head_dim != 128 || step) return OPTGQA_ERR_UNSUPPORTED;
+        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
         partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that reads E4M3 caches
     }
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
@@ -531,9 +534,14 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.k_new_stride = p.v_new_stride = 0;
     p.out_scale = 1.f;
     p.window = window > 0 ? window : 0;
+    p.new_token_in_combine = 0;
+    p.k_inv_scale = p.v_inv_scale = 1.f;
     if (kv_scales) {
         p.scale2 *= kv_scales[0];
         p.out_scale = kv_scales[1];
+        p.k_inv_scale = 1.0f / kv_scales[0];             // one fp32 division each, as the cache write does
+        p.v_inv_scale = 1.0f / kv_scales[1];
+        p.new_token_in_combine = step != nullptr;
     }
 
     // The cache write rides inside the equal-work kernel when that kernel runs and the new rows
@@ -542,6 +550,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (step) {
         fused = s.partition_size == OPTGQA_SPLIT_BALANCED && aligned16(step->k_new) && aligned16(step->v_new) &&
                 step->k_stride % 8 == 0 && step->v_stride % 8 == 0;
+        if (!fused && kv_scales) return OPTGQA_ERR_UNSUPPORTED;   // 8-bit step: new rows must move as 16-byte pieces
         if (!fused) {
             const int rc = write_new_tokens(*step, nullptr, block_tables, context_lens, num_seqs, num_kv_heads,
                                             head_dim, block_size, max_blocks_per_seq, st);
@@ -698,6 +707,22 @@ int optgqa_decode_step_window(void* out, const void* q, const void* k_new, const
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
                           static_cast<hipStream_t>(stream), &step, nullptr, window);
+}
+
+int optgqa_decode_step_fp8(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                           void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                           const float* alibi_slopes, float scale, float k_scale, float v_scale,
+                           int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                           int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
+                           int64_t v_token_stride, void* workspace, size_t workspace_bytes,
+                           optgqa_dtype dtype, void* stream)
+{
+    const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
+    const float kv_scales[2] = {k_scale, v_scale};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), &step, kv_scales);
 }
 
 static int prefill_impl(void* out, const void* q, const void* k_cache, const void* v_cache,

@@ -111,6 +111,10 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     g = lambda k=one, ks=1.0, stride=256, T=3: r(k, one, one, one, one, T, 2, 128, 16, stride, 256, ks, 1.0, 1, None)
     assert g(ks=0.0) == -2 and g(stride=100) == -2 and g(stride=260) == -3 and g(k=ctypes.c_void_p(8)) == -3
     assert g(T=0) == 0
+    sf = lib.optgqa_decode_step_fp8
+    h = lambda ks=1.0, D=128, kn=one, st=256, ws=None: sf(one, one, kn, one, one, one, one, one, None, 0.1, ks, 1.0, 2, 8, 2,
+                                                          D, 16, 8, 128, st, 256, ws, 0, 0, None)
+    assert h(ks=0.0) == -2 and h(D=64) == -3 and h(kn=None) == -1 and h(st=100) == -2 and h() == -4
     pf = lib.optgqa_paged_prefill_fp8
     e = lambda ks=1.0, D=128, B=2, cu=one: pf(one, one, one, one, one, one, cu, None, 0.1, ks, 1.0, B, 8, 2, D, 16, 8,
                                              32, 0, None)

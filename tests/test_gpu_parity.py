@@ -564,6 +564,79 @@ def test_fp8_prefill_workload_sampled(U, oracle):
     assert err <= U.TOL[case.dtype], err
 
 
+@pytest.mark.parametrize("i", [2, 3, 4, 5, 7, 9])
+def test_fp8_decode_step_sweep(U, oracle, i):
+    """optgqa_decode_step_fp8 on the head_dim 128 sweep shapes: caches holding every token but the
+    step's are quantised first; after the call the caches must equal the oracle's quantised image
+    of the whole batch bit for bit and the output its E4M3 attention clause."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
+    cfg = W.small_config(name=f"fp8step{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv, head_dim=D,
+                         block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi, seed=1900 + i)
+    case = W.make_case(cfg)
+    k_scale, v_scale = 0.0125, 0.03
+    kc8, vc8, _ = __import__("pins_e4m3").quantised_cache(case, k_scale, v_scale)       # all tokens, oracle side
+    k_old, v_old, slots_old = W.all_token_rows(case, include_new=False)
+    dk = torch.full(kc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    dv = torch.full(vc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    if len(slots_old):
+        G.reshape_and_cache_fp8(U.to_dev(k_old, dtype), U.to_dev(v_old, dtype), dk, dv,
+                                torch.from_numpy(slots_old).cuda(), k_scale, v_scale)
+    dev = U.DevCase(case)
+    ws = dev.workspace(BALANCED)[0]
+    for window_free in (True,):
+        dev.out.fill_(float("nan"))
+        G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens, dev.slopes,
+                          float(case.scale), k_scale, v_scale, case.max_context_len, ws)
+        torch.cuda.synchronize()
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                 k_scale, v_scale, dtype)
+    err = U.max_abs_err(U.to_host(dev.out), ref, dtype)
+    assert err <= U.TOL[dtype], err
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_fp8_decode_step_edge_lengths(U, oracle, dtype):
+    """The new token alone (L = 1: nothing is streamed, the combine kernel does it all), first / last
+    row of a block, absent sequences (L = 0), more than 64 sequences."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    import pins_e4m3
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1, 0, 300, 1, 1, 2] * 4, np.int32)
+    cfg = W.small_config(name="fp8step_edges", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=len(lens) * 33, ctx_lo=1, ctx_hi=512, seed=1921)
+    case = W.make_case(cfg, context_lens=lens)
+    full = lambda a, shape: (lambda z: (z.__setitem__(lens > 0, a), z)[1])(np.zeros(shape, np.uint16))
+    q_full = full(case.q, (len(lens), 8, 128))
+    k_full = full(case.k_new, (len(lens), 2, 128))
+    v_full = full(case.v_new, (len(lens), 2, 128))
+    k_scale, v_scale = 0.02, 0.0125
+    kc8, vc8, _ = pins_e4m3.quantised_cache(case, k_scale, v_scale)
+    k_old, v_old, slots_old = W.all_token_rows(case, include_new=False)
+    dk = torch.full(kc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    dv = torch.full(vc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    G.reshape_and_cache_fp8(U.to_dev(k_old, dtype), U.to_dev(v_old, dtype), dk, dv, torch.from_numpy(slots_old).cuda(),
+                            k_scale, v_scale)
+    case.q = q_full
+    dev = U.DevCase(case)
+    dev.k_new, dev.v_new = U.to_dev(k_full, dtype), U.to_dev(v_full, dtype)
+    ws = dev.workspace(BALANCED)[0]
+    dev.out.fill_(float("nan"))
+    G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens, dev.slopes,
+                      float(case.scale), k_scale, v_scale, case.max_context_len, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                 k_scale, v_scale, dtype)
+    got = U.to_host(dev.out)
+    assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype]
+    assert not got[lens == 0].any()
+
+
 def test_fp8_rejects_what_it_cannot_do(U):
     import torch
     import paper_2505_02351_amd as G
@@ -903,8 +976,8 @@ def test_random_mix_of_decode_calls(U, oracle):
         lens = rng.integers(1, hi + 1, size=B).astype(np.int32)
         case = W.make_case(cfg, context_lens=lens)
         kc, vc = oracle_filled(oracle, case)
-        mode = ["plain", "step", "window", "window_step", "fp8"][int(rng.integers(5))]
-        if mode == "fp8" and D != 128:
+        mode = ["plain", "step", "window", "window_step", "fp8", "fp8_step"][int(rng.integers(6))]
+        if mode in ("fp8", "fp8_step") and D != 128:
             mode = "plain"
         tag = f"case {it}: {mode} D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} {dtype}"
         dev = U.DevCase(case)
@@ -933,7 +1006,20 @@ def test_random_mix_of_decode_calls(U, oracle):
             k_scale, v_scale = float(rng.choice([0.01, 0.05, 1.0])), float(rng.choice([0.02, 0.5]))
             kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
             assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8), tag
-            got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
+            if mode == "fp8_step":
+                # wipe the new tokens' rows again: the step has to put them back
+                s_ = torch.from_numpy(case.slot_mapping).cuda()
+                dk[s_ // bs, :, s_ % bs, :] = 0x7F
+                dv[s_ // bs, :, s_ % bs, :] = 0x7F
+                ws = dev.workspace(BALANCED)[0]
+                dev.out.fill_(float("nan"))
+                G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens,
+                                  dev.slopes, float(case.scale), k_scale, v_scale, case.max_context_len, ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8), tag
+                got = U.to_host(dev.out)
+            else:
+                got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
             ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes,
                                          case.scale, k_scale, v_scale, dtype)
         check_scaled(U, got, ref, dtype, tag)
