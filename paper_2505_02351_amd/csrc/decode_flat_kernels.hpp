@@ -552,7 +552,10 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int b = blockIdx.y;
     if (h >= p.num_heads) return;
     uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;
+    // (this kernel is a few dependent memory round trips and little else: the three values that
+    // everything else depends on are fetched together, before the first branch)
     const int L = p.context_lens[b];
+    const int plan_total = p.plan[p.num_seqs], plan_b = p.plan[b];    // readable garbage where nobody wrote them
     if (L <= 0) {
         *reinterpret_cast<uint2*>(o) = make_uint2(0u, 0u);
         return;
@@ -581,8 +584,8 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
                          : p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);
     // (the clamps only matter if the lengths changed under the kernels: they keep every read
     // inside the workspace; n == 0 - NEWTOK only: nothing was streamed, nobody wrote the plan)
-    const int c = n > 0 ? max(p.plan[p.num_seqs], 1) : 1;
-    const int F0 = n > 0 ? Y * p.plan[b] + y * n : 0;
+    const int c = n > 0 ? max(plan_total, 1) : 1;
+    const int F0 = n > 0 ? Y * plan_b + y * n : 0;
     const int u0 = min(max(F0 / c, 0), p.num_units - 1);
     const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
     const int64_t base = ((int64_t)u0 + (int64_t)b * Y + y) * GH + hh;       // slot stride between units: GH
