@@ -70,6 +70,10 @@ def parse():
     ap.add_argument("--window", type=int, default=0,
                     help="> 0: the same workload with a sliding window of this many tokens (local mask of "
                          "Alg. 1), 2-byte caches; KV bytes and flops count the visible keys only")
+    ap.add_argument("--shared-prefix", type=int, default=0, metavar="GROUP",
+                    help="> 1: runs of GROUP consecutive sequences share 90 %% of their common cached length "
+                         "through the same physical blocks (decode workloads); rates still count every "
+                         "sequence's logical KV bytes")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache pass (evict, then time each step)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
@@ -220,6 +224,10 @@ def main():
         """Runs one workload; returns (result dict, case)."""
         cfg = W.CONFIGS[workload]
         case = W.make_case(cfg)
+        shared_tokens = 0
+        if args.shared_prefix > 1:
+            assert cfg.kind == "decode", "--shared-prefix applies to decode workloads"
+            shared_tokens = W.share_prefix_blocks(case, args.shared_prefix, 0.9)
         from paper_2505_02351_amd.testing import DevCase
         dev = DevCase(case)
         P = cfg.partition_size if args.partition_size is None else args.partition_size
@@ -431,13 +439,19 @@ def main():
                        "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
                        "calls_per_step": 1 if one_call or prompt else 2,
                        "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype,
-                       **({"window": window} if window else {})},
+                       **({"window": window} if window else {}),
+                       **({"shared_prefix_group": args.shared_prefix,
+                           "aliased_context_tokens": int(shared_tokens)} if shared_tokens else {})},
             "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
         }
         if cold:
             result["cold_step"] = cold
+        if shared_tokens:
+            result["roofline"]["note"] = ("algorithmic bytes count every sequence's logical KV; %d of %d context "
+                                          "tokens alias another sequence's blocks and may be served by the "
+                                          "last-level cache: not an HBM rate" % (shared_tokens, int(case.context_lens.sum())))
         result["cache_write"] = cache_write
         if stream_probe:
             result["stream_probe"] = stream_probe

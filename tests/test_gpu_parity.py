@@ -939,6 +939,24 @@ def test_prompt_prefill_rejects_what_it_cannot_do(U):
         G.prompt_prefill(torch.empty_like(q), q, kv, kv, None, None, None, cu, None, 0.1, 2)
 
 
+def test_decode_with_shared_prefix_blocks(U, oracle):
+    """Block tables that alias each other (groups of sequences served from the same physical
+    prefix blocks, Section III-B "cache sharing and reuse"): nothing in the path assumes blocks are
+    private, so the step must still match the oracle, which walks the same tables."""
+    cfg = W.small_config(name="shared", dtype=W.BF16, batch=12, num_heads=16, num_kv_heads=4, head_dim=128,
+                         block_size=16, num_blocks=12 * 64 + 7, ctx_lo=300, ctx_hi=1000, seed=2100)
+    case = W.make_case(cfg)
+    shared = W.share_prefix_blocks(case, group=4, fraction=0.9)
+    assert shared > 0
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    got = dev.step()
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+    assert U.max_abs_err(dev.decode(partition_size=256), ref, W.BF16) <= U.TOL[W.BF16]
+
+
 # ------------------------------------------------------------------ seeded random mixes
 def check_scaled(U, got, ref, dtype, tag):
     """The stated tolerances budget one output rounding at magnitudes below 4 (half an ulp there:

@@ -163,6 +163,24 @@ def all_token_rows(case: "Case", include_new: bool = True):
     return np.concatenate(ks), np.concatenate(vs), np.concatenate(slots).astype(np.int64)
 
 
+def share_prefix_blocks(case: "Case", group: int, fraction: float = 0.9) -> int:
+    """Rewrite the block tables so that the sequences of every run of ``group`` consecutive
+    sequences share their leading blocks with the run's first one (a common prompt prefix served
+    from the same physical blocks): ``fraction`` of the run's shortest cached length, rounded
+    down to whole blocks, never the block that receives a new token.  Returns the number of
+    context tokens that now alias another sequence's.  Pure index work."""
+    bs = case.cfg.block_size
+    shared = 0
+    for g0 in range(0, case.cfg.batch, group):
+        members = list(range(g0, min(g0 + group, case.cfg.batch)))
+        cached = case.context_lens[members].astype(np.int64) - case.q_lens[members]
+        nblk = int(max(int(cached.min()), 0) * fraction) // bs
+        for m in members[1:]:
+            case.block_tables[m, :nblk] = case.block_tables[g0, :nblk]
+            shared += nblk * bs
+    return shared
+
+
 def make_case(cfg: Config, seed: Optional[int] = None, perm_seed: Optional[int] = None,
               context_lens: Optional[np.ndarray] = None, slopes: Optional[np.ndarray] = None,
               identity_blocks: bool = False) -> Case:
