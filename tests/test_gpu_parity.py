@@ -957,6 +957,32 @@ def test_decode_with_shared_prefix_blocks(U, oracle):
     assert U.max_abs_err(dev.decode(partition_size=256), ref, W.BF16) <= U.TOL[W.BF16]
 
 
+def test_prefill_with_a_sequence_without_new_tokens(U, oracle):
+    """A batch in which one sequence contributes no query token (cu_q_lens repeats a value): its
+    workgroups have nothing to do, the others are unaffected."""
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="pf_empty", kind="prefill", dtype=W.F16, batch=3, num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=3 * 20 + 5, ctx_lo=40, ctx_hi=300, q_len=37, seed=2200)
+    case = W.make_case(cfg)
+    kc, vc = oracle_filled(oracle, case)
+    # insert an extra sequence (a copy of sequence 0's table and length) with zero new tokens after sequence 0
+    bt = np.insert(case.block_tables, 1, case.block_tables[0], axis=0)
+    cl = np.insert(case.context_lens, 1, case.context_lens[0]).astype(np.int32)
+    cu = np.insert(case.cu_q_lens, 1, case.cu_q_lens[1]).astype(np.int32)
+    ref = oracle.paged_prefill(case.q, kc, vc, bt, cl, cu, case.slopes, case.scale, W.F16)
+    ref0 = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                                case.scale, W.F16)
+    assert np.array_equal(ref, ref0)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    out = torch.full_like(dev.q, float("nan"))
+    G.paged_prefill(out, dev.q, dev.k_cache, dev.v_cache, torch.from_numpy(bt).cuda(), torch.from_numpy(cl).cuda(),
+                    torch.from_numpy(cu).cuda(), dev.slopes, float(case.scale), case.max_q_len)
+    torch.cuda.synchronize()
+    assert U.max_abs_err(U.to_host(out), ref, W.F16) <= U.TOL[W.F16]
+
+
 # ------------------------------------------------------------------ seeded random mixes
 def check_scaled(U, got, ref, dtype, tag):
     """The stated tolerances budget one output rounding at magnitudes below 4 (half an ulp there:
