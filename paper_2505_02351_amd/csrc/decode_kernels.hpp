@@ -140,8 +140,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
         const int64_t off = ((blk * Hkv + g) * bs + (t0 % bs) + r) * D + 8 * c;
         uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
         if (valid) {
-            kr = *reinterpret_cast<const uint4*>(kc + off);
-            vr = *reinterpret_cast<const uint4*>(vc + off);
+            kr = stream_load16(kc + off);
+            vr = stream_load16(vc + off);
         }
         const float vf[8] = {widen_lo<DT>(vr.x), widen_hi<DT>(vr.x), widen_lo<DT>(vr.y), widen_hi<DT>(vr.y),
                              widen_lo<DT>(vr.z), widen_hi<DT>(vr.z), widen_lo<DT>(vr.w), widen_hi<DT>(vr.w)};

@@ -201,8 +201,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
             const int t0 = min(tile_t0 + s * TPS, t_last0);                           // wave-uniform
             const int64_t uni = blk * block_stride + (int64_t)(t0 & (bs - 1)) * D;
             const int lane_off = (min(t0 + r, t_last) - t0) * D + 8 * c;
-            __builtin_amdgcn_global_load_lds(kc_g + uni + lane_off, slot + s * 1024, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vc_g + uni + lane_off, slot + (U + s) * 1024, 16, 0, 0);
+            // (last operand: cache policy; 2 = the non-temporal hint, see stream_load16)
+            __builtin_amdgcn_global_load_lds(kc_g + uni + lane_off, slot + s * 1024, 16, 0, OPTGQA_STREAM_NT ? 2 : 0);
+            __builtin_amdgcn_global_load_lds(vc_g + uni + lane_off, slot + (U + s) * 1024, 16, 0, OPTGQA_STREAM_NT ? 2 : 0);
         }
     };
 

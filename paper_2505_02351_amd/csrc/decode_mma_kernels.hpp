@@ -138,11 +138,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void 
         const int tk = min(tile_t0 + j16, t_last) - tile_t0;
         const uint16_t* ka = kc_g + uni + tk * D + 8 * hg;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) T.k[i] = *reinterpret_cast<const uint4*>(ka + 32 * i);
+        for (int i = 0; i < 4; ++i) T.k[i] = stream_load16(ka + 32 * i);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const int tv = min(tile_t0 + 4 * s + hg, t_last) - tile_t0;
-            T.v[s] = *reinterpret_cast<const uint4*>(vc_g + uni + tv * D + 8 * j16);
+            T.v[s] = stream_load16(vc_g + uni + tv * D + 8 * j16);
         }
     };
 

@@ -28,9 +28,9 @@ __global__ __launch_bounds__(256, 2) void stream_probe_kernel(
         const unsigned char* kp = k_pool + piece * 4096;
         const unsigned char* vp = v_pool + piece * 4096;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) T.r[i] = *reinterpret_cast<const uint4*>(kp + row * 256 + 64 * i + 16 * slab);
+        for (int i = 0; i < 4; ++i) T.r[i] = stream_load16(kp + row * 256 + 64 * i + 16 * slab);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) T.r[4 + i] = *reinterpret_cast<const uint4*>(vp + lane * 16 + 1024 * i);
+        for (int i = 0; i < 4; ++i) T.r[4 + i] = stream_load16(vp + lane * 16 + 1024 * i);
     };
     ProbeTile buf[2];
     uint4 acc = make_uint4(0, 0, 0, 0);
