@@ -42,8 +42,8 @@ KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-44
 # factor a plain copy kernel of known size reads on the same counters.  None until
 # measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # from the committed rocprofv3 counter summary of this workload: (310421.1 KiB FETCH_SIZE x 2.000 + 5373.0 KiB WRITE_SIZE x 1.000) x 1024
-    "C3": 641244365,
+    # from the committed rocprofv3 counter summary of this workload: (311544.7 KiB FETCH_SIZE x 2.000 + 5330.4 KiB WRITE_SIZE x 1.000) x 1024
+    "C3": 643501963,
 }
 
 
