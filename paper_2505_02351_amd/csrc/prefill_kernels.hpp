@@ -76,15 +76,11 @@ constexpr int kPfWaves = 4;
 constexpr int kPfRowBlocks = 2;                          // 16-row blocks per wave
 constexpr int kPfRows = kPfWaves * kPfRowBlocks * 16;    // (token, head) rows per workgroup
 constexpr int kPfKeys = 32;                              // keys per tile
-#ifndef OPTGQA_PF_GROUP
-#define OPTGQA_PF_GROUP 1
-#endif
-constexpr int kPfGroup = OPTGQA_PF_GROUP;                // 32-key tiles per LDS buffer (and per barrier)
 // LDS rows, elements: K rows padded by 8 (16-byte reads of 16 keys then cover all 64 banks), V rows
 // by 16 (so do the rows a transposing load touches) - head_dim 128: 272 / 288 bytes, 64: 144 / 160
 template <int D> struct PfTile {
     static constexpr int kKRow = D + 8, kVRow = D + 16;
-    static constexpr int kLdsBytes = 2 * kPfGroup * kPfKeys * (kKRow + kVRow) * 2;   // two buffers of K and V tiles
+    static constexpr int kLdsBytes = 2 * kPfKeys * (kKRow + kVRow) * 2;   // two buffers of one K and one V tile
 };
 
 template <int DT> __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return narrow2<DT>(lo, hi); }
@@ -140,9 +136,8 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     constexpr int kCPR = D / 8;                         // 16-byte (8-element) column pieces per row
     constexpr int kKPT = 4 * D / 128;                   // consecutive keys a loader thread moves per tile
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
-    // two tile buffers, each K tiles [32][kPfKRow] followed by V tiles [32][kPfVRow]
-    // (kPfGroup tiles of 32 keys each: the waves meet at a barrier once per group)
-    constexpr int kKTile = kPfGroup * kPfKeys * kPfKRow, kBuf = kKTile + kPfGroup * kPfKeys * kPfVRow;
+    // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
+    constexpr int kKTile = kPfKeys * kPfKRow, kBuf = kKTile + kPfKeys * kPfVRow;
     extern __shared__ __attribute__((aligned(16))) uint16_t tile_lds[];          // PfTile<D>::kLdsBytes
 
     // ---- which rows -----------------------------------------------------------------------
@@ -250,17 +245,19 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     // ---- tile staging: threads 0..127 fetch K, 128..255 fetch V; either way a thread moves the
     // same 16-byte column piece of kKPT consecutive keys (kCPR lanes cover one row) ----------------
-    const bool k_loader = tid < 128;
+    const bool k_loader = wave < 2;                              // wave-uniform (waves 0, 1: K; 2, 3: V)
+    const int l_ahead = k_loader ? 1 : 0;                        // K tiles run one tile ahead of V tiles (below)
     const int ld = k_loader ? tid : tid - 128;
     const int l_group = ld / kCPR, l_chunk = ld % kCPR;          // keys kKPT*group .. , dims 8*chunk ..
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
     const int l_dst = kKPT * l_group * l_pitch + 8 * l_chunk;
-    // One register stage: while tile t is computed, tile t + 1 sits in the other LDS buffer and
-    // tile t + 2 is on its way to registers; the block id of the next tile to fetch is read one
-    // fetch earlier, so a fetch never waits for the table.  Fetches past the last tile re-read it (cache hits, never stored):
-    // no branches around loads, which keeps the compiler's load counting exact.
+    // One register stage: while tile t is computed, the loader's next tile sits in the other LDS
+    // buffer and the one after it is on its way to registers; the block id of the next tile to
+    // fetch is read one fetch earlier, so a fetch never waits for the table.  Fetches past the last
+    // tile re-read it (cache hits): no branches around loads, which keeps the compiler's load
+    // counting exact.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: plain loads and stores
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     typedef typename std::conditional<KV8, u32x2, u32x4>::type StageT;   // 8 elements of one key
@@ -290,14 +287,9 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
             stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
         blk_next = load_blk(t + 1);
     };
-    // A tile's place in LDS: tile number j (counted from the first tile read) sits in buffer
-    // (j / kPfGroup) % 2 at position j % kPfGroup.
-    auto tile_base = [&](int j) __attribute__((always_inline)) {
-        return ((j / kPfGroup) & 1) * kBuf + (j % kPfGroup) * kPfKeys * kPfKRow;
-    };
-    auto tile_base_v = [&](int j) __attribute__((always_inline)) {
-        return ((j / kPfGroup) & 1) * kBuf + kKTile + (j % kPfGroup) * kPfKeys * kPfVRow;
-    };
+    // A tile's place in LDS: tile number j (counted from the first tile read) sits in buffer j % 2.
+    auto tile_base = [&](int j) __attribute__((always_inline)) { return (j & 1) * kBuf; };
+    auto tile_base_v = [&](int j) __attribute__((always_inline)) { return (j & 1) * kBuf + kKTile; };
     auto store_tile = [&](const StageT (&stage)[kKPT], int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kKPT; ++j) {
@@ -326,18 +318,20 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #define PF_STAMP(i)
 #define PF_TOUCH(x)
 #endif
-    auto compute_tile = [&](int kt, int buf, auto masked) __attribute__((always_inline)) {
-        constexpr bool MASKED = decltype(masked)::value;
-        // ---- S^T = K Q^T : element 4i + j = score of key 32kt + 8i + 4h2 + j against row n32
-        // (the accumulator starts from the tile-invariant part of the ALiBi term, already divided by the
-        // score scale, so that one FMA per score finishes eq. (3))
+    // ---- S^T = K Q^T : element 4i + j = score of key 32kt + 8i + 4h2 + j against row n32
+    // (the accumulator starts from the tile-invariant part of the ALiBi term, already divided by the
+    // score scale, so that one FMA per score finishes eq. (3))
+    auto scores = [&](int buf) __attribute__((always_inline)) {
         f32x16 st = key_bias;
 #pragma unroll
         for (int m = 0; m < kQ; ++m) {
             const uint4 ka = *reinterpret_cast<const uint4*>(&tile_lds[tile_base(buf) + n32 * kPfKRow + 16 * m + 8 * h2]);
             st = mfma32<DT>(ka, qb[m], st);
         }
-
+        return st;
+    };
+    auto softmax_pv = [&](int kt, int buf, f32x16 st, auto masked) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked)::value;
         PF_TOUCH(st[0]); PF_TOUCH(st[15]);
         PF_STAMP(0);                                             // scores ready
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
@@ -425,33 +419,43 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
 
-    // Prologue: the first kPfGroup tiles go to buffer 0, the one after them is left in flight.
-    const int nt = ntiles - kt0;                                 // tiles this workgroup reads, numbered j = 0 ..
-#pragma unroll
-    for (int j = 0; j < kPfGroup; ++j) {
-        fetch_tile(stage, kt0 + j);
-        store_tile(stage, j);
+    // Software pipeline: the score MFMAs of tile j + 1 are issued before the softmax of tile j, so
+    // that the matrix pipe has work while the vector ALU does the exponentials (measured: 3 % on
+    // the kernel).  For that the K tiles run one tile ahead of the V tiles: at the start of tile j,
+    // K tiles j and j + 1 and V tile j are in LDS, K tile j + 2 and V tile j + 1 are on their way to
+    // registers.  Prologue:
+    fetch_tile(stage, kt0);
+    store_tile(stage, 0);
+    if (k_loader) {                                              // wave-uniform
+        fetch_tile(stage, kt0 + 1);
+        store_tile(stage, 1);
     }
-    fetch_tile(stage, kt0 + kPfGroup);
+    fetch_tile(stage, kt0 + 1 + l_ahead);
     __syncthreads();
+    f32x16 st_next = scores(0);
+    __syncthreads();                                             // buffer 0's K tile is overwritten during tile 0
     // Tiles wholly inside every row's visible range need no mask: those that end at or below the
     // first row's position (causal side) and start at or above the last row's window start.
     const int n_unmasked = min(ntiles, max(0, (pos_min + 1) / kPfKeys));
     const int n_window_cut = W > 0 ? (max(kmax - W, 0) + kPfKeys - 1) / kPfKeys : 0;
-    // (three plain loops rather than one with a branch in it: the compiler schedules the loads of a
-    // loop whose body is one straight line far better)
-    // While tile j is computed, tile j + kPfGroup (fetched one step earlier) is put into the other
-    // buffer and tile j + kPfGroup + 1 is fetched; the waves meet after the last tile of a group.
+    // (three plain loops rather than one with a branch in it, and no branch around the stores: the
+    // compiler schedules a loop whose body is one straight line far better)
+    // While tile j is computed, K tile j + 2 / V tile j + 1 (fetched one step earlier) go into the
+    // buffers that tile j - 1 used and the next ones are fetched; the waves meet after every tile.
+    // The last tile's look-ahead scores read a stale K buffer and are never used; stores past the
+    // last tile put the clamped re-read of it into a buffer nobody reads again.
     auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
         for (int kt = from; kt < to; ++kt) {
             const int j = kt - kt0;
-            compute_tile(kt, j, masked);
+            const f32x16 st = st_next;
+            st_next = scores(j + 1);
+            softmax_pv(kt, j, st, masked);
             PF_STAMP(2);                                         // output MFMAs issued
-            if (j + kPfGroup < nt) store_tile(stage, j + kPfGroup);
+            store_tile(stage, j + 1 + l_ahead);
             PF_STAMP(3);                                         // a later tile stored (waits for its loads)
-            fetch_tile(stage, kt + kPfGroup + 1);
+            fetch_tile(stage, kt + 2 + l_ahead);
             PF_STAMP(4);
-            if (j % kPfGroup == kPfGroup - 1) __syncthreads();
+            __syncthreads();
             PF_STAMP(5);                                         // barrier passed
         }
     };
