@@ -143,9 +143,13 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
     // head) unit are given the same residue so that its K/V stay in one XCD's L2.
+    // Longest first: a later query tile sees more keys, and the hardware hands workgroups to free
+    // slots in id order, so the last query tiles of all units come first and the shortest
+    // workgroups fill the tail of the launch.
     const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
-    const int qt = w % p.q_tiles;
-    const int unit = (w / p.q_tiles) * 8 + xcd;
+    const int units8 = (p.units + 7) >> 3;
+    const int qt = p.q_tiles - 1 - w / units8;
+    const int unit = (w % units8) * 8 + xcd;
     if (unit >= p.units) return;
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
