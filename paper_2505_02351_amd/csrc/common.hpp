@@ -65,6 +65,18 @@ template <> __device__ __forceinline__ uint32_t narrow2<kBF16>(float lo, float h
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// Two fp32 softmax weights as a pair of bf16 heads and a pair of bf16 tails, head + tail = weight to
+// 2^-16 relative: the head is the fp32 value cut to its upper 16 bits (exactly a bf16 number, one
+// byte permute for the pair), the tail the rounded remainder (exact subtraction).  Six vector
+// instructions per pair; rounding the head to nearest instead costs two more and buys nothing, since
+// the tail carries what the head leaves.
+__device__ __forceinline__ void split_bf16(float w0, float w1, uint32_t& head, uint32_t& tail)
+{
+    const uint32_t b0 = __float_as_uint(w0), b1 = __float_as_uint(w1);
+    head = __builtin_amdgcn_perm(b1, b0, 0x07060302u);           // {b0 >> 16, b1 >> 16}
+    tail = narrow2<kBF16>(w0 - __uint_as_float(b0 & 0xffff0000u), w1 - __uint_as_float(b1 & 0xffff0000u));
+}
+
 // Data-parallel-primitive lane exchange inside a row of 16 lanes (full VALU rate, no LDS).
 template <int CTRL> __device__ __forceinline__ float dpp(float x)
 {

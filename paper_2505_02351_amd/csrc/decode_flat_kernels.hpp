@@ -375,20 +375,20 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
         typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
 
         auto weighted_sum = [&](const float (&w_even)[4], const float (&w_odd)[4]) __attribute__((always_inline)) {
-            uint32_t hi[4], lo[4];
-            hi[0] = narrow2<DT>(w_even[0], w_even[1]);
-            hi[1] = narrow2<DT>(w_even[2], w_even[3]);
-            hi[2] = narrow2<DT>(w_odd[0], w_odd[1]);
-            hi[3] = narrow2<DT>(w_odd[2], w_odd[3]);
-            const uint4 ph = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-            uint4 pl = make_uint4(0u, 0u, 0u, 0u);
+            uint32_t hi[4], lo[4] = {0u, 0u, 0u, 0u};
             if (FlatSoftmax<DT>::kSplitWeights) {
-                lo[0] = narrow2<DT>(w_even[0] - widen_lo<DT>(hi[0]), w_even[1] - widen_hi<DT>(hi[0]));
-                lo[1] = narrow2<DT>(w_even[2] - widen_lo<DT>(hi[1]), w_even[3] - widen_hi<DT>(hi[1]));
-                lo[2] = narrow2<DT>(w_odd[0] - widen_lo<DT>(hi[2]), w_odd[1] - widen_hi<DT>(hi[2]));
-                lo[3] = narrow2<DT>(w_odd[2] - widen_lo<DT>(hi[3]), w_odd[3] - widen_hi<DT>(hi[3]));
-                pl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                split_bf16(w_even[0], w_even[1], hi[0], lo[0]);
+                split_bf16(w_even[2], w_even[3], hi[1], lo[1]);
+                split_bf16(w_odd[0], w_odd[1], hi[2], lo[2]);
+                split_bf16(w_odd[2], w_odd[3], hi[3], lo[3]);
+            } else {
+                hi[0] = narrow2<DT>(w_even[0], w_even[1]);
+                hi[1] = narrow2<DT>(w_even[2], w_even[3]);
+                hi[2] = narrow2<DT>(w_odd[0], w_odd[1]);
+                hi[3] = narrow2<DT>(w_odd[2], w_odd[3]);
             }
+            const uint4 ph = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            const uint4 pl = make_uint4(lo[0], lo[1], lo[2], lo[3]);
             // sum of the weights as rounded (the output stays an exact convex combination of V rows)
             const uint32_t one2 = DT == kF16 ? 0x3c003c00u : 0x3f803f80u;
             const uint4 ones = make_uint4(one2, one2, one2, one2);

@@ -384,15 +384,15 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float w0 = fast_exp2(x[2 * e]), w1 = fast_exp2(x[2 * e + 1]);
-            const uint32_t hi = pack2<DT>(w0, w1);
-            pk[e >> 2][e & 3] = hi;
-            pk_lo[e >> 2][e & 3] = 0u;
             if (PfSoftmax<DT>::kSplitWeights) {
-                pk_lo[e >> 2][e & 3] = pack2<DT>(w0 - widen_lo<DT>(hi), w1 - widen_hi<DT>(hi));
+                split_bf16(w0, w1, pk[e >> 2][e & 3], pk_lo[e >> 2][e & 3]);
                 lsum += w0 + w1;
             } else {
                 // single rounding: normalise by the weights as rounded, so that the output stays
                 // an exact convex combination of V rows
+                const uint32_t hi = pack2<DT>(w0, w1);
+                pk[e >> 2][e & 3] = hi;
+                pk_lo[e >> 2][e & 3] = 0u;
                 lsum += widen_lo<DT>(hi) + widen_hi<DT>(hi);
             }
         }
