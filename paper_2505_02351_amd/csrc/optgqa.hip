@@ -315,7 +315,8 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const int gh = heads_per_workgroup(group, 128);
     int shift = 0;
     while ((1 << shift) < gh) ++shift;
-    const int tokens_per_wg = kPfRows >> shift;
+    const bool win = p.window > 0;
+    const int tokens_per_wg = pf_rows(win) >> shift;
     p.num_seqs = num_seqs;
     p.heads_per_wg = gh;
     p.heads_pow2_shift = shift;
@@ -323,7 +324,7 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     p.units = num_seqs * p.num_kv_heads * (group / gh);
     const int64_t blocks = (int64_t)((p.units + 7) / 8) * 8 * p.q_tiles;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(kPfWaves * 64);
+    const dim3 grid((unsigned)blocks), block(pf_waves(win) * 64);
 #ifdef OPTGQA_PF_TIMING
     p.timing = g_pf_timing;
 #endif

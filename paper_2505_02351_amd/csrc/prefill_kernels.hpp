@@ -1,9 +1,9 @@
 // Prefill over the paged cache: several new query tokens per sequence, causal mask + ALiBi
 // (Alg. 1, prompt branch: scores, bias, softmax, weighted sum), as tiled matrix-core contractions.
 //
-// Workgroup (4 waves) = kPfRows (query token, head) rows of one (sequence, KV head [x chunk of the
-// group]) against the whole visible context, in 32-key tiles staged through LDS and shared by the
-// four waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
+// Workgroup (8 waves; 4 with a sliding window) = 32 (query token, head) rows per wave of one
+// (sequence, KV head [x chunk of the group]) against the whole visible context, in 32-key tiles
+// staged through LDS and shared by the waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
 // tile (Section II, "Shared Key-Value").
 //
 // A wave owns 32 rows.  Both contractions are computed transposed, with v_mfma_f32_32x32x16, so that
@@ -72,9 +72,12 @@ struct PrefillParams {
 #endif
 };
 
-constexpr int kPfWaves = 4;
-constexpr int kPfRowBlocks = 2;                          // 16-row blocks per wave
-constexpr int kPfRows = kPfWaves * kPfRowBlocks * 16;    // (token, head) rows per workgroup
+// Waves per workgroup: 8 (256 rows against one K/V tile: half the loader work and LDS stores per
+// row; measured 4 % on the causal kernel) except with a sliding window, where a workgroup's rows
+// should span few keys because every tile that some row's window start or causal end cuts needs
+// the masked path (measured: 8 waves 9 % slower there).
+constexpr int pf_waves(bool win) { return win ? 4 : 8; }
+constexpr int pf_rows(bool win) { return pf_waves(win) * 32; }    // (token, head) rows per workgroup: 32 per wave
 constexpr int kPfKeys = 32;                              // keys per tile
 // LDS rows, elements: K rows padded by 8 (16-byte reads of 16 keys then cover all 64 banks), V rows
 // by 16 (so do the rows a transposing load touches) - head_dim 128: 272 / 288 bytes, 64: 144 / 160
@@ -125,8 +128,9 @@ template <> struct PfSoftmax<kBF16> {
 // head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1 "reshape
 // and store K, V"), so the step needs no separate cache-write launch.
 template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128>
-__global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
+__global__ __launch_bounds__(pf_waves(WIN) * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
+    constexpr int kPfWaves = pf_waves(WIN), kPfRows = pf_rows(WIN);
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
     static_assert(!(KV8 && D != 128), "8-bit caches: head_dim 128");
@@ -134,7 +138,7 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     constexpr int kQ = D / 16;                          // score MFMAs per tile (16 dims each)
     constexpr int kDB = D / 32;                         // 32-dim blocks of the output
     constexpr int kCPR = D / 8;                         // 16-byte (8-element) column pieces per row
-    constexpr int kKPT = 4 * D / 128;                   // consecutive keys a loader thread moves per tile
+    constexpr int kKPT = kPfKeys * (D / 8) / (kPfWaves * 32);   // consecutive keys a loader thread moves per tile (half the threads per tensor)
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
     // two tile buffers, each a K tile [32][kPfKRow] followed by a V tile [32][kPfVRow]
     constexpr int kKTile = kPfKeys * kPfKRow, kBuf = kKTile + kPfKeys * kPfVRow;
@@ -146,10 +150,12 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
     // Longest first: a later query tile sees more keys, and the hardware hands workgroups to free
     // slots in id order, so the last query tiles of all units come first and the shortest
     // workgroups fill the tail of the launch.
+    // (with a window all workgroups are about equally long, and keeping a unit's query tiles together
+    // is worth more: 3 % measured)
     const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
     const int units8 = (p.units + 7) >> 3;
-    const int qt = p.q_tiles - 1 - w / units8;
-    const int unit = (w % units8) * 8 + xcd;
+    const int qt = WIN ? w % p.q_tiles : p.q_tiles - 1 - w / units8;
+    const int unit = (WIN ? w / p.q_tiles : w % units8) * 8 + xcd;
     if (unit >= p.units) return;
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
@@ -249,9 +255,9 @@ __global__ __launch_bounds__(kPfWaves * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged
 
     // ---- tile staging: threads 0..127 fetch K, 128..255 fetch V; either way a thread moves the
     // same 16-byte column piece of kKPT consecutive keys (kCPR lanes cover one row) ----------------
-    const bool k_loader = wave < 2;                              // wave-uniform (waves 0, 1: K; 2, 3: V)
+    const bool k_loader = wave < kPfWaves / 2;                   // wave-uniform (first half of the waves: K; second: V)
     const int l_ahead = k_loader ? 1 : 0;                        // K tiles run one tile ahead of V tiles (below)
-    const int ld = k_loader ? tid : tid - 128;
+    const int ld = k_loader ? tid : tid - kPfWaves * 32;
     const int l_group = ld / kCPR, l_chunk = ld % kCPR;          // keys kKPT*group .. , dims 8*chunk ..
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
