@@ -454,19 +454,30 @@ __global__ __launch_bounds__(pf_waves(WIN) * 64, OPTGQA_PF_WAVES_PER_SIMD) void 
     // buffers that tile j - 1 used and the next ones are fetched; the waves meet after every tile.
     // The last tile's look-ahead scores read a stale K buffer and are never used; stores past the
     // last tile put the clamped re-read of it into a buffer nobody reads again.
+    // (two tiles per trip with the two score registers swapping roles, so that no trip copies the
+    // look-ahead scores into place)
+    f32x16 st_other;
+    auto one_tile = [&](int kt, const f32x16& st_cur, f32x16& st_ahead, auto masked) __attribute__((always_inline)) {
+        const int j = kt - kt0;
+        st_ahead = scores(j + 1);
+        softmax_pv(kt, j, st_cur, masked);
+        PF_STAMP(2);                                             // output MFMAs issued
+        store_tile(stage, j + 1 + l_ahead);
+        PF_STAMP(3);                                             // a later tile stored (waits for its loads)
+        fetch_tile(stage, kt + 2 + l_ahead);
+        PF_STAMP(4);
+        __syncthreads();
+        PF_STAMP(5);                                             // barrier passed
+    };
     auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
-        for (int kt = from; kt < to; ++kt) {
-            const int j = kt - kt0;
-            const f32x16 st = st_next;
-            st_next = scores(j + 1);
-            softmax_pv(kt, j, st, masked);
-            PF_STAMP(2);                                         // output MFMAs issued
-            store_tile(stage, j + 1 + l_ahead);
-            PF_STAMP(3);                                         // a later tile stored (waits for its loads)
-            fetch_tile(stage, kt + 2 + l_ahead);
-            PF_STAMP(4);
-            __syncthreads();
-            PF_STAMP(5);                                         // barrier passed
+        int kt = from;
+        for (; kt + 1 < to; kt += 2) {
+            one_tile(kt, st_next, st_other, masked);
+            one_tile(kt + 1, st_other, st_next, masked);
+        }
+        if (kt < to) {
+            one_tile(kt, st_next, st_other, masked);
+            st_next = st_other;
         }
     };
     const int cut_end = max(kt0, min(n_window_cut, n_unmasked));   // tiles cut by some row's window start
