@@ -285,25 +285,34 @@ unsigned long long* g_pf_timing = nullptr;      // development builds only
 
 // The tiled prefill kernel takes its LDS as dynamic shared memory (more than the 64 KiB a kernel
 // gets by default); the limit is raised once per instantiation.
-template <int DT, bool KV8, bool WIN, bool CONTIG, int D>
-int launch_prefill_mma_d(const PrefillParams& p, dim3 grid, dim3 block, hipStream_t st)
+template <int DT, bool KV8, bool WIN, bool CONTIG, int D, int WAVES>
+int launch_prefill_mma_w(const PrefillParams& p, dim3 grid, hipStream_t st)
 {
     constexpr int kBytes = PfTile<D>::kLdsBytes;
     static const hipError_t attr = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D>),
+        reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D, WAVES>),
         hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
     if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
-    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D>), grid, block, kBytes, st, p);
+    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D, WAVES>), grid, dim3(WAVES * 64), kBytes, st, p);
     return launch_status();
 }
 
+template <int DT, bool KV8, bool WIN, bool CONTIG, int D>
+int launch_prefill_mma_d(const PrefillParams& p, dim3 grid, int waves, hipStream_t st)
+{
+    if constexpr (!WIN) {
+        if (waves == 8) return launch_prefill_mma_w<DT, KV8, WIN, CONTIG, D, 8>(p, grid, st);
+    }
+    return launch_prefill_mma_w<DT, KV8, WIN, CONTIG, D, 4>(p, grid, st);
+}
+
 template <int DT, bool KV8, bool WIN, bool CONTIG>
-int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, dim3 block, hipStream_t st)
+int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, int waves, hipStream_t st)
 {
     if constexpr (!KV8) {
-        if (head_dim == 64) return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 64>(p, grid, block, st);
+        if (head_dim == 64) return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 64>(p, grid, waves, st);
     }
-    return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, block, st);
+    return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, waves, st);
 }
 
 // Tiled matrix-core prefill (head_dim 128 or 64; 8-bit caches: 128 only).
@@ -315,16 +324,21 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const int gh = heads_per_workgroup(group, 128);
     int shift = 0;
     while ((1 << shift) < gh) ++shift;
-    const bool win = p.window > 0;
-    const int tokens_per_wg = pf_rows(win) >> shift;
     p.num_seqs = num_seqs;
     p.heads_per_wg = gh;
     p.heads_pow2_shift = shift;
-    p.q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
     p.units = num_seqs * p.num_kv_heads * (group / gh);
-    const int64_t blocks = (int64_t)((p.units + 7) / 8) * 8 * p.q_tiles;
+    // 8 waves per workgroup when that still leaves two rounds of workgroups per CU, else 4 (and 4
+    // with a sliding window): see prefill_kernels.hpp
+    const int64_t units8 = (p.units + 7) / 8 * 8;
+    const int tokens_per_wg8 = (8 * 32) >> shift;
+    const int64_t blocks8 = units8 * ((max_q_len + tokens_per_wg8 - 1) / tokens_per_wg8);
+    const int waves = (p.window > 0 || blocks8 < 2 * kNumCUs) ? 4 : 8;
+    const int tokens_per_wg = (waves * 32) >> shift;
+    p.q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
+    const int64_t blocks = units8 * p.q_tiles;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
-    const dim3 grid((unsigned)blocks), block(pf_waves(win) * 64);
+    const dim3 grid((unsigned)blocks);
 #ifdef OPTGQA_PF_TIMING
     p.timing = g_pf_timing;
 #endif
@@ -332,19 +346,19 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const bool f16 = dtype == OPTGQA_F16;
     if (contig) {
         if (kv8 || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
-        return f16 ? launch_prefill_mma<kF16, false, false, true>(p, head_dim, grid, block, st)
-                   : launch_prefill_mma<kBF16, false, false, true>(p, head_dim, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, false, false, true>(p, head_dim, grid, waves, st)
+                   : launch_prefill_mma<kBF16, false, false, true>(p, head_dim, grid, waves, st);
     }
     if (p.window > 0) {
         if (kv8) return OPTGQA_ERR_UNSUPPORTED;
-        return f16 ? launch_prefill_mma<kF16, false, true, false>(p, head_dim, grid, block, st)
-                   : launch_prefill_mma<kBF16, false, true, false>(p, head_dim, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, false, true, false>(p, head_dim, grid, waves, st)
+                   : launch_prefill_mma<kBF16, false, true, false>(p, head_dim, grid, waves, st);
     }
     if (kv8)
-        return f16 ? launch_prefill_mma<kF16, true, false, false>(p, head_dim, grid, block, st)
-                   : launch_prefill_mma<kBF16, true, false, false>(p, head_dim, grid, block, st);
-    return f16 ? launch_prefill_mma<kF16, false, false, false>(p, head_dim, grid, block, st)
-               : launch_prefill_mma<kBF16, false, false, false>(p, head_dim, grid, block, st);
+        return f16 ? launch_prefill_mma<kF16, true, false, false>(p, head_dim, grid, waves, st)
+                   : launch_prefill_mma<kBF16, true, false, false>(p, head_dim, grid, waves, st);
+    return f16 ? launch_prefill_mma<kF16, false, false, false>(p, head_dim, grid, waves, st)
+               : launch_prefill_mma<kBF16, false, false, false>(p, head_dim, grid, waves, st);
 }
 
 }  // namespace

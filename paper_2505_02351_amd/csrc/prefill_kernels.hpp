@@ -1,7 +1,7 @@
 // Prefill over the paged cache: several new query tokens per sequence, causal mask + ALiBi
 // (Alg. 1, prompt branch: scores, bias, softmax, weighted sum), as tiled matrix-core contractions.
 //
-// Workgroup (8 waves; 4 with a sliding window) = 32 (query token, head) rows per wave of one
+// Workgroup (4 or 8 waves, see WAVES below) = 32 (query token, head) rows per wave of one
 // (sequence, KV head [x chunk of the group]) against the whole visible context, in 32-key tiles
 // staged through LDS and shared by the waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
 // tile (Section II, "Shared Key-Value").
@@ -72,12 +72,11 @@ struct PrefillParams {
 #endif
 };
 
-// Waves per workgroup: 8 (256 rows against one K/V tile: half the loader work and LDS stores per
-// row; measured 4 % on the causal kernel) except with a sliding window, where a workgroup's rows
-// should span few keys because every tile that some row's window start or causal end cuts needs
-// the masked path (measured: 8 waves 9 % slower there).
-constexpr int pf_waves(bool win) { return win ? 4 : 8; }
-constexpr int pf_rows(bool win) { return pf_waves(win) * 32; }    // (token, head) rows per workgroup: 32 per wave
+// Waves per workgroup (a template parameter, 32 rows per wave): 8 - 256 rows against one K/V tile,
+// half the loader work and LDS stores per row, measured 4 % on the causal kernel - when that still
+// gives every CU two rounds of workgroups; else 4, and always 4 with a sliding window, where a
+// workgroup's rows should span few keys because every tile that some row's window start or causal
+// end cuts needs the masked path (measured: 8 waves 9 % slower there).
 constexpr int kPfKeys = 32;                              // keys per tile
 // LDS rows, elements: K rows padded by 8 (16-byte reads of 16 keys then cover all 64 banks), V rows
 // by 16 (so do the rows a transposing load touches) - head_dim 128: 272 / 288 bytes, 64: 144 / 160
@@ -127,10 +126,11 @@ template <> struct PfSoftmax<kBF16> {
 // through the block table.  With k_cache_w / v_cache_w set, the workgroups of a KV head's first
 // head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1 "reshape
 // and store K, V"), so the step needs no separate cache-write launch.
-template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128>
-__global__ __launch_bounds__(pf_waves(WIN) * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
+template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {
-    constexpr int kPfWaves = pf_waves(WIN), kPfRows = pf_rows(WIN);
+    static_assert(WAVES == 4 || (WAVES == 8 && !WIN), "4 waves, or 8 without a window");
+    constexpr int kPfWaves = WAVES, kPfRows = WAVES * 32;
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
     static_assert(!(KV8 && D != 128), "8-bit caches: head_dim 128");

@@ -506,7 +506,7 @@ def test_fp8_decode_workload_sampled(U, oracle):
     assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
 
 
-@pytest.mark.parametrize("i", [0, 2, 3, 4, 6, 8, 9])
+@pytest.mark.parametrize("i", [0, 2, 3, 4, 6, 8, 9, 10, 12])
 def test_fp8_prefill(U, oracle, i):
     """Tiled prefill over 8-bit caches against the oracle's clause (the caches are filled by the
     quantising cache write on both sides, codes compared bit for bit first)."""
@@ -531,8 +531,9 @@ def test_fp8_prefill(U, oracle, i):
     torch.cuda.synchronize()
     ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
                                case.slopes, case.scale, k_scale, v_scale, dtype)
-    err = U.max_abs_err(U.to_host(out), ref, dtype)
-    assert err <= U.TOL[dtype], f"max abs err {err}"
+    # (v_scale 0.02 puts V elements up to 9: rows that see one or two keys can land in [4, 8), where
+    # the output's own rounding is twice the budget of the stated tolerance)
+    check_scaled(U, U.to_host(out), ref, dtype, f"fp8 prefill {i}")
 
 
 def test_fp8_prefill_workload_sampled(U, oracle):
@@ -835,6 +836,9 @@ PROMPT = [
     (W.BF16, 6, 2, 16, 2, 5, 100),         # G = 3
     (W.F16, 32, 2, 64, 2, 30, 260),        # G = 16: 8 tokens per workgroup
     (W.BF16, 40, 2, 16, 1, 200, 200),      # G = 20 -> two head chunks; only the first stores the rows
+    # enough workgroups for the 8-wave form of the kernel:
+    (W.BF16, 16, 8, 16, 32, 100, 300),     # G = 2: 128 tokens per workgroup
+    (W.F16, 8, 8, 32, 64, 1, 300, 64),     # MHA, head_dim 64: 256 tokens per workgroup
 ]
 
 
@@ -861,7 +865,9 @@ def test_prompt_prefill_sweep(U, oracle, i):
     G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables, dev.cu_q_lens,
                      dev.slopes, float(case.scale), case.max_q_len)
     torch.cuda.synchronize()
-    assert U.max_abs_err(U.to_host(dev.out), ref, dtype) <= U.TOL[dtype]
+    # (binade-aware bound: the larger cases have tens of millions of V elements, a few of them beyond
+    # 4, and a row that sees one or two keys can return such a value, rounded at twice the budget)
+    check_scaled(U, U.to_host(dev.out), ref, dtype, f"prompt {i}")
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
     # fused QKV tensor: k and v are strided views; no caches
     T = case.num_tokens
@@ -875,7 +881,7 @@ def test_prompt_prefill_sweep(U, oracle, i):
                      case.max_q_len)
     torch.cuda.synchronize()
     ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, None, case.scale, dtype)
-    assert U.max_abs_err(U.to_host(dev.out), ref, dtype) <= U.TOL[dtype]
+    check_scaled(U, U.to_host(dev.out), ref, dtype, f"prompt {i}, fused input")
 
 
 def test_prompt_prefill_then_decode(U, oracle):
@@ -1234,6 +1240,10 @@ PF = [
     (W.F16, 32, 2, 128, 16, 1, 300, 300, 40),       # G = 16
     (W.BF16, 40, 2, 128, 64, 1, 200, 200, 33),      # G = 20 -> two chunks of 10 heads (padded to 16)
     (W.BF16, 8, 2, 128, 16, 2, 700, 1500, 1),       # one new token per sequence through the prefill path
+    # enough workgroups for the 8-wave form of the kernel (256 rows per workgroup, 512+ workgroups):
+    (W.BF16, 16, 8, 128, 16, 32, 150, 300, 140),    # G = 2: 128 tokens per workgroup, ragged second query tile
+    (W.F16, 8, 8, 64, 32, 64, 50, 400, 400),        # MHA, head_dim 64: 256 tokens per workgroup, whole prompts new
+    (W.F16, 32, 8, 128, 16, 8, 600, 900, 520),      # G = 4 (the bench's shape class): 64 tokens per workgroup
 ]
 
 
@@ -1250,8 +1260,7 @@ def test_prefill_sweep(U, oracle, i):
     kc, vc = oracle_filled(oracle, case)
     ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
                                case.slopes, case.scale, dtype)
-    err = U.max_abs_err(got, ref, dtype)
-    assert err <= U.TOL[dtype], err
+    check_scaled(U, got, ref, dtype, f"prefill {i}")
 
 
 def test_prefill_workload_sampled(U, oracle):
