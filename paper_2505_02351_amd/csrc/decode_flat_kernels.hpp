@@ -438,22 +438,18 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_
                 x[v] = visible ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;   // eq. (3), base 2
                 need |= x[v] > m_ref + FlatSoftmax<DT>::kThreshold;
             }
-            if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(need) != 0, 0)) {   // rare: the reference moves lazily
                 float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
                 mx = fmaxf(mx, __shfl_xor(mx, 16));              // a head's tokens live in 4 lanes (hg)
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float m_new = fmaxf(m_ref, mx + FlatSoftmax<DT>::kHeadroom);
                 const float alpha = fast_exp2(m_ref - m_new);    // 1 when unchanged, 0 on first use
                 m_ref = m_new;
+                lsum *= alpha;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    lsum[v] *= alpha;
-                    pend[v] *= alpha;
-                }
+                for (int v = 0; v < 4; ++v) pend[v] *= alpha;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[e][v] *= alpha;
+                for (int e = 0; e < 8; ++e) acc[e] *= alpha;
             }
             float w[4];
 #pragma unroll
