@@ -585,8 +585,10 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int u0 = min(max(F0 / c, 0), p.num_units - 1);
     const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
     const int64_t base = ((int64_t)u0 + (int64_t)b * Y + y) * GH + hh;       // slot stride between units: GH
+    // One pass in batches of 8 partial results with a running reference (a segment rarely has more
+    // than 8 pieces, so this is one memory round trip; a separate pass for the maximum would be
+    // a second chain of them).
     float M = -INFINITY;
-    for (int i = 0; i < np; ++i) M = fmaxf(M, p.ws_m[base + (int64_t)i * GH]);
     float den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i0 = 0; i0 < np; i0 += 8) {
@@ -599,6 +601,16 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
             ll[k] = p.ws_l[e];
             x[k] = *reinterpret_cast<const float4*>(p.ws_o + e * D + od);
         }
+        float Mn = M;                                            // clamped repeats of the last piece do not change it
+#pragma unroll
+        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
+        const float keep = i0 == 0 ? 0.f : fast_exp2(M - Mn);    // nothing accumulated before the first batch
+        M = Mn;
+        den *= keep;
+        num.x *= keep;
+        num.y *= keep;
+        num.z *= keep;
+        num.w *= keep;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float fct = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
