@@ -254,8 +254,9 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_reduce_kernel(con
     }
     const int np = (L + p.partition_size - 1) / p.partition_size;
     const int64_t base = ((int64_t)row * p.num_heads + h) * p.num_partitions;
+    // One pass in batches of 8 partitions with a running reference (a separate pass for the maximum
+    // would be a second chain of memory round trips).
     float M = -INFINITY;
-    for (int i = 0; i < np; ++i) M = fmaxf(M, p.ws_m[base + i]);
     float den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int i0 = 0; i0 < np; i0 += 8) {
@@ -268,6 +269,16 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_reduce_kernel(con
             ll[k] = p.ws_l[base + i];
             x[k] = *reinterpret_cast<const float4*>(p.ws_o + (base + i) * D + od);
         }
+        float Mn = M;                                            // clamped repeats of the last partition do not change it
+#pragma unroll
+        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
+        const float keep = i0 == 0 ? 0.f : fast_exp2(M - Mn);    // nothing accumulated before the first batch
+        M = Mn;
+        den *= keep;
+        num.x *= keep;
+        num.y *= keep;
+        num.z *= keep;
+        num.w *= keep;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const float f = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
