@@ -460,6 +460,56 @@ def test_fp8_decode_sweep(U, oracle, i):
 
 
 @pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_fp8_every_code_through_decode_and_prefill(U, oracle, dtype):
+    """Caches of uniformly random bytes (every finite E4M3 code, subnormals and +-448 included, many
+    times in K and in V; the two NaN codes replaced) read by the decode and the prefill kernels: the
+    widening of codes on the device must agree with the oracle's decoder for all of them."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="fp8_codes", kind="prefill", dtype=dtype, batch=3, num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=60, ctx_lo=40, ctx_hi=300, q_len=37, seed=431)
+    case = W.make_case(cfg)
+    rng = np.random.default_rng(432)
+    shape = (cfg.num_blocks, cfg.num_kv_heads, cfg.block_size, cfg.head_dim)
+    kc8 = rng.integers(0, 256, size=shape, dtype=np.uint8)
+    vc8 = rng.integers(0, 256, size=shape, dtype=np.uint8)
+    kc8[(kc8 & 0x7F) == 0x7F] = 0x7E
+    vc8[(vc8 & 0x7F) == 0x7F] = 0x7E
+    for c in (kc8, vc8):
+        assert len(np.unique(c)) == 254
+    k_scale, v_scale = 0.002, 0.004                      # scores of a few units, outputs below 2
+    dk, dv = torch.from_numpy(kc8).cuda(), torch.from_numpy(vc8).cuda()
+    tables, lens = torch.from_numpy(case.block_tables).cuda(), torch.from_numpy(case.context_lens).cuda()
+    slopes = torch.from_numpy(case.slopes).cuda()
+    # prefill: every new token against its causal context
+    qd = U.to_dev(case.q, dtype)
+    out = torch.full_like(qd, float("nan"))
+    G.paged_prefill_fp8(out, qd, dk, dv, tables, lens, torch.from_numpy(case.cu_q_lens).cuda(), slopes,
+                        float(case.scale), k_scale, v_scale, case.max_q_len)
+    torch.cuda.synchronize()
+    ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, k_scale, v_scale, dtype)
+    check_scaled(U, U.to_host(out), ref, dtype, "prefill over random codes")
+    # decode: the last new token of every sequence as the query of a decode call
+    last = case.cu_q_lens[1:] - 1
+    q_dec = case.q[last]
+    qd = U.to_dev(q_dec, dtype)
+    out = torch.full_like(qd, float("nan"))
+    n, _ = G.paged_attention_workspace_bytes(cfg.batch, cfg.num_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_size,
+                                             case.max_context_len, G.SPLIT_BALANCED)
+    ws = torch.empty(n // 4, dtype=torch.float32, device="cuda")
+    G.paged_attention_fp8(out, qd, dk, dv, tables, lens, slopes, float(case.scale), k_scale, v_scale,
+                          case.max_context_len, ws)
+    torch.cuda.synchronize()
+    ref_dec = O.paged_attention_e4m3(q_dec, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                     k_scale, v_scale, dtype)
+    check_scaled(U, U.to_host(out), ref_dec, dtype, "decode over random codes")
+    # the two clauses agree on those rows (same keys, same position)
+    np.testing.assert_allclose(ref_dec, ref[last], rtol=1e-9, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
 def test_fp8_decode_edge_lengths(U, oracle, dtype):
     import oracle as O
     lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1, 0], np.int32)
