@@ -317,6 +317,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     const float scale2 = p.scale2;
 #ifdef OPTGQA_PF_TIMING
     unsigned long long tm_sum[6] = {0, 0, 0, 0, 0, 0}, tm_last = clock64();
+    const unsigned long long tm_clk0 = tm_last, tm_wall0 = wall_clock64();
     auto stamp = [&](int i) __attribute__((always_inline)) {
         const unsigned long long t = clock64();
         tm_sum[i] += t - tm_last;
@@ -491,7 +492,8 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         unsigned long long* t = p.timing + 8 * ((size_t)blockIdx.x * kPfWaves + wave);
         for (int i = 0; i < 6; ++i) t[i] = tm_sum[i];
         t[6] = (unsigned long long)(ntiles - kt0);
-        t[7] = clock64();
+        // core clock cycles per 1000 ticks of the 100 MHz wall clock over the loop: the clock the kernel ran at
+        t[7] = (clock64() - tm_clk0) * 1000ull / max(wall_clock64() - tm_wall0, 1ull);
     }
 #endif
     // ---- normalise and write: this lane holds dims 32db + 8i + 4h2 + (0..3) of its row -----------
