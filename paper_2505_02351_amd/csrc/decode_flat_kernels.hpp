@@ -46,6 +46,9 @@ namespace optgqa {
 #ifndef OPTGQA_FLAT_WGS_PER_CU
 #define OPTGQA_FLAT_WGS_PER_CU 1
 #endif
+#ifndef OPTGQA_FLAT_WGS_PER_CU_KV8
+#define OPTGQA_FLAT_WGS_PER_CU_KV8 2      // workgroups per CU (= waves per SIMD) for 8-bit caches
+#endif
 #ifndef OPTGQA_FLAT_WAVES_PER_SIMD
 #define OPTGQA_FLAT_WAVES_PER_SIMD 2
 #endif
@@ -113,7 +116,7 @@ struct MmaTile8 {
 };
 
 template <int DT, bool FUSED, bool KV8 = false>
-__global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? 2 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
+__global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
     constexpr bool NEW_TILE = FUSED && !KV8;            // the new token is a tile of its own, read from k_new / v_new
     typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;

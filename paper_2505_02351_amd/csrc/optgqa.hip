@@ -102,9 +102,6 @@ struct SplitPlan {
 // OPTGQA_FLAT_WGS_PER_CU_KV8 per CU for 8-bit caches (half the bytes per tile: the second wave
 // per SIMD hides the arithmetic); no wave with less than kFlatMinTiles tiles of 16 tokens when
 // the lengths are at their bound.  The workspace is sized for the larger of the two.
-#ifndef OPTGQA_FLAT_WGS_PER_CU_KV8
-#define OPTGQA_FLAT_WGS_PER_CU_KV8 2
-#endif
 constexpr int kFlatWorkgroups = kNumCUs * OPTGQA_FLAT_WGS_PER_CU;
 constexpr int kFlatWorkgroupsKv8 = kNumCUs * OPTGQA_FLAT_WGS_PER_CU_KV8;
 constexpr int kFlatMaxWorkgroups = kFlatWorkgroups > kFlatWorkgroupsKv8 ? kFlatWorkgroups : kFlatWorkgroupsKv8;
