@@ -119,6 +119,31 @@ int optgqa_paged_attention(void *out, const void *q, const void *k_cache, const 
                            void *stream);
 
 /*
+ * optgqa_paged_attention for callers that cannot allocate and cannot bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result
+ * as optgqa_paged_attention with partition_size 0 and a workspace of the size it asks for; the
+ * split-context scratch is a static array of OPTGQA_STATIC_SCRATCH_BYTES bytes in device memory
+ * that belongs to the library (one per GPU the library runs on, held until the process ends).
+ * The call allocates and frees nothing.
+ *
+ *   - Shapes whose split would need more than OPTGQA_STATIC_SCRATCH_BYTES return
+ *     OPTGQA_ERR_WORKSPACE and launch nothing (the five measured configurations need at most
+ *     9.5 MB; optgqa_paged_attention_workspace_bytes(..., 0, NULL) tells for any shape).
+ *   - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race.  Nothing needs clearing between calls.
+ *   - The array's address is looked up on the calling thread's current device at the first
+ *     call on that device (no allocation, but make that first call outside a graph capture).
+ * Other arguments, layouts and errors as optgqa_paged_attention.
+ */
+#define OPTGQA_STATIC_SCRATCH_BYTES (16u << 20)
+int optgqa_paged_attention_static(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                  const int32_t *block_tables, const int32_t *context_lens,
+                                  const float *alibi_slopes, float scale, int num_seqs, int num_heads,
+                                  int num_kv_heads, int head_dim, int block_size,
+                                  int max_blocks_per_seq, int max_context_len, optgqa_dtype dtype,
+                                  void *stream);
+
+/*
  * Measurement aid, not part of the method: with two hipEvent_t handles set, every later
  * optgqa_paged_attention / optgqa_decode_step / optgqa_paged_prefill call made by the SAME
  * host thread records `start_event` just before and `stop_event` just after it launches the

@@ -54,6 +54,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_attention.restype = i32
     lib.optgqa_paged_attention.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                            i32, vp, sz, i32, vp]
+    lib.optgqa_paged_attention_static.restype = i32
+    lib.optgqa_paged_attention_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                                  i32, vp]
     lib.optgqa_set_kernel_events.restype = i32
     lib.optgqa_set_kernel_events.argtypes = [vp, vp]
     lib.optgqa_decode_step.restype = i32
@@ -181,6 +184,30 @@ def paged_attention(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v
                                     int(block_tables.shape[1]), int(max_context_len), int(partition_size),
                                     _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_paged_attention")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20    # OPTGQA_STATIC_SCRATCH_BYTES
+
+
+def paged_attention_static(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                           block_tables: torch.Tensor, context_lens: torch.Tensor,
+                           alibi_slopes: Optional[torch.Tensor], scale: float, max_context_len: int,
+                           stream=None) -> None:
+    """optgqa_paged_attention_static: decode attention whose split-context scratch is the library's
+    own static device array (no workspace argument, nothing allocated)."""
+    lib = load_library()
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    rc = lib.optgqa_paged_attention_static(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                           _ptr(context_lens), _ptr(alibi_slopes), float(scale), B, Hq, Hkv, D, bs,
+                                           int(block_tables.shape[1]), int(max_context_len), _dtype_code(q),
+                                           _stream(stream))
+    _check(rc, "optgqa_paged_attention_static")
 
 
 def set_kernel_events(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:

@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "cache_kernels.hpp"
 #include "decode_kernels.hpp"
 #include "decode_mc_kernels.hpp"
@@ -13,6 +15,12 @@
 #include "probe_kernels.hpp"
 
 using namespace optgqa;
+
+// Split-context scratch for optgqa_paged_attention_static, whose callers cannot allocate or
+// bring a workspace.  One copy per GPU the library runs on, held until the process ends.  In
+// host code this name is only a stand-in for the symbol: its device address comes from
+// hipGetSymbolAddress (static_scratch() below) and is what kernels and size checks use.
+static __device__ __align__(256) unsigned char g_static_scratch[OPTGQA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -46,6 +54,24 @@ struct KernelEvents {
         if (g_event_stop) (void)hipEventRecord(g_event_stop, st);
     }
 };
+
+// Device address of g_static_scratch on the current device, looked up once per device (each GPU
+// holds its own copy at its own address).  nullptr if the runtime refuses.
+constexpr int kMaxDevices = 64;
+void* static_scratch()
+{
+    static std::mutex mu;
+    static void* ptr[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess) return nullptr;
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
 
 // Number of query heads one workgroup serves from a single pass over its K/V tiles; always a
 // divisor of the group size.  head_dim 128 uses the matrix-core kernel, whose score tile has
@@ -625,6 +651,29 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           partition_size, workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream),
                           nullptr);
+}
+
+int optgqa_paged_attention_static(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                  const int32_t* block_tables, const int32_t* context_lens,
+                                  const float* alibi_slopes, float scale, int num_seqs, int num_heads,
+                                  int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                                  int max_context_len, optgqa_dtype dtype, void* stream)
+{
+    // the split the library would choose for these sizes must fit the static scratch: no silent
+    // fall-back to the unsplit kernel here
+    if (num_seqs > 0 && num_heads > 0 && num_kv_heads > 0 && head_dim > 0 && block_size > 0 &&
+        max_context_len > 0 && num_heads % num_kv_heads == 0 && head_dim_ok(head_dim)) {
+        const SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len, 0);
+        if (s.bytes > (size_t)OPTGQA_STATIC_SCRATCH_BYTES) return OPTGQA_ERR_WORKSPACE;
+    }
+    void* scratch = static_scratch();
+    if (!scratch) return OPTGQA_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: every slot and plan entry the combine kernel
+    // reads for a non-empty sequence is written by the streaming kernel of the same call.
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len, 0,
+                          scratch, (size_t)OPTGQA_STATIC_SCRATCH_BYTES, (int)dtype,
+                          static_cast<hipStream_t>(stream), nullptr);
 }
 
 int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, void* v_cache,

@@ -194,3 +194,18 @@ def test_missing_library_fails_loudly():
             "sys.exit(0)\n" % root)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert r.returncode == 7 and "is missing" in r.stdout, (r.returncode, r.stdout, r.stderr[-300:])
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit(G):
+    """optgqa_paged_attention_static: a shape whose split needs more than the static array is
+    refused on the host (no GPU call is made before that decision)."""
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)
+    n, chosen = G.paged_attention_workspace_bytes(500, 32, 2, 128, 16, 4096, 0)
+    assert chosen != 0 and n > G.STATIC_SCRATCH_BYTES
+    rc = lib.optgqa_paged_attention_static(one, one, one, one, one, one, None, 0.1, 500, 32, 2, 128, 16, 256, 4096,
+                                           1, None)
+    assert rc == -4
+    header = open(HEADER).read()
+    m = re.search(r"#define OPTGQA_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == G.STATIC_SCRATCH_BYTES
