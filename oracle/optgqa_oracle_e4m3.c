@@ -41,7 +41,7 @@ enum { E4M3_F16 = 0, E4M3_BF16 = 1 };
 
 /* exact widening of the 2-byte query / new-token elements (written again here on purpose:
  * this file stands alone) */
-static double two_byte_value(uint16_t h, int dtype)
+static double two_byte_value_formula(uint16_t h, int dtype)
 {
     int sign = (h >> 15) & 1;
     double v;
@@ -59,7 +59,7 @@ static double two_byte_value(uint16_t h, int dtype)
     return sign ? -v : v;
 }
 
-static double e4m3_value(uint8_t c)
+static double e4m3_value_formula(uint8_t c)
 {
     int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
     double v;
@@ -68,6 +68,26 @@ static double e4m3_value(uint8_t c)
     else v = ldexp(1.0 + (double)m / 8.0, e - 7);
     return sign ? -v : v;
 }
+
+/* The two decoders above, tabulated once per process for all 65 536 two-byte patterns of both
+ * types and all 256 codes (the attention loops decode every cache element once per query row;
+ * nothing is computed differently, each entry is the formula's own result). */
+static double *g_two_byte_value_table[2];
+static double g_e4m3_value_table[256];
+
+static void two_byte_value_tabulate(void)
+{
+    for (int c = 0; c < 256; ++c) g_e4m3_value_table[c] = e4m3_value_formula((uint8_t)c);
+    for (int dt = 0; dt < 2; ++dt) {
+        if (g_two_byte_value_table[dt]) continue;
+        double *t = (double *)malloc(sizeof(double) * 65536);
+        for (int h = 0; h < 65536; ++h) t[h] = two_byte_value_formula((uint16_t)h, dt);
+        g_two_byte_value_table[dt] = t;
+    }
+}
+
+static double two_byte_value(uint16_t h, int dtype) { return g_two_byte_value_table[dtype][h]; }
+static double e4m3_value(uint8_t c) { return g_e4m3_value_table[c]; }
 
 /* nearest code, ties to even, saturating; nearbyint() rounds to nearest-even in the default
  * rounding mode, and every scaling below is by a power of two, hence exact */
@@ -92,6 +112,7 @@ static uint8_t e4m3_nearest(float x)
 
 void oracle_e4m3_values(double *out256)
 {
+    two_byte_value_tabulate();
     for (int c = 0; c < 256; ++c) out256[c] = e4m3_value((uint8_t)c);
 }
 
@@ -107,6 +128,7 @@ void oracle_reshape_and_cache_e4m3(const uint16_t *k, const uint16_t *v,
                                    int64_t k_token_stride, int64_t v_token_stride,
                                    float k_scale, float v_scale, int dtype)
 {
+    two_byte_value_tabulate();
     const float k_inv = 1.0f / k_scale, v_inv = 1.0f / v_scale;
     for (int t = 0; t < num_tokens; ++t) {
         int64_t slot = slot_mapping[t];
@@ -171,6 +193,7 @@ void oracle_paged_attention_e4m3(double *out, const int32_t *row_seq, const int3
                                  int num_heads, int num_kv_heads, int head_dim, int block_size,
                                  int max_blocks_per_seq, int dtype)
 {
+    two_byte_value_tabulate();
     int group = num_heads / num_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < n_rows; ++r) {
@@ -198,6 +221,7 @@ void oracle_paged_prefill_e4m3(double *out, const int32_t *row_token, const int3
                                int num_heads, int num_kv_heads, int head_dim, int block_size,
                                int max_blocks_per_seq, int dtype)
 {
+    two_byte_value_tabulate();
     int group = num_heads / num_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < n_rows; ++r) {

@@ -28,7 +28,7 @@
 
 enum { PROMPT_F16 = 0, PROMPT_BF16 = 1 };
 
-static double prompt_elem(uint16_t h, int dtype)
+static double prompt_elem_formula(uint16_t h, int dtype)
 {
     int sign = (h >> 15) & 1;
     double v;
@@ -46,6 +46,23 @@ static double prompt_elem(uint16_t h, int dtype)
     return sign ? -v : v;
 }
 
+/* The decoder above, tabulated once per process for all 65 536 patterns of both types (the
+ * attention loops decode every cache element once per query row; nothing is computed differently,
+ * each entry is prompt_elem_formula's own result). */
+static double *g_prompt_elem_table[2];
+
+static void prompt_elem_tabulate(void)
+{
+    for (int dt = 0; dt < 2; ++dt) {
+        if (g_prompt_elem_table[dt]) continue;
+        double *t = (double *)malloc(sizeof(double) * 65536);
+        for (int h = 0; h < 65536; ++h) t[h] = prompt_elem_formula((uint16_t)h, dt);
+        g_prompt_elem_table[dt] = t;
+    }
+}
+
+static double prompt_elem(uint16_t h, int dtype) { return g_prompt_elem_table[dtype][h]; }
+
 /* q: [T][num_heads][D]; k, v: [T][num_kv_heads][D], all dense.  For a list of (token, head) pairs
  * (row_token == NULL: all pairs in order, n_rows = T * num_heads); out is [n_rows, D] fp64. */
 void oracle_prompt_attention(double *out, const int32_t *row_token, const int32_t *row_head,
@@ -53,6 +70,7 @@ void oracle_prompt_attention(double *out, const int32_t *row_token, const int32_
                              const int32_t *cu_seq_lens, const float *alibi_slopes, float scale,
                              int num_seqs, int num_heads, int num_kv_heads, int head_dim, int dtype)
 {
+    prompt_elem_tabulate();
     int group = num_heads / num_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < n_rows; ++r) {

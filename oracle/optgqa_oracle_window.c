@@ -37,7 +37,7 @@
 
 enum { WIN_F16 = 0, WIN_BF16 = 1 };
 
-static double elem_value(uint16_t h, int dtype)
+static double elem_value_formula(uint16_t h, int dtype)
 {
     int sign = (h >> 15) & 1;
     double v;
@@ -54,6 +54,23 @@ static double elem_value(uint16_t h, int dtype)
     }
     return sign ? -v : v;
 }
+
+/* The decoder above, tabulated once per process for all 65 536 patterns of both types (the
+ * attention loops decode every cache element once per query row; nothing is computed differently,
+ * each entry is elem_value_formula's own result). */
+static double *g_elem_value_table[2];
+
+static void elem_value_tabulate(void)
+{
+    for (int dt = 0; dt < 2; ++dt) {
+        if (g_elem_value_table[dt]) continue;
+        double *t = (double *)malloc(sizeof(double) * 65536);
+        for (int h = 0; h < 65536; ++h) t[h] = elem_value_formula((uint16_t)h, dt);
+        g_elem_value_table[dt] = t;
+    }
+}
+
+static double elem_value(uint16_t h, int dtype) { return g_elem_value_table[dtype][h]; }
 
 /* One query row at position pos of a sequence whose cache holds n_ctx tokens (n_ctx > pos). */
 static void attend_row_window(double *out_row, const uint16_t *q_row,
@@ -103,6 +120,7 @@ void oracle_paged_attention_window(double *out, const int32_t *row_seq, const in
                                    int num_heads, int num_kv_heads, int head_dim, int block_size,
                                    int max_blocks_per_seq, int dtype)
 {
+    elem_value_tabulate();
     int group = num_heads / num_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < n_rows; ++r) {
@@ -129,6 +147,7 @@ void oracle_paged_prefill_window(double *out, const int32_t *row_token, const in
                                  int window, int num_seqs, int num_heads, int num_kv_heads,
                                  int head_dim, int block_size, int max_blocks_per_seq, int dtype)
 {
+    elem_value_tabulate();
     int group = num_heads / num_kv_heads;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < n_rows; ++r) {

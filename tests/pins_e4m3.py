@@ -214,6 +214,63 @@ def check_prefill_reduces_to_two_byte_oracle_and_to_decodes(lib=None):
     np.testing.assert_allclose(sub, np.stack([got[t, h] for t, h in rows]), rtol=0, atol=0)
 
 
+def check_two_byte_decoder_on_every_pattern(lib=None):
+    """The 2-byte decoder of this file (queries and new-token rows) on all 65 536 fp16 and bf16
+    patterns.  Two routes, both compared with numpy's own decoding of the pattern:
+
+    * as a query: one sequence per pattern, head_dim 1, two cached tokens with codes K = (0, 1),
+      V = (0, 1), no slopes, unit cache scales: the output is the weight of the second key,
+      1 / (1 + exp(-scale * q)) - a logistic function, which resolves the last mantissa bit of q
+      wherever |scale * k_scale * q| is of order 1.  scale * k_scale runs over the powers of two that bring
+      every finite magnitude there once.  Infinite and NaN queries give NaN (inf * 0 in the first
+      key's product), which a decoder that turned them into large finite numbers would not.
+    * as a new-token row of the quantising cache write at scale 1: every finite pattern of
+      magnitude <= 448 must land on the code the library cast gives its numpy-decoded value; larger
+      ones (infinities included) saturate, NaN patterns give 0x7f."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    one = 0x38                                           # code of 1.0
+    for dtype, e_lo, e_hi in ((W.F16, -24, 16), (W.BF16, -133, 128)):
+        x = W.from_bits(bits, dtype)
+        B = 65536
+        q = bits.reshape(B, 1, 1).copy()
+        kc8 = np.zeros((B, 1, 2, 1), np.uint8)
+        kc8[:, 0, 1, 0] = one
+        vc8 = kc8.copy()
+        tables = np.arange(B, dtype=np.int32).reshape(B, 1)
+        lens = np.full(B, 2, np.int32)
+        seen = np.zeros(B, bool)
+        fin = np.isfinite(x)
+        with np.errstate(over="ignore", invalid="ignore"):
+            for e in range(e_lo, e_hi + 1):
+                a = int(np.clip(-e, -100, 100))              # 2^-e split over the score scale and k_scale
+                scale, k_scale = np.float32(2.0 ** a), np.float32(2.0 ** (-e - a))
+                sens = fin & (np.abs(x) >= 2.0 ** (e - 2)) & (np.abs(x) < 2.0 ** (e + 1))
+                if not sens.any():
+                    continue
+                out = O.paged_attention_e4m3(q, kc8, vc8, tables, lens, None, scale, k_scale, 1.0, dtype, lib=lib)[:, 0, 0]
+                want = 1.0 / (1.0 + np.exp(-(2.0 ** -e * x[sens])))
+                np.testing.assert_allclose(out[sens], want, rtol=1e-13, atol=0, err_msg=f"{dtype} scale 2^{-e}")
+                seen |= sens
+                if e == 0:
+                    assert np.all(np.isnan(out[~fin])) and np.count_nonzero(~fin) > 2
+                    assert np.all(out[fin & (x == 0)] == 0.5)
+        assert np.all(seen[fin & (x != 0)]), f"{dtype}: a finite pattern was never in the sensitive range"
+        # the cache-write route
+        rows = bits.reshape(4096, 1, 16)
+        slots = np.arange(4096, dtype=np.int64)
+        kc = np.full((256, 1, 16, 16), 0x7F, np.uint8)
+        vc = np.full((256, 1, 16, 16), 0x7F, np.uint8)
+        O.reshape_and_cache_e4m3(rows, rows, kc, vc, slots, 1.0, 1.0, dtype, lib)
+        got = kc.reshape(-1)
+        assert np.array_equal(got, vc.reshape(-1))
+        inr = fin & (np.abs(x) <= 448)
+        lib_codes = torch.from_numpy(x[inr].astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(got[inr], lib_codes), f"{dtype}: cache write of in-range patterns"
+        assert np.all(got[np.isnan(x)] == 0x7F)
+        big = ~np.isnan(x) & (np.abs(x) > 448)
+        assert np.array_equal(got[big], np.where(x[big] > 0, 0x7E, 0xFE).astype(np.uint8))
+
+
 ALL_CHECKS = [
     check_prefill_reduces_to_two_byte_oracle_and_to_decodes,
     check_values_match_library_type,
@@ -223,4 +280,5 @@ ALL_CHECKS = [
     check_cache_write_against_library_cast,
     check_attention_reduces_to_two_byte_oracle,
     check_scales_enter_where_the_definition_says,
+    check_two_byte_decoder_on_every_pattern,
 ]

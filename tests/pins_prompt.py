@@ -65,6 +65,24 @@ def check_first_token_returns_its_own_value_row(lib=None):
             assert np.array_equal(got[t, h], V[t, h // 4])
 
 
+def check_decoder_on_every_two_byte_pattern(lib=None):
+    """All 65 536 fp16 and bf16 patterns (subnormals, infinities, NaNs) as the V row of a one-token
+    prompt: token 0 attends to itself with weight exactly 1, so the output is the decoder's value
+    of each pattern, compared with numpy's own decoding."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    for dtype in (W.F16, W.BF16):
+        want = W.from_bits(bits, dtype)
+        D = 65536
+        zeros = np.zeros((1, 1, D), np.uint16)
+        out = O.prompt_attention(zeros, zeros, bits.reshape(1, 1, D).copy(), np.array([0, 1], np.int32),
+                                 np.ones(1, np.float32), 1.0, dtype, lib=lib)[0, 0]
+        fin = np.isfinite(want)
+        assert np.array_equal(out[fin], want[fin]), f"{dtype} decoding"
+        inf = np.isinf(want)
+        assert np.array_equal(out[inf], want[inf]), f"{dtype} infinities"
+        assert np.all(np.isnan(out[np.isnan(want)])), f"{dtype} NaN patterns"
+
+
 def check_sequences_do_not_see_each_other(lib=None):
     """Each sequence alone gives the rows it gives inside the batch; row lists pick the same rows."""
     case = _case(W.BF16, 25)
@@ -86,5 +104,6 @@ ALL_CHECKS = [
     check_equals_paged_prefill_after_the_cache_write,
     check_against_dense_lower_triangular_mask,
     check_first_token_returns_its_own_value_row,
+    check_decoder_on_every_two_byte_pattern,
     check_sequences_do_not_see_each_other,
 ]

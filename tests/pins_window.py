@@ -118,6 +118,26 @@ def check_window_of_one_returns_own_value_row(lib=None):
             assert np.array_equal(got[b, h], own[h // 4])
 
 
+def check_decoder_on_every_two_byte_pattern(lib=None):
+    """All 65 536 fp16 and bf16 patterns (subnormals, infinities, NaNs) as the V row of a one-token
+    context read with W = 1: the single weight is exactly 1, so the output is the decoder's value of
+    each pattern, compared with numpy's own decoding."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    for dtype in (W.F16, W.BF16):
+        want = W.from_bits(bits, dtype)
+        D = 65536
+        kc = np.zeros((1, 1, 1, D), np.uint16)
+        vc = bits.reshape(1, 1, 1, D).copy()
+        q = np.zeros((1, 1, D), np.uint16)
+        out = O.paged_attention_window(q, kc, vc, np.zeros((1, 1), np.int32), np.ones(1, np.int32),
+                                       np.ones(1, np.float32), 1.0, 1, dtype, lib=lib)[0, 0]
+        fin = np.isfinite(want)
+        assert np.array_equal(out[fin], want[fin]), f"{dtype} decoding"
+        inf = np.isinf(want)
+        assert np.array_equal(out[inf], want[inf]), f"{dtype} infinities"
+        assert np.all(np.isnan(out[np.isnan(want)])), f"{dtype} NaN patterns"
+
+
 def check_against_dense_mask_matrix(lib=None):
     """Dense formulation with library pieces: scores = Q K^T, bias matrix, a banded 0 / -inf mask
     built with numpy's triangle routines, scipy's softmax, weights @ V."""
@@ -189,6 +209,7 @@ ALL_CHECKS = [
     check_wide_window_is_full_attention,
     check_window_equals_full_attention_over_the_window_tokens,
     check_window_of_one_returns_own_value_row,
+    check_decoder_on_every_two_byte_pattern,
     check_against_dense_mask_matrix,
     check_row_lists_pick_the_same_rows,
 ]

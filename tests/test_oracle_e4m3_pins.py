@@ -18,8 +18,8 @@ def test_pin(oracle, check):
 SRC = os.path.join(os.path.dirname(O.__file__), "optgqa_oracle_e4m3.c")
 
 MUTANTS = {
-    "exponent_bias": ("else v = ldexp(1.0 + (double)m / 8.0, e - 7);\n    return sign ? -v : v;\n}\n\n/* nearest",
-                      "else v = ldexp(1.0 + (double)m / 8.0, e - 8);\n    return sign ? -v : v;\n}\n\n/* nearest"),
+    "exponent_bias": ("else v = ldexp(1.0 + (double)m / 8.0, e - 7);\n    return sign ? -v : v;\n}\n\n/* The two decoders",
+                      "else v = ldexp(1.0 + (double)m / 8.0, e - 8);\n    return sign ? -v : v;\n}\n\n/* The two decoders"),
     "subnormal_step": ("else if (e == 0) v = ldexp((double)m, -9);", "else if (e == 0) v = ldexp((double)m, -10);"),
     "nan_code_is_a_number": ("if (e == 15 && m == 7) v = NAN;", "if (0) v = NAN;"),
     "truncates": ("int q = (int)nearbyint(ldexp(f, 4)) - 8;", "int q = (int)floor(ldexp(f, 4)) - 8;"),
@@ -41,6 +41,13 @@ MUTANTS = {
                            "block_tables + (int64_t)b * max_blocks_per_seq, context_lens[b], pos,\n                        h / group"),
     "prefill_ignores_prefix": ("int pos = context_lens[b] - new_tokens + (t - cu_q_lens[b]);", "int pos = (t - cu_q_lens[b]);"),
     "v_read_from_k": ("out_row[d] += w * e4m3_value(v_cache[at + d]);", "out_row[d] += w * e4m3_value(k_cache[at + d]);"),
+    # the file's own 2-byte decoder (queries and new-token rows)
+    "two_byte_f16_subnormal_step": ("if (e == 0) v = ldexp((double)m, -24);\n        else if (e == 31) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 1024.0, e - 15);\n    } else {\n        int e = (h >> 7) & 0xFF, m = h & 0x7F;\n        if (e == 0) v = ldexp((double)m, -133);\n        else if (e == 255) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula",
+                                    "if (e == 0) v = ldexp((double)m, -25);\n        else if (e == 31) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 1024.0, e - 15);\n    } else {\n        int e = (h >> 7) & 0xFF, m = h & 0x7F;\n        if (e == 0) v = ldexp((double)m, -133);\n        else if (e == 255) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula"),
+    "two_byte_bf16_infinity_is_finite": ("else if (e == 255) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula",
+                                         "else if (e == 255 && m) v = NAN;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula"),
+    "two_byte_bf16_mantissa_width": ("else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula",
+                                     "else v = ldexp(1.0 + (double)m / 256.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula"),
 }
 
 

@@ -35,6 +35,10 @@ MUTANTS = {
     "not_normalised": ("double w = s[j] / denom;", "double w = s[j];"),
     "sequence_boundary_off_by_one": ("while (b + 1 < num_seqs && cu_seq_lens[b + 1] <= t) ++b;",
                                      "while (b + 1 < num_seqs && cu_seq_lens[b + 1] < t) ++b;"),
+    # the file's own 2-byte decoder
+    "decoder_f16_subnormal_step": ("if (e == 0) v = ldexp((double)m, -24);", "if (e == 0) v = ldexp((double)m, -23);"),
+    "decoder_bf16_infinity_is_nan": ("else if (e == 255) v = m ? NAN : INFINITY;", "else if (e == 255) v = NAN;"),
+    "decoder_bf16_exponent_bias": ("else v = ldexp(1.0 + (double)m / 128.0, e - 127);", "else v = ldexp(1.0 + (double)m / 128.0, e - 126);"),
 }
 
 

@@ -42,6 +42,10 @@ MUTANTS = {
                                    "window, h % num_kv_heads, slope, (double)scale, num_kv_heads, head_dim,\n                          block_size, dtype);\n    }\n}\n\n/* Prefill"),
     "scale_dropped": ("s[j] = scale * dot + slope * (double)(j - pos) + mask;",
                       "s[j] = dot + slope * (double)(j - pos) + mask;"),
+    # the file's own 2-byte decoder
+    "decoder_bf16_subnormal_step": ("if (e == 0) v = ldexp((double)m, -133);", "if (e == 0) v = ldexp((double)m, -134);"),
+    "decoder_f16_nan_is_infinity": ("else if (e == 31) v = m ? NAN : INFINITY;", "else if (e == 31) v = INFINITY;"),
+    "decoder_f16_sign_lost_on_subnormals": ("if (e == 0) v = ldexp((double)m, -24);", "if (e == 0) return ldexp((double)m, -24);"),
 }
 
 
