@@ -11,9 +11,19 @@
  *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every
  *     buffer.  The library never allocates, frees or synchronises; all work is enqueued on
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream).
+ *   - State the library keeps between calls: the per-thread event pair of
+ *     optgqa_set_kernel_events, the static scratch array of optgqa_paged_attention_static, and
+ *     three facts about the device that are asked once per process (compute-unit count,
+ *     resident workgroups per kernel, address of that array).  Nothing that depends on a
+ *     call's inputs survives the call.
  *   - dtype selects the 2-byte element type of q, k, v, the caches and out.
  *   - Return value: OPTGQA_OK or a negative optgqa_status.  Arguments are checked on the host
- *     before anything is launched; on error nothing has been enqueued.
+ *     before anything is launched; on error nothing has been enqueued.  OPTGQA_ERR_LAUNCH
+ *     reports the status of the library's own launch only: an error that earlier work of the
+ *     caller left pending in the HIP runtime is neither reported here nor cleared.
+ *   - `scale` must be finite (else OPTGQA_ERR_SHAPE).  The prefill entry points evaluate
+ *     |scale| < 2^-64 (zero included) as +-2^-64, which changes no output bit at the stated
+ *     tolerances, and need |alibi_slopes| * 2^64 to stay finite in fp32.
  *   - Contents of device tables (block ids, slots, context lengths) are NOT checked by the
  *     kernels; out-of-range values are undefined behaviour.  optgqa_validate_tables_host
  *     checks host copies.

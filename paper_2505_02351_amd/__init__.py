@@ -139,10 +139,55 @@ def _dense(t: torch.Tensor, name: str) -> torch.Tensor:
     return t
 
 
+def _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, *, kv8=False, new=(),
+                cu_q_lens=None) -> None:
+    """_typed for the attention entry points: out, the new rows and (2-byte) caches as q, 8-bit caches
+    uint8, tables / lengths / prefix sums int32, slopes float32, all on q's GPU."""
+    caches = [("k_cache", k_cache), ("v_cache", v_cache)]
+    same = [("out", out)] + [(n, t) for n, t in zip(("k_new", "v_new"), new)] + ([] if kv8 else caches)
+    _typed(q, same=same, u8=caches if kv8 else (),
+           i32=[("block_tables", block_tables), ("context_lens", context_lens), ("cu_q_lens", cu_q_lens)],
+           f32=[("alibi_slopes", alibi_slopes)])
+
+
+def _workspace(ws: Optional[torch.Tensor], ref: torch.Tensor) -> int:
+    """Bytes of a caller-owned workspace (0 for None); it must be a dense tensor on ref's GPU."""
+    if ws is None:
+        return 0
+    if not isinstance(ws, torch.Tensor) or not ws.is_cuda or ws.device != ref.device or not ws.is_contiguous():
+        raise ValueError("optgqa: the workspace must be a contiguous tensor on the same GPU")
+    return ws.numel() * ws.element_size()
+
+
+def _typed(ref: torch.Tensor, *, same=(), u8=(), i32=(), i64=(), f32=()) -> None:
+    """Refuse, before any pointer is taken, what the C ABI cannot check: the library reads raw
+    device pointers, so a tensor of another element type or on another device would be misread
+    (block ids and slots out of range make the kernels write out of bounds).  ``ref`` (q, or k for
+    the cache writes) fixes the 2-byte type and the device; each group is a list of (name, tensor
+    or None).  Element types first (TypeError), then devices (ValueError)."""
+    _dtype_code(ref)
+    groups = ((same, ref.dtype), (u8, torch.uint8), (i32, torch.int32), (i64, torch.int64), (f32, torch.float32))
+    for group, want in groups:
+        for name, t in group:
+            if t is None:
+                continue
+            if not isinstance(t, torch.Tensor):
+                raise TypeError(f"optgqa: {name} must be a torch.Tensor")
+            if t.dtype != want:
+                raise TypeError(f"optgqa: {name} must be {want}, got {t.dtype}")
+    if not ref.is_cuda:
+        raise ValueError("optgqa: tensors must live in GPU memory")
+    for group, _ in groups:
+        for name, t in group:
+            if t is not None and t.device != ref.device:
+                raise ValueError(f"optgqa: {name} is on {t.device}, expected {ref.device}")
+
+
 def reshape_and_cache(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
                       slot_mapping: torch.Tensor, stream=None) -> None:
     """optgqa_reshape_and_cache: scatter the new tokens' K/V rows into the paged caches."""
     lib = load_library()
+    _typed(k, same=[("v", v), ("k_cache", k_cache), ("v_cache", v_cache)], i64=[("slot_mapping", slot_mapping)])
     NB, Hkv, bs, D = k_cache.shape
     T = int(slot_mapping.shape[0])
     _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(slot_mapping, "slot_mapping")
@@ -171,6 +216,7 @@ def paged_attention(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v
                     partition_size: int = 0, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """optgqa_paged_attention: decode attention of one query token per sequence."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes)
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
@@ -178,7 +224,7 @@ def paged_attention(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v
     for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
                  (block_tables, "block_tables"), (context_lens, "context_lens")):
         _dense(t, n)
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_paged_attention(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
                                     _ptr(context_lens), _ptr(alibi_slopes), float(scale), B, Hq, Hkv, D, bs,
                                     int(block_tables.shape[1]), int(max_context_len), int(partition_size),
@@ -196,6 +242,7 @@ def paged_attention_static(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Te
     """optgqa_paged_attention_static: decode attention whose split-context scratch is the library's
     own static device array (no workspace argument, nothing allocated)."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes)
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
@@ -230,6 +277,7 @@ def decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: 
                 max_context_len: int, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """optgqa_decode_step: the step's cache write and its decode attention in one call."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, new=(k_new, v_new))
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
@@ -241,7 +289,7 @@ def decode_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: 
         raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
     ks = int(k_new.stride(0)) if B else Hkv * D
     vs = int(v_new.stride(0)) if B else Hkv * D
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_decode_step(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                 _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale), B, Hq,
                                 Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len), ks, vs,
@@ -254,10 +302,9 @@ def reshape_and_cache_fp8(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tenso
     """optgqa_reshape_and_cache_fp8: quantise the new tokens' K/V rows to E4M3 codes in the paged
     caches (uint8 tensors [NB, Hkv, bs, D])."""
     lib = load_library()
+    _typed(k, same=[("v", v)], u8=[("k_cache", k_cache), ("v_cache", v_cache)], i64=[("slot_mapping", slot_mapping)])
     NB, Hkv, bs, D = k_cache.shape
     T = int(slot_mapping.shape[0])
-    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
-        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
     _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(slot_mapping, "slot_mapping")
     if T and (k.stride(-1) != 1 or k.stride(-2) != D or v.stride(-1) != 1 or v.stride(-2) != D):
         raise ValueError("optgqa: k and v must be dense in their last two dims")
@@ -275,16 +322,15 @@ def paged_attention_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tenso
                         max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
     """optgqa_paged_attention_fp8: decode attention over E4M3 caches (uint8 tensors)."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True)
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
         raise ValueError("optgqa: shape mismatch between q, out and the caches")
-    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
-        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
     for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
                  (block_tables, "block_tables"), (context_lens, "context_lens")):
         _dense(t, n)
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_paged_attention_fp8(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
                                         _ptr(context_lens), _ptr(alibi_slopes), float(scale), float(k_scale),
                                         float(v_scale), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
@@ -300,12 +346,11 @@ def decode_step_fp8(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_n
     """optgqa_decode_step_fp8: quantising cache write of the step's new tokens and decode attention over
     the E4M3 caches in one call."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True, new=(k_new, v_new))
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
         raise ValueError("optgqa: shape mismatch between q, out, the new rows and the caches")
-    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
-        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
     for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
                  (block_tables, "block_tables"), (context_lens, "context_lens")):
         _dense(t, n)
@@ -313,7 +358,7 @@ def decode_step_fp8(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_n
         raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
     ks = int(k_new.stride(0)) if B else Hkv * D
     vs = int(v_new.stride(0)) if B else Hkv * D
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_decode_step_fp8(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                     _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale),
                                     float(k_scale), float(v_scale), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
@@ -328,12 +373,11 @@ def paged_prefill_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor,
                       max_q_len: int, stream=None) -> None:
     """optgqa_paged_prefill_fp8: causal + ALiBi attention of the new tokens over E4M3 caches."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True, cu_q_lens=cu_q_lens)
     T, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
         raise ValueError("optgqa: shape mismatch between q, out and the caches")
-    if k_cache.dtype != torch.uint8 or v_cache.dtype != torch.uint8:
-        raise TypeError("optgqa: the 8-bit caches are uint8 tensors")
     for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
                  (block_tables, "block_tables"), (context_lens, "context_lens"), (cu_q_lens, "cu_q_lens")):
         _dense(t, n)
@@ -349,6 +393,7 @@ def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_c
                   alibi_slopes: Optional[torch.Tensor], scale: float, max_q_len: int, stream=None) -> None:
     """optgqa_paged_prefill: causal + ALiBi attention of the new tokens over the paged cache."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, cu_q_lens=cu_q_lens)
     T, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
@@ -370,6 +415,7 @@ def paged_attention_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Te
                            workspace: Optional[torch.Tensor], stream=None) -> None:
     """optgqa_paged_attention_window: decode attention over the last ``window`` tokens."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes)
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
@@ -377,7 +423,7 @@ def paged_attention_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Te
     for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
                  (block_tables, "block_tables"), (context_lens, "context_lens")):
         _dense(t, n)
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_paged_attention_window(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
                                            _ptr(context_lens), _ptr(alibi_slopes), float(scale), int(window), B, Hq,
                                            Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len),
@@ -391,6 +437,7 @@ def decode_step_window(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, 
                        max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
     """optgqa_decode_step_window: the step's cache write and its windowed decode attention."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, new=(k_new, v_new))
     B, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
@@ -402,7 +449,7 @@ def decode_step_window(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, 
         raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
     ks = int(k_new.stride(0)) if B else Hkv * D
     vs = int(v_new.stride(0)) if B else Hkv * D
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ws_bytes = _workspace(workspace, q)
     rc = lib.optgqa_decode_step_window(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale),
                                        int(window), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
@@ -417,6 +464,7 @@ def paged_prefill_window(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tens
                          stream=None) -> None:
     """optgqa_paged_prefill_window: causal attention of the new tokens, each over its last ``window`` keys."""
     lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, cu_q_lens=cu_q_lens)
     T, Hq, D = q.shape
     NB, Hkv, bs, Dk = k_cache.shape
     if Dk != D or out.shape != q.shape:
@@ -439,6 +487,8 @@ def prompt_prefill(out: torch.Tensor, q: torch.Tensor, k: torch.Tensor, v: torch
     """optgqa_prompt_prefill: causal (+ ALiBi) attention of whole prompts over their own K / V, storing
     K / V into the paged caches in the same launch when the caches are given."""
     lib = load_library()
+    _typed(q, same=[("out", out), ("k", k), ("v", v), ("k_cache", k_cache), ("v_cache", v_cache)],
+           i32=[("block_tables", block_tables), ("cu_seq_lens", cu_seq_lens)], f32=[("alibi_slopes", alibi_slopes)])
     T, Hq, D = q.shape
     Hkv = k.shape[1]
     if out.shape != q.shape or k.shape != (T, Hkv, D) or v.shape != (T, Hkv, D):
@@ -466,6 +516,8 @@ def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v
               block_tables: torch.Tensor, context_lens: torch.Tensor, stream=None) -> None:
     """optgqa_gather_kv: un-page the caches into [B, max_context_len, Hkv, D] (bit copy)."""
     lib = load_library()
+    _typed(k_cache, same=[("k_out", k_out), ("v_out", v_out), ("v_cache", v_cache)],
+           i32=[("block_tables", block_tables), ("context_lens", context_lens)])
     B, Lmax, Hkv, D = k_out.shape
     NB, Hkv2, bs, D2 = k_cache.shape
     if (Hkv, D) != (Hkv2, D2) or v_out.shape != k_out.shape:

@@ -132,10 +132,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j16 = lane & 15;
     const int hg = lane >> 4;
-#ifdef OPTGQA_FLAT_TIMING
-    const unsigned long long tm0 = wall_clock64();
-    unsigned long long tm1 = 0, tm2 = 0;
-#endif
 
     const int B = p.num_seqs, Y = p.segs_per_seq;
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
@@ -475,9 +471,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             d1 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau + min(j + 1, j_last));
             load_tile(buf[1], d1);
             compute_tile(buf[0], d0, std::false_type{});
-#ifdef OPTGQA_FLAT_TIMING
-            if (tm1 == 0) tm1 = wall_clock64();
-#endif
             const bool more = j + 2 <= j_last;
             d0 = tile_src(more ? table : x_table, more ? head_off : x_head_off, more ? L : x_L, more ? n : x_n,
                           more ? reg_end : x_reg_end, more ? new_k : x_new_k, more ? new_v : x_new_v,
@@ -495,9 +488,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             }
         }
 
-#ifdef OPTGQA_FLAT_TIMING
-        tm2 = wall_clock64();
-#endif
         // ---- leave the piece's partial result in slot u + s: this lane holds dims 16db + 4hg + v of
         // head j16 ----------------------------------------------------------------------------------
         const int64_t slot = (int64_t)u + (int64_t)b * Y + y;
@@ -514,14 +504,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         }
 
         // ---- next piece ------------------------------------------------------------------------
-#ifdef OPTGQA_FLAT_TIMING
-        if (!has_next && p.timing && lane == 0) {
-            p.timing[4 * u + 0] = tm0;
-            p.timing[4 * u + 1] = tm1;
-            p.timing[4 * u + 2] = tm2;
-            p.timing[4 * u + 3] = wall_clock64();
-        }
-#endif
         if (!has_next) break;
         f += ntw;
         if (y + 1 == Y) P_b += n;                            // sequences skipped on the way have no tiles

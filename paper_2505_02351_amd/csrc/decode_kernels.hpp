@@ -50,9 +50,6 @@ struct DecodeParams {
     int64_t k_new_stride, v_new_stride;
     void* k_cache_w;            // the caches again, writable
     void* v_cache_w;
-#ifdef OPTGQA_FLAT_TIMING
-    unsigned long long* timing; // development builds only: 4 clock samples per unit
-#endif
 };
 
 // Sequence and number of visible keys of one output row (decode: row = sequence).

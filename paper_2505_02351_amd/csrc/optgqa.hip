@@ -4,7 +4,12 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cmath>
 #include <mutex>
+#include <tuple>
+#include <type_traits>
+#include <utility>
 
 #include "cache_kernels.hpp"
 #include "decode_kernels.hpp"
@@ -25,7 +30,6 @@ static __device__ __align__(256) unsigned char g_static_scratch[OPTGQA_STATIC_SC
 namespace {
 
 constexpr int kAbiVersion = 1;
-constexpr int kNumCUs = 256;              // MI355X
 constexpr int kMinPartition = 256;        // tokens; smaller runs are dominated by the merge
 
 bool dtype_ok(int dt) { return dt == OPTGQA_F16 || dt == OPTGQA_BF16; }
@@ -33,9 +37,32 @@ bool head_dim_ok(int d) { return d == 64 || d == 128; }
 bool block_size_ok(int bs) { return bs == 16 || bs == 32 || bs == 64; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int launch_status()
+// Launch through the call that reports THIS launch's own status (hipLaunchKernel): an error
+// some earlier work of the caller left behind in the runtime's "last error" slot is neither
+// reported as ours nor cleared.
+template <typename... KArgs, typename... Args>
+int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, Args&&... args)
 {
-    return hipGetLastError() == hipSuccess ? OPTGQA_OK : OPTGQA_ERR_LAUNCH;
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count does not match the kernel");
+    std::tuple<std::decay_t<KArgs>...> vals(std::forward<Args>(args)...);
+    void* ptrs[sizeof...(KArgs)];
+    std::apply([&](auto&... v) { int i = 0; ((ptrs[i++] = static_cast<void*>(&v)), ...); }, vals);
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, st) == hipSuccess
+               ? OPTGQA_OK : OPTGQA_ERR_LAUNCH;
+}
+
+// Compute units of the current device, asked once (every GPU of a box is the same part); 256,
+// the MI355X count, where no device answers (the sizing calls also work on a GPU-less host).
+int num_cus()
+{
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return 256;
+        return n;
+    }();
+    return cus;
 }
 
 // Profiling aid (optgqa_set_kernel_events): events recorded around the launch of the kernel that
@@ -99,7 +126,7 @@ int auto_partition(int num_seqs, int num_heads, int num_kv_heads, int head_dim, 
     if (max_context_len <= kMinPartition) return 0;
     const int group = num_heads / num_kv_heads;
     const long units = (long)num_seqs * num_kv_heads * (group / heads_per_workgroup(group, head_dim));
-    const long want_wgs = 8L * kNumCUs;
+    const long want_wgs = 8L * num_cus();
     if (units >= want_wgs) return 0;
     long np = (want_wgs + units - 1) / units;                       // partitions per sequence
     int step = block_size > 16 ? block_size : 16;
@@ -128,9 +155,8 @@ struct SplitPlan {
 // OPTGQA_FLAT_WGS_PER_CU_KV8 per CU for 8-bit caches (half the bytes per tile: the second wave
 // per SIMD hides the arithmetic); no wave with less than kFlatMinTiles tiles of 16 tokens when
 // the lengths are at their bound.  The workspace is sized for the larger of the two.
-constexpr int kFlatWorkgroups = kNumCUs * OPTGQA_FLAT_WGS_PER_CU;
-constexpr int kFlatWorkgroupsKv8 = kNumCUs * OPTGQA_FLAT_WGS_PER_CU_KV8;
-constexpr int kFlatMaxWorkgroups = kFlatWorkgroups > kFlatWorkgroupsKv8 ? kFlatWorkgroups : kFlatWorkgroupsKv8;
+int flat_workgroups(bool kv8) { return num_cus() * (kv8 ? OPTGQA_FLAT_WGS_PER_CU_KV8 : OPTGQA_FLAT_WGS_PER_CU); }
+int flat_max_workgroups() { return std::max(flat_workgroups(false), flat_workgroups(true)); }
 #ifndef OPTGQA_FLAT_MIN_TILES
 #define OPTGQA_FLAT_MIN_TILES 8
 #endif
@@ -152,7 +178,7 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     const int seen = window > 0 && window + kMmaTile - 1 < max_context_len ? window + kMmaTile - 1 : max_context_len;
     const int64_t tiles = segs * ((seen + kMmaTile - 1) / kMmaTile);
     int64_t wgs = (tiles + (int64_t)kDecodeWaves * kFlatMinTiles - 1) / ((int64_t)kDecodeWaves * kFlatMinTiles);
-    if (wgs > kFlatMaxWorkgroups) wgs = kFlatMaxWorkgroups;
+    if (wgs > flat_max_workgroups()) wgs = flat_max_workgroups();
     if (wgs < 1) wgs = 1;
     s.partition_size = OPTGQA_SPLIT_BALANCED;
     s.num_partitions = 1;
@@ -194,8 +220,7 @@ int launch_decode_mc(const DecodeParams& p, dim3 grid, dim3 block, hipStream_t s
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&paged_decode_mc_kernel<DT, D, GH>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
     if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
-    hipLaunchKernelGGL((paged_decode_mc_kernel<DT, D, GH>), grid, block, kBytes, st, p);
-    return launch_status();
+    return launch(paged_decode_mc_kernel<DT, D, GH>, grid, block, kBytes, st, p);
 }
 
 template <int DT, int D>
@@ -203,8 +228,7 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
 {
     const dim3 block(kDecodeWaves * 64);
     if (D == 128) {
-        hipLaunchKernelGGL((paged_decode_mma_kernel<DT>), grid, block, 0, st, p);
-        return launch_status();
+        return launch(paged_decode_mma_kernel<DT>, grid, block, 0, st, p);
     }
 #ifndef OPTGQA_VALU_ONLY_DECODE
     if (p.window <= 0) {                                 // (the general kernel is the one that knows about windows)
@@ -213,12 +237,11 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
     }
 #endif
     switch (gh) {
-    case 8: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 8>), grid, block, 0, st, p); break;
-    case 4: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 4>), grid, block, 0, st, p); break;
-    case 2: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 2>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((paged_decode_kernel<DT, D, 1>), grid, block, 0, st, p); break;
+    case 8: return launch(paged_decode_kernel<DT, D, 8>, grid, block, 0, st, p);
+    case 4: return launch(paged_decode_kernel<DT, D, 4>, grid, block, 0, st, p);
+    case 2: return launch(paged_decode_kernel<DT, D, 2>, grid, block, 0, st, p);
+    default: return launch(paged_decode_kernel<DT, D, 1>, grid, block, 0, st, p);
     }
-    return launch_status();
 }
 
 
@@ -240,9 +263,8 @@ int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
         if (rc != OPTGQA_OK) return rc;
         if (p.num_partitions == 1) continue;
         constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
-        hipLaunchKernelGGL((paged_decode_reduce_kernel<DT, D>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, rows),
-                           dim3(kReduceThreads), 0, st, p);
-        rc = launch_status();
+        rc = launch(paged_decode_reduce_kernel<DT, D>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, rows),
+                    dim3(kReduceThreads), 0, st, p);
         if (rc != OPTGQA_OK) return rc;
     }
     return OPTGQA_OK;
@@ -275,16 +297,15 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     const int group = p.num_heads / p.num_kv_heads;
     p.heads_per_wg = heads_per_workgroup(group, 128);
     p.num_units = workgroups * kDecodeWaves;
+    int rc;
     {
         KernelEvents ev(st);
-        hipLaunchKernelGGL((paged_decode_flat_kernel<DT, FUSED, KV8>), dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
     }
-    int rc = launch_status();
     if (rc != OPTGQA_OK) return rc;
     constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
-    hipLaunchKernelGGL((paged_decode_flat_reduce_kernel<DT, FUSED && KV8>), dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
-                       dim3(kReduceThreads), 0, st, p);
-    return launch_status();
+    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+                  dim3(kReduceThreads), 0, st, p);
 }
 
 int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
@@ -302,9 +323,6 @@ int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStre
                                : launch_decode_flat_dt<kBF16, false>(p, workgroups, st);
 }
 
-#ifdef OPTGQA_PF_TIMING
-unsigned long long* g_pf_timing = nullptr;      // development builds only
-#endif
 
 // The tiled prefill kernel takes its LDS as dynamic shared memory (more than the 64 KiB a kernel
 // gets by default); the limit is raised once per instantiation.
@@ -316,8 +334,7 @@ int launch_prefill_mma_w(const PrefillParams& p, dim3 grid, hipStream_t st)
         reinterpret_cast<const void*>(&paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D, WAVES>),
         hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
     if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
-    hipLaunchKernelGGL((paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D, WAVES>), grid, dim3(WAVES * 64), kBytes, st, p);
-    return launch_status();
+    return launch(paged_prefill_mma_kernel<DT, KV8, WIN, CONTIG, D, WAVES>, grid, dim3(WAVES * 64), kBytes, st, p);
 }
 
 template <int DT, bool KV8, bool WIN, bool CONTIG, int D>
@@ -338,6 +355,17 @@ int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, int wave
     return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, waves, st);
 }
 
+// The tiled prefill kernel carries the tile-invariant part of the ALiBi term inside the score
+// accumulator as slope / scale, so it cannot take a score scale of exactly zero.  Magnitudes
+// below 2^-64 (zero included) are evaluated as +-2^-64: the scores then differ from the exact
+// ones by |q.k| * 2^-64, far below fp32 resolution of the bias they are added to.
+float prefill_scale2(float scale)
+{
+    const float tiny = 0x1p-64f;
+    const float s = std::fabs(scale) < tiny ? std::copysign(tiny, scale) : scale;
+    return s * kLog2e;
+}
+
 // Tiled matrix-core prefill (head_dim 128 or 64; 8-bit caches: 128 only).
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
                    bool kv8 = false, bool contig = false)
@@ -356,15 +384,12 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const int64_t units8 = (p.units + 7) / 8 * 8;
     const int tokens_per_wg8 = (8 * 32) >> shift;
     const int64_t blocks8 = units8 * ((max_q_len + tokens_per_wg8 - 1) / tokens_per_wg8);
-    const int waves = (p.window > 0 || blocks8 < 2 * kNumCUs) ? 4 : 8;
+    const int waves = (p.window > 0 || blocks8 < 2 * num_cus()) ? 4 : 8;
     const int tokens_per_wg = (waves * 32) >> shift;
     p.q_tiles = (max_q_len + tokens_per_wg - 1) / tokens_per_wg;
     const int64_t blocks = units8 * p.q_tiles;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
     const dim3 grid((unsigned)blocks);
-#ifdef OPTGQA_PF_TIMING
-    p.timing = g_pf_timing;
-#endif
     KernelEvents ev(st);
     const bool f16 = dtype == OPTGQA_F16;
     if (contig) {
@@ -386,9 +411,6 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
 
 }  // namespace
 
-#ifdef OPTGQA_PF_TIMING
-extern "C" int optgqa_set_pf_timing(void* buf) { g_pf_timing = static_cast<unsigned long long*>(buf); return 0; }
-#endif
 
 extern "C" {
 
@@ -441,15 +463,9 @@ int optgqa_reshape_and_cache(const void* k, const void* v, void* k_cache, void* 
     auto vv = static_cast<const uint16_t*>(v);
     auto kc = static_cast<uint16_t*>(k_cache);
     auto vc = static_cast<uint16_t*>(v_cache);
-    if (wide)
-        hipLaunchKernelGGL((reshape_and_cache_kernel<uint4>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
-                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
-                           v_token_stride);
-    else
-        hipLaunchKernelGGL((reshape_and_cache_kernel<uint16_t>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv,
-                           kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size,
-                           k_token_stride, v_token_stride);
-    return launch_status();
+    return launch(wide ? reshape_and_cache_kernel<uint4> : reshape_and_cache_kernel<uint16_t>, dim3((unsigned)blocks),
+                  dim3(256), 0, st, kk, vv, kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size,
+                  k_token_stride, v_token_stride, nullptr, nullptr, 0);
 }
 
 size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads,
@@ -493,15 +509,9 @@ int write_new_tokens(const StepInputs& n, const int64_t* slot_mapping, const int
     auto vv = static_cast<const uint16_t*>(n.v_new);
     auto kc = static_cast<uint16_t*>(n.k_cache_w);
     auto vc = static_cast<uint16_t*>(n.v_cache_w);
-    if (wide)
-        hipLaunchKernelGGL((reshape_and_cache_kernel<uint4>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
-                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, n.k_stride,
-                           n.v_stride, block_tables, context_lens, max_blocks_per_seq);
-    else
-        hipLaunchKernelGGL((reshape_and_cache_kernel<uint16_t>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv,
-                           kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, n.k_stride,
-                           n.v_stride, block_tables, context_lens, max_blocks_per_seq);
-    return launch_status();
+    return launch(wide ? reshape_and_cache_kernel<uint4> : reshape_and_cache_kernel<uint16_t>, dim3((unsigned)blocks),
+                  dim3(256), 0, st, kk, vv, kc, vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size,
+                  n.k_stride, n.v_stride, block_tables, context_lens, max_blocks_per_seq);
 }
 
 // Decode attention, optionally preceded by (or fused with) the step's cache write.
@@ -524,6 +534,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_context_len < 0)
         return OPTGQA_ERR_SHAPE;
+    if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if ((int64_t)max_context_len > (int64_t)max_blocks_per_seq * block_size) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
@@ -612,11 +623,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
             p.k_cache_w = step->k_cache_w;
             p.v_cache_w = step->v_cache_w;
         }
-#ifdef OPTGQA_FLAT_TIMING
-        p.timing = workspace_bytes >= s.bytes + (size_t)s.workgroups * kDecodeWaves * 32
-                       ? reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + s.bytes) : nullptr;
-#endif
-        const int cap = kv_scales ? kFlatWorkgroupsKv8 : kFlatWorkgroups;
+        const int cap = flat_workgroups(kv_scales != nullptr);
         return launch_decode_flat(dtype, p, s.workgroups < cap ? s.workgroups : cap, st, kv_scales != nullptr);
     }
     p.plan = nullptr;
@@ -702,15 +709,9 @@ int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, vo
     auto vv = static_cast<const uint16_t*>(v);
     auto kc = static_cast<unsigned char*>(k_cache);
     auto vc = static_cast<unsigned char*>(v_cache);
-    if (dtype == OPTGQA_F16)
-        hipLaunchKernelGGL((reshape_and_cache_e4m3_kernel<kF16>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
-                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
-                           v_token_stride, k_inv, v_inv);
-    else
-        hipLaunchKernelGGL((reshape_and_cache_e4m3_kernel<kBF16>), dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc,
-                           vc, slot_mapping, num_tokens, num_kv_heads, head_dim, block_size, k_token_stride,
-                           v_token_stride, k_inv, v_inv);
-    return launch_status();
+    return launch(dtype == OPTGQA_F16 ? reshape_and_cache_e4m3_kernel<kF16> : reshape_and_cache_e4m3_kernel<kBF16>,
+                  dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc, vc, slot_mapping, num_tokens, num_kv_heads,
+                  head_dim, block_size, k_token_stride, v_token_stride, k_inv, v_inv);
 }
 
 int optgqa_paged_attention_fp8(void* out, const void* q, const void* k_cache, const void* v_cache,
@@ -798,6 +799,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_q_len < 0)
         return OPTGQA_ERR_SHAPE;
+    if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
     if (kv_scales && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;   // tiled kernel only
@@ -814,7 +816,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     p.context_lens = context_lens;
     p.cu_q_lens = cu_q_lens;
     p.slopes = alibi_slopes;
-    p.scale2 = scale * kLog2e * (kv_scales ? kv_scales[0] : 1.f);
+    p.scale2 = prefill_scale2(scale * (kv_scales ? kv_scales[0] : 1.f));
     p.out_scale = kv_scales ? kv_scales[1] : 1.f;
     p.window = window > 0 ? window : 0;
     p.k_in = p.v_in = nullptr;
@@ -872,6 +874,7 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
 {
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || max_seq_len < 0)
         return OPTGQA_ERR_SHAPE;
+    if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     const int64_t row = (int64_t)num_kv_heads * head_dim;
     if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
@@ -898,7 +901,7 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
     p.context_lens = nullptr;
     p.cu_q_lens = cu_seq_lens;
     p.slopes = alibi_slopes;
-    p.scale2 = scale * kLog2e;
+    p.scale2 = prefill_scale2(scale);
     p.out_scale = 1.f;
     p.window = 0;
     p.k_in = k;
@@ -926,10 +929,9 @@ int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_byte
     const int64_t n = (int64_t)num_workgroups * 4 * tiles_per_wave;
     for (int64_t i = 0; i < n; ++i)
         if (tile_list_host[i] < 0 || tile_list_host[i] >= pieces) return OPTGQA_ERR_TABLE;
-    hipLaunchKernelGGL(stream_probe_kernel, dim3(num_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const unsigned char*>(k_pool), static_cast<const unsigned char*>(v_pool),
-                       tile_list, tiles_per_wave, static_cast<uint4*>(sink));
-    return launch_status();
+    return launch(stream_probe_kernel, dim3(num_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                  static_cast<const unsigned char*>(k_pool), static_cast<const unsigned char*>(v_pool), tile_list,
+                  tiles_per_wave, static_cast<uint4*>(sink));
 }
 
 int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* v_cache,
@@ -947,12 +949,10 @@ int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* 
     if (num_seqs > 65535) return OPTGQA_ERR_SHAPE;
     const int64_t pieces = (int64_t)max_context_len * num_kv_heads * (head_dim / 8);
     const dim3 grid((unsigned)((pieces + 255) / 256), num_seqs, 2);
-    hipLaunchKernelGGL(gather_kv_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out),
-                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
-                       block_tables, context_lens, num_kv_heads, head_dim, block_size, max_blocks_per_seq,
-                       max_context_len);
-    return launch_status();
+    return launch(gather_kv_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+                  static_cast<uint16_t*>(k_out), static_cast<uint16_t*>(v_out), static_cast<const uint16_t*>(k_cache),
+                  static_cast<const uint16_t*>(v_cache), block_tables, context_lens, num_kv_heads, head_dim,
+                  block_size, max_blocks_per_seq, max_context_len);
 }
 
 int optgqa_validate_tables_host(const int32_t* block_tables_host, const int32_t* context_lens_host,

@@ -67,9 +67,6 @@ struct PrefillParams {
     int64_t k_in_stride, v_in_stride;
     void* k_cache_w;            // caches to store the prompt's K/V into (both or neither), else nullptr
     void* v_cache_w;
-#ifdef OPTGQA_PF_TIMING
-    unsigned long long* timing; // development builds: per-wave cycle sums of the loop's phases
-#endif
 };
 
 // Waves per workgroup (a template parameter, 32 rows per wave): 8 - 256 rows against one K/V tile,
@@ -315,20 +312,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     };
 
     const float scale2 = p.scale2;
-#ifdef OPTGQA_PF_TIMING
-    unsigned long long tm_sum[6] = {0, 0, 0, 0, 0, 0}, tm_last = clock64();
-    const unsigned long long tm_clk0 = tm_last, tm_wall0 = wall_clock64();
-    auto stamp = [&](int i) __attribute__((always_inline)) {
-        const unsigned long long t = clock64();
-        tm_sum[i] += t - tm_last;
-        tm_last = t;
-    };
-#define PF_STAMP(i) stamp(i)
-#define PF_TOUCH(x) asm volatile("v_mov_b32 %0, %0" : "+v"(x))
-#else
-#define PF_STAMP(i)
-#define PF_TOUCH(x)
-#endif
     // ---- S^T = K Q^T : element 4i + j = score of key 32kt + 8i + 4h2 + j against row n32
     // (the accumulator starts from the tile-invariant part of the ALiBi term, already divided by the
     // score scale, so that one FMA per score finishes eq. (3))
@@ -343,8 +326,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     };
     auto softmax_pv = [&](int kt, int buf, f32x16 st, auto masked) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked)::value;
-        PF_TOUCH(st[0]); PF_TOUCH(st[15]);
-        PF_STAMP(0);                                             // scores ready
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
         // x = score - reference, formed directly: st*scale2 + slope2*key + (-slope2*pos - m_ref)
         const float k0 = (float)(kt * kPfKeys + 4 * h2);
@@ -403,9 +384,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
                 lsum += widen_lo<DT>(hi) + widen_hi<DT>(hi);
             }
         }
-
-        PF_TOUCH(pk[1][3]);
-        PF_STAMP(1);                                             // weights packed
         // ---- O^T += V^T P^T ---------------------------------------------------------------------
         // A = V^T for dims 32db .. +31: this lane is dim 32db + n32 and needs keys 16m + 4h2 + (0..3)
         // and 16m + 8 + 4h2 + (0..3).  One transposing load hands each group of 16 lanes 4 keys x
@@ -462,13 +440,9 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         const int j = kt - kt0;
         st_ahead = scores(j + 1);
         softmax_pv(kt, j, st_cur, masked);
-        PF_STAMP(2);                                             // output MFMAs issued
         store_tile(stage, j + 1 + l_ahead);
-        PF_STAMP(3);                                             // a later tile stored (waits for its loads)
         fetch_tile(stage, kt + 2 + l_ahead);
-        PF_STAMP(4);
         __syncthreads();
-        PF_STAMP(5);                                             // barrier passed
     };
     auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
         int kt = from;
@@ -487,15 +461,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     run_tiles(cut_end, plain_end, std::false_type{});
     run_tiles(plain_end, ntiles, std::true_type{});
 
-#ifdef OPTGQA_PF_TIMING
-    if (p.timing && lane == 0) {
-        unsigned long long* t = p.timing + 8 * ((size_t)blockIdx.x * kPfWaves + wave);
-        for (int i = 0; i < 6; ++i) t[i] = tm_sum[i];
-        t[6] = (unsigned long long)(ntiles - kt0);
-        // core clock cycles per 1000 ticks of the 100 MHz wall clock over the loop: the clock the kernel ran at
-        t[7] = (clock64() - tm_clk0) * 1000ull / max(wall_clock64() - tm_wall0, 1ull);
-    }
-#endif
     // ---- normalise and write: this lane holds dims 32db + 8i + 4h2 + (0..3) of its row -----------
     uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);
     float lt = lsum;
