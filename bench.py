@@ -34,6 +34,7 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+sys.path.insert(1, os.path.join(ROOT, "tests"))      # harness.py: device copies of a generated batch
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
@@ -228,7 +229,7 @@ def main():
         if args.shared_prefix > 1:
             assert cfg.kind == "decode", "--shared-prefix applies to decode workloads"
             shared_tokens = W.share_prefix_blocks(case, args.shared_prefix, 0.9)
-        from paper_2505_02351_amd.testing import DevCase
+        from harness import DevCase
         dev = DevCase(case)
         P = cfg.partition_size if args.partition_size is None else args.partition_size
         decode = cfg.kind == "decode"
@@ -249,7 +250,7 @@ def main():
             shape = (cfg.num_blocks, cfg.num_kv_heads, cfg.block_size, cfg.head_dim)
             k8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
             v8 = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
-            from paper_2505_02351_amd.testing import to_dev
+            from harness import to_dev
             if len(slots_old):
                 G.reshape_and_cache_fp8(to_dev(k_old, case.dtype), to_dev(v_old, case.dtype), k8, v8,
                                         torch.from_numpy(slots_old).cuda(), KV_SCALE, KV_SCALE)

@@ -209,3 +209,66 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit(G):
     header = open(HEADER).read()
     m = re.search(r"#define OPTGQA_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
     assert m and int(m.group(1)) << int(m.group(2)) == G.STATIC_SCRATCH_BYTES
+
+
+def test_binding_refuses_wrong_element_types_and_host_tensors(G):
+    """The binding hands raw pointers to the library, so it must refuse - before any pointer is
+    taken or anything is launched - index tensors of torch's default int64, slopes that are not
+    float32, caches of another 2-byte type than q, and tensors that are not in GPU memory."""
+    import torch
+    q = torch.zeros(2, 8, 64, dtype=torch.float16)
+    out = torch.empty_like(q)
+    c = torch.zeros(4, 2, 16, 64, dtype=torch.float16)
+    c8 = torch.zeros(4, 2, 16, 64, dtype=torch.uint8)
+    bt = torch.zeros(2, 2, dtype=torch.int32)
+    cl = torch.ones(2, dtype=torch.int32)
+    cu = torch.tensor([0, 1, 2], dtype=torch.int32)
+    sl = torch.ones(8, dtype=torch.float32)
+    slots = torch.zeros(2, dtype=torch.int64)
+    kv = torch.zeros(2, 2, 64, dtype=torch.float16)
+    ws = torch.zeros(1024, dtype=torch.float32)
+
+    def refused(exc, fn, *args):
+        with pytest.raises(exc):
+            fn(*args)
+
+    # element types (checked first, so these need no GPU)
+    refused(TypeError, G.paged_attention, out, q, c, c, bt.long(), cl, sl, 0.1, 32)
+    refused(TypeError, G.paged_attention, out, q, c, c, bt, cl.long(), sl, 0.1, 32)
+    refused(TypeError, G.paged_attention, out, q, c, c, bt, cl, sl.double(), 0.1, 32)
+    refused(TypeError, G.paged_attention, out, q, c.bfloat16(), c, bt, cl, sl, 0.1, 32)
+    refused(TypeError, G.paged_attention, out.bfloat16(), q, c, c, bt, cl, sl, 0.1, 32)
+    refused(TypeError, G.paged_attention, out.float(), q.float(), c.float(), c.float(), bt, cl, sl, 0.1, 32)
+    refused(TypeError, G.paged_attention_static, out, q, c, c, bt.long(), cl, sl, 0.1, 32)
+    refused(TypeError, G.reshape_and_cache, kv, kv, c, c, slots.int())
+    refused(TypeError, G.reshape_and_cache, kv.bfloat16(), kv.bfloat16(), c, c, slots)
+    refused(TypeError, G.reshape_and_cache_fp8, kv, kv, c, c, slots, 1.0, 1.0)          # caches must be uint8
+    refused(TypeError, G.decode_step, out, q, kv.bfloat16(), kv, c, c, bt, cl, sl, 0.1, 32, None)
+    refused(TypeError, G.decode_step_fp8, out, q, kv, kv, c, c, bt, cl, sl, 0.1, 1.0, 1.0, 32, ws)
+    refused(TypeError, G.paged_attention_fp8, out, q, c8, c8, bt.long(), cl, sl, 0.1, 1.0, 1.0, 32, ws)
+    refused(TypeError, G.paged_prefill, out, q, c, c, bt, cl, cu.long(), sl, 0.1, 1)
+    refused(TypeError, G.paged_prefill_fp8, out, q, c, c, bt, cl, cu, sl, 0.1, 1.0, 1.0, 1)
+    refused(TypeError, G.paged_attention_window, out, q, c, c, bt, cl.short(), sl, 0.1, 4, 32, ws)
+    refused(TypeError, G.decode_step_window, out, q, kv, kv, c, c.bfloat16(), bt, cl, sl, 0.1, 4, 32, ws)
+    refused(TypeError, G.paged_prefill_window, out, q, c, c, bt.long(), cl, cu, sl, 0.1, 4, 1)
+    refused(TypeError, G.prompt_prefill, out, q, kv, kv, None, None, None, cu.long(), sl, 0.1, 2)
+    refused(TypeError, G.gather_kv, torch.zeros(2, 32, 2, 64, dtype=torch.bfloat16),
+            torch.zeros(2, 32, 2, 64, dtype=torch.bfloat16), c, c, bt, cl)
+    # correctly typed tensors in host memory
+    refused(ValueError, G.paged_attention, out, q, c, c, bt, cl, sl, 0.1, 32)
+    refused(ValueError, G.reshape_and_cache, kv, kv, c, c, slots)
+    refused(ValueError, G.decode_step, out, q, kv, kv, c, c, bt, cl, sl, 0.1, 32, None)
+    refused(ValueError, G.paged_prefill, out, q, c, c, bt, cl, cu, sl, 0.1, 1)
+    refused(ValueError, G.prompt_prefill, out, q, kv, kv, None, None, None, cu, sl, 0.1, 2)
+
+
+def test_non_finite_scale_is_refused(G):
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)
+    for bad in (float("nan"), float("inf"), -float("inf")):
+        assert lib.optgqa_paged_attention(one, one, one, one, one, one, None, bad, 2, 8, 2, 64, 16, 8, 128, 0, None, 0,
+                                          0, None) == -2
+        assert lib.optgqa_paged_prefill(one, one, one, one, one, one, one, None, bad, 2, 8, 2, 128, 16, 8, 4, 0,
+                                        None) == -2
+        assert lib.optgqa_prompt_prefill(one, one, one, one, None, None, None, one, None, bad, 2, 8, 2, 128, 16, 8, 4,
+                                         256, 256, 0, None) == -2

@@ -17,8 +17,26 @@ def U():
         pytest.fail("GPU tests need a GPU")
     import paper_2505_02351_amd as G
     G.load_library()                       # fails loudly if the HIP library is not built
-    from paper_2505_02351_amd import testing
-    return testing
+    import harness
+    return harness
+
+
+# Full-size workloads: the stated tolerance on every element of magnitude below 4.  Heads with a steep
+# ALiBi slope (2^-0.25 per token for head 0) put most of their weight on the last one or two keys, so
+# a handful of the millions of outputs are single N(0,1) V elements beyond 4, which the 2-byte output
+# format itself rounds by more than the stated bar; harness.check_scaled bounds those by the format's
+# half-ulp plus the unchanged compute budget, and at most this fraction of the elements may be such.
+WORKLOAD_EXEMPT = 1e-4
+
+_CASES = {}
+
+
+def workload_case(name):
+    """The full-size batches take seconds to draw; tests that do not modify them share one."""
+    if name not in _CASES:
+        _CASES.clear()                      # one at a time: each holds up to 1.3 GB of cache images
+        _CASES[name] = W.make_case(W.CONFIGS[name])
+    return _CASES[name]
 
 
 def oracle_filled(O, case):
@@ -403,14 +421,17 @@ def fp8_decode(U, case, dk, dv, k_scale, v_scale, q=None):
     import paper_2505_02351_amd as G
     c = case.cfg
     qd = U.to_dev(case.q if q is None else q, case.dtype)
-    out = torch.full_like(qd, float("nan"))
+    g_out = U.Guarded(qd.numel() * qd.element_size())
+    out = g_out.view(qd.dtype, qd.shape)
+    out.fill_(float("nan"))
     n, _ = G.paged_attention_workspace_bytes(qd.shape[0], c.num_heads, c.num_kv_heads, c.head_dim, c.block_size,
                                              max(case.max_context_len, 1), G.SPLIT_BALANCED)
-    ws = torch.empty(n // 4, dtype=torch.float32, device="cuda")
+    g_ws = U.Guarded(n)
     G.paged_attention_fp8(out, qd, dk, dv, torch.from_numpy(case.block_tables).cuda(),
                           torch.from_numpy(case.context_lens).cuda(), torch.from_numpy(case.slopes).cuda(),
-                          float(case.scale), k_scale, v_scale, case.max_context_len, ws)
+                          float(case.scale), k_scale, v_scale, case.max_context_len, g_ws.view(torch.float32))
     torch.cuda.synchronize()
+    assert g_out.intact() and g_ws.intact(), "a kernel wrote outside out or the workspace"
     return U.to_host(out)
 
 
@@ -490,7 +511,7 @@ def test_fp8_every_code_through_decode_and_prefill(U, oracle, dtype):
     torch.cuda.synchronize()
     ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
                                case.slopes, case.scale, k_scale, v_scale, dtype)
-    check_scaled(U, U.to_host(out), ref, dtype, "prefill over random codes")
+    U.check_scaled(U.to_host(out), ref, dtype, "prefill over random codes")
     # decode: the last new token of every sequence as the query of a decode call
     last = case.cu_q_lens[1:] - 1
     q_dec = case.q[last]
@@ -504,7 +525,7 @@ def test_fp8_every_code_through_decode_and_prefill(U, oracle, dtype):
     torch.cuda.synchronize()
     ref_dec = O.paged_attention_e4m3(q_dec, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
                                      k_scale, v_scale, dtype)
-    check_scaled(U, U.to_host(out), ref_dec, dtype, "decode over random codes")
+    U.check_scaled(U.to_host(out), ref_dec, dtype, "decode over random codes")
     # the two clauses agree on those rows (same keys, same position)
     np.testing.assert_allclose(ref_dec, ref[last], rtol=1e-9, atol=1e-12)
 
@@ -537,23 +558,17 @@ def test_fp8_decode_edge_lengths(U, oracle, dtype):
             assert np.array_equal(got[b, h], want)
 
 
-def test_fp8_decode_workload_sampled(U, oracle):
-    """The bench's batch (C3 shapes) with 8-bit caches; the oracle evaluates sampled rows."""
+def test_fp8_decode_workload_full(U, oracle):
+    """The bench's batch (C3 shapes) with 8-bit caches, every output row against the oracle."""
     import oracle as O
-    cfg = W.CONFIGS["C3"]
-    case = W.make_case(cfg)
+    case = workload_case("C3")
     k_scale, v_scale = 0.0125, 0.0125
     kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
     assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
     got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
-    rng = np.random.default_rng(98)
-    seqs = {int(np.argmax(case.context_lens)), int(np.argmin(case.context_lens)), 0, cfg.batch - 1}
-    rows = [(b, h) for b in sorted(seqs) for h in (0, cfg.num_heads // 2 + 1, cfg.num_heads - 1)]
-    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(20)]
     ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
-                                 k_scale, v_scale, case.dtype, rows=rows)
-    sub = np.stack([got[b, h] for b, h in rows])
-    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+                                 k_scale, v_scale, case.dtype)
+    U.check_scaled(got, ref, case.dtype, "C3, E4M3 caches", max_exempt=WORKLOAD_EXEMPT)
 
 
 @pytest.mark.parametrize("i", [0, 2, 3, 4, 6, 8, 9, 10, 12])
@@ -583,16 +598,16 @@ def test_fp8_prefill(U, oracle, i):
                                case.slopes, case.scale, k_scale, v_scale, dtype)
     # (v_scale 0.02 puts V elements up to 9: rows that see one or two keys can land in [4, 8), where
     # the output's own rounding is twice the budget of the stated tolerance)
-    check_scaled(U, U.to_host(out), ref, dtype, f"fp8 prefill {i}")
+    U.check_scaled(U.to_host(out), ref, dtype, f"fp8 prefill {i}")
 
 
-def test_fp8_prefill_workload_sampled(U, oracle):
-    """The prefill workload (8 sequences, 512 new tokens after 2048 cached ones) over 8-bit caches: sampled rows."""
+def test_fp8_prefill_workload_full(U, oracle):
+    """The prefill workload (8 sequences, 512 new tokens after 2048 cached ones) over 8-bit caches,
+    every output row against the oracle."""
     import torch
     import oracle as O
     import paper_2505_02351_amd as G
-    cfg = W.CONFIGS["C5"]
-    case = W.make_case(cfg)
+    case = workload_case("C5")
     k_scale, v_scale = 0.0125, 0.0125
     kc8, vc8, dk, dv = fp8_caches(U, case, k_scale, v_scale)
     assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
@@ -602,17 +617,9 @@ def test_fp8_prefill_workload_sampled(U, oracle):
                         torch.from_numpy(case.context_lens).cuda(), torch.from_numpy(case.cu_q_lens).cuda(),
                         torch.from_numpy(case.slopes).cuda(), float(case.scale), k_scale, v_scale, case.max_q_len)
     torch.cuda.synchronize()
-    got = U.to_host(out)
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    rng = np.random.default_rng(99)
-    T = case.num_tokens
-    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (T // 2, 17)]
-    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
     ref = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
-                               case.slopes, case.scale, k_scale, v_scale, case.dtype, rows=rows)
-    sub = np.stack([got[t, h] for t, h in rows])
-    err = U.max_abs_err(sub, ref, case.dtype)
-    assert err <= U.TOL[case.dtype], err
+                               case.slopes, case.scale, k_scale, v_scale, case.dtype)
+    U.check_scaled(U.to_host(out), ref, case.dtype, "C5, E4M3 caches", max_exempt=WORKLOAD_EXEMPT)
 
 
 @pytest.mark.parametrize("i", [2, 3, 4, 5, 7, 9])
@@ -642,6 +649,7 @@ def test_fp8_decode_step_sweep(U, oracle, i):
         G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens, dev.slopes,
                           float(case.scale), k_scale, v_scale, case.max_context_len, ws)
         torch.cuda.synchronize()
+        dev.check_canaries()
     assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
     ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
                                  k_scale, v_scale, dtype)
@@ -680,6 +688,7 @@ def test_fp8_decode_step_edge_lengths(U, oracle, dtype):
     G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens, dev.slopes,
                       float(case.scale), k_scale, v_scale, case.max_context_len, ws)
     torch.cuda.synchronize()
+    dev.check_canaries()
     assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
     ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
                                  k_scale, v_scale, dtype)
@@ -769,23 +778,19 @@ def test_decode_window_edge_lengths(U, oracle, dtype):
         assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype], window
 
 
-def test_decode_window_workload_sampled(U, oracle):
-    """The decode workload (batch 64, contexts 6k..8k) with a 1024-token window: sampled rows."""
+@pytest.mark.parametrize("window", [1024, 4096])
+def test_decode_window_workload_full(U, oracle, window):
+    """The decode workload (batch 64, contexts 1k..8k) with a sliding window, cache write in the
+    same call: caches bit-exact, every output row against the oracle."""
     import oracle as O
-    cfg = W.CONFIGS["C3"]
-    case = W.make_case(cfg)
+    case = workload_case("C3")
     dev = U.DevCase(case)
-    got = dev.decode_window(1024, fused=True)
+    got = dev.decode_window(window, fused=True)
     kc, vc = oracle_filled(oracle, case)
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    rng = np.random.default_rng(7)
-    rows = [(0, 0), (cfg.batch - 1, cfg.num_heads - 1)]
-    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(60)]
     ref = O.paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens, case.slopes, case.scale,
-                                   1024, case.dtype, rows=rows)
-    sub = np.stack([got[b, h] for b, h in rows])
-    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+                                   window, case.dtype)
+    U.check_scaled(got, ref, case.dtype, f"C3, window {window}", max_exempt=WORKLOAD_EXEMPT)
 
 
 @pytest.mark.parametrize("i", range(10))
@@ -809,24 +814,17 @@ def test_prefill_window_sweep(U, oracle, i):
     assert U.max_abs_err(dev.prefill_window(20, slopes=None), ref, dtype) <= U.TOL[dtype]
 
 
-def test_prefill_window_workload_sampled(U, oracle):
-    """The prefill workload with a 512-key window: sampled rows."""
+def test_prefill_window_workload_full(U, oracle):
+    """The prefill workload with a 512-key window, every output row against the oracle."""
     import oracle as O
-    cfg = W.CONFIGS["C5"]
-    case = W.make_case(cfg)
+    case = workload_case("C5")
     dev = U.DevCase(case)
     dev.write_cache()
     kc, vc = oracle_filled(oracle, case)
     got = dev.prefill_window(512)
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    rng = np.random.default_rng(97)
-    T = case.num_tokens
-    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (513, 7), (T // 2, 17)]
-    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
     ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
-                                 case.slopes, case.scale, 512, case.dtype, rows=rows)
-    sub = np.stack([got[t, h] for t, h in rows])
-    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+                                 case.slopes, case.scale, 512, case.dtype)
+    U.check_scaled(got, ref, case.dtype, "C5, window 512", max_exempt=WORKLOAD_EXEMPT)
 
 
 @pytest.mark.parametrize("dtype", [W.F16, W.BF16])
@@ -915,9 +913,10 @@ def test_prompt_prefill_sweep(U, oracle, i):
     G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables, dev.cu_q_lens,
                      dev.slopes, float(case.scale), case.max_q_len)
     torch.cuda.synchronize()
+    dev.check_canaries()
     # (binade-aware bound: the larger cases have tens of millions of V elements, a few of them beyond
     # 4, and a row that sees one or two keys can return such a value, rounded at twice the budget)
-    check_scaled(U, U.to_host(dev.out), ref, dtype, f"prompt {i}")
+    U.check_scaled(U.to_host(dev.out), ref, dtype, f"prompt {i}")
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
     # fused QKV tensor: k and v are strided views; no caches
     T = case.num_tokens
@@ -931,7 +930,7 @@ def test_prompt_prefill_sweep(U, oracle, i):
                      case.max_q_len)
     torch.cuda.synchronize()
     ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, None, case.scale, dtype)
-    check_scaled(U, U.to_host(dev.out), ref, dtype, f"prompt {i}, fused input")
+    U.check_scaled(U.to_host(dev.out), ref, dtype, f"prompt {i}, fused input")
 
 
 def test_prompt_prefill_then_decode(U, oracle):
@@ -958,30 +957,25 @@ def test_prompt_prefill_then_decode(U, oracle):
     assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
 
 
-def test_prompt_prefill_workload_sampled(U, oracle):
-    """Eight prompts of 2560 tokens at the prefill workload's head shapes: sampled rows, caches bit-exact."""
+def test_prompt_prefill_workload_full(U, oracle):
+    """Eight prompts of 2560 tokens at the prefill workload's head shapes: caches bit-exact, every
+    output row against the oracle.  (Rows 1 and 2 of a prompt see two or three keys, so an output can
+    exceed magnitude 4: the bound follows the output type's own rounding there and only there.)"""
     import torch
     import oracle as O
     import paper_2505_02351_amd as G
-    case = W.make_case(W.CONFIGS["C5-prompt"])
-    cfg = case.cfg
+    case = workload_case("C5-prompt")
     dev = U.DevCase(case)
     dev.out.fill_(float("nan"))
     G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables, dev.cu_q_lens,
                      dev.slopes, float(case.scale), case.max_q_len)
     torch.cuda.synchronize()
+    dev.check_canaries()
     got = U.to_host(dev.out)
     kc, vc = oracle_filled(oracle, case)
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    rng = np.random.default_rng(96)
-    T = case.num_tokens
-    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (2559, 5), (2560, 6), (T // 2, 17)]
-    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
-    ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, case.dtype,
-                             rows=rows)
-    sub = np.stack([got[t, h] for t, h in rows])
-    assert U.max_abs_err(sub, ref, case.dtype) <= U.TOL[case.dtype]
+    ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, case.dtype)
+    U.check_scaled(got, ref, case.dtype, "C5-prompt", max_exempt=WORKLOAD_EXEMPT)
 
 
 def test_prompt_prefill_rejects_what_it_cannot_do(U):
@@ -1040,19 +1034,6 @@ def test_prefill_with_a_sequence_without_new_tokens(U, oracle):
 
 
 # ------------------------------------------------------------------ seeded random mixes
-def check_scaled(U, got, ref, dtype, tag):
-    """The stated tolerances budget one output rounding at magnitudes below 4 (half an ulp there:
-    7.8e-3 bf16, 9.8e-4 fp16).  Random mixes also produce the odd output of magnitude 4 .. 8 (a row
-    that sees one or two keys with a large V element), whose own rounding is twice that: the bound
-    doubles with every binade beyond [2, 4), and only there."""
-    g = W.from_bits(got, dtype)
-    assert np.all(np.isfinite(g)), f"{tag}: non-finite values in the GPU output"
-    binade = np.floor(np.log2(np.maximum(np.abs(ref), 2.0)))        # 1 for |ref| < 4, 2 for [4, 8), ...
-    err = np.abs(g - ref) / np.exp2(binade - 1.0)
-    i = np.unravel_index(np.argmax(err), err.shape)
-    assert err[i] <= U.TOL[dtype], f"{tag}: |{g[i]} - {ref[i]}| = {abs(g[i] - ref[i])} at {i}"
-
-
 def test_random_mix_of_decode_calls(U, oracle):
     """Forty seeded random decode batches (head counts, group sizes, block sizes, ragged lengths incl.
     empty sequences) through a randomly chosen entry point each: plain attention with a random split,
@@ -1116,13 +1097,14 @@ def test_random_mix_of_decode_calls(U, oracle):
                 G.decode_step_fp8(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens,
                                   dev.slopes, float(case.scale), k_scale, v_scale, case.max_context_len, ws)
                 torch.cuda.synchronize()
+                dev.check_canaries()
                 assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8), tag
                 got = U.to_host(dev.out)
             else:
                 got = fp8_decode(U, case, dk, dv, k_scale, v_scale)
             ref = O.paged_attention_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes,
                                          case.scale, k_scale, v_scale, dtype)
-        check_scaled(U, got, ref, dtype, tag)
+        U.check_scaled(got, ref, dtype, tag)
 
 
 def test_random_mix_of_prefill_calls(U, oracle):
@@ -1182,7 +1164,7 @@ def test_random_mix_of_prefill_calls(U, oracle):
             got = U.to_host(dev.out)
             assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), tag
             ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale, dtype)
-        check_scaled(U, got, ref, dtype, tag)
+        U.check_scaled(got, ref, dtype, tag)
 
 
 def test_decode_step_replays_from_a_hip_graph(U, oracle):
@@ -1234,48 +1216,33 @@ def test_stream_probe_runs_and_checks_its_list(U):
 
 
 # ------------------------------------------------------------------ the workloads themselves
-@pytest.mark.parametrize("name", ["C1", "C2"])
-def test_decode_workload_full(U, oracle, name):
-    case = W.make_case(W.CONFIGS[name])
+WORKLOAD_RUNS = [
+    ("C1", 0), ("C1", -1), ("C2", 0), ("C2", -1), ("C2", "step"),
+    ("C3", 0), ("C3", 1024), ("C3", "step"),          # "step": optgqa_decode_step, the call the bench times
+    ("C3-all8k", "step"),                              # the "batch 64 / 8k" upper case of the target
+    ("C4", 512), ("C4", BALANCED), ("C4", "step"),     # 512: the configuration's own partition size
+]
+
+
+@pytest.mark.parametrize("name,mode", WORKLOAD_RUNS)
+def test_decode_workload_full(U, oracle, name, mode):
+    """Every decode workload at full size, in the launch configuration the bench times and in the
+    other split modes: the ENTIRE caches bit for bit after the cache write, and every output row
+    against the oracle at the stated tolerance."""
+    case = workload_case(name)
+    cfg = case.cfg
+    if mode == 512:
+        assert cfg.partition_size == 512
     dev = U.DevCase(case)
-    dev.write_cache()
+    if mode == "step":
+        got = dev.step()
+    else:
+        dev.write_cache()
+        got = dev.decode(partition_size=mode)
     kc, vc = oracle_filled(oracle, case)
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
     ref = oracle_decode(oracle, case, kc, vc)
-    for partition in (0, -1):
-        got = dev.decode(partition_size=partition)
-        err = U.max_abs_err(got, ref, case.dtype)
-        assert err <= U.TOL[case.dtype], (name, partition, err)
-
-
-@pytest.mark.parametrize("name,partition", [("C3", None), ("C4", None), ("C4", BALANCED), ("C3", 1024), ("C3", "step")])
-def test_decode_workload_sampled(U, oracle, name, partition):
-    """Full-size batch in the launch configuration the bench times (and in the other split mode);
-    the oracle evaluates a sample of (sequence, head) rows one by one, chosen to include the
-    longest and shortest sequences."""
-    cfg = W.CONFIGS[name]
-    case = W.make_case(cfg)
-    dev = U.DevCase(case)
-    dev.write_cache()
-    if partition == "step":
-        dev = U.DevCase(case)           # caches still without the new tokens
-        got = dev.step()
-    else:
-        got = dev.decode(partition_size=cfg.partition_size if partition is None else partition)
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    kc, vc = oracle_filled(oracle, case)
-    rng = np.random.default_rng(99)
-    seqs = {int(np.argmax(case.context_lens)), int(np.argmin(case.context_lens)), 0, cfg.batch - 1}
-    rows = [(b, h) for b in sorted(seqs) for h in (0, cfg.num_heads // 2 + 1, cfg.num_heads - 1)]
-    rows += [(int(rng.integers(cfg.batch)), int(rng.integers(cfg.num_heads))) for _ in range(20)]
-    ref = oracle_decode(oracle, case, kc, vc, rows=rows)
-    sub = np.stack([got[b, h] for b, h in rows])
-    err = U.max_abs_err(sub, ref, case.dtype)
-    assert err <= U.TOL[case.dtype], (name, err)
-    # the new tokens' cache rows were written bit-exactly
-    for b in range(cfg.batch):
-        s = int(case.slot_mapping[b])
-        assert np.array_equal(U.to_host(dev.k_cache[s // cfg.block_size, :, s % cfg.block_size]), case.k_new[b])
+    U.check_scaled(got, ref, case.dtype, f"{name}, mode {mode}", max_exempt=WORKLOAD_EXEMPT)
 
 
 # ------------------------------------------------------------------ prefill
@@ -1310,24 +1277,66 @@ def test_prefill_sweep(U, oracle, i):
     kc, vc = oracle_filled(oracle, case)
     ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
                                case.slopes, case.scale, dtype)
-    check_scaled(U, got, ref, dtype, f"prefill {i}")
+    U.check_scaled(got, ref, dtype, f"prefill {i}")
 
 
-def test_prefill_workload_sampled(U, oracle):
-    cfg = W.CONFIGS["C5"]
-    case = W.make_case(cfg)
+@pytest.mark.parametrize("scale", [0.0, 1e-30, -0.05])
+def test_prefill_with_zero_tiny_and_negative_scale(U, oracle, scale):
+    """The tiled kernel carries part of the ALiBi term inside the score accumulator as slope / scale;
+    a score scale of zero (bias-only softmax), a vanishing one and a negative one must still give
+    what eq. (3), (4) give, through the paged, windowed and whole-prompt entry points."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    for dtype in (W.F16, W.BF16):
+        cfg = W.small_config(name="pf_scale", kind="prefill", dtype=dtype, batch=2, num_heads=8, num_kv_heads=2,
+                             head_dim=128, block_size=16, num_blocks=50, ctx_lo=100, ctx_hi=300, q_len=300,
+                             seed=2300)
+        case = W.make_case(cfg)
+        kc, vc = oracle_filled(oracle, case)
+        dev = U.DevCase(case)
+        dev.write_cache()
+        ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                   case.slopes, scale, dtype)
+        dev.out.fill_(float("nan"))
+        G.paged_prefill(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens, dev.cu_q_lens,
+                        dev.slopes, scale, case.max_q_len)
+        torch.cuda.synchronize()
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"paged prefill, scale {scale}")
+        dev.out.fill_(float("nan"))
+        G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, None, None, None, dev.cu_q_lens, dev.slopes, scale,
+                         case.max_q_len)
+        torch.cuda.synchronize()
+        ref = O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, scale, dtype)
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"whole prompt, scale {scale}")
+        dev.out.fill_(float("nan"))
+        G.paged_prefill_window(dev.out, dev.q, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens,
+                               dev.cu_q_lens, dev.slopes, scale, 40, case.max_q_len)
+        torch.cuda.synchronize()
+        ref = O.paged_prefill_window(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                     case.slopes, scale, 40, dtype)
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"windowed prefill, scale {scale}")
+        dev.check_canaries()
+        # decode takes the same scales
+        last = case.cu_q_lens[1:] - 1
+        qd = dev.q[torch.from_numpy(last.astype(np.int64)).cuda()].contiguous()
+        out = torch.full_like(qd, float("nan"))
+        G.paged_attention(out, qd, dev.k_cache, dev.v_cache, dev.block_tables, dev.context_lens, dev.slopes, scale,
+                          case.max_context_len, -1, None)
+        torch.cuda.synchronize()
+        ref = oracle.paged_attention(case.q[last], kc, vc, case.block_tables, case.context_lens, case.slopes, scale,
+                                     dtype)
+        U.check_scaled(U.to_host(out), ref, dtype, f"decode, scale {scale}")
+
+
+def test_prefill_workload_full(U, oracle):
+    """C5 at full size: caches bit-exact, all 4096 x 32 output rows against the oracle."""
+    case = workload_case("C5")
     dev = U.DevCase(case)
     dev.write_cache()
     kc, vc = oracle_filled(oracle, case)
     assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
     got = dev.prefill()
-    assert np.all(np.isfinite(W.from_bits(got, case.dtype)))
-    rng = np.random.default_rng(98)
-    T = case.num_tokens
-    rows = [(0, 0), (T - 1, cfg.num_heads - 1), (511, 5), (512, 6), (T // 2, 17)]
-    rows += [(int(rng.integers(T)), int(rng.integers(cfg.num_heads))) for _ in range(40)]
     ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
-                               case.slopes, case.scale, case.dtype, rows=rows)
-    sub = np.stack([got[t, h] for t, h in rows])
-    err = U.max_abs_err(sub, ref, case.dtype)
-    assert err <= U.TOL[case.dtype], err
+                               case.slopes, case.scale, case.dtype)
+    U.check_scaled(got, ref, case.dtype, "C5", max_exempt=WORKLOAD_EXEMPT)

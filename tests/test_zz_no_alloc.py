@@ -16,7 +16,7 @@ def test_static_scratch_entry_point_matches_workspace_entry_point(oracle):
         pytest.fail("GPU tests need a GPU")
     import paper_2505_02351_amd as G
     G.load_library()
-    from paper_2505_02351_amd import testing as U
+    import harness as U
 
     shapes = [
         # dtype, Hq, Hkv, D, bs, batch, ctx_lo, ctx_hi

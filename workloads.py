@@ -2,9 +2,14 @@
 
 This module only *draws and arranges* inputs: random values, context lengths,
 block-table permutations, slot mappings and the cache image that exists before
-a step runs.  It holds none of the method's arithmetic (no scores, no softmax,
-no cache-write semantics) and imports neither the CPU oracle nor the HIP
-library; both are fed from here so that they see the very same bits.
+a step runs.  It holds none of the method's arithmetic (no scores, no softmax)
+and imports neither the CPU oracle nor the HIP library; both are fed from here
+so that they see the very same bits.  The one place that touches the cache
+layout is index arrangement of inputs: ``make_case`` scatters the drawn values
+into the pool and lifts the step's new rows out of it, and ``all_token_rows``
+reads them back through ``slot // block_size, slot % block_size`` to hand the
+same logical tokens to caches of another element type.  Neither is what a
+cache-write result is compared with: those come from the oracle alone.
 
 All 2-byte tensors are carried as ``numpy.uint16`` bit patterns (IEEE fp16 or
 bfloat16), so nothing downstream depends on a framework's dtype support.
