@@ -75,6 +75,9 @@ def parse():
                     help="> 1: runs of GROUP consecutive sequences share 90 %% of their common cached length "
                          "through the same physical blocks (decode workloads); rates still count every "
                          "sequence's logical KV bytes")
+    ap.add_argument("--shared-prefix-kernel", choices=["bundled", "plain"], default="bundled",
+                    help="with --shared-prefix: bundled = optgqa_decode_step_shared (a bundle of sequences reads "
+                         "its shared blocks once); plain = optgqa_decode_step on the same aliased tables")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache pass (evict, then time each step)")
     ap.add_argument("--cpu-sample-seqs", type=int, default=0,
                     help="sequences of the batch the CPU oracle is timed on (0 = all)")
@@ -229,6 +232,7 @@ def main():
         if args.shared_prefix > 1:
             assert cfg.kind == "decode", "--shared-prefix applies to decode workloads"
             shared_tokens = W.share_prefix_blocks(case, args.shared_prefix, 0.9)
+        bundled = shared_tokens > 0 and args.shared_prefix_kernel == "bundled"
         from harness import DevCase
         dev = DevCase(case)
         P = cfg.partition_size if args.partition_size is None else args.partition_size
@@ -259,6 +263,21 @@ def main():
             if decode:
                 ws, chosen_P = dev.workspace(G.SPLIT_BALANCED)
         one_call = decode and (P == 0 or window or e4m3)
+        bundle_read_tokens = 0
+        if bundled:
+            assert not (e4m3 or window) and P == 0, "--shared-prefix-kernel bundled: 2-byte caches, no window, library's split"
+            bundle = G.shared_prefix_bundle(cfg.num_heads, cfg.num_kv_heads, cfg.head_dim)
+            shared_host = W.bundle_shared_blocks(case, bundle)
+            assert G.validate_shared_prefix_host(case.block_tables, case.context_lens, shared_host, cfg.block_size,
+                                                 bundle, 1) == 0
+            shared_dev = torch.from_numpy(shared_host).cuda()
+            ws = dev.shared_workspace()
+            chosen_P = G.SPLIT_BALANCED
+            # tokens a bundle reads once instead of once per sharing member
+            for b0 in range(0, cfg.batch, bundle):
+                members = [b for b in range(b0 + 1, min(b0 + bundle, cfg.batch)) if shared_host[b] > 0]
+                if members:
+                    bundle_read_tokens += len(members) * int(min(shared_host[b] for b in members)) * cfg.block_size
 
         prompt = cfg.name.endswith("-prompt")       # whole prompts, caches empty: one call stores K/V and attends
         assert not (prompt and (e4m3 or window)), "the whole-prompt workload runs over 2-byte inputs, full causal mask"
@@ -276,6 +295,10 @@ def main():
                 G.reshape_and_cache_fp8(dev.k_new, dev.v_new, k8, v8, dev.slot_mapping, KV_SCALE, KV_SCALE, stream)
                 G.paged_prefill_fp8(dev.out, dev.q, k8, v8, dev.block_tables, dev.context_lens, dev.cu_q_lens,
                                     dev.slopes, scale, KV_SCALE, KV_SCALE, case.max_q_len, stream)
+                return
+            if bundled:
+                G.decode_step_shared(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                                     dev.context_lens, shared_dev, dev.slopes, scale, max_ctx, ws, stream)
                 return
             if one_call and window:
                 G.decode_step_window(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache,
@@ -442,7 +465,10 @@ def main():
                        "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype,
                        **({"window": window} if window else {}),
                        **({"shared_prefix_group": args.shared_prefix,
-                           "aliased_context_tokens": int(shared_tokens)} if shared_tokens else {})},
+                           "aliased_context_tokens": int(shared_tokens),
+                           "shared_prefix_kernel": args.shared_prefix_kernel,
+                           "kv_bytes_read_once_per_bundle": int(kv_bytes - 2 * bundle_read_tokens * cfg.num_kv_heads
+                                                                * cfg.head_dim * 2)} if shared_tokens else {})},
             "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
             "query_tokens_per_s": n_q / (ms_per_step * 1e-3),
             "roofline": roofline,
@@ -451,8 +477,10 @@ def main():
             result["cold_step"] = cold
         if shared_tokens:
             result["roofline"]["note"] = ("algorithmic bytes count every sequence's logical KV; %d of %d context "
-                                          "tokens alias another sequence's blocks and may be served by the "
-                                          "last-level cache: not an HBM rate" % (shared_tokens, int(case.context_lens.sum())))
+                                          "tokens alias another sequence's blocks (%s): not an HBM rate"
+                                          % (shared_tokens, int(case.context_lens.sum()),
+                                             "the bundled kernel reads a bundle's shared blocks once" if bundled
+                                             else "the plain kernel reads them once per sequence"))
         result["cache_write"] = cache_write
         if stream_probe:
             result["stream_probe"] = stream_probe

@@ -328,6 +328,64 @@ int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, c
                                 int max_q_len, optgqa_dtype dtype, void *stream);
 
 /*
+ * Shared prefixes (Section III-B: cached key-value blocks are shared and reused across requests;
+ * the paper gives no interface - this is the one built here).  Sequences that start with the same
+ * prompt carry the same physical block ids in the leading entries of their block tables.  The
+ * plain entry points already accept such tables (they read the shared blocks once per sequence);
+ * these two read them once per BUNDLE of sequences, batching the bundle's queries against each
+ * shared K/V tile - the score matrix instruction has 16 query-head columns, a KV head's group
+ * fills num_heads / num_kv_heads of them (or the largest divisor <= 16), and the other columns
+ * carry the other members' heads at no extra matrix or vector work.
+ *
+ *   bundle        = optgqa_shared_prefix_bundle(...): sequences per bundle (16 / heads per pass:
+ *                   2 for a group of 8, 4 for a group of 4, 16 for multi-head attention).
+ *                   Bundles are aligned runs of consecutive sequences: the bundle of sequence b is
+ *                   led by sequence b0 = b - b % bundle.  The caller (its scheduler) orders the
+ *                   batch so that sequences with a common prefix are neighbours.
+ *   shared_blocks   [num_seqs] int32, device.  shared_blocks[b] = n > 0: the first n block-table
+ *                   entries of sequence b equal the leader's, every one of those blocks is full
+ *                   and already cached for both (never the block that receives a new token);
+ *                   0: b shares nothing (always 0 for a leader).  Per bundle the kernel reads
+ *                   min over its sharing members of those prefixes once, for all of them, and the
+ *                   rest of every sequence as the plain entry points do.  Contents that break
+ *                   these rules are undefined behaviour, as for the other device tables;
+ *                   optgqa_validate_shared_prefix_host checks host copies (new_tokens = 1 before a
+ *                   decode step whose token is counted in context_lens but not yet cached, else 0).
+ *   workspace       required: optgqa_shared_prefix_workspace_bytes(...) bytes (always the
+ *                   equal-work split; OPTGQA_ERR_WORKSPACE without it).
+ * head_dim 128, 2-byte caches, no window (OPTGQA_ERR_UNSUPPORTED otherwise).  Results: what
+ * optgqa_paged_attention / optgqa_decode_step give on the same tables, to rounding (the
+ * definition does not know about sharing: eq. (3), (4) over the tokens the tables name).
+ */
+int optgqa_shared_prefix_bundle(int num_heads, int num_kv_heads, int head_dim);
+
+size_t optgqa_shared_prefix_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                                            int block_size, int max_context_len);
+
+int optgqa_paged_attention_shared(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                  const int32_t *block_tables, const int32_t *context_lens,
+                                  const int32_t *shared_blocks, const float *alibi_slopes, float scale,
+                                  int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                                  int block_size, int max_blocks_per_seq, int max_context_len,
+                                  void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                                  void *stream);
+
+int optgqa_decode_step_shared(void *out, const void *q, const void *k_new, const void *v_new,
+                              void *k_cache, void *v_cache, const int32_t *block_tables,
+                              const int32_t *context_lens, const int32_t *shared_blocks,
+                              const float *alibi_slopes, float scale, int num_seqs, int num_heads,
+                              int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                              int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
+                              void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                              void *stream);
+
+int optgqa_validate_shared_prefix_host(const int32_t *block_tables_host,
+                                       const int32_t *context_lens_host,
+                                       const int32_t *shared_blocks_host, int num_seqs,
+                                       int max_blocks_per_seq, int block_size, int bundle,
+                                       int new_tokens);
+
+/*
  * Whole-prompt attention with empty caches (Alg. 1, prompt branch: "Reshape and store K, V into
  * C_K, C_V", then causal / ALiBi attention computed on the inputs themselves).  Sequence b owns
  * tokens cu_seq_lens[b] .. cu_seq_lens[b+1] - 1 of q, k, v; token i of a sequence attends to

@@ -57,6 +57,18 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_attention_static.restype = i32
     lib.optgqa_paged_attention_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                                   i32, vp]
+    lib.optgqa_shared_prefix_bundle.restype = i32
+    lib.optgqa_shared_prefix_bundle.argtypes = [i32, i32, i32]
+    lib.optgqa_shared_prefix_workspace_bytes.restype = sz
+    lib.optgqa_shared_prefix_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+    lib.optgqa_paged_attention_shared.restype = i32
+    lib.optgqa_paged_attention_shared.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32,
+                                                  i32, vp, sz, i32, vp]
+    lib.optgqa_decode_step_shared.restype = i32
+    lib.optgqa_decode_step_shared.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32,
+                                              i32, i32, i64, i64, vp, sz, i32, vp]
+    lib.optgqa_validate_shared_prefix_host.restype = i32
+    lib.optgqa_validate_shared_prefix_host.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32]
     lib.optgqa_set_kernel_events.restype = i32
     lib.optgqa_set_kernel_events.argtypes = [vp, vp]
     lib.optgqa_decode_step.restype = i32
@@ -255,6 +267,89 @@ def paged_attention_static(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Te
                                            int(block_tables.shape[1]), int(max_context_len), _dtype_code(q),
                                            _stream(stream))
     _check(rc, "optgqa_paged_attention_static")
+
+
+def shared_prefix_bundle(num_heads: int, num_kv_heads: int, head_dim: int) -> int:
+    """optgqa_shared_prefix_bundle: sequences whose heads share one pass over a shared K/V tile."""
+    m = int(load_library().optgqa_shared_prefix_bundle(num_heads, num_kv_heads, head_dim))
+    if m <= 0:
+        raise OptGqaError(m, "optgqa_shared_prefix_bundle")
+    return m
+
+
+def shared_prefix_workspace_bytes(num_seqs: int, num_heads: int, num_kv_heads: int, head_dim: int, block_size: int,
+                                  max_context_len: int) -> int:
+    """optgqa_shared_prefix_workspace_bytes."""
+    return int(load_library().optgqa_shared_prefix_workspace_bytes(num_seqs, num_heads, num_kv_heads, head_dim,
+                                                                   block_size, max_context_len))
+
+
+def paged_attention_shared(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                           block_tables: torch.Tensor, context_lens: torch.Tensor, shared_blocks: torch.Tensor,
+                           alibi_slopes: Optional[torch.Tensor], scale: float, max_context_len: int,
+                           workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_paged_attention_shared: decode attention that reads a bundle's shared prefix blocks once."""
+    lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes)
+    _typed(q, i32=[("shared_blocks", shared_blocks)])
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape or shared_blocks.shape != (B,):
+        raise ValueError("optgqa: shape mismatch between q, out, shared_blocks and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (shared_blocks, "shared_blocks")):
+        _dense(t, n)
+    ws_bytes = _workspace(workspace, q)
+    rc = lib.optgqa_paged_attention_shared(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                           _ptr(context_lens), _ptr(shared_blocks), _ptr(alibi_slopes), float(scale),
+                                           B, Hq, Hkv, D, bs, int(block_tables.shape[1]), int(max_context_len),
+                                           _ptr(workspace), ws_bytes, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_attention_shared")
+
+
+def decode_step_shared(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                       k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                       context_lens: torch.Tensor, shared_blocks: torch.Tensor,
+                       alibi_slopes: Optional[torch.Tensor], scale: float, max_context_len: int,
+                       workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_decode_step_shared: the step's cache write and decode attention, shared prefix blocks
+    read once per bundle of sequences."""
+    lib = load_library()
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, new=(k_new, v_new))
+    _typed(q, i32=[("shared_blocks", shared_blocks)])
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if (Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D)
+            or shared_blocks.shape != (B,)):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows, shared_blocks and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (shared_blocks, "shared_blocks")):
+        _dense(t, n)
+    if B and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if B else Hkv * D
+    vs = int(v_new.stride(0)) if B else Hkv * D
+    ws_bytes = _workspace(workspace, q)
+    rc = lib.optgqa_decode_step_shared(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(block_tables), _ptr(context_lens), _ptr(shared_blocks),
+                                       _ptr(alibi_slopes), float(scale), B, Hq, Hkv, D, bs,
+                                       int(block_tables.shape[1]), int(max_context_len), ks, vs, _ptr(workspace),
+                                       ws_bytes, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_decode_step_shared")
+
+
+def validate_shared_prefix_host(block_tables, context_lens, shared_blocks, block_size: int, bundle: int,
+                                new_tokens: int) -> int:
+    """optgqa_validate_shared_prefix_host on host numpy int32 arrays; returns the status code."""
+    import numpy as np
+    lib = load_library()
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    cl = np.ascontiguousarray(context_lens, dtype=np.int32)
+    sb = np.ascontiguousarray(shared_blocks, dtype=np.int32)
+    return int(lib.optgqa_validate_shared_prefix_host(bt.ctypes.data_as(ctypes.c_void_p),
+                                                      cl.ctypes.data_as(ctypes.c_void_p),
+                                                      sb.ctypes.data_as(ctypes.c_void_p), int(cl.shape[0]),
+                                                      int(bt.shape[1]), int(block_size), int(bundle), int(new_tokens)))
 
 
 def set_kernel_events(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:

@@ -96,6 +96,87 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
     return x;
 }
 
+// ---- shared prefixes (Section III-B: cached key-value blocks are shared and reused) --------------
+// Sequences whose block tables start with the same physical blocks (a common prompt) need those
+// blocks read only once if their queries are batched against the shared tiles.  The score MFMA has
+// 16 query-head columns and a KV head's group fills GH of them, so `bundle` = 16 / GH sequences ride
+// through one pass: sequences come in aligned bundles of that many consecutive ones, led by
+// sequence b0 = b - b % bundle, and shared_blocks[b] > 0 says that the first shared_blocks[b]
+// block-table entries of b are the leader's.  The bundle's shared prefix is the part EVERY taking-part
+// member shares: S tokens, a multiple of 16, never beyond any member's cached tokens.
+//
+// The flat order then runs over 2 * num_seqs "virtual sequences": v = 2b is the shared prefix of
+// the bundle that b leads (tokens 0 .. S-1 through the leader's table, all members' heads in the
+// columns; no tiles unless b is a leader with S > 0), v = 2b + 1 is what b reads alone (tokens S ..,
+// or 0 .. if b shares nothing, and its new token's tile in the fused step).  Slots, plan entries
+// and the staircase are indexed by v instead of b; every slot holds 16 columns.
+template <bool UNIFORM> __device__ __forceinline__ int flat_ld(const int32_t* ptr)
+{
+    // wave-uniform addresses inside the streaming loop go through the scalar cache: a vector load
+    // would make the wave wait for every tile load still in flight
+    if constexpr (UNIFORM) return scalar_load_i32(ptr);
+    else return *ptr;
+}
+
+template <bool UNIFORM>
+__device__ __forceinline__ int shared_prefix_tokens(const DecodeParams& p, int b0, int fused)
+{
+    const int L0 = flat_ld<UNIFORM>(p.context_lens + b0);
+    int S = 0x7fffffff;
+    bool any = false;
+    for (int i = 1; i < p.bundle && b0 + i < p.num_seqs; ++i) {
+        const int s = flat_ld<UNIFORM>(p.shared_blocks + b0 + i), Li = flat_ld<UNIFORM>(p.context_lens + b0 + i);
+        if (s > 0 && Li > 0) {
+            any = true;
+            S = min(S, min(s * p.block_size, Li - fused));
+        }
+    }
+    if (!any || L0 <= 0) return 0;
+    return max(min(S, L0 - fused), 0) & ~(kMmaTile - 1);
+}
+
+// What the segments of one (virtual) sequence cover: cached tokens [lo, hi) read through the block
+// table of sequence tb, plus - fused step over 2-byte caches, not for a shared prefix - a last tile
+// that is the new token of sequence b alone.  n = tiles per segment.
+struct FlatSeg {
+    int b, tb, L, lo, hi, n;
+    int shared;             // (an int: a struct with padding bytes does not stay in registers)
+};
+
+template <bool FUSED, bool KV8, bool SHARED, bool UNIFORM>
+__device__ __forceinline__ FlatSeg flat_seg(const DecodeParams& p, int v)
+{
+    FlatSeg s;
+    if constexpr (!SHARED) {
+        s.b = s.tb = v;
+        s.L = flat_ld<UNIFORM>(p.context_lens + v);
+        s.lo = flat_first_token(s.L, p.window);
+        s.hi = FUSED ? s.L - 1 : s.L;
+        s.shared = 0;
+        s.n = flat_tiles<FUSED, KV8>(s.L, p.window);
+    } else {
+        const int b = v >> 1;
+        const int b0 = b - b % p.bundle;
+        const int S = shared_prefix_tokens<UNIFORM>(p, b0, FUSED ? 1 : 0);
+        s.b = b;
+        s.L = flat_ld<UNIFORM>(p.context_lens + b);
+        s.shared = (v & 1) == 0 ? 1 : 0;
+        if (s.shared) {
+            s.tb = b0;
+            s.lo = 0;
+            s.hi = b == b0 ? S : 0;
+            s.n = s.hi / kMmaTile;
+        } else {
+            const bool takes_part = S > 0 && (b == b0 || flat_ld<UNIFORM>(p.shared_blocks + b) > 0);
+            s.tb = b;
+            s.lo = takes_part ? S : 0;
+            s.hi = FUSED ? s.L - 1 : s.L;
+            s.n = s.L <= 0 ? 0 : (s.hi > s.lo ? (s.hi + kMmaTile - 1) / kMmaTile - s.lo / kMmaTile : 0) + (FUSED && !KV8 ? 1 : 0);
+        }
+    }
+    return s;
+}
+
 //
 // FUSED: the kernel also performs the step's cache write (Alg. 2 stores the new K/V, then attends
 // over the cache).  The new token of sequence b is its last one; it is given a tile of its own at
@@ -110,14 +191,17 @@ __device__ __forceinline__ int wave_inclusive_scan(int x, int lane)
 // 16-byte K piece holds 16 consecutive dims and feeds two score MFMAs after widening to DT
 // (exact: every E4M3 value is an fp16 and a bf16 number), a lane's 8-byte V piece widens to 8 DT
 // values on its way into the LDS copy.  Not combined with FUSED.
+//
+// SHARED: shared prefixes are read once per bundle of sequences (above).  2-byte caches, no window.
 struct MmaTile8 {
     uint4 k[2];     // K: token j16, dims 64j + 16hg .. +15
     uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
 };
 
-template <int DT, bool FUSED, bool KV8 = false>
+template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
+    static_assert(!(SHARED && KV8), "shared prefixes: 2-byte caches");
     constexpr bool NEW_TILE = FUSED && !KV8;            // the new token is a tile of its own, read from k_new / v_new
     typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
@@ -134,22 +218,28 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const int hg = lane >> 4;
 
     const int B = p.num_seqs, Y = p.segs_per_seq;
+    const int NV = SHARED ? 2 * B : B;                  // (virtual) sequences of the flat order
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
     const int GH = p.heads_per_wg;
     const int G = Hq / Hkv;
     const int chunks = G / GH;
+    const int CS = SHARED ? 16 : GH;                    // columns (query heads) per partial-result slot
     const int u = blockIdx.x * kDecodeWaves + wave;
     const int32_t* __restrict__ ctx = p.context_lens;
     const int W = p.window;
 
     // ---- where does this unit start?  level 1: lane i sums the tiles of sequences [i*k, (i+1)*k)
-    const int k = (B + 63) >> 6;
+    const int k = (NV + 63) >> 6;
     int mine = 0, my_len = 0;
     for (int i = 0; i < k; ++i) {
         const int idx = lane * k + i;
-        my_len = idx < B ? ctx[idx] : 0;
-        mine += flat_tiles<FUSED, KV8>(my_len, W);
+        if constexpr (SHARED) {
+            if (idx < NV) mine += flat_seg<FUSED, KV8, true, false>(p, idx).n;
+        } else {
+            my_len = idx < B ? ctx[idx] : 0;
+            mine += flat_tiles<FUSED, KV8>(my_len, W);
+        }
     }
     const int incl = wave_inclusive_scan(mine, lane);
     const int P_total = __builtin_amdgcn_readlane(incl, 63);
@@ -161,38 +251,50 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 
     // the lane whose chunk holds flat tile f0: the last one whose chunk starts at or before it
     const int cl = __builtin_popcountll(__builtin_amdgcn_ballot_w64(Y * (incl - mine) <= f0)) - 1;
-    int b = cl * k;
-    int P_b = __builtin_amdgcn_readlane(incl - mine, cl);
-    int n, L;                                               // tiles per segment / length of sequence b
+    int v = cl * k;                                         // (virtual) sequence of the piece at hand
+    int P_v = __builtin_amdgcn_readlane(incl - mine, cl);
+    FlatSeg seg;
     if (k == 1) {
-        n = __builtin_amdgcn_readlane(mine, cl);
-        L = __builtin_amdgcn_readlane(my_len, cl);
+        if constexpr (SHARED) {
+            seg = flat_seg<FUSED, KV8, true, true>(p, v);
+        } else {
+            seg.b = seg.tb = v;
+            seg.n = __builtin_amdgcn_readlane(mine, cl);
+            seg.L = __builtin_amdgcn_readlane(my_len, cl);
+            seg.lo = flat_first_token(seg.L, W);
+            seg.hi = FUSED ? seg.L - 1 : seg.L;
+            seg.shared = 0;
+        }
     } else {
         // level 2: the k sequences of that chunk, 64 at a time
-        n = 0;
-        L = 0;
+        int n = 0;
         for (int base = 0; base < k; base += 64) {
             const int idx = cl * k + base + lane;
-            const int nl = flat_tiles<FUSED, KV8>(base + lane < k && idx < B ? ctx[idx] : 0, W);
+            const bool in = base + lane < k && idx < NV;
+            int nl;
+            if constexpr (SHARED) nl = in ? flat_seg<FUSED, KV8, true, false>(p, idx).n : 0;
+            else nl = flat_tiles<FUSED, KV8>(in ? ctx[idx] : 0, W);
             const int inc2 = wave_inclusive_scan(nl, lane);
             const int tot = __builtin_amdgcn_readlane(inc2, 63);
-            if (Y * (P_b + tot) > f0) {
-                const int x = __builtin_popcountll(__builtin_amdgcn_ballot_w64(Y * (P_b + inc2 - nl) <= f0)) - 1;
-                P_b += __builtin_amdgcn_readlane(inc2 - nl, x);
+            if (Y * (P_v + tot) > f0) {
+                const int x = __builtin_popcountll(__builtin_amdgcn_ballot_w64(Y * (P_v + inc2 - nl) <= f0)) - 1;
+                P_v += __builtin_amdgcn_readlane(inc2 - nl, x);
                 n = __builtin_amdgcn_readlane(nl, x);
-                b = cl * k + base + x;
-                L = __builtin_amdgcn_readfirstlane(ctx[b]);
+                v = cl * k + base + x;
                 break;
             }
-            P_b += tot;
+            P_v += tot;
         }
         if (n <= 0) return;                                 // cannot happen for consistent lengths
+        seg = flat_seg<FUSED, KV8, SHARED, true>(p, v);
+        if (seg.n != n) return;                             // the lengths changed under the kernel
     }
+    if (seg.n <= 0) return;                                 // (as above)
     int y, tau;
     {
-        const int r = f0 - Y * P_b;
-        y = r / n;
-        tau = r - y * n;
+        const int r = f0 - Y * P_v;
+        y = r / seg.n;
+        tau = r - y * seg.n;
     }
 
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
@@ -212,16 +314,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const unsigned char* v;
         int last_row;           // >= 0
         int tok0;               // row r is token tok0 + r ...
-        int rel0, span;         // ... and visible if 0 <= rel0 + r < span (window start .. end of the piece)
+        int rel0, span;         // ... and visible if 0 <= rel0 + r < span (first visible token .. end of the piece)
     };
-    // (segment: block table row, element offset of the KV head inside a block, length, tiles;
+    // (segment: block table row, element offset of the KV head inside a block, first cached token
+    //  its tiles cover, length of the sequence, tiles, whether its last tile is the new token;
     //  reg_end: end of the regular tokens the piece covers; new_k / new_v: element offsets of the
     //  sequence's new rows in k_new / v_new, FUSED only; ti counts from the segment's first tile,
-    //  the one that holds the first visible token)
-    auto tile_src = [&](const int32_t* tab, int64_t head_off, int Lseg, int nseg, int reg_end,
+    //  the one that holds token lo)
+    auto tile_src = [&](const int32_t* tab, int64_t head_off, int lo, int Lseg, int nseg, bool has_new, int reg_end,
                         int64_t new_k, int64_t new_v, int ti) __attribute__((always_inline)) {
         TileSrc s;
-        if (NEW_TILE && ti == nseg - 1) {
+        if (NEW_TILE && has_new && ti == nseg - 1) {
             s.k = k_new + new_k * 2;
             s.v = v_new + new_v * 2;
             s.last_row = 0;
@@ -229,7 +332,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             s.rel0 = 0;
             s.span = 1;
         } else {
-            const int lo = flat_first_token(Lseg, W);
             const int t0 = (ti + lo / TILE) * TILE;
             // through the scalar cache: a vector load here would make the wave wait for every tile
             // load still in flight before it could read the block number
@@ -261,52 +363,71 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
                 Tl.v[r] = stream_load16(s.v + min(4 * r + hg, s.last_row) * (D * 2) + 16 * j16);
         }
     };
-    // B operand of the score MFMAs for segment (bb, yy) - lane (head j16, k-slab hg) holds dims
-    // 32i + 8hg .. +7 of its head, rows >= GH zero - and that head's slope (base 2).
-    auto load_q = [&](uint4 (&qd)[4], float& sd, int bb, int yy) __attribute__((always_inline)) {
+    // B operand of the score MFMAs for segment (sg, yy) - lane (column j16, k-slab hg) holds dims
+    // 32i + 8hg .. +7 of its column's query row, unused columns zero - with that head's slope (base 2)
+    // and the position of that query (the ALiBi term is relative to it).  A column is head j16 of the
+    // segment's GH heads; in a shared prefix, head j16 % GH of the bundle's member j16 / GH.
+    auto load_q = [&](uint4 (&qd)[4], float& sd, int& pos, int sg_b, int sg_L, bool sg_shared, int yy) __attribute__((always_inline)) {
         const int gg = yy / chunks;
         const int hh0 = gg * G + (yy - gg * chunks) * GH;
+        int col_b = sg_b, col_h = min(j16, GH - 1);
+        bool ok = j16 < GH;
+        pos = sg_L - 1;
+        if constexpr (SHARED) {
+            if (sg_shared) {
+                const int i = j16 / GH;                      // member of the bundle (sg_b is its leader)
+                col_h = j16 - i * GH;
+                ok = i < p.bundle && sg_b + i < B;
+                col_b = min(sg_b + i, B - 1);
+                const int Li = ctx[col_b];
+                if (i > 0) ok = ok && p.shared_blocks[col_b] > 0 && Li > 0;
+                pos = Li - 1;
+            }
+        }
         // (2-byte caches: MFMA i contracts dims 32i + 8hg .. +7; E4M3 caches: dims
         // 64(i/2) + 16hg + 8(i%2) .. +7, the order in which a lane's 16-byte K pieces arrive)
-        const uint16_t* qrow = qp + ((int64_t)bb * Hq + hh0 + min(j16, GH - 1)) * D + (KV8 ? 16 : 8) * hg;
-        const uint32_t keep = j16 < GH ? 0xffffffffu : 0u;
+        const uint16_t* qrow = qp + ((int64_t)col_b * Hq + hh0 + col_h) * D + (KV8 ? 16 : 8) * hg;
+        const uint32_t keep = ok ? 0xffffffffu : 0u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint4 x = *reinterpret_cast<const uint4*>(qrow + (KV8 ? 64 * (i >> 1) + 8 * (i & 1) : 32 * i));
             qd[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
         float sl = 0.f;
-        if (p.slopes) sl = p.slopes[hh0 + min(j16, GH - 1)];
-        sd = j16 < GH ? sl * kLog2e : 0.f;
+        if (p.slopes) sl = p.slopes[hh0 + col_h];
+        sd = ok ? sl * kLog2e : 0.f;
     };
 
     Tile buf[2];
     TileSrc d0, d1;               // what buf[0] / buf[1] hold (or are receiving)
     uint4 qa[4];
-    float slope2;                 // ALiBi slope (base 2) of head j16
+    float slope2;                 // ALiBi slope (base 2) of column j16
+    int q_pos;                    // position of column j16's query: its sequence's last token
     bool chained = false;         // buf[0] / d0 were filled by the previous piece
     int f = f0;
     for (;;) {
-        // ---- one piece: tiles [tau, tau_end) of segment (b, y) -------------------------------
+        // ---- one piece: tiles [tau, tau_end) of segment (v, y) -------------------------------
+        const int n = seg.n, L = seg.L, lo = seg.lo;
+        const bool has_new = NEW_TILE && !(SHARED && seg.shared);   // the segment's last tile is the new token
         const int tau_end = min(n, tau + (f1 - f));
         const int ntw = tau_end - tau;                      // >= 1
         const int j_last = ntw - 1;
         const int Lm1 = L - 1;
-        // regular (cached) tokens the piece covers end here; FUSED: the segment's last tile is the new token
-        const int first = flat_first_token(L, W) / TILE;     // the segment's tiles start at this tile of the cache
-        const int reg_end = min(FUSED ? Lm1 : L, ((NEW_TILE && tau_end == n ? tau_end - 1 : tau_end) + first) * TILE);
+        // regular (cached) tokens the piece covers end here
+        const int first = lo / TILE;                        // the segment's tiles start at this tile of the cache
+        const int reg_end = min(seg.hi, ((has_new && tau_end == n ? tau_end - 1 : tau_end) + first) * TILE);
         const int g = y / chunks;
-        const int32_t* table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
+        const int32_t* table = p.block_tables + (int64_t)seg.tb * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
-        const int64_t new_k = NEW_TILE ? b * p.k_new_stride + (int64_t)g * D : 0;
-        const int64_t new_v = NEW_TILE ? b * p.v_new_stride + (int64_t)g * D : 0;
+        const int64_t new_k = NEW_TILE ? seg.b * p.k_new_stride + (int64_t)g * D : 0;
+        const int64_t new_v = NEW_TILE ? seg.b * p.v_new_stride + (int64_t)g * D : 0;
 
-        load_q(qa, slope2, b, y);
+        load_q(qa, slope2, q_pos, seg.b, seg.L, seg.shared != 0, y);
         if (!chained) {
-            d0 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau);
+            d0 = tile_src(table, head_off, lo, L, n, has_new, reg_end, new_k, new_v, tau);
             load_tile(buf[0], d0);
         }
-        if (NEW_TILE && tau_end == n && y == g * chunks) {
+        if (has_new && tau_end == n && y == g * chunks) {
             // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
             const int blk = scalar_load_i32(table + (Lm1 >> bs_shift));
             const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
@@ -318,41 +439,44 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             }
         }
         if (lane == 0) {
-            // the combine kernel needs P_b of every non-empty sequence and the unit length
-            if (y == 0 && tau == 0) p.plan[b] = P_b;
-            if (f == 0) p.plan[B] = c;
+            // the combine kernel needs P_v of every non-empty (virtual) sequence and the unit length
+            if (y == 0 && tau == 0) p.plan[v] = P_v;
+            if (f == 0) p.plan[NV] = c;
         }
 
         // ---- the piece after this one (same unit), so that its first tile is on its way before this
         // piece ends.  Without one, the spare prefetch slot re-reads this piece's last tile (a cache
         // hit, never consumed).
         bool has_next = f + ntw < f1;                        // then this piece ends its segment
-        int nb = b, ny = y, nL = L, nn = n;
+        int nv = v, ny = y;
+        FlatSeg nseg = seg;
         if (has_next) {
             if (++ny == Y) {
                 ny = 0;
-                do {                                         // skip sequences without tokens
-                    ++nb;
-                    nL = scalar_load_i32(ctx + nb);
-                    nn = flat_tiles<FUSED, KV8>(nL, W);
-                } while (nn == 0 && nb + 1 < B);
-                if (nn == 0) {                               // cannot happen for consistent lengths
+                do {                                         // skip sequences without tiles
+                    ++nv;
+                    nseg = flat_seg<FUSED, KV8, SHARED, true>(p, nv);
+                } while (nseg.n == 0 && nv + 1 < NV);
+                if (nseg.n == 0) {                           // cannot happen for consistent lengths
                     has_next = false;
-                    nb = b, ny = y, nL = L, nn = n;
+                    nv = v, ny = y, nseg = seg;
                 }
             }
         }
         // arguments of tile_src for "the tile after this piece": the next piece's first one, or
         // (nothing follows) this piece's last one again
+        const int nn = nseg.n;
+        const bool n_has_new = NEW_TILE && !(SHARED && nseg.shared);
         const int n_tau_end = min(nn, f1 - (f + ntw));
-        const int32_t* x_table = has_next ? p.block_tables + (int64_t)nb * p.max_blocks_per_seq : table;
+        const int32_t* x_table = has_next ? p.block_tables + (int64_t)nseg.tb * p.max_blocks_per_seq : table;
         const int64_t x_head_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
-        const int x_L = has_next ? nL : L, x_n = has_next ? nn : n;
-        const int n_first = flat_first_token(nL, W) / TILE;
+        const int x_L = has_next ? nseg.L : L, x_n = has_next ? nn : n, x_lo = has_next ? nseg.lo : lo;
+        const bool x_has_new = has_next ? n_has_new : has_new;
+        const int n_first = nseg.lo / TILE;
         const int x_reg_end = !has_next ? reg_end
-                              : min(FUSED ? nL - 1 : nL, ((NEW_TILE && n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE);
-        const int64_t x_new_k = !has_next ? new_k : NEW_TILE ? nb * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
-        const int64_t x_new_v = !has_next ? new_v : NEW_TILE ? nb * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
+                              : min(nseg.hi, ((n_has_new && n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE);
+        const int64_t x_new_k = !has_next ? new_k : NEW_TILE ? nseg.b * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
+        const int64_t x_new_v = !has_next ? new_v : NEW_TILE ? nseg.b * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int x_ti = has_next ? 0 : tau + j_last;
 
         // ---- both contractions on 16-bit MFMAs, transposed so that nothing is transposed in registers:
@@ -372,6 +496,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         uint16_t* const v_rows = &v_lds[wave][0][0];
         typedef short i16x4 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
+        // position the ALiBi term is relative to: the segment's sequence, or (shared prefix) the column's
+        const int rel_pos = SHARED ? q_pos : Lm1;
 
         auto weighted_sum = [&](const float (&w_even)[4], const float (&w_odd)[4]) __attribute__((always_inline)) {
             uint32_t hi[4], lo[4] = {0u, 0u, 0u, 0u};
@@ -430,12 +556,12 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             float x[4];
             bool need = false;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int t = t0 + v;
-                // one unsigned compare covers both ends: rows before the window and rows past the piece
-                const bool visible = (unsigned)(r0 + v) < (unsigned)src.span;
-                x[v] = visible ? fmaf(S[v], scale2, slope2 * (float)(t - Lm1)) : -INFINITY;   // eq. (3), base 2
-                need |= x[v] > m_ref + FlatSoftmax<DT>::kThreshold;
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int t = t0 + v4;
+                // one unsigned compare covers both ends: rows before the first visible token and rows past the piece
+                const bool visible = (unsigned)(r0 + v4) < (unsigned)src.span;
+                x[v4] = visible ? fmaf(S[v4], scale2, slope2 * (float)(t - rel_pos)) : -INFINITY;   // eq. (3), base 2
+                need |= x[v4] > m_ref + FlatSoftmax<DT>::kThreshold;
             }
             if (__builtin_expect(__builtin_amdgcn_ballot_w64(need) != 0, 0)) {   // rare: the reference moves lazily
                 float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
@@ -446,18 +572,18 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
                 m_ref = m_new;
                 lsum *= alpha;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) pend[v] *= alpha;
+                for (int v4 = 0; v4 < 4; ++v4) pend[v4] *= alpha;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[e] *= alpha;
             }
             float w[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) w[v] = fast_exp2(x[v] - m_ref);                               // eq. (4) numerators
+            for (int v4 = 0; v4 < 4; ++v4) w[v4] = fast_exp2(x[v4] - m_ref);                          // eq. (4) numerators
             if constexpr (ODD) {
                 weighted_sum(pend, w);
             } else {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) pend[v] = w[v];
+                for (int v4 = 0; v4 < 4; ++v4) pend[v4] = w[v4];
             }
         };
 
@@ -468,13 +594,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const int trips = (ntw + 1) >> 1;
         for (int it = 0; it < trips; ++it) {
             const int j = 2 * it;
-            d1 = tile_src(table, head_off, L, n, reg_end, new_k, new_v, tau + min(j + 1, j_last));
+            d1 = tile_src(table, head_off, lo, L, n, has_new, reg_end, new_k, new_v, tau + min(j + 1, j_last));
             load_tile(buf[1], d1);
             compute_tile(buf[0], d0, std::false_type{});
             const bool more = j + 2 <= j_last;
-            d0 = tile_src(more ? table : x_table, more ? head_off : x_head_off, more ? L : x_L, more ? n : x_n,
-                          more ? reg_end : x_reg_end, more ? new_k : x_new_k, more ? new_v : x_new_v,
-                          more ? tau + j + 2 : x_ti);
+            d0 = tile_src(more ? table : x_table, more ? head_off : x_head_off, more ? lo : x_lo, more ? L : x_L,
+                          more ? n : x_n, more ? has_new : x_has_new, more ? reg_end : x_reg_end,
+                          more ? new_k : x_new_k, more ? new_v : x_new_v, more ? tau + j + 2 : x_ti);
             load_tile(buf[0], d0);
             if (j + 1 <= j_last) {
                 compute_tile(buf[1], d1, std::true_type{});
@@ -488,11 +614,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             }
         }
 
-        // ---- leave the piece's partial result in slot u + s: this lane holds dims 16db + 4hg + v of
-        // head j16 ----------------------------------------------------------------------------------
-        const int64_t slot = (int64_t)u + (int64_t)b * Y + y;
-        if (j16 < GH) {
-            const int64_t e0 = slot * GH + j16;
+        // ---- leave the piece's partial result in slot u + s (s = v * Y + y): this lane holds dims
+        // 16db + 4hg + v of column j16 ---------------------------------------------------------------
+        const int64_t slot = (int64_t)u + (int64_t)v * Y + y;
+        if (j16 < CS) {
+            const int64_t e0 = slot * CS + j16;
             if (hg == 0) {
                 p.ws_m[e0] = m_ref;
                 p.ws_l[e0] = lsum[0];
@@ -506,14 +632,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // ---- next piece ------------------------------------------------------------------------
         if (!has_next) break;
         f += ntw;
-        if (y + 1 == Y) P_b += n;                            // sequences skipped on the way have no tiles
-        b = nb, y = ny, L = nL, n = nn, tau = 0;
+        if (y + 1 == Y) P_v += n;                            // sequences skipped on the way have no tiles
+        v = nv, y = ny, seg = nseg, tau = 0;
         chained = true;
     }
 }
 
 // Combine the partial results of the equal-work split: head h of sequence b collects slots
-// u + s for the units u that touched its segment (a contiguous range found from P_b, n_b and c).
+// u + s for the units u that touched its segment (a contiguous range found from P_v, n_v and c).
 // Same arithmetic as the fixed-partition combine:
 //   M = max_u m_u,  out = sum_u 2^(m_u-M) o_u / sum_u 2^(m_u-M) l_u.
 //
@@ -522,9 +648,14 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 // so that it is the cache's own codes that are attended to - and the thread that holds dims
 // od .. od + 3 of a KV head's first query head stores the four K and four V codes into the caches
 // (Alg. 2 "store K, V": nothing in the step has read that cache row).
-template <int DT, bool NEWTOK = false>
+//
+// SHARED: a head's partial results lie in two staircases - the pieces of its own segment (virtual
+// sequence 2b + 1, column = the head) and, if the sequence takes part in its bundle's shared
+// prefix, the pieces of that segment (virtual sequence 2 * leader, column = member * GH + head).
+template <int DT, bool NEWTOK = false, bool SHARED = false>
 __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kernel(const DecodeParams p)
 {
+    static_assert(!(NEWTOK && SHARED), "shared prefixes: 2-byte caches");
     constexpr int D = 128;
     constexpr int kVecPerHead = D / 4;
     constexpr int kHeads = kReduceThreads / kVecPerHead;
@@ -533,15 +664,18 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int b = blockIdx.y;
     if (h >= p.num_heads) return;
     uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;
+    const int NV = SHARED ? 2 * p.num_seqs : p.num_seqs;
+    const int v_own = SHARED ? 2 * b + 1 : b;
     // (this kernel is a few dependent memory round trips and little else: the three values that
     // everything else depends on are fetched together, before the first branch)
     const int L = p.context_lens[b];
-    const int plan_total = p.plan[p.num_seqs], plan_b = p.plan[b];    // readable garbage where nobody wrote them
+    const int plan_total = p.plan[NV], plan_own = p.plan[v_own];      // readable garbage where nobody wrote them
     if (L <= 0) {
         *reinterpret_cast<uint2*>(o) = make_uint2(0u, 0u);
         return;
     }
     const int GH = p.heads_per_wg;
+    const int CS = SHARED ? 16 : GH;                         // columns per slot
     const int G = p.num_heads / p.num_kv_heads;
     const int chunks = G / GH;
     const int g = h / G;
@@ -560,52 +694,75 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     const int hh = within - chunk * GH;
     const int Y = p.segs_per_seq;
     const int y = g * chunks + chunk;
+    const int c = max(plan_total, 1);
     // the numbering the main kernel used
-    const int n = NEWTOK ? flat_tiles<true, true>(L, p.window)
-                         : p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);
-    // (the clamps only matter if the lengths changed under the kernels: they keep every read
-    // inside the workspace; n == 0 - NEWTOK only: nothing was streamed, nobody wrote the plan)
-    const int c = n > 0 ? max(plan_total, 1) : 1;
-    const int F0 = n > 0 ? Y * plan_b + y * n : 0;
-    const int u0 = min(max(F0 / c, 0), p.num_units - 1);
-    const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
-    const int64_t base = ((int64_t)u0 + (int64_t)b * Y + y) * GH + hh;       // slot stride between units: GH
+    int n_own, n_shared = 0, col_shared = 0, plan_shared = 0, v_shared = 0;
+    if constexpr (SHARED) {
+        const bool fused = p.k_new != nullptr;
+        const int b0 = b - b % p.bundle;
+        const int S = shared_prefix_tokens<false>(p, b0, fused ? 1 : 0);
+        const bool takes_part = S > 0 && (b == b0 || p.shared_blocks[b] > 0);
+        const int lo = takes_part ? S : 0, hi = fused ? L - 1 : L;
+        n_own = (hi > lo ? (hi + kMmaTile - 1) / kMmaTile - lo / kMmaTile : 0) + (fused ? 1 : 0);
+        if (takes_part) {
+            n_shared = S / kMmaTile;
+            v_shared = 2 * b0;
+            col_shared = (b - b0) * GH + hh;
+            plan_shared = p.plan[v_shared];
+        }
+    } else {
+        n_own = NEWTOK ? flat_tiles<true, true>(L, p.window)
+                       : p.k_new ? flat_tiles<true>(L, p.window) : flat_tiles<false>(L, p.window);
+    }
     // One pass in batches of 8 partial results with a running reference (a segment rarely has more
     // than 8 pieces, so this is one memory round trip; a separate pass for the maximum would be
     // a second chain of them).
     float M = -INFINITY;
     float den = 0.f;
     float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i0 = 0; i0 < np; i0 += 8) {
-        float mm[8], ll[8];
-        float4 x[8];
+    bool any = false;                                        // something has been accumulated
+    // the pieces of segment y of (virtual) sequence vv, which has n tiles per segment and tile prefix P
+    auto collect = [&](int vv, int n, int P, int col) __attribute__((always_inline)) {
+        // (the clamps only matter if the lengths changed under the kernels: they keep every read
+        // inside the workspace; n == 0: nothing was streamed, nobody wrote the plan entry)
+        const int F0 = n > 0 ? Y * P + y * n : 0;
+        const int u0 = min(max(F0 / c, 0), p.num_units - 1);
+        const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
+        const int64_t base = ((int64_t)u0 + (int64_t)vv * Y + y) * CS + col;     // slot stride between units: CS
+        for (int i0 = 0; i0 < np; i0 += 8) {
+            float mm[8], ll[8];
+            float4 x[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int64_t e = base + (int64_t)min(i0 + k, np - 1) * GH;
-            mm[k] = p.ws_m[e];
-            ll[k] = p.ws_l[e];
-            x[k] = *reinterpret_cast<const float4*>(p.ws_o + e * D + od);
+            for (int k = 0; k < 8; ++k) {
+                const int64_t e = base + (int64_t)min(i0 + k, np - 1) * CS;
+                mm[k] = p.ws_m[e];
+                ll[k] = p.ws_l[e];
+                x[k] = *reinterpret_cast<const float4*>(p.ws_o + e * D + od);
+            }
+            float Mn = M;                                            // clamped repeats of the last piece do not change it
+#pragma unroll
+            for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
+            const float keep = any ? fast_exp2(M - Mn) : 0.f;        // nothing accumulated before the first batch
+            any = true;
+            M = Mn;
+            den *= keep;
+            num.x *= keep;
+            num.y *= keep;
+            num.z *= keep;
+            num.w *= keep;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float fct = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
+                den = fmaf(fct, ll[k], den);
+                num.x = fmaf(fct, x[k].x, num.x);
+                num.y = fmaf(fct, x[k].y, num.y);
+                num.z = fmaf(fct, x[k].z, num.z);
+                num.w = fmaf(fct, x[k].w, num.w);
+            }
         }
-        float Mn = M;                                            // clamped repeats of the last piece do not change it
-#pragma unroll
-        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
-        const float keep = i0 == 0 ? 0.f : fast_exp2(M - Mn);    // nothing accumulated before the first batch
-        M = Mn;
-        den *= keep;
-        num.x *= keep;
-        num.y *= keep;
-        num.z *= keep;
-        num.w *= keep;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const float fct = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
-            den = fmaf(fct, ll[k], den);
-            num.x = fmaf(fct, x[k].x, num.x);
-            num.y = fmaf(fct, x[k].y, num.y);
-            num.z = fmaf(fct, x[k].z, num.z);
-            num.w = fmaf(fct, x[k].w, num.w);
-        }
-    }
+    };
+    collect(v_own, n_own, plan_own, hh);
+    if constexpr (SHARED) collect(v_shared, n_shared, plan_shared, col_shared);
     if constexpr (NEWTOK) {
         // the new token, at the query's own position (ALiBi term 0): codes, their values, its score
         const uint32_t kcodes = e4m3_codes2(widen_lo<DT>(kw.x) * p.k_inv_scale, widen_hi<DT>(kw.x) * p.k_inv_scale) |
@@ -622,7 +779,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
         for (int off = 1; off < kVecPerHead; off <<= 1) dot += __shfl_xor(dot, off);      // a head's 32 threads are half a wave
         const float s_new = dot * p.scale2;                                               // eq. (3), base 2, k_scale folded in
         const float M2 = fmaxf(M, s_new);
-        const float f_old = np > 0 ? fast_exp2(M - M2) : 0.f, f_new = fast_exp2(s_new - M2);
+        const float f_old = any ? fast_exp2(M - M2) : 0.f, f_new = fast_exp2(s_new - M2);
         den = fmaf(den, f_old, f_new);
         num.x = fmaf(num.x, f_old, f_new * v01[0]);
         num.y = fmaf(num.y, f_old, f_new * v01[1]);

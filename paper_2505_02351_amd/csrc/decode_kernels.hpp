@@ -50,6 +50,11 @@ struct DecodeParams {
     int64_t k_new_stride, v_new_stride;
     void* k_cache_w;            // the caches again, writable
     void* v_cache_w;
+    // Shared prefixes (equal-work kernel only): sequences come in aligned bundles of `bundle`
+    // consecutive ones; shared_blocks[b] > 0 says that the first shared_blocks[b] block-table
+    // entries of sequence b are the bundle leader's (sequence b - b % bundle), 0 that b shares nothing.
+    const int32_t* shared_blocks;   // [num_seqs] or nullptr
+    int bundle;                     // sequences whose heads fit the score tile together: 16 / heads_per_wg
 };
 
 // Sequence and number of visible keys of one output row (decode: row = sequence).

@@ -164,19 +164,23 @@ constexpr int kFlatMinTiles = OPTGQA_FLAT_MIN_TILES;
 
 size_t round_up4(size_t x) { return (x + 3) / 4 * 4; }
 
-bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int window = 0)
+// (shared: the flat order runs over two virtual sequences per sequence - a bundle's shared prefix
+// and a sequence's own part - and every slot holds 16 columns, see decode_flat_kernels.hpp)
+bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int window = 0,
+               bool shared = false)
 {
     const int group = num_heads / num_kv_heads;
     const int gh = heads_per_workgroup(group, 128);
     const int64_t Y = (int64_t)num_kv_heads * (group / gh);
-    const int64_t segs = Y * num_seqs;
+    const int64_t segs = Y * num_seqs * (shared ? 2 : 1);
+    const int cols = shared ? 16 : gh;
     if (num_seqs > kMaxRowsPerLaunch) return false;          // the combine kernel's grid.y
     // Flat tile indices are 32-bit.  2^30 tiles would be 8 TiB of cache, so the margin of 2 also
     // covers lengths above the stated bound.
     if (segs * ((max_context_len + kMmaTile - 1) / kMmaTile) >= (1LL << 30)) return false;
     // tiles that will be read: with a sliding window at most window + 15 tokens per segment
     const int seen = window > 0 && window + kMmaTile - 1 < max_context_len ? window + kMmaTile - 1 : max_context_len;
-    const int64_t tiles = segs * ((seen + kMmaTile - 1) / kMmaTile);
+    const int64_t tiles = Y * num_seqs * ((seen + kMmaTile - 1) / kMmaTile);
     int64_t wgs = (tiles + (int64_t)kDecodeWaves * kFlatMinTiles - 1) / ((int64_t)kDecodeWaves * kFlatMinTiles);
     if (wgs > flat_max_workgroups()) wgs = flat_max_workgroups();
     if (wgs < 1) wgs = 1;
@@ -185,21 +189,21 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     s.workgroups = (int)wgs;
     s.segs_per_seq = (int)Y;
     const size_t slots = (size_t)wgs * kDecodeWaves + (size_t)segs;
-    s.plan_floats = round_up4((size_t)num_seqs + 1);
-    s.ml_floats = round_up4(slots * gh);
-    s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * gh * 128) * sizeof(float);
+    s.plan_floats = round_up4((size_t)num_seqs * (shared ? 2 : 1) + 1);
+    s.ml_floats = round_up4(slots * cols);
+    s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * cols * 128) * sizeof(float);
     return true;
 }
 
 SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
-                     int max_context_len, int partition_size, int window = 0)
+                     int max_context_len, int partition_size, int window = 0, bool shared = false)
 {
     SplitPlan s{0, 1, 0, 0, 0, 0, 0};
     int P = partition_size;
     if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
     // The library's own choice for head_dim 128 is the equal-work split whenever splitting pays.
     if (head_dim == 128 && (partition_size == OPTGQA_SPLIT_BALANCED || (partition_size == 0 && P > 0))) {
-        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len, window))
+        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len, window, shared))
             return s;
         if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
     }
@@ -281,12 +285,12 @@ int launch_decode_any(int dtype, int head_dim, A... args)
 // Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
 // the device keeps resident at once, because a unit that has to wait for a free slot would start
 // when every other unit is nearly done.
-template <int DT, bool FUSED, bool KV8 = false>
+template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false>
 int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 {
     static const int resident = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8>, kDecodeWaves * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8, SHARED>, kDecodeWaves * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -300,16 +304,22 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     int rc;
     {
         KernelEvents ev(st);
-        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8, SHARED>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
     }
     if (rc != OPTGQA_OK) return rc;
     constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
-    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
                   dim3(kReduceThreads), 0, st, p);
 }
 
 int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
 {
+    if (p.shared_blocks && p.k_new)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, false, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, true, false, true>(p, workgroups, st);
+    if (p.shared_blocks)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, false, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, false, false, true>(p, workgroups, st);
     if (kv8 && p.k_new)
         return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, true>(p, workgroups, st)
                                    : launch_decode_flat_dt<kBF16, true, true>(p, workgroups, st);
@@ -521,8 +531,14 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
                    int max_blocks_per_seq, int max_context_len, int partition_size, void* workspace,
                    size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step,
                    const float* kv_scales = nullptr,      // {k_scale, v_scale}: the caches hold E4M3 codes
-                   int window = 0)                        // > 0: sliding window (Alg. 1, local mask)
+                   int window = 0,                        // > 0: sliding window (Alg. 1, local mask)
+                   const int32_t* shared_blocks = nullptr) // shared prefixes, read once per bundle of sequences
 {
+    if (shared_blocks) {
+        if (kv_scales || window > 0) return OPTGQA_ERR_UNSUPPORTED;
+        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;      // the equal-work kernel only
+        partition_size = OPTGQA_SPLIT_BALANCED;
+    }
     if (window > 0)                                      // head_dim 128: the equal-work kernel; 64: the general
         partition_size = head_dim == 128 ? OPTGQA_SPLIT_BALANCED : -1;   // kernel, unsplit (a window bounds the work)
     if (kv_scales) {
@@ -552,7 +568,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (num_heads > 65535) return OPTGQA_ERR_SHAPE;
 
     SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
-                             max_context_len > 0 ? max_context_len : 1, partition_size, window);
+                             max_context_len > 0 ? max_context_len : 1, partition_size, window, shared_blocks != nullptr);
     if (partition_size == OPTGQA_SPLIT_BALANCED && s.partition_size != OPTGQA_SPLIT_BALANCED)
         return OPTGQA_ERR_UNSUPPORTED;                   // head_dim 64, or sizes beyond 32-bit tile indices
     if (s.partition_size != 0) {
@@ -585,6 +601,8 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.window = window > 0 ? window : 0;
     p.new_token_in_combine = 0;
     p.k_inv_scale = p.v_inv_scale = 1.f;
+    p.shared_blocks = shared_blocks;
+    p.bundle = shared_blocks ? kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128) : 1;
     if (kv_scales) {
         p.scale2 *= kv_scales[0];
         p.out_scale = kv_scales[1];
@@ -785,6 +803,79 @@ int optgqa_decode_step_fp8(void* out, const void* q, const void* k_new, const vo
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
                           static_cast<hipStream_t>(stream), &step, kv_scales);
+}
+
+int optgqa_shared_prefix_bundle(int num_heads, int num_kv_heads, int head_dim)
+{
+    if (num_heads <= 0 || num_kv_heads <= 0 || num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
+    if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
+    return kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128);
+}
+
+size_t optgqa_shared_prefix_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads, int head_dim,
+                                            int block_size, int max_context_len)
+{
+    if (num_seqs <= 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim != 128 || block_size <= 0 ||
+        max_context_len <= 0 || num_heads % num_kv_heads)
+        return 0;
+    const SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len,
+                                   OPTGQA_SPLIT_BALANCED, 0, true);
+    return s.partition_size == OPTGQA_SPLIT_BALANCED ? s.bytes : 0;
+}
+
+int optgqa_paged_attention_shared(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                  const int32_t* block_tables, const int32_t* context_lens,
+                                  const int32_t* shared_blocks, const float* alibi_slopes, float scale,
+                                  int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                  int max_blocks_per_seq, int max_context_len, void* workspace,
+                                  size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+{
+    if (!shared_blocks && num_seqs > 0) return OPTGQA_ERR_NULL;
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), nullptr, nullptr, 0, shared_blocks);
+}
+
+int optgqa_decode_step_shared(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                              void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                              const int32_t* shared_blocks, const float* alibi_slopes, float scale, int num_seqs,
+                              int num_heads, int num_kv_heads, int head_dim, int block_size,
+                              int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
+                              int64_t v_token_stride, void* workspace, size_t workspace_bytes,
+                              optgqa_dtype dtype, void* stream)
+{
+    if (!shared_blocks && num_seqs > 0) return OPTGQA_ERR_NULL;
+    const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          static_cast<hipStream_t>(stream), &step, nullptr, 0, shared_blocks);
+}
+
+int optgqa_validate_shared_prefix_host(const int32_t* block_tables_host, const int32_t* context_lens_host,
+                                       const int32_t* shared_blocks_host, int num_seqs, int max_blocks_per_seq,
+                                       int block_size, int bundle, int new_tokens)
+{
+    if (num_seqs < 0 || max_blocks_per_seq <= 0 || block_size <= 0 || bundle <= 0 || new_tokens < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (num_seqs == 0) return OPTGQA_OK;
+    if (!block_tables_host || !context_lens_host || !shared_blocks_host) return OPTGQA_ERR_NULL;
+    for (int b = 0; b < num_seqs; ++b) {
+        const int s = shared_blocks_host[b];
+        if (s < 0) return OPTGQA_ERR_TABLE;
+        if (s == 0) continue;
+        const int b0 = b - b % bundle;
+        if (b == b0) return OPTGQA_ERR_TABLE;                   // a leader shares with nobody before it
+        // whole blocks that both the sequence and its leader already hold in the cache
+        const int64_t cached = (int64_t)context_lens_host[b] - new_tokens, cached0 = (int64_t)context_lens_host[b0] - new_tokens;
+        if ((int64_t)s * block_size > cached || (int64_t)s * block_size > cached0 || s > max_blocks_per_seq)
+            return OPTGQA_ERR_TABLE;
+        for (int i = 0; i < s; ++i)
+            if (block_tables_host[(int64_t)b * max_blocks_per_seq + i] != block_tables_host[(int64_t)b0 * max_blocks_per_seq + i])
+                return OPTGQA_ERR_TABLE;
+    }
+    return OPTGQA_OK;
 }
 
 static int prefill_impl(void* out, const void* q, const void* k_cache, const void* v_cache,

@@ -106,6 +106,32 @@ class DevCase:
         self.check_canaries()
         return to_host(self.out)
 
+    def shared_workspace(self):
+        c = self.case.cfg
+        n = G.shared_prefix_workspace_bytes(c.batch, c.num_heads, c.num_kv_heads, c.head_dim, c.block_size,
+                                            max(self.case.max_context_len, 1))
+        g = Guarded(n)
+        self._guards.append(("the workspace", g))
+        return g.view(torch.float32)
+
+    def decode_shared(self, shared_blocks, fused=False):
+        """Decode with shared prefix blocks read once per bundle: over filled caches, or (fused) with the
+        step's cache write in the call.  ``shared_blocks``: numpy int32 [B]."""
+        sb = torch.from_numpy(np.ascontiguousarray(shared_blocks, dtype=np.int32)).to("cuda")
+        ws = self.shared_workspace()
+        self.out.fill_(float("nan"))
+        if fused:
+            G.decode_step_shared(self.out, self.q, self.k_new, self.v_new, self.k_cache, self.v_cache,
+                                 self.block_tables, self.context_lens, sb, self.slopes, float(self.case.scale),
+                                 self.case.max_context_len, ws)
+        else:
+            G.paged_attention_shared(self.out, self.q, self.k_cache, self.v_cache, self.block_tables,
+                                     self.context_lens, sb, self.slopes, float(self.case.scale),
+                                     self.case.max_context_len, ws)
+        torch.cuda.synchronize()
+        self.check_canaries()
+        return to_host(self.out)
+
     def decode_window(self, window, slopes="case", fused=False):
         """Windowed decode: over filled caches, or (fused) with the step's cache write in the call."""
         sl = self.slopes if isinstance(slopes, str) else slopes

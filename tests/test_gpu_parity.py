@@ -1007,6 +1007,96 @@ def test_decode_with_shared_prefix_blocks(U, oracle):
     assert U.max_abs_err(dev.decode(partition_size=256), ref, W.BF16) <= U.TOL[W.BF16]
 
 
+SHARED = [
+    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi            heads per pass -> bundle
+    (W.BF16, 32, 4, 32, 10, 40, 900),      # G = 8  -> pairs
+    (W.F16, 32, 8, 16, 13, 20, 700),       # G = 4  -> bundles of 4, last bundle incomplete
+    (W.BF16, 8, 8, 16, 35, 1, 300),        # G = 1  -> bundles of 16; 70 virtual sequences: two-level scan
+    (W.F16, 12, 2, 16, 7, 30, 500),        # G = 6  -> pairs, 12 of the 16 columns in use
+    (W.BF16, 6, 2, 64, 11, 64, 700),       # G = 3  -> bundles of 5 (15 columns), block 64
+    (W.F16, 32, 2, 16, 4, 50, 400),        # G = 16 -> bundle of 1: nothing can be shared
+    (W.BF16, 16, 2, 16, 80, 1, 120),       # G = 8, 80 sequences: 160 virtual sequences, many short
+]
+
+
+@pytest.mark.parametrize("i", range(len(SHARED)))
+def test_decode_shared_prefix_sweep(U, oracle, i):
+    """Shared prefixes read once per bundle (Section III-B): ragged numbers of shared blocks per
+    member, members that share nothing, members whose whole cached context is shared, sequences of
+    length 0 and 1.  The oracle knows nothing of sharing - it walks the aliased tables - and the
+    plain and fused calls must both match it; the fused call's caches bit for bit."""
+    import paper_2505_02351_amd as G
+    dtype, Hq, Hkv, bs, B, lo, hi = SHARED[i]
+    cfg = W.small_config(name=f"shared{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv, head_dim=128,
+                         block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi, seed=2400 + i)
+    rng = np.random.default_rng(2500 + i)
+    lens = rng.integers(lo, hi + 1, size=B).astype(np.int32)
+    lens[rng.choice(B, size=max(B // 6, 1), replace=False)] = rng.choice([0, 1, bs, bs + 1, 2 * bs + 1])
+    case = W.make_case(cfg, context_lens=lens)
+    bundle = G.shared_prefix_bundle(Hq, Hkv, 128)
+    assert bundle == 16 // max(d for d in range(1, 17) if (Hq // Hkv) % d == 0)
+    shared = W.share_prefix_in_bundles(case, bundle, seed=2600 + i)
+    assert bundle == 1 or shared.any()
+    assert G.validate_shared_prefix_host(case.block_tables, case.context_lens, shared, bs, bundle, 1) == 0
+    full = lambda a, shape: (lambda z: (z.__setitem__(lens > 0, a), z)[1])(np.zeros(shape, np.uint16))
+    q_full = full(case.q, (B, Hq, 128))
+    k_full, v_full = full(case.k_new, (B, Hkv, 128)), full(case.v_new, (B, Hkv, 128))
+    kc, vc = oracle_filled(oracle, case)
+    case.q = q_full
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    dev.k_new, dev.v_new = U.to_dev(k_full, dtype), U.to_dev(v_full, dtype)
+    got = dev.decode_shared(shared, fused=True)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert not got[lens == 0].any()
+    U.check_scaled(got, ref, dtype, f"shared prefixes {i}, fused step")
+    got = dev.decode_shared(shared)                         # caches now filled: the plain call
+    assert not got[lens == 0].any()
+    U.check_scaled(got, ref, dtype, f"shared prefixes {i}, plain")
+    # no sharing declared at all: the same kernel degenerates to the plain equal-work split
+    got = dev.decode_shared(np.zeros(B, np.int32))
+    U.check_scaled(got, ref, dtype, f"shared prefixes {i}, nothing declared")
+
+
+@pytest.mark.parametrize("group", [2, 4, 16])
+def test_decode_shared_prefix_workload_full(U, oracle, group):
+    """The bench's batch (C3 shapes) with runs of `group` sequences sharing 90 % of their common cached
+    length, through optgqa_decode_step_shared in bundles of two: every row against the oracle."""
+    import paper_2505_02351_amd as G
+    case = W.make_case(W.CONFIGS["C3"])
+    cfg = case.cfg
+    W.share_prefix_blocks(case, group, 0.9)
+    bundle = G.shared_prefix_bundle(cfg.num_heads, cfg.num_kv_heads, cfg.head_dim)
+    shared = W.bundle_shared_blocks(case, bundle)
+    assert bundle == 2 and np.count_nonzero(shared) == cfg.batch // 2
+    assert G.validate_shared_prefix_host(case.block_tables, case.context_lens, shared, cfg.block_size, bundle, 1) == 0
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    got = dev.decode_shared(shared, fused=True)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    U.check_scaled(got, ref, case.dtype, f"C3, groups of {group} share a prefix", max_exempt=WORKLOAD_EXEMPT)
+
+
+def test_shared_prefix_rejects_what_it_cannot_do(U):
+    import torch
+    import paper_2505_02351_amd as G
+    bt = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
+    cl = torch.ones(2, dtype=torch.int32, device="cuda")
+    sb = torch.zeros(2, dtype=torch.int32, device="cuda")
+    ws = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
+    q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
+    c = torch.zeros(4, 2, 16, 128, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # no workspace
+        G.paged_attention_shared(torch.empty_like(q), q, c, c, bt, cl, sb, None, 0.1, 32, None)
+    q64 = torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda")
+    c64 = torch.zeros(4, 2, 16, 64, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 64
+        G.paged_attention_shared(torch.empty_like(q64), q64, c64, c64, bt, cl, sb, None, 0.1, 32, ws)
+    with pytest.raises(TypeError):                       # int64 sharing table
+        G.paged_attention_shared(torch.empty_like(q), q, c, c, bt, cl, sb.long(), None, 0.1, 32, ws)
+
+
 def test_prefill_with_a_sequence_without_new_tokens(U, oracle):
     """A batch in which one sequence contributes no query token (cu_q_lens repeats a value): its
     workgroups have nothing to do, the others are unaffected."""

@@ -186,6 +186,49 @@ def share_prefix_blocks(case: "Case", group: int, fraction: float = 0.9) -> int:
     return shared
 
 
+def share_prefix_in_bundles(case: "Case", bundle: int, seed: int, share_prob: float = 0.8) -> np.ndarray:
+    """Ragged prefix sharing in aligned bundles of ``bundle`` consecutive sequences: every non-leading
+    member shares, with probability ``share_prob``, a random number of leading whole cached blocks
+    (at least one, at most what both it and the bundle's first sequence hold in the cache, never a
+    block that receives a new token) with the bundle's first sequence; its block table is rewritten
+    to alias those blocks.  Returns ``shared_blocks`` (int32 [B], 0 = shares nothing).  Pure index work."""
+    bs, B = case.cfg.block_size, case.cfg.batch
+    rng = np.random.default_rng(seed)
+    shared = np.zeros(B, dtype=np.int32)
+    cached = case.context_lens.astype(np.int64) - case.q_lens
+    for b in range(B):
+        b0 = b - b % bundle
+        if b == b0 or rng.random() >= share_prob:
+            continue
+        most = int(min(cached[b], cached[b0])) // bs
+        if most < 1:
+            continue
+        n = int(rng.integers(1, most + 1))
+        if rng.random() < 0.3:
+            n = most                                    # often everything that can be shared
+        case.block_tables[b, :n] = case.block_tables[b0, :n]
+        shared[b] = n
+    return shared
+
+
+def bundle_shared_blocks(case: "Case", bundle: int) -> np.ndarray:
+    """``shared_blocks`` for aligned bundles of ``bundle`` sequences, read off the block tables as they
+    are: for every non-leading member, the number of leading table entries equal to those of the
+    bundle's first sequence, limited to whole blocks both hold in the cache.  Pure index work (what
+    a scheduler that aliased the tables would know anyway)."""
+    bs, B = case.cfg.block_size, case.cfg.batch
+    cached = case.context_lens.astype(np.int64) - case.q_lens
+    shared = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        b0 = b - b % bundle
+        if b == b0:
+            continue
+        most = int(min(cached[b], cached[b0])) // bs
+        same = case.block_tables[b, :most] == case.block_tables[b0, :most]
+        shared[b] = most if same.all() else int(np.argmin(same))
+    return shared
+
+
 def make_case(cfg: Config, seed: Optional[int] = None, perm_seed: Optional[int] = None,
               context_lens: Optional[np.ndarray] = None, slopes: Optional[np.ndarray] = None,
               identity_blocks: bool = False) -> Case:
