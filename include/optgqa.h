@@ -46,6 +46,8 @@
 extern "C" {
 #endif
 
+/* Values of every `dtype` argument.  The arguments themselves are plain ints, so that a value
+ * outside this list is answered with OPTGQA_ERR_UNSUPPORTED instead of being undefined behaviour. */
 typedef enum { OPTGQA_F16 = 0, OPTGQA_BF16 = 1 } optgqa_dtype;
 
 /* partition_size value that asks optgqa_paged_attention for the equal-work split. */
@@ -86,7 +88,7 @@ const char *optgqa_status_string(int status);
 int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *v_cache,
                              const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
                              int head_dim, int block_size, int64_t k_token_stride,
-                             int64_t v_token_stride, optgqa_dtype dtype, void *stream);
+                             int64_t v_token_stride, int dtype, void *stream);
 
 /*
  * Decode attention over the paged cache (Alg. 2 "Compute context attention with caches";
@@ -125,7 +127,7 @@ int optgqa_paged_attention(void *out, const void *q, const void *k_cache, const 
                            const float *alibi_slopes, float scale, int num_seqs, int num_heads,
                            int num_kv_heads, int head_dim, int block_size,
                            int max_blocks_per_seq, int max_context_len, int partition_size,
-                           void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                           void *workspace, size_t workspace_bytes, int dtype,
                            void *stream);
 
 /*
@@ -150,7 +152,7 @@ int optgqa_paged_attention_static(void *out, const void *q, const void *k_cache,
                                   const int32_t *block_tables, const int32_t *context_lens,
                                   const float *alibi_slopes, float scale, int num_seqs, int num_heads,
                                   int num_kv_heads, int head_dim, int block_size,
-                                  int max_blocks_per_seq, int max_context_len, optgqa_dtype dtype,
+                                  int max_blocks_per_seq, int max_context_len, int dtype,
                                   void *stream);
 
 /*
@@ -190,7 +192,7 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
                        int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                        int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
                        int64_t v_token_stride, void *workspace, size_t workspace_bytes,
-                       optgqa_dtype dtype, void *stream);
+                       int dtype, void *stream);
 
 /*
  * 8-bit KV cache (the paper's title and Section I pair quantisation with grouped-query attention
@@ -230,14 +232,14 @@ int optgqa_reshape_and_cache_fp8(const void *k, const void *v, void *k_cache, vo
                                  const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
                                  int head_dim, int block_size, int64_t k_token_stride,
                                  int64_t v_token_stride, float k_scale, float v_scale,
-                                 optgqa_dtype dtype, void *stream);
+                                 int dtype, void *stream);
 
 int optgqa_paged_attention_fp8(void *out, const void *q, const void *k_cache, const void *v_cache,
                                const int32_t *block_tables, const int32_t *context_lens,
                                const float *alibi_slopes, float scale, float k_scale, float v_scale,
                                int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                                int block_size, int max_blocks_per_seq, int max_context_len,
-                               void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                               void *workspace, size_t workspace_bytes, int dtype,
                                void *stream);
 
 int optgqa_decode_step_fp8(void *out, const void *q, const void *k_new, const void *v_new,
@@ -246,14 +248,14 @@ int optgqa_decode_step_fp8(void *out, const void *q, const void *k_new, const vo
                            float k_scale, float v_scale, int num_seqs, int num_heads,
                            int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                            int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
-                           void *workspace, size_t workspace_bytes, optgqa_dtype dtype, void *stream);
+                           void *workspace, size_t workspace_bytes, int dtype, void *stream);
 
 int optgqa_paged_prefill_fp8(void *out, const void *q, const void *k_cache, const void *v_cache,
                              const int32_t *block_tables, const int32_t *context_lens,
                              const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
                              float k_scale, float v_scale, int num_seqs, int num_heads,
                              int num_kv_heads, int head_dim, int block_size,
-                             int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype,
+                             int max_blocks_per_seq, int max_q_len, int dtype,
                              void *stream);
 
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
@@ -282,7 +284,7 @@ int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const vo
                          const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
                          int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                          int block_size, int max_blocks_per_seq, int max_q_len,
-                         optgqa_dtype dtype, void *stream);
+                         int dtype, void *stream);
 
 /*
  * Local attention (Alg. 1: when no ALiBi slopes are given the bias is built from "causal and
@@ -309,7 +311,7 @@ int optgqa_paged_attention_window(void *out, const void *q, const void *k_cache,
                                   float scale, int window, int num_seqs, int num_heads,
                                   int num_kv_heads, int head_dim, int block_size,
                                   int max_blocks_per_seq, int max_context_len, void *workspace,
-                                  size_t workspace_bytes, optgqa_dtype dtype, void *stream);
+                                  size_t workspace_bytes, int dtype, void *stream);
 
 int optgqa_decode_step_window(void *out, const void *q, const void *k_new, const void *v_new,
                               void *k_cache, void *v_cache, const int32_t *block_tables,
@@ -317,7 +319,7 @@ int optgqa_decode_step_window(void *out, const void *q, const void *k_new, const
                               int window, int num_seqs, int num_heads, int num_kv_heads,
                               int head_dim, int block_size, int max_blocks_per_seq,
                               int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
-                              void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                              void *workspace, size_t workspace_bytes, int dtype,
                               void *stream);
 
 int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, const void *v_cache,
@@ -325,7 +327,7 @@ int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, c
                                 const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
                                 int window, int num_seqs, int num_heads, int num_kv_heads,
                                 int head_dim, int block_size, int max_blocks_per_seq,
-                                int max_q_len, optgqa_dtype dtype, void *stream);
+                                int max_q_len, int dtype, void *stream);
 
 /*
  * Shared prefixes (Section III-B: cached key-value blocks are shared and reused across requests;
@@ -367,7 +369,7 @@ int optgqa_paged_attention_shared(void *out, const void *q, const void *k_cache,
                                   const int32_t *shared_blocks, const float *alibi_slopes, float scale,
                                   int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                                   int block_size, int max_blocks_per_seq, int max_context_len,
-                                  void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                                  void *workspace, size_t workspace_bytes, int dtype,
                                   void *stream);
 
 int optgqa_decode_step_shared(void *out, const void *q, const void *k_new, const void *v_new,
@@ -376,7 +378,7 @@ int optgqa_decode_step_shared(void *out, const void *q, const void *k_new, const
                               const float *alibi_slopes, float scale, int num_seqs, int num_heads,
                               int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                               int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
-                              void *workspace, size_t workspace_bytes, optgqa_dtype dtype,
+                              void *workspace, size_t workspace_bytes, int dtype,
                               void *stream);
 
 int optgqa_validate_shared_prefix_host(const int32_t *block_tables_host,
@@ -409,7 +411,7 @@ int optgqa_prompt_prefill(void *out, const void *q, const void *k, const void *v
                           const float *alibi_slopes, float scale, int num_seqs, int num_heads,
                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                           int max_seq_len, int64_t k_token_stride, int64_t v_token_stride,
-                          optgqa_dtype dtype, void *stream);
+                          int dtype, void *stream);
 
 /*
  * Diagnostic: un-page the cache (Section III-A: pages are only a re-arrangement of the
@@ -419,7 +421,7 @@ int optgqa_prompt_prefill(void *out, const void *q, const void *k, const void *v
 int optgqa_gather_kv(void *k_out, void *v_out, const void *k_cache, const void *v_cache,
                      const int32_t *block_tables, const int32_t *context_lens, int num_seqs,
                      int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                     int max_context_len, optgqa_dtype dtype, void *stream);
+                     int max_context_len, int dtype, void *stream);
 
 /*
  * Measurement aid, not part of the method: the decode kernels' memory access pattern with no

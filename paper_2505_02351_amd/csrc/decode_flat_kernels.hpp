@@ -617,7 +617,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // ---- leave the piece's partial result in slot u + s (s = v * Y + y): this lane holds dims
         // 16db + 4hg + v of column j16 ---------------------------------------------------------------
         const int64_t slot = (int64_t)u + (int64_t)v * Y + y;
-        if (j16 < CS) {
+        if (j16 < (SHARED && seg.shared ? CS : GH)) {          // (a shared prefix fills all 16 columns of its slots)
             const int64_t e0 = slot * CS + j16;
             if (hg == 0) {
                 p.ws_m[e0] = m_ref;

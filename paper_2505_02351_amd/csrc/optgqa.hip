@@ -451,7 +451,7 @@ const char* optgqa_status_string(int status)
 int optgqa_reshape_and_cache(const void* k, const void* v, void* k_cache, void* v_cache,
                              const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
                              int head_dim, int block_size, int64_t k_token_stride,
-                             int64_t v_token_stride, optgqa_dtype dtype, void* stream)
+                             int64_t v_token_stride, int dtype, void* stream)
 {
     if (num_tokens < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
@@ -670,11 +670,11 @@ int optgqa_paged_attention(void* out, const void* q, const void* k_cache, const 
                            const float* alibi_slopes, float scale, int num_seqs, int num_heads,
                            int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                            int max_context_len, int partition_size, void* workspace,
-                           size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+                           size_t workspace_bytes, int dtype, void* stream)
 {
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          partition_size, workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream),
+                          partition_size, workspace, workspace_bytes, dtype, static_cast<hipStream_t>(stream),
                           nullptr);
 }
 
@@ -682,7 +682,7 @@ int optgqa_paged_attention_static(void* out, const void* q, const void* k_cache,
                                   const int32_t* block_tables, const int32_t* context_lens,
                                   const float* alibi_slopes, float scale, int num_seqs, int num_heads,
                                   int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                                  int max_context_len, optgqa_dtype dtype, void* stream)
+                                  int max_context_len, int dtype, void* stream)
 {
     // the split the library would choose for these sizes must fit the static scratch: no silent
     // fall-back to the unsplit kernel here
@@ -697,7 +697,7 @@ int optgqa_paged_attention_static(void* out, const void* q, const void* k_cache,
     // reads for a non-empty sequence is written by the streaming kernel of the same call.
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len, 0,
-                          scratch, (size_t)OPTGQA_STATIC_SCRATCH_BYTES, (int)dtype,
+                          scratch, (size_t)OPTGQA_STATIC_SCRATCH_BYTES, dtype,
                           static_cast<hipStream_t>(stream), nullptr);
 }
 
@@ -705,7 +705,7 @@ int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, vo
                                  const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
                                  int head_dim, int block_size, int64_t k_token_stride,
                                  int64_t v_token_stride, float k_scale, float v_scale,
-                                 optgqa_dtype dtype, void* stream)
+                                 int dtype, void* stream)
 {
     if (num_tokens < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
@@ -737,12 +737,12 @@ int optgqa_paged_attention_fp8(void* out, const void* q, const void* k_cache, co
                                const float* alibi_slopes, float scale, float k_scale, float v_scale,
                                int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                                int block_size, int max_blocks_per_seq, int max_context_len,
-                               void* workspace, size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+                               void* workspace, size_t workspace_bytes, int dtype, void* stream)
 {
     const float kv_scales[2] = {k_scale, v_scale};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), nullptr, kv_scales);
 }
 
@@ -751,12 +751,12 @@ int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* 
                        const float* alibi_slopes, float scale, int num_seqs, int num_heads,
                        int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                        int max_context_len, int64_t k_token_stride, int64_t v_token_stride,
-                       void* workspace, size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+                       void* workspace, size_t workspace_bytes, int dtype, void* stream)
 {
     const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len, 0,
-                          workspace, workspace_bytes, (int)dtype, static_cast<hipStream_t>(stream), &step);
+                          workspace, workspace_bytes, dtype, static_cast<hipStream_t>(stream), &step);
 }
 
 int optgqa_paged_attention_window(void* out, const void* q, const void* k_cache, const void* v_cache,
@@ -764,12 +764,12 @@ int optgqa_paged_attention_window(void* out, const void* q, const void* k_cache,
                                   const float* alibi_slopes, float scale, int window, int num_seqs,
                                   int num_heads, int num_kv_heads, int head_dim, int block_size,
                                   int max_blocks_per_seq, int max_context_len, void* workspace,
-                                  size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+                                  size_t workspace_bytes, int dtype, void* stream)
 {
     if (window <= 0) return OPTGQA_ERR_SHAPE;
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), nullptr, nullptr, window);
 }
 
@@ -779,13 +779,13 @@ int optgqa_decode_step_window(void* out, const void* q, const void* k_new, const
                               int num_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
                               int64_t v_token_stride, void* workspace, size_t workspace_bytes,
-                              optgqa_dtype dtype, void* stream)
+                              int dtype, void* stream)
 {
     if (window <= 0) return OPTGQA_ERR_SHAPE;
     const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), &step, nullptr, window);
 }
 
@@ -795,13 +795,13 @@ int optgqa_decode_step_fp8(void* out, const void* q, const void* k_new, const vo
                            int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                            int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
                            int64_t v_token_stride, void* workspace, size_t workspace_bytes,
-                           optgqa_dtype dtype, void* stream)
+                           int dtype, void* stream)
 {
     const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
     const float kv_scales[2] = {k_scale, v_scale};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), &step, kv_scales);
 }
 
@@ -828,12 +828,12 @@ int optgqa_paged_attention_shared(void* out, const void* q, const void* k_cache,
                                   const int32_t* shared_blocks, const float* alibi_slopes, float scale,
                                   int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                                   int max_blocks_per_seq, int max_context_len, void* workspace,
-                                  size_t workspace_bytes, optgqa_dtype dtype, void* stream)
+                                  size_t workspace_bytes, int dtype, void* stream)
 {
     if (!shared_blocks && num_seqs > 0) return OPTGQA_ERR_NULL;
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), nullptr, nullptr, 0, shared_blocks);
 }
 
@@ -843,13 +843,13 @@ int optgqa_decode_step_shared(void* out, const void* q, const void* k_new, const
                               int num_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
                               int64_t v_token_stride, void* workspace, size_t workspace_bytes,
-                              optgqa_dtype dtype, void* stream)
+                              int dtype, void* stream)
 {
     if (!shared_blocks && num_seqs > 0) return OPTGQA_ERR_NULL;
     const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
-                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, (int)dtype,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
                           static_cast<hipStream_t>(stream), &step, nullptr, 0, shared_blocks);
 }
 
@@ -882,7 +882,7 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
                         const int32_t* block_tables, const int32_t* context_lens,
                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
-                        int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream,
+                        int max_blocks_per_seq, int max_q_len, int dtype, void* stream,
                         const float* kv_scales, int window = 0)
 {
     if (kv_scales && (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f))
@@ -924,7 +924,7 @@ int optgqa_paged_prefill(void* out, const void* q, const void* k_cache, const vo
                          const int32_t* block_tables, const int32_t* context_lens,
                          const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                          int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
-                         int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype, void* stream)
+                         int max_blocks_per_seq, int max_q_len, int dtype, void* stream)
 {
     return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
                         num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
@@ -936,7 +936,7 @@ int optgqa_paged_prefill_fp8(void* out, const void* q, const void* k_cache, cons
                              const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                              float k_scale, float v_scale, int num_seqs, int num_heads,
                              int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                             int max_q_len, optgqa_dtype dtype, void* stream)
+                             int max_q_len, int dtype, void* stream)
 {
     const float kv_scales[2] = {k_scale, v_scale};
     return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
@@ -948,7 +948,7 @@ int optgqa_paged_prefill_window(void* out, const void* q, const void* k_cache, c
                                 const int32_t* block_tables, const int32_t* context_lens,
                                 const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                                 int window, int num_seqs, int num_heads, int num_kv_heads, int head_dim,
-                                int block_size, int max_blocks_per_seq, int max_q_len, optgqa_dtype dtype,
+                                int block_size, int max_blocks_per_seq, int max_q_len, int dtype,
                                 void* stream)
 {
     if (window <= 0) return OPTGQA_ERR_SHAPE;
@@ -961,7 +961,7 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
                           const int32_t* block_tables, const int32_t* cu_seq_lens, const float* alibi_slopes,
                           float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                           int block_size, int max_blocks_per_seq, int max_seq_len, int64_t k_token_stride,
-                          int64_t v_token_stride, optgqa_dtype dtype, void* stream)
+                          int64_t v_token_stride, int dtype, void* stream)
 {
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || max_seq_len < 0)
         return OPTGQA_ERR_SHAPE;
@@ -1028,7 +1028,7 @@ int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_byte
 int optgqa_gather_kv(void* k_out, void* v_out, const void* k_cache, const void* v_cache,
                      const int32_t* block_tables, const int32_t* context_lens, int num_seqs,
                      int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                     int max_context_len, optgqa_dtype dtype, void* stream)
+                     int max_context_len, int dtype, void* stream)
 {
     if (num_seqs < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 || max_blocks_per_seq <= 0 ||
         max_context_len < 0)

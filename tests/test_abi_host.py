@@ -272,3 +272,49 @@ def test_non_finite_scale_is_refused(G):
                                         None) == -2
         assert lib.optgqa_prompt_prefill(one, one, one, one, None, None, None, one, None, bad, 2, 8, 2, 128, 16, 8, 4,
                                          256, 256, 0, None) == -2
+
+
+def test_shared_prefix_host_checks(G):
+    """Bundle size, workspace size and the host validator of the shared-prefix entry points, and their
+    argument errors (nothing here reaches the GPU)."""
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)
+    assert G.shared_prefix_bundle(32, 4, 128) == 2          # group 8
+    assert G.shared_prefix_bundle(32, 8, 128) == 4          # group 4
+    assert G.shared_prefix_bundle(8, 8, 128) == 16          # multi-head
+    assert G.shared_prefix_bundle(12, 2, 128) == 2          # group 6: 12 of the 16 columns
+    assert G.shared_prefix_bundle(40, 2, 128) == 1          # group 20 -> 10 heads per pass
+    assert lib.optgqa_shared_prefix_bundle(32, 5, 128) == -2
+    assert lib.optgqa_shared_prefix_bundle(32, 4, 64) == -3
+    plain, _ = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, G.SPLIT_BALANCED)
+    shared = G.shared_prefix_workspace_bytes(64, 32, 4, 128, 32, 8192)
+    assert shared > plain > 0                               # twice the segments, 16 columns per slot
+    assert G.shared_prefix_workspace_bytes(64, 32, 4, 64, 32, 8192) == 0
+    # entry points: head_dim 64, missing workspace, missing table
+    f = lib.optgqa_paged_attention_shared
+    args = lambda D=128, sb=one, ws=one, wsb=1 << 30: (one, one, one, one, one, one, sb, None, 0.1, 2, 8, 2, D, 16, 8, 128,
+                                                       ws, wsb, 0, None)
+    assert f(*args(D=64)) == -3
+    assert f(*args(sb=None)) == -1
+    assert f(*args(ws=None, wsb=0)) == -4
+    g = lib.optgqa_decode_step_shared
+    assert g(one, one, one, one, one, one, one, one, None, None, 0.1, 2, 8, 2, 128, 16, 8, 128, 256, 256, one, 1 << 30,
+             0, None) == -1
+    # validator: two bundles of two, block size 4
+    bt = np.array([[5, 6, 7, 8], [5, 6, 9, 10], [1, 2, 3, 4], [1, 11, 12, 13]], np.int32)
+    cl = np.array([14, 13, 16, 9], np.int32)
+    ok = np.array([0, 2, 0, 1], np.int32)
+    v = lambda sb, new=1, bundle=2, lens=cl: G.validate_shared_prefix_host(bt, lens, np.asarray(sb, np.int32), 4, bundle, new)
+    assert v(ok) == 0
+    assert v([0, 3, 0, 1]) == -6                  # third block differs from the leader's
+    assert v([1, 2, 0, 1]) == -6                  # a leader cannot share
+    assert v([0, 2, 0, 3]) == -6                  # 3 blocks = 12 tokens > 9 - 1 cached
+    assert v([0, 2, 0, 2]) == -6                  # second block differs
+    assert v([0, -1, 0, 0]) == -6
+    assert v([0, 0, 0, 0]) == 0
+    assert v(ok, lens=np.array([14, 8, 16, 9], np.int32)) == -6      # 2 blocks = 8 tokens > 8 - 1 cached
+    assert v(ok, new=0, lens=np.array([14, 8, 16, 9], np.int32)) == 0
+    assert v(ok, bundle=4) == -6                  # sequence 3 would then share with sequence 0
+    assert lib.optgqa_validate_shared_prefix_host(None, None, None, 0, 4, 4, 2, 1) == 0
+    assert lib.optgqa_validate_shared_prefix_host(None, one, one, 2, 4, 4, 2, 1) == -1
+    assert lib.optgqa_validate_shared_prefix_host(one, one, one, 2, 4, 4, 0, 1) == -2
