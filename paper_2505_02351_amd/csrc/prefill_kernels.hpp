@@ -36,12 +36,32 @@
 //   bf16: 8 significant bits are not enough for the 1e-2 output budget once the output itself is
 //         rounded to bf16 (measured: 1.003e-2), so each weight is split into a bf16 head and a
 //         bf16 tail and the contraction runs twice; bf16's range allows the wide lazy reference.
+//
+// Key order.  Without a window the tiles are walked from the diagonal BACKWARDS (newest keys
+// first).  With ALiBi the bias falls as the walk goes on, so the softmax reference that the first
+// tiles set stays valid (walking forwards, steep heads push it up every other tile and the
+// accumulators are rescaled each time), and a tile can be judged against what has already been
+// summed: when, for every row of the wave, the largest weight of the tile is below 2^-24 of the
+// row's sum so far - half an ulp of that fp32 sum, a fact read off the scores, not assumed from
+// the slopes - the tile's exponentials, weight packing and output MFMAs are skipped.  Each dropped
+// weight is one that an fp32 "sum += w" would have rounded away by itself; a tile drops at most
+// 32 of them per row (2^-19 of the row sum), and since skipping only sets in where the weights
+// keep falling, the total stays within a few 2^-19 - three orders of magnitude below the compute
+// budget of the stated tolerance.  (The definition, eq. (3)-(4), still sums every key; heads with a
+// steep slope simply give most keys a weight that no fp32 sum can see.)
 #pragma once
 #include <type_traits>
 
 #include "decode_mma_kernels.hpp"
 
 namespace optgqa {
+
+// log2 of the fraction of a row's running sum below which a whole tile's weights are dropped
+// (half an ulp of an fp32 sum)
+#ifndef OPTGQA_PF_SKIP_LOG2
+#define OPTGQA_PF_SKIP_LOG2 (-24.f)
+#endif
+constexpr float kPfSkipLog2 = OPTGQA_PF_SKIP_LOG2;
 
 struct PrefillParams {
     void* out;                  // [T][Hq][D] dtype
@@ -128,6 +148,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
 {
     static_assert(WAVES == 4 || (WAVES == 8 && !WIN), "4 waves, or 8 without a window");
     constexpr int kPfWaves = WAVES, kPfRows = WAVES * 32;
+    constexpr bool REV = !WIN;                          // walk the key tiles from the diagonal backwards
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
     static_assert(!(KV8 && D != 128), "8-bit caches: head_dim 128");
@@ -144,23 +165,29 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     // ---- which rows -----------------------------------------------------------------------
     // XCD-aware order: workgroups go to XCD (flat id % 8); all query tiles of one (sequence, KV
     // head) unit are given the same residue so that its K/V stay in one XCD's L2.
-    // Longest first: a later query tile sees more keys, and the hardware hands workgroups to free
-    // slots in id order, so the last query tiles of all units come first and the shortest
-    // workgroups fill the tail of the launch.
-    // (with a window all workgroups are about equally long, and keeping a unit's query tiles together
-    // is worth more: 3 % measured)
+    // Longest first: the hardware hands workgroups to free slots in id order, so the workgroups that
+    // will run longest should have the lowest ids and the short ones fill the tail of the launch.
+    // A later query tile sees more keys; and, walking backwards from the diagonal, a head with a
+    // steep ALiBi slope skips most of its tiles while one with a shallow slope skips none - slopes
+    // fall with the head number in every usual recipe, so the units are taken from the last KV head
+    // down (a wrong guess costs nothing but the order).  Consecutive units, which then share a KV
+    // head, are dealt to different XCDs (rotation by the row of eight).
+    // (with a window all workgroups are about equally long, and the plain unit order is kept)
     const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
-    const int units8 = (p.units + 7) >> 3;
-    const int qt = WIN ? w % p.q_tiles : p.q_tiles - 1 - w / units8;
-    const int unit = (WIN ? w / p.q_tiles : w % units8) * 8 + xcd;
-    if (unit >= p.units) return;
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
     const int GH = p.heads_per_wg, gshift = p.heads_pow2_shift;
     const int G = Hq / Hkv, chunks = G / GH;
     const int units_per_seq = Hkv * chunks;
-    const int b = unit / units_per_seq;
-    const int gu = unit - b * units_per_seq;
+    // (without slopes nothing is skipped and only the query tile decides the length: query tiles first)
+    const bool by_head = !WIN && p.slopes != nullptr;
+    const int units8 = (p.units + 7) >> 3;
+    const int urow = WIN || by_head ? w / p.q_tiles : w % units8;
+    const int qt = WIN ? w % p.q_tiles : p.q_tiles - 1 - (by_head ? w % p.q_tiles : w / units8);
+    const int ui = urow * 8 + (WIN ? xcd : (xcd - urow) & 7);
+    if (ui >= p.units) return;
+    const int b = by_head ? ui % p.num_seqs : ui / units_per_seq;
+    const int gu = by_head ? units_per_seq - 1 - ui / p.num_seqs : ui - b * units_per_seq;
     const int g = gu / chunks;
     const int h0 = g * G + (gu - g * chunks) * GH;
     const int tokens_per_wg = kPfRows >> gshift;
@@ -270,21 +297,27 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     typedef typename std::conditional<KV8, u32x2, u32x4>::type StageT;   // 8 elements of one key
     StageT stage[kKPT];
     const int last_tile = ntiles - 1;                             // >= kt0
-    auto load_blk = [&](int t) __attribute__((always_inline)) {
+    const int nt = ntiles - kt0;                                  // tiles this workgroup walks
+    // the i-th tile of the walk (i past the end: the last one again)
+    auto tile_of = [&](int i) __attribute__((always_inline)) {
+        const int ic = min(i, nt - 1);
+        return REV ? last_tile - ic : kt0 + ic;
+    };
+    auto load_blk = [&](int i) __attribute__((always_inline)) {
         // the keys of a group share a block (groups are aligned, clamping keeps the block)
         if (CONTIG) return 0;
-        const int key = min(min(t, last_tile) * kPfKeys + kKPT * l_group, kmax - 1);
+        const int key = min(tile_of(i) * kPfKeys + kKPT * l_group, kmax - 1);
         return table[key >> bs_shift];
     };
-    int blk_next = load_blk(kt0);
+    int blk_next = load_blk(0);
 
     // (address arithmetic kept short on purpose - this loop pays for every instruction: one 64-bit
     // multiply-add for the block, one shift-add for the first row, then per key a clamp and a shift-add;
     // rows past the sequence's last key re-read that key, which lies in the same block)
     const unsigned char* const l_lane = l_src + 8 * l_chunk * ES;                 // this lane's column piece
     const uint32_t l_blk_bytes = (uint32_t)(block_stride * ES);                   // < 2^32: one block of all KV heads
-    auto fetch_tile = [&](StageT (&stage)[kKPT], int t) __attribute__((always_inline)) {
-        const int key0 = min(min(t, last_tile) * kPfKeys + kKPT * l_group, kmax - 1);
+    auto fetch_tile = [&](StageT (&stage)[kKPT], int i) __attribute__((always_inline)) {
+        const int key0 = min(tile_of(i) * kPfKeys + kKPT * l_group, kmax - 1);
         const int rmax = kmax - 1 - key0;                         // >= 0; < kKPT - 1 only at the sequence's end
         const unsigned char* base;
         if (CONTIG) base = l_lane + (uint64_t)(uint32_t)key0 * (uint32_t)l_row;
@@ -292,9 +325,9 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
 #pragma unroll
         for (int j = 0; j < kKPT; ++j)
             stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
-        blk_next = load_blk(t + 1);
+        blk_next = load_blk(i + 1);
     };
-    // A tile's place in LDS: tile number j (counted from the first tile read) sits in buffer j % 2.
+    // A tile's place in LDS: the j-th tile of the walk sits in buffer j % 2.
     auto tile_base = [&](int j) __attribute__((always_inline)) { return (j & 1) * kBuf; };
     auto tile_base_v = [&](int j) __attribute__((always_inline)) { return (j & 1) * kBuf + kKTile; };
     auto store_tile = [&](const StageT (&stage)[kKPT], int buf) __attribute__((always_inline)) {
@@ -324,7 +357,8 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         }
         return st;
     };
-    auto softmax_pv = [&](int kt, int buf, f32x16 st, auto masked) __attribute__((always_inline)) {
+    // kt: the tile's number along the context; buf: its number in the walk (LDS buffer buf % 2)
+    auto softmax_pv = [&](int kt, int buf, bool first_of_walk, f32x16 st, auto masked) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked)::value;
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
         // x = score - reference, formed directly: st*scale2 + slope2*key + (-slope2*pos - m_ref)
@@ -344,9 +378,17 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         float mx = x[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, x[e]);
-        // Has the row seen a key yet?  Plain causal rows all see key 0 in tile 0, so there the
-        // answer is wave-uniform; with a window a row's first visible key may lie in a later tile.
-        const bool first = WIN ? !started : kt == 0;
+        if constexpr (REV) {
+            // Walking backwards, the weights of a tile can be judged against what is already summed:
+            // below 2^kPfSkipLog2 of the row's sum (this lane's half of it, which is no more) for
+            // every row of the wave, the tile changes no bit that the accumulators keep.
+            const float room = __builtin_amdgcn_logf(lsum) + kPfSkipLog2;        // log2; -inf before the row's first key
+            if (__builtin_amdgcn_ballot_w64(mx > room) == 0) return;
+        }
+        // Has the row seen a key yet?  Walking forwards without a window every row sees key 0 in the
+        // first tile, so there the answer is wave-uniform; with a window, or walking backwards from the
+        // diagonal, a row's first visible key may lie in a later tile of the walk.
+        const bool first = (WIN || REV) ? !started : first_of_walk;
         if (__builtin_amdgcn_ballot_w64(first || mx > PfSoftmax<DT>::kThreshold) != 0) {
             mx = fmaxf(mx, __shfl_xor(mx, 32));                  // the row's keys live in 2 lanes (h2)
             // The first keys a row sees put its reference kHeadroom above their maximum, wherever
@@ -356,7 +398,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
             const float delta = first ? (sees ? mx + PfSoftmax<DT>::kHeadroom : 0.f)
                                       : fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
             const float alpha = first ? 1.f : fast_exp2(-delta);
-            if (WIN) started = started || sees;
+            if (WIN || REV) started = started || sees;
             m_ref += delta;
             lsum *= alpha;
 #pragma unroll
@@ -384,6 +426,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
                 lsum += widen_lo<DT>(hi) + widen_hi<DT>(hi);
             }
         }
+
         // ---- O^T += V^T P^T ---------------------------------------------------------------------
         // A = V^T for dims 32db .. +31: this lane is dim 32db + n32 and needs keys 16m + 4h2 + (0..3)
         // and 16m + 8 + 4h2 + (0..3).  One transposing load hands each group of 16 lanes 4 keys x
@@ -408,58 +451,64 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
 
     const int pos_min = pos0 + tq0;                             // tiles ending at or below it need no causal mask
 
-    // Software pipeline: the score MFMAs of tile j + 1 are issued before the softmax of tile j, so
-    // that the matrix pipe has work while the vector ALU does the exponentials (measured: 3 % on
-    // the kernel).  For that the K tiles run one tile ahead of the V tiles: at the start of tile j,
-    // K tiles j and j + 1 and V tile j are in LDS, K tile j + 2 and V tile j + 1 are on their way to
-    // registers.  Prologue:
-    fetch_tile(stage, kt0);
+    // Software pipeline: the score MFMAs of the walk's next tile are issued before the softmax of the
+    // current one, so that the matrix pipe has work while the vector ALU does the exponentials
+    // (measured: 3 % on the kernel).  For that the K tiles run one tile ahead of the V tiles: at the
+    // start of step j, K tiles j and j + 1 and V tile j are in LDS, K tile j + 2 and V tile j + 1 are
+    // on their way to registers.  Prologue:
+    fetch_tile(stage, 0);
     store_tile(stage, 0);
     if (k_loader) {                                              // wave-uniform
-        fetch_tile(stage, kt0 + 1);
+        fetch_tile(stage, 1);
         store_tile(stage, 1);
     }
-    fetch_tile(stage, kt0 + 1 + l_ahead);
+    fetch_tile(stage, 1 + l_ahead);
     __syncthreads();
     f32x16 st_next = scores(0);
-    __syncthreads();                                             // buffer 0's K tile is overwritten during tile 0
+    __syncthreads();                                             // buffer 0's K tile is overwritten during step 0
     // Tiles wholly inside every row's visible range need no mask: those that end at or below the
     // first row's position (causal side) and start at or above the last row's window start.
     const int n_unmasked = min(ntiles, max(0, (pos_min + 1) / kPfKeys));
     const int n_window_cut = W > 0 ? (max(kmax - W, 0) + kPfKeys - 1) / kPfKeys : 0;
-    // (three plain loops rather than one with a branch in it, and no branch around the stores: the
+    // (plain loops rather than one with a branch in it, and no branch around the stores: the
     // compiler schedules a loop whose body is one straight line far better)
-    // While tile j is computed, K tile j + 2 / V tile j + 1 (fetched one step earlier) go into the
-    // buffers that tile j - 1 used and the next ones are fetched; the waves meet after every tile.
-    // The last tile's look-ahead scores read a stale K buffer and are never used; stores past the
+    // While step j is computed, K tile j + 2 / V tile j + 1 (fetched one step earlier) go into the
+    // buffers that step j - 1 used and the next ones are fetched; the waves meet after every step.
+    // The last step's look-ahead scores read a stale K buffer and are never used; stores past the
     // last tile put the clamped re-read of it into a buffer nobody reads again.
-    // (two tiles per trip with the two score registers swapping roles, so that no trip copies the
+    // (two steps per trip with the two score registers swapping roles, so that no trip copies the
     // look-ahead scores into place)
     f32x16 st_other;
-    auto one_tile = [&](int kt, const f32x16& st_cur, f32x16& st_ahead, auto masked) __attribute__((always_inline)) {
-        const int j = kt - kt0;
+    auto one_tile = [&](int j, const f32x16& st_cur, f32x16& st_ahead, auto masked) __attribute__((always_inline)) {
         st_ahead = scores(j + 1);
-        softmax_pv(kt, j, st_cur, masked);
+        softmax_pv(REV ? last_tile - j : kt0 + j, j, j == 0, st_cur, masked);
         store_tile(stage, j + 1 + l_ahead);
-        fetch_tile(stage, kt + 2 + l_ahead);
+        fetch_tile(stage, j + 2 + l_ahead);
         __syncthreads();
     };
+    // steps [from, to) of the walk
     auto run_tiles = [&](int from, int to, auto masked) __attribute__((always_inline)) {
-        int kt = from;
-        for (; kt + 1 < to; kt += 2) {
-            one_tile(kt, st_next, st_other, masked);
-            one_tile(kt + 1, st_other, st_next, masked);
+        int j = from;
+        for (; j + 1 < to; j += 2) {
+            one_tile(j, st_next, st_other, masked);
+            one_tile(j + 1, st_other, st_next, masked);
         }
-        if (kt < to) {
-            one_tile(kt, st_next, st_other, masked);
+        if (j < to) {
+            one_tile(j, st_next, st_other, masked);
             st_next = st_other;
         }
     };
     const int cut_end = max(kt0, min(n_window_cut, n_unmasked));   // tiles cut by some row's window start
     const int plain_end = max(cut_end, n_unmasked);                // tiles no mask touches
-    if (WIN) run_tiles(kt0, cut_end, std::true_type{});
-    run_tiles(cut_end, plain_end, std::false_type{});
-    run_tiles(plain_end, ntiles, std::true_type{});
+    if constexpr (REV) {
+        // from the diagonal backwards: the tiles the causal mask cuts come first
+        run_tiles(0, ntiles - plain_end, std::true_type{});
+        run_tiles(ntiles - plain_end, nt, std::false_type{});
+    } else {
+        run_tiles(0, cut_end - kt0, std::true_type{});
+        run_tiles(cut_end - kt0, plain_end - kt0, std::false_type{});
+        run_tiles(plain_end - kt0, nt, std::true_type{});
+    }
 
     // ---- normalise and write: this lane holds dims 32db + 8i + 4h2 + (0..3) of its row -----------
     uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);
