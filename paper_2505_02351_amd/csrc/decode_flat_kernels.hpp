@@ -143,6 +143,7 @@ struct FlatSeg {
     int shared;             // (an int: a struct with padding bytes does not stay in registers)
 };
 
+
 template <bool FUSED, bool KV8, bool SHARED, bool UNIFORM>
 __device__ __forceinline__ FlatSeg flat_seg(const DecodeParams& p, int v)
 {
@@ -193,15 +194,25 @@ __device__ __forceinline__ FlatSeg flat_seg(const DecodeParams& p, int v)
 // values on its way into the LDS copy.  Not combined with FUSED.
 //
 // SHARED: shared prefixes are read once per bundle of sequences (above).  2-byte caches, no window.
+//
+// PARTS: fixed partitions (Section III-A: the context is cut into partitions of a given size whose
+// results are merged) on the equal-work machinery: pieces end where a unit or a segment ends AND
+// at every multiple of part_tiles tiles inside a segment, so no piece spans two partitions.  The
+// waves still stream equal shares, with the prefetch chained from one partition to the next.  A
+// unit is at least one partition long, so a unit boundary cuts a partition into at most two
+// fragments: partition pi of segment (b, y) leaves its partial results in slots
+// ((b * Y + y) * num_partitions + pi) * 2 + (0: the fragment that starts the partition, 1: the
+// rest, if a unit boundary fell inside).  Plain attention over 2-byte caches only.
 struct MmaTile8 {
     uint4 k[2];     // K: token j16, dims 64j + 16hg .. +15
     uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
 };
 
-template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false>
+template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false>
 __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
     static_assert(!(SHARED && KV8), "shared prefixes: 2-byte caches");
+    static_assert(!(PARTS && (FUSED || KV8 || SHARED)), "fixed partitions: plain attention over 2-byte caches");
     constexpr bool NEW_TILE = FUSED && !KV8;            // the new token is a tile of its own, read from k_new / v_new
     typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
@@ -228,6 +239,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const int u = blockIdx.x * kDecodeWaves + wave;
     const int32_t* __restrict__ ctx = p.context_lens;
     const int W = p.window;
+    const int tp = PARTS ? p.part_tiles : 0;            // tiles per fixed partition
 
     // ---- where does this unit start?  level 1: lane i sums the tiles of sequences [i*k, (i+1)*k)
     const int k = (NV + 63) >> 6;
@@ -244,7 +256,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const int incl = wave_inclusive_scan(mine, lane);
     const int P_total = __builtin_amdgcn_readlane(incl, 63);
     const int T = Y * P_total;
-    const int c = max(1, (T + p.num_units - 1) / p.num_units);
+    const int c = max(PARTS ? tp : 1, (T + p.num_units - 1) / p.num_units);     // (PARTS: at least one partition)
     const int f0 = u * c;
     const int f1 = min(f0 + c, T);
     if (f0 >= f1) return;                                   // no workgroup-wide barrier below
@@ -409,7 +421,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // ---- one piece: tiles [tau, tau_end) of segment (v, y) -------------------------------
         const int n = seg.n, L = seg.L, lo = seg.lo;
         const bool has_new = NEW_TILE && !(SHARED && seg.shared);   // the segment's last tile is the new token
-        const int tau_end = min(n, tau + (f1 - f));
+        // (PARTS: a piece also ends where its partition ends)
+        const int tau_end = min(PARTS ? min(n, (tau / tp + 1) * tp) : n, tau + (f1 - f));
         const int ntw = tau_end - tau;                      // >= 1
         const int j_last = ntw - 1;
         const int Lm1 = L - 1;
@@ -447,10 +460,13 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // ---- the piece after this one (same unit), so that its first tile is on its way before this
         // piece ends.  Without one, the spare prefetch slot re-reads this piece's last tile (a cache
         // hit, never consumed).
-        bool has_next = f + ntw < f1;                        // then this piece ends its segment
+        bool has_next = f + ntw < f1;                        // (not PARTS: then this piece ends its segment)
         int nv = v, ny = y;
+        int ntau = 0;                                        // first tile of the next piece in its segment
         FlatSeg nseg = seg;
-        if (has_next) {
+        if (PARTS && has_next && tau_end < n) {
+            ntau = tau_end;                                  // the next partition of the same segment
+        } else if (has_next) {
             if (++ny == Y) {
                 ny = 0;
                 do {                                         // skip sequences without tiles
@@ -467,7 +483,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // (nothing follows) this piece's last one again
         const int nn = nseg.n;
         const bool n_has_new = NEW_TILE && !(SHARED && nseg.shared);
-        const int n_tau_end = min(nn, f1 - (f + ntw));
+        const int n_tau_end = min(PARTS ? min(nn, (ntau / tp + 1) * tp) : nn, ntau + f1 - (f + ntw));
         const int32_t* x_table = has_next ? p.block_tables + (int64_t)nseg.tb * p.max_blocks_per_seq : table;
         const int64_t x_head_off = has_next ? (int64_t)(ny / chunks) * bs * D : head_off;
         const int x_L = has_next ? nseg.L : L, x_n = has_next ? nn : n, x_lo = has_next ? nseg.lo : lo;
@@ -477,7 +493,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
                               : min(nseg.hi, ((n_has_new && n_tau_end == nn ? n_tau_end - 1 : n_tau_end) + n_first) * TILE);
         const int64_t x_new_k = !has_next ? new_k : NEW_TILE ? nseg.b * p.k_new_stride + (int64_t)(ny / chunks) * D : 0;
         const int64_t x_new_v = !has_next ? new_v : NEW_TILE ? nseg.b * p.v_new_stride + (int64_t)(ny / chunks) * D : 0;
-        const int x_ti = has_next ? 0 : tau + j_last;
+        const int x_ti = has_next ? ntau : tau + j_last;
 
         // ---- both contractions on 16-bit MFMAs, transposed so that nothing is transposed in registers:
         //   S^T[token][head] = K Q^T : A = the K tile as fetched (lane (token j16, slab hg)), B = the query
@@ -616,7 +632,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 
         // ---- leave the piece's partial result in slot u + s (s = v * Y + y): this lane holds dims
         // 16db + 4hg + v of column j16 ---------------------------------------------------------------
-        const int64_t slot = (int64_t)u + (int64_t)v * Y + y;
+        const int64_t slot = PARTS ? ((((int64_t)v * Y + y) * p.num_partitions + tau / tp) << 1) + (tau % tp != 0)
+                                   : (int64_t)u + (int64_t)v * Y + y;
         if (j16 < (SHARED && seg.shared ? CS : GH)) {          // (a shared prefix fills all 16 columns of its slots)
             const int64_t e0 = slot * CS + j16;
             if (hg == 0) {
@@ -632,8 +649,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         // ---- next piece ------------------------------------------------------------------------
         if (!has_next) break;
         f += ntw;
-        if (y + 1 == Y) P_v += n;                            // sequences skipped on the way have no tiles
-        v = nv, y = ny, seg = nseg, tau = 0;
+        if (ny != y || nv != v) {                            // the next piece starts a segment
+            if (y + 1 == Y) P_v += n;                        // sequences skipped on the way have no tiles
+        }
+        v = nv, y = ny, seg = nseg, tau = ntau;
         chained = true;
     }
 }
@@ -723,12 +742,16 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     bool any = false;                                        // something has been accumulated
     // the pieces of segment y of (virtual) sequence vv, which has n tiles per segment and tile prefix P
     auto collect = [&](int vv, int n, int P, int col) __attribute__((always_inline)) {
-        // (the clamps only matter if the lengths changed under the kernels: they keep every read
-        // inside the workspace; n == 0: nothing was streamed, nobody wrote the plan entry)
-        const int F0 = n > 0 ? Y * P + y * n : 0;
-        const int u0 = min(max(F0 / c, 0), p.num_units - 1);
-        const int np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
-        const int64_t base = ((int64_t)u0 + (int64_t)vv * Y + y) * CS + col;     // slot stride between units: CS
+        int np = 0;
+        int64_t base = 0;
+        {
+            // (the clamps only matter if the lengths changed under the kernels: they keep every read
+            // inside the workspace; n == 0: nothing was streamed, nobody wrote the plan entry)
+            const int F0 = n > 0 ? Y * P + y * n : 0;
+            const int u0 = min(max(F0 / c, 0), p.num_units - 1);
+            np = n > 0 ? min(max((F0 + n - 1) / c - u0 + 1, 1), p.num_units - u0) : 0;
+            base = ((int64_t)u0 + (int64_t)vv * Y + y) * CS + col;          // slot stride between units: CS
+        }
         for (int i0 = 0; i0 < np; i0 += 8) {
             float mm[8], ll[8];
             float4 x[8];
@@ -796,6 +819,108 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     uint2 packed;
     packed.x = narrow2<DT>(num.x * inv, num.y * inv);
     packed.y = narrow2<DT>(num.z * inv, num.w * inv);
+    *reinterpret_cast<uint2*>(o) = packed;
+}
+
+// Combine for fixed partitions run by the equal-work kernel (PARTS): head h of sequence b has two
+// slots per partition, ((b * Y + y) * num_partitions + pi) * 2 + fragment; fragment 0 (the piece that
+// starts the partition) always exists, fragment 1 only if a unit boundary - a multiple of c in the
+// flat order - fell strictly inside the partition.  One workgroup per (head, sequence): eight groups of
+// 32 threads (4 output dims each) take every eighth slot with all their loads in flight at once,
+// then the eight partial sums are merged through LDS - a long context has dozens of partitions and
+// a single chain of memory round trips over them would cost more than the streaming they merge.
+constexpr int kPartsReduceGroups = 8;
+
+template <int DT>
+__global__ __launch_bounds__(kPartsReduceGroups * 32) void paged_decode_parts_reduce_kernel(const DecodeParams p)
+{
+    constexpr int D = 128;
+    __shared__ float s_m[kPartsReduceGroups][32], s_den[kPartsReduceGroups][32];
+    __shared__ float4 s_num[kPartsReduceGroups][32];
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int l32 = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const int od = l32 * 4;
+    uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;
+    const int L = p.context_lens[b];
+    const int c = max(p.plan[p.num_seqs], 1), P = p.plan[b];          // readable garbage where nobody wrote them
+    if (L <= 0) {                                                      // (uniform over the workgroup)
+        if (grp == 0) *reinterpret_cast<uint2*>(o) = make_uint2(0u, 0u);
+        return;
+    }
+    const int GH = p.heads_per_wg;
+    const int G = p.num_heads / p.num_kv_heads;
+    const int chunks = G / GH;
+    const int g = h / G;
+    const int within = h - g * G;
+    const int chunk = within / GH;
+    const int hh = within - chunk * GH;
+    const int Y = p.segs_per_seq;
+    const int y = g * chunks + chunk;
+    const int tp = p.part_tiles;
+    const int n = flat_tiles<false>(L, 0);
+    const int parts = min((n + tp - 1) / tp, p.num_partitions);
+    const int64_t first = (((int64_t)b * Y + y) * p.num_partitions) << 1;
+    const int64_t F0 = (int64_t)Y * P + (int64_t)y * n;
+    float M = -INFINITY, den = 0.f;
+    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i0 = grp; i0 < 2 * parts; i0 += 8 * kPartsReduceGroups) {
+        float mm[8], ll[8];
+        float4 x[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = i0 + k * kPartsReduceGroups, pi = i >> 1;
+            const int64_t start = F0 + (int64_t)pi * tp, len = min(tp, n - pi * tp);
+            const bool there = i < 2 * parts && ((i & 1) == 0 || (start / c + 1) * c < start + len);
+            const int64_t e = (first + i) * GH + hh;
+            mm[k] = there ? p.ws_m[e] : -INFINITY;
+            ll[k] = there ? p.ws_l[e] : 0.f;
+            x[k] = there ? *reinterpret_cast<const float4*>(p.ws_o + e * D + od) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        float Mn = M;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
+        const float keep = Mn > -INFINITY ? fast_exp2(M - Mn) : 0.f;      // (M = -inf before the first slot: keep 0)
+        M = Mn;
+        den *= keep;
+        num.x *= keep;
+        num.y *= keep;
+        num.z *= keep;
+        num.w *= keep;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float fct = mm[k] > -INFINITY ? fast_exp2(mm[k] - M) : 0.f;
+            den = fmaf(fct, ll[k], den);
+            num.x = fmaf(fct, x[k].x, num.x);
+            num.y = fmaf(fct, x[k].y, num.y);
+            num.z = fmaf(fct, x[k].z, num.z);
+            num.w = fmaf(fct, x[k].w, num.w);
+        }
+    }
+    s_m[grp][l32] = M;
+    s_den[grp][l32] = den;
+    s_num[grp][l32] = num;
+    __syncthreads();
+    if (grp != 0) return;
+    float Mt = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kPartsReduceGroups; ++k) Mt = fmaxf(Mt, s_m[k][l32]);
+    float dt = 0.f;
+    float4 nt = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int k = 0; k < kPartsReduceGroups; ++k) {
+        const float mk = s_m[k][l32];
+        const float fct = mk > -INFINITY ? fast_exp2(mk - Mt) : 0.f;
+        const float4 nk = s_num[k][l32];
+        dt = fmaf(fct, s_den[k][l32], dt);
+        nt.x = fmaf(fct, nk.x, nt.x);
+        nt.y = fmaf(fct, nk.y, nt.y);
+        nt.z = fmaf(fct, nk.z, nt.z);
+        nt.w = fmaf(fct, nk.w, nt.w);
+    }
+    const float inv = p.out_scale / dt;
+    uint2 packed;
+    packed.x = narrow2<DT>(nt.x * inv, nt.y * inv);
+    packed.y = narrow2<DT>(nt.z * inv, nt.w * inv);
     *reinterpret_cast<uint2*>(o) = packed;
 }
 

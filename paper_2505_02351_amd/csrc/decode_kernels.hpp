@@ -55,6 +55,10 @@ struct DecodeParams {
     // entries of sequence b are the bundle leader's (sequence b - b % bundle), 0 that b shares nothing.
     const int32_t* shared_blocks;   // [num_seqs] or nullptr
     int bundle;                     // sequences whose heads fit the score tile together: 16 / heads_per_wg
+    // Fixed partitions through the equal-work kernel: pieces also end at every multiple of part_tiles
+    // tiles of 16 tokens (partition_size / 16) inside a segment, and num_partitions bounds the
+    // partitions of a segment; 0 = pieces end only where a unit or a segment ends.
+    int part_tiles;
 };
 
 // Sequence and number of visible keys of one output row (decode: row = sequence).

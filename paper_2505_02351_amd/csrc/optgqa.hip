@@ -145,10 +145,12 @@ struct SplitPlan {
     int partition_size;   // 0 = unsplit, OPTGQA_SPLIT_BALANCED = equal-work split
     int num_partitions;
     size_t bytes;
-    // equal-work split only
+    // equal-work kernel only (the equal-work split, and fixed partitions at head_dim 128)
     int workgroups;
     int segs_per_seq;
     size_t plan_floats, ml_floats;
+    int64_t slots;        // partial-result slots
+    bool flat;            // the equal-work kernel runs this plan
 };
 
 // Equal-work split: one workgroup per CU for 2-byte caches (one wave per SIMD streams best),
@@ -192,13 +194,41 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     s.plan_floats = round_up4((size_t)num_seqs * (shared ? 2 : 1) + 1);
     s.ml_floats = round_up4(slots * cols);
     s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * cols * 128) * sizeof(float);
+    s.slots = (int64_t)slots;
+    s.flat = true;
+    return true;
+}
+
+// Fixed partitions of P tokens at head_dim 128, run by the equal-work kernel: two partial-result
+// slots per partition of every (sequence, KV head / head chunk) segment (a unit boundary may cut a
+// partition in two).
+bool plan_flat_parts(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int P)
+{
+    const int group = num_heads / num_kv_heads;
+    const int gh = heads_per_workgroup(group, 128);
+    const int64_t Y = (int64_t)num_kv_heads * (group / gh);
+    const int np = (max_context_len + P - 1) / P;
+    const int64_t parts = Y * num_seqs * np;                 // upper bound: every sequence at max_context_len
+    if (num_seqs > kMaxRowsPerLaunch) return false;
+    if (parts * (P / kMmaTile) >= (1LL << 30)) return false;  // flat tile indices are 32-bit
+    int64_t wgs = (parts + kDecodeWaves - 1) / kDecodeWaves;  // no more units than partitions
+    if (wgs > flat_workgroups(false)) wgs = flat_workgroups(false);
+    s.partition_size = P;
+    s.num_partitions = np;
+    s.workgroups = (int)wgs;
+    s.segs_per_seq = (int)Y;
+    s.slots = 2 * parts;
+    s.plan_floats = round_up4((size_t)num_seqs + 1);
+    s.ml_floats = round_up4((size_t)s.slots * gh);
+    s.bytes = (s.plan_floats + 2 * s.ml_floats + (size_t)s.slots * gh * 128) * sizeof(float);
+    s.flat = true;
     return true;
 }
 
 SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                      int max_context_len, int partition_size, int window = 0, bool shared = false)
 {
-    SplitPlan s{0, 1, 0, 0, 0, 0, 0};
+    SplitPlan s{0, 1, 0, 0, 0, 0, 0, 0, false};
     int P = partition_size;
     if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
     // The library's own choice for head_dim 128 is the equal-work split whenever splitting pays.
@@ -208,6 +238,9 @@ SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim
         if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
     }
     if (P <= 0) return s;
+    if (head_dim == 128 && window <= 0 && !shared && P % kMmaTile == 0 &&
+        plan_flat_parts(s, num_seqs, num_heads, num_kv_heads, max_context_len, P))
+        return s;
     s.partition_size = P;
     s.num_partitions = (max_context_len + P - 1) / P;
     if (s.num_partitions < 1) s.num_partitions = 1;
@@ -285,12 +318,12 @@ int launch_decode_any(int dtype, int head_dim, A... args)
 // Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
 // the device keeps resident at once, because a unit that has to wait for a free slot would start
 // when every other unit is nearly done.
-template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false>
+template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false>
 int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 {
     static const int resident = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8, SHARED>, kDecodeWaves * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS>, kDecodeWaves * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -304,9 +337,11 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     int rc;
     {
         KernelEvents ev(st);
-        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8, SHARED>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
     }
     if (rc != OPTGQA_OK) return rc;
+    if constexpr (PARTS)
+        return launch(paged_decode_parts_reduce_kernel<DT>, dim3(p.num_heads, p.num_seqs), dim3(kPartsReduceGroups * 32), 0, st, p);
     constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
     return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
                   dim3(kReduceThreads), 0, st, p);
@@ -314,6 +349,9 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 
 int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
 {
+    if (p.part_tiles > 0)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, false, false, true>(p, workgroups, st)
+                                   : launch_decode_flat_dt<kBF16, false, false, false, true>(p, workgroups, st);
     if (p.shared_blocks && p.k_new)
         return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, false, true>(p, workgroups, st)
                                    : launch_decode_flat_dt<kBF16, true, false, true>(p, workgroups, st);
@@ -575,7 +613,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
         const bool have = workspace && workspace_bytes >= s.bytes && aligned16(workspace);
         if (!have) {
             if (partition_size != 0) return OPTGQA_ERR_WORKSPACE;
-            s = SplitPlan{0, 1, 0, 0, 0, 0, 0};          // library's own choice: fall back to unsplit
+            s = SplitPlan{0, 1, 0, 0, 0, 0, 0, 0, false};          // library's own choice: fall back to unsplit
         }
     }
 
@@ -601,6 +639,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.window = window > 0 ? window : 0;
     p.new_token_in_combine = 0;
     p.k_inv_scale = p.v_inv_scale = 1.f;
+    p.part_tiles = 0;
     p.shared_blocks = shared_blocks;
     p.bundle = shared_blocks ? kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128) : 1;
     if (kv_scales) {
@@ -615,7 +654,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     // can be moved as 16-byte pieces; otherwise it is a launch of its own ahead of the attention.
     bool fused = false;
     if (step) {
-        fused = s.partition_size == OPTGQA_SPLIT_BALANCED && aligned16(step->k_new) && aligned16(step->v_new) &&
+        fused = s.flat && s.partition_size == OPTGQA_SPLIT_BALANCED && aligned16(step->k_new) && aligned16(step->v_new) &&
                 step->k_stride % 8 == 0 && step->v_stride % 8 == 0;
         if (!fused && kv_scales) return OPTGQA_ERR_UNSUPPORTED;   // 8-bit step: new rows must move as 16-byte pieces
         if (!fused) {
@@ -625,13 +664,17 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
         }
     }
 
-    if (s.partition_size == OPTGQA_SPLIT_BALANCED) {
+    if (s.flat) {
         p.plan = static_cast<int32_t*>(workspace);
         p.ws_m = static_cast<float*>(workspace) + s.plan_floats;
         p.ws_l = p.ws_m + s.ml_floats;
         p.ws_o = p.ws_l + s.ml_floats;
         p.partition_size = 1 << 30;
         p.num_partitions = 1;
+        if (s.partition_size > 0) {                          // fixed partitions
+            p.part_tiles = s.partition_size / kMmaTile;
+            p.num_partitions = s.num_partitions;
+        }
         p.segs_per_seq = s.segs_per_seq;
         if (fused) {
             p.k_new = step->k_new;

@@ -152,8 +152,13 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
 
 
 def test_workspace_query(G):
+    # fixed partitions at head_dim 128: two slots per partition of every (sequence, KV head) segment,
+    # 8 heads x (128 + 2) floats each, after 4 + 1 plan entries padded to 4
     n, P = G.paged_attention_workspace_bytes(4, 64, 8, 128, 16, 32768, 512)
-    assert P == 512 and n == 4 * 64 * 64 * (128 + 2) * 4
+    assert P == 512 and n == (8 + 2 * 4 * 8 * 64 * 8 * (128 + 2)) * 4
+    # ... and at head_dim 64: [sequence][head][partition] x (64 + 2) floats
+    n, P = G.paged_attention_workspace_bytes(4, 64, 8, 64, 16, 32768, 512)
+    assert P == 512 and n == 4 * 64 * 64 * (64 + 2) * 4
     n, P = G.paged_attention_workspace_bytes(1, 8, 2, 64, 16, 128, 0)
     assert (n, P) == (0, 0)                      # short context: no split
     # head_dim 128 and worth splitting: the equal-work split, one slot per wave (one wave per SIMD

@@ -305,17 +305,22 @@ def test_decode_balanced_many_sequences(U, oracle, B, hi, zeros):
     assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
 
 
-def test_decode_balanced_matches_fixed_partitions(U):
-    """The two ways of splitting the context agree to fp32 combine rounding (both well inside the
-    output rounding), on a ragged batch whose units start and end inside segments."""
+def test_decode_balanced_and_fixed_partitions_against_the_oracle(U, oracle):
+    """The two ways of splitting the context, on a ragged batch whose units start and end inside
+    segments: each against the oracle at the stated tolerance, and against each other to well inside
+    it (they differ only in fp32 combine order)."""
     cfg = W.small_config(name="bal", dtype=W.F16, batch=9, num_heads=16, num_kv_heads=4, head_dim=128,
                          block_size=32, num_blocks=9 * 40 + 3, ctx_lo=1, ctx_hi=1200, seed=77)
     case = W.make_case(cfg)
     dev = U.DevCase(case)
     dev.write_cache()
-    a = W.from_bits(dev.decode(partition_size=BALANCED), W.F16)
-    b = W.from_bits(dev.decode(partition_size=256), W.F16)
-    assert np.max(np.abs(a - b)) <= 2.0 ** -9
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    got_a, got_b = dev.decode(partition_size=BALANCED), dev.decode(partition_size=256)
+    assert U.max_abs_err(got_a, ref, W.F16) <= U.TOL[W.F16]
+    assert U.max_abs_err(got_b, ref, W.F16) <= U.TOL[W.F16]
+    a, b = W.from_bits(got_a, W.F16), W.from_bits(got_b, W.F16)
+    assert np.max(np.abs(a - b)) <= 2.0 ** -9          # one fp16 ulp in [1, 2): both sit on the same side of the oracle
 
 
 def test_decode_balanced_rejects_head_dim_64(U):
@@ -1306,6 +1311,26 @@ def test_stream_probe_runs_and_checks_its_list(U):
 
 
 # ------------------------------------------------------------------ the workloads themselves
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_workload_block_permutation_bit_identical(U, name):
+    """Every configuration under three different assignments of physical blocks (same logical
+    content, tables permuted consistently - Section III-A: pages only re-arrange the sequence): the
+    outputs must be the same bits, through the call the bench times."""
+    cfg = W.CONFIGS[name]
+    outs = []
+    for perm_seed in (None, 101, 102):
+        case = W.make_case(cfg, perm_seed=perm_seed)
+        dev = U.DevCase(case)
+        if cfg.kind == "decode":
+            outs.append(dev.step() if cfg.partition_size == 0 else
+                        (dev.write_cache(), dev.decode(partition_size=cfg.partition_size))[1])
+        else:
+            dev.write_cache()
+            outs.append(dev.prefill())
+        del dev, case
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
 WORKLOAD_RUNS = [
     ("C1", 0), ("C1", -1), ("C2", 0), ("C2", -1), ("C2", "step"),
     ("C3", 0), ("C3", 1024), ("C3", "step"),          # "step": optgqa_decode_step, the call the bench times
