@@ -257,6 +257,82 @@ def paged_prefill_e4m3(q, k_cache, v_cache, block_tables, context_lens, cu_q_len
     return out
 
 
+def _scales(x, n: int) -> np.ndarray:
+    a = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    assert a.shape == (n,), f"expected {n} per-KV-head scales"
+    return a
+
+
+def reshape_and_cache_e4m3_heads(k, v, k_cache, v_cache, slot_mapping, k_scales, v_scales, dtype, lib=None) -> None:
+    """Quantising cache write with one scale pair per KV head (arrays [Hkv]), in place."""
+    lib = lib or _get()
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    k, v = _c(k, np.uint16), _c(v, np.uint16)
+    slots = _c(slot_mapping, np.int64)
+    NB, Hkv, bs, D = k_cache.shape
+    ks, vs = _scales(k_scales, Hkv), _scales(v_scales, Hkv)
+    stride = Hkv * D
+    lib.oracle_reshape_and_cache_e4m3_heads(_p(k), _p(v), _p(k_cache), _p(v_cache), _p(slots),
+                                            ctypes.c_int(slots.shape[0]), ctypes.c_int(Hkv), ctypes.c_int(D),
+                                            ctypes.c_int(bs), ctypes.c_int64(stride), ctypes.c_int64(stride),
+                                            _p(ks), _p(vs), ctypes.c_int(DTYPES[dtype]))
+
+
+def paged_attention_e4m3_heads(q, k_cache, v_cache, block_tables, context_lens, slopes, scale, k_scales, v_scales,
+                               dtype, rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Decode attention over an E4M3 cache with per-KV-head scales, fp64."""
+    lib = lib or _get()
+    q = _c(q, np.uint16)
+    bt, cl = _c(block_tables, np.int32), _c(context_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    NB, Hkv, bs, D = k_cache.shape
+    ks, vs = _scales(k_scales, Hkv), _scales(v_scales, Hkv)
+    B, Hq, _ = q.shape
+    if rows is None:
+        n, rs, rh = B * Hq, None, None
+        out = np.zeros((B, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rs, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_attention_e4m3_heads(_p(out), _p(rs), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                          _p(bt), _p(cl), _p(sl), ctypes.c_float(scale), _p(ks), _p(vs),
+                                          ctypes.c_int(Hq), ctypes.c_int(Hkv), ctypes.c_int(D), ctypes.c_int(bs),
+                                          ctypes.c_int(bt.shape[1]), ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
+def paged_prefill_e4m3_heads(q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, slopes, scale, k_scales,
+                             v_scales, dtype, rows: Optional[Sequence] = None, lib=None) -> np.ndarray:
+    """Causal + ALiBi attention of the new tokens over an E4M3 cache with per-KV-head scales, fp64."""
+    lib = lib or _get()
+    q = _c(q, np.uint16)
+    bt, cl, cu = _c(block_tables, np.int32), _c(context_lens, np.int32), _c(cu_q_lens, np.int32)
+    sl = None if slopes is None else _c(slopes, np.float32)
+    assert k_cache.dtype == np.uint8 and v_cache.dtype == np.uint8
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    NB, Hkv, bs, D = k_cache.shape
+    ks, vs = _scales(k_scales, Hkv), _scales(v_scales, Hkv)
+    T, Hq, _ = q.shape
+    assert int(cu[-1]) == T
+    if rows is None:
+        n, rt, rh = T * Hq, None, None
+        out = np.zeros((T, Hq, D), dtype=np.float64)
+    else:
+        rows = np.asarray(rows, dtype=np.int32).reshape(-1, 2)
+        n, rt, rh = rows.shape[0], _c(rows[:, 0], np.int32), _c(rows[:, 1], np.int32)
+        out = np.zeros((n, D), dtype=np.float64)
+    lib.oracle_paged_prefill_e4m3_heads(_p(out), _p(rt), _p(rh), ctypes.c_int(n), _p(q), _p(k_cache), _p(v_cache),
+                                        _p(bt), _p(cl), _p(cu), _p(sl), ctypes.c_float(scale), _p(ks), _p(vs),
+                                        ctypes.c_int(cl.shape[0]), ctypes.c_int(Hq), ctypes.c_int(Hkv),
+                                        ctypes.c_int(D), ctypes.c_int(bs), ctypes.c_int(bt.shape[1]),
+                                        ctypes.c_int(DTYPES[dtype]))
+    return out
+
+
 # ---------------------------------------------------------------------------------------------
 # causal + sliding-window masks: optgqa_oracle_window.c
 # ---------------------------------------------------------------------------------------------

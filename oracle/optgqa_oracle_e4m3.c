@@ -28,6 +28,12 @@
  * exact rational arithmetic; attention reduced to the 2-byte oracle on a cache that holds the
  * dequantised values exactly (every E4M3 value is a bf16 and an fp16 value).
  *
+ *   scales    one pair (k_scale, v_scale) per tensor, or - the *_heads functions at the end of this
+ *             file - one pair per KV head g (arrays of num_kv_heads fp32 values): the same three
+ *             clauses with k_scale, v_scale replaced by k_scales[g], v_scales[g], g being the KV head
+ *             the element belongs to (store) or the KV head h div G that query head h reads (attend).
+ *             Pinned by reduction to the per-tensor clauses, KV head by KV head.
+ *
  * Cache layout: [num_blocks][num_kv_heads][block_size][head_dim], 1-byte elements.
  */
 #include <math.h>
@@ -235,6 +241,87 @@ void oracle_paged_prefill_e4m3(double *out, const int32_t *row_token, const int3
         attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)t * num_heads + h) * head_dim,
                         k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,
                         h / group, slope, (double)scale, (double)k_scale, (double)v_scale,
+                        num_kv_heads, head_dim, block_size, dtype);
+    }
+}
+
+/* ---- one scale pair per KV head ---------------------------------------------------------
+ * The three clauses above with k_scales[g], v_scales[g] in place of k_scale, v_scale. */
+void oracle_reshape_and_cache_e4m3_heads(const uint16_t *k, const uint16_t *v,
+                                         uint8_t *k_cache, uint8_t *v_cache, const int64_t *slot_mapping,
+                                         int num_tokens, int num_kv_heads, int head_dim, int block_size,
+                                         int64_t k_token_stride, int64_t v_token_stride,
+                                         const float *k_scales, const float *v_scales, int dtype)
+{
+    two_byte_value_tabulate();
+    for (int t = 0; t < num_tokens; ++t) {
+        int64_t slot = slot_mapping[t];
+        if (slot < 0) continue;
+        int64_t block = slot / block_size, row = slot % block_size;
+        for (int g = 0; g < num_kv_heads; ++g) {
+            const float k_inv_g = 1.0f / k_scales[g], v_inv_g = 1.0f / v_scales[g];   /* one fp32 division each */
+            int64_t dst_g = ((block * num_kv_heads + g) * block_size + row) * head_dim;
+            for (int d = 0; d < head_dim; ++d) {
+                float kf = (float)two_byte_value(k[t * k_token_stride + (int64_t)g * head_dim + d], dtype);
+                float vf = (float)two_byte_value(v[t * v_token_stride + (int64_t)g * head_dim + d], dtype);
+                volatile float kq = kf * k_inv_g;
+                volatile float vq = vf * v_inv_g;
+                k_cache[dst_g + d] = e4m3_nearest(kq);
+                v_cache[dst_g + d] = e4m3_nearest(vq);
+            }
+        }
+    }
+}
+
+void oracle_paged_attention_e4m3_heads(double *out, const int32_t *row_seq, const int32_t *row_head,
+                                       int n_rows, const uint16_t *q,
+                                       const uint8_t *k_cache, const uint8_t *v_cache,
+                                       const int32_t *block_tables, const int32_t *context_lens,
+                                       const float *alibi_slopes, float scale,
+                                       const float *k_scales, const float *v_scales,
+                                       int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                       int max_blocks_per_seq, int dtype)
+{
+    two_byte_value_tabulate();
+    int group = num_heads / num_kv_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < n_rows; ++r) {
+        int b = row_seq ? row_seq[r] : r / num_heads;
+        int h = row_seq ? row_head[r] : r % num_heads;
+        int L = context_lens[b];
+        int kv = h / group;                                  /* the KV head this query head reads */
+        double slope = alibi_slopes ? (double)alibi_slopes[h] : 0.0;
+        attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)b * num_heads + h) * head_dim,
+                        k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, L, L - 1,
+                        kv, slope, (double)scale, (double)k_scales[kv], (double)v_scales[kv],
+                        num_kv_heads, head_dim, block_size, dtype);
+    }
+}
+
+void oracle_paged_prefill_e4m3_heads(double *out, const int32_t *row_token, const int32_t *row_head,
+                                     int n_rows, const uint16_t *q,
+                                     const uint8_t *k_cache, const uint8_t *v_cache,
+                                     const int32_t *block_tables, const int32_t *context_lens,
+                                     const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
+                                     const float *k_scales, const float *v_scales, int num_seqs,
+                                     int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                     int max_blocks_per_seq, int dtype)
+{
+    two_byte_value_tabulate();
+    int group = num_heads / num_kv_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < n_rows; ++r) {
+        int t = row_token ? row_token[r] : r / num_heads;
+        int h = row_token ? row_head[r] : r % num_heads;
+        int b = 0;
+        while (b + 1 < num_seqs && cu_q_lens[b + 1] <= t) ++b;
+        int n_new = cu_q_lens[b + 1] - cu_q_lens[b];          /* new tokens of sequence b */
+        int pos = context_lens[b] - n_new + (t - cu_q_lens[b]);
+        int kv = h / group;
+        double slope = alibi_slopes ? (double)alibi_slopes[h] : 0.0;
+        attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)t * num_heads + h) * head_dim,
+                        k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,
+                        kv, slope, (double)scale, (double)k_scales[kv], (double)v_scales[kv],
                         num_kv_heads, head_dim, block_size, dtype);
     }
 }

@@ -214,6 +214,62 @@ def check_prefill_reduces_to_two_byte_oracle_and_to_decodes(lib=None):
     np.testing.assert_allclose(sub, np.stack([got[t, h] for t, h in rows]), rtol=0, atol=0)
 
 
+def check_per_head_scales_reduce_to_per_tensor_clauses(lib=None):
+    """One scale pair per KV head: KV head by KV head, the cache write, the decode clause and the prefill
+    clause must give what the per-tensor clauses (pinned above; always the built oracle's here) give
+    with that head's pair - on the codes of that head and on the rows of the query heads that read
+    it.  Three KV heads with very different scales, so that a scale taken from the wrong head, from
+    the query-head index or from the other tensor shows."""
+    k_scales = np.array([0.5, 0.03125, 2.0], np.float32)
+    v_scales = np.array([1.5, 0.25, 0.0078125], np.float32)
+    for dtype in (W.F16, W.BF16):
+        cfg = W.small_config(name="e4m3heads", kind="prefill", dtype=dtype, batch=3, num_heads=6, num_kv_heads=3,
+                             head_dim=16, block_size=4, num_blocks=64, ctx_lo=9, ctx_hi=37, q_len=5, seed=41)
+        case = W.make_case(cfg)
+        k_all, v_all, slots = _all_tokens(case)
+        shape = (cfg.num_blocks, cfg.num_kv_heads, cfg.block_size, cfg.head_dim)
+        kc8, vc8 = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
+        O.reshape_and_cache_e4m3_heads(k_all, v_all, kc8, vc8, slots, k_scales, v_scales, dtype, lib=lib)
+        for g in range(3):
+            kt, vt = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
+            O.reshape_and_cache_e4m3(k_all, v_all, kt, vt, slots, k_scales[g], v_scales[g], dtype)
+            assert np.array_equal(kc8[:, g], kt[:, g]) and np.array_equal(vc8[:, g], vt[:, g]), f"cache write, KV head {g}"
+        assert len({kc8[:, g].tobytes() for g in range(3)}) == 3
+        # decode: the last new token of every sequence as the query
+        last = case.cu_q_lens[1:] - 1
+        qd = case.q[last]
+        got = O.paged_attention_e4m3_heads(qd, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                           k_scales, v_scales, dtype, lib=lib)
+        pf = O.paged_prefill_e4m3_heads(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                        case.slopes, case.scale, k_scales, v_scales, dtype, lib=lib)
+        for g in range(3):
+            ref = O.paged_attention_e4m3(qd, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                         k_scales[g], v_scales[g], dtype)
+            refp = O.paged_prefill_e4m3(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                        case.slopes, case.scale, k_scales[g], v_scales[g], dtype)
+            for h in (2 * g, 2 * g + 1):
+                np.testing.assert_allclose(got[:, h], ref[:, h], rtol=1e-13, atol=0, err_msg=f"decode, head {h}")
+                np.testing.assert_allclose(pf[:, h], refp[:, h], rtol=1e-13, atol=0, err_msg=f"prefill, head {h}")
+            other = (2 * g + 2) % 6
+            assert np.max(np.abs(got[:, other] - ref[:, other])) > 1e-6          # the scales do differ in effect
+        # row lists pick the same rows
+        rows = [(0, 0), (2, 5), (1, 3)]
+        sub = O.paged_attention_e4m3_heads(qd, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                           k_scales, v_scales, dtype, rows=rows, lib=lib)
+        assert np.array_equal(sub, np.stack([got[b, h] for b, h in rows]))
+        rows = [(0, 0), (case.num_tokens - 1, 5), (4, 2)]
+        sub = O.paged_prefill_e4m3_heads(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                         case.slopes, case.scale, k_scales, v_scales, dtype, rows=rows, lib=lib)
+        assert np.array_equal(sub, np.stack([pf[t, h] for t, h in rows]))
+        # the same pair for every head is the per-tensor clause
+        u = np.full(3, 0.125, np.float32)
+        a = O.paged_attention_e4m3_heads(qd, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                         u, 2 * u, dtype, lib=lib)
+        b_ = O.paged_attention_e4m3(qd, kc8, vc8, case.block_tables, case.context_lens, case.slopes, case.scale,
+                                    np.float32(0.125), np.float32(0.25), dtype)
+        np.testing.assert_allclose(a, b_, rtol=1e-14, atol=0)
+
+
 def check_two_byte_decoder_on_every_pattern(lib=None):
     """The 2-byte decoder of this file (queries and new-token rows) on all 65 536 fp16 and bf16
     patterns.  Two routes, both compared with numpy's own decoding of the pattern:
@@ -281,4 +337,5 @@ ALL_CHECKS = [
     check_attention_reduces_to_two_byte_oracle,
     check_scales_enter_where_the_definition_says,
     check_two_byte_decoder_on_every_pattern,
+    check_per_head_scales_reduce_to_per_tensor_clauses,
 ]

@@ -41,6 +41,16 @@ MUTANTS = {
                            "block_tables + (int64_t)b * max_blocks_per_seq, context_lens[b], pos,\n                        h / group"),
     "prefill_ignores_prefix": ("int pos = context_lens[b] - new_tokens + (t - cu_q_lens[b]);", "int pos = (t - cu_q_lens[b]);"),
     "v_read_from_k": ("out_row[d] += w * e4m3_value(v_cache[at + d]);", "out_row[d] += w * e4m3_value(k_cache[at + d]);"),
+    # one scale pair per KV head
+    "heads_write_uses_head_zero": ("const float k_inv_g = 1.0f / k_scales[g], v_inv_g = 1.0f / v_scales[g];",
+                                   "const float k_inv_g = 1.0f / k_scales[0], v_inv_g = 1.0f / v_scales[0];"),
+    "heads_write_v_with_k_scales": ("volatile float vq = vf * v_inv_g;", "volatile float vq = vf * k_inv_g;"),
+    "heads_decode_scale_of_query_head": ("int kv = h / group;                                  /* the KV head this query head reads */",
+                                         "int kv = h % num_kv_heads;"),
+    "heads_decode_v_scale_of_next_head": ("kv, slope, (double)scale, (double)k_scales[kv], (double)v_scales[kv],\n                        num_kv_heads, head_dim, block_size, dtype);\n    }\n}\n\nvoid oracle_paged_prefill_e4m3_heads",
+                                          "kv, slope, (double)scale, (double)k_scales[kv], (double)v_scales[(kv + 1) % num_kv_heads],\n                        num_kv_heads, head_dim, block_size, dtype);\n    }\n}\n\nvoid oracle_paged_prefill_e4m3_heads"),
+    "heads_prefill_k_scale_of_head_zero": ("int kv = h / group;\n        double slope = alibi_slopes ? (double)alibi_slopes[h] : 0.0;\n        attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)t * num_heads + h) * head_dim,\n                        k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,\n                        kv, slope, (double)scale, (double)k_scales[kv],",
+                                           "int kv = h / group;\n        double slope = alibi_slopes ? (double)alibi_slopes[h] : 0.0;\n        attend_row_e4m3(out + (int64_t)r * head_dim, q + ((int64_t)t * num_heads + h) * head_dim,\n                        k_cache, v_cache, block_tables + (int64_t)b * max_blocks_per_seq, pos + 1, pos,\n                        kv, slope, (double)scale, (double)k_scales[0],"),
     # the file's own 2-byte decoder (queries and new-token rows)
     "two_byte_f16_subnormal_step": ("if (e == 0) v = ldexp((double)m, -24);\n        else if (e == 31) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 1024.0, e - 15);\n    } else {\n        int e = (h >> 7) & 0xFF, m = h & 0x7F;\n        if (e == 0) v = ldexp((double)m, -133);\n        else if (e == 255) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula",
                                     "if (e == 0) v = ldexp((double)m, -25);\n        else if (e == 31) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 1024.0, e - 15);\n    } else {\n        int e = (h >> 7) & 0xFF, m = h & 0x7F;\n        if (e == 0) v = ldexp((double)m, -133);\n        else if (e == 255) v = m ? NAN : INFINITY;\n        else v = ldexp(1.0 + (double)m / 128.0, e - 127);\n    }\n    return sign ? -v : v;\n}\n\nstatic double e4m3_value_formula"),
