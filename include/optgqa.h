@@ -199,7 +199,8 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
  * as the levers on KV-cache traffic; it fixes no format - this is the variant built here).
  * The caches hold 1-byte E4M3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no
  * infinities, largest finite value 448, codes 0x7f / 0xff are NaN) in the same
- * [num_blocks][num_kv_heads][block_size][head_dim] layout, with ONE scale per tensor.
+ * [num_blocks][num_kv_heads][block_size][head_dim] layout, with one scale per tensor (these four
+ * calls) or one per KV head (the *_heads calls after them).
  *
  * optgqa_reshape_and_cache_fp8: as optgqa_reshape_and_cache, with a quantiser in front:
  *     code = nearest_e4m3( fp32(x) * fp32(1 / scale) )
@@ -257,6 +258,46 @@ int optgqa_paged_prefill_fp8(void *out, const void *q, const void *k_cache, cons
                              int num_kv_heads, int head_dim, int block_size,
                              int max_blocks_per_seq, int max_q_len, int dtype,
                              void *stream);
+
+/*
+ * The same four calls with ONE SCALE PAIR PER KV HEAD (k_scales, v_scales: DEVICE arrays of
+ * num_kv_heads fp32 values, finite and > 0 - contents are not checked): every formula above with
+ * k_scale, v_scale replaced by k_scales[g], v_scales[g], g being the KV head an element belongs
+ * to (store: code = nearest_e4m3(fp32(x) * fp32(1 / k_scales[g])), the division done once per use
+ * in fp32 on the device, correctly rounded) or the KV head h / (num_heads / num_kv_heads) that query
+ * head h reads (attend).  Key and value magnitudes differ from head to head far more than inside
+ * one; a scale per head keeps each head's codes in the format's best range.  Shapes, alignment,
+ * workspace and errors as for the per-tensor calls; a NULL scale array is OPTGQA_ERR_NULL.
+ */
+int optgqa_reshape_and_cache_fp8_heads(const void *k, const void *v, void *k_cache, void *v_cache,
+                                       const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
+                                       int head_dim, int block_size, int64_t k_token_stride,
+                                       int64_t v_token_stride, const float *k_scales,
+                                       const float *v_scales, int dtype, void *stream);
+
+int optgqa_paged_attention_fp8_heads(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *block_tables, const int32_t *context_lens,
+                                     const float *alibi_slopes, float scale, const float *k_scales,
+                                     const float *v_scales, int num_seqs, int num_heads,
+                                     int num_kv_heads, int head_dim, int block_size,
+                                     int max_blocks_per_seq, int max_context_len, void *workspace,
+                                     size_t workspace_bytes, int dtype, void *stream);
+
+int optgqa_decode_step_fp8_heads(void *out, const void *q, const void *k_new, const void *v_new,
+                                 void *k_cache, void *v_cache, const int32_t *block_tables,
+                                 const int32_t *context_lens, const float *alibi_slopes, float scale,
+                                 const float *k_scales, const float *v_scales, int num_seqs,
+                                 int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                 int max_blocks_per_seq, int max_context_len, int64_t k_token_stride,
+                                 int64_t v_token_stride, void *workspace, size_t workspace_bytes,
+                                 int dtype, void *stream);
+
+int optgqa_paged_prefill_fp8_heads(void *out, const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *context_lens,
+                                   const int32_t *cu_q_lens, const float *alibi_slopes, float scale,
+                                   const float *k_scales, const float *v_scales, int num_seqs,
+                                   int num_heads, int num_kv_heads, int head_dim, int block_size,
+                                   int max_blocks_per_seq, int max_q_len, int dtype, void *stream);
 
 /* Bytes of workspace optgqa_paged_attention wants for these arguments (0 = none needed).
  * Also reports, when chosen_partition_size is not NULL, the partition size the library would

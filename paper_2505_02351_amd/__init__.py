@@ -85,6 +85,17 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_paged_prefill_fp8.restype = i32
     lib.optgqa_paged_prefill_fp8.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, f32, f32, i32, i32, i32, i32, i32,
                                              i32, i32, i32, vp]
+    lib.optgqa_reshape_and_cache_fp8_heads.restype = i32
+    lib.optgqa_reshape_and_cache_fp8_heads.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, vp, vp, i32, vp]
+    lib.optgqa_paged_attention_fp8_heads.restype = i32
+    lib.optgqa_paged_attention_fp8_heads.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, i32, i32, i32, i32, i32,
+                                                     i32, i32, vp, sz, i32, vp]
+    lib.optgqa_decode_step_fp8_heads.restype = i32
+    lib.optgqa_decode_step_fp8_heads.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, i32, i32, i32, i32,
+                                                 i32, i32, i32, i64, i64, vp, sz, i32, vp]
+    lib.optgqa_paged_prefill_fp8_heads.restype = i32
+    lib.optgqa_paged_prefill_fp8_heads.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, f32, vp, vp, i32, i32, i32, i32, i32,
+                                                   i32, i32, i32, vp]
     lib.optgqa_paged_attention_workspace_bytes.restype = sz
     lib.optgqa_paged_attention_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32, i32,
                                                            ctypes.POINTER(ctypes.c_int)]
@@ -481,6 +492,110 @@ def paged_prefill_fp8(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor,
                                       float(k_scale), float(v_scale), int(context_lens.shape[0]), Hq, Hkv, D, bs,
                                       int(block_tables.shape[1]), int(max_q_len), _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_paged_prefill_fp8")
+
+
+def _head_scales(ref: torch.Tensor, k_cache: torch.Tensor, k_scales, v_scales) -> None:
+    """Per-KV-head scale arrays: float32, dense, [Hkv], on ref's GPU."""
+    _typed(ref, f32=[("k_scales", k_scales), ("v_scales", v_scales)])
+    hkv = k_cache.shape[1]
+    for t, n in ((k_scales, "k_scales"), (v_scales, "v_scales")):
+        if t is None or tuple(t.shape) != (hkv,) or not t.is_contiguous():
+            raise ValueError(f"optgqa: {n} must be a dense tensor of {hkv} values, one per KV head")
+
+
+def reshape_and_cache_fp8_heads(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                          slot_mapping: torch.Tensor, k_scales: torch.Tensor, v_scales: torch.Tensor, stream=None) -> None:
+    """optgqa_reshape_and_cache_fp8_heads (one scale pair per KV head, float32 device tensors [Hkv]): quantise the new tokens' K/V rows to E4M3 codes in the paged
+    caches (uint8 tensors [NB, Hkv, bs, D])."""
+    lib = load_library()
+    _head_scales(k, k_cache, k_scales, v_scales)
+    _typed(k, same=[("v", v)], u8=[("k_cache", k_cache), ("v_cache", v_cache)], i64=[("slot_mapping", slot_mapping)])
+    NB, Hkv, bs, D = k_cache.shape
+    T = int(slot_mapping.shape[0])
+    _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache"), _dense(slot_mapping, "slot_mapping")
+    if T and (k.stride(-1) != 1 or k.stride(-2) != D or v.stride(-1) != 1 or v.stride(-2) != D):
+        raise ValueError("optgqa: k and v must be dense in their last two dims")
+    ks = int(k.stride(0)) if T else Hkv * D
+    vs = int(v.stride(0)) if T else Hkv * D
+    rc = lib.optgqa_reshape_and_cache_fp8_heads(_ptr(k), _ptr(v), _ptr(k_cache), _ptr(v_cache), _ptr(slot_mapping),
+                                          T, Hkv, D, bs, ks, vs, _ptr(k_scales), _ptr(v_scales),
+                                          _dtype_code(k), _stream(stream))
+    _check(rc, "optgqa_reshape_and_cache_fp8_heads")
+
+
+def paged_attention_fp8_heads(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                        block_tables: torch.Tensor, context_lens: torch.Tensor,
+                        alibi_slopes: Optional[torch.Tensor], scale: float, k_scales: torch.Tensor, v_scales: torch.Tensor,
+                        max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_paged_attention_fp8_heads (one scale pair per KV head, float32 device tensors [Hkv]): decode attention over E4M3 caches (uint8 tensors)."""
+    lib = load_library()
+    _head_scales(q, k_cache, k_scales, v_scales)
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True)
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    ws_bytes = _workspace(workspace, q)
+    rc = lib.optgqa_paged_attention_fp8_heads(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                        _ptr(context_lens), _ptr(alibi_slopes), float(scale), _ptr(k_scales),
+                                        _ptr(v_scales), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
+                                        int(max_context_len), _ptr(workspace), ws_bytes, _dtype_code(q),
+                                        _stream(stream))
+    _check(rc, "optgqa_paged_attention_fp8_heads")
+
+
+def decode_step_fp8_heads(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                    k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                    context_lens: torch.Tensor, alibi_slopes: Optional[torch.Tensor], scale: float, k_scales: torch.Tensor,
+                    v_scales: torch.Tensor, max_context_len: int, workspace: Optional[torch.Tensor], stream=None) -> None:
+    """optgqa_decode_step_fp8_heads (one scale pair per KV head, float32 device tensors [Hkv]): quantising cache write of the step's new tokens and decode attention over
+    the E4M3 caches in one call."""
+    lib = load_library()
+    _head_scales(q, k_cache, k_scales, v_scales)
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True, new=(k_new, v_new))
+    B, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape or k_new.shape != (B, Hkv, D) or v_new.shape != (B, Hkv, D):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens")):
+        _dense(t, n)
+    if B and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if B else Hkv * D
+    vs = int(v_new.stride(0)) if B else Hkv * D
+    ws_bytes = _workspace(workspace, q)
+    rc = lib.optgqa_decode_step_fp8_heads(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                    _ptr(block_tables), _ptr(context_lens), _ptr(alibi_slopes), float(scale),
+                                    _ptr(k_scales), _ptr(v_scales), B, Hq, Hkv, D, bs, int(block_tables.shape[1]),
+                                    int(max_context_len), ks, vs, _ptr(workspace), ws_bytes, _dtype_code(q),
+                                    _stream(stream))
+    _check(rc, "optgqa_decode_step_fp8_heads")
+
+
+def paged_prefill_fp8_heads(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                      block_tables: torch.Tensor, context_lens: torch.Tensor, cu_q_lens: torch.Tensor,
+                      alibi_slopes: Optional[torch.Tensor], scale: float, k_scales: torch.Tensor, v_scales: torch.Tensor,
+                      max_q_len: int, stream=None) -> None:
+    """optgqa_paged_prefill_fp8_heads (one scale pair per KV head, float32 device tensors [Hkv]): causal + ALiBi attention of the new tokens over E4M3 caches."""
+    lib = load_library()
+    _head_scales(q, k_cache, k_scales, v_scales)
+    _attn_typed(q, out, k_cache, v_cache, block_tables, context_lens, alibi_slopes, kv8=True, cu_q_lens=cu_q_lens)
+    T, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if Dk != D or out.shape != q.shape:
+        raise ValueError("optgqa: shape mismatch between q, out and the caches")
+    for t, n in ((out, "out"), (q, "q"), (k_cache, "k_cache"), (v_cache, "v_cache"),
+                 (block_tables, "block_tables"), (context_lens, "context_lens"), (cu_q_lens, "cu_q_lens")):
+        _dense(t, n)
+    rc = lib.optgqa_paged_prefill_fp8_heads(_ptr(out), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_tables),
+                                      _ptr(context_lens), _ptr(cu_q_lens), _ptr(alibi_slopes), float(scale),
+                                      _ptr(k_scales), _ptr(v_scales), int(context_lens.shape[0]), Hq, Hkv, D, bs,
+                                      int(block_tables.shape[1]), int(max_q_len), _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_paged_prefill_fp8_heads")
 
 
 def paged_prefill(out: torch.Tensor, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

@@ -50,8 +50,10 @@ __global__ __launch_bounds__(256) void reshape_and_cache_kernel(
 }
 
 // Cache store with a quantiser in front, for caches that hold 1-byte E4M3 codes (largest finite
-// value 448, no infinities) and one scale per tensor:
-//     code = nearest_e4m3( fp32(x) * inv_scale ),  inv_scale = fp32(1 / scale) computed on the host.
+// value 448, no infinities) and one scale per tensor, or - k_scales / v_scales given, device arrays
+// of num_kv_heads values - one per KV head:
+//     code = nearest_e4m3( fp32(x) * inv_scale ),  inv_scale = fp32(1 / scale): one correctly rounded
+// fp32 division, on the host for the per-tensor scale, here for a KV head's.
 // One fp32 multiplication, then e4m3_codes2 (round to nearest even, saturating, NaN -> 0x7f).
 // One thread moves 8 elements of one token's K or V row: 16 bytes in, 8 bytes out.
 template <int DT>
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(256) void reshape_and_cache_e4m3_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, unsigned char* __restrict__ k_cache,
     unsigned char* __restrict__ v_cache, const int64_t* __restrict__ slot_mapping, int num_tokens,
     int num_kv_heads, int head_dim, int block_size, int64_t k_token_stride, int64_t v_token_stride,
-    float k_inv_scale, float v_inv_scale)
+    float k_inv_scale, float v_inv_scale, const float* __restrict__ k_scales, const float* __restrict__ v_scales)
 {
     const int pieces_per_head = head_dim / 8;
     const int pieces_per_token = num_kv_heads * pieces_per_head;
@@ -78,7 +80,8 @@ __global__ __launch_bounds__(256) void reshape_and_cache_e4m3_kernel(
     const int64_t row = slot - block * block_size;
     const int64_t dst = ((block * num_kv_heads + g) * block_size + row) * head_dim + d0;
     const uint16_t* src = which == 0 ? k + t * k_token_stride : v + t * v_token_stride;
-    const float inv = which == 0 ? k_inv_scale : v_inv_scale;
+    float inv = which == 0 ? k_inv_scale : v_inv_scale;
+    if (k_scales) inv = 1.0f / (which == 0 ? k_scales[g] : v_scales[g]);
     const uint4 x = *reinterpret_cast<const uint4*>(src + (int64_t)g * head_dim + d0);
     const uint32_t w[4] = {x.x, x.y, x.z, x.w};
     uint32_t packed[2] = {0u, 0u};

@@ -314,7 +314,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const unsigned char* __restrict__ vc = static_cast<const unsigned char*>(p.v_cache);
     const unsigned char* __restrict__ k_new = static_cast<const unsigned char*>(p.k_new);
     const unsigned char* __restrict__ v_new = static_cast<const unsigned char*>(p.v_new);
-    const float scale2 = p.scale2;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
 
     // Where a tile comes from, in wave-uniform terms: the byte address of its first K / V row, the
@@ -430,6 +429,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const int first = lo / TILE;                        // the segment's tiles start at this tile of the cache
         const int reg_end = min(seg.hi, ((has_new && tau_end == n ? tau_end - 1 : tau_end) + first) * TILE);
         const int g = y / chunks;
+        // score scale (base 2); E4M3 caches with per-KV-head scales: times this KV head's k_scale
+        float scale2 = p.scale2;
+        if constexpr (KV8) {
+            if (p.k_scales) scale2 *= __builtin_bit_cast(float, scalar_load_i32(reinterpret_cast<const int32_t*>(p.k_scales + g)));
+        }
         const int32_t* table = p.block_tables + (int64_t)seg.tb * p.max_blocks_per_seq;
         const int64_t head_off = (int64_t)g * bs * D;
         const int64_t new_k = NEW_TILE ? seg.b * p.k_new_stride + (int64_t)g * D : 0;
@@ -786,12 +790,15 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     };
     collect(v_own, n_own, plan_own, hh);
     if constexpr (SHARED) collect(v_shared, n_shared, plan_shared, col_shared);
+    // E4M3 caches with per-KV-head scales: this head's pair
+    const float k_scale_g = p.k_scales ? p.k_scales[g] : 1.f, v_scale_g = p.v_scales ? p.v_scales[g] : 1.f;
     if constexpr (NEWTOK) {
         // the new token, at the query's own position (ALiBi term 0): codes, their values, its score
-        const uint32_t kcodes = e4m3_codes2(widen_lo<DT>(kw.x) * p.k_inv_scale, widen_hi<DT>(kw.x) * p.k_inv_scale) |
-                                e4m3_codes2(widen_lo<DT>(kw.y) * p.k_inv_scale, widen_hi<DT>(kw.y) * p.k_inv_scale) << 16;
-        const uint32_t vcodes = e4m3_codes2(widen_lo<DT>(vw.x) * p.v_inv_scale, widen_hi<DT>(vw.x) * p.v_inv_scale) |
-                                e4m3_codes2(widen_lo<DT>(vw.y) * p.v_inv_scale, widen_hi<DT>(vw.y) * p.v_inv_scale) << 16;
+        const float k_inv = p.k_scales ? 1.0f / k_scale_g : p.k_inv_scale, v_inv = p.v_scales ? 1.0f / v_scale_g : p.v_inv_scale;
+        const uint32_t kcodes = e4m3_codes2(widen_lo<DT>(kw.x) * k_inv, widen_hi<DT>(kw.x) * k_inv) |
+                                e4m3_codes2(widen_lo<DT>(kw.y) * k_inv, widen_hi<DT>(kw.y) * k_inv) << 16;
+        const uint32_t vcodes = e4m3_codes2(widen_lo<DT>(vw.x) * v_inv, widen_hi<DT>(vw.x) * v_inv) |
+                                e4m3_codes2(widen_lo<DT>(vw.y) * v_inv, widen_hi<DT>(vw.y) * v_inv) << 16;
         const f32x2 k01 = __builtin_amdgcn_cvt_pk_f32_fp8(kcodes, false), k23 = __builtin_amdgcn_cvt_pk_f32_fp8(kcodes, true);
         const f32x2 v01 = __builtin_amdgcn_cvt_pk_f32_fp8(vcodes, false), v23 = __builtin_amdgcn_cvt_pk_f32_fp8(vcodes, true);
         float dot = widen_lo<DT>(qw.x) * k01[0];
@@ -800,7 +807,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
         dot = fmaf(widen_hi<DT>(qw.y), k23[1], dot);
 #pragma unroll
         for (int off = 1; off < kVecPerHead; off <<= 1) dot += __shfl_xor(dot, off);      // a head's 32 threads are half a wave
-        const float s_new = dot * p.scale2;                                               // eq. (3), base 2, k_scale folded in
+        const float s_new = dot * (p.scale2 * k_scale_g);                                 // eq. (3), base 2, k_scale folded in
         const float M2 = fmaxf(M, s_new);
         const float f_old = any ? fast_exp2(M - M2) : 0.f, f_new = fast_exp2(s_new - M2);
         den = fmaf(den, f_old, f_new);
@@ -815,7 +822,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
             *reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(p.v_cache_w) + dst) = vcodes;
         }
     }
-    const float inv = p.out_scale / den;                 // out_scale: 1, or v_scale of an E4M3 cache
+    const float inv = p.out_scale * v_scale_g / den;     // out_scale: 1, or the v_scale of an E4M3 cache
     uint2 packed;
     packed.x = narrow2<DT>(num.x * inv, num.y * inv);
     packed.y = narrow2<DT>(num.z * inv, num.w * inv);

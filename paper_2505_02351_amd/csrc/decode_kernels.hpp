@@ -42,6 +42,10 @@ struct DecodeParams {
     // (quantised with these reciprocal scales, as the cache write does) and stores its codes
     int new_token_in_combine;
     float k_inv_scale, v_inv_scale;
+    // E4M3 caches with one scale pair per KV head: device arrays of num_kv_heads values (then scale2
+    // holds no k_scale, out_scale is 1 and the two reciprocals above are unused), else nullptr
+    const float* k_scales;
+    const float* v_scales;
     int window;                 // > 0: a query sees only the last `window` tokens up to its own (equal-work kernel only)
     // Fused decode step (cache write inside the attention kernel): the new token of sequence b
     // sits at position context_lens[b] - 1; its rows come from k_new / v_new instead of the cache.

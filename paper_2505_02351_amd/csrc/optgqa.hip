@@ -534,6 +534,20 @@ size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int n
 
 namespace {
 
+// Scales of 8-bit (E4M3) caches: one pair per tensor (k, v), or - k_heads / v_heads set, device
+// arrays of num_kv_heads values each - one pair per KV head.
+struct KvScales {
+    float k, v;
+    const float* k_heads;
+    const float* v_heads;
+    bool per_head() const { return k_heads != nullptr; }
+    bool valid() const
+    {
+        if (per_head()) return v_heads != nullptr;           // contents live on the device: not checked here
+        return k > 0.f && v > 0.f && k <= 3e38f && v <= 3e38f;
+    }
+};
+
 // New-token inputs of a fused decode step (all null / zero for plain attention).
 struct StepInputs {
     const void* k_new;
@@ -568,7 +582,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
                    float scale, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                    int max_blocks_per_seq, int max_context_len, int partition_size, void* workspace,
                    size_t workspace_bytes, int dtype, hipStream_t st, const StepInputs* step,
-                   const float* kv_scales = nullptr,      // {k_scale, v_scale}: the caches hold E4M3 codes
+                   const KvScales* kv_scales = nullptr,   // the caches hold E4M3 codes with these scales
                    int window = 0,                        // > 0: sliding window (Alg. 1, local mask)
                    const int32_t* shared_blocks = nullptr) // shared prefixes, read once per bundle of sequences
 {
@@ -580,8 +594,8 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     if (window > 0)                                      // head_dim 128: the equal-work kernel; 64: the general
         partition_size = head_dim == 128 ? OPTGQA_SPLIT_BALANCED : -1;   // kernel, unsplit (a window bounds the work)
     if (kv_scales) {
-        if (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f)
-            return OPTGQA_ERR_SHAPE;
+        if (kv_scales->per_head() && !kv_scales->v_heads) return OPTGQA_ERR_NULL;
+        if (!kv_scales->valid()) return OPTGQA_ERR_SHAPE;
         if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
         partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that reads E4M3 caches
     }
@@ -642,11 +656,16 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.part_tiles = 0;
     p.shared_blocks = shared_blocks;
     p.bundle = shared_blocks ? kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128) : 1;
-    if (kv_scales) {
-        p.scale2 *= kv_scales[0];
-        p.out_scale = kv_scales[1];
-        p.k_inv_scale = 1.0f / kv_scales[0];             // one fp32 division each, as the cache write does
-        p.v_inv_scale = 1.0f / kv_scales[1];
+    p.k_scales = p.v_scales = nullptr;
+    if (kv_scales && kv_scales->per_head()) {
+        p.k_scales = kv_scales->k_heads;                     // applied per KV head inside the kernels
+        p.v_scales = kv_scales->v_heads;
+        p.new_token_in_combine = step != nullptr;
+    } else if (kv_scales) {
+        p.scale2 *= kv_scales->k;
+        p.out_scale = kv_scales->v;
+        p.k_inv_scale = 1.0f / kv_scales->k;                 // one fp32 division each, as the cache write does
+        p.v_inv_scale = 1.0f / kv_scales->v;
         p.new_token_in_combine = step != nullptr;
     }
 
@@ -744,17 +763,17 @@ int optgqa_paged_attention_static(void* out, const void* q, const void* k_cache,
                           static_cast<hipStream_t>(stream), nullptr);
 }
 
-int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, void* v_cache,
-                                 const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
-                                 int head_dim, int block_size, int64_t k_token_stride,
-                                 int64_t v_token_stride, float k_scale, float v_scale,
-                                 int dtype, void* stream)
+static int reshape_and_cache_fp8_impl(const void* k, const void* v, void* k_cache, void* v_cache,
+                                      const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
+                                      int head_dim, int block_size, int64_t k_token_stride,
+                                      int64_t v_token_stride, const KvScales& sc, int dtype, void* stream)
 {
     if (num_tokens < 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
     const int64_t row = (int64_t)num_kv_heads * head_dim;
     if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
-    if (!(k_scale > 0.f) || !(v_scale > 0.f) || k_scale > 3e38f || v_scale > 3e38f) return OPTGQA_ERR_SHAPE;
+    if (sc.per_head() && !sc.v_heads) return OPTGQA_ERR_NULL;
+    if (!sc.valid()) return OPTGQA_ERR_SHAPE;
     if (num_tokens == 0) return OPTGQA_OK;
     if (!k || !v || !k_cache || !v_cache || !slot_mapping) return OPTGQA_ERR_NULL;
     // 16-byte pieces in, 8-byte pieces out
@@ -764,7 +783,8 @@ int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, vo
     const int64_t threads = (int64_t)num_tokens * num_kv_heads * (head_dim / 8) * 2;
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffffLL) return OPTGQA_ERR_SHAPE;
-    const float k_inv = 1.0f / k_scale, v_inv = 1.0f / v_scale;       // one fp32 division each
+    // one fp32 division each (per KV head: the same division, in the kernel)
+    const float k_inv = sc.per_head() ? 1.f : 1.0f / sc.k, v_inv = sc.per_head() ? 1.f : 1.0f / sc.v;
     hipStream_t st = static_cast<hipStream_t>(stream);
     auto kk = static_cast<const uint16_t*>(k);
     auto vv = static_cast<const uint16_t*>(v);
@@ -772,7 +792,30 @@ int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, vo
     auto vc = static_cast<unsigned char*>(v_cache);
     return launch(dtype == OPTGQA_F16 ? reshape_and_cache_e4m3_kernel<kF16> : reshape_and_cache_e4m3_kernel<kBF16>,
                   dim3((unsigned)blocks), dim3(256), 0, st, kk, vv, kc, vc, slot_mapping, num_tokens, num_kv_heads,
-                  head_dim, block_size, k_token_stride, v_token_stride, k_inv, v_inv);
+                  head_dim, block_size, k_token_stride, v_token_stride, k_inv, v_inv, sc.k_heads, sc.v_heads);
+}
+
+int optgqa_reshape_and_cache_fp8(const void* k, const void* v, void* k_cache, void* v_cache,
+                                 const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
+                                 int head_dim, int block_size, int64_t k_token_stride,
+                                 int64_t v_token_stride, float k_scale, float v_scale,
+                                 int dtype, void* stream)
+{
+    return reshape_and_cache_fp8_impl(k, v, k_cache, v_cache, slot_mapping, num_tokens, num_kv_heads, head_dim,
+                                      block_size, k_token_stride, v_token_stride,
+                                      KvScales{k_scale, v_scale, nullptr, nullptr}, dtype, stream);
+}
+
+int optgqa_reshape_and_cache_fp8_heads(const void* k, const void* v, void* k_cache, void* v_cache,
+                                       const int64_t* slot_mapping, int num_tokens, int num_kv_heads,
+                                       int head_dim, int block_size, int64_t k_token_stride,
+                                       int64_t v_token_stride, const float* k_scales, const float* v_scales,
+                                       int dtype, void* stream)
+{
+    if (!k_scales || !v_scales) return OPTGQA_ERR_NULL;
+    return reshape_and_cache_fp8_impl(k, v, k_cache, v_cache, slot_mapping, num_tokens, num_kv_heads, head_dim,
+                                      block_size, k_token_stride, v_token_stride,
+                                      KvScales{1.f, 1.f, k_scales, v_scales}, dtype, stream);
 }
 
 int optgqa_paged_attention_fp8(void* out, const void* q, const void* k_cache, const void* v_cache,
@@ -782,11 +825,26 @@ int optgqa_paged_attention_fp8(void* out, const void* q, const void* k_cache, co
                                int block_size, int max_blocks_per_seq, int max_context_len,
                                void* workspace, size_t workspace_bytes, int dtype, void* stream)
 {
-    const float kv_scales[2] = {k_scale, v_scale};
+    const KvScales kv_scales{k_scale, v_scale, nullptr, nullptr};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
-                          static_cast<hipStream_t>(stream), nullptr, kv_scales);
+                          static_cast<hipStream_t>(stream), nullptr, &kv_scales);
+}
+
+int optgqa_paged_attention_fp8_heads(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                     const int32_t* block_tables, const int32_t* context_lens,
+                                     const float* alibi_slopes, float scale, const float* k_scales,
+                                     const float* v_scales, int num_seqs, int num_heads, int num_kv_heads,
+                                     int head_dim, int block_size, int max_blocks_per_seq, int max_context_len,
+                                     void* workspace, size_t workspace_bytes, int dtype, void* stream)
+{
+    if (!k_scales || !v_scales) return OPTGQA_ERR_NULL;
+    const KvScales kv_scales{1.f, 1.f, k_scales, v_scales};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
+                          static_cast<hipStream_t>(stream), nullptr, &kv_scales);
 }
 
 int optgqa_decode_step(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
@@ -841,11 +899,28 @@ int optgqa_decode_step_fp8(void* out, const void* q, const void* k_new, const vo
                            int dtype, void* stream)
 {
     const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
-    const float kv_scales[2] = {k_scale, v_scale};
+    const KvScales kv_scales{k_scale, v_scale, nullptr, nullptr};
     return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
                           num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
                           OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
-                          static_cast<hipStream_t>(stream), &step, kv_scales);
+                          static_cast<hipStream_t>(stream), &step, &kv_scales);
+}
+
+int optgqa_decode_step_fp8_heads(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                                 void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                                 const float* alibi_slopes, float scale, const float* k_scales,
+                                 const float* v_scales, int num_seqs, int num_heads, int num_kv_heads,
+                                 int head_dim, int block_size, int max_blocks_per_seq, int max_context_len,
+                                 int64_t k_token_stride, int64_t v_token_stride, void* workspace,
+                                 size_t workspace_bytes, int dtype, void* stream)
+{
+    if (!k_scales || !v_scales) return OPTGQA_ERR_NULL;
+    const StepInputs step{k_new, v_new, k_token_stride, v_token_stride, k_cache, v_cache};
+    const KvScales kv_scales{1.f, 1.f, k_scales, v_scales};
+    return attention_impl(out, q, k_cache, v_cache, block_tables, context_lens, alibi_slopes, scale, num_seqs,
+                          num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_context_len,
+                          OPTGQA_SPLIT_BALANCED, workspace, workspace_bytes, dtype,
+                          static_cast<hipStream_t>(stream), &step, &kv_scales);
 }
 
 int optgqa_shared_prefix_bundle(int num_heads, int num_kv_heads, int head_dim)
@@ -926,10 +1001,10 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
                         const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
                         int num_seqs, int num_heads, int num_kv_heads, int head_dim, int block_size,
                         int max_blocks_per_seq, int max_q_len, int dtype, void* stream,
-                        const float* kv_scales, int window = 0)
+                        const KvScales* kv_scales, int window = 0)
 {
-    if (kv_scales && (!(kv_scales[0] > 0.f) || !(kv_scales[1] > 0.f) || kv_scales[0] > 3e38f || kv_scales[1] > 3e38f))
-        return OPTGQA_ERR_SHAPE;
+    if (kv_scales && kv_scales->per_head() && !kv_scales->v_heads) return OPTGQA_ERR_NULL;
+    if (kv_scales && !kv_scales->valid()) return OPTGQA_ERR_SHAPE;
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
         max_blocks_per_seq <= 0 || max_q_len < 0)
         return OPTGQA_ERR_SHAPE;
@@ -950,8 +1025,11 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     p.context_lens = context_lens;
     p.cu_q_lens = cu_q_lens;
     p.slopes = alibi_slopes;
-    p.scale2 = prefill_scale2(scale * (kv_scales ? kv_scales[0] : 1.f));
-    p.out_scale = kv_scales ? kv_scales[1] : 1.f;
+    const bool heads = kv_scales && kv_scales->per_head();
+    p.scale2 = prefill_scale2(scale * (kv_scales && !heads ? kv_scales->k : 1.f));
+    p.out_scale = kv_scales && !heads ? kv_scales->v : 1.f;
+    p.k_scales = heads ? kv_scales->k_heads : nullptr;
+    p.v_scales = heads ? kv_scales->v_heads : nullptr;
     p.window = window > 0 ? window : 0;
     p.k_in = p.v_in = nullptr;
     p.k_in_stride = p.v_in_stride = 0;
@@ -981,10 +1059,24 @@ int optgqa_paged_prefill_fp8(void* out, const void* q, const void* k_cache, cons
                              int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                              int max_q_len, int dtype, void* stream)
 {
-    const float kv_scales[2] = {k_scale, v_scale};
+    const KvScales kv_scales{k_scale, v_scale, nullptr, nullptr};
     return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
                         num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
-                        dtype, stream, kv_scales);
+                        dtype, stream, &kv_scales);
+}
+
+int optgqa_paged_prefill_fp8_heads(void* out, const void* q, const void* k_cache, const void* v_cache,
+                                   const int32_t* block_tables, const int32_t* context_lens,
+                                   const int32_t* cu_q_lens, const float* alibi_slopes, float scale,
+                                   const float* k_scales, const float* v_scales, int num_seqs, int num_heads,
+                                   int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                                   int max_q_len, int dtype, void* stream)
+{
+    if (!k_scales || !v_scales) return OPTGQA_ERR_NULL;
+    const KvScales kv_scales{1.f, 1.f, k_scales, v_scales};
+    return prefill_impl(out, q, k_cache, v_cache, block_tables, context_lens, cu_q_lens, alibi_slopes, scale,
+                        num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, max_q_len,
+                        dtype, stream, &kv_scales);
 }
 
 int optgqa_paged_prefill_window(void* out, const void* q, const void* k_cache, const void* v_cache,
@@ -1037,6 +1129,7 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
     p.slopes = alibi_slopes;
     p.scale2 = prefill_scale2(scale);
     p.out_scale = 1.f;
+    p.k_scales = p.v_scales = nullptr;
     p.window = 0;
     p.k_in = k;
     p.v_in = v;

@@ -74,6 +74,8 @@ struct PrefillParams {
     const float* slopes;        // [Hq] or nullptr
     float scale2;               // scale * log2(e) (times k_scale for E4M3 caches)
     float out_scale;            // multiplies the output (v_scale of an E4M3 cache, else 1)
+    const float* k_scales;      // E4M3 caches with one scale pair per KV head: device arrays [num_kv_heads]
+    const float* v_scales;      // (then scale2 holds no k_scale and out_scale is 1), else nullptr
     int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
     int num_seqs;
     int heads_per_wg;           // GH: query heads per workgroup (divides the group size, <= 16)
@@ -263,11 +265,14 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
             qb[m] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
     }
+    // score scale (base 2) and output scale of this workgroup's KV head
+    const float scale2 = KV8 && p.k_scales ? p.scale2 * p.k_scales[g] : p.scale2;
+    const float out_scale = KV8 && p.v_scales ? p.v_scales[g] : p.out_scale;
     // slope * (offset of the lane's e-th key from its first key in a tile) / score scale: the part of
     // the ALiBi term that does not change from tile to tile, as the score MFMAs' starting value
     f32x16 key_bias;
     {
-        const float per_key = slope2 / p.scale2;
+        const float per_key = slope2 / scale2;
 #pragma unroll
         for (int e = 0; e < 16; ++e) key_bias[e] = per_key * (float)(8 * (e >> 2) + (e & 3));
     }
@@ -344,7 +349,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         }
     };
 
-    const float scale2 = p.scale2;
     // ---- S^T = K Q^T : element 4i + j = score of key 32kt + 8i + 4h2 + j against row n32
     // (the accumulator starts from the tile-invariant part of the ALiBi term, already divided by the
     // score scale, so that one FMA per score finishes eq. (3))
@@ -515,7 +519,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     float lt = lsum;
     lt += __shfl_xor(lt, 32);
     if (row_ok) {
-        const float inv = p.out_scale / lt;
+        const float inv = out_scale / lt;
 #pragma unroll
         for (int db = 0; db < kDB; ++db)
 #pragma unroll

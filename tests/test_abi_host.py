@@ -323,3 +323,24 @@ def test_shared_prefix_host_checks(G):
     assert lib.optgqa_validate_shared_prefix_host(None, None, None, 0, 4, 4, 2, 1) == 0
     assert lib.optgqa_validate_shared_prefix_host(None, one, one, 2, 4, 4, 2, 1) == -1
     assert lib.optgqa_validate_shared_prefix_host(one, one, one, 2, 4, 4, 0, 1) == -2
+
+
+def test_per_head_scale_entry_points_reject_missing_arrays(G):
+    lib = G.load_library()
+    one = ctypes.c_void_p(16)
+    assert lib.optgqa_reshape_and_cache_fp8_heads(one, one, one, one, one, 4, 2, 128, 16, 256, 256, None, one, 0,
+                                                  None) == -1
+    assert lib.optgqa_reshape_and_cache_fp8_heads(one, one, one, one, one, 4, 2, 48, 16, 96, 96, one, one, 0,
+                                                  None) == -3
+    assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, None, 2, 8, 2, 128, 16,
+                                                8, 128, one, 1 << 30, 0, None) == -1
+    assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 64, 16,
+                                                8, 128, one, 1 << 30, 0, None) == -3          # head_dim 64
+    assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 128, 16,
+                                                8, 128, None, 0, 0, None) == -4               # workspace required
+    assert lib.optgqa_decode_step_fp8_heads(one, one, one, one, one, one, one, one, None, 0.1, None, None, 2, 8, 2,
+                                            128, 16, 8, 128, 256, 256, one, 1 << 30, 0, None) == -1
+    assert lib.optgqa_paged_prefill_fp8_heads(one, one, one, one, one, one, one, None, 0.1, None, one, 2, 8, 2, 128,
+                                              16, 8, 4, 0, None) == -1
+    assert lib.optgqa_paged_prefill_fp8_heads(one, one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 64,
+                                              16, 8, 4, 0, None) == -3

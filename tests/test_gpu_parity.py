@@ -702,6 +702,101 @@ def test_fp8_decode_step_edge_lengths(U, oracle, dtype):
     assert not got[lens == 0].any()
 
 
+HEAD_SCALES = [
+    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi, new tokens per sequence
+    (W.BF16, 32, 4, 32, 5, 40, 900, 1),
+    (W.F16, 12, 3, 16, 4, 1, 500, 1),           # G = 4, three KV heads
+    (W.BF16, 8, 8, 16, 3, 100, 400, 37),        # MHA, a prefill chunk
+    (W.F16, 16, 2, 64, 2, 200, 700, 130),       # G = 8, prefill
+]
+
+
+@pytest.mark.parametrize("i", range(len(HEAD_SCALES)))
+def test_fp8_per_head_scales(U, oracle, i):
+    """8-bit caches with one scale pair per KV head (scales spread over four orders of magnitude):
+    quantising cache write bit for bit, then - one new token per sequence - the decode call and the
+    one-call decode step (caches bit for bit again), or - a chunk of new tokens - the prefill, each
+    against the oracle's per-head clause."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    dtype, Hq, Hkv, bs, B, lo, hi, q_len = HEAD_SCALES[i]
+    kind = "decode" if q_len == 1 else "prefill"
+    cfg = W.small_config(name=f"fp8heads{i}", kind=kind, dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=128, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi,
+                         q_len=q_len, seed=2700 + i)
+    case = W.make_case(cfg)
+    rng = np.random.default_rng(2800 + i)
+    k_scales = (0.0125 * np.exp2(rng.integers(-3, 4, size=Hkv))).astype(np.float32)
+    v_scales = (0.02 * np.exp2(rng.uniform(-6, 6, size=Hkv))).astype(np.float32)       # not powers of two
+    shape = (cfg.num_blocks, Hkv, bs, 128)
+    k_all, v_all, slots = W.all_token_rows(case)
+    kc8, vc8 = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
+    O.reshape_and_cache_e4m3_heads(k_all, v_all, kc8, vc8, slots, k_scales, v_scales, dtype)
+    ks_d, vs_d = torch.from_numpy(k_scales).cuda(), torch.from_numpy(v_scales).cuda()
+    dk = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
+    dv = torch.full(shape, 0x7F, dtype=torch.uint8, device="cuda")
+    G.reshape_and_cache_fp8_heads(U.to_dev(k_all, dtype), U.to_dev(v_all, dtype), dk, dv, torch.from_numpy(slots).cuda(),
+                                  ks_d, vs_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+    dev = U.DevCase(case)
+    if kind == "decode":
+        ref = O.paged_attention_e4m3_heads(case.q, kc8, vc8, case.block_tables, case.context_lens, case.slopes,
+                                           case.scale, k_scales, v_scales, dtype)
+        ws = dev.workspace(BALANCED)[0]
+        dev.out.fill_(float("nan"))
+        G.paged_attention_fp8_heads(dev.out, dev.q, dk, dv, dev.block_tables, dev.context_lens, dev.slopes,
+                                    float(case.scale), ks_d, vs_d, case.max_context_len, ws)
+        torch.cuda.synchronize()
+        dev.check_canaries()
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"per-head scales {i}, decode")
+        # the one-call step: wipe the new tokens' rows, the step has to put the same codes back
+        s_ = torch.from_numpy(case.slot_mapping).cuda()
+        dk[s_ // bs, :, s_ % bs, :] = 0x7F
+        dv[s_ // bs, :, s_ % bs, :] = 0x7F
+        ws = dev.workspace(BALANCED)[0]
+        dev.out.fill_(float("nan"))
+        G.decode_step_fp8_heads(dev.out, dev.q, dev.k_new, dev.v_new, dk, dv, dev.block_tables, dev.context_lens,
+                                dev.slopes, float(case.scale), ks_d, vs_d, case.max_context_len, ws)
+        torch.cuda.synchronize()
+        dev.check_canaries()
+        assert np.array_equal(dk.cpu().numpy(), kc8) and np.array_equal(dv.cpu().numpy(), vc8)
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"per-head scales {i}, decode step")
+    else:
+        ref = O.paged_prefill_e4m3_heads(case.q, kc8, vc8, case.block_tables, case.context_lens, case.cu_q_lens,
+                                         case.slopes, case.scale, k_scales, v_scales, dtype)
+        dev.out.fill_(float("nan"))
+        G.paged_prefill_fp8_heads(dev.out, dev.q, dk, dv, dev.block_tables, dev.context_lens, dev.cu_q_lens,
+                                  dev.slopes, float(case.scale), ks_d, vs_d, case.max_q_len)
+        torch.cuda.synchronize()
+        dev.check_canaries()
+        U.check_scaled(U.to_host(dev.out), ref, dtype, f"per-head scales {i}, prefill")
+
+
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_fp8_per_head_cache_write_every_input_pattern(U, oracle, dtype):
+    """All 65 536 two-byte patterns through the quantising cache write with a different scale per KV
+    head (eight heads: subnormal codes, the normal range, saturation): codes bit for bit."""
+    import torch
+    import oracle as O
+    import paper_2505_02351_amd as G
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(64, 8, 128)     # [T][Hkv][D]
+    slots = np.random.default_rng(2).permutation(96)[:64].astype(np.int64)
+    k_scales = np.array([1.0, 37.5, 3e-3, 0.013, 2.0 ** -12, 1e4, 0.7, 5.0], np.float32)
+    v_scales = k_scales[::-1].copy()
+    kc8 = np.full((6, 8, 16, 128), 0x7F, np.uint8)
+    vc8 = np.full((6, 8, 16, 128), 0x7F, np.uint8)
+    O.reshape_and_cache_e4m3_heads(bits, bits, kc8, vc8, slots, k_scales, v_scales, dtype)
+    dk = torch.full(kc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    dv = torch.full(vc8.shape, 0x7F, dtype=torch.uint8, device="cuda")
+    G.reshape_and_cache_fp8_heads(U.to_dev(bits, dtype), U.to_dev(bits, dtype), dk, dv, torch.from_numpy(slots).cuda(),
+                                  torch.from_numpy(k_scales).cuda(), torch.from_numpy(v_scales).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(dk.cpu().numpy(), kc8)
+    assert np.array_equal(dv.cpu().numpy(), vc8)
+
+
 def test_fp8_rejects_what_it_cannot_do(U):
     import torch
     import paper_2505_02351_amd as G

@@ -77,6 +77,7 @@ T.test_validate_tables_host(G)
 T.test_static_scratch_entry_point_refuses_what_does_not_fit(G)
 T.test_non_finite_scale_is_refused(G)
 T.test_shared_prefix_host_checks(G)
+T.test_per_head_scale_entry_points_reject_missing_arrays(G)
 print("host paths ok")
 """
     out = run_child(code, rt[-1])
