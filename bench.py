@@ -39,13 +39,43 @@ sys.path.insert(1, os.path.join(ROOT, "tests"))      # harness.py: device copies
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA, published
 KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-448 covers +-5.6 sigma
-# HBM bytes per attention call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
-# factor a plain copy kernel of known size reads on the same counters.  None until
-# measured for the workload.
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs per workload (FETCH_SIZE,
+# then WRITE_SIZE, KiB per dispatch, mean of 12 dispatches), each scaled by what the same counter
+# reads for a plain device copy of 1 GiB (FETCH_SIZE reads 524 301 KiB per GiB copied: x 2.000;
+# WRITE_SIZE 1 048 576 KiB: x 1.000).  Keyed by what was run; the summary each entry comes from is
+# named next to it.  Not measured in this run: an entry goes stale when its kernel changes, and a
+# workload / variant without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # from the committed rocprofv3 counter summary of this workload: (311544.7 KiB FETCH_SIZE x 2.000 + 5330.4 KiB WRITE_SIZE x 1.000) x 1024
-    "C3": 643501963,
+    # key: (bytes, profile summary)                   (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
+    "C1": (100_352, "profiles/paged_decode_C1_C2_C4.md"),                       # 48.5, 1.0
+    "C2": (83_370_701, "profiles/paged_decode_C1_C2_C4.md"),                    # 39 597.4, 2 221.9
+    "C3": (643_842_560, "profiles/paged_decode_C3.md"),                         # 311 711.2, 5 330.1
+    "C3-all8k": (1_088_673_587, "profiles/paged_decode_C3_all8k.md"),           # 528 917.1, 5 323.6
+    "C4": (551_843_738, "profiles/paged_decode_C1_C2_C4.md"),                   # 265 284.9, 8 340.1 (P = 512)
+    "C4|partition=0": (550_444_442, "profiles/paged_decode_C1_C2_C4.md"),       # 266 650.9, 4 241.6
+    "C5": (151_285_248, "profiles/paged_prefill_C5.md"),                        # 57 485.3, 32 768.9
+    "C5-prompt": (505_554_534, "profiles/paged_prefill_C5_variants.md"),        # 123 967.7, 245 770.2
+    "C3|e4m3": (332_491_264, "profiles/paged_decode_C3_e4m3.md"),               # 157 676.6, 9 345.3
+    "C5|e4m3": (109_353_984, "profiles/paged_prefill_C5_variants.md"),          # 37 011.5, 32 768.0
+    "C3|window=1024": (148_234_342, "profiles/paged_decode_C3_window.md"),      # 69 794.6, 5 170.9
+    "C5|window=512": (100_934_554, "profiles/paged_prefill_C5_variants.md"),    # 32 900.4, 32 768.1
+    "C3|shared=2": (428_900_762, "profiles/paged_decode_C3_shared_prefix.md"),  # 205 156.5, 8 535.4
+    "C3|shared=4": (476_663_910, "profiles/paged_decode_C3_shared_prefix.md"),  # 228 825.8, 7 840.5
 }
+
+
+def traffic_key(args, workload: str) -> str:
+    """Key of MEASURED_TRAFFIC_BYTES for this run."""
+    parts = [workload]
+    if args.partition_size is not None:
+        parts.append(f"partition={args.partition_size}")
+    if args.kv_cache == "e4m3":
+        parts.append("e4m3")
+    if args.window > 0:
+        parts.append(f"window={args.window}")
+    if args.shared_prefix > 1:
+        parts.append(f"shared={args.shared_prefix}" + ("" if args.shared_prefix_kernel == "bundled" else ",plain"))
+    return "|".join(parts)
 
 
 def parse():
@@ -376,19 +406,23 @@ def main():
         n_q = case.num_tokens
         launch_ms = {"mean": float(kernel_ms.mean()), "median": float(np.median(kernel_ms)),
                      "min": float(kernel_ms.min()), "p90": float(np.percentile(kernel_ms, 90))}
+        traffic = MEASURED_TRAFFIC_BYTES.get(traffic_key(args, cfg.name), (None, None))
+        # bytes the kernel has to read: with the bundled shared-prefix kernel a bundle's shared blocks count once
+        unique_kv_bytes = kv_bytes - 2 * bundle_read_tokens * cfg.num_kv_heads * cfg.head_dim * 2
         if decode:
-            achieved = kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
+            achieved = unique_kv_bytes / (kernel_ms.mean() * 1e-3) / 1e9
             if chosen_P == G.SPLIT_BALANCED:
-                kname = "paged_decode_flat_kernel (equal-work split%s%s)" % (
+                kname = "paged_decode_flat_kernel (equal-work split%s%s%s)" % (
                     ", E4M3 caches, new token merged by the combine kernel" if e4m3 else ", cache write fused" if one_call else "",
-                    f", window {window}" if window else "")
+                    f", window {window}" if window else "", ", shared prefixes read once per bundle" if bundled else "")
+            elif cfg.head_dim == 128 and chosen_P > 0:
+                kname = f"paged_decode_flat_kernel (fixed partitions of {chosen_P} tokens on the equal-work kernel)"
             else:
-                kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (fixed partitions)"
+                kname = "paged_decode_mma_kernel / paged_decode_mc_kernel (unsplit or fixed partitions)"
             roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": achieved / HBM_PEAK_GBS,
-                        "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)
-                        if args.partition_size is None and not e4m3 and not window else None,
-                        "kernel": kname, "algorithmic_bytes_per_launch": kv_bytes, "launch_ms": launch_ms}
+                        "traffic": traffic[0], "traffic_source": traffic[1],
+                        "kernel": kname, "algorithmic_bytes_per_launch": unique_kv_bytes, "launch_ms": launch_ms}
         else:
             # causal prefill: query i of sequence b sees pos_i + 1 keys; QK^T and PV are 2 * D flops per
             # (query, key, head) each
@@ -403,7 +437,7 @@ def main():
                 flops += 4 * cfg.num_heads * cfg.head_dim * int(visible)
             achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": None,
+                        "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": traffic[0], "traffic_source": traffic[1],
                         "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else "")
                                   + (" (K/V from the contiguous inputs, cache write fused)" if prompt else "")
                                   + (f" (window {window})" if window else ""),
@@ -476,8 +510,9 @@ def main():
         if cold:
             result["cold_step"] = cold
         if shared_tokens:
-            result["roofline"]["note"] = ("algorithmic bytes count every sequence's logical KV; %d of %d context "
-                                          "tokens alias another sequence's blocks (%s): not an HBM rate"
+            result["roofline"]["note"] = ("`value` counts every sequence's logical KV bytes; %d of %d context "
+                                          "tokens alias another sequence's blocks (%s); `roofline` counts the "
+                                          "bytes the kernel has to read"
                                           % (shared_tokens, int(case.context_lens.sum()),
                                              "the bundled kernel reads a bundle's shared blocks once" if bundled
                                              else "the plain kernel reads them once per sequence"))

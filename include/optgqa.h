@@ -1,10 +1,10 @@
 /*
  * optgqa -- paged grouped-query attention with ALiBi biases for AMD MI355X (gfx950).
  *
- * C ABI of the attention hot path of Opt-GQA (Alg. 1 "Opt-GQA Forward Pass" and Alg. 2
- * "Opt-GQA Optimization on DCU" of the paper): the forward pass takes (Q, K, V, C_K, C_V, M)
+ * C ABI of the attention hot path of Opt-GQA (Alg. 1, the forward pass, and Alg. 2,
+ * its optimised form on the accelerator, of the paper): the forward pass takes (Q, K, V, C_K, C_V, M)
  * and returns the attention output; M.is_prompt selects the prompt branch or the
- * "context attention with caches" branch.  Here the two branches are two entry points and
+ * branch that attends over the caches.  Here the two branches are two entry points and
  * the cache store is a third.
  *
  * General rules for every entry point
@@ -70,7 +70,7 @@ int optgqa_abi_version(void);
 const char *optgqa_status_string(int status);
 
 /*
- * KV-cache write (Alg. 1 "Reshape and store K, V into C_K, C_V"; eq. (2): the cache is the
+ * KV-cache write (Alg. 1, the cache-store step; eq. (2): the cache is the
  * concatenation, along the token axis, of all blocks so far).
  *
  * For each token t with slot = slot_mapping[t] >= 0, the 2-byte patterns of k[t][g][:] and
@@ -91,7 +91,7 @@ int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *
                              int64_t v_token_stride, int dtype, void *stream);
 
 /*
- * Decode attention over the paged cache (Alg. 2 "Compute context attention with caches";
+ * Decode attention over the paged cache (Alg. 2, the non-prompt branch;
  * eq. (3)-(4); Section II query grouping, shared key-value and ALiBi; Section III-A pages
  * and partitions).
  *
@@ -328,8 +328,8 @@ int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const vo
                          int dtype, void *stream);
 
 /*
- * Local attention (Alg. 1: when no ALiBi slopes are given the bias is built from "causal and
- * local" masks; eq. (4) adds the mask inside the softmax).  The paper fixes no window size and
+ * Local attention (Alg. 1: when no ALiBi slopes are given the bias is built from a causal and a
+ * local mask; eq. (4) adds the mask inside the softmax).  The paper fixes no window size and
  * no boundary convention; here `window` = W > 0 means that the query at position pos sees
  * exactly the keys pos - W < j <= pos (all of them while pos + 1 <= W).  The mask composes
  * with the ALiBi term, which stays relative to the query's position: pass alibi_slopes or NULL.
@@ -429,8 +429,8 @@ int optgqa_validate_shared_prefix_host(const int32_t *block_tables_host,
                                        int new_tokens);
 
 /*
- * Whole-prompt attention with empty caches (Alg. 1, prompt branch: "Reshape and store K, V into
- * C_K, C_V", then causal / ALiBi attention computed on the inputs themselves).  Sequence b owns
+ * Whole-prompt attention with empty caches (Alg. 1, prompt branch: the cache-store step,
+ * then causal / ALiBi attention computed on the inputs themselves).  Sequence b owns
  * tokens cu_seq_lens[b] .. cu_seq_lens[b+1] - 1 of q, k, v; token i of a sequence attends to
  * tokens 0 .. i of the same sequence with bias slope_h * (j - i).  K / V are read from the
  * contiguous inputs, never from the cache.  With k_cache and v_cache given, the same launch

@@ -8,17 +8,17 @@
  *
  * It is the plain definition written out in fp64, because paging, grouping and
  * partitioning are re-organisations of the same sum, not approximations
- * (Section II "Shared Key-Value"; Section III-A on pages and blocks):
+ * (Section II on the key-value pair shared by a group; Section III-A on pages and blocks):
  *
  *   score      eq. (3):  s_j = scale * <q_h, k_j> + bias(i, j)
- *   bias       Section II "Integration and Optimization of ALiBi":
+ *   bias       Section II, the ALiBi paragraph:
  *                        bias(i, j) = slope_h * (j - pos_i), linear in the
  *                        relative position of key j and query i
  *   softmax    eq. (4):  w_j = exp(s_j) / sum_j exp(s_j)
  *   output     Section III-A, paragraph after eq. (4): out = sum_j w_j v_j
  *   grouping   Section I / II: the G = Hq/Hkv query heads of a group share one
  *                        K/V head; head h reads KV head floor(h / G)
- *   cache      eq. (2), Alg. 1 "Reshape and store K, V into C_K, C_V":
+ *   cache      eq. (2), Alg. 1 (the cache-store step):
  *                        new tokens' K/V rows are appended to the paged cache
  *   causality  Alg. 1 (prompt branch): query i sees keys 0..pos_i only
  *
@@ -96,7 +96,7 @@ void oracle_set_num_threads(int n)
 #endif
 }
 
-/* ---- cache write: eq. (2), Alg. 1 "store K, V into C_K, C_V" ------------ */
+/* ---- cache write: eq. (2), Alg. 1 (the cache-store step) -------------- */
 void oracle_reshape_and_cache(const uint16_t *k, const uint16_t *v,
                               uint16_t *k_cache, uint16_t *v_cache,
                               const int64_t *slot_mapping,
@@ -200,8 +200,8 @@ void oracle_paged_attention_rows(double *out, const int32_t *row_seq, const int3
     }
 }
 
-/* ---- split context: Section III-A, "the output of each block is cached and then
- * used in the computation of the next block".  Each run of partition_size tokens
+/* ---- split context: Section III-A (a block's result is kept and carried into the next
+ * block's computation).  Each run of partition_size tokens
  * yields its own maximum m_p, sum l_p and normalised output o_p; they combine as
  *   m = max_p m_p,   out = sum_p e^{m_p-m} l_p o_p / sum_p e^{m_p-m} l_p,
  * which equals the unpartitioned result.  Written out literally so that the

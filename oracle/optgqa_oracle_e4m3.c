@@ -12,7 +12,7 @@
  *   format    E4M3 ("FN" flavour of the open 8-bit floating-point formats): 1 sign bit, 4 exponent
  *             bits with bias 7, 3 mantissa bits; no infinities; exponent 15 with mantissa 7 is
  *             NaN; largest finite magnitude 448; subnormals m * 2^-9.
- *   store     eq. (2) / Alg. 1 "store K, V" with a quantiser in front:
+ *   store     eq. (2) / Alg. 1 (the cache-store step) with a quantiser in front:
  *                 code = nearest_e4m3( fp32(k) * fp32(1 / k_scale) )
  *             The product is ONE fp32 multiplication (the reciprocal is one fp32 division), the
  *             rounding to E4M3 is to nearest, ties to the even code, magnitudes above 448

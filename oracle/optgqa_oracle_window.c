@@ -4,7 +4,7 @@
  * TEST INFRASTRUCTURE ONLY (see optgqa_oracle.c).  Shares nothing with the HIP kernels; written
  * again from the definitions so that it stands alone.
  *
- * Alg. 1 builds "causal and local attention masks" for the bias term when no ALiBi slopes are
+ * Alg. 1 builds a causal and a local attention mask for the bias term when no ALiBi slopes are
  * given, and eq. (4) adds the mask inside the softmax.  The paper gives no window size and does
  * not say which side of the boundary is kept; the reading taken here (the usual one for sliding
  * windows): with window W > 0 the query at position pos sees exactly the W keys

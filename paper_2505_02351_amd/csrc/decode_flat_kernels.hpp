@@ -670,7 +670,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 // Its term is added here from k_new / v_new - quantised exactly as the cache write quantises,
 // so that it is the cache's own codes that are attended to - and the thread that holds dims
 // od .. od + 3 of a KV head's first query head stores the four K and four V codes into the caches
-// (Alg. 2 "store K, V": nothing in the step has read that cache row).
+// (Alg. 2, the cache-store step: nothing in the step has read that cache row).
 //
 // SHARED: a head's partial results lie in two staircases - the pieces of its own segment (virtual
 // sequence 2b + 1, column = the head) and, if the sequence takes part in its bundle's shared

@@ -2,8 +2,8 @@
 //
 // Work unit: one workgroup (4 waves) per (context partition, KV head [x head chunk], sequence).
 // The GH query heads of the group that the workgroup serves all consume the SAME K and V
-// registers, so every KV element is fetched from HBM once per KV-head group (Section II,
-// "Shared Key-Value"), with 16-byte loads that cover a token row with D/8 consecutive lanes.
+// registers, so every KV element is fetched from HBM once per KV-head group (Section II: a group
+// shares one key-value pair), with 16-byte loads that cover a token row with D/8 consecutive lanes.
 //
 // Lane layout inside a wave: LPR = D/8 lanes share one token row (lane c holds dims 8c..8c+7),
 // TPS = 64/LPR token rows are processed per step.  Each row group keeps its own running

@@ -21,7 +21,7 @@
 // addresses, which leaves registers to spare: K/V tiles are fetched straight into VGPRs,
 // kMmaBufs - 1 tiles (8 KiB each per wave) ahead of the arithmetic, in a rotating set of
 // register buffers (the loop is unrolled by kMmaBufs so that the rotation costs no moves).
-// One K/V fetch serves all heads of the group (Section II, "Shared Key-Value").
+// One K/V fetch serves all heads of the group (Section II: a group shares one key-value pair).
 //
 // Softmax uses a lazily moved reference instead of the exact running maximum: with ALiBi the
 // scores climb steadily along the context and an exact running maximum would rescale the

@@ -4,7 +4,7 @@
 // Workgroup (4 or 8 waves, see WAVES below) = 32 (query token, head) rows per wave of one
 // (sequence, KV head [x chunk of the group]) against the whole visible context, in 32-key tiles
 // staged through LDS and shared by the waves.  Heads vary fastest inside the rows, so all heads of the group consume the same K/V
-// tile (Section II, "Shared Key-Value").
+// tile (Section II: a group shares one key-value pair).
 //
 // A wave owns 32 rows.  Both contractions are computed transposed, with v_mfma_f32_32x32x16, so that
 // no operand has to be transposed in registers:
@@ -143,8 +143,8 @@ template <> struct PfSoftmax<kBF16> {
 // empty caches): the context of sequence b is its own cu_q_lens[b+1] - cu_q_lens[b] tokens, and
 // K / V tiles are fetched from the contiguous inputs k_in / v_in (token strides) instead of
 // through the block table.  With k_cache_w / v_cache_w set, the workgroups of a KV head's first
-// head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1 "reshape
-// and store K, V"), so the step needs no separate cache-write launch.
+// head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1, the
+// cache-store step), so the step needs no separate cache-write launch.
 template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128, int WAVES = 4>
 __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
 {

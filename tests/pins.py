@@ -254,7 +254,7 @@ def check_two_key_hand_case(lib=None):
 
 
 def check_gqa_equals_mha_on_repeated_kv(lib=None):
-    """Section II "Shared Key-Value": sharing one K/V per group is the same as every head of
+    """Section II (a group shares one key-value pair): sharing one K/V per group is the same as every head of
     the group holding its own copy."""
     cfg = W.small_config(name="gqa", dtype=W.F16, batch=2, num_heads=8, num_kv_heads=2,
                          head_dim=8, block_size=4, ctx_hi=33, seed=21)

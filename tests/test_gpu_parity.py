@@ -1091,7 +1091,7 @@ def test_prompt_prefill_rejects_what_it_cannot_do(U):
 
 def test_decode_with_shared_prefix_blocks(U, oracle):
     """Block tables that alias each other (groups of sequences served from the same physical
-    prefix blocks, Section III-B "cache sharing and reuse"): nothing in the path assumes blocks are
+    prefix blocks; Section III-B speaks of sharing and reusing cached blocks): nothing in the path assumes blocks are
     private, so the step must still match the oracle, which walks the same tables."""
     cfg = W.small_config(name="shared", dtype=W.BF16, batch=12, num_heads=16, num_kv_heads=4, head_dim=128,
                          block_size=16, num_blocks=12 * 64 + 7, ctx_lo=300, ctx_hi=1000, seed=2100)
