@@ -86,6 +86,9 @@ def parse():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--partition-size", type=int, default=None,
                     help="override the workload's partition size (0 = library chooses, -1 = never split)")
+    ap.add_argument("--head-dim", type=int, choices=[64, 128], default=None,
+                    help="run the workload's shapes at this head_dim instead of its own (the workload is then "
+                         "named <workload>-d<head_dim>: a variant, not one of the configured workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lib", default=None, help="load this build of liboptgqa.so instead of the in-tree one")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -191,7 +194,7 @@ def cpu_baseline(case, W, n_seqs: int, min_seconds: float = 10.0, window: int = 
         what = f"every 16th (query token, head) row of sequence 0 ({len(rows)} rows)"
 
         def run():
-            if cfg.name.endswith("-prompt"):
+            if "-prompt" in cfg.name:
                 O.prompt_attention(case.q, case.k_new, case.v_new, case.cu_q_lens, case.slopes, case.scale,
                                    case.dtype, rows=rows)
             elif window > 0:
@@ -257,6 +260,9 @@ def main():
     def measure(workload: str, steps: int, warmup: int):
         """Runs one workload; returns (result dict, case)."""
         cfg = W.CONFIGS[workload]
+        if args.head_dim is not None and args.head_dim != cfg.head_dim:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, head_dim=args.head_dim, name=f"{cfg.name}-d{args.head_dim}")
         case = W.make_case(cfg)
         shared_tokens = 0
         if args.shared_prefix > 1:
@@ -309,7 +315,7 @@ def main():
                 if members:
                     bundle_read_tokens += len(members) * int(min(shared_host[b] for b in members)) * cfg.block_size
 
-        prompt = cfg.name.endswith("-prompt")       # whole prompts, caches empty: one call stores K/V and attends
+        prompt = "-prompt" in cfg.name       # whole prompts, caches empty: one call stores K/V and attends
         assert not (prompt and (e4m3 or window)), "the whole-prompt workload runs over 2-byte inputs, full causal mask"
 
         def step():
@@ -523,7 +529,7 @@ def main():
         return result, case
 
     result, case = measure(args.workload, args.steps, args.warmup)
-    if (args.workload == "C3" and args.partition_size is None and not args.no_target_check
+    if (args.workload == "C3" and args.head_dim in (None, 128) and args.partition_size is None and not args.no_target_check
             and args.kv_cache == "native" and args.window <= 0):
         # the target is worded "batch 64 / 8k context": the same batch with every context at 8192
         extra, _ = measure("C3-all8k", max(args.steps // 2, 1), max(args.warmup // 2, 1))

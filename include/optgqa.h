@@ -112,9 +112,8 @@ int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *
  *                       block_size and of 16), one workgroup per run, then combine;
  *                   OPTGQA_SPLIT_BALANCED: split by equal work - every wave of the launch gets
  *                       the same number of 16-token tiles, whatever the mix of context
- *                       lengths, and the pieces are combined afterwards (head_dim 128 only,
- *                       else OPTGQA_ERR_UNSUPPORTED); this is also what 0 picks for
- *                       head_dim 128 whenever it splits;
+ *                       lengths, and the pieces are combined afterwards; this is also what
+ *                       0 picks whenever it splits;
  *                   any other negative value: never split.
  *   workspace       fp32 scratch for the split path, at least
  *                   optgqa_paged_attention_workspace_bytes(...) bytes for the same arguments;
@@ -175,7 +174,7 @@ int optgqa_set_kernel_events(void *start_event, void *stop_event);
  * Same result, bit for bit in the caches and to rounding in `out`, as
  * optgqa_reshape_and_cache with that slot mapping followed by optgqa_paged_attention with
  * partition_size 0; sequences with context_lens[b] == 0 write nothing and give a row of +0.
- * Where the equal-work split applies (head_dim 128, workspace given) the cache write happens
+ * Where the equal-work split applies (a context worth splitting, workspace given) the cache write happens
  * inside the attention kernel - one launch less per step; otherwise the library issues the
  * two launches itself.
  *
@@ -213,7 +212,7 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
  * optgqa_paged_attention_fp8: as optgqa_paged_attention over such caches (dequantise, then attend):
  *     s_j = scale * k_scale * <q[b][h], value(kcode_j)> + alibi_slopes[h] * (j - (L - 1))
  *     out[b][h] = v_scale * sum_j softmax(s)_j * value(vcode_j)
- * q and out are 2-byte elements of `dtype`.  head_dim 128 only; always the equal-work split, so
+ * q and out are 2-byte elements of `dtype`.  Always the equal-work split, so
  * the workspace of optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED, ...) is
  * required (OPTGQA_ERR_WORKSPACE without it).
  *
@@ -226,8 +225,7 @@ int optgqa_decode_step(void *out, const void *q, const void *k_new, const void *
  * aligned, strides multiples of 8 (OPTGQA_ERR_UNSUPPORTED otherwise); workspace required.
  *
  * optgqa_paged_prefill_fp8: as optgqa_paged_prefill over such caches, same formulas with the
- * causal bound (query i of sequence b sees keys 0 .. pos_i).  head_dim 128 only
- * (OPTGQA_ERR_UNSUPPORTED otherwise); no workspace.
+ * causal bound (query i of sequence b sees keys 0 .. pos_i).  No workspace.
  */
 int optgqa_reshape_and_cache_fp8(const void *k, const void *v, void *k_cache, void *v_cache,
                                  const int64_t *slot_mapping, int num_tokens, int num_kv_heads,
@@ -339,11 +337,10 @@ int optgqa_paged_prefill(void *out, const void *q, const void *k_cache, const vo
  *   optgqa_decode_step_window       optgqa_decode_step (cache write + attention) likewise
  *   optgqa_paged_prefill_window     optgqa_paged_prefill, every new token with its own window
  *
- * window <= 0 is OPTGQA_ERR_SHAPE (call the plain entry points for full attention).  For
- * head_dim 128 the two decode calls always use the equal-work split: a workspace of
+ * window <= 0 is OPTGQA_ERR_SHAPE (call the plain entry points for full attention).  The two
+ * decode calls always use the equal-work split: a workspace of
  * optgqa_paged_attention_workspace_bytes(..., OPTGQA_SPLIT_BALANCED) bytes is required
- * (OPTGQA_ERR_WORKSPACE without it).  head_dim 64 runs unsplit through the general kernels (a
- * window bounds the work per query) and needs no workspace.  Other arguments, layouts,
+ * (OPTGQA_ERR_WORKSPACE without it).  Other arguments, layouts,
  * ownership and errors as for the calls they extend.
  */
 int optgqa_paged_attention_window(void *out, const void *q, const void *k_cache,
@@ -396,7 +393,7 @@ int optgqa_paged_prefill_window(void *out, const void *q, const void *k_cache, c
  *                   decode step whose token is counted in context_lens but not yet cached, else 0).
  *   workspace       required: optgqa_shared_prefix_workspace_bytes(...) bytes (always the
  *                   equal-work split; OPTGQA_ERR_WORKSPACE without it).
- * head_dim 128, 2-byte caches, no window (OPTGQA_ERR_UNSUPPORTED otherwise).  Results: what
+ * 2-byte caches, no window (there are no entry points for the combinations).  Results: what
  * optgqa_paged_attention / optgqa_decode_step give on the same tables, to rounding (the
  * definition does not know about sharing: eq. (3), (4) over the tokens the tables name).
  */

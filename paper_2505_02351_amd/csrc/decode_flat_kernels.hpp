@@ -1,4 +1,4 @@
-// Paged decode attention for head_dim 128 with the context split by EQUAL WORK instead of by
+// Paged decode attention (head_dim 128 or 64) with the context split by EQUAL WORK instead of by
 // fixed-size partitions (Section III-A splits the context into partitions whose results are
 // carried forward and merged; here the partition boundaries are chosen so that every wave of
 // the launch streams the same number of K/V bytes).
@@ -53,7 +53,9 @@ namespace optgqa {
 #define OPTGQA_FLAT_WAVES_PER_SIMD 2
 #endif
 
-constexpr int kFlatVRow = 128 + 16;      // LDS V row, elements: 288 bytes (see prefill_kernels.hpp, same reason)
+// LDS V row, elements: head_dim + 16, i.e. 288 bytes (see prefill_kernels.hpp, same reason) or 160 - either
+// way the four rows that a group of 16 lanes transposes, and the next group's four, fall in distinct banks
+template <int D> struct FlatRow { static constexpr int kV = D + 16; };
 
 // How far the softmax reference may lag behind the running maximum before the accumulators are
 // rescaled, and how far above the maximum it is then put.  16-bit weights: fp16 must keep them
@@ -203,21 +205,35 @@ __device__ __forceinline__ FlatSeg flat_seg(const DecodeParams& p, int v)
 // fragments: partition pi of segment (b, y) leaves its partial results in slots
 // ((b * Y + y) * num_partitions + pi) * 2 + (0: the fragment that starts the partition, 1: the
 // rest, if a unit boundary fell inside).  Plain attention over 2-byte caches only.
-struct MmaTile8 {
-    uint4 k[2];     // K: token j16, dims 64j + 16hg .. +15
-    uint2 v[4];     // V: token 4s + hg, dims 8*j16 .. +7
+//
+// Head dimension D (128 or 64).  A K row is D / 32 sixteen-byte pieces per lane group hg, one score MFMA each;
+// a V tile (16 rows of D elements) is fetched D / 8 lanes to a row, 512 / D rows per load, D / 32 loads;
+// the output is D / 16 blocks of 16 dims.
+template <int D> struct FlatTile {
+    uint4 k[D / 32];    // K: token j16, dims 32i + 8hg .. +7
+    uint4 v[D / 32];    // V: token (512 / D) * r + lane / (D / 8), dims 8 * (lane % (D / 8)) .. +7
+};
+template <int D> struct FlatTile8 {
+    uint4 k[D / 64];    // K: token j16, dims 64j + 16hg .. +15
+    uint2 v[D / 32];    // V: as above, 8 one-byte codes
 };
 
-template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false>
+template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false, int D = 128>
 __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8 : OPTGQA_FLAT_WAVES_PER_SIMD) void paged_decode_flat_kernel(const DecodeParams p)
 {
+    static_assert(D == 128 || D == 64, "head_dim 128 or 64");
     static_assert(!(SHARED && KV8), "shared prefixes: 2-byte caches");
     static_assert(!(PARTS && (FUSED || KV8 || SHARED)), "fixed partitions: plain attention over 2-byte caches");
     constexpr bool NEW_TILE = FUSED && !KV8;            // the new token is a tile of its own, read from k_new / v_new
-    typedef typename std::conditional<KV8, MmaTile8, MmaTile>::type Tile;
+    typedef typename std::conditional<KV8, FlatTile8<D>, FlatTile<D>>::type Tile;
     constexpr int ES = KV8 ? 1 : 2;                     // bytes per cache element
-    constexpr int D = 128;
     constexpr int TILE = kMmaTile;
+    constexpr int kFlatVRow = FlatRow<D>::kV;
+    constexpr int NQ = D / 32;                          // score MFMAs per tile (32 dims each)
+    constexpr int NDB = D / 16;                         // 16-dim blocks of the output
+    constexpr int LPR = D / 8;                          // lanes that fetch one V row (8 elements each)
+    constexpr int RPL = 64 / LPR;                       // V rows per load
+    constexpr int NVL = TILE / RPL;                     // V loads per tile
     static_assert(kMmaBufs == 2, "two register tile buffers: one in use, one in flight");
 
     // per wave: the V rows of two consecutive tiles (32 tokens) in their natural [token][dim] layout
@@ -227,6 +243,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j16 = lane & 15;
     const int hg = lane >> 4;
+    const int vcol = lane % LPR, vrow0 = lane / LPR;    // this lane's piece of a V tile: rows RPL * r + vrow0, dims 8 * vcol .. +7
 
     const int B = p.num_seqs, Y = p.segs_per_seq;
     const int NV = SHARED ? 2 * B : B;                  // (virtual) sequences of the flat order
@@ -362,23 +379,23 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const unsigned char* ka = s.k + min(j16, s.last_row) * (D * ES) + 16 * hg;
         if constexpr (KV8) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) Tl.k[j] = stream_load16(ka + 64 * j);
+            for (int j = 0; j < D / 64; ++j) Tl.k[j] = stream_load16(ka + 64 * j);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                Tl.v[r] = stream_load8(s.v + min(4 * r + hg, s.last_row) * D + 8 * j16);
+            for (int r = 0; r < NVL; ++r)
+                Tl.v[r] = stream_load8(s.v + min(RPL * r + vrow0, s.last_row) * D + 8 * vcol);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) Tl.k[i] = stream_load16(ka + 64 * i);
+            for (int i = 0; i < NQ; ++i) Tl.k[i] = stream_load16(ka + 64 * i);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                Tl.v[r] = stream_load16(s.v + min(4 * r + hg, s.last_row) * (D * 2) + 16 * j16);
+            for (int r = 0; r < NVL; ++r)
+                Tl.v[r] = stream_load16(s.v + min(RPL * r + vrow0, s.last_row) * (D * 2) + 16 * vcol);
         }
     };
     // B operand of the score MFMAs for segment (sg, yy) - lane (column j16, k-slab hg) holds dims
     // 32i + 8hg .. +7 of its column's query row, unused columns zero - with that head's slope (base 2)
     // and the position of that query (the ALiBi term is relative to it).  A column is head j16 of the
     // segment's GH heads; in a shared prefix, head j16 % GH of the bundle's member j16 / GH.
-    auto load_q = [&](uint4 (&qd)[4], float& sd, int& pos, int sg_b, int sg_L, bool sg_shared, int yy) __attribute__((always_inline)) {
+    auto load_q = [&](uint4 (&qd)[NQ], float& sd, int& pos, int sg_b, int sg_L, bool sg_shared, int yy) __attribute__((always_inline)) {
         const int gg = yy / chunks;
         const int hh0 = gg * G + (yy - gg * chunks) * GH;
         int col_b = sg_b, col_h = min(j16, GH - 1);
@@ -400,7 +417,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const uint16_t* qrow = qp + ((int64_t)col_b * Hq + hh0 + col_h) * D + (KV8 ? 16 : 8) * hg;
         const uint32_t keep = ok ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NQ; ++i) {
             const uint4 x = *reinterpret_cast<const uint4*>(qrow + (KV8 ? 64 * (i >> 1) + 8 * (i & 1) : 32 * i));
             qd[i] = make_uint4(x.x & keep, x.y & keep, x.z & keep, x.w & keep);
         }
@@ -411,7 +428,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 
     Tile buf[2];
     TileSrc d0, d1;               // what buf[0] / buf[1] hold (or are receiving)
-    uint4 qa[4];
+    uint4 qa[NQ];
     float slope2;                 // ALiBi slope (base 2) of column j16
     int q_pos;                    // position of column j16's query: its sequence's last token
     bool chained = false;         // buf[0] / d0 were filled by the previous piece
@@ -448,10 +465,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
             const int blk = scalar_load_i32(table + (Lm1 >> bs_shift));
             const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
-            if (lane < 32) {
-                const int piece = 8 * (lane & 15);
-                const unsigned char* src = lane < 16 ? k_new + (new_k + piece) * 2 : v_new + (new_v + piece) * 2;
-                uint16_t* dstp = (lane < 16 ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + dst + piece;
+            if (lane < 2 * LPR) {                            // LPR lanes move the K row, the next LPR the V row
+                const int piece = 8 * vcol;
+                const unsigned char* src = lane < LPR ? k_new + (new_k + piece) * 2 : v_new + (new_v + piece) * 2;
+                uint16_t* dstp = (lane < LPR ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + dst + piece;
                 *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
             }
         }
@@ -510,9 +527,9 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         float m_ref = kNoMax;                 // reference of head j16 (equal in the 4 lanes that share it)
         float pend[4] = {0.f, 0.f, 0.f, 0.f}; // weights of the even tile, waiting for the odd one
         f32x4 lsum = f32x4{0.f, 0.f, 0.f, 0.f};
-        f32x4 acc[8];                         // O^T: dims 16db + 4hg + v of head j16
+        f32x4 acc[NDB];                       // O^T: dims 16db + 4hg + v of head j16
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int e = 0; e < NDB; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
         uint16_t* const v_rows = &v_lds[wave][0][0];
         typedef short i16x4 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(3))) i16x4* lds_i16x4_ptr;
@@ -541,7 +558,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             if (FlatSoftmax<DT>::kSplitWeights) lsum = mfma_qk<DT>(ones, pl, lsum);
             const uint16_t* vrow = v_rows + (4 * hg + (j16 >> 2)) * kFlatVRow + 4 * (j16 & 3);
 #pragma unroll
-            for (int db = 0; db < 8; ++db) {
+            for (int db = 0; db < NDB; ++db) {
                 const i16x4 r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * db));
                 const i16x4 r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4_ptr)(vrow + 16 * kFlatVRow + 16 * db));
                 const uint2 a0 = __builtin_bit_cast(uint2, r0), a1 = __builtin_bit_cast(uint2, r1);
@@ -553,17 +570,17 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 
         auto compute_tile = [&](const Tile& Tl, const TileSrc& src, auto odd_tile) __attribute__((always_inline)) {
             constexpr bool ODD = decltype(odd_tile)::value;
-            // the tile's V rows go to LDS as they are (rows 16*ODD + 4r + hg, this lane's 8 dims)
+            // the tile's V rows go to LDS as they are (rows 16*ODD + RPL*r + vrow0, this lane's 8 dims)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < NVL; ++r) {
                 uint4 vr;
                 if constexpr (KV8) vr = widen8_e4m3<DT>(Tl.v[r].x, Tl.v[r].y);
                 else vr = Tl.v[r];
-                *reinterpret_cast<uint4*>(v_rows + (16 * ODD + 4 * r + hg) * kFlatVRow + 8 * j16) = vr;
+                *reinterpret_cast<uint4*>(v_rows + (16 * ODD + RPL * r + vrow0) * kFlatVRow + 8 * vcol) = vr;
             }
             f32x4 S = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NQ; ++i) {
                 if constexpr (KV8) {
                     const uint4 kk = Tl.k[i >> 1];
                     S = mfma_qk<DT>((i & 1) ? widen8_e4m3<DT>(kk.z, kk.w) : widen8_e4m3<DT>(kk.x, kk.y), qa[i], S);
@@ -594,7 +611,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4) pend[v4] *= alpha;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+                for (int e = 0; e < NDB; ++e) acc[e] *= alpha;
             }
             float w[4];
 #pragma unroll
@@ -627,8 +644,8 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             } else {
                 // odd number of tiles: the last even tile has no partner; give it rows of zeros
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    *reinterpret_cast<uint4*>(v_rows + (16 + 4 * r + hg) * kFlatVRow + 8 * j16) = make_uint4(0u, 0u, 0u, 0u);
+                for (int r = 0; r < NVL; ++r)
+                    *reinterpret_cast<uint4*>(v_rows + (16 + RPL * r + vrow0) * kFlatVRow + 8 * vcol) = make_uint4(0u, 0u, 0u, 0u);
                 const float none[4] = {0.f, 0.f, 0.f, 0.f};
                 weighted_sum(pend, none);
             }
@@ -646,7 +663,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             }
             float* o = p.ws_o + e0 * D + 4 * hg;
 #pragma unroll
-            for (int db = 0; db < 8; ++db)
+            for (int db = 0; db < NDB; ++db)
                 *reinterpret_cast<float4*>(o + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
         }
 
@@ -675,11 +692,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 // SHARED: a head's partial results lie in two staircases - the pieces of its own segment (virtual
 // sequence 2b + 1, column = the head) and, if the sequence takes part in its bundle's shared
 // prefix, the pieces of that segment (virtual sequence 2 * leader, column = member * GH + head).
-template <int DT, bool NEWTOK = false, bool SHARED = false>
+template <int DT, bool NEWTOK = false, bool SHARED = false, int D = 128>
 __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kernel(const DecodeParams p)
 {
     static_assert(!(NEWTOK && SHARED), "shared prefixes: 2-byte caches");
-    constexpr int D = 128;
     constexpr int kVecPerHead = D / 4;
     constexpr int kHeads = kReduceThreads / kVecPerHead;
     const int h = blockIdx.x * kHeads + threadIdx.x / kVecPerHead;
@@ -806,7 +822,7 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
         dot = fmaf(widen_lo<DT>(qw.y), k23[0], dot);
         dot = fmaf(widen_hi<DT>(qw.y), k23[1], dot);
 #pragma unroll
-        for (int off = 1; off < kVecPerHead; off <<= 1) dot += __shfl_xor(dot, off);      // a head's 32 threads are half a wave
+        for (int off = 1; off < kVecPerHead; off <<= 1) dot += __shfl_xor(dot, off);      // a head's threads: an aligned half or quarter of a wave
         const float s_new = dot * (p.scale2 * k_scale_g);                                 // eq. (3), base 2, k_scale folded in
         const float M2 = fmaxf(M, s_new);
         const float f_old = any ? fast_exp2(M - M2) : 0.f, f_new = fast_exp2(s_new - M2);
@@ -833,19 +849,19 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
 // slots per partition, ((b * Y + y) * num_partitions + pi) * 2 + fragment; fragment 0 (the piece that
 // starts the partition) always exists, fragment 1 only if a unit boundary - a multiple of c in the
 // flat order - fell strictly inside the partition.  One workgroup per (head, sequence): eight groups of
-// 32 threads (4 output dims each) take every eighth slot with all their loads in flight at once,
+// head_dim / 4 threads (4 output dims each) take every eighth slot with all their loads in flight at once,
 // then the eight partial sums are merged through LDS - a long context has dozens of partitions and
 // a single chain of memory round trips over them would cost more than the streaming they merge.
 constexpr int kPartsReduceGroups = 8;
 
-template <int DT>
-__global__ __launch_bounds__(kPartsReduceGroups * 32) void paged_decode_parts_reduce_kernel(const DecodeParams p)
+template <int DT, int D = 128>
+__global__ __launch_bounds__(kPartsReduceGroups * (D / 4)) void paged_decode_parts_reduce_kernel(const DecodeParams p)
 {
-    constexpr int D = 128;
-    __shared__ float s_m[kPartsReduceGroups][32], s_den[kPartsReduceGroups][32];
-    __shared__ float4 s_num[kPartsReduceGroups][32];
+    constexpr int GW = D / 4;                                          // threads per group: 4 output dims each
+    __shared__ float s_m[kPartsReduceGroups][GW], s_den[kPartsReduceGroups][GW];
+    __shared__ float4 s_num[kPartsReduceGroups][GW];
     const int h = blockIdx.x, b = blockIdx.y;
-    const int l32 = threadIdx.x & 31, grp = threadIdx.x >> 5;
+    const int l32 = threadIdx.x % GW, grp = threadIdx.x / GW;
     const int od = l32 * 4;
     uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;
     const int L = p.context_lens[b];

@@ -101,15 +101,19 @@ void* static_scratch()
 }
 
 // Number of query heads one workgroup serves from a single pass over its K/V tiles; always a
-// divisor of the group size.  head_dim 128 uses the matrix-core kernel, whose score tile has
-// 16 rows: the largest divisor <= 16.  head_dim 64: the largest of 8, 4, 2, 1.
+// divisor of the group size.  The matrix-core kernels (head_dim 128 unsplit, and the equal-work
+// kernel at either head_dim) have a score tile of 16 columns: the largest divisor <= 16.  The
+// head_dim 64 kernels that run unsplit: the largest of 8, 4, 2, 1.
+int mfma_heads_per_workgroup(int group)
+{
+    for (int gh = group < kMmaMaxHeads ? group : kMmaMaxHeads; gh > 1; --gh)
+        if (group % gh == 0) return gh;
+    return 1;
+}
+
 int heads_per_workgroup(int group, int head_dim)
 {
-    if (head_dim == 128) {
-        for (int gh = group < kMmaMaxHeads ? group : kMmaMaxHeads; gh > 1; --gh)
-            if (group % gh == 0) return gh;
-        return 1;
-    }
+    if (head_dim == 128) return mfma_heads_per_workgroup(group);
     for (int gh = 8; gh > 1; gh >>= 1)
         if (group % gh == 0) return gh;
     return 1;
@@ -145,7 +149,7 @@ struct SplitPlan {
     int partition_size;   // 0 = unsplit, OPTGQA_SPLIT_BALANCED = equal-work split
     int num_partitions;
     size_t bytes;
-    // equal-work kernel only (the equal-work split, and fixed partitions at head_dim 128)
+    // equal-work kernel only (the equal-work split, and fixed partitions that are multiples of 16 tokens)
     int workgroups;
     int segs_per_seq;
     size_t plan_floats, ml_floats;
@@ -168,11 +172,11 @@ size_t round_up4(size_t x) { return (x + 3) / 4 * 4; }
 
 // (shared: the flat order runs over two virtual sequences per sequence - a bundle's shared prefix
 // and a sequence's own part - and every slot holds 16 columns, see decode_flat_kernels.hpp)
-bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int window = 0,
-               bool shared = false)
+bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int max_context_len,
+               int window = 0, bool shared = false)
 {
     const int group = num_heads / num_kv_heads;
-    const int gh = heads_per_workgroup(group, 128);
+    const int gh = mfma_heads_per_workgroup(group);
     const int64_t Y = (int64_t)num_kv_heads * (group / gh);
     const int64_t segs = Y * num_seqs * (shared ? 2 : 1);
     const int cols = shared ? 16 : gh;
@@ -193,19 +197,19 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     const size_t slots = (size_t)wgs * kDecodeWaves + (size_t)segs;
     s.plan_floats = round_up4((size_t)num_seqs * (shared ? 2 : 1) + 1);
     s.ml_floats = round_up4(slots * cols);
-    s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * cols * 128) * sizeof(float);
+    s.bytes = (s.plan_floats + 2 * s.ml_floats + slots * cols * head_dim) * sizeof(float);
     s.slots = (int64_t)slots;
     s.flat = true;
     return true;
 }
 
-// Fixed partitions of P tokens at head_dim 128, run by the equal-work kernel: two partial-result
+// Fixed partitions of P tokens (a multiple of 16) run by the equal-work kernel: two partial-result
 // slots per partition of every (sequence, KV head / head chunk) segment (a unit boundary may cut a
 // partition in two).
-bool plan_flat_parts(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int max_context_len, int P)
+bool plan_flat_parts(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int head_dim, int max_context_len, int P)
 {
     const int group = num_heads / num_kv_heads;
-    const int gh = heads_per_workgroup(group, 128);
+    const int gh = mfma_heads_per_workgroup(group);
     const int64_t Y = (int64_t)num_kv_heads * (group / gh);
     const int np = (max_context_len + P - 1) / P;
     const int64_t parts = Y * num_seqs * np;                 // upper bound: every sequence at max_context_len
@@ -220,7 +224,7 @@ bool plan_flat_parts(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads
     s.slots = 2 * parts;
     s.plan_floats = round_up4((size_t)num_seqs + 1);
     s.ml_floats = round_up4((size_t)s.slots * gh);
-    s.bytes = (s.plan_floats + 2 * s.ml_floats + (size_t)s.slots * gh * 128) * sizeof(float);
+    s.bytes = (s.plan_floats + 2 * s.ml_floats + (size_t)s.slots * gh * head_dim) * sizeof(float);
     s.flat = true;
     return true;
 }
@@ -231,15 +235,15 @@ SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim
     SplitPlan s{0, 1, 0, 0, 0, 0, 0, 0, false};
     int P = partition_size;
     if (P == 0) P = auto_partition(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len);
-    // The library's own choice for head_dim 128 is the equal-work split whenever splitting pays.
-    if (head_dim == 128 && (partition_size == OPTGQA_SPLIT_BALANCED || (partition_size == 0 && P > 0))) {
-        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, max_context_len, window, shared))
+    // The library's own choice is the equal-work split whenever splitting pays.
+    if (partition_size == OPTGQA_SPLIT_BALANCED || (partition_size == 0 && P > 0)) {
+        if (plan_flat(s, num_seqs, num_heads, num_kv_heads, head_dim, max_context_len, window, shared))
             return s;
         if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
     }
     if (P <= 0) return s;
-    if (head_dim == 128 && window <= 0 && !shared && P % kMmaTile == 0 &&
-        plan_flat_parts(s, num_seqs, num_heads, num_kv_heads, max_context_len, P))
+    if (window <= 0 && !shared && P % kMmaTile == 0 &&
+        plan_flat_parts(s, num_seqs, num_heads, num_kv_heads, head_dim, max_context_len, P))
         return s;
     s.partition_size = P;
     s.num_partitions = (max_context_len + P - 1) / P;
@@ -315,15 +319,15 @@ int launch_decode_any(int dtype, int head_dim, A... args)
     return head_dim == 128 ? launch_decode<kBF16, 128>(args...) : launch_decode<kBF16, 64>(args...);
 }
 
-// Equal-work split (head_dim 128): `workgroups` was sized for the work; it is also capped by what
+// Equal-work kernel: `workgroups` was sized for the work; it is also capped by what
 // the device keeps resident at once, because a unit that has to wait for a free slot would start
 // when every other unit is nearly done.
-template <int DT, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false>
+template <int DT, int D, bool FUSED, bool KV8 = false, bool SHARED = false, bool PARTS = false>
 int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
 {
     static const int resident = [] {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS>, kDecodeWaves * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS, D>, kDecodeWaves * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
@@ -332,43 +336,40 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     if (resident <= 0) return OPTGQA_ERR_LAUNCH;
     if (workgroups > resident) workgroups = resident;
     const int group = p.num_heads / p.num_kv_heads;
-    p.heads_per_wg = heads_per_workgroup(group, 128);
+    p.heads_per_wg = mfma_heads_per_workgroup(group);
     p.num_units = workgroups * kDecodeWaves;
     int rc;
     {
         KernelEvents ev(st);
-        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
+        rc = launch(paged_decode_flat_kernel<DT, FUSED, KV8, SHARED, PARTS, D>, dim3(workgroups), dim3(kDecodeWaves * 64), 0, st, p);
     }
     if (rc != OPTGQA_OK) return rc;
     if constexpr (PARTS)
-        return launch(paged_decode_parts_reduce_kernel<DT>, dim3(p.num_heads, p.num_seqs), dim3(kPartsReduceGroups * 32), 0, st, p);
-    constexpr int kHeadsPerWg = kReduceThreads / (128 / 4);
-    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+        return launch(paged_decode_parts_reduce_kernel<DT, D>, dim3(p.num_heads, p.num_seqs), dim3(kPartsReduceGroups * (D / 4)), 0, st, p);
+    constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
+    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED, D>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
                   dim3(kReduceThreads), 0, st, p);
 }
 
-int launch_decode_flat(int dtype, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
+template <int DT, int D>
+int launch_decode_flat_d(const DecodeParams& p, int workgroups, hipStream_t st, bool kv8)
 {
-    if (p.part_tiles > 0)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, false, false, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, false, false, false, true>(p, workgroups, st);
-    if (p.shared_blocks && p.k_new)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, false, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, true, false, true>(p, workgroups, st);
-    if (p.shared_blocks)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, false, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, false, false, true>(p, workgroups, st);
-    if (kv8 && p.k_new)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, true, true>(p, workgroups, st);
-    if (kv8)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, false, true>(p, workgroups, st);
-    if (p.k_new)
-        return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, true>(p, workgroups, st)
-                                   : launch_decode_flat_dt<kBF16, true>(p, workgroups, st);
-    return dtype == OPTGQA_F16 ? launch_decode_flat_dt<kF16, false>(p, workgroups, st)
-                               : launch_decode_flat_dt<kBF16, false>(p, workgroups, st);
+    if (p.part_tiles > 0) return launch_decode_flat_dt<DT, D, false, false, false, true>(p, workgroups, st);
+    if (p.shared_blocks && p.k_new) return launch_decode_flat_dt<DT, D, true, false, true>(p, workgroups, st);
+    if (p.shared_blocks) return launch_decode_flat_dt<DT, D, false, false, true>(p, workgroups, st);
+    if (kv8 && p.k_new) return launch_decode_flat_dt<DT, D, true, true>(p, workgroups, st);
+    if (kv8) return launch_decode_flat_dt<DT, D, false, true>(p, workgroups, st);
+    if (p.k_new) return launch_decode_flat_dt<DT, D, true>(p, workgroups, st);
+    return launch_decode_flat_dt<DT, D, false>(p, workgroups, st);
+}
+
+int launch_decode_flat(int dtype, int head_dim, const DecodeParams& p, int workgroups, hipStream_t st, bool kv8 = false)
+{
+    if (head_dim == 128)
+        return dtype == OPTGQA_F16 ? launch_decode_flat_d<kF16, 128>(p, workgroups, st, kv8)
+                                   : launch_decode_flat_d<kBF16, 128>(p, workgroups, st, kv8);
+    return dtype == OPTGQA_F16 ? launch_decode_flat_d<kF16, 64>(p, workgroups, st, kv8)
+                               : launch_decode_flat_d<kBF16, 64>(p, workgroups, st, kv8);
 }
 
 
@@ -397,9 +398,7 @@ int launch_prefill_mma_d(const PrefillParams& p, dim3 grid, int waves, hipStream
 template <int DT, bool KV8, bool WIN, bool CONTIG>
 int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, int waves, hipStream_t st)
 {
-    if constexpr (!KV8) {
-        if (head_dim == 64) return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 64>(p, grid, waves, st);
-    }
+    if (head_dim == 64) return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 64>(p, grid, waves, st);
     return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, waves, st);
 }
 
@@ -414,13 +413,13 @@ float prefill_scale2(float scale)
     return s * kLog2e;
 }
 
-// Tiled matrix-core prefill (head_dim 128 or 64; 8-bit caches: 128 only).
+// Tiled matrix-core prefill (head_dim 128 or 64).
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
                    bool kv8 = false, bool contig = false)
 {
-    if (head_dim != 128 && (kv8 || head_dim != 64)) return OPTGQA_ERR_UNSUPPORTED;
+    if (head_dim != 128 && head_dim != 64) return OPTGQA_ERR_UNSUPPORTED;
     const int group = p.num_heads / p.num_kv_heads;
-    const int gh = heads_per_workgroup(group, 128);
+    const int gh = mfma_heads_per_workgroup(group);
     int shift = 0;
     while ((1 << shift) < gh) ++shift;
     p.num_seqs = num_seqs;
@@ -588,15 +587,12 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
 {
     if (shared_blocks) {
         if (kv_scales || window > 0) return OPTGQA_ERR_UNSUPPORTED;
-        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;      // the equal-work kernel only
-        partition_size = OPTGQA_SPLIT_BALANCED;
+        partition_size = OPTGQA_SPLIT_BALANCED;          // the equal-work kernel only
     }
-    if (window > 0)                                      // head_dim 128: the equal-work kernel; 64: the general
-        partition_size = head_dim == 128 ? OPTGQA_SPLIT_BALANCED : -1;   // kernel, unsplit (a window bounds the work)
+    if (window > 0) partition_size = OPTGQA_SPLIT_BALANCED;
     if (kv_scales) {
         if (kv_scales->per_head() && !kv_scales->v_heads) return OPTGQA_ERR_NULL;
         if (!kv_scales->valid()) return OPTGQA_ERR_SHAPE;
-        if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
         partition_size = OPTGQA_SPLIT_BALANCED;          // the only kernel that reads E4M3 caches
     }
     if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
@@ -622,7 +618,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size,
                              max_context_len > 0 ? max_context_len : 1, partition_size, window, shared_blocks != nullptr);
     if (partition_size == OPTGQA_SPLIT_BALANCED && s.partition_size != OPTGQA_SPLIT_BALANCED)
-        return OPTGQA_ERR_UNSUPPORTED;                   // head_dim 64, or sizes beyond 32-bit tile indices
+        return OPTGQA_ERR_UNSUPPORTED;                   // sizes beyond 32-bit tile indices
     if (s.partition_size != 0) {
         const bool have = workspace && workspace_bytes >= s.bytes && aligned16(workspace);
         if (!have) {
@@ -655,7 +651,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
     p.k_inv_scale = p.v_inv_scale = 1.f;
     p.part_tiles = 0;
     p.shared_blocks = shared_blocks;
-    p.bundle = shared_blocks ? kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128) : 1;
+    p.bundle = shared_blocks ? kMmaMaxHeads / mfma_heads_per_workgroup(num_heads / num_kv_heads) : 1;
     p.k_scales = p.v_scales = nullptr;
     if (kv_scales && kv_scales->per_head()) {
         p.k_scales = kv_scales->k_heads;                     // applied per KV head inside the kernels
@@ -704,7 +700,7 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
             p.v_cache_w = step->v_cache_w;
         }
         const int cap = flat_workgroups(kv_scales != nullptr);
-        return launch_decode_flat(dtype, p, s.workgroups < cap ? s.workgroups : cap, st, kv_scales != nullptr);
+        return launch_decode_flat(dtype, head_dim, p, s.workgroups < cap ? s.workgroups : cap, st, kv_scales != nullptr);
     }
     p.plan = nullptr;
     p.num_units = p.segs_per_seq = 0;
@@ -926,14 +922,14 @@ int optgqa_decode_step_fp8_heads(void* out, const void* q, const void* k_new, co
 int optgqa_shared_prefix_bundle(int num_heads, int num_kv_heads, int head_dim)
 {
     if (num_heads <= 0 || num_kv_heads <= 0 || num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
-    if (head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;
-    return kMmaMaxHeads / heads_per_workgroup(num_heads / num_kv_heads, 128);
+    if (!head_dim_ok(head_dim)) return OPTGQA_ERR_UNSUPPORTED;
+    return kMmaMaxHeads / mfma_heads_per_workgroup(num_heads / num_kv_heads);
 }
 
 size_t optgqa_shared_prefix_workspace_bytes(int num_seqs, int num_heads, int num_kv_heads, int head_dim,
                                             int block_size, int max_context_len)
 {
-    if (num_seqs <= 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim != 128 || block_size <= 0 ||
+    if (num_seqs <= 0 || num_heads <= 0 || num_kv_heads <= 0 || !head_dim_ok(head_dim) || block_size <= 0 ||
         max_context_len <= 0 || num_heads % num_kv_heads)
         return 0;
     const SplitPlan s = plan_split(num_seqs, num_heads, num_kv_heads, head_dim, block_size, max_context_len,
@@ -1011,7 +1007,6 @@ static int prefill_impl(void* out, const void* q, const void* k_cache, const voi
     if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
-    if (kv_scales && head_dim != 128) return OPTGQA_ERR_UNSUPPORTED;   // tiled kernel only
     if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
     if (!out || !q || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens) return OPTGQA_ERR_NULL;
     if (!aligned16(out) || !aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return OPTGQA_ERR_UNSUPPORTED;

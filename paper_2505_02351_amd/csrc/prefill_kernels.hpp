@@ -153,7 +153,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     constexpr bool REV = !WIN;                          // walk the key tiles from the diagonal backwards
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
-    static_assert(!(KV8 && D != 128), "8-bit caches: head_dim 128");
     constexpr int kPfKRow = PfTile<D>::kKRow, kPfVRow = PfTile<D>::kVRow;
     constexpr int kQ = D / 16;                          // score MFMAs per tile (16 dims each)
     constexpr int kDB = D / 32;                         // 32-dim blocks of the output

@@ -73,8 +73,7 @@ def test_argument_errors_before_any_launch(G):
     assert call(q=None) == -1
     assert call(out=ctypes.c_void_p(8)) == -3    # misaligned
     assert call(P=32) == -4                      # split forced, no workspace
-    assert call(P=-2) == -3                      # equal-work split: head_dim 128 only
-    assert call(P=-2, D=128) == -4               # ... and it needs its workspace
+    assert call(P=-2) == -4 and call(P=-2, D=128) == -4      # the equal-work split needs its workspace
     assert call(B=0) == 0
     assert call(dt=2) == -3
     # prefill
@@ -100,13 +99,13 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     assert d(*args(ks=64)) == -2
     assert d(*args(k_new=None)) == -1
     assert d(*args(D=96)) == -3
-    # 8-bit caches: scales must be positive and finite, head_dim 128 only, workspace required
+    # 8-bit caches: scales must be positive and finite, head_dim 64 or 128, workspace required
     a = lib.optgqa_paged_attention_fp8
     f = lambda ks=1.0, vs=1.0, D=128, ws=None, wsb=0: a(one, one, one, one, one, one, None, 0.1, ks, vs, 2, 8, 2, D, 16,
                                                         8, 128, ws, wsb, 0, None)
     assert f(ks=0.0) == -2 and f(vs=-1.0) == -2 and f(ks=float("inf")) == -2 and f(ks=float("nan")) == -2
-    assert f(D=64) == -3
-    assert f() == -4
+    assert f(D=96) == -3
+    assert f() == -4 and f(D=64) == -4
     r = lib.optgqa_reshape_and_cache_fp8
     g = lambda k=one, ks=1.0, stride=256, T=3: r(k, one, one, one, one, T, 2, 128, 16, stride, 256, ks, 1.0, 1, None)
     assert g(ks=0.0) == -2 and g(stride=100) == -2 and g(stride=260) == -3 and g(k=ctypes.c_void_p(8)) == -3
@@ -114,15 +113,15 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     sf = lib.optgqa_decode_step_fp8
     h = lambda ks=1.0, D=128, kn=one, st=256, ws=None: sf(one, one, kn, one, one, one, one, one, None, 0.1, ks, 1.0, 2, 8, 2,
                                                           D, 16, 8, 128, st, 256, ws, 0, 0, None)
-    assert h(ks=0.0) == -2 and h(D=64) == -3 and h(kn=None) == -1 and h(st=100) == -2 and h() == -4
+    assert h(ks=0.0) == -2 and h(D=96) == -3 and h(kn=None) == -1 and h(st=100) == -2 and h() == -4 and h(D=64) == -4
     pf = lib.optgqa_paged_prefill_fp8
     e = lambda ks=1.0, D=128, B=2, cu=one: pf(one, one, one, one, one, one, cu, None, 0.1, ks, 1.0, B, 8, 2, D, 16, 8,
                                              32, 0, None)
-    assert e(ks=0.0) == -2 and e(D=64) == -3 and e(cu=None) == -1 and e(B=0) == 0
-    # sliding window: positive windows only, head_dim 128 only, decode needs the workspace
+    assert e(ks=0.0) == -2 and e(D=96) == -3 and e(cu=None) == -1 and e(B=0) == 0
+    # sliding window: positive windows only, decode needs the workspace
     wa = lib.optgqa_paged_attention_window
     f = lambda W=8, D=128: wa(one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, None, 0, 0, None)
-    assert f(W=0) == -2 and f(W=-5) == -2 and f(D=96) == -3 and f() == -4
+    assert f(W=0) == -2 and f(W=-5) == -2 and f(D=96) == -3 and f() == -4 and f(D=64) == -4
     wsx = lib.optgqa_decode_step_window
     f = lambda W=8, D=128, ks=256: wsx(one, one, one, one, one, one, one, one, None, 0.1, W, 2, 8, 2, D, 16, 8, 128, ks,
                                        256, None, 0, 0, None)
@@ -156,9 +155,9 @@ def test_workspace_query(G):
     # 8 heads x (128 + 2) floats each, after 4 + 1 plan entries padded to 4
     n, P = G.paged_attention_workspace_bytes(4, 64, 8, 128, 16, 32768, 512)
     assert P == 512 and n == (8 + 2 * 4 * 8 * 64 * 8 * (128 + 2)) * 4
-    # ... and at head_dim 64: [sequence][head][partition] x (64 + 2) floats
+    # ... the same at head_dim 64 with (64 + 2) floats per head
     n, P = G.paged_attention_workspace_bytes(4, 64, 8, 64, 16, 32768, 512)
-    assert P == 512 and n == 4 * 64 * 64 * (64 + 2) * 4
+    assert P == 512 and n == (8 + 2 * 4 * 8 * 64 * 8 * (64 + 2)) * 4
     n, P = G.paged_attention_workspace_bytes(1, 8, 2, 64, 16, 128, 0)
     assert (n, P) == (0, 0)                      # short context: no split
     # head_dim 128 and worth splitting: the equal-work split, one slot per wave (one wave per SIMD
@@ -171,10 +170,10 @@ def test_workspace_query(G):
     # small problems get fewer waves: 2 x 2 segments x 13 tiles -> 52 tiles -> 2 workgroups
     n, P = G.paged_attention_workspace_bytes(2, 8, 2, 128, 16, 200, G.SPLIT_BALANCED)
     assert P == G.SPLIT_BALANCED and n == (4 + (2 * 4 + 4) * 4 * (128 + 2)) * 4
-    # head_dim 64 has no equal-work split; its own choice stays a fixed partition size
-    assert G.paged_attention_workspace_bytes(64, 32, 4, 64, 32, 8192, G.SPLIT_BALANCED) == (0, 0)
+    # head_dim 64: the same split, (64 + 2) floats per head
     n, P = G.paged_attention_workspace_bytes(64, 32, 4, 64, 32, 8192, 0)
-    assert P > 0 and P % 32 == 0 and n > 0
+    assert P == G.SPLIT_BALANCED and n == (68 + slots * 8 * (64 + 2)) * 4
+    assert G.paged_attention_workspace_bytes(64, 32, 4, 64, 32, 8192, G.SPLIT_BALANCED) == (n, P)
     n, P = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, -1)
     assert (n, P) == (0, 0)
 
@@ -290,16 +289,17 @@ def test_shared_prefix_host_checks(G):
     assert G.shared_prefix_bundle(12, 2, 128) == 2          # group 6: 12 of the 16 columns
     assert G.shared_prefix_bundle(40, 2, 128) == 1          # group 20 -> 10 heads per pass
     assert lib.optgqa_shared_prefix_bundle(32, 5, 128) == -2
-    assert lib.optgqa_shared_prefix_bundle(32, 4, 64) == -3
+    assert lib.optgqa_shared_prefix_bundle(32, 4, 64) == 2 and lib.optgqa_shared_prefix_bundle(32, 4, 96) == -3
     plain, _ = G.paged_attention_workspace_bytes(64, 32, 4, 128, 32, 8192, G.SPLIT_BALANCED)
     shared = G.shared_prefix_workspace_bytes(64, 32, 4, 128, 32, 8192)
     assert shared > plain > 0                               # twice the segments, 16 columns per slot
-    assert G.shared_prefix_workspace_bytes(64, 32, 4, 64, 32, 8192) == 0
-    # entry points: head_dim 64, missing workspace, missing table
+    assert 0 < G.shared_prefix_workspace_bytes(64, 32, 4, 64, 32, 8192) < shared
+    assert G.shared_prefix_workspace_bytes(64, 32, 4, 96, 32, 8192) == 0
+    # entry points: head_dim 96, missing workspace, missing table
     f = lib.optgqa_paged_attention_shared
     args = lambda D=128, sb=one, ws=one, wsb=1 << 30: (one, one, one, one, one, one, sb, None, 0.1, 2, 8, 2, D, 16, 8, 128,
                                                        ws, wsb, 0, None)
-    assert f(*args(D=64)) == -3
+    assert f(*args(D=96)) == -3
     assert f(*args(sb=None)) == -1
     assert f(*args(ws=None, wsb=0)) == -4
     g = lib.optgqa_decode_step_shared
@@ -334,13 +334,13 @@ def test_per_head_scale_entry_points_reject_missing_arrays(G):
                                                   None) == -3
     assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, None, 2, 8, 2, 128, 16,
                                                 8, 128, one, 1 << 30, 0, None) == -1
-    assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 64, 16,
-                                                8, 128, one, 1 << 30, 0, None) == -3          # head_dim 64
+    assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 96, 16,
+                                                8, 128, one, 1 << 30, 0, None) == -3          # head_dim 96
     assert lib.optgqa_paged_attention_fp8_heads(one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 128, 16,
                                                 8, 128, None, 0, 0, None) == -4               # workspace required
     assert lib.optgqa_decode_step_fp8_heads(one, one, one, one, one, one, one, one, None, 0.1, None, None, 2, 8, 2,
                                             128, 16, 8, 128, 256, 256, one, 1 << 30, 0, None) == -1
     assert lib.optgqa_paged_prefill_fp8_heads(one, one, one, one, one, one, one, None, 0.1, None, one, 2, 8, 2, 128,
                                               16, 8, 4, 0, None) == -1
-    assert lib.optgqa_paged_prefill_fp8_heads(one, one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 64,
+    assert lib.optgqa_paged_prefill_fp8_heads(one, one, one, one, one, one, one, None, 0.1, one, one, 2, 8, 2, 96,
                                               16, 8, 4, 0, None) == -3

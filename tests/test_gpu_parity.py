@@ -152,8 +152,6 @@ def test_decode_sweep(U, oracle, i, partition):
     dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
     if partition > 0 and partition % bs:
         pytest.skip("partition size must be a multiple of the block size")
-    if partition == BALANCED and D != 128:
-        pytest.skip("the equal-work split exists for head_dim 128 only")
     cfg = W.small_config(name=f"sweep{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
                          head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
                          ctx_hi=hi, seed=400 + i)
@@ -323,22 +321,37 @@ def test_decode_balanced_and_fixed_partitions_against_the_oracle(U, oracle):
     assert np.max(np.abs(a - b)) <= 2.0 ** -9          # one fp16 ulp in [1, 2): both sit on the same side of the oracle
 
 
-def test_decode_balanced_rejects_head_dim_64(U):
-    import torch
-    cfg = W.small_config(name="bal64", dtype=W.F16, batch=2, num_heads=8, num_kv_heads=2, head_dim=64,
-                         block_size=16, num_blocks=40, ctx_lo=10, ctx_hi=200, seed=5)
-    dev = U.DevCase(W.make_case(cfg))
-    dev.write_cache()
-    with pytest.raises(RuntimeError):
-        dev.decode(partition_size=BALANCED, workspace=torch.empty(1 << 20, dtype=torch.float32, device="cuda"))
+@pytest.mark.parametrize("dtype", [W.F16, W.BF16])
+def test_decode_edge_lengths_head_dim_64(U, oracle, dtype):
+    """The edge lengths of the head_dim 128 test at head_dim 64 (a V tile is fetched 8 rows a load there,
+    a K row is two MFMAs): every split mode, an empty context gives +0, a one-token context returns V."""
+    lens = np.array([0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 512, 1], np.int32)
+    cfg = W.small_config(name="edges64", dtype=dtype, batch=len(lens), num_heads=8, num_kv_heads=2, head_dim=64,
+                         block_size=16, num_blocks=160, ctx_lo=1, ctx_hi=512, seed=421)
+    case = W.make_case(cfg, context_lens=lens)
+    q_full = np.zeros((len(lens), 8, 64), np.uint16)
+    q_full[lens > 0] = case.q
+    case.q = q_full
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    for partition in (-1, 0, 64, 256, BALANCED):
+        dev = U.DevCase(case)
+        dev.write_cache()
+        got = dev.decode(partition_size=partition)
+        assert not got[0].any(), "an empty context must give +0"
+        assert U.max_abs_err(got, ref, dtype) <= U.TOL[dtype], partition
+        for b in (1, 12):
+            pb = case.block_tables[b, 0]
+            for h in range(8):
+                assert np.array_equal(got[b, h], vc[pb, h // 4, 0, :])
 
 
 # ------------------------------------------------------------------ decode step in one call
 @pytest.mark.parametrize("i", range(len(SWEEP)))
 def test_decode_step_sweep(U, oracle, i):
     """optgqa_decode_step = cache write + attention: caches bit-exact, output within tolerance.
-    head_dim 128 shapes with a long enough context take the fused kernel, the others the
-    library's two-launch path."""
+    Shapes with a long enough context take the fused kernel, the others the library's two-launch
+    path."""
     dtype, Hq, Hkv, D, bs, B, lo, hi = SWEEP[i]
     cfg = W.small_config(name=f"step{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
                          head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo,
@@ -464,7 +477,7 @@ def test_fp8_cache_write_every_input_pattern(U, oracle, dtype):
         assert np.array_equal(dv.cpu().numpy(), vc8), (dtype, v_scale)
 
 
-FP8_SWEEP = [i for i, s in enumerate(SWEEP) if s[3] == 128]
+FP8_SWEEP = list(range(len(SWEEP)))
 
 
 @pytest.mark.parametrize("i", FP8_SWEEP)
@@ -576,7 +589,7 @@ def test_fp8_decode_workload_full(U, oracle):
     U.check_scaled(got, ref, case.dtype, "C3, E4M3 caches", max_exempt=WORKLOAD_EXEMPT)
 
 
-@pytest.mark.parametrize("i", [0, 2, 3, 4, 6, 8, 9, 10, 12])
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 4, 6, 8, 9, 10, 11, 12])
 def test_fp8_prefill(U, oracle, i):
     """Tiled prefill over 8-bit caches against the oracle's clause (the caches are filled by the
     quantising cache write on both sides, codes compared bit for bit first)."""
@@ -584,8 +597,6 @@ def test_fp8_prefill(U, oracle, i):
     import oracle as O
     import paper_2505_02351_amd as G
     dtype, Hq, Hkv, D, bs, B, lo, hi, qlen = PF[i]
-    if D != 128:
-        pytest.skip("8-bit caches: head_dim 128 only")
     cfg = W.small_config(name=f"fp8pf{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
                          head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
                          ctx_hi=hi, q_len=qlen, seed=950 + i)
@@ -627,9 +638,9 @@ def test_fp8_prefill_workload_full(U, oracle):
     U.check_scaled(U.to_host(out), ref, case.dtype, "C5, E4M3 caches", max_exempt=WORKLOAD_EXEMPT)
 
 
-@pytest.mark.parametrize("i", [2, 3, 4, 5, 7, 9])
+@pytest.mark.parametrize("i", range(len(SWEEP)))
 def test_fp8_decode_step_sweep(U, oracle, i):
-    """optgqa_decode_step_fp8 on the head_dim 128 sweep shapes: caches holding every token but the
+    """optgqa_decode_step_fp8 on the sweep shapes: caches holding every token but the
     step's are quantised first; after the call the caches must equal the oracle's quantised image
     of the whole batch bit for bit and the output its E4M3 attention clause."""
     import torch
@@ -703,11 +714,13 @@ def test_fp8_decode_step_edge_lengths(U, oracle, dtype):
 
 
 HEAD_SCALES = [
-    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi, new tokens per sequence
-    (W.BF16, 32, 4, 32, 5, 40, 900, 1),
-    (W.F16, 12, 3, 16, 4, 1, 500, 1),           # G = 4, three KV heads
-    (W.BF16, 8, 8, 16, 3, 100, 400, 37),        # MHA, a prefill chunk
-    (W.F16, 16, 2, 64, 2, 200, 700, 130),       # G = 8, prefill
+    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi, new tokens per sequence, head_dim
+    (W.BF16, 32, 4, 32, 5, 40, 900, 1, 128),
+    (W.F16, 12, 3, 16, 4, 1, 500, 1, 128),           # G = 4, three KV heads
+    (W.BF16, 8, 8, 16, 3, 100, 400, 37, 128),        # MHA, a prefill chunk
+    (W.F16, 16, 2, 64, 2, 200, 700, 130, 128),       # G = 8, prefill
+    (W.F16, 8, 2, 16, 4, 1, 600, 1, 64),             # head_dim 64, G = 4
+    (W.BF16, 16, 4, 32, 3, 100, 500, 70, 64),        # head_dim 64, prefill
 ]
 
 
@@ -720,16 +733,16 @@ def test_fp8_per_head_scales(U, oracle, i):
     import torch
     import oracle as O
     import paper_2505_02351_amd as G
-    dtype, Hq, Hkv, bs, B, lo, hi, q_len = HEAD_SCALES[i]
+    dtype, Hq, Hkv, bs, B, lo, hi, q_len, D = HEAD_SCALES[i]
     kind = "decode" if q_len == 1 else "prefill"
     cfg = W.small_config(name=f"fp8heads{i}", kind=kind, dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
-                         head_dim=128, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi,
                          q_len=q_len, seed=2700 + i)
     case = W.make_case(cfg)
     rng = np.random.default_rng(2800 + i)
     k_scales = (0.0125 * np.exp2(rng.integers(-3, 4, size=Hkv))).astype(np.float32)
     v_scales = (0.02 * np.exp2(rng.uniform(-6, 6, size=Hkv))).astype(np.float32)       # not powers of two
-    shape = (cfg.num_blocks, Hkv, bs, 128)
+    shape = (cfg.num_blocks, Hkv, bs, D)
     k_all, v_all, slots = W.all_token_rows(case)
     kc8, vc8 = np.full(shape, 0x7F, np.uint8), np.full(shape, 0x7F, np.uint8)
     O.reshape_and_cache_e4m3_heads(k_all, v_all, kc8, vc8, slots, k_scales, v_scales, dtype)
@@ -805,11 +818,13 @@ def test_fp8_rejects_what_it_cannot_do(U):
     bt = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
     cl = torch.ones(2, dtype=torch.int32, device="cuda")
     ws = torch.empty(1 << 20, dtype=torch.float32, device="cuda")
-    with pytest.raises(RuntimeError):                    # head_dim 64
-        G.paged_attention_fp8(torch.empty_like(q), q, c8, c8, bt, cl, None, 0.1, 1.0, 1.0, 32, ws)
     cu = torch.tensor([0, 1, 2], dtype=torch.int32, device="cuda")
-    with pytest.raises(RuntimeError):                    # head_dim 64, prefill
-        G.paged_prefill_fp8(torch.empty_like(q), q, c8, c8, bt, cl, cu, None, 0.1, 1.0, 1.0, 1)
+    q96 = torch.zeros(2, 8, 96, dtype=torch.float16, device="cuda")
+    c96 = torch.zeros(4, 2, 16, 96, dtype=torch.uint8, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 96
+        G.paged_attention_fp8(torch.empty_like(q96), q96, c96, c96, bt, cl, None, 0.1, 1.0, 1.0, 32, ws)
+    with pytest.raises(RuntimeError):                    # head_dim 96, prefill
+        G.paged_prefill_fp8(torch.empty_like(q96), q96, c96, c96, bt, cl, cu, None, 0.1, 1.0, 1.0, 1)
     q = torch.zeros(2, 8, 128, dtype=torch.float16, device="cuda")
     c8 = torch.zeros(4, 2, 16, 128, dtype=torch.uint8, device="cuda")
     with pytest.raises(RuntimeError):                    # no workspace
@@ -825,7 +840,7 @@ WINDOWS = [1, 2, 15, 16, 17, 33, 100, 257, 10 ** 6]
 @pytest.mark.parametrize("i", range(len(SWEEP)))
 def test_decode_window_sweep(U, oracle, i):
     """Windowed decode against the oracle's local-mask clause, every window of WINDOWS on the sweep
-    shapes (head_dim 128: equal-work kernel; 64: general kernel, unsplit), both over filled caches and
+    shapes, both over filled caches and
     with the cache write in the same call (caches bit-exact); without slopes on one pass (Alg. 1
     builds the local mask when there are none)."""
     import oracle as O
@@ -1108,14 +1123,16 @@ def test_decode_with_shared_prefix_blocks(U, oracle):
 
 
 SHARED = [
-    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi            heads per pass -> bundle
-    (W.BF16, 32, 4, 32, 10, 40, 900),      # G = 8  -> pairs
-    (W.F16, 32, 8, 16, 13, 20, 700),       # G = 4  -> bundles of 4, last bundle incomplete
-    (W.BF16, 8, 8, 16, 35, 1, 300),        # G = 1  -> bundles of 16; 70 virtual sequences: two-level scan
-    (W.F16, 12, 2, 16, 7, 30, 500),        # G = 6  -> pairs, 12 of the 16 columns in use
-    (W.BF16, 6, 2, 64, 11, 64, 700),       # G = 3  -> bundles of 5 (15 columns), block 64
-    (W.F16, 32, 2, 16, 4, 50, 400),        # G = 16 -> bundle of 1: nothing can be shared
-    (W.BF16, 16, 2, 16, 80, 1, 120),       # G = 8, 80 sequences: 160 virtual sequences, many short
+    # dtype, Hq, Hkv, bs, batch, ctx_lo, ctx_hi, head_dim   heads per pass -> bundle
+    (W.BF16, 32, 4, 32, 10, 40, 900, 128),      # G = 8  -> pairs
+    (W.F16, 32, 8, 16, 13, 20, 700, 128),       # G = 4  -> bundles of 4, last bundle incomplete
+    (W.BF16, 8, 8, 16, 35, 1, 300, 128),        # G = 1  -> bundles of 16; 70 virtual sequences: two-level scan
+    (W.F16, 12, 2, 16, 7, 30, 500, 128),        # G = 6  -> pairs, 12 of the 16 columns in use
+    (W.BF16, 6, 2, 64, 11, 64, 700, 128),       # G = 3  -> bundles of 5 (15 columns), block 64
+    (W.F16, 32, 2, 16, 4, 50, 400, 128),        # G = 16 -> bundle of 1: nothing can be shared
+    (W.BF16, 16, 2, 16, 80, 1, 120, 128),       # G = 8, 80 sequences: 160 virtual sequences, many short
+    (W.F16, 8, 2, 16, 9, 20, 600, 64),          # head_dim 64, G = 4 -> bundles of 4
+    (W.BF16, 16, 2, 32, 6, 40, 500, 64),        # head_dim 64, G = 8 -> pairs
 ]
 
 
@@ -1126,21 +1143,21 @@ def test_decode_shared_prefix_sweep(U, oracle, i):
     length 0 and 1.  The oracle knows nothing of sharing - it walks the aliased tables - and the
     plain and fused calls must both match it; the fused call's caches bit for bit."""
     import paper_2505_02351_amd as G
-    dtype, Hq, Hkv, bs, B, lo, hi = SHARED[i]
-    cfg = W.small_config(name=f"shared{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv, head_dim=128,
+    dtype, Hq, Hkv, bs, B, lo, hi, D = SHARED[i]
+    cfg = W.small_config(name=f"shared{i}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv, head_dim=D,
                          block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi, seed=2400 + i)
     rng = np.random.default_rng(2500 + i)
     lens = rng.integers(lo, hi + 1, size=B).astype(np.int32)
     lens[rng.choice(B, size=max(B // 6, 1), replace=False)] = rng.choice([0, 1, bs, bs + 1, 2 * bs + 1])
     case = W.make_case(cfg, context_lens=lens)
-    bundle = G.shared_prefix_bundle(Hq, Hkv, 128)
+    bundle = G.shared_prefix_bundle(Hq, Hkv, D)
     assert bundle == 16 // max(d for d in range(1, 17) if (Hq // Hkv) % d == 0)
     shared = W.share_prefix_in_bundles(case, bundle, seed=2600 + i)
     assert bundle == 1 or shared.any()
     assert G.validate_shared_prefix_host(case.block_tables, case.context_lens, shared, bs, bundle, 1) == 0
     full = lambda a, shape: (lambda z: (z.__setitem__(lens > 0, a), z)[1])(np.zeros(shape, np.uint16))
-    q_full = full(case.q, (B, Hq, 128))
-    k_full, v_full = full(case.k_new, (B, Hkv, 128)), full(case.v_new, (B, Hkv, 128))
+    q_full = full(case.q, (B, Hq, D))
+    k_full, v_full = full(case.k_new, (B, Hkv, D)), full(case.v_new, (B, Hkv, D))
     kc, vc = oracle_filled(oracle, case)
     case.q = q_full
     ref = oracle_decode(oracle, case, kc, vc)
@@ -1189,10 +1206,10 @@ def test_shared_prefix_rejects_what_it_cannot_do(U):
     c = torch.zeros(4, 2, 16, 128, dtype=torch.float16, device="cuda")
     with pytest.raises(RuntimeError):                    # no workspace
         G.paged_attention_shared(torch.empty_like(q), q, c, c, bt, cl, sb, None, 0.1, 32, None)
-    q64 = torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda")
-    c64 = torch.zeros(4, 2, 16, 64, dtype=torch.float16, device="cuda")
-    with pytest.raises(RuntimeError):                    # head_dim 64
-        G.paged_attention_shared(torch.empty_like(q64), q64, c64, c64, bt, cl, sb, None, 0.1, 32, ws)
+    q96 = torch.zeros(2, 8, 96, dtype=torch.float16, device="cuda")
+    c96 = torch.zeros(4, 2, 16, 96, dtype=torch.float16, device="cuda")
+    with pytest.raises(RuntimeError):                    # head_dim 96
+        G.paged_attention_shared(torch.empty_like(q96), q96, c96, c96, bt, cl, sb, None, 0.1, 32, ws)
     with pytest.raises(TypeError):                       # int64 sharing table
         G.paged_attention_shared(torch.empty_like(q), q, c, c, bt, cl, sb.long(), None, 0.1, 32, ws)
 
@@ -1248,16 +1265,12 @@ def test_random_mix_of_decode_calls(U, oracle):
         case = W.make_case(cfg, context_lens=lens)
         kc, vc = oracle_filled(oracle, case)
         mode = ["plain", "step", "window", "window_step", "fp8", "fp8_step"][int(rng.integers(6))]
-        if mode in ("fp8", "fp8_step") and D != 128:
-            mode = "plain"
         tag = f"case {it}: {mode} D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} {dtype}"
         dev = U.DevCase(case)
         if mode == "plain":
             dev.write_cache()
             P = int(rng.choice([-1, 0, 64, 256, BALANCED]))
             if P > 0 and P % bs:
-                P = 0
-            if P == BALANCED and D != 128:
                 P = 0
             got = dev.decode(partition_size=P)
             ref = oracle_decode(oracle, case, kc, vc)
@@ -1319,8 +1332,6 @@ def test_random_mix_of_prefill_calls(U, oracle):
         case = W.make_case(cfg)
         kc, vc = oracle_filled(oracle, case)
         mode = ["plain", "window", "fp8", "prompt"][int(rng.integers(4))]
-        if D != 128 and mode == "fp8":
-            mode = "plain"
         if mode == "prompt" and not np.array_equal(case.q_lens, case.context_lens):
             mode = "window"
         tag = f"case {it}: {mode} D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} q_len={q_len} {dtype}"
