@@ -57,6 +57,11 @@ namespace optgqa {
 // way the four rows that a group of 16 lanes transposes, and the next group's four, fall in distinct banks
 template <int D> struct FlatRow { static constexpr int kV = D + 16; };
 
+// What a wave can park in LDS before it has to write it out: the results of up to kStagePieces
+// pieces, kStageCols query-head columns in all (one piece of a shared prefix, two at 8 heads per KV
+// head, five at 4).  Sized so that two workgroups still fit a CU's LDS.
+constexpr int kStagePieces = 5, kStageCols = 20, kStageHdrInts = 16;
+
 // How far the softmax reference may lag behind the running maximum before the accumulators are
 // rescaled, and how far above the maximum it is then put.  16-bit weights: fp16 must keep them
 // inside its range; bf16 has the range but not the precision, so its weights are split in two.
@@ -238,6 +243,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
 
     // per wave: the V rows of two consecutive tiles (32 tokens) in their natural [token][dim] layout
     __shared__ __attribute__((aligned(16))) uint16_t v_lds[kDecodeWaves][2 * TILE][kFlatVRow];
+    // per wave: what finished pieces leave behind, parked until the unit ends (see "side effects" below)
+    constexpr int SROW = D + 4;                         // floats per parked column: D outputs, reference, weight sum; the
+                                                        // odd stride spreads the columns over the LDS banks
+    __shared__ __attribute__((aligned(16))) float st_lds[kDecodeWaves][kStageCols * SROW];
+    __shared__ int st_hdr[kDecodeWaves][kStagePieces][kStageHdrInts];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -431,7 +441,46 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
     uint4 qa[NQ];
     float slope2;                 // ALiBi slope (base 2) of column j16
     int q_pos;                    // position of column j16's query: its sequence's last token
+    // (see "side effects" in the piece loop)
+    auto side_effects = [&](int fx, int64_t row, int64_t new_k, int64_t new_v, int vv, int P_vv) __attribute__((always_inline)) {
+        if constexpr (NEW_TILE) {
+            if ((fx & 1) && lane < 2 * LPR) {                // LPR lanes move the K row, the next LPR the V row
+                const int piece = 8 * vcol;
+                const unsigned char* src = lane < LPR ? k_new + (new_k + piece) * 2 : v_new + (new_v + piece) * 2;
+                uint16_t* dstp = (lane < LPR ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + row + piece;
+                *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
+            }
+        }
+        if (lane == 0) {
+            if (fx & 2) p.plan[vv] = P_vv;
+            if (fx & 4) p.plan[NV] = c;
+        }
+    };
+    auto flush = [&](int count) __attribute__((always_inline)) {
+        for (int k = 0; k < count; ++k) {
+            const int* h = &st_hdr[wave][k][0];
+            const int64_t slot = (int64_t)(((uint64_t)(uint32_t)h[1] << 32) | (uint32_t)h[0]);
+            const int ncols = h[2];
+            side_effects(h[3], (int64_t)(((uint64_t)(uint32_t)h[5] << 32) | (uint32_t)h[4]),
+                         (int64_t)(((uint64_t)(uint32_t)h[7] << 32) | (uint32_t)h[6]),
+                         (int64_t)(((uint64_t)(uint32_t)h[9] << 32) | (uint32_t)h[8]), h[10], h[11]);
+            if (j16 < ncols) {
+                const float* st = &st_lds[wave][0] + (h[12] + j16) * SROW;
+                const int64_t e0 = slot * CS + j16;
+                if (hg == 0) {
+                    p.ws_m[e0] = st[D];
+                    p.ws_l[e0] = st[D + 1];
+                }
+                float* o = p.ws_o + e0 * D + 4 * hg;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+                    *reinterpret_cast<float4*>(o + 16 * db) = *reinterpret_cast<const float4*>(st + 16 * db + 4 * hg);
+            }
+        }
+    };
+    int staged = 0, staged_cols = 0;    // pieces parked in LDS, and the columns they take
     bool chained = false;         // buf[0] / d0 were filled by the previous piece
+    bool same_q = false;          // ... and it was a piece of the same segment (PARTS): qa, slope2, q_pos still hold
     int f = f0;
     for (;;) {
         // ---- one piece: tiles [tau, tau_end) of segment (v, y) -------------------------------
@@ -456,27 +505,27 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         const int64_t new_k = NEW_TILE ? seg.b * p.k_new_stride + (int64_t)g * D : 0;
         const int64_t new_v = NEW_TILE ? seg.b * p.v_new_stride + (int64_t)g * D : 0;
 
-        load_q(qa, slope2, q_pos, seg.b, seg.L, seg.shared != 0, y);
+        if (!(PARTS && same_q)) load_q(qa, slope2, q_pos, seg.b, seg.L, seg.shared != 0, y);
         if (!chained) {
             d0 = tile_src(table, head_off, lo, L, n, has_new, reg_end, new_k, new_v, tau);
             load_tile(buf[0], d0);
         }
+        // ---- side effects of the piece, none of which anything in this launch reads: its partial
+        // result; the new token's K / V rows into the cache if the piece ends a KV head's segment (Alg. 2,
+        // the cache store); P_v of a (virtual) sequence and the unit length, for the combine kernel.
+        // A store in the middle of the stream would hold up the wave: loads complete in issue order
+        // with stores, so the first tile fetched after a store cannot be used before the store is
+        // acknowledged, several tile times later on a busy memory system.  All of them are therefore
+        // parked in LDS (results) and in a header (the rest) and written after the unit's last tile.
+        int fx = 0;
+        int64_t fx_row = 0;                                  // element offset of the new token's cache row
         if (has_new && tau_end == n && y == g * chunks) {
-            // this piece ends the KV head's segment: store the new token's K and V rows (Alg. 2)
             const int blk = scalar_load_i32(table + (Lm1 >> bs_shift));
-            const int64_t dst = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
-            if (lane < 2 * LPR) {                            // LPR lanes move the K row, the next LPR the V row
-                const int piece = 8 * vcol;
-                const unsigned char* src = lane < LPR ? k_new + (new_k + piece) * 2 : v_new + (new_v + piece) * 2;
-                uint16_t* dstp = (lane < LPR ? static_cast<uint16_t*>(p.k_cache_w) : static_cast<uint16_t*>(p.v_cache_w)) + dst + piece;
-                *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
-            }
+            fx_row = blk * block_stride + head_off + (int64_t)(Lm1 & (bs - 1)) * D;
+            fx |= 1;
         }
-        if (lane == 0) {
-            // the combine kernel needs P_v of every non-empty (virtual) sequence and the unit length
-            if (y == 0 && tau == 0) p.plan[v] = P_v;
-            if (f == 0) p.plan[NV] = c;
-        }
+        if (y == 0 && tau == 0) fx |= 2;                     // plan[v] = P_v
+        if (f == 0) fx |= 4;                                 // plan[NV] = c
 
         // ---- the piece after this one (same unit), so that its first tile is on its way before this
         // piece ends.  Without one, the spare prefetch slot re-reads this piece's last tile (a cache
@@ -651,28 +700,60 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
             }
         }
 
-        // ---- leave the piece's partial result in slot u + s (s = v * Y + y): this lane holds dims
+        // ---- the piece's partial result belongs in slot u + s (s = v * Y + y): this lane holds dims
         // 16db + 4hg + v of column j16 ---------------------------------------------------------------
         const int64_t slot = PARTS ? ((((int64_t)v * Y + y) * p.num_partitions + tau / tp) << 1) + (tau % tp != 0)
                                    : (int64_t)u + (int64_t)v * Y + y;
-        if (j16 < (SHARED && seg.shared ? CS : GH)) {          // (a shared prefix fills all 16 columns of its slots)
-            const int64_t e0 = slot * CS + j16;
-            if (hg == 0) {
-                p.ws_m[e0] = m_ref;
-                p.ws_l[e0] = lsum[0];
+        const int ncols = SHARED && seg.shared ? CS : GH;    // (a shared prefix fills all 16 columns of its slots)
+        if (has_next) {
+            if (staged == kStagePieces || staged_cols + ncols > kStageCols) {    // no room: write out what is parked
+                flush(staged);
+                staged = staged_cols = 0;
             }
-            float* o = p.ws_o + e0 * D + 4 * hg;
+            if (j16 < ncols) {
+                float* st = &st_lds[wave][0] + (staged_cols + j16) * SROW;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
-                *reinterpret_cast<float4*>(o + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+                for (int db = 0; db < NDB; ++db)
+                    *reinterpret_cast<float4*>(st + 16 * db + 4 * hg) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+                if (hg == 0) {
+                    st[D] = m_ref;
+                    st[D + 1] = lsum[0];
+                }
+            }
+            if (lane == 0) {
+                int* h = &st_hdr[wave][staged][0];
+                h[0] = (int)(uint32_t)slot, h[1] = (int)(slot >> 32), h[2] = ncols, h[3] = fx;
+                h[4] = (int)(uint32_t)fx_row, h[5] = (int)(fx_row >> 32);
+                h[6] = (int)(uint32_t)new_k, h[7] = (int)(new_k >> 32);
+                h[8] = (int)(uint32_t)new_v, h[9] = (int)(new_v >> 32);
+                h[10] = v, h[11] = P_v, h[12] = staged_cols;
+            }
+            ++staged;
+            staged_cols += ncols;
+        } else {
+            // the unit's last piece: straight from the registers, then everything that was parked
+            side_effects(fx, fx_row, new_k, new_v, v, P_v);
+            if (j16 < ncols) {
+                const int64_t e0 = slot * CS + j16;
+                if (hg == 0) {
+                    p.ws_m[e0] = m_ref;
+                    p.ws_l[e0] = lsum[0];
+                }
+                float* o = p.ws_o + e0 * D + 4 * hg;
+#pragma unroll
+                for (int db = 0; db < NDB; ++db)
+                    *reinterpret_cast<float4*>(o + 16 * db) = make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+            }
+            flush(staged);
+            break;
         }
 
         // ---- next piece ------------------------------------------------------------------------
-        if (!has_next) break;
         f += ntw;
         if (ny != y || nv != v) {                            // the next piece starts a segment
             if (y + 1 == Y) P_v += n;                        // sequences skipped on the way have no tiles
         }
+        same_q = nv == v && ny == y;
         v = nv, y = ny, seg = nseg, tau = ntau;
         chained = true;
     }
