@@ -46,21 +46,23 @@ KV_SCALE = 0.0125              # --kv-cache e4m3: N(0,1) data, the format's +-44
 # named next to it.  Not measured in this run: an entry goes stale when its kernel changes, and a
 # workload / variant without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # key: (bytes, profile summary)                   (FETCH_SIZE KiB x 2.000 + WRITE_SIZE KiB x 1.000) x 1024
-    "C1": (100_352, "profiles/paged_decode_C1_C2_C4.md"),                       # 48.5, 1.0
-    "C2": (83_370_701, "profiles/paged_decode_C1_C2_C4.md"),                    # 39 597.4, 2 221.9
-    "C3": (643_842_560, "profiles/paged_decode_C3.md"),                         # 311 711.2, 5 330.1
-    "C3-all8k": (1_088_673_587, "profiles/paged_decode_C3_all8k.md"),           # 528 917.1, 5 323.6
-    "C4": (551_843_738, "profiles/paged_decode_C1_C2_C4.md"),                   # 265 284.9, 8 340.1 (P = 512)
-    "C4|partition=0": (550_444_442, "profiles/paged_decode_C1_C2_C4.md"),       # 266 650.9, 4 241.6
-    "C5": (151_285_248, "profiles/paged_prefill_C5.md"),                        # 57 485.3, 32 768.9
-    "C5-prompt": (505_554_534, "profiles/paged_prefill_C5_variants.md"),        # 123 967.7, 245 770.2
-    "C3|e4m3": (332_491_264, "profiles/paged_decode_C3_e4m3.md"),               # 157 676.6, 9 345.3
-    "C5|e4m3": (109_353_984, "profiles/paged_prefill_C5_variants.md"),          # 37 011.5, 32 768.0
-    "C3|window=1024": (148_234_342, "profiles/paged_decode_C3_window.md"),      # 69 794.6, 5 170.9
-    "C5|window=512": (100_934_554, "profiles/paged_prefill_C5_variants.md"),    # 32 900.4, 32 768.1
-    "C3|shared=2": (428_900_762, "profiles/paged_decode_C3_shared_prefix.md"),  # 205 156.5, 8 535.4
-    "C3|shared=4": (476_663_910, "profiles/paged_decode_C3_shared_prefix.md"),  # 228 825.8, 7 840.5
+    # key: (bytes, profile summary)                                                    # FETCH_SIZE KiB, WRITE_SIZE KiB
+    "C1":              (100_352, "profiles/paged_decode_C1_C2_C4.md"),                # 48.5, 1.0
+    "C2":              (83_445_555, "profiles/paged_decode_C1_C2_C4.md"),             # 39 634.0, 2 221.8
+    "C3":              (644_162_765, "profiles/paged_decode_C3.md"),                  # 311 871.7, 5 321.8
+    "C3-all8k":        (1_089_124_045, "profiles/paged_decode_C3_all8k.md"),          # 529 144.4, 5 308.9
+    "C4":              (550_505_882, "profiles/paged_decode_C1_C2_C4.md"),            # 264 641.4, 8 320.6 (P = 512)
+    "C4|partition=0":  (551_163_494, "profiles/paged_decode_C1_C2_C4.md"),            # 267 002.1, 4 241.4
+    "C5":              (151_277_670, "profiles/paged_prefill_C5.md"),                 # 57 481.5, 32 769.1
+    "C5-prompt":       (505_036_083, "profiles/paged_prefill_C5_variants.md"),        # 123 718.5, 245 762.3
+    "C3|e4m3":         (331_807_642, "profiles/paged_decode_C3_e4m3.md"),             # 157 346.7, 9 337.5
+    "C5|e4m3":         (109_350_093, "profiles/paged_prefill_C5_variants.md"),        # 37 009.6, 32 768.0
+    "C3|window=1024":  (148_694_733, "profiles/paged_decode_C3_window.md"),           # 70 019.7, 5 170.3
+    "C3|window=4096":  (475_426_816, "profiles/paged_decode_C3_window.md"),           # 229 492.9, 5 298.2
+    "C5|window=512":   (100_956_774, "profiles/paged_prefill_C5_variants.md"),        # 32 911.2, 32 768.2
+    "C3|shared=2":     (429_063_475, "profiles/paged_decode_C3_shared_prefix.md"),    # 205 238.6, 8 530.1
+    "C3|shared=4":     (476_824_166, "profiles/paged_decode_C3_shared_prefix.md"),    # 228 907.5, 7 833.6
+    "C3-d64":          (321_057_690, "profiles/paged_decode_C3.md"),                  # 155 409.8, 2 713.3 (C3 shapes at head_dim 64)
 }
 
 
