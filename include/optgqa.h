@@ -108,8 +108,10 @@ int optgqa_reshape_and_cache(const void *k, const void *v, void *k_cache, void *
  *   alibi_slopes    [num_heads] fp32, or NULL for no bias
  *   max_context_len an upper bound on context_lens (used for sizing only)
  *   partition_size  0: the library decides whether and how to split the context;
- *                   >0: split the context into runs of this many tokens (multiple of
- *                       block_size and of 16), one workgroup per run, then combine;
+ *                   >0: split the context into partitions of this many tokens (multiple of
+ *                       block_size and of 16) whose results are computed separately and then
+ *                       combined (the waves of the launch still get equal shares: a share
+ *                       boundary may cut a partition into two separately computed pieces);
  *                   OPTGQA_SPLIT_BALANCED: split by equal work - every wave of the launch gets
  *                       the same number of 16-token tiles, whatever the mix of context
  *                       lengths, and the pieces are combined afterwards; this is also what

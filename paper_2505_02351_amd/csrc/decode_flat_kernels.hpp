@@ -15,7 +15,7 @@
 //
 // A unit's range is a short list of pieces, each inside one segment; per piece the wave runs a
 // register-prefetched matrix-core loop (K/V tiles fetched one tile ahead straight into VGPRs, as
-// in the fixed-partition kernel) and leaves one partial result (reference, weight sum,
+// in the unsplit kernel of decode_mma_kernels.hpp) and leaves one partial result (reference, weight sum,
 // un-normalised output) for the combine kernel.  The pairs
 // (unit, segment) that occur form a staircase, so slot = u + s (s = b*Y + y) numbers them
 // without collisions and without any bookkeeping: at most U + B*Y slots.
@@ -24,7 +24,7 @@
 // the context lengths itself (two memory round trips for any batch size), and the wave that
 // processes the first tile of a sequence records P_b for the combine kernel.
 //
-// Arithmetic.  Unlike the fixed-partition kernel (fp32 output MFMAs, 32 per tile), both
+// Arithmetic.  Unlike the unsplit kernel (fp32 output MFMAs, 32 per tile), both
 // contractions here are 16-bit MFMAs, computed transposed so that no operand is transposed in
 // registers (the scheme of the tiled prefill kernel): S^T = K Q^T leaves a lane with the scores of
 // four tokens of ONE head, which after the softmax are exactly its slice of the B operand of
@@ -779,9 +779,9 @@ __global__ __launch_bounds__(kReduceThreads) void paged_decode_flat_reduce_kerne
     static_assert(!(NEWTOK && SHARED), "shared prefixes: 2-byte caches");
     constexpr int kVecPerHead = D / 4;
     constexpr int kHeads = kReduceThreads / kVecPerHead;
-    const int h = blockIdx.x * kHeads + threadIdx.x / kVecPerHead;
+    const int h = blockIdx.y * kHeads + threadIdx.x / kVecPerHead;
     const int od = (threadIdx.x % kVecPerHead) * 4;
-    const int b = blockIdx.y;
+    const int b = blockIdx.x;                                // (sequences along x: no 16-bit limit)
     if (h >= p.num_heads) return;
     uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;
     const int NV = SHARED ? 2 * p.num_seqs : p.num_seqs;
@@ -941,7 +941,7 @@ __global__ __launch_bounds__(kPartsReduceGroups * (D / 4)) void paged_decode_par
     constexpr int GW = D / 4;                                          // threads per group: 4 output dims each
     __shared__ float s_m[kPartsReduceGroups][GW], s_den[kPartsReduceGroups][GW];
     __shared__ float4 s_num[kPartsReduceGroups][GW];
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int h = blockIdx.y, b = blockIdx.x;
     const int l32 = threadIdx.x % GW, grp = threadIdx.x / GW;
     const int od = l32 * 4;
     uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)b * p.num_heads + h) * D + od;

@@ -1,6 +1,6 @@
 // Paged decode attention: one query token per sequence against the block-indirected KV cache.
 //
-// Work unit: one workgroup (4 waves) per (context partition, KV head [x head chunk], sequence).
+// Work unit: one workgroup (4 waves) per (KV head [x head chunk], sequence), the whole context.
 // The GH query heads of the group that the workgroup serves all consume the SAME K and V
 // registers, so every KV element is fetched from HBM once per KV-head group (Section II: a group
 // shares one key-value pair), with 16-byte loads that cover a token row with D/8 consecutive lanes.
@@ -16,9 +16,9 @@ namespace optgqa {
 
 struct DecodeParams {
     void* out;                  // [B][Hq][D] dtype
-    float* ws_m;                // split path: [B][Hq][NP]   running max (base-2 domain)
-    float* ws_l;                //             [B][Hq][NP]   sum of weights
-    float* ws_o;                //             [B][Hq][NP][D] un-normalised weighted sum
+    float* ws_m;                // split context (equal-work kernel): per partial-result slot and head,
+    float* ws_l;                //   the softmax reference (base-2 domain), the sum of weights and the
+    float* ws_o;                //   un-normalised weighted sum [D]
     const void* q;              // [B][Hq][D]
     const void* k_cache;        // [NB][Hkv][bs][D]
     const void* v_cache;
@@ -27,13 +27,12 @@ struct DecodeParams {
     const float* slopes;        // [Hq] or nullptr
     float scale2;               // scale * log2(e)
     int num_heads, num_kv_heads, block_size, max_blocks_per_seq;
-    int partition_size;         // tokens per workgroup; >= max context when unsplit
-    int num_partitions;         // 1 = unsplit: the kernel writes `out` itself
+    int num_partitions;         // fixed partitions on the equal-work kernel: partitions per segment, else 1
     int num_seqs;
     int row_offset;             // first row handled by this launch (grid.z/y counts from here)
     int heads_per_wg;           // query heads one workgroup serves (divides the group size)
-    // Equal-work split (head_dim 128): one unit per wave, see decode_flat_kernels.hpp.
-    // There ws_m / ws_l are [slot][heads_per_wg] and ws_o is [slot][heads_per_wg][D].
+    // Equal-work kernel: one unit per wave, see decode_flat_kernels.hpp; ws_m / ws_l are
+    // [slot][columns] and ws_o is [slot][columns][D].
     int num_units;              // waves of the launch
     int segs_per_seq;           // KV heads x head chunks
     int32_t* plan;              // [num_seqs + 1]: tile prefix P_b per non-empty sequence, then tiles per unit
@@ -75,15 +74,6 @@ __device__ __forceinline__ bool row_to_seq(const DecodeParams& p, int row, int& 
 
 constexpr int kDecodeWaves = 4;
 
-// Partition index of this workgroup.  Workgroups go to the 8 XCDs round-robin by flat id; with
-// grid.x = number of partitions and late partitions mostly empty (short sequences), the plain
-// mapping would give some XCDs all the work whenever grid.x shares a factor with 8.  Rotating
-// the partition index by the other two grid coordinates hands every XCD the same mix.
-__device__ __forceinline__ int skewed_partition(int num_partitions)
-{
-    return (blockIdx.x + blockIdx.y + blockIdx.z) % num_partitions;
-}
-
 template <int DT, int D, int GH>
 __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const DecodeParams p)
 {
@@ -95,7 +85,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
     const int r = lane / LPR, c = lane % LPR;
 
     const int row = p.row_offset + blockIdx.z;
-    const int part = skewed_partition(p.num_partitions);
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int G = Hq / Hkv;
     const int chunks = G / GH;
@@ -104,21 +93,15 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
 
     int b, L;
     if (!row_to_seq(p, row, b, L)) return;
-    // Sliding window (Alg. 1, local mask; unsplit launches only): the query at position L - 1 sees
-    // tokens lo .. L - 1; the steps start at the row group that holds token lo.
-    const int lo = (p.window > 0 && p.num_partitions == 1) ? max(L - p.window, 0) : 0;
-    const int t_begin = max(part * p.partition_size, lo / TPS * TPS);
-    const int t_end = min(L, part * p.partition_size + p.partition_size);
+    const int t_begin = 0, t_end = L;                   // the whole context in one workgroup
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
     const uint16_t* __restrict__ kc = static_cast<const uint16_t*>(p.k_cache);
     const uint16_t* __restrict__ vc = static_cast<const uint16_t*>(p.v_cache);
 
     if (t_begin >= t_end) {
-        // An empty context still owes an output row (all +0); empty partitions owe nothing.
-        if (p.num_partitions == 1) {
-            uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
-            for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
-        }
+        // an empty context still owes an output row (all +0)
+        uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
+        for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
         return;
     }
 
@@ -146,7 +129,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
         const int t0 = t_begin + s * TPS;                 // wave-uniform, never straddles a block
         const int64_t blk = table[t0 / bs];
         const int t = t0 + r;
-        const bool valid = t < t_end && t >= lo;
+        const bool valid = t < t_end;
         const int64_t off = ((blk * Hkv + g) * bs + (t0 % bs) + r) * D + 8 * c;
         uint4 kr = make_uint4(0, 0, 0, 0), vr = make_uint4(0, 0, 0, 0);
         if (valid) {
@@ -225,85 +208,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64) void paged_decode_kernel(const D
             den = fmaf(f, sm_l[w][i], den);
         }
         const int h = h0 + i;
-        if (p.num_partitions == 1) {
-            static_cast<uint16_t*>(p.out)[((int64_t)row * Hq + h) * D + d] = narrow<DT>(num / den);
-        } else {
-            const int64_t slot = ((int64_t)row * Hq + h) * p.num_partitions + part;
-            if (d == 0) {
-                p.ws_m[slot] = M;
-                p.ws_l[slot] = den;
-            }
-            p.ws_o[slot * D + d] = num;
-        }
+        static_cast<uint16_t*>(p.out)[((int64_t)row * Hq + h) * D + d] = narrow<DT>(num / den);
     }
 }
 
-// Combine the per-partition (max, sum, weighted sum) triples of the split path:
-//   M = max_p m_p,  out = sum_p 2^(m_p-M) o_p / sum_p 2^(m_p-M) l_p
-// (Section III-A: the per-partition results are carried forward and merged).
-// One thread per 4 output dims; kReduceHeads heads per workgroup; grid = (ceil(Hq / kReduceHeads), rows).
-// Partitions are taken in batches of 8 whose loads are all issued before the first use: the
-// kernel is a few microseconds of pure memory latency, so the loads must overlap.
-constexpr int kReduceThreads = 256;
-
-template <int DT, int D>
-__global__ __launch_bounds__(kReduceThreads) void paged_decode_reduce_kernel(const DecodeParams p)
-{
-    constexpr int kVecPerHead = D / 4;
-    constexpr int kHeads = kReduceThreads / kVecPerHead;
-    const int h = blockIdx.x * kHeads + threadIdx.x / kVecPerHead;
-    const int od = (threadIdx.x % kVecPerHead) * 4;
-    const int row = p.row_offset + blockIdx.y;
-    if (h >= p.num_heads) return;
-    int b, L;
-    if (!row_to_seq(p, row, b, L)) return;
-    uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * p.num_heads + h) * D + od;
-    if (L <= 0) {
-        *reinterpret_cast<uint2*>(o) = make_uint2(0u, 0u);
-        return;
-    }
-    const int np = (L + p.partition_size - 1) / p.partition_size;
-    const int64_t base = ((int64_t)row * p.num_heads + h) * p.num_partitions;
-    // One pass in batches of 8 partitions with a running reference (a separate pass for the maximum
-    // would be a second chain of memory round trips).
-    float M = -INFINITY;
-    float den = 0.f;
-    float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i0 = 0; i0 < np; i0 += 8) {
-        float mm[8], ll[8];
-        float4 x[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int i = min(i0 + k, np - 1);
-            mm[k] = p.ws_m[base + i];
-            ll[k] = p.ws_l[base + i];
-            x[k] = *reinterpret_cast<const float4*>(p.ws_o + (base + i) * D + od);
-        }
-        float Mn = M;                                            // clamped repeats of the last partition do not change it
-#pragma unroll
-        for (int k = 0; k < 8; ++k) Mn = fmaxf(Mn, mm[k]);
-        const float keep = i0 == 0 ? 0.f : fast_exp2(M - Mn);    // nothing accumulated before the first batch
-        M = Mn;
-        den *= keep;
-        num.x *= keep;
-        num.y *= keep;
-        num.z *= keep;
-        num.w *= keep;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const float f = i0 + k < np ? fast_exp2(mm[k] - M) : 0.f;
-            den = fmaf(f, ll[k], den);
-            num.x = fmaf(f, x[k].x, num.x);
-            num.y = fmaf(f, x[k].y, num.y);
-            num.z = fmaf(f, x[k].z, num.z);
-            num.w = fmaf(f, x[k].w, num.w);
-        }
-    }
-    const float inv = 1.f / den;
-    uint2 packed;
-    packed.x = narrow2<DT>(num.x * inv, num.y * inv);
-    packed.y = narrow2<DT>(num.z * inv, num.w * inv);
-    *reinterpret_cast<uint2*>(o) = packed;
-}
+constexpr int kReduceThreads = 256;      // threads of a combine workgroup (decode_flat_kernels.hpp)
 
 }  // namespace optgqa

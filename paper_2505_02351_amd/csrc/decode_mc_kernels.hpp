@@ -130,7 +130,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
     const int r = lane / LPR, c = lane % LPR, u = lane & 3;
 
     const int row = p.row_offset + blockIdx.z;
-    const int part = skewed_partition(p.num_partitions);
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
     const int G = Hq / Hkv;
@@ -140,13 +139,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
 
     int b, L;
     if (!row_to_seq(p, row, b, L)) return;
-    const int t_begin = part * p.partition_size;
-    const int t_end = min(L, t_begin + p.partition_size);
-    if (t_begin >= t_end) {
-        if (p.num_partitions == 1) {
-            uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
-            for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
-        }
+    const int t_begin = 0, t_end = L;                   // the whole context in one workgroup
+    if (t_begin >= t_end) {                             // an empty context still owes an output row (all +0)
+        uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
+        for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
         return;
     }
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
@@ -361,20 +357,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, 2) void paged_decode_mc_kernel(c
 #pragma unroll
         for (int s = 0; s < NSTREAM; ++s) den = fmaf(fast_exp2(sm_m[s][oh] - M), sm_l[s][oh], den);
         const int h = h0 + oh;
-        if (p.num_partitions == 1) {
-            const float inv = 1.f / den;
-            uint2 packed;
-            packed.x = narrow2<DT>(num.x * inv, num.y * inv);
-            packed.y = narrow2<DT>(num.z * inv, num.w * inv);
-            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h) * D + od) = packed;
-        } else {
-            const int64_t slot = ((int64_t)row * Hq + h) * p.num_partitions + part;
-            if (od == 0) {
-                p.ws_m[slot] = M;
-                p.ws_l[slot] = den;
-            }
-            *reinterpret_cast<float4*>(p.ws_o + slot * D + od) = num;
-        }
+        const float inv = 1.f / den;
+        uint2 packed;
+        packed.x = narrow2<DT>(num.x * inv, num.y * inv);
+        packed.y = narrow2<DT>(num.z * inv, num.w * inv);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h) * D + od) = packed;
     }
 }
 

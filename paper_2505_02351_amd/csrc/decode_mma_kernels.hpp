@@ -90,7 +90,6 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void 
     const int hg = lane >> 4;                       // head quad (scores, output) / k-slab (K) / token row (V)
 
     const int row = p.row_offset + blockIdx.z;
-    const int part = skewed_partition(p.num_partitions);
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
     const int GH = p.heads_per_wg;
@@ -101,13 +100,10 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void 
 
     int b, L;
     if (!row_to_seq(p, row, b, L)) return;
-    const int t_begin = part * p.partition_size;
-    const int t_end = min(L, t_begin + p.partition_size);
-    if (t_begin >= t_end) {
-        if (p.num_partitions == 1) {
-            uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
-            for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
-        }
+    const int t_begin = 0, t_end = L;                   // the whole context in one workgroup
+    if (t_begin >= t_end) {                             // an empty context still owes an output row (all +0)
+        uint16_t* o = static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h0) * D;
+        for (int i = threadIdx.x; i < GH * D; i += NW * 64) o[i] = 0;
         return;
     }
     const uint16_t* __restrict__ qp = static_cast<const uint16_t*>(p.q);
@@ -122,7 +118,7 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void 
     const int64_t block_stride = (int64_t)Hkv * bs * D;
     const int t_last = t_end - 1;
 
-    // Each wave owns a contiguous quarter of the partition's tiles.
+    // Each wave owns a contiguous quarter of the context's tiles.
     const int ntiles = (t_end - t_begin + TILE - 1) / TILE;
     const int tpw = (ntiles + NW - 1) / NW;
     const int tile_first = wave * tpw;
@@ -300,20 +296,11 @@ __global__ __launch_bounds__(kDecodeWaves * 64, OPTGQA_MMA_WAVES_PER_SIMD) void 
             num.w += x.w;
         }
         const int h = h0 + oh;
-        if (p.num_partitions == 1) {
-            const float inv = 1.f / den;
-            uint2 packed;
-            packed.x = narrow2<DT>(num.x * inv, num.y * inv);
-            packed.y = narrow2<DT>(num.z * inv, num.w * inv);
-            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h) * D + od) = packed;
-        } else {
-            const int64_t slot = ((int64_t)row * Hq + h) * p.num_partitions + part;
-            if (od == 0) {
-                p.ws_m[slot] = M;
-                p.ws_l[slot] = den;
-            }
-            *reinterpret_cast<float4*>(p.ws_o + slot * D + od) = num;
-        }
+        const float inv = 1.f / den;
+        uint2 packed;
+        packed.x = narrow2<DT>(num.x * inv, num.y * inv);
+        packed.y = narrow2<DT>(num.z * inv, num.w * inv);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + ((int64_t)row * Hq + h) * D + od) = packed;
     }
 }
 

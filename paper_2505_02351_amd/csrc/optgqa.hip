@@ -180,7 +180,6 @@ bool plan_flat(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads, int 
     const int64_t Y = (int64_t)num_kv_heads * (group / gh);
     const int64_t segs = Y * num_seqs * (shared ? 2 : 1);
     const int cols = shared ? 16 : gh;
-    if (num_seqs > kMaxRowsPerLaunch) return false;          // the combine kernel's grid.y
     // Flat tile indices are 32-bit.  2^30 tiles would be 8 TiB of cache, so the margin of 2 also
     // covers lengths above the stated bound.
     if (segs * ((max_context_len + kMmaTile - 1) / kMmaTile) >= (1LL << 30)) return false;
@@ -213,7 +212,6 @@ bool plan_flat_parts(SplitPlan& s, int num_seqs, int num_heads, int num_kv_heads
     const int64_t Y = (int64_t)num_kv_heads * (group / gh);
     const int np = (max_context_len + P - 1) / P;
     const int64_t parts = Y * num_seqs * np;                 // upper bound: every sequence at max_context_len
-    if (num_seqs > kMaxRowsPerLaunch) return false;
     if (parts * (P / kMmaTile) >= (1LL << 30)) return false;  // flat tile indices are 32-bit
     int64_t wgs = (parts + kDecodeWaves - 1) / kDecodeWaves;  // no more units than partitions
     if (wgs > flat_workgroups(false)) wgs = flat_workgroups(false);
@@ -241,15 +239,10 @@ SplitPlan plan_split(int num_seqs, int num_heads, int num_kv_heads, int head_dim
             return s;
         if (partition_size == OPTGQA_SPLIT_BALANCED) return s;      // cannot: the caller sees "unsplit"
     }
-    if (P <= 0) return s;
-    if (window <= 0 && !shared && P % kMmaTile == 0 &&
-        plan_flat_parts(s, num_seqs, num_heads, num_kv_heads, head_dim, max_context_len, P))
-        return s;
-    s.partition_size = P;
-    s.num_partitions = (max_context_len + P - 1) / P;
-    if (s.num_partitions < 1) s.num_partitions = 1;
-    s.bytes = (size_t)num_seqs * num_heads * s.num_partitions * (head_dim + 2) * sizeof(float);
-    return s;
+    // fixed partitions (multiples of 16 tokens: checked by the caller) run on the same kernel
+    if (partition_size > 0 && window <= 0 && !shared)
+        plan_flat_parts(s, num_seqs, num_heads, num_kv_heads, head_dim, max_context_len, P);
+    return s;                                                // (unsplit if that could not be planned)
 }
 
 // The fast decode kernel takes its LDS as dynamic shared memory (the ring may exceed the 64 KiB
@@ -272,10 +265,8 @@ int launch_decode_gh(const DecodeParams& p, int gh, dim3 grid, hipStream_t st)
         return launch(paged_decode_mma_kernel<DT>, grid, block, 0, st, p);
     }
 #ifndef OPTGQA_VALU_ONLY_DECODE
-    if (p.window <= 0) {                                 // (the general kernel is the one that knows about windows)
-        if (gh == 8) return launch_decode_mc<DT, D, 8>(p, grid, block, st);
-        if (gh == 4) return launch_decode_mc<DT, D, 4>(p, grid, block, st);
-    }
+    if (gh == 8) return launch_decode_mc<DT, D, 8>(p, grid, block, st);
+    if (gh == 4) return launch_decode_mc<DT, D, 4>(p, grid, block, st);
 #endif
     switch (gh) {
     case 8: return launch(paged_decode_kernel<DT, D, 8>, grid, block, 0, st, p);
@@ -295,17 +286,12 @@ int launch_decode(DecodeParams p, int num_rows, hipStream_t st)
     for (int first = 0; first < num_rows; first += kMaxRowsPerLaunch) {
         const int rows = num_rows - first < kMaxRowsPerLaunch ? num_rows - first : kMaxRowsPerLaunch;
         p.row_offset = first;
-        const dim3 grid(p.num_partitions, p.num_kv_heads * (group / gh), rows);
+        const dim3 grid(1, p.num_kv_heads * (group / gh), rows);
         int rc;
         {
             KernelEvents ev(st);
             rc = launch_decode_gh<DT, D>(p, gh, grid, st);
         }
-        if (rc != OPTGQA_OK) return rc;
-        if (p.num_partitions == 1) continue;
-        constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
-        rc = launch(paged_decode_reduce_kernel<DT, D>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, rows),
-                    dim3(kReduceThreads), 0, st, p);
         if (rc != OPTGQA_OK) return rc;
     }
     return OPTGQA_OK;
@@ -345,9 +331,9 @@ int launch_decode_flat_dt(DecodeParams p, int workgroups, hipStream_t st)
     }
     if (rc != OPTGQA_OK) return rc;
     if constexpr (PARTS)
-        return launch(paged_decode_parts_reduce_kernel<DT, D>, dim3(p.num_heads, p.num_seqs), dim3(kPartsReduceGroups * (D / 4)), 0, st, p);
+        return launch(paged_decode_parts_reduce_kernel<DT, D>, dim3(p.num_seqs, p.num_heads), dim3(kPartsReduceGroups * (D / 4)), 0, st, p);
     constexpr int kHeadsPerWg = kReduceThreads / (D / 4);
-    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED, D>, dim3((p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg, p.num_seqs),
+    return launch(paged_decode_flat_reduce_kernel<DT, FUSED && KV8, SHARED, D>, dim3(p.num_seqs, (p.num_heads + kHeadsPerWg - 1) / kHeadsPerWg),
                   dim3(kReduceThreads), 0, st, p);
 }
 
@@ -684,7 +670,6 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
         p.ws_m = static_cast<float*>(workspace) + s.plan_floats;
         p.ws_l = p.ws_m + s.ml_floats;
         p.ws_o = p.ws_l + s.ml_floats;
-        p.partition_size = 1 << 30;
         p.num_partitions = 1;
         if (s.partition_size > 0) {                          // fixed partitions
             p.part_tiles = s.partition_size / kMmaTile;
@@ -702,20 +687,11 @@ int attention_impl(void* out, const void* q, const void* k_cache, const void* v_
         const int cap = flat_workgroups(kv_scales != nullptr);
         return launch_decode_flat(dtype, head_dim, p, s.workgroups < cap ? s.workgroups : cap, st, kv_scales != nullptr);
     }
+    // unsplit: one workgroup per (sequence, KV head / head chunk) walks the whole context
     p.plan = nullptr;
     p.num_units = p.segs_per_seq = 0;
-    if (s.partition_size > 0) {
-        const size_t n = (size_t)num_seqs * num_heads * s.num_partitions;
-        p.ws_m = static_cast<float*>(workspace);
-        p.ws_l = p.ws_m + n;
-        p.ws_o = p.ws_l + n;
-        p.partition_size = s.partition_size;
-        p.num_partitions = s.num_partitions;
-    } else {
-        p.ws_m = p.ws_l = p.ws_o = nullptr;
-        p.partition_size = 1 << 30;
-        p.num_partitions = 1;
-    }
+    p.ws_m = p.ws_l = p.ws_o = nullptr;
+    p.num_partitions = 1;
     return launch_decode_any(dtype, head_dim, p, num_seqs, st);
 }
 

@@ -303,6 +303,31 @@ def test_decode_balanced_many_sequences(U, oracle, B, hi, zeros):
     assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
 
 
+def test_decode_more_sequences_than_a_16_bit_grid(U, oracle):
+    """70 000 one-block sequences in one call: the unsplit kernels run in slices of 65 535 rows, and
+    the equal-work kernel with its two combine kernels takes the whole batch (sequences run along
+    the x dimension of their grids)."""
+    B = 70000
+    rng = np.random.default_rng(70)
+    lens = rng.integers(1, 17, size=B).astype(np.int32)
+    lens[rng.choice(B, size=2000, replace=False)] = 0
+    lens[B - 1] = 16
+    cfg = W.small_config(name="grid16", dtype=W.F16, batch=B, num_heads=2, num_kv_heads=1, head_dim=64,
+                         block_size=16, num_blocks=B + 3, ctx_lo=1, ctx_hi=16, seed=71)
+    case = W.make_case(cfg, context_lens=lens)
+    q_full = np.zeros((B, 2, 64), np.uint16)
+    q_full[lens > 0] = case.q
+    case.q = q_full
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    for partition in (-1, BALANCED, 16):
+        dev = U.DevCase(case)
+        dev.write_cache()
+        got = dev.decode(partition_size=partition)
+        assert not got[lens == 0].any(), partition
+        assert U.max_abs_err(got, ref, W.F16) <= U.TOL[W.F16], partition
+
+
 def test_decode_balanced_and_fixed_partitions_against_the_oracle(U, oracle):
     """The two ways of splitting the context, on a ragged batch whose units start and end inside
     segments: each against the oracle at the stated tolerance, and against each other to well inside
