@@ -328,6 +328,106 @@ def test_decode_more_sequences_than_a_16_bit_grid(U, oracle):
         assert U.max_abs_err(got, ref, W.F16) <= U.TOL[W.F16], partition
 
 
+def lift_to_large_pool(dev, total_blocks):
+    """Moves a DevCase's cache blocks to the top of a pool of ``total_blocks`` blocks (the rest is
+    left uninitialised: no table names it), so that block offsets no longer fit 32 bits."""
+    import torch
+    n, bs = dev.k_cache.shape[0], dev.k_cache.shape[2]
+    off = total_blocks - n
+    for name in ("k_cache", "v_cache"):
+        small = getattr(dev, name)
+        big = torch.empty((total_blocks,) + tuple(small.shape[1:]), dtype=small.dtype, device="cuda")
+        big[off:] = small
+        setattr(dev, name, big)
+    dev.block_tables = dev.block_tables + off
+    dev.slot_mapping = torch.where(dev.slot_mapping >= 0, dev.slot_mapping + off * bs, dev.slot_mapping)
+    return off
+
+
+def test_pool_larger_than_4_gib(U, oracle):
+    """Caches of 4.6 GB each with the batch's blocks at the top: element offsets beyond 2^31 and byte
+    offsets beyond 2^32 in the cache write, every decode path and the prefill (the oracle sees the
+    same blocks in a small pool: results do not depend on where a block lives)."""
+    import torch
+    total = 70000                                            # x 64 KiB per block and tensor
+    cfg = W.small_config(name="bigpool", dtype=W.BF16, batch=6, num_heads=16, num_kv_heads=8, head_dim=128,
+                         block_size=32, num_blocks=6 * 20 + 5, ctx_lo=30, ctx_hi=600, seed=4100)
+    case = W.make_case(cfg)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    off = lift_to_large_pool(dev, total)
+    assert off * kc[0].size * 2 > 2 ** 32
+    got = dev.step()                                         # fused cache write + equal-work split
+    assert np.array_equal(U.to_host(dev.k_cache[off:]), kc) and np.array_equal(U.to_host(dev.v_cache[off:]), vc)
+    assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+    for partition in (-1, 64, BALANCED):
+        assert U.max_abs_err(dev.decode(partition_size=partition), ref, W.BF16) <= U.TOL[W.BF16], partition
+    assert U.max_abs_err(dev.decode_window(10 ** 6), ref, W.BF16) <= U.TOL[W.BF16]
+    dev2 = U.DevCase(case)
+    lift_to_large_pool(dev2, total)
+    dev2.write_cache()                                       # the separate cache-write kernel
+    assert np.array_equal(U.to_host(dev2.k_cache[off:]), kc) and np.array_equal(U.to_host(dev2.v_cache[off:]), vc)
+    del dev, dev2
+    torch.cuda.empty_cache()
+    pcfg = W.small_config(name="bigpool-pf", kind="prefill", dtype=W.F16, batch=3, num_heads=8, num_kv_heads=8,
+                          head_dim=128, block_size=32, num_blocks=3 * 12 + 5, ctx_lo=100, ctx_hi=380, q_len=70,
+                          seed=4101)
+    pcase = W.make_case(pcfg)
+    kc, vc = oracle_filled(oracle, pcase)
+    pref = oracle.paged_prefill(pcase.q, kc, vc, pcase.block_tables, pcase.context_lens, pcase.cu_q_lens,
+                                pcase.slopes, pcase.scale, pcase.dtype)
+    pdev = U.DevCase(pcase)
+    off = lift_to_large_pool(pdev, total)
+    pdev.write_cache()
+    assert np.array_equal(U.to_host(pdev.k_cache[off:]), kc)
+    U.check_scaled(pdev.prefill(), pref, W.F16, "prefill, pool of 4.6 GB")
+    del pdev
+    torch.cuda.empty_cache()
+    # 8-bit caches of 4.6 GB each (140 000 blocks of 32 KiB): quantising write, decode, prefill
+    import oracle as O
+    import paper_2505_02351_amd as G
+    import pins_e4m3
+    total8 = 140000
+    k_scale, v_scale = 0.0125, 0.02
+    kc8, vc8, (k_all, v_all, slots) = pins_e4m3.quantised_cache(pcase, k_scale, v_scale)
+    off = total8 - kc8.shape[0]
+    assert off * kc8[0].size > 2 ** 32
+    dk = torch.empty((total8,) + kc8.shape[1:], dtype=torch.uint8, device="cuda")
+    dv = torch.empty((total8,) + vc8.shape[1:], dtype=torch.uint8, device="cuda")
+    dk[off:] = 0x7F
+    dv[off:] = 0x7F
+    G.reshape_and_cache_fp8(U.to_dev(k_all, pcase.dtype), U.to_dev(v_all, pcase.dtype), dk, dv,
+                            torch.from_numpy(slots + off * pcfg.block_size).cuda(), k_scale, v_scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(dk[off:].cpu().numpy(), kc8) and np.array_equal(dv[off:].cpu().numpy(), vc8)
+    qd = U.to_dev(pcase.q, pcase.dtype)
+    out = torch.full_like(qd, float("nan"))
+    G.paged_prefill_fp8(out, qd, dk, dv, torch.from_numpy(pcase.block_tables + off).cuda(),
+                        torch.from_numpy(pcase.context_lens).cuda(), torch.from_numpy(pcase.cu_q_lens).cuda(),
+                        torch.from_numpy(pcase.slopes).cuda(), float(pcase.scale), k_scale, v_scale, pcase.max_q_len)
+    ref8 = O.paged_prefill_e4m3(pcase.q, kc8, vc8, pcase.block_tables, pcase.context_lens, pcase.cu_q_lens,
+                                pcase.slopes, pcase.scale, k_scale, v_scale, pcase.dtype)
+    U.check_scaled(U.to_host(out), ref8, pcase.dtype, "prefill over E4M3 caches, pool of 4.6 GB")
+    # decode over the same caches: the last new token of every sequence as the query
+    last = pcase.cu_q_lens[1:] - 1
+    q_dec = np.ascontiguousarray(pcase.q[last])
+    n, _ = G.paged_attention_workspace_bytes(pcfg.batch, pcfg.num_heads, pcfg.num_kv_heads, 128, pcfg.block_size,
+                                             pcase.max_context_len, G.SPLIT_BALANCED)
+    ws = torch.empty(n // 4, dtype=torch.float32, device="cuda")
+    qdd = U.to_dev(q_dec, pcase.dtype)
+    outd = torch.full_like(qdd, float("nan"))
+    G.paged_attention_fp8(outd, qdd, dk, dv, torch.from_numpy(pcase.block_tables + off).cuda(),
+                          torch.from_numpy(pcase.context_lens).cuda(), torch.from_numpy(pcase.slopes).cuda(),
+                          float(pcase.scale), k_scale, v_scale, pcase.max_context_len, ws)
+    torch.cuda.synchronize()
+    refd = O.paged_attention_e4m3(q_dec, kc8, vc8, pcase.block_tables, pcase.context_lens, pcase.slopes, pcase.scale,
+                                  k_scale, v_scale, pcase.dtype)
+    assert U.max_abs_err(U.to_host(outd), refd, pcase.dtype) <= U.TOL[pcase.dtype]
+    del dk, dv
+    torch.cuda.empty_cache()
+
+
 def test_decode_balanced_and_fixed_partitions_against_the_oracle(U, oracle):
     """The two ways of splitting the context, on a ragged batch whose units start and end inside
     segments: each against the oracle at the stated tolerance, and against each other to well inside
