@@ -328,6 +328,43 @@ def test_decode_more_sequences_than_a_16_bit_grid(U, oracle):
         assert U.max_abs_err(got, ref, W.F16) <= U.TOL[W.F16], partition
 
 
+def test_decode_one_very_long_context(U, oracle):
+    """A context of 2^20 tokens next to one of five tokens: 65 536 tiles in one segment, every
+    unit of the equal-work split inside the same sequence, 256 fixed partitions of 4096 tokens,
+    and the unsplit kernel walking it alone."""
+    lens = np.array([1 << 20, 5], np.int32)
+    cfg = W.small_config(name="long", dtype=W.BF16, batch=2, num_heads=4, num_kv_heads=1, head_dim=128,
+                         block_size=64, num_blocks=(1 << 14) + 3, ctx_lo=1, ctx_hi=1 << 20, seed=4200)
+    case = W.make_case(cfg, context_lens=lens)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle_decode(oracle, case, kc, vc)
+    dev = U.DevCase(case)
+    got = dev.step()
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert U.max_abs_err(got, ref, W.BF16) <= U.TOL[W.BF16]
+    for partition in (4096, BALANCED, -1):
+        assert U.max_abs_err(dev.decode(partition_size=partition), ref, W.BF16) <= U.TOL[W.BF16], partition
+    ref_w = __import__("oracle").paged_attention_window(case.q, kc, vc, case.block_tables, case.context_lens,
+                                                        case.slopes, case.scale, 100000, W.BF16)
+    assert U.max_abs_err(dev.decode_window(100000), ref_w, W.BF16) <= U.TOL[W.BF16]
+
+
+def test_prefill_long_cached_context(U, oracle):
+    """100 new tokens behind 150 000 cached ones: 4 700 key tiles per workgroup, nearly all of them
+    far enough back for the steep-slope head to skip and none for the head without a slope."""
+    cfg = W.small_config(name="longpf", kind="prefill", dtype=W.BF16, batch=1, num_heads=4, num_kv_heads=2,
+                         head_dim=128, block_size=64, num_blocks=2400, ctx_lo=150100, ctx_hi=150100, q_len=100,
+                         seed=4300)
+    slopes = np.array([0.5, 0.0, 2.0 ** -10, 2.0 ** -16], np.float32)
+    case = W.make_case(cfg, slopes=slopes)
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens, case.slopes,
+                               case.scale, case.dtype)
+    dev = U.DevCase(case)
+    dev.write_cache()
+    U.check_scaled(dev.prefill(), ref, W.BF16, "prefill behind 150 000 cached tokens")
+
+
 def lift_to_large_pool(dev, total_blocks):
     """Moves a DevCase's cache blocks to the top of a pool of ``total_blocks`` blocks (the rest is
     left uninitialised: no table names it), so that block offsets no longer fit 32 bits."""
