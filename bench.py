@@ -59,7 +59,7 @@ MEASURED_TRAFFIC_BYTES = {
     "C5|e4m3":         (109_350_093, "profiles/paged_prefill_C5_variants.md"),        # 37 009.6, 32 768.0
     "C3|window=1024":  (148_694_733, "profiles/paged_decode_C3_window.md"),           # 70 019.7, 5 170.3
     "C3|window=4096":  (475_426_816, "profiles/paged_decode_C3_window.md"),           # 229 492.9, 5 298.2
-    "C5|window=512":   (100_956_774, "profiles/paged_prefill_C5_variants.md"),        # 32 911.2, 32 768.2
+    "C5|window=512":   (100_962_509, "profiles/paged_prefill_C5_variants.md"),        # 32 916.8, 32 768.0
     "C3|shared=2":     (429_063_475, "profiles/paged_decode_C3_shared_prefix.md"),    # 205 238.6, 8 530.1
     "C3|shared=4":     (476_824_166, "profiles/paged_decode_C3_shared_prefix.md"),    # 228 907.5, 7 833.6
     "C3-d64":          (321_057_690, "profiles/paged_decode_C3.md"),                  # 155 409.8, 2 713.3 (C3 shapes at head_dim 64)

@@ -150,7 +150,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
 {
     static_assert(WAVES == 4 || (WAVES == 8 && !WIN), "4 waves, or 8 without a window");
     constexpr int kPfWaves = WAVES, kPfRows = WAVES * 32;
-    constexpr bool REV = !WIN;                          // walk the key tiles from the diagonal backwards
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
     constexpr int kPfKRow = PfTile<D>::kKRow, kPfVRow = PfTile<D>::kVRow;
@@ -173,7 +172,6 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     // fall with the head number in every usual recipe, so the units are taken from the last KV head
     // down (a wrong guess costs nothing but the order).  Consecutive units, which then share a KV
     // head, are dealt to different XCDs (rotation by the row of eight).
-    // (with a window all workgroups are about equally long, and the plain unit order is kept)
     const int xcd = blockIdx.x & 7, w = blockIdx.x >> 3;
     const int Hq = p.num_heads, Hkv = p.num_kv_heads, bs = p.block_size;
     const int bs_shift = __builtin_ctz(bs);
@@ -181,11 +179,11 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     const int G = Hq / Hkv, chunks = G / GH;
     const int units_per_seq = Hkv * chunks;
     // (without slopes nothing is skipped and only the query tile decides the length: query tiles first)
-    const bool by_head = !WIN && p.slopes != nullptr;
+    const bool by_head = p.slopes != nullptr;
     const int units8 = (p.units + 7) >> 3;
-    const int urow = WIN || by_head ? w / p.q_tiles : w % units8;
-    const int qt = WIN ? w % p.q_tiles : p.q_tiles - 1 - (by_head ? w % p.q_tiles : w / units8);
-    const int ui = urow * 8 + (WIN ? xcd : (xcd - urow) & 7);
+    const int urow = by_head ? w / p.q_tiles : w % units8;
+    const int qt = p.q_tiles - 1 - (by_head ? w % p.q_tiles : w / units8);
+    const int ui = urow * 8 + ((xcd - urow) & 7);
     if (ui >= p.units) return;
     const int b = by_head ? ui % p.num_seqs : ui / units_per_seq;
     const int gu = by_head ? units_per_seq - 1 - ui / p.num_seqs : ui - b * units_per_seq;
@@ -305,7 +303,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     // the i-th tile of the walk (i past the end: the last one again)
     auto tile_of = [&](int i) __attribute__((always_inline)) {
         const int ic = min(i, nt - 1);
-        return REV ? last_tile - ic : kt0 + ic;
+        return last_tile - ic;                                    // from the diagonal backwards
     };
     auto load_blk = [&](int i) __attribute__((always_inline)) {
         // the keys of a group share a block (groups are aligned, clamping keeps the block)
@@ -361,7 +359,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         return st;
     };
     // kt: the tile's number along the context; buf: its number in the walk (LDS buffer buf % 2)
-    auto softmax_pv = [&](int kt, int buf, bool first_of_walk, f32x16 st, auto masked) __attribute__((always_inline)) {
+    auto softmax_pv = [&](int kt, int buf, f32x16 st, auto masked) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked)::value;
         // ---- bias, causal mask, lazily referenced exponentials (eq. (3), (4)) --------------------
         // x = score - reference, formed directly: st*scale2 + slope2*key + (-slope2*pos - m_ref)
@@ -381,17 +379,16 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         float mx = x[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) mx = fmaxf(mx, x[e]);
-        if constexpr (REV) {
+        {
             // Walking backwards, the weights of a tile can be judged against what is already summed:
             // below 2^kPfSkipLog2 of the row's sum (this lane's half of it, which is no more) for
             // every row of the wave, the tile changes no bit that the accumulators keep.
             const float room = __builtin_amdgcn_logf(lsum) + kPfSkipLog2;        // log2; -inf before the row's first key
             if (__builtin_amdgcn_ballot_w64(mx > room) == 0) return;
         }
-        // Has the row seen a key yet?  Walking forwards without a window every row sees key 0 in the
-        // first tile, so there the answer is wave-uniform; with a window, or walking backwards from the
-        // diagonal, a row's first visible key may lie in a later tile of the walk.
-        const bool first = (WIN || REV) ? !started : first_of_walk;
+        // Has the row seen a key yet?  Walking backwards from the diagonal, a row's first visible key
+        // may lie in a later tile of the walk than another row's.
+        const bool first = !started;
         if (__builtin_amdgcn_ballot_w64(first || mx > PfSoftmax<DT>::kThreshold) != 0) {
             mx = fmaxf(mx, __shfl_xor(mx, 32));                  // the row's keys live in 2 lanes (h2)
             // The first keys a row sees put its reference kHeadroom above their maximum, wherever
@@ -401,7 +398,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
             const float delta = first ? (sees ? mx + PfSoftmax<DT>::kHeadroom : 0.f)
                                       : fmaxf(mx + PfSoftmax<DT>::kHeadroom, 0.f);
             const float alpha = first ? 1.f : fast_exp2(-delta);
-            if (WIN || REV) started = started || sees;
+            started = started || sees;
             m_ref += delta;
             lsum *= alpha;
 #pragma unroll
@@ -484,7 +481,7 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     f32x16 st_other;
     auto one_tile = [&](int j, const f32x16& st_cur, f32x16& st_ahead, auto masked) __attribute__((always_inline)) {
         st_ahead = scores(j + 1);
-        softmax_pv(REV ? last_tile - j : kt0 + j, j, j == 0, st_cur, masked);
+        softmax_pv(last_tile - j, j, st_cur, masked);
         store_tile(stage, j + 1 + l_ahead);
         fetch_tile(stage, j + 2 + l_ahead);
         __syncthreads();
@@ -503,15 +500,11 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     };
     const int cut_end = max(kt0, min(n_window_cut, n_unmasked));   // tiles cut by some row's window start
     const int plain_end = max(cut_end, n_unmasked);                // tiles no mask touches
-    if constexpr (REV) {
-        // from the diagonal backwards: the tiles the causal mask cuts come first
-        run_tiles(0, ntiles - plain_end, std::true_type{});
-        run_tiles(ntiles - plain_end, nt, std::false_type{});
-    } else {
-        run_tiles(0, cut_end - kt0, std::true_type{});
-        run_tiles(cut_end - kt0, plain_end - kt0, std::false_type{});
-        run_tiles(plain_end - kt0, nt, std::true_type{});
-    }
+    // from the diagonal backwards: the tiles the causal mask cuts come first, those that some
+    // row's window start cuts (if there is a window) last
+    run_tiles(0, ntiles - plain_end, std::true_type{});
+    run_tiles(ntiles - plain_end, ntiles - cut_end, std::false_type{});
+    run_tiles(ntiles - cut_end, nt, std::true_type{});
 
     // ---- normalise and write: this lane holds dims 32db + 8i + 4h2 + (0..3) of its row -----------
     uint16_t* __restrict__ op = static_cast<uint16_t*>(p.out);
