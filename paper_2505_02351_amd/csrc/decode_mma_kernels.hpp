@@ -1,5 +1,7 @@
-// Paged decode attention for head_dim 128: the fast path (any group size up to 16 heads per
-// workgroup).
+// Paged decode attention for head_dim 128, unsplit: one workgroup walks the whole context of one
+// (sequence, KV head [x head chunk]), any group size up to 16 heads per workgroup.  It runs when
+// the context is too short to be worth splitting or the caller forbids the split; every split
+// runs on the equal-work kernel (decode_flat_kernels.hpp), which took this kernel's tile loop.
 //
 // Decode reads every K/V byte once and does G multiply-adds per byte; on MI355X that is still
 // HBM-bound only if the arithmetic stays off the critical path, and the vector ALU alone
