@@ -385,20 +385,23 @@ __global__ __launch_bounds__(kDecodeWaves * 64, KV8 ? OPTGQA_FLAT_WGS_PER_CU_KV8
         return s;
     };
     // The tile's bytes into operand order: no branches, rows clamped.
+    // (lane offsets are unsigned 32-bit on top of the tile's wave-uniform address, so that the loads
+    // take that address from scalar registers and no 64-bit vector arithmetic is spent on them)
     auto load_tile = [&](Tile& Tl, const TileSrc& s) __attribute__((always_inline)) {
-        const unsigned char* ka = s.k + min(j16, s.last_row) * (D * ES) + 16 * hg;
+        const uint32_t last = (uint32_t)s.last_row;
+        const uint32_t ko = min((uint32_t)j16, last) * (uint32_t)(D * ES) + 16u * (uint32_t)hg;
         if constexpr (KV8) {
 #pragma unroll
-            for (int j = 0; j < D / 64; ++j) Tl.k[j] = stream_load16(ka + 64 * j);
+            for (int j = 0; j < D / 64; ++j) Tl.k[j] = stream_load16(s.k + (ko + 64u * j));
 #pragma unroll
             for (int r = 0; r < NVL; ++r)
-                Tl.v[r] = stream_load8(s.v + min(RPL * r + vrow0, s.last_row) * D + 8 * vcol);
+                Tl.v[r] = stream_load8(s.v + (min((uint32_t)(RPL * r + vrow0), last) * (uint32_t)D + 8u * (uint32_t)vcol));
         } else {
 #pragma unroll
-            for (int i = 0; i < NQ; ++i) Tl.k[i] = stream_load16(ka + 64 * i);
+            for (int i = 0; i < NQ; ++i) Tl.k[i] = stream_load16(s.k + (ko + 64u * i));
 #pragma unroll
             for (int r = 0; r < NVL; ++r)
-                Tl.v[r] = stream_load16(s.v + min(RPL * r + vrow0, s.last_row) * (D * 2) + 16 * vcol);
+                Tl.v[r] = stream_load16(s.v + (min((uint32_t)(RPL * r + vrow0), last) * (uint32_t)(D * 2) + 16u * (uint32_t)vcol));
         }
     };
     // B operand of the score MFMAs for segment (sg, yy) - lane (column j16, k-slab hg) holds dims
