@@ -88,6 +88,9 @@ def parse():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--partition-size", type=int, default=None,
                     help="override the workload's partition size (0 = library chooses, -1 = never split)")
+    ap.add_argument("--no-alibi", action="store_true",
+                    help="run the workload without ALiBi slopes (plain causal attention; the workload is then named "
+                         "<workload>-noalibi: a variant - the prefill kernel can then drop no key tile)")
     ap.add_argument("--head-dim", type=int, choices=[64, 128], default=None,
                     help="run the workload's shapes at this head_dim instead of its own (the workload is then "
                          "named <workload>-d<head_dim>: a variant, not one of the configured workloads)")
@@ -265,7 +268,12 @@ def main():
         if args.head_dim is not None and args.head_dim != cfg.head_dim:
             import dataclasses
             cfg = dataclasses.replace(cfg, head_dim=args.head_dim, name=f"{cfg.name}-d{args.head_dim}")
+        if args.no_alibi:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, name=f"{cfg.name}-noalibi")
         case = W.make_case(cfg)
+        if args.no_alibi:
+            case.slopes = None
         shared_tokens = 0
         if args.shared_prefix > 1:
             assert cfg.kind == "decode", "--shared-prefix applies to decode workloads"

@@ -312,7 +312,9 @@ size_t optgqa_paged_attention_workspace_bytes(int num_seqs, int num_heads, int n
  * n_b = cu_q_lens[b+1] - cu_q_lens[b] new query tokens whose K/V are already in the cache;
  * query i sits at position pos = context_lens[b] - n_b + i, sees keys 0..pos, and gets the
  * bias alibi_slopes[h] * (j - pos).  QK^T and PV run as bf16/fp16 MFMA contractions with
- * fp32 accumulation; the softmax weights are rounded to dtype before the PV product.  Keys are
+ * fp32 accumulation; the softmax weights enter the PV product as 2-byte values (fp16: one
+ * rounding, the row sum taken over the rounded weights; bf16: a bf16 head plus a bf16 tail, two
+ * contractions, so that the weights keep 16 significant bits).  Keys are
  * visited from the query's own position backwards; a 32-key tile in which every weight, for
  * every query row a wave holds, is below 2^-24 of that row's sum so far is dropped (less than
  * half an ulp of the fp32 sum per tile: with ALiBi slopes the far keys of steep heads).

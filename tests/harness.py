@@ -61,7 +61,7 @@ class DevCase:
         self.block_tables = torch.from_numpy(case.block_tables).to("cuda")
         self.context_lens = torch.from_numpy(case.context_lens).to("cuda")
         self.cu_q_lens = torch.from_numpy(case.cu_q_lens).to("cuda")
-        self.slopes = torch.from_numpy(case.slopes).to("cuda")
+        self.slopes = None if case.slopes is None else torch.from_numpy(case.slopes).to("cuda")
         self._guards = []
         g = Guarded(self.q.numel() * self.q.element_size())
         self._guards.append(("out", g))
