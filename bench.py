@@ -53,7 +53,8 @@ MEASURED_TRAFFIC_BYTES = {
     "C3-all8k":        (1_089_124_045, "profiles/paged_decode_C3_all8k.md"),          # 529 144.4, 5 308.9
     "C4":              (550_505_882, "profiles/paged_decode_C1_C2_C4.md"),            # 264 641.4, 8 320.6 (P = 512)
     "C4|partition=0":  (551_163_494, "profiles/paged_decode_C1_C2_C4.md"),            # 267 002.1, 4 241.4
-    "C5":              (151_277_670, "profiles/paged_prefill_C5.md"),                 # 57 481.5, 32 769.1
+    "C5":              (170_643_047, "profiles/paged_prefill_C5.md"),                 # 58 733.6, 49 176.4 (one-call step)
+    "C5|two-call":     (151_277_670, "profiles/paged_prefill_C5.md"),                 # 57 481.5, 32 769.1
     "C5-prompt":       (505_036_083, "profiles/paged_prefill_C5_variants.md"),        # 123 718.5, 245 762.3
     "C3|e4m3":         (331_807_642, "profiles/paged_decode_C3_e4m3.md"),             # 157 346.7, 9 337.5
     "C5|e4m3":         (109_350_093, "profiles/paged_prefill_C5_variants.md"),        # 37 009.6, 32 768.0
@@ -77,6 +78,9 @@ def traffic_key(args, workload: str) -> str:
         parts.append(f"window={args.window}")
     if args.shared_prefix > 1:
         parts.append(f"shared={args.shared_prefix}" + ("" if args.shared_prefix_kernel == "bundled" else ",plain"))
+    if args.prefill_calls == "two" and workload in ("C5", "C5-d64", "C5-noalibi") and args.kv_cache != "e4m3" \
+            and args.window <= 0:
+        parts.append("two-call")
     return "|".join(parts)
 
 
@@ -88,6 +92,9 @@ def parse():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--partition-size", type=int, default=None,
                     help="override the workload's partition size (0 = library chooses, -1 = never split)")
+    ap.add_argument("--prefill-calls", choices=["one", "two"], default="one",
+                    help="prefill workloads over 2-byte caches without a window: 'one' = optgqa_prefill_step (cache "
+                         "write inside the prefill kernel), 'two' = optgqa_reshape_and_cache + optgqa_paged_prefill")
     ap.add_argument("--no-alibi", action="store_true",
                     help="run the workload without ALiBi slopes (plain causal attention; the workload is then named "
                          "<workload>-noalibi: a variant - the prefill kernel can then drop no key tile)")
@@ -328,6 +335,9 @@ def main():
         prompt = "-prompt" in cfg.name       # whole prompts, caches empty: one call stores K/V and attends
         assert not (prompt and (e4m3 or window)), "the whole-prompt workload runs over 2-byte inputs, full causal mask"
 
+        # prefill over cached context, 2-byte caches, full causal mask: one call stores the new rows and attends
+        pf_one_call = not decode and not prompt and not e4m3 and not window and args.prefill_calls == "one"
+
         def step():
             if prompt:
                 G.prompt_prefill(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
@@ -353,6 +363,10 @@ def main():
             if one_call:
                 G.decode_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
                               dev.context_lens, dev.slopes, scale, max_ctx, ws, stream)
+                return
+            if pf_one_call:
+                G.prefill_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                               dev.context_lens, dev.cu_q_lens, dev.slopes, scale, case.max_q_len, stream)
                 return
             G.reshape_and_cache(dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.slot_mapping, stream)
             if decode:
@@ -454,7 +468,8 @@ def main():
             achieved = flops / (kernel_ms.mean() * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": traffic[0], "traffic_source": traffic[1],
-                        "kernel": "paged_prefill_mma_kernel" + (" (E4M3 caches)" if e4m3 else "")
+                        "kernel": ("paged_prefill_step_kernel (cache write inside)" if pf_one_call else "paged_prefill_mma_kernel")
+                                  + (" (E4M3 caches)" if e4m3 else "")
                                   + (" (K/V from the contiguous inputs, cache write fused)" if prompt else "")
                                   + (f" (window {window})" if window else ""),
                         "algorithmic_flops_per_launch": flops,
@@ -511,7 +526,7 @@ def main():
                        "num_kv_heads": cfg.num_kv_heads, "head_dim": cfg.head_dim, "block_size": cfg.block_size,
                        "context_len_range": [cfg.ctx_lo, cfg.ctx_hi], "sum_context_lens": int(case.context_lens.sum()),
                        "kv_bytes": kv_bytes, "partition_size": int(chosen_P), "num_blocks": cfg.num_blocks,
-                       "calls_per_step": 1 if one_call or prompt else 2,
+                       "calls_per_step": 1 if one_call or prompt or pf_one_call else 2,
                        "kv_cache": "e4m3, per-tensor scales" if e4m3 else case.dtype,
                        **({"window": window} if window else {}),
                        **({"shared_prefix_group": args.shared_prefix,

@@ -445,7 +445,8 @@ int optgqa_validate_shared_prefix_host(const int32_t *block_tables_host,
  *
  *   out, q          [T][num_heads][head_dim], dense
  *   k, v            [T][num_kv_heads][head_dim]; token t starts at element t * k_token_stride
- *                   (resp. v_token_stride): strides >= num_kv_heads * head_dim and multiples of 8
+ *                   (resp. v_token_stride): strides >= num_kv_heads * head_dim, multiples of 8,
+ *                   at most 2^30
  *   cu_seq_lens     [num_seqs + 1] int32, cu_seq_lens[0] = 0, T = cu_seq_lens[num_seqs]
  *   max_seq_len     an upper bound on the sequences' lengths (<= max_blocks_per_seq * block_size
  *                   when the caches are given)
@@ -457,6 +458,33 @@ int optgqa_prompt_prefill(void *out, const void *q, const void *k, const void *v
                           int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
                           int max_seq_len, int64_t k_token_stride, int64_t v_token_stride,
                           int dtype, void *stream);
+
+/*
+ * One prefill step as a single call (Alg. 1: store K, V into the caches, then the attention over the
+ * caches - what optgqa_decode_step is for decoding, for any number of new tokens per sequence).
+ * Sequence b appends n_b = cu_q_lens[b+1] - cu_q_lens[b] tokens after the
+ * context_lens[b] - n_b it already has in the cache (context_lens counts the new tokens): their
+ * K / V rows k_new[cu_q_lens[b] + i], v_new[...] go to positions context_lens[b] - n_b + i (slot
+ * block_tables[b][pos / block_size] * block_size + pos % block_size), and out is what
+ * optgqa_paged_prefill gives afterwards.  Same result, bit for bit in the caches AND in `out`, as
+ * optgqa_reshape_and_cache with that slot mapping followed by optgqa_paged_prefill - in one launch:
+ * keys before a sequence's first new position are read through the block table, the new ones
+ * from k_new / v_new, and the workgroups store the new rows on the side.  No row this call writes is
+ * read by it; rows of earlier tokens must be in the cache already.
+ *
+ *   k_new, v_new    [total_q_tokens][num_kv_heads][head_dim]; token t starts at element
+ *                   t * k_token_stride (resp. v_token_stride): strides >= num_kv_heads * head_dim,
+ *                   multiples of 8, at most 2^30
+ *   k_cache,v_cache modified in place (2-byte caches; n_b rows per sequence and KV head)
+ * All pointers device memory, 16-byte aligned.  Other arguments, the dropped key tiles, and errors
+ * as optgqa_paged_prefill.
+ */
+int optgqa_prefill_step(void *out, const void *q, const void *k_new, const void *v_new, void *k_cache,
+                        void *v_cache, const int32_t *block_tables, const int32_t *context_lens,
+                        const int32_t *cu_q_lens, const float *alibi_slopes, float scale, int num_seqs,
+                        int num_heads, int num_kv_heads, int head_dim, int block_size,
+                        int max_blocks_per_seq, int max_q_len, int64_t k_token_stride,
+                        int64_t v_token_stride, int dtype, void *stream);
 
 /*
  * Diagnostic: un-page the cache (Section III-A: pages are only a re-arrangement of the

@@ -114,6 +114,9 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.optgqa_prompt_prefill.restype = i32
     lib.optgqa_prompt_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
                                           i64, i64, i32, vp]
+    lib.optgqa_prefill_step.restype = i32
+    lib.optgqa_prefill_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, i32, i32,
+                                        i64, i64, i32, vp]
     lib.optgqa_stream_probe.restype = i32
     lib.optgqa_stream_probe.argtypes = [vp, vp, sz, vp, vp, i32, i32, vp, vp]
     lib.optgqa_gather_kv.restype = i32
@@ -720,6 +723,35 @@ def prompt_prefill(out: torch.Tensor, q: torch.Tensor, k: torch.Tensor, v: torch
                                    int(cu_seq_lens.shape[0]) - 1, Hq, Hkv, D, int(bs), mb, int(max_seq_len), ks, vs,
                                    _dtype_code(q), _stream(stream))
     _check(rc, "optgqa_prompt_prefill")
+
+
+def prefill_step(out: torch.Tensor, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                 k_cache: torch.Tensor, v_cache: torch.Tensor, block_tables: torch.Tensor,
+                 context_lens: torch.Tensor, cu_q_lens: torch.Tensor, alibi_slopes: Optional[torch.Tensor],
+                 scale: float, max_q_len: int, stream=None) -> None:
+    """optgqa_prefill_step: store the new tokens' K / V rows into the paged caches and attend over the
+    caches, in one launch."""
+    lib = load_library()
+    _typed(q, same=[("out", out), ("k_new", k_new), ("v_new", v_new), ("k_cache", k_cache), ("v_cache", v_cache)],
+           i32=[("block_tables", block_tables), ("context_lens", context_lens), ("cu_q_lens", cu_q_lens)],
+           f32=[("alibi_slopes", alibi_slopes)])
+    T, Hq, D = q.shape
+    NB, Hkv, bs, Dk = k_cache.shape
+    if (out.shape != q.shape or Dk != D or v_cache.shape != k_cache.shape or k_new.shape != (T, Hkv, D)
+            or v_new.shape != (T, Hkv, D) or cu_q_lens.shape[0] != context_lens.shape[0] + 1
+            or block_tables.shape[0] != context_lens.shape[0]):
+        raise ValueError("optgqa: shape mismatch between q, out, the new rows, the tables and the caches")
+    _dense(out, "out"), _dense(q, "q"), _dense(k_cache, "k_cache"), _dense(v_cache, "v_cache")
+    _dense(block_tables, "block_tables"), _dense(context_lens, "context_lens"), _dense(cu_q_lens, "cu_q_lens")
+    if T and (k_new.stride(-1) != 1 or k_new.stride(-2) != D or v_new.stride(-1) != 1 or v_new.stride(-2) != D):
+        raise ValueError("optgqa: k_new and v_new must be dense in their last two dims")
+    ks = int(k_new.stride(0)) if T else Hkv * D
+    vs = int(v_new.stride(0)) if T else Hkv * D
+    rc = lib.optgqa_prefill_step(_ptr(out), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                 _ptr(block_tables), _ptr(context_lens), _ptr(cu_q_lens), _ptr(alibi_slopes),
+                                 float(scale), int(context_lens.shape[0]), Hq, Hkv, D, int(bs),
+                                 int(block_tables.shape[1]), int(max_q_len), ks, vs, _dtype_code(q), _stream(stream))
+    _check(rc, "optgqa_prefill_step")
 
 
 def gather_kv(k_out: torch.Tensor, v_out: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,

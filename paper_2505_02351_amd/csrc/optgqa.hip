@@ -29,7 +29,7 @@ static __device__ __align__(256) unsigned char g_static_scratch[OPTGQA_STATIC_SC
 
 namespace {
 
-constexpr int kAbiVersion = 1;
+constexpr int kAbiVersion = 2;
 constexpr int kMinPartition = 256;        // tokens; smaller runs are dominated by the merge
 
 bool dtype_ok(int dt) { return dt == OPTGQA_F16 || dt == OPTGQA_BF16; }
@@ -388,6 +388,26 @@ int launch_prefill_mma(const PrefillParams& p, int head_dim, dim3 grid, int wave
     return launch_prefill_mma_d<DT, KV8, WIN, CONTIG, 128>(p, grid, waves, st);
 }
 
+// The one-call prefill step (cache write inside the prefill kernel).
+template <int DT, int D, int WAVES>
+int launch_prefill_step_w(const PrefillParams& p, dim3 grid, hipStream_t st)
+{
+    constexpr int kBytes = PfTile<D>::kLdsBytes;
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&paged_prefill_step_kernel<DT, D, WAVES>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+    if (attr != hipSuccess) return OPTGQA_ERR_LAUNCH;
+    return launch(paged_prefill_step_kernel<DT, D, WAVES>, grid, dim3(WAVES * 64), kBytes, st, p);
+}
+
+template <int DT>
+int launch_prefill_step(const PrefillParams& p, int head_dim, dim3 grid, int waves, hipStream_t st)
+{
+    if (head_dim == 64)
+        return waves == 8 ? launch_prefill_step_w<DT, 64, 8>(p, grid, st) : launch_prefill_step_w<DT, 64, 4>(p, grid, st);
+    return waves == 8 ? launch_prefill_step_w<DT, 128, 8>(p, grid, st) : launch_prefill_step_w<DT, 128, 4>(p, grid, st);
+}
+
 // The tiled prefill kernel carries the tile-invariant part of the ALiBi term inside the score
 // accumulator as slope / scale, so it cannot take a score scale of exactly zero.  Magnitudes
 // below 2^-64 (zero included) are evaluated as +-2^-64: the scores then differ from the exact
@@ -401,7 +421,7 @@ float prefill_scale2(float scale)
 
 // Tiled matrix-core prefill (head_dim 128 or 64).
 int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, int dtype, hipStream_t st,
-                   bool kv8 = false, bool contig = false)
+                   bool kv8 = false, bool contig = false, bool step = false)
 {
     if (head_dim != 128 && head_dim != 64) return OPTGQA_ERR_UNSUPPORTED;
     const int group = p.num_heads / p.num_kv_heads;
@@ -425,6 +445,11 @@ int launch_prefill(PrefillParams p, int num_seqs, int max_q_len, int head_dim, i
     const dim3 grid((unsigned)blocks);
     KernelEvents ev(st);
     const bool f16 = dtype == OPTGQA_F16;
+    if (step) {
+        if (kv8 || contig || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
+        return f16 ? launch_prefill_step<kF16>(p, head_dim, grid, waves, st)
+                   : launch_prefill_step<kBF16>(p, head_dim, grid, waves, st);
+    }
     if (contig) {
         if (kv8 || p.window > 0) return OPTGQA_ERR_UNSUPPORTED;
         return f16 ? launch_prefill_mma<kF16, false, false, true>(p, head_dim, grid, waves, st)
@@ -1074,7 +1099,9 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
     if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
     if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
     const int64_t row = (int64_t)num_kv_heads * head_dim;
-    if (k_token_stride < row || v_token_stride < row) return OPTGQA_ERR_SHAPE;
+    // (the kernel forms byte offsets between token rows in 32 bits)
+    if (k_token_stride < row || v_token_stride < row || k_token_stride > (1LL << 30) || v_token_stride > (1LL << 30))
+        return OPTGQA_ERR_SHAPE;
     if ((k_cache == nullptr) != (v_cache == nullptr)) return OPTGQA_ERR_NULL;
     const bool store = k_cache != nullptr;
     if (store) {
@@ -1113,6 +1140,56 @@ int optgqa_prompt_prefill(void* out, const void* q, const void* k, const void* v
     p.block_size = store ? block_size : 16;
     p.max_blocks_per_seq = store ? max_blocks_per_seq : 0;
     return launch_prefill(p, num_seqs, max_seq_len, head_dim, dtype, static_cast<hipStream_t>(stream), false, true);
+}
+
+int optgqa_prefill_step(void* out, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                        void* v_cache, const int32_t* block_tables, const int32_t* context_lens,
+                        const int32_t* cu_q_lens, const float* alibi_slopes, float scale, int num_seqs,
+                        int num_heads, int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                        int max_q_len, int64_t k_token_stride, int64_t v_token_stride, int dtype, void* stream)
+{
+    if (num_seqs < 0 || num_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || block_size <= 0 ||
+        max_blocks_per_seq <= 0 || max_q_len < 0)
+        return OPTGQA_ERR_SHAPE;
+    if (!std::isfinite(scale)) return OPTGQA_ERR_SHAPE;
+    if (num_heads % num_kv_heads) return OPTGQA_ERR_SHAPE;
+    const int64_t row = (int64_t)num_kv_heads * head_dim;
+    // (the kernel forms byte offsets between token rows in 32 bits)
+    if (k_token_stride < row || v_token_stride < row || k_token_stride > (1LL << 30) || v_token_stride > (1LL << 30))
+        return OPTGQA_ERR_SHAPE;
+    if (!dtype_ok(dtype) || !head_dim_ok(head_dim) || !block_size_ok(block_size)) return OPTGQA_ERR_UNSUPPORTED;
+    if (k_token_stride % 8 || v_token_stride % 8) return OPTGQA_ERR_UNSUPPORTED;   // rows move as 16-byte pieces
+    if (num_seqs == 0 || max_q_len == 0) return OPTGQA_OK;
+    if (!out || !q || !k_new || !v_new || !k_cache || !v_cache || !block_tables || !context_lens || !cu_q_lens)
+        return OPTGQA_ERR_NULL;
+    if (!aligned16(out) || !aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) ||
+        !aligned16(v_cache))
+        return OPTGQA_ERR_UNSUPPORTED;
+    if (num_seqs > 65535) return OPTGQA_ERR_SHAPE;
+    PrefillParams p;
+    p.out = out;
+    p.q = q;
+    p.k_cache = k_cache;
+    p.v_cache = v_cache;
+    p.block_tables = block_tables;
+    p.context_lens = context_lens;
+    p.cu_q_lens = cu_q_lens;
+    p.slopes = alibi_slopes;
+    p.scale2 = prefill_scale2(scale);
+    p.out_scale = 1.f;
+    p.k_scales = p.v_scales = nullptr;
+    p.window = 0;
+    p.k_in = k_new;
+    p.v_in = v_new;
+    p.k_in_stride = k_token_stride;
+    p.v_in_stride = v_token_stride;
+    p.k_cache_w = k_cache;
+    p.v_cache_w = v_cache;
+    p.num_heads = num_heads;
+    p.num_kv_heads = num_kv_heads;
+    p.block_size = block_size;
+    p.max_blocks_per_seq = max_blocks_per_seq;
+    return launch_prefill(p, num_seqs, max_q_len, head_dim, dtype, static_cast<hipStream_t>(stream), false, false, true);
 }
 
 int optgqa_stream_probe(const void* k_pool, const void* v_pool, size_t pool_bytes,

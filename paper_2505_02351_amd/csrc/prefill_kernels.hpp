@@ -145,12 +145,21 @@ template <> struct PfSoftmax<kBF16> {
 // through the block table.  With k_cache_w / v_cache_w set, the workgroups of a KV head's first
 // head chunk also store their own tokens' K / V rows into the paged caches (Alg. 1, the
 // cache-store step), so the step needs no separate cache-write launch.
-template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128, int WAVES = 4>
-__global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
+//
+// STEP: one prefill step over a cache that already holds the earlier tokens (Alg. 1: the cache-store
+// step, then the attention): the n_b new tokens of sequence b have their K / V rows in k_in / v_in
+// (token cu_q_lens[b] + i = position context_lens[b] - n_b + i) and NOT yet in the cache.  A key
+// below the first new position is fetched through the block table, a key at or above it from the
+// inputs - chosen per key, both addresses are always valid - and, as with CONTIG, the workgroups of
+// a KV head's first head chunk store their own tokens' rows into the caches.  No workgroup reads
+// a cache row that this launch writes.
+template <int DT, bool KV8, bool WIN, bool CONTIG, int D, int WAVES, bool STEP>
+__device__ __forceinline__ void prefill_body(const PrefillParams& p)
 {
     static_assert(WAVES == 4 || (WAVES == 8 && !WIN), "4 waves, or 8 without a window");
     constexpr int kPfWaves = WAVES, kPfRows = WAVES * 32;
     static_assert(!(CONTIG && (KV8 || WIN)), "the whole-prompt variant reads 2-byte inputs, full causal mask");
+    static_assert(!(STEP && (KV8 || WIN || CONTIG)), "the one-call step runs over 2-byte caches, full causal mask");
     static_assert(D == 128 || D == 64, "head_dim 64 or 128");
     constexpr int kPfKRow = PfTile<D>::kKRow, kPfVRow = PfTile<D>::kVRow;
     constexpr int kQ = D / 16;                          // score MFMAs per tile (16 dims each)
@@ -222,16 +231,42 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     const int32_t* __restrict__ table = p.block_tables + (int64_t)b * p.max_blocks_per_seq;
     const int64_t block_stride = (int64_t)Hkv * bs * D;
 
-    if (CONTIG && p.k_cache_w && gu == g * chunks) {
-        // store this workgroup's own tokens' K / V rows of head g (16-byte pieces: kCPR per row and tensor)
-        const int ntok = min(tokens_per_wg, n_b - tq0);
-        for (int idx = threadIdx.x; idx < ntok * 2 * kCPR; idx += kPfWaves * 64) {
-            const int tok = tq0 + idx / (2 * kCPR), is_v = (idx / kCPR) & 1, piece = idx % kCPR;
-            const int blk = table[tok >> bs_shift];
-            const int64_t dst = blk * block_stride + (int64_t)g * bs * D + (int64_t)(tok & (bs - 1)) * D + 8 * piece;
-            const unsigned char* src = (is_v ? vc + (int64_t)tok * p.v_in_stride * 2 : kc + (int64_t)tok * p.k_in_stride * 2) + 16 * piece;
-            uint16_t* dstp = (is_v ? static_cast<uint16_t*>(p.v_cache_w) : static_cast<uint16_t*>(p.k_cache_w)) + dst;
-            *reinterpret_cast<uint4*>(dstp) = *reinterpret_cast<const uint4*>(src);
+    // STEP: the sequence's first new token, KV head g, in the inputs
+    const unsigned char* __restrict__ kin = !STEP ? kc
+        : static_cast<const unsigned char*>(p.k_in) + (cu0 * p.k_in_stride + (int64_t)g * D) * 2;
+    const unsigned char* __restrict__ vin = !STEP ? vc
+        : static_cast<const unsigned char*>(p.v_in) + (cu0 * p.v_in_stride + (int64_t)g * D) * 2;
+
+    // CONTIG / STEP: this workgroup's own tokens' K / V rows of head g go into the caches, as 16-byte
+    // pieces (kCPR per row and tensor; piece idx = ((token * 2 + is_v) * kCPR + column piece)).  The
+    // first kOwnBatch pieces of every thread are loaded here, in front of the first tile fetch, and
+    // stored once that tile has landed - one memory latency shared with the fetch instead of a
+    // load-then-store loop of its own in front of or behind the walk (each workgroup has the CU to
+    // itself, so such a loop is not overlapped by anything: measured 2 us per workgroup round);
+    // whatever is left (more than 64 tokens per workgroup) goes out behind the output.
+    constexpr int kOwnBatch = 4;
+    typedef uint32_t own_u32x4 __attribute__((ext_vector_type(4)));
+    const int n_own = ((CONTIG || STEP) && p.k_cache_w && gu == g * chunks) ? min(tokens_per_wg, n_b - tq0) * 2 * kCPR : 0;
+    auto own_src = [&](int idx) __attribute__((always_inline)) {
+        const int ti = tq0 + idx / (2 * kCPR), is_v = (idx / kCPR) & 1, piece = idx % kCPR;
+        return (is_v ? vin + (int64_t)ti * p.v_in_stride * 2 : kin + (int64_t)ti * p.k_in_stride * 2) + 16 * piece;
+    };
+    auto own_blk_of = [&](int idx) __attribute__((always_inline)) {
+        return table[(pos0 + tq0 + idx / (2 * kCPR)) >> bs_shift];   // position in the sequence (CONTIG: pos0 == 0)
+    };
+    auto own_dst = [&](int idx, int blk) __attribute__((always_inline)) {
+        const int tok = pos0 + tq0 + idx / (2 * kCPR), is_v = (idx / kCPR) & 1, piece = idx % kCPR;
+        const int64_t dst = blk * block_stride + (int64_t)g * bs * D + (int64_t)(tok & (bs - 1)) * D + 8 * piece;
+        return reinterpret_cast<own_u32x4*>((is_v ? static_cast<uint16_t*>(p.v_cache_w) : static_cast<uint16_t*>(p.k_cache_w)) + dst);
+    };
+    own_u32x4 own[kOwnBatch];
+    int own_blk[kOwnBatch];
+    if (n_own > 0) {                                             // workgroup-uniform
+#pragma unroll
+        for (int c = 0; c < kOwnBatch; ++c) {
+            const int ic = min((int)threadIdx.x + c * kPfWaves * 64, n_own - 1);
+            own[c] = *reinterpret_cast<const own_u32x4*>(own_src(ic));
+            own_blk[c] = own_blk_of(ic);
         }
     }
 
@@ -287,6 +322,9 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     const int l_group = ld / kCPR, l_chunk = ld % kCPR;          // keys kKPT*group .. , dims 8*chunk ..
     const unsigned char* __restrict__ l_src = k_loader ? kc : vc;
     const int64_t l_row = CONTIG ? (k_loader ? p.k_in_stride : p.v_in_stride) * 2 : D * ES;   // bytes from key to key
+    // STEP: this lane's column piece of the first new token, and the inputs' bytes from token to token
+    const unsigned char* const l_in = (k_loader ? kin : vin) + 8 * l_chunk * 2;
+    const uint32_t l_in_row = STEP ? (uint32_t)((k_loader ? p.k_in_stride : p.v_in_stride) * 2) : 0u;
     const int l_pitch = k_loader ? kPfKRow : kPfVRow;
     const int l_dst = kKPT * l_group * l_pitch + 8 * l_chunk;
     // One register stage: while tile t is computed, the loader's next tile sits in the other LDS
@@ -324,9 +362,22 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         const unsigned char* base;
         if (CONTIG) base = l_lane + (uint64_t)(uint32_t)key0 * (uint32_t)l_row;
         else base = l_lane + (uint64_t)(uint32_t)blk_next * l_blk_bytes + (uint32_t)((key0 & (bs - 1)) * (D * ES));
+        // STEP: a tile that ends below the first new position is all cache (the plain path: most
+        // tiles); otherwise the keys from that position on come from the inputs, chosen per key (the
+        // clamped key, so that rows past the last visible key re-read it from wherever it lives)
+        if (STEP && tile_of(i) * kPfKeys + kPfKeys > pos0) {     // workgroup-uniform
 #pragma unroll
-        for (int j = 0; j < kKPT; ++j)
-            stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
+            for (int j = 0; j < kKPT; ++j) {
+                const unsigned char* a = base + (uint32_t)(min(j, rmax) * (D * ES));
+                const int nk = key0 + min(j, rmax) - pos0;
+                if (nk >= 0) a = l_in + (uint64_t)(uint32_t)nk * l_in_row;
+                stage[j] = *reinterpret_cast<const StageT*>(a);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kKPT; ++j)
+                stage[j] = *reinterpret_cast<const StageT*>(base + (uint32_t)(min(j, rmax) * (CONTIG ? (int)l_row : D * ES)));
+        }
         blk_next = load_blk(i + 1);
     };
     // A tile's place in LDS: the j-th tile of the walk sits in buffer j % 2.
@@ -458,6 +509,13 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
     // on their way to registers.  Prologue:
     fetch_tile(stage, 0);
     store_tile(stage, 0);
+    if (n_own > 0) {                                             // the rows loaded at the top have landed with tile 0
+#pragma unroll
+        for (int c = 0; c < kOwnBatch; ++c) {
+            const int idx = (int)threadIdx.x + c * kPfWaves * 64;
+            if (idx < n_own) *own_dst(idx, own_blk[c]) = own[c];
+        }
+    }
     if (k_loader) {                                              // wave-uniform
         fetch_tile(stage, 1);
         store_tile(stage, 1);
@@ -516,12 +574,29 @@ __global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_pr
         for (int db = 0; db < kDB; ++db)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                uint2 packed;
+                u32x2 packed;
                 packed.x = narrow2<DT>(acc[db][4 * i] * inv, acc[db][4 * i + 1] * inv);
                 packed.y = narrow2<DT>(acc[db][4 * i + 2] * inv, acc[db][4 * i + 3] * inv);
-                *reinterpret_cast<uint2*>(op + out_off + 32 * db + 8 * i + 4 * h2) = packed;
+                *reinterpret_cast<u32x2*>(op + out_off + 32 * db + 8 * i + 4 * h2) = packed;
             }
     }
+    // own rows beyond the first batch (stores inside the walk would delay the tile loads behind
+    // them - loads and stores complete in issue order; measured twice as costly as this)
+    for (int idx = threadIdx.x + kOwnBatch * kPfWaves * 64; idx < n_own; idx += kPfWaves * 64)
+        *own_dst(idx, own_blk_of(idx)) = *reinterpret_cast<const own_u32x4*>(own_src(idx));
+}
+
+template <int DT, bool KV8 = false, bool WIN = false, bool CONTIG = false, int D = 128, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_mma_kernel(const PrefillParams p)
+{
+    prefill_body<DT, KV8, WIN, CONTIG, D, WAVES, false>(p);
+}
+
+// cache write + prefill over the cached context in one launch (see STEP above)
+template <int DT, int D = 128, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64, OPTGQA_PF_WAVES_PER_SIMD) void paged_prefill_step_kernel(const PrefillParams p)
+{
+    prefill_body<DT, false, false, false, D, WAVES, true>(p);
 }
 
 }  // namespace optgqa

@@ -158,6 +158,16 @@ class DevCase:
         self.check_canaries()
         return to_host(self.out)
 
+    def prefill_step(self, k_new=None, v_new=None):
+        """Cache write + prefill in one call (the caches must not hold the new tokens yet)."""
+        self.out.fill_(float("nan"))
+        G.prefill_step(self.out, self.q, self.k_new if k_new is None else k_new, self.v_new if v_new is None else v_new,
+                       self.k_cache, self.v_cache, self.block_tables, self.context_lens, self.cu_q_lens, self.slopes,
+                       float(self.case.scale), self.case.max_q_len)
+        torch.cuda.synchronize()
+        self.check_canaries()
+        return to_host(self.out)
+
     def prefill(self):
         self.out.fill_(float("nan"))
         G.paged_prefill(self.out, self.q, self.k_cache, self.v_cache, self.block_tables, self.context_lens,

@@ -137,6 +137,17 @@ def test_more_entry_points_reject_bad_arguments_before_any_launch(G):
     assert f(kc=one) == -1                                   # one cache without the other
     assert f(kc=one, vc=one) == -1                           # caches without block tables
     assert f(kc=one, vc=one, bt=one, L=8 * 16 + 1) == -2     # prompts longer than the tables can address
+    # one-call prefill step: new rows and caches both required, strides checked like the prompt call's
+    ps = lib.optgqa_prefill_step
+    f = lambda kn=one, kc=one, D=128, ks=256, vs=256, cu=one, B=2, mq=4, scale=0.1: ps(
+        one, one, kn, one, kc, one, one, one, cu, None, scale, B, 8, 2, D, 16, 8, mq, ks, vs, 0, None)
+    assert f(kn=None) == -1 and f(kc=None) == -1 and f(cu=None) == -1
+    assert f(ks=100) == -2 and f(ks=260) == -3 and f(vs=(1 << 30) + 8) == -2 and f(D=96) == -3
+    assert f(scale=float("nan")) == -2 and f(kn=ctypes.c_void_p(18)) == -3
+    assert f(B=0) == 0 and f(mq=0) == 0
+    pp = lib.optgqa_prompt_prefill
+    assert pp(one, one, one, one, None, None, None, one, None, 0.1, 2, 8, 2, 128, 16, 8, 32, (1 << 30) + 8, 256, 0,
+              None) == -2
     # streaming probe: the host copy of the tile list is checked against the pool size
     p = lib.optgqa_stream_probe
     lst = np.array([0, 1, 2, 3, 4, 5, 6, 7], np.int32)
@@ -256,6 +267,8 @@ def test_binding_refuses_wrong_element_types_and_host_tensors(G):
     refused(TypeError, G.decode_step_window, out, q, kv, kv, c, c.bfloat16(), bt, cl, sl, 0.1, 4, 32, ws)
     refused(TypeError, G.paged_prefill_window, out, q, c, c, bt.long(), cl, cu, sl, 0.1, 4, 1)
     refused(TypeError, G.prompt_prefill, out, q, kv, kv, None, None, None, cu.long(), sl, 0.1, 2)
+    refused(TypeError, G.prefill_step, out, q, kv, kv, c, c, bt, cl.long(), cu, sl, 0.1, 1)
+    refused(TypeError, G.prefill_step, out, q, kv.bfloat16(), kv, c, c, bt, cl, cu, sl, 0.1, 1)
     refused(TypeError, G.gather_kv, torch.zeros(2, 32, 2, 64, dtype=torch.bfloat16),
             torch.zeros(2, 32, 2, 64, dtype=torch.bfloat16), c, c, bt, cl)
     # correctly typed tensors in host memory
@@ -264,6 +277,7 @@ def test_binding_refuses_wrong_element_types_and_host_tensors(G):
     refused(ValueError, G.decode_step, out, q, kv, kv, c, c, bt, cl, sl, 0.1, 32, None)
     refused(ValueError, G.paged_prefill, out, q, c, c, bt, cl, cu, sl, 0.1, 1)
     refused(ValueError, G.prompt_prefill, out, q, kv, kv, None, None, None, cu, sl, 0.1, 2)
+    refused(ValueError, G.prefill_step, out, q, kv, kv, c, c, bt, cl, cu, sl, 0.1, 1)
 
 
 def test_non_finite_scale_is_refused(G):

@@ -1663,6 +1663,124 @@ def test_prefill_sweep(U, oracle, i):
     U.check_scaled(got, ref, dtype, f"prefill {i}")
 
 
+@pytest.mark.parametrize("i", range(len(PF)))
+def test_prefill_step_sweep(U, oracle, i):
+    """Cache write + prefill in one launch: caches and output bit for bit what the two calls give
+    (the new tokens' rows are NaN patterns in the cache until the call stores them, so a key read
+    from the wrong place would show), and both against the oracle."""
+    dtype, Hq, Hkv, D, bs, B, lo, hi, q_len = PF[i]
+    cfg = W.small_config(name=f"pfs{i}", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                         head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5, ctx_lo=lo,
+                         ctx_hi=hi, q_len=q_len, seed=500 + i)
+    case = W.make_case(cfg)
+    two = U.DevCase(case)
+    two.write_cache()
+    want = two.prefill()
+    one = U.DevCase(case)
+    got = one.prefill_step()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(one.k_cache), kc) and np.array_equal(U.to_host(one.v_cache), vc)
+    assert np.array_equal(U.to_host(two.k_cache), kc) and np.array_equal(U.to_host(two.v_cache), vc)
+    assert np.array_equal(got, want), f"prefill step {i}: output differs from write + prefill"
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, dtype)
+    U.check_scaled(got, ref, dtype, f"prefill step {i}")
+
+
+def test_prefill_step_strided_rows_and_chunks(U, oracle):
+    """New rows handed over with a token stride, and a prompt fed in three chunks of uneven size
+    (each step reads what the earlier ones stored): the caches end up as the oracle fills them and
+    every chunk's output matches the oracle's for the same positions."""
+    import torch
+    import paper_2505_02351_amd as G
+    for dtype, D in ((W.BF16, 128), (W.F16, 64)):
+        Hq, Hkv, bs, B = 8, 2, 16, 3
+        cfg = W.small_config(name="pfs_chunks", kind="prefill", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv,
+                             head_dim=D, block_size=bs, num_blocks=B * 25 + 3, ctx_lo=150, ctx_hi=390, q_len=390,
+                             seed=911)
+        case = W.make_case(cfg)                       # whole prompts new: lengths L_b, positions 0 .. L_b - 1
+        kc, vc = oracle_filled(oracle, case)
+        ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                   case.slopes, case.scale, dtype)
+        dev = U.DevCase(case)
+        L = case.context_lens.astype(np.int64)
+        cu = case.cu_q_lens.astype(np.int64)
+        assert np.array_equal(cu[1:] - cu[:-1], L)
+        # strided copies of the new rows (token stride 1.5 rows)
+        row = Hkv * D
+        kbig = torch.zeros((int(cu[-1]), row + row // 2), dtype=dev.k_new.dtype, device="cuda")
+        vbig = torch.zeros_like(kbig)
+        kbig[:, :row] = dev.k_new.view(-1, row)
+        vbig[:, :row] = dev.v_new.view(-1, row)
+        done = np.zeros(B, dtype=np.int64)
+        out_all = np.zeros_like(U.to_host(dev.out))
+        for frac in (0.37, 0.8, 1.0):
+            upto = np.maximum(np.minimum((L * frac).astype(np.int64) | 1, L), done)   # odd chunk ends, except the last
+            if frac == 1.0:
+                upto = L
+            n = upto - done
+            idx = np.concatenate([np.arange(cu[b] + done[b], cu[b] + upto[b]) for b in range(B)]).astype(np.int64)
+            sel = torch.from_numpy(idx).cuda()
+            cu_chunk = torch.from_numpy(np.concatenate([[0], np.cumsum(n)]).astype(np.int32)).cuda()
+            ctx = torch.from_numpy(upto.astype(np.int32)).cuda()
+            q = dev.q[sel].contiguous()
+            out = torch.full_like(q, float("nan"))
+            kn = kbig[sel].contiguous()[:, :row].view(-1, Hkv, D)       # rows with a token stride of 1.5 rows
+            vn = vbig[sel].contiguous()[:, :row].view(-1, Hkv, D)
+            assert kn.stride(0) == row + row // 2
+            G.prefill_step(out, q, kn, vn, dev.k_cache, dev.v_cache, dev.block_tables, ctx, cu_chunk, dev.slopes,
+                           float(case.scale), int(n.max()))
+            torch.cuda.synchronize()
+            out_all[idx] = U.to_host(out)
+            done = upto
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+        U.check_scaled(out_all, ref, dtype, f"chunked prefill steps, head_dim {D}")
+
+
+def test_prefill_step_workload_full(U, oracle):
+    """C5 at full size through the one-call step: caches bit-exact, output bit for bit the two-call
+    path's and every row against the oracle."""
+    case = workload_case("C5")
+    two = U.DevCase(case)
+    two.write_cache()
+    want = two.prefill()
+    del two
+    dev = U.DevCase(case)
+    got = dev.prefill_step()
+    kc, vc = oracle_filled(oracle, case)
+    assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc)
+    assert np.array_equal(got, want)
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, case.dtype)
+    U.check_scaled(got, ref, case.dtype, "C5, one-call step", max_exempt=WORKLOAD_EXEMPT)
+
+
+def test_prefill_step_rejects_what_it_cannot_do(U):
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="pfs_rej", kind="prefill", dtype=W.BF16, batch=2, num_heads=8, num_kv_heads=2,
+                         head_dim=128, block_size=16, num_blocks=40, ctx_lo=40, ctx_hi=100, q_len=20, seed=77)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    lib = G.load_library()
+    args = lambda **kw: [kw.get(k, v) for k, v in dict(
+        out=dev.out.data_ptr(), q=dev.q.data_ptr(), k_new=dev.k_new.data_ptr(), v_new=dev.v_new.data_ptr(),
+        k_cache=dev.k_cache.data_ptr(), v_cache=dev.v_cache.data_ptr(), bt=dev.block_tables.data_ptr(),
+        cl=dev.context_lens.data_ptr(), cu=dev.cu_q_lens.data_ptr(), sl=dev.slopes.data_ptr(), scale=0.1, B=2, Hq=8,
+        Hkv=2, D=128, bs=16, mb=int(dev.block_tables.shape[1]), mq=20, ks=256, vs=256, dt=1, st=None).items()]
+    assert lib.optgqa_prefill_step(*args(k_new=None)) == -1
+    assert lib.optgqa_prefill_step(*args(k_cache=None)) == -1
+    assert lib.optgqa_prefill_step(*args(ks=255)) == -2          # rows overlap
+    assert lib.optgqa_prefill_step(*args(ks=260)) == -3          # not a multiple of 8 elements
+    assert lib.optgqa_prefill_step(*args(vs=(1 << 30) + 8)) == -2
+    assert lib.optgqa_prefill_step(*args(D=96)) == -3
+    assert lib.optgqa_prefill_step(*args(scale=float("inf"))) == -2
+    assert lib.optgqa_prefill_step(*args(k_new=dev.k_new.data_ptr() + 2)) == -3
+    assert lib.optgqa_prefill_step(*args(mq=0)) == 0             # nothing to do
+    torch.cuda.synchronize()
+    assert np.array_equal(U.to_host(dev.k_cache), case.k_cache)  # nothing was stored by any of them
+
+
 @pytest.mark.parametrize("scale", [0.0, 1e-30, -0.05])
 def test_prefill_with_zero_tiny_and_negative_scale(U, oracle, scale):
     """The tiled kernel carries part of the ALiBi term inside the score accumulator as slope / scale;
