@@ -1530,6 +1530,38 @@ def test_random_mix_of_prefill_calls(U, oracle):
         U.check_scaled(got, ref, dtype, tag)
 
 
+def test_random_mix_of_prefill_steps(U, oracle):
+    """Thirty seeded random prefill batches (chunk lengths from 1 token to the whole prompt, every
+    group size and block size) through the one-call step: caches and output bit for bit those of
+    cache write + prefill, and the output against the oracle."""
+    rng = np.random.default_rng(20253)
+    for it in range(30):
+        D = int(rng.choice([64, 128, 128, 128]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        Gq = int(rng.choice([1, 2, 3, 4, 8, 16, 20]))
+        bs = int(rng.choice([16, 32, 64]))
+        B = int(rng.integers(1, 6))
+        hi = int(rng.choice([60, 300, 900]))
+        q_len = int(rng.choice([1, 2, 7, 33, 130, 257, hi]))
+        dtype = W.F16 if rng.integers(2) else W.BF16
+        cfg = W.small_config(name=f"psmix{it}", kind="prefill", dtype=dtype, batch=B, num_heads=Hkv * Gq,
+                             num_kv_heads=Hkv, head_dim=D, block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 5,
+                             ctx_lo=1, ctx_hi=hi, q_len=q_len, seed=3300 + it)
+        case = W.make_case(cfg)
+        tag = f"case {it}: D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} q_len={q_len} {dtype}"
+        kc, vc = oracle_filled(oracle, case)
+        two = U.DevCase(case)
+        two.write_cache()
+        want = two.prefill()
+        one = U.DevCase(case)
+        got = one.prefill_step()
+        assert np.array_equal(U.to_host(one.k_cache), kc) and np.array_equal(U.to_host(one.v_cache), vc), tag
+        assert np.array_equal(got, want), tag
+        ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                                   case.slopes, case.scale, dtype)
+        U.check_scaled(got, ref, dtype, tag)
+
+
 def test_decode_step_replays_from_a_hip_graph(U, oracle):
     """The one-call step allocates nothing, synchronises nothing and records no memset, so it can be
     captured: every replay (with eager steps and synchronisations in between) must reproduce the
