@@ -1596,6 +1596,41 @@ def test_decode_step_replays_from_a_hip_graph(U, oracle):
         assert torch.equal(dev.out, eager), rep
 
 
+def test_prefill_step_replays_from_a_hip_graph(U, oracle):
+    """The same for the one-call prefill step (one launch, nothing allocated): every replay gives
+    the eager output bit for bit and the caches the oracle's cache write leaves."""
+    import torch
+    import paper_2505_02351_amd as G
+    cfg = W.small_config(name="graph-pf", kind="prefill", dtype=W.BF16, batch=3, num_heads=16, num_kv_heads=4,
+                         head_dim=128, block_size=16, num_blocks=3 * 40 + 3, ctx_lo=150, ctx_hi=600, q_len=97, seed=18)
+    case = W.make_case(cfg)
+    dev = U.DevCase(case)
+    def step():
+        G.prefill_step(dev.out, dev.q, dev.k_new, dev.v_new, dev.k_cache, dev.v_cache, dev.block_tables,
+                       dev.context_lens, dev.cu_q_lens, dev.slopes, float(case.scale), case.max_q_len)
+    step()                                   # also raises the kernel's dynamic LDS limit, once per process
+    torch.cuda.synchronize()
+    eager = dev.out.clone()
+    kc, vc = oracle_filled(oracle, case)
+    ref = oracle.paged_prefill(case.q, kc, vc, case.block_tables, case.context_lens, case.cu_q_lens,
+                               case.slopes, case.scale, case.dtype)
+    U.check_scaled(U.to_host(eager), ref, case.dtype, "prefill step before capture")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        dev.out.fill_(float("nan"))
+        dev.k_cache.copy_(U.to_dev(case.k_cache, case.dtype))      # back to the image before the step
+        dev.v_cache.copy_(U.to_dev(case.v_cache, case.dtype))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dev.out, eager), rep
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), rep
+        step()                               # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(dev.out, eager), rep
+
+
 def test_stream_probe_runs_and_checks_its_list(U):
     import torch
     import paper_2505_02351_amd as G
