@@ -198,7 +198,9 @@ def check_scaled(got_bits: np.ndarray, ref: np.ndarray, dtype: str, tag: str, ma
     TOL - that half-ulp (1.02e-3 fp16, 2.2e-3 bf16).  An output of magnitude >= 4 (a row that sees
     one or two keys with a large V element) is rounded more coarsely by its own format; there the
     bound is half an ulp of the type AT |ref| plus the SAME compute budget, nothing more, and
-    such elements must be rare (at most ``max_exempt`` of the elements, or four of them)."""
+    such elements must be rare: at most ``max_exempt`` of the elements, or 64 of them (one V element
+    beyond 4 shows in every head of its group when a row sees a single key: four such elements in
+    groups of up to 16 heads)."""
     g = W.from_bits(got_bits, dtype)
     assert np.all(np.isfinite(g)), f"{tag}: non-finite values in the GPU output"
     if not ref.size:
@@ -211,4 +213,4 @@ def check_scaled(got_bits: np.ndarray, ref: np.ndarray, dtype: str, tag: str, ma
     i = np.unravel_index(np.argmax(over), over.shape)
     assert over[i] <= 0, f"{tag}: |{g[i]} - {ref[i]}| = {err[i]} > {bound[i]} at {i}"
     n_big = int(np.count_nonzero(big))
-    assert n_big <= max(max_exempt * ref.size, 4), f"{tag}: {n_big} of {ref.size} outputs have magnitude >= 4"
+    assert n_big <= max(max_exempt * ref.size, 64), f"{tag}: {n_big} of {ref.size} outputs have magnitude >= 4"
