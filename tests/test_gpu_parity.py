@@ -1530,6 +1530,41 @@ def test_random_mix_of_prefill_calls(U, oracle):
         U.check_scaled(got, ref, dtype, tag)
 
 
+def test_random_mix_of_shared_prefix_calls(U, oracle):
+    """Forty seeded random batches whose runs of sequences share a prefix of random length (runs that
+    match the kernel's bundles, shorter ones, longer ones), through both shared-prefix entry points."""
+    import paper_2505_02351_amd as G
+    rng = np.random.default_rng(20254)
+    for it in range(40):
+        D = int(rng.choice([64, 128, 128]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        Gq = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 20]))
+        bs = int(rng.choice([16, 32, 64]))
+        B = int(rng.integers(1, 40))
+        hi = int(rng.choice([40, 200, 700, 1500]))
+        lo = int(rng.integers(1, hi + 1))
+        dtype = W.F16 if rng.integers(2) else W.BF16
+        frac = float(rng.choice([0.2, 0.5, 0.9, 1.0]))
+        Hq = Hkv * Gq
+        bundle = G.shared_prefix_bundle(Hq, Hkv, D)
+        group = max(int(rng.choice([2, 3, bundle, 2 * bundle])) if rng.integers(2) else bundle, 2)
+        tag = f"case {it}: D={D} Hkv={Hkv} G={Gq} bs={bs} B={B} lens {lo}..{hi} {dtype} bundle={bundle} runs of {group}"
+        cfg = W.small_config(name=f"spmix{it}", dtype=dtype, batch=B, num_heads=Hq, num_kv_heads=Hkv, head_dim=D,
+                             block_size=bs, num_blocks=B * ((hi + bs - 1) // bs) + 7, ctx_lo=lo, ctx_hi=hi,
+                             seed=3400 + it)
+        case = W.make_case(cfg)
+        W.share_prefix_blocks(case, group, frac)
+        shared = W.bundle_shared_blocks(case, bundle)
+        assert G.validate_shared_prefix_host(case.block_tables, case.context_lens, shared, bs, bundle, 1) == 0, tag
+        kc, vc = oracle_filled(oracle, case)
+        ref = oracle_decode(oracle, case, kc, vc)
+        dev = U.DevCase(case)
+        got = dev.decode_shared(shared, fused=True)
+        assert np.array_equal(U.to_host(dev.k_cache), kc) and np.array_equal(U.to_host(dev.v_cache), vc), tag
+        U.check_scaled(got, ref, dtype, tag + ", fused step")
+        U.check_scaled(dev.decode_shared(shared), ref, dtype, tag + ", plain")
+
+
 def test_random_mix_of_prefill_steps(U, oracle):
     """Thirty seeded random prefill batches (chunk lengths from 1 token to the whole prompt, every
     group size and block size) through the one-call step: caches and output bit for bit those of
